@@ -1,0 +1,141 @@
+/*
+ * libmlip -- the four-phase training step of a conservative message-passing interatomic
+ * potential on one MI355X (gfx950), behind a C ABI.
+ *
+ * A training iteration of a conservative potential has four compute phases (paper, Sec. 2
+ * "Training MLIPs with Four Phases"): Forward Energy (FE) predicts E, Forward Force (FF)
+ * obtains F = -dE/dx by differentiating FE, Backward Force (BF) back-propagates the force
+ * loss through FF (the double backward) and Backward Energy (BE) back-propagates through FE.
+ * The parameter gradient is split between the last two as in Eq. 2 (Sec. 4.1, Pass 1,
+ * Rule 2): BF contributes only the second-order term, BE every first-order term.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its name ends in _host.  The caller owns every
+ *    buffer it passes; the library owns the context and all workspace inside it.
+ *  - All floating-point tensors are float32, row-major, densely packed.  Indices are int32.
+ *  - Calls enqueue work on the HIP stream given at mlip_create and return without waiting,
+ *    except where "synchronous" is stated.  The library never uses atomics on floating-point
+ *    data: results are bitwise reproducible from run to run.
+ *  - Return value: MLIP_OK (0) or a negative mlip_status; no C++ exception crosses the
+ *    boundary.  mlip_last_error gives a message for the last failure on a context.
+ *  - There is no CPU fallback: every step of the path runs in the library's GPU kernels.
+ *
+ * Parameter vector (float32, each tensor row-major [out, in], concatenated in this order):
+ *    whole model : emb[S,C]; per layer {W1[H,K], W2[C,H], V1[C,C], V2[C,C]} (edge MLP depth 2)
+ *                  or {W1[H,K], W2[H,H], W3[C,H], V1, V2} (depth 3); U[C,C]; w_o[C]
+ *    equivariant : emb[S,C]; per layer {W1[H,K], W2[11*C,H] (row = path*C + channel),
+ *                  Wl0[C,C], Wl1[C,C], Wl2[C,C]}; U[C,C]; w_o[C]
+ *    stage       : the per-layer blocks only.
+ *
+ * Model (no biases anywhere; sigma = SiLU):
+ *    phi_k(r) = exp(-gamma (r - k r_c/(K-1))^2), gamma = ((K-1)/r_c)^2 / 2;
+ *    f_c(r) = (1 + cos(pi r / r_c)) / 2;
+ *    invariant layer: w_e = W2 sigma(W1 phi(r_e))  (depth 3: W3 sigma(W2 sigma(W1 phi))),
+ *        a_i = sum_{e=(i<-j)} f_c(r_e) w_e (.) h_j,   h_i <- h_i + V2 sigma(V1 a_i);
+ *    readout: E_s = sum_{i in s} w_o . sigma(U h_i);   h^0_i = emb[species_i];
+ *    loss: L = mean_s (E_s - E_ref,s)^2 + force_weight * mean_{i,alpha} (F - F_ref)^2.
+ */
+#ifndef MLIP_H
+#define MLIP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mlip_ctx mlip_ctx;
+
+typedef enum {
+  MLIP_OK = 0,
+  MLIP_E_INVALID = -1,     /* null pointer, non-positive size, cutoff <= 0 or > a cell edge, bad order of calls' arguments */
+  MLIP_E_CAPACITY = -2,    /* more atoms / structures / edges than the context was created for */
+  MLIP_E_UNSUPPORTED = -3, /* non-orthorhombic cell, unsupported model shape */
+  MLIP_E_STATE = -4,       /* phase called out of order (FE -> FF -> BF -> BE) or without a graph */
+  MLIP_E_HIP = -5,         /* a HIP runtime call failed */
+  MLIP_E_POSITION = -6     /* a position lies outside [0, L) of its cell, or is not finite (found at graph build) */
+} mlip_status;
+
+enum { MLIP_MODEL_INVARIANT = 0, MLIP_MODEL_EQUIVARIANT = 1, MLIP_MODEL_STAGE = 2 };
+enum { MLIP_GEMM_FP32 = 0, MLIP_GEMM_BF16 = 1 };
+
+typedef struct {
+  int32_t model_kind;       /* MLIP_MODEL_* */
+  int32_t n_species;        /* S (ignored for a stage) */
+  int32_t channels;         /* C, multiple of 4 */
+  int32_t n_layers;
+  int32_t n_rbf;            /* K >= 2, multiple of 4 */
+  int32_t edge_hidden;      /* H, multiple of 4 */
+  int32_t edge_mlp_depth;   /* 2 or 3 */
+  int32_t l_max;            /* 0 (invariant, stage) or 2 (equivariant) */
+  int32_t gemm_dtype;       /* MLIP_GEMM_FP32, or MLIP_GEMM_BF16: both operands of every matrix
+                               product rounded to bf16 (nearest even), fp32 accumulation */
+  float cutoff;             /* r_c, Angstrom */
+  float force_weight;       /* weight of the force term of the loss */
+  int64_t max_atoms;        /* capacities the workspace is sized for */
+  int64_t max_structs;
+  int64_t max_edges;
+} mlip_config;
+
+/* Synchronous.  Allocates the context and all device workspace for the given capacities.
+ * hip_stream is a hipStream_t (NULL = the default stream); it must outlive the context. */
+int mlip_create(const mlip_config* cfg, void* hip_stream, mlip_ctx** out);
+/* Synchronous.  Waits for the stream, frees everything.  NULL is accepted. */
+int mlip_destroy(mlip_ctx* ctx);
+/* Length of the flat parameter vector for this context's model. */
+int64_t mlip_param_count(const mlip_ctx* ctx);
+/* Message of the last failing call on this context (host string owned by the context). */
+const char* mlip_last_error(const mlip_ctx* ctx);
+/* Bytes of device memory held by the context. */
+int64_t mlip_workspace_bytes(const mlip_ctx* ctx);
+
+/* Periodic radius graph (cell-list binning, receiver-sorted CSR).
+ * Edge e = (i <- j, S) exists iff |x_j + S.cell - x_i|^2 < cutoff^2 in float32 (differences
+ * first, then the shift, then the three squares summed left to right, no fused multiply-add)
+ * and (j, S) != (i, 0); i, j in the same structure.  Rows are receivers in global atom order;
+ * inside a row edges are ordered by (sender, then (Sx+1)*9 + (Sy+1)*3 + (Sz+1)).
+ *   pos[N,3], struct_ptr[B+1] (atom ranges of the structures), cell[B,3,3] (rows = lattice
+ *   vectors; must be orthorhombic, i.e. diagonal, with cutoff <= every edge).
+ * Synchronous: reads struct_ptr and cell back to validate them and returns the edge count in
+ * *n_edges_host.  On MLIP_E_CAPACITY *n_edges_host holds the count that was needed.
+ * The graph stays in the context until the next build. */
+int mlip_graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos,
+                     const int32_t* struct_ptr, const float* cell, float cutoff,
+                     int64_t* n_edges_host);
+/* Sizes of the current graph, written to host integers (any may be NULL).  Does not wait. */
+int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host);
+/* Copies the current graph into caller buffers (any may be NULL): row_ptr[N+1], sender[E],
+ * shift[E,3] (int32 components in {-1,0,1}), rev[E] (index of the opposite edge j <- i, -S). */
+int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+
+/* FE.  Whole model: h^0 = emb[species], E[B] written.  Stage: h_in[N,C] read, h_out[N,C]
+ * written, species and E may be NULL.  pos and params are copied into the context, so the
+ * caller may reuse them at once.  Needs a graph built from the same positions. */
+int mlip_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params,
+                        const float* h_in, float* E, float* h_out);
+/* FF.  Whole model: F[N,3] = -dE_total/dx.  Stage: g_out[N,C] = dE/dh_out read; g_in[N,C] =
+ * dE/dh_in and F[N,3] = +(dH/dx)^T g_out (this stage's additive contribution to dE/dx) written. */
+int mlip_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in);
+/* Loss and its cotangents (whole model): loss[1], Ebar[B] = dL/dE, v[N,3] = -dL/dF. */
+int mlip_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref,
+              float* loss, float* Ebar, float* v);
+/* BF.  v[N,3] = -dL/dF.  Adds the second-order share of the parameter gradient (Eq. 2) to
+ * grad_params.  Stage: hdot_in[N,C] = dL_F/d(dE/dh_in) read (NULL = zero), hdot_out written. */
+int mlip_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad_params,
+                        float* hdot_out);
+/* BE.  Adds the merged first-order share (Eq. 2) to grad_params.  Whole model: Ebar[B] = dL/dE.
+ * Stage: lam_out[N,C] = dL/dh_out read, lam_in[N,C] = dL/dh_in written. */
+int mlip_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad_params,
+                         float* lam_in);
+/* Whole step for a whole model: graph build, FE, FF, loss, BF, BE.  grad_params is overwritten.
+ * phase_ms_host[5] (graph, FE, FF+loss, BF, BE; milliseconds from HIP events) makes the call
+ * synchronous; NULL skips timing.  The graph build inside is synchronous in any case. */
+int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos,
+                    const int32_t* species, const int32_t* struct_ptr, const float* cell, float cutoff,
+                    const float* params, const float* E_ref, const float* F_ref, float* loss, float* E,
+                    float* F, float* grad_params, float* phase_ms_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLIP_H */

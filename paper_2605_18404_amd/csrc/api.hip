@@ -1,0 +1,199 @@
+// C-ABI entry points (declared in include/mlip.h): argument checks, context life cycle,
+// the whole-step driver with per-phase HIP-event timing.
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+void* ctx_alloc(mlip_ctx* ctx, size_t bytes) {
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    ctx->err = std::string("hipMalloc failed: ") + hipGetErrorString(e);
+    return nullptr;
+  }
+  ctx->allocs.push_back(p);
+  ctx->bytes += (int64_t)bytes;
+  return p;
+}
+
+namespace {
+
+struct StepBufs {
+  float* Ebar = nullptr;
+  float* v = nullptr;
+};
+
+int layout_params(mlip_ctx* ctx) {
+  const mlip_config& c = ctx->cfg;
+  const int64_t C = c.channels, H = c.edge_hidden, K = c.n_rbf;
+  int64_t off = 0;
+  ctx->lay.assign(c.n_layers, LayerOffsets{});
+  if (c.model_kind != MLIP_MODEL_STAGE) { ctx->off_emb = off; off += (int64_t)c.n_species * C; }
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerOffsets& lo = ctx->lay[l];
+    lo.W[0] = off; off += H * K;
+    if (c.model_kind == MLIP_MODEL_EQUIVARIANT) {
+      lo.W[1] = off; off += MLIP_NPATH * C * H;
+      lo.W[2] = -1;
+      for (int k = 0; k < 3; ++k) { lo.Wl[k] = off; off += C * C; }
+    } else {
+      if (c.edge_mlp_depth == 3) { lo.W[1] = off; off += H * H; lo.W[2] = off; off += C * H; }
+      else { lo.W[1] = off; off += C * H; lo.W[2] = -1; }
+      lo.V1 = off; off += C * C;
+      lo.V2 = off; off += C * C;
+    }
+  }
+  if (c.model_kind != MLIP_MODEL_STAGE) { ctx->off_U = off; off += C * C; ctx->off_wo = off; off += C; }
+  ctx->n_params = off;
+  return MLIP_OK;
+}
+
+const char* check_config(const mlip_config& c) {
+  if (c.model_kind < 0 || c.model_kind > 2) return "model_kind must be 0, 1 or 2";
+  if (c.channels < 4 || c.channels % 4 || c.channels > 1024) return "channels must be a multiple of 4 in [4, 1024]";
+  if (c.edge_hidden < 4 || c.edge_hidden % 4) return "edge_hidden must be a positive multiple of 4";
+  if (c.n_rbf < 4 || c.n_rbf % 4) return "n_rbf must be a positive multiple of 4";
+  if (c.n_layers < 1 || c.n_layers > 64) return "n_layers must be in [1, 64]";
+  if (c.edge_mlp_depth != 2 && c.edge_mlp_depth != 3) return "edge_mlp_depth must be 2 or 3";
+  if (c.model_kind == MLIP_MODEL_EQUIVARIANT ? (c.l_max != 2 || c.edge_mlp_depth != 2) : (c.l_max != 0))
+    return "l_max must be 2 (edge_mlp_depth 2) for the equivariant model and 0 otherwise";
+  if (c.model_kind != MLIP_MODEL_STAGE && c.n_species < 1) return "n_species must be positive";
+  if (c.gemm_dtype != MLIP_GEMM_FP32 && c.gemm_dtype != MLIP_GEMM_BF16) return "gemm_dtype must be 0 or 1";
+  if (!(c.cutoff > 0.f)) return "cutoff must be positive";
+  if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
+  if (c.max_atoms > 50000000 || c.max_edges > 2000000000LL) return "capacity too large for 32-bit indices";
+  return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mlip_create(const mlip_config* cfg, void* hip_stream, mlip_ctx** out) {
+  if (!cfg || !out) return MLIP_E_INVALID;
+  *out = nullptr;
+  if (check_config(*cfg)) return MLIP_E_INVALID;
+  mlip_ctx* ctx = new (std::nothrow) mlip_ctx();
+  if (!ctx) return MLIP_E_HIP;
+  ctx->cfg = *cfg;
+  ctx->stream = (hipStream_t)hip_stream;
+  layout_params(ctx);
+  int s = graph_alloc(ctx);
+  if (s == MLIP_OK) s = model_alloc(ctx);
+  if (s == MLIP_OK) {
+    StepBufs* sb = new StepBufs();
+    sb->Ebar = (float*)ctx_alloc(ctx, sizeof(float) * cfg->max_structs);
+    sb->v = (float*)ctx_alloc(ctx, sizeof(float) * 3 * cfg->max_atoms);
+    ctx->step_bufs = sb;
+    if (!sb->Ebar || !sb->v) s = MLIP_E_HIP;
+  }
+  if (s != MLIP_OK) {
+    mlip_destroy(ctx);
+    return s;
+  }
+  *out = ctx;
+  return MLIP_OK;
+}
+
+int mlip_destroy(mlip_ctx* ctx) {
+  if (!ctx) return MLIP_OK;
+  hipStreamSynchronize(ctx->stream);
+  for (void* p : ctx->allocs) hipFree(p);
+  model_free(ctx);
+  delete (StepBufs*)ctx->step_bufs;
+  delete ctx;
+  return MLIP_OK;
+}
+
+int64_t mlip_param_count(const mlip_ctx* ctx) { return ctx ? ctx->n_params : -1; }
+const char* mlip_last_error(const mlip_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+int64_t mlip_workspace_bytes(const mlip_ctx* ctx) { return ctx ? ctx->bytes : -1; }
+
+int mlip_graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* struct_ptr,
+                     const float* cell, float cutoff, int64_t* n_edges_host) {
+  if (!ctx) return MLIP_E_INVALID;
+  return graph_build(ctx, n_atoms, n_structs, pos, struct_ptr, cell, cutoff, n_edges_host);
+}
+
+int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (ctx->phase < PH_GRAPH) return MLIP_E_STATE;
+  if (n_atoms_host) *n_atoms_host = ctx->N;
+  if (n_structs_host) *n_structs_host = ctx->B;
+  if (n_edges_host) *n_edges_host = ctx->E;
+  return MLIP_OK;
+}
+
+int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev) {
+  if (!ctx) return MLIP_E_INVALID;
+  return graph_export(ctx, row_ptr, sender, shift, rev);
+}
+
+int mlip_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
+                        float* E, float* h_out) {
+  if (!ctx) return MLIP_E_INVALID;
+  return model_forward_energy(ctx, pos, species, params, h_in, E, h_out);
+}
+
+int mlip_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
+  if (!ctx) return MLIP_E_INVALID;
+  return model_forward_force(ctx, g_out, F, g_in);
+}
+
+int mlip_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
+              float* Ebar, float* v) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (ctx->cfg.model_kind == MLIP_MODEL_STAGE) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "loss: a stage has no loss");
+  return model_loss(ctx, E, F, E_ref, F_ref, loss, Ebar, v);
+}
+
+int mlip_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad_params, float* hdot_out) {
+  if (!ctx) return MLIP_E_INVALID;
+  return model_backward_force(ctx, v, hdot_in, grad_params, hdot_out);
+}
+
+int mlip_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad_params, float* lam_in) {
+  if (!ctx) return MLIP_E_INVALID;
+  return model_backward_energy(ctx, Ebar, lam_out, grad_params, lam_in);
+}
+
+int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* species,
+                    const int32_t* struct_ptr, const float* cell, float cutoff, const float* params, const float* E_ref,
+                    const float* F_ref, float* loss, float* E, float* F, float* grad_params, float* phase_ms_host) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (ctx->cfg.model_kind == MLIP_MODEL_STAGE) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "train_step: a stage is driven phase by phase");
+  if (!E_ref || !F_ref || !loss || !E || !F || !grad_params) MLIP_FAIL(ctx, MLIP_E_INVALID, "train_step: null pointer");
+  hipStream_t st = ctx->stream;
+  StepBufs* sb = (StepBufs*)ctx->step_bufs;
+  hipEvent_t ev[6];
+  const bool timed = phase_ms_host != nullptr;
+  if (timed) {
+    for (auto& e : ev) MLIP_HIP_CHECK(ctx, hipEventCreate(&e));
+    MLIP_HIP_CHECK(ctx, hipEventRecord(ev[0], st));
+  }
+  int64_t n_edges = 0;
+  int s = mlip_graph_build(ctx, n_atoms, n_structs, pos, struct_ptr, cell, cutoff, &n_edges);
+  if (s == MLIP_OK && timed) hipEventRecord(ev[1], st);
+  if (s == MLIP_OK) s = model_forward_energy(ctx, pos, species, params, nullptr, E, nullptr);
+  if (s == MLIP_OK && timed) hipEventRecord(ev[2], st);
+  if (s == MLIP_OK) s = model_forward_force(ctx, nullptr, F, nullptr);
+  if (s == MLIP_OK) s = model_loss(ctx, E, F, E_ref, F_ref, loss, sb->Ebar, sb->v);
+  if (s == MLIP_OK && timed) hipEventRecord(ev[3], st);
+  if (s == MLIP_OK && hipMemsetAsync(grad_params, 0, sizeof(float) * ctx->n_params, st) != hipSuccess) s = MLIP_E_HIP;
+  if (s == MLIP_OK) s = model_backward_force(ctx, sb->v, nullptr, grad_params, nullptr);
+  if (s == MLIP_OK && timed) hipEventRecord(ev[4], st);
+  if (s == MLIP_OK) s = model_backward_energy(ctx, sb->Ebar, nullptr, grad_params, nullptr);
+  if (s == MLIP_OK && timed) hipEventRecord(ev[5], st);
+  if (timed) {
+    if (s == MLIP_OK) {
+      if (hipEventSynchronize(ev[5]) != hipSuccess) s = MLIP_E_HIP;
+      for (int k = 0; k < 5 && s == MLIP_OK; ++k)
+        if (hipEventElapsedTime(&phase_ms_host[k], ev[k], ev[k + 1]) != hipSuccess) s = MLIP_E_HIP;
+    }
+    for (auto& e : ev) hipEventDestroy(e);
+  }
+  return s;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/mlip.h"
+
+#define MLIP_HIP_CHECK(ctx, expr)                                                         \
+  do {                                                                                    \
+    hipError_t _e = (expr);                                                               \
+    if (_e != hipSuccess) {                                                               \
+      (ctx)->err = std::string(#expr) + ": " + hipGetErrorString(_e);                     \
+      return MLIP_E_HIP;                                                                  \
+    }                                                                                     \
+  } while (0)
+
+#define MLIP_FAIL(ctx, code, msg) \
+  do {                            \
+    (ctx)->err = (msg);           \
+    return (code);                \
+  } while (0)
+
+#define MLIP_TRY(expr)          \
+  do {                          \
+    int _s = (expr);            \
+    if (_s != MLIP_OK) return _s; \
+  } while (0)
+
+constexpr int MLIP_NPATH = 11;  // (l1,l2,l3), l <= 2, triangle rule, even parity
+
+// Per-structure record used by the graph kernels (built on the host at graph build).
+struct StructMeta {
+  int32_t atom_begin, atom_end;
+  int32_t nb[3];     // bins per axis
+  int32_t bin_base;  // first global bin of this structure
+  float L[3];        // orthorhombic cell edges
+};
+
+enum Phase { PH_NONE = 0, PH_GRAPH = 1, PH_FE = 2, PH_FF = 3, PH_BF = 4, PH_BE = 5 };
+
+struct LayerOffsets {  // offsets (in floats) into the flat parameter vector
+  int64_t W[3];        // edge MLP matrices (W[2] unused for depth 2)
+  int64_t V1, V2;      // invariant update
+  int64_t Wl[3];       // equivariant per-l mixing
+};
+
+struct mlip_ctx {
+  mlip_config cfg{};
+  hipStream_t stream = nullptr;
+  std::string err;
+  std::vector<void*> allocs;
+  int64_t bytes = 0;
+  int phase = PH_NONE;
+  // sizes of the current batch
+  int64_t N = 0, E = 0;
+  int32_t B = 0;
+  int64_t n_params = 0;
+  int64_t off_emb = -1, off_U = -1, off_wo = -1;
+  std::vector<LayerOffsets> lay;
+
+  // ---- graph
+  StructMeta* d_meta = nullptr;       // [max_structs]
+  int32_t* d_atom_struct = nullptr;   // [N]
+  int32_t* d_atom_bin = nullptr;      // [N]
+  int32_t* d_bin_count = nullptr;     // [max_bins + 1]
+  int32_t* d_bin_start = nullptr;     // [max_bins + 1]
+  int32_t* d_bin_cursor = nullptr;    // [max_bins]
+  int32_t* d_bin_atoms = nullptr;     // [N]
+  int32_t* d_deg = nullptr;           // [N + 1]
+  int32_t* d_row_ptr = nullptr;       // [N + 1]
+  int32_t* d_key_tmp = nullptr;       // [max_edges] unsorted keys sender*27+code
+  int32_t* d_sender = nullptr;        // [max_edges]
+  int32_t* d_code = nullptr;          // [max_edges] shift code 0..26
+  int32_t* d_receiver = nullptr;      // [max_edges]
+  int32_t* d_rev = nullptr;           // [max_edges]
+  int32_t* d_scan_tmp = nullptr;      // block sums for the scans
+  int32_t* d_flag = nullptr;          // device error flag
+  int64_t max_bins = 0;
+  std::vector<StructMeta> h_meta;
+  std::vector<int32_t> h_struct_ptr;
+  std::vector<float> h_cell;
+
+  // ---- model workspace (see model.hip)
+  float* d_pos = nullptr;      // [N,3] copy taken at FE
+  float* d_params = nullptr;   // copy taken at FE
+  int32_t* d_species = nullptr;
+  float4* d_geo = nullptr;     // [E] unit vector and length of each edge
+  void* model_ws = nullptr;    // workspace of the model kind, owned by its translation unit
+  void* step_bufs = nullptr;   // cotangent buffers of mlip_train_step
+};
+
+void* ctx_alloc(mlip_ctx* ctx, size_t bytes);  // returns nullptr on failure (err set)
+
+// graph.hip
+int graph_alloc(mlip_ctx* ctx);
+int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* struct_ptr,
+                const float* cell, float cutoff, int64_t* n_edges_host);
+int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+
+// model.hip
+int model_alloc(mlip_ctx* ctx);
+void model_free(mlip_ctx* ctx);
+int model_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params,
+                         const float* h_in, float* E, float* h_out);
+int model_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in);
+int model_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
+               float* Ebar, float* v);
+int model_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out);
+int model_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in);

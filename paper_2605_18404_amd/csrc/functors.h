@@ -1,0 +1,194 @@
+// Operand loaders and epilogues plugged into the GEMM template, and SiLU derivatives.
+// Every loader maps (matrix row, first of four consecutive columns) -> float4.
+// "Jets" are pairs (value, derivative with respect to the edge length r) stored as two
+// consecutive rows per edge: row 2e holds the value, row 2e+1 the derivative.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fx {
+
+__device__ __forceinline__ float sigm(float x) { return 1.f / (1.f + __expf(-x)); }
+__device__ __forceinline__ float silu(float x) { return x * sigm(x); }
+__device__ __forceinline__ float dsilu(float x) {
+  float s = sigm(x);
+  return s * (1.f + x * (1.f - s));
+}
+__device__ __forceinline__ float d2silu(float x) {
+  float s = sigm(x);
+  return s * (1.f - s) * (2.f + x * (1.f - 2.f * s));
+}
+// silu', silu'' together (one exponential)
+__device__ __forceinline__ void dsilu12(float x, float& d1, float& d2) {
+  float s = sigm(x);
+  d1 = s * (1.f + x * (1.f - s));
+  d2 = s * (1.f - s) * (2.f + x * (1.f - 2.f * s));
+}
+
+#define FX_MAP4(out, expr_x, expr_y, expr_z, expr_w) float4 out = make_float4(expr_x, expr_y, expr_z, expr_w)
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 mul4(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
+__device__ __forceinline__ float4 silu4(float4 a) { return make_float4(silu(a.x), silu(a.y), silu(a.z), silu(a.w)); }
+__device__ __forceinline__ float4 dsilu4(float4 a) { return make_float4(dsilu(a.x), dsilu(a.y), dsilu(a.z), dsilu(a.w)); }
+
+// ---------------------------------------------------------------------------- loaders
+struct LdPlain {  // p[row * ld + col]
+  const float* p;
+  int64_t ld;
+  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const { return ld4(p + r * ld + c); }
+};
+struct LdSilu {  // silu(p[row * ld + col])
+  const float* p;
+  int64_t ld;
+  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const { return silu4(ld4(p + r * ld + c)); }
+};
+struct LdJetSilu {  // rows of a jet matrix u [2E][W]: even -> silu(u), odd -> silu'(u_even) * u_odd
+  const float* u;
+  int64_t W;
+  __device__ __forceinline__ float4 operator()(int64_t rho, int64_t c) const {
+    const float* pe = u + (rho & ~(int64_t)1) * W + c;
+    float4 a = ld4(pe);
+    if (rho & 1) return mul4(dsilu4(a), ld4(pe + W));
+    return silu4(a);
+  }
+};
+struct LdJetSiluEven {  // row e -> silu(u[2e])
+  const float* u;
+  int64_t W;
+  __device__ __forceinline__ float4 operator()(int64_t e, int64_t c) const { return silu4(ld4(u + 2 * e * W + c)); }
+};
+struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
+  const float* u;
+  int64_t W;
+  __device__ __forceinline__ float4 operator()(int64_t e, int64_t c) const {
+    const float* pe = u + 2 * e * W + c;
+    return mul4(dsilu4(ld4(pe)), ld4(pe + W));
+  }
+};
+struct LdDsiluMul {  // silu'(q[row]) * x[row]
+  const float* q;
+  const float* x;
+  int64_t ld;
+  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const {
+    return mul4(dsilu4(ld4(q + r * ld + c)), ld4(x + r * ld + c));
+  }
+};
+struct LdMuY {  // w_o[col] * silu'(y[row, col])
+  const float* y;
+  const float* wo;
+  int64_t ld;
+  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const {
+    return mul4(dsilu4(ld4(y + r * ld + c)), ld4(wo + c));
+  }
+};
+
+// ---------------------------------------------------------------------------- epilogues
+struct EpiStore {
+  float* p;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) p[(r0 + j) * ld + col] = v[j];
+  }
+};
+struct EpiAddStore {  // p = add + v
+  float* p;
+  const float* add;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) p[(r0 + j) * ld + col] = add[(r0 + j) * ld + col] + v[j];
+  }
+};
+struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  env[e] = (c, c')
+  float* out;
+  const float2* env;
+  int64_t ld, M;  // M = 2E
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; j += 2)
+      if (r0 + j + 1 < M) {
+        float2 c = env[(r0 + j) >> 1];
+        out[(r0 + j) * ld + col] = c.x * v[j];
+        out[(r0 + j + 1) * ld + col] = c.y * v[j] + c.x * v[j + 1];
+      }
+  }
+};
+struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
+  float* mu_t;
+  float* mu_q;
+  const float* q;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) {
+        int64_t o = (r0 + j) * ld + col;
+        mu_t[o] = v[j];
+        mu_q[o] = dsilu(q[o]) * v[j];
+      }
+  }
+};
+struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld])
+  float* Y;
+  float* Z;
+  const float* u;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) {
+        int64_t o = (r0 + j) * ld + col;
+        Y[o] = v[j];
+        Z[o] = dsilu(u[2 * (r0 + j) * ld + col]) * v[j];
+      }
+  }
+};
+struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y
+  float* out;
+  const float* u;
+  const float* Y;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) {
+        int64_t o = (r0 + j) * ld + col;
+        const float* pu = u + 2 * (r0 + j) * ld + col;
+        float d1, d2;
+        dsilu12(pu[0], d1, d2);
+        out[o] = d1 * v[j] + d2 * pu[ld] * Y[o];
+      }
+  }
+};
+struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
+  float* out;
+  const float* q;
+  const float* qd;
+  const float* mu_t;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) {
+        int64_t o = (r0 + j) * ld + col;
+        float d1, d2;
+        dsilu12(q[o], d1, d2);
+        out[o] = d1 * v[j] + d2 * qd[o] * mu_t[o];
+      }
+  }
+};
+struct EpiPartial {  // split-k partial sums: part[z][row][col]
+  float* part;
+  int64_t ld, M;
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int z) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (r0 + j < M) part[((int64_t)z * M + r0 + j) * ld + col] = v[j];
+  }
+};
+
+}  // namespace fx

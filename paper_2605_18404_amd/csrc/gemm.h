@@ -1,0 +1,230 @@
+// MFMA GEMM template for gfx950 with functor operand loaders and epilogues.
+//
+//   D(m, n) = sum_k A(m, k) * B(n, k)
+//
+// The operands are not plain arrays but functors that return four consecutive values, so
+// element-wise producers (activation, jets, products with saved tensors) are evaluated while a
+// tile is staged into LDS and never written to HBM.  Two orientations exist per operand:
+//   k-contiguous (KC): ld(row, k4) returns A(row, k4 .. k4+3)     -- forward / data-gradient
+//   k-strided    (KS): ld(k, row4) returns A(row4 .. row4+3, k)   -- weight gradients, where
+//                      the reduction index is the row (edge or atom) of both stored operands.
+// Precision policies:
+//   Fp32: v_mfma_f32_32x32x2_f32, LDS tiles k-major [BK][rows+pad] (fragment = one float).
+//   Bf16: v_mfma_f32_32x32x16_bf16, operands rounded to bf16 (nearest even) while staged,
+//         LDS tiles row-major [rows][BK+pad] (fragment = 8 consecutive k), fp32 accumulate.
+// A workgroup is 256 threads = 4 waves arranged WM x WN, each wave owning TM x TN blocks of
+// 32x32.  grid = (tiles, splits): split z reduces k in [z*kchunk, (z+1)*kchunk).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gemm {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+struct Fp32 {
+  typedef float lds_t;
+  static constexpr int BK = 16;
+  static constexpr bool K_MAJOR = true;
+};
+struct Bf16 {
+  typedef __bf16 lds_t;
+  static constexpr int BK = 32;
+  static constexpr bool K_MAJOR = false;
+};
+
+template <typename P, int ROWS>
+struct Tile {
+  // Fp32: [BK][ROWS + 4] floats.  Bf16: [ROWS][BK + 8] bf16 (80-byte rows: conflict-free 16-byte reads).
+  static constexpr int LD = P::K_MAJOR ? (ROWS + 4) : (P::BK + 8);
+  static constexpr int SIZE = P::K_MAJOR ? (P::BK * LD) : (ROWS * LD);
+};
+
+// ---- staging: global (through the loader functor) -> registers -> LDS ------------------------
+// Each thread moves NV = ROWS*BK/4/256 float4 per tile.
+template <typename P, int ROWS, bool KC, typename Ld>
+struct Stager {
+  static constexpr int NVT = ROWS * P::BK / 4;       // float4 per tile
+  static constexpr int NV = (NVT + 255) / 256;       // per thread
+  static constexpr int Q = KC ? (P::BK / 4) : (ROWS / 4);
+  float4 v[NV];
+
+  // KC: a row holds Q = BK/4 float4;    idx -> (row = idx / Q, kq = idx % Q)
+  // KS: a k-row holds Q = ROWS/4 float4; idx -> (k = idx / Q,  rq = idx % Q)
+  __device__ __forceinline__ void load(const Ld& ld, int64_t row0, int64_t n_rows, int64_t k0, int64_t k_end, int t) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = t + it * 256;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (NVT % 256 == 0 || idx < NVT) {
+        if (KC) {
+          int64_t row = row0 + idx / Q, k = k0 + 4 * (idx % Q);
+          if (row < n_rows && k < k_end) x = ld(row, k);
+        } else {
+          int64_t k = k0 + idx / Q, row = row0 + 4 * (idx % Q);
+          if (row < n_rows && k < k_end) x = ld(k, row);
+        }
+      }
+      v[it] = x;
+    }
+  }
+
+  __device__ __forceinline__ void store(typename P::lds_t* s, int t) const {
+    constexpr int LD = Tile<P, ROWS>::LD;
+    typedef typename P::lds_t T;
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = t + it * 256;
+      if (NVT % 256 != 0 && idx >= NVT) continue;
+      const float4 x = v[it];
+      const int a = idx / Q, b = idx % Q;  // KC: (row, kq); KS: (k, rq)
+      if (KC) {
+        if constexpr (P::K_MAJOR) {  // transpose into [k][row]
+          s[(4 * b + 0) * LD + a] = (T)x.x;
+          s[(4 * b + 1) * LD + a] = (T)x.y;
+          s[(4 * b + 2) * LD + a] = (T)x.z;
+          s[(4 * b + 3) * LD + a] = (T)x.w;
+        } else {  // [row][k], 4 bf16 = one 8-byte store
+          bf16x4 p = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + a * LD + 4 * b) = p;
+        }
+      } else {
+        if constexpr (P::K_MAJOR) {  // [k][row], one 16-byte store
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(s) + a * LD + 4 * b) = x;
+        } else {  // transpose into [row][k]
+          s[(4 * b + 0) * LD + a] = (T)x.x;
+          s[(4 * b + 1) * LD + a] = (T)x.y;
+          s[(4 * b + 2) * LD + a] = (T)x.z;
+          s[(4 * b + 3) * LD + a] = (T)x.w;
+        }
+      }
+    }
+  }
+};
+
+// ---- the kernel -----------------------------------------------------------------------------
+// Epi: void operator()(int64_t row0, int col, const float (&v)[4], int z) const  -- rows row0..row0+3
+// of column col (the functor checks row0 + j < M itself; col < N is guaranteed), z = split index.
+template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
+__global__ void __launch_bounds__(256)
+k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk) {
+  static_assert(WM * WN == 4, "four waves per workgroup");
+  constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, BK = P::BK;
+  typedef typename P::lds_t lds_t;
+  constexpr int LDA = Tile<P, BM>::LD, LDB = Tile<P, BN>::LD;
+  __shared__ __attribute__((aligned(16))) lds_t sA[2][Tile<P, BM>::SIZE];
+  __shared__ __attribute__((aligned(16))) lds_t sB[2][Tile<P, BN>::SIZE];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int li = lane & 31, g = lane >> 5;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): the column tiles of
+  // one row tile are given to the same XCD, one after the other, so the A rows are fetched once.
+  const int tiles_n = (N + BN - 1) / BN;
+  const int64_t tiles_m = (M + BM - 1) / BM;
+  const int64_t local = blockIdx.x >> 3;
+  const int64_t m_tile = (local / tiles_n) * 8 + (blockIdx.x & 7);
+  if (m_tile >= tiles_m) return;  // uniform for the workgroup, before any barrier
+  const int64_t m0 = m_tile * BM;
+  const int n0 = (int)(local % tiles_n) * BN;
+  const int64_t kb = (int64_t)blockIdx.y * k_chunk;
+  const int64_t ke = (kb + k_chunk < K) ? kb + k_chunk : K;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  Stager<P, BM, KC, LdA> stA;
+  Stager<P, BN, KC, LdB> stB;
+  const int64_t nk = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
+  if (nk > 0) {
+    stA.load(lda, m0, M, kb, ke, t);
+    stB.load(ldb, n0, N, kb, ke, t);
+    stA.store(sA[0], t);
+    stB.store(sB[0], t);
+  }
+  __syncthreads();
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    const int cur = (int)(kt & 1);
+    if (kt + 1 < nk) {
+      stA.load(lda, m0, M, kb + (kt + 1) * BK, ke, t);
+      stB.load(ldb, n0, N, kb + (kt + 1) * BK, ke, t);
+    }
+    const lds_t* a_s = sA[cur];
+    const lds_t* b_s = sB[cur];
+    if constexpr (P::K_MAJOR) {
+#pragma unroll
+      for (int kk = 0; kk < BK / 2; ++kk) {
+        float af[TM], bf[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = ((const float*)a_s)[(2 * kk + g) * LDA + (wm * TM + i) * 32 + li];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[j] = ((const float*)b_s)[(2 * kk + g) * LDB + (wn * TN + j) * 32 + li];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8 af[TM], bf[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>((const __bf16*)a_s + ((wm * TM + i) * 32 + li) * LDA + 16 * kk + 8 * g);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          bf[j] = *reinterpret_cast<const bf16x8*>((const __bf16*)b_s + ((wn * TN + j) * 32 + li) * LDB + 16 * kk + 8 * g);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    if (kt + 1 < nk) {
+      stA.store(sA[cur ^ 1], t);
+      stB.store(sB[cur ^ 1], t);
+    }
+    __syncthreads();
+  }
+  // accumulator q of a 32x32 block: row = 8*(q/4) + 4*g + q%4, column = lane % 32
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + (wn * TN + j) * 32 + li;
+      if (col < N) {
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+          const int64_t row0 = m0 + (wm * TM + i) * 32 + 8 * qq + 4 * g;
+          if (row0 < M) {
+            float v[4] = {acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]};
+            epi(row0, col, v, (int)blockIdx.y);
+          }
+        }
+      }
+    }
+}
+
+template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
+inline void launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
+  constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+  if (M <= 0 || N <= 0) return;
+  if (splits < 1) splits = 1;
+  int64_t k_chunk = (K + splits - 1) / splits;
+  k_chunk = (k_chunk + P::BK - 1) / P::BK * P::BK;
+  if (k_chunk < P::BK) k_chunk = P::BK;
+  const int64_t tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
+  dim3 grid((unsigned)(((tiles_m + 7) / 8) * 8 * tiles_n), (unsigned)splits, 1);
+  hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk);
+}
+
+}  // namespace gemm

@@ -1,0 +1,372 @@
+// Periodic radius graph on the GPU: cell-list binning, receiver-sorted CSR with a canonical
+// in-row order, and the reverse-edge map.  Integer work throughout; the only floating-point
+// decision is r^2 < r_c^2, taken in float32 with a fixed operation order (see mlip.h).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+
+constexpr int SCAN_BLOCK = 256;
+constexpr int SCAN_ITEMS = 8;  // per thread
+constexpr int SCAN_TILE = SCAN_BLOCK * SCAN_ITEMS;
+
+// ------------------------------------------------------------------ exclusive scan (int32)
+__global__ void k_scan_block_sums(const int32_t* __restrict__ in, int32_t* __restrict__ block_sums, int64_t n) {
+  __shared__ int32_t red[SCAN_BLOCK];
+  int64_t base = (int64_t)blockIdx.x * SCAN_TILE + threadIdx.x * SCAN_ITEMS;
+  int32_t s = 0;
+  for (int k = 0; k < SCAN_ITEMS; ++k)
+    if (base + k < n) s += in[base + k];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = SCAN_BLOCK / 2; off > 0; off >>= 1) {
+    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
+}
+
+__global__ void k_scan_sums_serial(int32_t* block_sums, int n_blocks) {
+  // one thread: n_blocks is at most a few thousand
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int32_t run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+      int32_t t = block_sums[b];
+      block_sums[b] = run;
+      run += t;
+    }
+  }
+}
+
+// out[i] = sum_{k<i} in[k] for i in [0, n]; out has n+1 entries (last = total).
+__global__ void k_scan_apply(const int32_t* __restrict__ in, const int32_t* __restrict__ block_sums,
+                             int32_t* __restrict__ out, int64_t n) {
+  __shared__ int32_t part[SCAN_BLOCK];
+  int64_t base = (int64_t)blockIdx.x * SCAN_TILE + threadIdx.x * SCAN_ITEMS;
+  int32_t v[SCAN_ITEMS];
+  int32_t s = 0;
+  for (int k = 0; k < SCAN_ITEMS; ++k) {
+    v[k] = (base + k < n) ? in[base + k] : 0;
+    s += v[k];
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  // Hillis-Steele inclusive scan of the per-thread sums
+  for (int off = 1; off < SCAN_BLOCK; off <<= 1) {
+    int32_t t = (threadIdx.x >= off) ? part[threadIdx.x - off] : 0;
+    __syncthreads();
+    part[threadIdx.x] += t;
+    __syncthreads();
+  }
+  int32_t run = block_sums[blockIdx.x] + part[threadIdx.x] - s;
+  for (int k = 0; k < SCAN_ITEMS; ++k) {
+    if (base + k < n) out[base + k] = run;
+    run += v[k];
+    if (base + k == n - 1) out[n] = run;
+  }
+}
+
+int scan_exclusive(mlip_ctx* ctx, const int32_t* in, int32_t* out, int64_t n) {
+  int n_blocks = (int)((n + SCAN_TILE - 1) / SCAN_TILE);
+  hipLaunchKernelGGL(k_scan_block_sums, dim3(n_blocks), dim3(SCAN_BLOCK), 0, ctx->stream, in, ctx->d_scan_tmp, n);
+  hipLaunchKernelGGL(k_scan_sums_serial, dim3(1), dim3(64), 0, ctx->stream, ctx->d_scan_tmp, n_blocks);
+  hipLaunchKernelGGL(k_scan_apply, dim3(n_blocks), dim3(SCAN_BLOCK), 0, ctx->stream, in, ctx->d_scan_tmp, out, n);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+// ------------------------------------------------------------------ binning
+__device__ __forceinline__ int struct_of_atom(const StructMeta* meta, int B, int i) {
+  int lo = 0, hi = B - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (meta[mid].atom_begin <= i) lo = mid; else hi = mid - 1;
+  }
+  // skip empty structures that share atom_begin
+  while (lo + 1 < B && meta[lo].atom_end <= i) ++lo;
+  return lo;
+}
+
+__device__ __forceinline__ int bin_coord(float x, float L, int nb) {
+  int b = (int)(x / L * (float)nb);
+  return b < 0 ? 0 : (b >= nb ? nb - 1 : b);
+}
+
+__global__ void k_bin_count(const float* __restrict__ pos, const StructMeta* __restrict__ meta, int B, int N,
+                            int32_t* __restrict__ atom_struct, int32_t* __restrict__ atom_bin,
+                            int32_t* __restrict__ bin_count, int32_t* __restrict__ flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int s = struct_of_atom(meta, B, i);
+  StructMeta m = meta[s];
+  float x = pos[3 * i], y = pos[3 * i + 1], z = pos[3 * i + 2];
+  bool ok = (x >= 0.f) && (x < m.L[0]) && (y >= 0.f) && (y < m.L[1]) && (z >= 0.f) && (z < m.L[2]);
+  if (!ok) atomicOr(flag, 1);  // also catches NaN
+  int bx = ok ? bin_coord(x, m.L[0], m.nb[0]) : 0;
+  int by = ok ? bin_coord(y, m.L[1], m.nb[1]) : 0;
+  int bz = ok ? bin_coord(z, m.L[2], m.nb[2]) : 0;
+  int g = m.bin_base + (bz * m.nb[1] + by) * m.nb[0] + bx;
+  atom_struct[i] = s;
+  atom_bin[i] = g;
+  atomicAdd(&bin_count[g], 1);
+}
+
+__global__ void k_bin_fill(const int32_t* __restrict__ atom_bin, const int32_t* __restrict__ bin_start,
+                           int32_t* __restrict__ bin_cursor, int32_t* __restrict__ bin_atoms, int N) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int g = atom_bin[i];
+  int slot = atomicAdd(&bin_cursor[g], 1);  // order inside a bin is arbitrary; rows are sorted later
+  bin_atoms[bin_start[g] + slot] = i;
+}
+
+// The float32 neighbour test, in the documented operation order, without contraction.
+__device__ __forceinline__ bool within(float xi, float yi, float zi, float xj, float yj, float zj, float sx,
+                                       float sy, float sz, float rc2) {
+  float dx = __fadd_rn(__fsub_rn(xj, xi), sx);
+  float dy = __fadd_rn(__fsub_rn(yj, yi), sy);
+  float dz = __fadd_rn(__fsub_rn(zj, zi), sz);
+  float r2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+  return r2 < rc2;
+}
+
+// One 64-lane wave per receiver atom.  FILL = false: count neighbours; true: write keys.
+template <bool FILL>
+__global__ void __launch_bounds__(256) k_neighbours(const float* __restrict__ pos, const StructMeta* __restrict__ meta,
+                                                    const int32_t* __restrict__ atom_struct,
+                                                    const int32_t* __restrict__ atom_bin,
+                                                    const int32_t* __restrict__ bin_start,
+                                                    const int32_t* __restrict__ bin_atoms, int N, float rc2,
+                                                    int32_t* __restrict__ deg, const int32_t* __restrict__ row_ptr,
+                                                    int32_t* __restrict__ key_tmp) {
+  int lane = threadIdx.x & 63;
+  int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= N) return;
+  StructMeta m = meta[atom_struct[i]];
+  float xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+  int g = atom_bin[i] - m.bin_base;
+  int bx = g % m.nb[0], by = (g / m.nb[0]) % m.nb[1], bz = g / (m.nb[0] * m.nb[1]);
+  int count = 0;
+  int out_base = FILL ? row_ptr[i] : 0;
+  for (int o = 0; o < 27; ++o) {
+    int ox = o / 9 - 1, oy = (o / 3) % 3 - 1, oz = o % 3 - 1;
+    // unwrapped bin coordinate -> wrapped bin + image shift (floor division)
+    int ux = bx + ox, uy = by + oy, uz = bz + oz;
+    int Sx = (ux < 0) ? -1 : (ux >= m.nb[0] ? 1 : 0);
+    int Sy = (uy < 0) ? -1 : (uy >= m.nb[1] ? 1 : 0);
+    int Sz = (uz < 0) ? -1 : (uz >= m.nb[2] ? 1 : 0);
+    int wx = ux - Sx * m.nb[0], wy = uy - Sy * m.nb[1], wz = uz - Sz * m.nb[2];
+    int gb = m.bin_base + (wz * m.nb[1] + wy) * m.nb[0] + wx;
+    float sx = (float)Sx * m.L[0], sy = (float)Sy * m.L[1], sz = (float)Sz * m.L[2];
+    int code = (Sx + 1) * 9 + (Sy + 1) * 3 + (Sz + 1);
+    int b0 = bin_start[gb], b1 = bin_start[gb + 1];
+    for (int t0 = b0; t0 < b1; t0 += 64) {
+      int t = t0 + lane;
+      bool hit = false;
+      int j = -1;
+      if (t < b1) {
+        j = bin_atoms[t];
+        hit = within(xi, yi, zi, pos[3 * j], pos[3 * j + 1], pos[3 * j + 2], sx, sy, sz, rc2);
+        if (j == i && code == 13) hit = false;
+      }
+      unsigned long long mask = __ballot(hit);
+      if (FILL && hit) {
+        int rank = __popcll(mask & ((1ull << lane) - 1ull));
+        key_tmp[out_base + count + rank] = j * 27 + code;
+      }
+      count += __popcll(mask);
+    }
+  }
+  if (!FILL && lane == 0) deg[i] = count;
+}
+
+// Rank sort of each row's keys (unique), one wave per row; writes sender, code, receiver.
+__global__ void __launch_bounds__(256) k_sort_rows(const int32_t* __restrict__ row_ptr,
+                                                   const int32_t* __restrict__ key_tmp, int N,
+                                                   int32_t* __restrict__ sender, int32_t* __restrict__ code,
+                                                   int32_t* __restrict__ receiver) {
+  int lane = threadIdx.x & 63;
+  int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= N) return;
+  int a = row_ptr[i], b = row_ptr[i + 1];
+  for (int t = a + lane; t < b; t += 64) {
+    int key = key_tmp[t];
+    int rank = 0;
+    for (int u = a; u < b; ++u) rank += (key_tmp[u] < key) ? 1 : 0;
+    sender[a + rank] = key / 27;
+    code[a + rank] = key % 27;
+    receiver[a + rank] = i;
+  }
+}
+
+__global__ void k_reverse_map(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                              const int32_t* __restrict__ code, const int32_t* __restrict__ receiver, int64_t E,
+                              int32_t* __restrict__ rev, int32_t* __restrict__ flag) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  int i = receiver[e], j = sender[e];
+  int want = i * 27 + (26 - code[e]);
+  int lo = row_ptr[j], hi = row_ptr[j + 1] - 1;
+  int found = -1;
+  while (lo <= hi) {
+    int mid = (lo + hi) >> 1;
+    int k = sender[mid] * 27 + code[mid];
+    if (k == want) { found = mid; break; }
+    if (k < want) lo = mid + 1; else hi = mid - 1;
+  }
+  if (found < 0) atomicOr(flag, 2);
+  rev[e] = found;
+}
+
+__global__ void k_export_shift(const int32_t* __restrict__ code, int64_t E, int32_t* __restrict__ shift) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  int c = code[e];
+  shift[3 * e] = c / 9 - 1;
+  shift[3 * e + 1] = (c / 3) % 3 - 1;
+  shift[3 * e + 2] = c % 3 - 1;
+}
+
+template <typename T>
+T* alloc_n(mlip_ctx* ctx, int64_t n) {
+  return (T*)ctx_alloc(ctx, (size_t)std::max<int64_t>(n, 1) * sizeof(T));
+}
+
+}  // namespace
+
+int graph_alloc(mlip_ctx* ctx) {
+  const int64_t N = ctx->cfg.max_atoms, B = ctx->cfg.max_structs, E = ctx->cfg.max_edges;
+  ctx->max_bins = 2 * N + 8 * B;
+  bool ok = true;
+  ok &= (ctx->d_meta = alloc_n<StructMeta>(ctx, B)) != nullptr;
+  ok &= (ctx->d_atom_struct = alloc_n<int32_t>(ctx, N)) != nullptr;
+  ok &= (ctx->d_atom_bin = alloc_n<int32_t>(ctx, N)) != nullptr;
+  ok &= (ctx->d_bin_count = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
+  ok &= (ctx->d_bin_start = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
+  ok &= (ctx->d_bin_cursor = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
+  ok &= (ctx->d_bin_atoms = alloc_n<int32_t>(ctx, N)) != nullptr;
+  ok &= (ctx->d_deg = alloc_n<int32_t>(ctx, N + 1)) != nullptr;
+  ok &= (ctx->d_row_ptr = alloc_n<int32_t>(ctx, N + 1)) != nullptr;
+  ok &= (ctx->d_key_tmp = alloc_n<int32_t>(ctx, E)) != nullptr;
+  ok &= (ctx->d_sender = alloc_n<int32_t>(ctx, E)) != nullptr;
+  ok &= (ctx->d_code = alloc_n<int32_t>(ctx, E)) != nullptr;
+  ok &= (ctx->d_receiver = alloc_n<int32_t>(ctx, E)) != nullptr;
+  ok &= (ctx->d_rev = alloc_n<int32_t>(ctx, E)) != nullptr;
+  int64_t scan_blocks = (std::max(N, ctx->max_bins) + SCAN_TILE) / SCAN_TILE + 1;
+  ok &= (ctx->d_scan_tmp = alloc_n<int32_t>(ctx, scan_blocks)) != nullptr;
+  ok &= (ctx->d_flag = alloc_n<int32_t>(ctx, 4)) != nullptr;
+  return ok ? MLIP_OK : MLIP_E_HIP;
+}
+
+int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* struct_ptr,
+                const float* cell, float cutoff, int64_t* n_edges_host) {
+  ctx->phase = PH_NONE;
+  if (!pos || !struct_ptr || !cell || !n_edges_host) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: null pointer");
+  if (n_atoms <= 0 || n_structs <= 0) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: n_atoms and n_structs must be positive");
+  if (!(cutoff > 0.f) || !std::isfinite(cutoff)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff must be positive");
+  *n_edges_host = 0;
+  if (n_atoms > ctx->cfg.max_atoms) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: n_atoms exceeds max_atoms");
+  if (n_structs > ctx->cfg.max_structs) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: n_structs exceeds max_structs");
+  const int N = (int)n_atoms, B = n_structs;
+  hipStream_t st = ctx->stream;
+
+  ctx->h_struct_ptr.resize(B + 1);
+  ctx->h_cell.resize((size_t)B * 9);
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->h_struct_ptr.data(), struct_ptr, sizeof(int32_t) * (B + 1), hipMemcpyDeviceToHost, st));
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->h_cell.data(), cell, sizeof(float) * 9 * B, hipMemcpyDeviceToHost, st));
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(st));
+
+  // validate and lay out the bins on the host
+  ctx->h_meta.resize(B);
+  if (ctx->h_struct_ptr[0] != 0 || ctx->h_struct_ptr[B] != N)
+    MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: struct_ptr must start at 0 and end at n_atoms");
+  int64_t bins = 0;
+  for (int s = 0; s < B; ++s) {
+    StructMeta& m = ctx->h_meta[s];
+    m.atom_begin = ctx->h_struct_ptr[s];
+    m.atom_end = ctx->h_struct_ptr[s + 1];
+    if (m.atom_end < m.atom_begin) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: struct_ptr must be non-decreasing");
+    const float* c = &ctx->h_cell[(size_t)s * 9];
+    for (int a = 0; a < 3; ++a)
+      for (int b = 0; b < 3; ++b)
+        if (a != b && c[3 * a + b] != 0.f) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "graph_build: only orthorhombic (diagonal) cells are supported");
+    int64_t cap = std::max<int64_t>(8, 2 * (int64_t)(m.atom_end - m.atom_begin));
+    for (int a = 0; a < 3; ++a) {
+      m.L[a] = c[4 * a];
+      if (!(m.L[a] > 0.f) || !std::isfinite(m.L[a])) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell edge must be positive");
+      if (cutoff > m.L[a]) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a cell edge");
+      // bins at least (1 + 1e-5) r_c wide, so rounding in the bin assignment cannot lose a neighbour
+      m.nb[a] = std::max(1, (int)std::floor((double)m.L[a] / ((double)cutoff * (1.0 + 1e-5))));
+    }
+    // coarser bins are still correct: cap the bin count near the atom count
+    while ((int64_t)m.nb[0] * m.nb[1] * m.nb[2] > cap) {
+      int a = (m.nb[0] >= m.nb[1] && m.nb[0] >= m.nb[2]) ? 0 : (m.nb[1] >= m.nb[2] ? 1 : 2);
+      m.nb[a] = std::max(1, m.nb[a] - 1);
+    }
+    m.bin_base = (int32_t)bins;
+    bins += (int64_t)m.nb[0] * m.nb[1] * m.nb[2];
+  }
+  if (bins > ctx->max_bins) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: bin table too small");
+  const int n_bins = (int)bins;
+
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_meta, ctx->h_meta.data(), sizeof(StructMeta) * B, hipMemcpyHostToDevice, st));
+  MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_count, 0, sizeof(int32_t) * (n_bins + 1), st));
+  MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_cursor, 0, sizeof(int32_t) * (n_bins + 1), st));
+  MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_flag, 0, sizeof(int32_t) * 4, st));
+
+  const int TB = 256;
+  hipLaunchKernelGGL(k_bin_count, dim3((N + TB - 1) / TB), dim3(TB), 0, st, pos, ctx->d_meta, B, N, ctx->d_atom_struct,
+                     ctx->d_atom_bin, ctx->d_bin_count, ctx->d_flag);
+  MLIP_TRY(scan_exclusive(ctx, ctx->d_bin_count, ctx->d_bin_start, n_bins));
+  hipLaunchKernelGGL(k_bin_fill, dim3((N + TB - 1) / TB), dim3(TB), 0, st, ctx->d_atom_bin, ctx->d_bin_start,
+                     ctx->d_bin_cursor, ctx->d_bin_atoms, N);
+  const int rows_per_block = TB / 64;
+  const int nb_rows = (N + rows_per_block - 1) / rows_per_block;
+  const float rc2 = cutoff * cutoff;
+  hipLaunchKernelGGL(k_neighbours<false>, dim3(nb_rows), dim3(TB), 0, st, pos, ctx->d_meta, ctx->d_atom_struct,
+                     ctx->d_atom_bin, ctx->d_bin_start, ctx->d_bin_atoms, N, rc2, ctx->d_deg, nullptr, nullptr);
+  MLIP_TRY(scan_exclusive(ctx, ctx->d_deg, ctx->d_row_ptr, N));
+  int32_t h_tail[1] = {0};
+  int32_t h_flag[4] = {0, 0, 0, 0};
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_tail, ctx->d_row_ptr + N, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_flag, ctx->d_flag, sizeof(int32_t) * 4, hipMemcpyDeviceToHost, st));
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  if (h_flag[0] & 1) MLIP_FAIL(ctx, MLIP_E_POSITION, "graph_build: a position is outside its cell or not finite");
+  const int64_t E = h_tail[0];
+  *n_edges_host = E;
+  if (E > ctx->cfg.max_edges) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: edge count exceeds max_edges");
+  if (E > 0) {
+    hipLaunchKernelGGL(k_neighbours<true>, dim3(nb_rows), dim3(TB), 0, st, pos, ctx->d_meta, ctx->d_atom_struct,
+                       ctx->d_atom_bin, ctx->d_bin_start, ctx->d_bin_atoms, N, rc2, nullptr, ctx->d_row_ptr,
+                       ctx->d_key_tmp);
+    hipLaunchKernelGGL(k_sort_rows, dim3(nb_rows), dim3(TB), 0, st, ctx->d_row_ptr, ctx->d_key_tmp, N, ctx->d_sender,
+                       ctx->d_code, ctx->d_receiver);
+    hipLaunchKernelGGL(k_reverse_map, dim3((unsigned)((E + TB - 1) / TB)), dim3(TB), 0, st, ctx->d_row_ptr,
+                       ctx->d_sender, ctx->d_code, ctx->d_receiver, E, ctx->d_rev, ctx->d_flag);
+  }
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  ctx->N = N;
+  ctx->B = B;
+  ctx->E = E;
+  ctx->phase = PH_GRAPH;
+  return MLIP_OK;
+}
+
+int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev) {
+  if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "graph_export: no graph has been built");
+  hipStream_t st = ctx->stream;
+  const int64_t E = ctx->E;
+  if (row_ptr) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(row_ptr, ctx->d_row_ptr, sizeof(int32_t) * (ctx->N + 1), hipMemcpyDeviceToDevice, st));
+  if (E > 0) {
+    if (sender) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(sender, ctx->d_sender, sizeof(int32_t) * E, hipMemcpyDeviceToDevice, st));
+    if (rev) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(rev, ctx->d_rev, sizeof(int32_t) * E, hipMemcpyDeviceToDevice, st));
+    if (shift) {
+      hipLaunchKernelGGL(k_export_shift, dim3((unsigned)((E + 255) / 256)), dim3(256), 0, st, ctx->d_code, E, shift);
+      MLIP_HIP_CHECK(ctx, hipGetLastError());
+    }
+  }
+  return MLIP_OK;
+}

@@ -1,0 +1,734 @@
+// Invariant message-passing potential and its pipeline-stage variant: the four phases
+// FE / FF / BF / BE (paper, Sec. 2) with hand-derived adjoints, no autograd.
+//
+// Derivation used throughout.  The edge MLP depends on the geometry only through the edge
+// length r, so each layer's radial filter omega(r) = f_c(r) w(r) in R^C is carried together
+// with its derivative omega'(r) as a "jet" (two rows per edge).  With m_e = omega_e (.) h_j:
+//   FE  a_i = sum_e omega_e (.) h_j
+//   FF  mu_h[i] += sum_e omega_e (.) mu_a[j]          (the graph is symmetric and omega, r are
+//       F_i  = sum_e rhat_e sum_c omega'_e (h_j mu_a_i + h_i mu_a_j)   equal on opposite edges)
+//   BF  adot_i = sum_e rdot_e omega'_e (.) h_j + omega_e (.) hdot_j,  rdot_e = rhat_e.(v_j - v_i)
+//   BE  lam_h[i] += sum_e omega_e (.) lam_a[j] + rdot_e omega'_e (.) mu_a[j]
+// where mu = dE/d(.) (FF's activation gradients), dotted quantities are tangents along
+// v = -dL/dF, and lam = dPsi/d(.) with Psi = sum_s Ebar_s E_s + D_v E, whose parameter
+// gradient is dL/dtheta.  Weight gradients: products that involve a derivative row of a jet
+// (or a tangent) are the second-order term of Eq. 2 and are added by BF; products with value
+// rows are the merged first-order term and are added by BE.
+#include <algorithm>
+#include <cmath>
+
+#include "common.h"
+#include "functors.h"
+#include "gemm.h"
+
+namespace {
+
+using namespace fx;
+
+struct InvWs {
+  int L = 0, depth = 2;
+  float* paramsT = nullptr;
+  float* jphi = nullptr;   // [E][2][K]
+  float2* env = nullptr;   // [E] (f_c, f_c')
+  std::vector<float*> U[2];   // hidden pre-activations, jets [E][2][H]; U[0] level 1, U[1] level 2 (depth 3)
+  std::vector<float*> Om;     // [E][2][C]
+  std::vector<float*> Y[2];   // [E][H]  BF -> BE
+  float* X = nullptr;         // [E][max(C,H)] scratch
+  float* X2 = nullptr;
+  std::vector<float*> h, a, q, mu_h, mu_a, mu_q, mu_t, hd, ad, qd;
+  float* lam_h[2] = {nullptr, nullptr};
+  float* lam_q = nullptr;
+  float* lam_a = nullptr;
+  float* y = nullptr;
+  float* yd = nullptr;
+  float* lam_y = nullptr;
+  float* eps = nullptr;     // [N]
+  float* Facc = nullptr;    // [N,3]
+  float* v = nullptr;       // [N,3] copy taken at BF
+  float* Ebar = nullptr;    // [B]
+  float* partial = nullptr;
+  int64_t partial_cap = 0;
+};
+
+inline InvWs* ws_of(mlip_ctx* ctx) { return (InvWs*)ctx->model_ws; }
+
+// ------------------------------------------------------------------------------ small kernels
+__global__ void k_transpose(const float* __restrict__ src, float* __restrict__ dst, int rows, int cols) {
+  __shared__ float tile[32][33];
+  int c = blockIdx.x * 32 + threadIdx.x;
+  for (int r = blockIdx.y * 32 + threadIdx.y; r < min(rows, (int)(blockIdx.y + 1) * 32); r += 8)
+    if (c < cols) tile[r - blockIdx.y * 32][threadIdx.x] = src[(int64_t)r * cols + c];
+  __syncthreads();
+  int r2 = blockIdx.y * 32 + threadIdx.x;
+  for (int c2 = blockIdx.x * 32 + threadIdx.y; c2 < min(cols, (int)(blockIdx.x + 1) * 32); c2 += 8)
+    if (r2 < rows) dst[(int64_t)c2 * rows + r2] = tile[threadIdx.x][c2 - blockIdx.x * 32];
+}
+
+// Edge geometry and featurisation: unit vector, length, Gaussian basis jets, envelope jet.
+__global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
+                                const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
+                                const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta, int64_t E,
+                                int K, float rc, float4* __restrict__ geo, float2* __restrict__ env,
+                                float* __restrict__ jphi) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= E * K) return;
+  int64_t e = idx / K;
+  int k = (int)(idx % K);
+  int i = receiver[e], j = sender[e], c = code[e];
+  const StructMeta& m = meta[atom_struct[i]];
+  float sx = (float)(c / 9 - 1) * m.L[0], sy = (float)((c / 3) % 3 - 1) * m.L[1], sz = (float)(c % 3 - 1) * m.L[2];
+  float dx = (pos[3 * j] - pos[3 * i]) + sx;
+  float dy = (pos[3 * j + 1] - pos[3 * i + 1]) + sy;
+  float dz = (pos[3 * j + 2] - pos[3 * i + 2]) + sz;
+  float r = sqrtf(dx * dx + dy * dy + dz * dz);
+  float dmu = rc / (float)(K - 1);
+  float gamma = 0.5f / (dmu * dmu);
+  float t = r - (float)k * dmu;
+  float p = expf(-gamma * t * t);
+  jphi[(2 * e) * K + k] = p;
+  jphi[(2 * e + 1) * K + k] = -2.f * gamma * t * p;
+  if (k == 0) {
+    float inv = 1.f / r;
+    geo[e] = make_float4(dx * inv, dy * inv, dz * inv, r);
+    float w = 3.14159265358979323846f / rc;
+    float sn, cs;
+    sincosf(w * r, &sn, &cs);
+    env[e] = make_float2(0.5f * (1.f + cs), -0.5f * w * sn);
+  }
+}
+
+__global__ void k_embed(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C,
+                        float* __restrict__ h) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= N * C) return;
+  int64_t i = idx / C;
+  h[idx] = emb[(int64_t)species[i] * C + (idx % C)];
+}
+
+// Row-parallel gather kernels.  A row (receiver atom) is handled by TPR = C/4 threads, one
+// float4 of channels each; a block of 256 threads holds 256/TPR rows.
+struct RowThread {
+  int row, cq;
+  bool active;
+};
+__device__ __forceinline__ RowThread row_thread(int N, int CQ) {
+  int rpb = 256 / CQ;
+  int rl = threadIdx.x / CQ;
+  RowThread t;
+  t.cq = threadIdx.x % CQ;
+  t.row = blockIdx.x * rpb + rl;
+  t.active = (rl < rpb) && (t.row < N);
+  return t;
+}
+__device__ __forceinline__ void fma4(float4& acc, float4 a, float4 b) {
+  acc.x += a.x * b.x; acc.y += a.y * b.y; acc.z += a.z * b.z; acc.w += a.w * b.w;
+}
+__device__ __forceinline__ void fma4s(float4& acc, float s, float4 a, float4 b) {
+  acc.x += s * a.x * b.x; acc.y += s * a.y * b.y; acc.z += s * a.z * b.z; acc.w += s * a.w * b.w;
+}
+
+__global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const float* __restrict__ Om, const float* __restrict__ h, int N, int C,
+                                                float* __restrict__ a) {
+  RowThread t = row_thread(N, C / 4);
+  if (!t.active) return;
+  const int c0 = 4 * t.cq;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+#pragma unroll 4
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    fma4(acc, ld4(Om + (int64_t)(2 * e) * C + c0), ld4(h + (int64_t)j * C + c0));
+  }
+  *reinterpret_cast<float4*>(a + (int64_t)t.row * C + c0) = acc;
+}
+
+__global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const float4* __restrict__ geo, const float* __restrict__ Om,
+                                                const float* __restrict__ h, const float* __restrict__ mu_a,
+                                                const float* __restrict__ mu_h_next, int N, int C,
+                                                float* __restrict__ mu_h, float* __restrict__ Facc) {
+  __shared__ float3 red[256];
+  const int CQ = C / 4;
+  RowThread t = row_thread(N, CQ);
+  float3 f = make_float3(0.f, 0.f, 0.f);
+  if (t.active) {
+    const int c0 = 4 * t.cq;
+    const int64_t ro = (int64_t)t.row * C + c0;
+    float4 acc = ld4(mu_h_next + ro);
+    const float4 hi = ld4(h + ro), mai = ld4(mu_a + ro);
+    const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+#pragma unroll 2
+    for (int e = e0; e < e1; ++e) {
+      int j = sender[e];
+      float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+      float4 hj = ld4(h + (int64_t)j * C + c0), maj = ld4(mu_a + (int64_t)j * C + c0);
+      fma4(acc, w, maj);
+      float g = wp.x * (hj.x * mai.x + hi.x * maj.x) + wp.y * (hj.y * mai.y + hi.y * maj.y) +
+                wp.z * (hj.z * mai.z + hi.z * maj.z) + wp.w * (hj.w * mai.w + hi.w * maj.w);
+      float4 ge = geo[e];
+      f.x += g * ge.x; f.y += g * ge.y; f.z += g * ge.z;
+    }
+    *reinterpret_cast<float4*>(mu_h + ro) = acc;
+  }
+  red[threadIdx.x] = f;
+  __syncthreads();
+  if (t.active && t.cq == 0) {
+    float3 s = make_float3(0.f, 0.f, 0.f);
+    for (int k = 0; k < CQ; ++k) {
+      float3 x = red[threadIdx.x + k];
+      s.x += x.x; s.y += x.y; s.z += x.z;
+    }
+    Facc[3 * t.row] += s.x;
+    Facc[3 * t.row + 1] += s.y;
+    Facc[3 * t.row + 2] += s.z;
+  }
+}
+
+__device__ __forceinline__ float rdot_of(const float4& ge, const float* __restrict__ v, int i, int j) {
+  return ge.x * (v[3 * j] - v[3 * i]) + ge.y * (v[3 * j + 1] - v[3 * i + 1]) + ge.z * (v[3 * j + 2] - v[3 * i + 2]);
+}
+
+__global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const float4* __restrict__ geo, const float2* __restrict__ env,
+                                                const float* __restrict__ Om, const float* __restrict__ h,
+                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                                const float* __restrict__ v, int N, int C, float* __restrict__ ad,
+                                                float* __restrict__ X) {
+  RowThread t = row_thread(N, C / 4);
+  if (!t.active) return;
+  const int c0 = 4 * t.cq;
+  const int64_t ro = (int64_t)t.row * C + c0;
+  const float4 mai = ld4(mu_a + ro);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+#pragma unroll 2
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    float4 ge = geo[e];
+    float rd = rdot_of(ge, v, t.row, j);
+    float c = env[e].x;
+    float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+    float4 hj = ld4(h + (int64_t)j * C + c0), hdj = ld4(hd + (int64_t)j * C + c0);
+    fma4s(acc, rd, wp, hj);
+    fma4(acc, w, hdj);
+    float s = rd * c;
+    *reinterpret_cast<float4*>(X + (int64_t)e * C + c0) = make_float4(s * hj.x * mai.x, s * hj.y * mai.y, s * hj.z * mai.z, s * hj.w * mai.w);
+  }
+  *reinterpret_cast<float4*>(ad + ro) = acc;
+}
+
+__global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const float4* __restrict__ geo, const float2* __restrict__ env,
+                                                const float* __restrict__ Om, const float* __restrict__ h,
+                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                                const float* __restrict__ lam_a, const float* __restrict__ v,
+                                                const float* __restrict__ lam_h_next, int N, int C,
+                                                float* __restrict__ lam_h, float* __restrict__ X) {
+  RowThread t = row_thread(N, C / 4);
+  if (!t.active) return;
+  const int c0 = 4 * t.cq;
+  const int64_t ro = (int64_t)t.row * C + c0;
+  const float4 mai = ld4(mu_a + ro), lai = ld4(lam_a + ro);
+  float4 acc = ld4(lam_h_next + ro);
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+#pragma unroll 2
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    float4 ge = geo[e];
+    float rd = rdot_of(ge, v, t.row, j);
+    float2 cc = env[e];
+    float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+    const int64_t jo = (int64_t)j * C + c0;
+    float4 hj = ld4(h + jo), hdj = ld4(hd + jo), laj = ld4(lam_a + jo), maj = ld4(mu_a + jo);
+    fma4(acc, w, laj);
+    fma4s(acc, rd, wp, maj);
+    float s = cc.y * rd;
+    float4 x;
+    x.x = cc.x * (hj.x * lai.x + hdj.x * mai.x) + s * hj.x * mai.x;
+    x.y = cc.x * (hj.y * lai.y + hdj.y * mai.y) + s * hj.y * mai.y;
+    x.z = cc.x * (hj.z * lai.z + hdj.z * mai.z) + s * hj.z * mai.z;
+    x.w = cc.x * (hj.w * lai.w + hdj.w * mai.w) + s * hj.w * mai.w;
+    *reinterpret_cast<float4*>(X + (int64_t)e * C + c0) = x;
+  }
+  *reinterpret_cast<float4*>(lam_h + ro) = acc;
+}
+
+// eps_i = sum_c w_o[c] silu(y[i,c]); one wave per atom, fixed reduction order.
+__global__ void __launch_bounds__(256) k_atom_energy(const float* __restrict__ y, const float* __restrict__ wo, int N,
+                                                     int C, float* __restrict__ eps) {
+  int lane = threadIdx.x & 63;
+  int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += wo[c] * silu(y[(int64_t)i * C + c]);
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+  if (lane == 0) eps[i] = s;
+}
+
+__global__ void __launch_bounds__(256) k_struct_sum(const float* __restrict__ eps, const StructMeta* __restrict__ meta,
+                                                    float* __restrict__ E) {
+  __shared__ float red[256];
+  const StructMeta& m = meta[blockIdx.x];
+  float s = 0.f;
+  for (int i = m.atom_begin + threadIdx.x; i < m.atom_end; i += 256) s += eps[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) E[blockIdx.x] = red[0];
+}
+
+// Column sums over atoms: out[c] += sum_i f(i, c), 64 channels x 4 atom lanes per block.
+// MODE 0: silu'(y) * yd     MODE 1: Ebar[struct(i)] * silu(y)
+template <int MODE>
+__global__ void __launch_bounds__(256) k_wo_grad(const float* __restrict__ y, const float* __restrict__ yd,
+                                                 const float* __restrict__ Ebar, const int32_t* __restrict__ atom_struct,
+                                                 int N, int C, float* __restrict__ out) {
+  __shared__ float red[4][64];
+  int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  int al = threadIdx.x >> 6;
+  float s = 0.f;
+  if (c < C)
+    for (int i = al; i < N; i += 4) {
+      float yy = y[(int64_t)i * C + c];
+      s += (MODE == 0) ? dsilu(yy) * yd[(int64_t)i * C + c] : Ebar[atom_struct[i]] * silu(yy);
+    }
+  red[al][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (al == 0 && c < C) out[c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+__global__ void k_lam_y(const float* __restrict__ y, const float* __restrict__ yd, const float* __restrict__ wo,
+                        const float* __restrict__ Ebar, const int32_t* __restrict__ atom_struct, int64_t N, int C,
+                        float* __restrict__ lam_y) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= N * C) return;
+  int64_t i = idx / C;
+  int c = (int)(idx % C);
+  float d1, d2;
+  dsilu12(y[idx], d1, d2);
+  lam_y[idx] = wo[c] * (Ebar[atom_struct[i]] * d1 + d2 * yd[idx]);
+}
+
+__global__ void __launch_bounds__(256) k_emb_grad(const float* __restrict__ lam_h0, const int32_t* __restrict__ species,
+                                                  int N, int C, float* __restrict__ gemb) {
+  __shared__ float red[4][64];
+  int z = blockIdx.y;
+  int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  int al = threadIdx.x >> 6;
+  float s = 0.f;
+  if (c < C)
+    for (int i = al; i < N; i += 4)
+      if (species[i] == z) s += lam_h0[(int64_t)i * C + c];
+  red[al][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (al == 0 && c < C)
+    gemb[(int64_t)z * C + c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+__global__ void k_scale3(const float* __restrict__ src, float s, int64_t n, float* __restrict__ dst) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) dst[idx] = s * src[idx];
+}
+
+__global__ void k_fill(float* __restrict__ p, float val, int64_t n) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) p[idx] = val;
+}
+
+__global__ void k_reduce_partials(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ grad) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + idx];
+  grad[idx] += s;
+}
+
+// Loss, one block: deterministic tree.  loss = mean_s (E-Eref)^2 + fw * mean (F-Fref)^2.
+__global__ void __launch_bounds__(1024) k_loss(const float* __restrict__ E, const float* __restrict__ Eref, int B,
+                                               const float* __restrict__ F, const float* __restrict__ Fref, int64_t n3,
+                                               float fw, float* __restrict__ loss) {
+  __shared__ float red[1024];
+  float se = 0.f, sf = 0.f;
+  for (int s = threadIdx.x; s < B; s += 1024) {
+    float d = E[s] - Eref[s];
+    se += d * d;
+  }
+  for (int64_t k = threadIdx.x; k < n3; k += 1024) {
+    float d = F[k] - Fref[k];
+    sf += d * d;
+  }
+  red[threadIdx.x] = se / (float)B + fw * sf / (float)n3;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = red[0];
+}
+
+__global__ void k_loss_cotangents(const float* __restrict__ E, const float* __restrict__ Eref, int B,
+                                  const float* __restrict__ F, const float* __restrict__ Fref, int64_t n3, float fw,
+                                  float* __restrict__ Ebar, float* __restrict__ v) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < B) Ebar[idx] = 2.f * (E[idx] - Eref[idx]) / (float)B;
+  if (idx < n3) v[idx] = -2.f * fw * (F[idx] - Fref[idx]) / (float)n3;
+}
+
+inline unsigned nblk(int64_t n, int b = 256) { return (unsigned)((n + b - 1) / b); }
+
+template <typename T>
+T* alloc_n(mlip_ctx* ctx, int64_t n) {
+  return (T*)ctx_alloc(ctx, (size_t)std::max<int64_t>(n, 1) * sizeof(T));
+}
+
+// ------------------------------------------------------------------------------ GEMM wrappers
+// D[M][N] = A[M][K] * W[N][K]^T with loader / epilogue functors; tile chosen from N.
+template <typename P, typename LdA, typename Epi>
+void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
+  LdPlain b{W, K};
+  const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+  if (N > 64 && tiles128 >= 512)
+    gemm::launch<P, 2, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
+  else
+    gemm::launch<P, 1, 1, 2, 2, true>(st, a, b, epi, M, N, K, 1);
+}
+
+int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
+  int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
+  int64_t s = std::max<int64_t>(1, 1536 / tiles);
+  s = std::min<int64_t>(s, std::max<int64_t>(1, K / 256));
+  return (int)std::min<int64_t>(s, 1024);
+}
+
+// grad[Nout][Kout] += A^T B, A [R][Nout], B [R][Kout] given by loaders (reduction over R rows).
+template <typename P, typename LdA, typename LdB>
+int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
+  InvWs* w = ws_of(ctx);
+  hipStream_t st = ctx->stream;
+  if (R <= 0) return MLIP_OK;
+  const bool narrow = Kout <= 32;
+  const int bm = narrow ? 128 : (Nout > 64 ? 128 : 64), bn = narrow ? 32 : (Nout > 64 ? 128 : 64);
+  int splits = pick_splits(Nout, Kout, R, bm, bn);
+  while ((int64_t)splits * Nout * Kout > w->partial_cap && splits > 1) --splits;
+  EpiPartial epi{w->partial, Kout, Nout};
+  if (narrow)
+    gemm::launch<P, 1, 1, 4, 1, false>(st, a, b, epi, Nout, Kout, R, splits);
+  else if (Nout > 64)
+    gemm::launch<P, 2, 2, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
+  else
+    gemm::launch<P, 1, 1, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
+  int64_t n = (int64_t)Nout * Kout;
+  hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n)), dim3(256), 0, st, w->partial, splits, n, grad);
+  return MLIP_OK;
+}
+
+// ------------------------------------------------------------------------------ phases
+template <typename P>
+int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
+  InvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
+  const float* th = ctx->d_params;
+  const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
+
+  // transposed copies of every matrix, for the data-gradient products of the later phases
+  auto tr = [&](int64_t off, int rows, int cols) {
+    hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
+  };
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    if (d == 3) { tr(lo.W[1], H, H); tr(lo.W[2], C, H); } else { tr(lo.W[1], C, H); }
+    tr(lo.V1, C, C);
+    tr(lo.V2, C, C);
+  }
+  if (!stage) tr(ctx->off_U, C, C);
+
+  if (E > 0)
+    hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
+                       ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
+  if (stage)
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->h[0], h_in, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  else
+    hipLaunchKernelGGL(k_embed, dim3(nblk(N * C)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);
+
+  const int rpb = 256 / (C / 4);
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    if (E > 0) {
+      gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[0][l], H, 2 * E});
+      const float* ulast = w->U[0][l];
+      if (d == 3) {
+        gemm_nt<P>(st, LdJetSilu{w->U[0][l], H}, th + lo.W[1], 2 * E, H, H, EpiStore{w->U[1][l], H, 2 * E});
+        ulast = w->U[1][l];
+      }
+      gemm_nt<P>(st, LdJetSilu{ulast, H}, th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
+    }
+    hipLaunchKernelGGL(k_msg_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
+                       (int)N, C, w->a[l]);
+    gemm_nt<P>(st, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
+    gemm_nt<P>(st, LdSilu{w->q[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->h[l + 1], w->h[l], C, N});
+  }
+  if (stage) {
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_out, w->h[L], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  } else {
+    gemm_nt<P>(st, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
+    hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
+    hipLaunchKernelGGL(k_struct_sum, dim3(ctx->B), dim3(256), 0, st, w->eps, ctx->d_meta, E_out);
+  }
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
+  InvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N;
+  const int C = cf.channels, L = cf.n_layers;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
+  if (stage)
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->mu_h[L], g_out, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  else  // mu_y = w_o silu'(y);  mu_h^L = mu_y U
+    gemm_nt<P>(st, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
+  hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
+  const int rpb = 256 / (C / 4);
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    gemm_nt<P>(st, LdPlain{w->mu_h[l + 1], C}, tT + lo.V2, N, C, C, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
+    gemm_nt<P>(st, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
+    hipLaunchKernelGGL(k_msg_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
+                       w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+  }
+  // F_i = + sum_e g_e rhat_e = -dE/dx_i ; a stage reports its contribution to +dE/dx
+  hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, stage ? -1.f : 1.f, 3 * N, F);
+  if (stage) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(g_in, w->mu_h[0], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
+  InvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
+  if (stage && hdot_in)
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->hd[0], hdot_in, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  else
+    hipLaunchKernelGGL(k_fill, dim3(nblk(N * C)), dim3(256), 0, st, w->hd[0], 0.f, N * C);
+  const int rpb = 256 / (C / 4);
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    hipLaunchKernelGGL(k_msg_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                       w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+    gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
+    gemm_nt<P>(st, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
+    // second-order weight gradients of the update MLP: mu_{h'}^T tdot, mu_q^T adot
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1], C}, LdDsiluMul{w->q[l], w->qd[l], C}, N, C, C, grad + lo.V2)));
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_q[l], C}, LdPlain{w->ad[l], C}, N, C, C, grad + lo.V1)));
+    if (E > 0) {
+      // X = rdot * mu_w (adjoint of the derivative row w').  Chain back through the jets' derivative rows.
+      const float* ulast = w->U[d - 2][l];
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluOdd{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+      gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiYZ{w->Y[d - 2][l], w->X2, ulast, H, E});
+      if (d == 3) {
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluOdd{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
+        gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiYZ{w->Y[0][l], w->X, w->U[0][l], H, E});
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+      } else {
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+      }
+    }
+  }
+  if (stage) {
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(hdot_out, w->hd[L], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  } else {
+    gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
+    hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, grad + ctx->off_wo);
+  }
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
+  InvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
+  int cur = 0;
+  if (stage) {
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->lam_h[cur], lam_out, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  } else {
+    hipLaunchKernelGGL(k_lam_y, dim3(nblk(N * C)), dim3(256), 0, st, w->y, w->yd, th + ctx->off_wo, w->Ebar, ctx->d_atom_struct, N, C, w->lam_y);
+    hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, grad + ctx->off_wo);
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
+    gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
+  }
+  const int rpb = 256 / (C / 4);
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    float* lh_next = w->lam_h[cur];
+    float* lh = w->lam_h[cur ^ 1];
+    gemm_nt<P>(st, LdPlain{lh_next, C}, tT + lo.V2, N, C, C, EpiLamQ{w->lam_q, w->q[l], w->qd[l], w->mu_t[l], C, N});
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next, C}, LdSilu{w->q[l], C}, N, C, C, grad + lo.V2)));
+    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_q, C}, LdPlain{w->a[l], C}, N, C, C, grad + lo.V1)));
+    gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
+    hipLaunchKernelGGL(k_msg_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                       w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+    if (E > 0) {
+      const float* ulast = w->U[d - 2][l];
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluEven{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+      gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiLamU{w->X2, ulast, w->Y[d - 2][l], H, E});
+      if (d == 3) {
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluEven{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
+        gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiLamU{w->X, w->U[0][l], w->Y[0][l], H, E});
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+      } else {
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+      }
+    }
+    cur ^= 1;
+  }
+  if (stage)
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(lam_in, w->lam_h[cur], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
+  else
+    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, cf.n_species), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, grad + ctx->off_emb);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+}  // namespace
+
+// =================================================================================== interface
+int model_alloc(mlip_ctx* ctx) {
+  const mlip_config& cf = ctx->cfg;
+  const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
+  if (cf.model_kind == MLIP_MODEL_EQUIVARIANT) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: not built into this library yet");
+  InvWs* w = new InvWs();
+  ctx->model_ws = w;
+  w->L = L;
+  w->depth = d;
+  bool ok = true;
+  auto A = [&](int64_t n) { float* p = alloc_n<float>(ctx, n); ok &= (p != nullptr); return p; };
+  ok &= (ctx->d_pos = alloc_n<float>(ctx, 3 * N)) != nullptr;
+  ok &= (ctx->d_params = alloc_n<float>(ctx, ctx->n_params)) != nullptr;
+  ok &= (ctx->d_species = alloc_n<int32_t>(ctx, N)) != nullptr;
+  ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
+  w->paramsT = A(ctx->n_params);
+  w->jphi = A(2 * E * K);
+  ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
+  const int64_t Wmax = std::max(C, H);
+  w->X = A(E * Wmax);
+  w->X2 = A(E * Wmax);
+  for (int l = 0; l < L; ++l) {
+    w->U[0].push_back(A(2 * E * H));
+    w->U[1].push_back(d == 3 ? A(2 * E * H) : nullptr);
+    w->Om.push_back(A(2 * E * C));
+    w->Y[0].push_back(A(E * H));
+    w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);
+    w->a.push_back(A(N * C)); w->q.push_back(A(N * C));
+    w->mu_a.push_back(A(N * C)); w->mu_q.push_back(A(N * C)); w->mu_t.push_back(A(N * C));
+    w->ad.push_back(A(N * C)); w->qd.push_back(A(N * C));
+  }
+  for (int l = 0; l <= L; ++l) {
+    w->h.push_back(A(N * C)); w->mu_h.push_back(A(N * C)); w->hd.push_back(A(N * C));
+  }
+  w->lam_h[0] = A(N * C); w->lam_h[1] = A(N * C); w->lam_q = A(N * C); w->lam_a = A(N * C);
+  w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
+  w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
+  // split-k partial sums: the largest weight matrix times its split count
+  int64_t cap = 0;
+  auto need = [&](int64_t rows, int cols, int64_t R) {
+    const bool narrow = cols <= 32;
+    int bm = narrow ? 128 : (rows > 64 ? 128 : 64), bn = narrow ? 32 : (rows > 64 ? 128 : 64);
+    cap = std::max<int64_t>(cap, (int64_t)pick_splits(rows, cols, R, bm, bn) * rows * cols);
+  };
+  need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
+  w->partial_cap = cap;
+  w->partial = A(cap);
+  if (!ok) return MLIP_E_HIP;
+  return MLIP_OK;
+}
+
+void model_free(mlip_ctx* ctx) {
+  delete ws_of(ctx);
+  ctx->model_ws = nullptr;
+}
+
+#define DISPATCH(fn, ...) (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16 ? fn<gemm::Bf16>(__VA_ARGS__) : fn<gemm::Fp32>(__VA_ARGS__))
+
+int model_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
+                         float* E, float* h_out) {
+  const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
+  if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: build the graph first");
+  if (!pos || !params) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: null pos or params");
+  if (stage ? (!h_in || !h_out) : (!species || !E)) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: missing tensor for this model kind");
+  hipStream_t st = ctx->stream;
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
+  if (!stage) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_species, species, sizeof(int32_t) * ctx->N, hipMemcpyDeviceToDevice, st));
+  MLIP_TRY(DISPATCH(fe_impl, ctx, h_in, E, h_out));
+  ctx->phase = PH_FE;
+  return MLIP_OK;
+}
+
+int model_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
+  const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
+  if (ctx->phase < PH_FE) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_force: run forward_energy first");
+  if (!F || (stage && (!g_out || !g_in))) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_force: missing tensor for this model kind");
+  MLIP_TRY(DISPATCH(ff_impl, ctx, g_out, F, g_in));
+  ctx->phase = PH_FF;
+  return MLIP_OK;
+}
+
+int model_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
+               float* Ebar, float* v) {
+  if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "loss: no batch");
+  if (!E || !F || !E_ref || !F_ref || !loss || !Ebar || !v) MLIP_FAIL(ctx, MLIP_E_INVALID, "loss: null pointer");
+  const int64_t n3 = 3 * ctx->N;
+  hipLaunchKernelGGL(k_loss, dim3(1), dim3(1024), 0, ctx->stream, E, E_ref, ctx->B, F, F_ref, n3, ctx->cfg.force_weight, loss);
+  hipLaunchKernelGGL(k_loss_cotangents, dim3(nblk(std::max<int64_t>(n3, ctx->B))), dim3(256), 0, ctx->stream, E, E_ref, ctx->B, F,
+                     F_ref, n3, ctx->cfg.force_weight, Ebar, v);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+int model_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out) {
+  const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
+  if (ctx->phase < PH_FF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_force: run forward_force first");
+  if (!v || !grad || (stage && !hdot_out)) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_force: missing tensor for this model kind");
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->v, v, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, ctx->stream));
+  MLIP_TRY(DISPATCH(bf_impl, ctx, hdot_in, grad, hdot_out));
+  ctx->phase = PH_BF;
+  return MLIP_OK;
+}
+
+int model_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in) {
+  const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
+  if (ctx->phase < PH_BF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_energy: run backward_force first");
+  if (!grad || (stage ? (!lam_out || !lam_in) : !Ebar)) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_energy: missing tensor for this model kind");
+  if (!stage) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->Ebar, Ebar, sizeof(float) * ctx->B, hipMemcpyDeviceToDevice, ctx->stream));
+  MLIP_TRY(DISPATCH(be_impl, ctx, lam_out, grad, lam_in));
+  ctx->phase = PH_BE;
+  return MLIP_OK;
+}

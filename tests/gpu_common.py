@@ -1,0 +1,71 @@
+"""Helpers shared by the GPU parity tests: device copies of seeded inputs, the oracle run per
+structure, and the normwise error measure."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import mlip_oracle as O
+from paper_2605_18404_amd import synth
+from paper_2605_18404_amd.binding import Mlip
+
+DEV = "cuda:0"
+
+
+def rel(a, b):
+    """||a - b||_2 / ||b||_2 in float64 (b is the oracle)."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    b = np.asarray(b, dtype=np.float64).ravel()
+    nb = np.linalg.norm(b)
+    if nb < 1e-30:
+        return float(np.linalg.norm(a - b))
+    return float(np.linalg.norm(a - b) / nb)
+
+
+def dev(x):
+    return torch.as_tensor(np.ascontiguousarray(x)).to(DEV)
+
+
+class DevInputs:
+    def __init__(self, inp: synth.Inputs):
+        self.pos, self.species = dev(inp.pos), dev(inp.species)
+        self.struct_ptr, self.cell = dev(inp.struct_ptr), dev(inp.cell)
+        self.params, self.E_ref, self.F_ref = dev(inp.params), dev(inp.E_ref), dev(inp.F_ref)
+        self.stage = {k: dev(v) for k, v in inp.stage.items()}
+
+
+def oracle_train_step(w, inp, split=False):
+    """Oracle results for a batch, one structure at a time (structures do not interact):
+    E and F per structure; loss and gradient assembled from the per-structure terms."""
+    cfg = O.cfg_from_workload(w)
+    B, N = len(inp.struct_ptr) - 1, inp.pos.shape[0]
+    E = np.zeros(B)
+    F = np.zeros((N, 3))
+    keys = ["grad"] + (["grad_bf", "grad_be"] if split else [])
+    g = {k: np.zeros(inp.params.shape[0]) for k in keys}
+    loss = 0.0
+    for s in range(B):
+        a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
+        # the batch loss is mean_s(.) + fw * mean over all 3N components: rescale a single
+        # structure's loss terms so that the sum over structures equals the batch loss
+        n = b - a
+        sub = dict(cfg)
+        sub["force_weight"] = cfg["force_weight"] * (n / N) * B
+        r = O.train_step(sub, inp.pos[a:b], inp.species[a:b], np.array([0, n], np.int32), inp.cell[s:s + 1],
+                         inp.params, inp.E_ref[s:s + 1], inp.F_ref[a:b], split=split)
+        E[s] = r["E"][0]
+        F[a:b] = r["F"]
+        loss += r["loss"] / B
+        for k in keys:
+            g[k] += r[k] / B
+    out = dict(E=E, F=F, loss=loss)
+    out.update(g)
+    return out
+
+
+def per_tensor_rel(w, got, want):
+    res = {}
+    for name, (off, shp) in synth.param_slices(w).items():
+        n = int(np.prod(shp))
+        res[name] = rel(got[off:off + n], want[off:off + n])
+    return res
