@@ -109,7 +109,7 @@ struct Stager {
 // of column col (the functor checks row0 + j < M itself; col < N is guaranteed), z = split index.
 template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
 __global__ void __launch_bounds__(256)
-k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk) {
+k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, int splits) {
   static_assert(WM * WN == 4, "four waves per workgroup");
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, BK = P::BK;
   typedef typename P::lds_t lds_t;
@@ -120,16 +120,18 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk) 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int li = lane & 31, g = lane >> 5;
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): the column tiles of
-  // one row tile are given to the same XCD, one after the other, so the A rows are fetched once.
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  A group is one
+  // (row tile, k split); its column tiles go to the same XCD one after the other, so the A rows
+  // are fetched into one L2 only, and consecutive groups spread over all XCDs.
   const int tiles_n = (N + BN - 1) / BN;
   const int64_t tiles_m = (M + BM - 1) / BM;
   const int64_t local = blockIdx.x >> 3;
-  const int64_t m_tile = (local / tiles_n) * 8 + (blockIdx.x & 7);
-  if (m_tile >= tiles_m) return;  // uniform for the workgroup, before any barrier
-  const int64_t m0 = m_tile * BM;
+  const int64_t group = (local / tiles_n) * 8 + (blockIdx.x & 7);
+  if (group >= tiles_m * splits) return;  // uniform for the workgroup, before any barrier
+  const int z = (int)(group / tiles_m);
+  const int64_t m0 = (group % tiles_m) * BM;
   const int n0 = (int)(local % tiles_n) * BN;
-  const int64_t kb = (int64_t)blockIdx.y * k_chunk;
+  const int64_t kb = (int64_t)z * k_chunk;
   const int64_t ke = (kb + k_chunk < K) ? kb + k_chunk : K;
 
   floatx16 acc[TM][TN];
@@ -207,7 +209,7 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk) 
           const int64_t row0 = m0 + (wm * TM + i) * 32 + 8 * qq + 4 * g;
           if (row0 < M) {
             float v[4] = {acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]};
-            epi(row0, col, v, (int)blockIdx.y);
+            epi(row0, col, v, z);
           }
         }
       }
@@ -223,8 +225,8 @@ inline void launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int
   k_chunk = (k_chunk + P::BK - 1) / P::BK * P::BK;
   if (k_chunk < P::BK) k_chunk = P::BK;
   const int64_t tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
-  dim3 grid((unsigned)(((tiles_m + 7) / 8) * 8 * tiles_n), (unsigned)splits, 1);
-  hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk);
+  dim3 grid((unsigned)(((tiles_m * splits + 7) / 8) * 8 * tiles_n), 1, 1);
+  hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk, splits);
 }
 
 }  // namespace gemm

@@ -281,24 +281,27 @@ __global__ void __launch_bounds__(256) k_struct_sum(const float* __restrict__ ep
   if (threadIdx.x == 0) E[blockIdx.x] = red[0];
 }
 
-// Column sums over atoms: out[c] += sum_i f(i, c), 64 channels x 4 atom lanes per block.
+// Column sums over atoms in two deterministic stages: part[chunk][c] = sum over the chunk's
+// atoms of f(i, c) (64 channels x 4 atom lanes per block), then k_reduce_partials.
 // MODE 0: silu'(y) * yd     MODE 1: Ebar[struct(i)] * silu(y)
 template <int MODE>
 __global__ void __launch_bounds__(256) k_wo_grad(const float* __restrict__ y, const float* __restrict__ yd,
                                                  const float* __restrict__ Ebar, const int32_t* __restrict__ atom_struct,
-                                                 int N, int C, float* __restrict__ out) {
+                                                 int N, int C, int chunk_len, float* __restrict__ part) {
   __shared__ float red[4][64];
   int c = blockIdx.x * 64 + (threadIdx.x & 63);
   int al = threadIdx.x >> 6;
+  int i0 = blockIdx.y * chunk_len, i1 = min(N, i0 + chunk_len);
   float s = 0.f;
   if (c < C)
-    for (int i = al; i < N; i += 4) {
+    for (int i = i0 + al; i < i1; i += 4) {
       float yy = y[(int64_t)i * C + c];
       s += (MODE == 0) ? dsilu(yy) * yd[(int64_t)i * C + c] : Ebar[atom_struct[i]] * silu(yy);
     }
   red[al][threadIdx.x & 63] = s;
   __syncthreads();
-  if (al == 0 && c < C) out[c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  if (al == 0 && c < C)
+    part[(int64_t)blockIdx.y * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
 __global__ void k_lam_y(const float* __restrict__ y, const float* __restrict__ yd, const float* __restrict__ wo,
@@ -313,20 +316,22 @@ __global__ void k_lam_y(const float* __restrict__ y, const float* __restrict__ y
   lam_y[idx] = wo[c] * (Ebar[atom_struct[i]] * d1 + d2 * yd[idx]);
 }
 
+// part[chunk][z][c] = sum over the chunk's atoms of species z of lam_h0[i][c].
 __global__ void __launch_bounds__(256) k_emb_grad(const float* __restrict__ lam_h0, const int32_t* __restrict__ species,
-                                                  int N, int C, float* __restrict__ gemb) {
+                                                  int N, int C, int S, int chunk_len, float* __restrict__ part) {
   __shared__ float red[4][64];
-  int z = blockIdx.y;
+  int z = blockIdx.z;
   int c = blockIdx.x * 64 + (threadIdx.x & 63);
   int al = threadIdx.x >> 6;
+  int i0 = blockIdx.y * chunk_len, i1 = min(N, i0 + chunk_len);
   float s = 0.f;
   if (c < C)
-    for (int i = al; i < N; i += 4)
+    for (int i = i0 + al; i < i1; i += 4)
       if (species[i] == z) s += lam_h0[(int64_t)i * C + c];
   red[al][threadIdx.x & 63] = s;
   __syncthreads();
   if (al == 0 && c < C)
-    gemb[(int64_t)z * C + c] += (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    part[((int64_t)blockIdx.y * S + z) * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
 __global__ void k_scale3(const float* __restrict__ src, float s, int64_t n, float* __restrict__ dst) {
@@ -339,12 +344,26 @@ __global__ void k_fill(float* __restrict__ p, float val, int64_t n) {
   if (idx < n) p[idx] = val;
 }
 
-__global__ void k_reduce_partials(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ grad) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n) return;
-  float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + idx];
-  grad[idx] += s;
+// grad[i] += sum_z part[z][i]: 64 elements x 4 split groups per block, fixed summation order.
+__global__ void __launch_bounds__(256) k_reduce_partials(const float* __restrict__ part, int splits, int64_t n,
+                                                         float* __restrict__ grad) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, zg = threadIdx.x >> 6;
+  const int64_t idx = (int64_t)blockIdx.x * 64 + lane;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (idx < n) {
+    int z = zg;
+    for (; z + 12 < splits; z += 16) {
+      s0 += part[(int64_t)z * n + idx];
+      s1 += part[(int64_t)(z + 4) * n + idx];
+      s2 += part[(int64_t)(z + 8) * n + idx];
+      s3 += part[(int64_t)(z + 12) * n + idx];
+    }
+    for (; z < splits; z += 4) s0 += part[(int64_t)z * n + idx];
+  }
+  red[zg][lane] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (zg == 0 && idx < n) grad[idx] += (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
 // Loss, one block: deterministic tree.  loss = mean_s (E-Eref)^2 + fw * mean (F-Fref)^2.
@@ -379,6 +398,7 @@ __global__ void k_loss_cotangents(const float* __restrict__ E, const float* __re
 }
 
 inline unsigned nblk(int64_t n, int b = 256) { return (unsigned)((n + b - 1) / b); }
+inline int atom_chunks(int64_t N) { return (int)std::max<int64_t>(1, std::min<int64_t>(128, N / 32)); }
 
 template <typename T>
 T* alloc_n(mlip_ctx* ctx, int64_t n) {
@@ -399,9 +419,9 @@ void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int
 
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
   int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
-  int64_t s = std::max<int64_t>(1, 1536 / tiles);
+  int64_t s = std::max<int64_t>(1, 768 / tiles);
   s = std::min<int64_t>(s, std::max<int64_t>(1, K / 256));
-  return (int)std::min<int64_t>(s, 1024);
+  return (int)std::min<int64_t>(s, 768);
 }
 
 // grad[Nout][Kout] += A^T B, A [R][Nout], B [R][Kout] given by loaders (reduction over R rows).
@@ -422,7 +442,7 @@ int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, i
   else
     gemm::launch<P, 1, 1, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
   int64_t n = (int64_t)Nout * Kout;
-  hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n)), dim3(256), 0, st, w->partial, splits, n, grad);
+  hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n, 64)), dim3(256), 0, st, w->partial, splits, n, grad);
   return MLIP_OK;
 }
 
@@ -558,7 +578,11 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   } else {
     gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
     MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
-    hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, grad + ctx->off_wo);
+    {
+      const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
+      hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, len, w->partial);
+      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)C, grad + ctx->off_wo);
+    }
   }
   MLIP_HIP_CHECK(ctx, hipGetLastError());
   return MLIP_OK;
@@ -579,7 +603,11 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->lam_h[cur], lam_out, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   } else {
     hipLaunchKernelGGL(k_lam_y, dim3(nblk(N * C)), dim3(256), 0, st, w->y, w->yd, th + ctx->off_wo, w->Ebar, ctx->d_atom_struct, N, C, w->lam_y);
-    hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, grad + ctx->off_wo);
+    {
+      const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
+      hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, len, w->partial);
+      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)C, grad + ctx->off_wo);
+    }
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
     gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   }
@@ -610,8 +638,11 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
   }
   if (stage)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(lam_in, w->lam_h[cur], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
-  else
-    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, cf.n_species), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, grad + ctx->off_emb);
+  else {
+    const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks), S = cf.n_species;
+    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, chunks, S), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, S, len, w->partial);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk((int64_t)S * C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)S * C, grad + ctx->off_emb);
+  }
   MLIP_HIP_CHECK(ctx, hipGetLastError());
   return MLIP_OK;
 }
@@ -664,6 +695,7 @@ int model_alloc(mlip_ctx* ctx) {
     cap = std::max<int64_t>(cap, (int64_t)pick_splits(rows, cols, R, bm, bn) * rows * cols);
   };
   need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
+  cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);  // atom-chunk partials
   w->partial_cap = cap;
   w->partial = A(cap);
   if (!ok) return MLIP_E_HIP;
