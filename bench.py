@@ -24,6 +24,37 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 
 
+# Kernel ids of include/mlip.h and the algorithmic work of one launch (E edges, N atoms):
+# GEMMs in flop (2 x rows x inner x out), gather kernels in HBM bytes (each edge tensor and each
+# node table touched once, indices and geometry included).
+def kernel_table(w, E, N):
+    C, H, K = w.channels, w.edge_hidden, w.n_rbf
+    f4 = 4
+    node = N * C * f4
+    return {
+        1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H),
+        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * C),
+        3: ("msg_fe", "hbm", E * C * f4 + 2 * node + E * 4),
+        4: ("msg_ff", "hbm", 2 * E * C * f4 + 4 * node + E * 20),
+        5: ("msg_bf", "hbm", 3 * E * C * f4 + 4 * node + E * 28),
+        6: ("msg_be", "hbm", 3 * E * C * f4 + 6 * node + E * 28),
+        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * C * H),
+        8: ("be_dgrad_gemm", "mfma", 2.0 * E * C * H),
+        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * C * H),
+        10: ("be_wgrad_gemm", "mfma", 2.0 * E * C * H),
+    }
+
+
+def load_traffic(workload, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if one exists."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[workload][kernel]["bytes_per_launch"]
+    except Exception:
+        return None
+
+
 def cpu_baseline(w, inp, budget_s=20.0):
     """Times the oracle as it stands on a bounded sample: whole structures of the batch, one
     after the other, until about budget_s seconds of CPU work have been spent."""
@@ -55,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch the library's 256 MiB copy kernel once (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -84,6 +117,22 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    if args.copy_probe:
+        src = torch.ones(64 * 1024 * 1024, device=dev, dtype=torch.float32)
+        m.mlip_copy_probe(torch.empty_like(src), src)
+    torch.cuda.synchronize()
+    E_edges, N = m.n_edges, w.n_atoms
+    table = kernel_table(w, E_edges, N)
+    # which kernel dominates: one untimed step per candidate with the library's event timer
+    per_kernel_us = {}
+    for kid, (name, _, _) in table.items():
+        m.mlip_kernel_timer_select(kid)
+        step()
+        n, tot = m.mlip_kernel_timer_read()
+        per_kernel_us[name] = {"launches_per_step": n, "avg_us": (tot / n * 1e3) if n else 0.0, "ms_per_step": tot}
+    dom = max(table, key=lambda k: per_kernel_us[table[k][0]]["ms_per_step"])
+    m.mlip_kernel_timer_select(dom)  # event pairs around its launches during the timed steps
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -91,15 +140,26 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms = (t1 - t0) * 1e3 / args.steps
+    n_launch, tot_ms = m.mlip_kernel_timer_read()
+    m.mlip_kernel_timer_select(0)
+    name, bound, work = table[dom]
+    avg_s = tot_ms * 1e-3 / max(n_launch, 1)
+    if bound == "mfma":
+        peak, unit = (PEAK_BF16_MFMA_TFLOPS if w.gemm_bf16 else PEAK_FP32_MFMA_TFLOPS), "TFLOP/s"
+        achieved = work / avg_s / 1e12
+    else:
+        peak, unit = PEAK_HBM_GBS, "GB/s"
+        achieved = work / avg_s / 1e9
+    roof = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+            "traffic": load_traffic(w.name, name), "avg_launch_us": avg_s * 1e6, "launches_timed": n_launch,
+            "algorithmic_work_per_launch": work, "per_kernel": per_kernel_us}
     # per-phase times from HIP events (a separate, synchronous pass: it does not enter `value`)
     ph = np.zeros(5)
     n_ph = max(3, min(20, args.steps))
     for _ in range(n_ph):
         ph += np.array(step(timed=True)["phase_ms"])
     ph /= n_ph
-    E_edges = m.n_edges
 
-    roof = m.roofline(reps=20) if hasattr(m, "roofline") else None
     line = {
         "metric": "atoms/s per FE+FF+BF+BE train step", "value": w.n_atoms / (ms * 1e-3), "unit": "atoms/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,

@@ -135,6 +135,32 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
                     const float* params, const float* E_ref, const float* F_ref, float* loss, float* E,
                     float* F, float* grad_params, float* phase_ms_host);
 
+/* Measurement aid (Appendix "Four Phase Profiler" times whole phases; this times one kernel).
+ * Selecting a kernel id makes the library record a HIP-event pair, on the context's stream,
+ * around every later launch of that kernel; 0 switches it off.  Selecting resets the counters.
+ * mlip_kernel_timer_read is synchronous: it waits for the recorded events and returns the
+ * number of launches and the sum of their durations in milliseconds. */
+enum {
+  MLIP_K_NONE = 0,
+  MLIP_K_FE_HIDDEN_GEMM = 1,  /* jets of the first hidden layer: [2E,K] x [K,H] */
+  MLIP_K_FE_FILTER_GEMM = 2,  /* last edge-MLP product with the envelope epilogue: [2E,H] x [H,C] */
+  MLIP_K_MSG_FE = 3,          /* gather * filter, segmented sum into receivers */
+  MLIP_K_MSG_FF = 4,
+  MLIP_K_MSG_BF = 5,
+  MLIP_K_MSG_BE = 6,
+  MLIP_K_BF_DGRAD = 7,        /* [E,C] x [C,H] data gradient with the activation-derivative epilogue */
+  MLIP_K_BE_DGRAD = 8,
+  MLIP_K_BF_WGRAD = 9,        /* [C,E] x [E,H] weight gradient of the last edge-MLP matrix (split-k) */
+  MLIP_K_BE_WGRAD = 10,
+  MLIP_K_GRAPH_NEIGHBOURS = 11,
+  MLIP_K_EDGE_FEATURES = 12
+};
+int mlip_kernel_timer_select(mlip_ctx* ctx, int kernel_id);
+/* Plain copy kernel of known size (dst[i] = src[i], n_floats a multiple of 4; reads and writes
+ * 4*n_floats bytes each): the reference that hardware byte counters are scaled against. */
+int mlip_copy_probe(mlip_ctx* ctx, float* dst, const float* src, int64_t n_floats);
+int mlip_kernel_timer_read(mlip_ctx* ctx, int64_t* launches_host, float* total_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,6 +60,9 @@ def load():
     lib.mlip_graph_build.argtypes = [P, I64, I32, P, P, P, F, C.POINTER(I64)]
     lib.mlip_graph_export.argtypes = [P, P, P, P, P]
     lib.mlip_graph_sizes.argtypes = [P, C.POINTER(I64), C.POINTER(I64), C.POINTER(I64)]
+    lib.mlip_kernel_timer_select.argtypes = [P, I32]
+    lib.mlip_kernel_timer_read.argtypes = [P, C.POINTER(I64), C.POINTER(C.c_float)]
+    lib.mlip_copy_probe.argtypes = [P, P, P, I64]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
     lib.mlip_loss.argtypes = [P, P, P, P, P, P, P, P]
@@ -153,6 +156,18 @@ class Mlip:
         a, b, e = C.c_int64(0), C.c_int64(0), C.c_int64(0)
         self._check(self.lib.mlip_graph_sizes(self.ctx, C.byref(a), C.byref(b), C.byref(e)))
         return int(a.value), int(b.value), int(e.value)
+
+    def mlip_kernel_timer_select(self, kernel_id: int):
+        self._check(self.lib.mlip_kernel_timer_select(self.ctx, kernel_id))
+
+    def mlip_kernel_timer_read(self):
+        """(launches, total milliseconds) of the selected kernel since it was selected."""
+        n, ms = C.c_int64(0), C.c_float(0.0)
+        self._check(self.lib.mlip_kernel_timer_read(self.ctx, C.byref(n), C.byref(ms)))
+        return int(n.value), float(ms.value)
+
+    def mlip_copy_probe(self, dst, src):
+        self._check(self.lib.mlip_copy_probe(self.ctx, _ptr(dst, torch.float32), _ptr(src, torch.float32), src.numel()))
 
     def mlip_graph_export(self):
         E, N = self.n_edges, self.n_atoms

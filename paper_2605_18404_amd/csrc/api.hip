@@ -49,6 +49,11 @@ int layout_params(mlip_ctx* ctx) {
   return MLIP_OK;
 }
 
+__global__ void k_copy_probe(float4* __restrict__ dst, const float4* __restrict__ src, int64_t n4) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) dst[i] = src[i];
+}
+
 const char* check_config(const mlip_config& c) {
   if (c.model_kind < 0 || c.model_kind > 2) return "model_kind must be 0, 1 or 2";
   if (c.channels < 4 || c.channels % 4 || c.channels > 1024) return "channels must be a multiple of 4 in [4, 1024]";
@@ -100,6 +105,7 @@ int mlip_destroy(mlip_ctx* ctx) {
   if (!ctx) return MLIP_OK;
   hipStreamSynchronize(ctx->stream);
   for (void* p : ctx->allocs) hipFree(p);
+  for (hipEvent_t e : ctx->tev) hipEventDestroy(e);
   model_free(ctx);
   delete (StepBufs*)ctx->step_bufs;
   delete ctx;
@@ -122,6 +128,38 @@ int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_stru
   if (n_atoms_host) *n_atoms_host = ctx->N;
   if (n_structs_host) *n_structs_host = ctx->B;
   if (n_edges_host) *n_edges_host = ctx->E;
+  return MLIP_OK;
+}
+
+int mlip_copy_probe(mlip_ctx* ctx, float* dst, const float* src, int64_t n_floats) {
+  if (!ctx || !dst || !src || n_floats <= 0 || (n_floats & 3)) return MLIP_E_INVALID;
+  const int64_t n4 = n_floats / 4;
+  hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, ctx->stream,
+                     reinterpret_cast<float4*>(dst), reinterpret_cast<const float4*>(src), n4);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+int mlip_kernel_timer_select(mlip_ctx* ctx, int kernel_id) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (kernel_id < 0 || kernel_id > MLIP_K_EDGE_FEATURES) MLIP_FAIL(ctx, MLIP_E_INVALID, "kernel_timer_select: unknown kernel id");
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+  ctx->timed_kernel = kernel_id;
+  ctx->tev_used = 0;
+  return MLIP_OK;
+}
+
+int mlip_kernel_timer_read(mlip_ctx* ctx, int64_t* launches_host, float* total_ms_host) {
+  if (!ctx || !launches_host || !total_ms_host) return MLIP_E_INVALID;
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+  double total = 0.0;
+  for (size_t k = 0; k + 1 < ctx->tev_used; k += 2) {
+    float ms = 0.f;
+    MLIP_HIP_CHECK(ctx, hipEventElapsedTime(&ms, ctx->tev[k], ctx->tev[k + 1]));
+    total += ms;
+  }
+  *launches_host = (int64_t)(ctx->tev_used / 2);
+  *total_ms_host = (float)total;
   return MLIP_OK;
 }
 

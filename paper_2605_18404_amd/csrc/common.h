@@ -90,6 +90,33 @@ struct mlip_ctx {
   float4* d_geo = nullptr;     // [E] unit vector and length of each edge
   void* model_ws = nullptr;    // workspace of the model kind, owned by its translation unit
   void* step_bufs = nullptr;   // cotangent buffers of mlip_train_step
+
+  // ---- kernel timer (mlip_kernel_timer_select / _read): event pairs around one kernel's launches
+  int timed_kernel = 0;
+  std::vector<hipEvent_t> tev;  // pool, pairs (start, stop)
+  size_t tev_used = 0;
+};
+
+// Scope guard: brackets the launches made inside its lifetime with a HIP-event pair when the
+// given kernel id is the one selected for timing.  Costs nothing otherwise.
+struct KernelTimer {
+  mlip_ctx* c;
+  bool on;
+  KernelTimer(mlip_ctx* ctx, int id) : c(ctx), on(ctx->timed_kernel == id && id != 0) {
+    if (!on) return;
+    if (c->tev_used + 2 > c->tev.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+      c->tev.push_back(a);
+      c->tev.push_back(b);
+    }
+    hipEventRecord(c->tev[c->tev_used], c->stream);
+  }
+  ~KernelTimer() {
+    if (!on) return;
+    hipEventRecord(c->tev[c->tev_used + 1], c->stream);
+    c->tev_used += 2;
+  }
 };
 
 void* ctx_alloc(mlip_ctx* ctx, size_t bytes);  // returns nullptr on failure (err set)

@@ -33,54 +33,71 @@ __device__ __forceinline__ float4 silu4(float4 a) { return make_float4(silu(a.x)
 __device__ __forceinline__ float4 dsilu4(float4 a) { return make_float4(dsilu(a.x), dsilu(a.y), dsilu(a.z), dsilu(a.w)); }
 
 // ---------------------------------------------------------------------------- loaders
+// fetch() only issues loads (so they overlap the matrix products of the current tile),
+// finish() applies the element-wise function when the tile is staged.
+struct Raw2 { float4 a, b; };
+struct Raw2f { float4 a, b; bool odd; };
+
 struct LdPlain {  // p[row * ld + col]
+  typedef float4 Raw;
   const float* p;
   int64_t ld;
-  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const { return ld4(p + r * ld + c); }
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return ld4(p + r * ld + c); }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return x; }
 };
 struct LdSilu {  // silu(p[row * ld + col])
+  typedef float4 Raw;
   const float* p;
   int64_t ld;
-  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const { return silu4(ld4(p + r * ld + c)); }
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return ld4(p + r * ld + c); }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return silu4(x); }
 };
 struct LdJetSilu {  // rows of a jet matrix u [2E][W]: even -> silu(u), odd -> silu'(u_even) * u_odd
+  typedef Raw2f Raw;
   const float* u;
   int64_t W;
-  __device__ __forceinline__ float4 operator()(int64_t rho, int64_t c) const {
+  __device__ __forceinline__ Raw fetch(int64_t rho, int64_t c) const {
     const float* pe = u + (rho & ~(int64_t)1) * W + c;
-    float4 a = ld4(pe);
-    if (rho & 1) return mul4(dsilu4(a), ld4(pe + W));
-    return silu4(a);
+    Raw x;
+    x.a = ld4(pe);
+    x.odd = (rho & 1) != 0;
+    x.b = x.odd ? ld4(pe + W) : make_float4(0.f, 0.f, 0.f, 0.f);
+    return x;
   }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return x.odd ? mul4(dsilu4(x.a), x.b) : silu4(x.a); }
 };
 struct LdJetSiluEven {  // row e -> silu(u[2e])
+  typedef float4 Raw;
   const float* u;
   int64_t W;
-  __device__ __forceinline__ float4 operator()(int64_t e, int64_t c) const { return silu4(ld4(u + 2 * e * W + c)); }
+  __device__ __forceinline__ Raw fetch(int64_t e, int64_t c) const { return ld4(u + 2 * e * W + c); }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return silu4(x); }
 };
 struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
+  typedef Raw2 Raw;
   const float* u;
   int64_t W;
-  __device__ __forceinline__ float4 operator()(int64_t e, int64_t c) const {
+  __device__ __forceinline__ Raw fetch(int64_t e, int64_t c) const {
     const float* pe = u + 2 * e * W + c;
-    return mul4(dsilu4(ld4(pe)), ld4(pe + W));
+    return Raw{ld4(pe), ld4(pe + W)};
   }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return mul4(dsilu4(x.a), x.b); }
 };
 struct LdDsiluMul {  // silu'(q[row]) * x[row]
+  typedef Raw2 Raw;
   const float* q;
   const float* x;
   int64_t ld;
-  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const {
-    return mul4(dsilu4(ld4(q + r * ld + c)), ld4(x + r * ld + c));
-  }
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return Raw{ld4(q + r * ld + c), ld4(x + r * ld + c)}; }
+  __device__ __forceinline__ float4 finish(const Raw& v) const { return mul4(dsilu4(v.a), v.b); }
 };
 struct LdMuY {  // w_o[col] * silu'(y[row, col])
+  typedef Raw2 Raw;
   const float* y;
   const float* wo;
   int64_t ld;
-  __device__ __forceinline__ float4 operator()(int64_t r, int64_t c) const {
-    return mul4(dsilu4(ld4(y + r * ld + c)), ld4(wo + c));
-  }
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return Raw{ld4(y + r * ld + c), ld4(wo + c)}; }
+  __device__ __forceinline__ float4 finish(const Raw& v) const { return mul4(dsilu4(v.a), v.b); }
 };
 
 // ---------------------------------------------------------------------------- epilogues

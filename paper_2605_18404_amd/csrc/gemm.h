@@ -43,42 +43,50 @@ struct Tile {
 };
 
 // ---- staging: global (through the loader functor) -> registers -> LDS ------------------------
-// Each thread moves NV = ROWS*BK/4/256 float4 per tile.
+// A loader functor has two halves so that the global loads of the next tile stay in flight
+// while the current tile is multiplied:  Raw fetch(row, col4)  issues the loads only, and
+// float4 finish(raw)  applies the element-wise producer when the tile is written to LDS.
 template <typename P, int ROWS, bool KC, typename Ld>
 struct Stager {
   static constexpr int NVT = ROWS * P::BK / 4;       // float4 per tile
   static constexpr int NV = (NVT + 255) / 256;       // per thread
   static constexpr int Q = KC ? (P::BK / 4) : (ROWS / 4);
-  float4 v[NV];
+  typename Ld::Raw v[NV];
+  unsigned ok = 0;
 
   // KC: a row holds Q = BK/4 float4;    idx -> (row = idx / Q, kq = idx % Q)
   // KS: a k-row holds Q = ROWS/4 float4; idx -> (k = idx / Q,  rq = idx % Q)
   __device__ __forceinline__ void load(const Ld& ld, int64_t row0, int64_t n_rows, int64_t k0, int64_t k_end, int t) {
+    ok = 0;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = t + it * 256;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
       if (NVT % 256 == 0 || idx < NVT) {
+        int64_t r, c;
+        bool in;
         if (KC) {
-          int64_t row = row0 + idx / Q, k = k0 + 4 * (idx % Q);
-          if (row < n_rows && k < k_end) x = ld(row, k);
+          r = row0 + idx / Q; c = k0 + 4 * (idx % Q);
+          in = r < n_rows && c < k_end;
         } else {
-          int64_t k = k0 + idx / Q, row = row0 + 4 * (idx % Q);
-          if (row < n_rows && k < k_end) x = ld(k, row);
+          r = k0 + idx / Q; c = row0 + 4 * (idx % Q);
+          in = c < n_rows && r < k_end;
+        }
+        if (in) {
+          v[it] = ld.fetch(r, c);
+          ok |= 1u << it;
         }
       }
-      v[it] = x;
     }
   }
 
-  __device__ __forceinline__ void store(typename P::lds_t* s, int t) const {
+  __device__ __forceinline__ void store(const Ld& ld, typename P::lds_t* s, int t) const {
     constexpr int LD = Tile<P, ROWS>::LD;
     typedef typename P::lds_t T;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = t + it * 256;
       if (NVT % 256 != 0 && idx >= NVT) continue;
-      const float4 x = v[it];
+      const float4 x = (ok >> it) & 1u ? ld.finish(v[it]) : make_float4(0.f, 0.f, 0.f, 0.f);
       const int a = idx / Q, b = idx % Q;  // KC: (row, kq); KS: (k, rq)
       if (KC) {
         if constexpr (P::K_MAJOR) {  // transpose into [k][row]
@@ -148,8 +156,8 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
   if (nk > 0) {
     stA.load(lda, m0, M, kb, ke, t);
     stB.load(ldb, n0, N, kb, ke, t);
-    stA.store(sA[0], t);
-    stB.store(sB[0], t);
+    stA.store(lda, sA[0], t);
+    stB.store(ldb, sB[0], t);
   }
   __syncthreads();
   for (int64_t kt = 0; kt < nk; ++kt) {
@@ -192,8 +200,8 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
       }
     }
     if (kt + 1 < nk) {
-      stA.store(sA[cur ^ 1], t);
-      stB.store(sB[cur ^ 1], t);
+      stA.store(lda, sA[cur ^ 1], t);
+      stB.store(ldb, sB[cur ^ 1], t);
     }
     __syncthreads();
   }

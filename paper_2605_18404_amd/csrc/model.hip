@@ -481,16 +481,25 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     if (E > 0) {
-      gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[0][l], H, 2 * E});
+      {
+        KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
+        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[0][l], H, 2 * E});
+      }
       const float* ulast = w->U[0][l];
       if (d == 3) {
         gemm_nt<P>(st, LdJetSilu{w->U[0][l], H}, th + lo.W[1], 2 * E, H, H, EpiStore{w->U[1][l], H, 2 * E});
         ulast = w->U[1][l];
       }
-      gemm_nt<P>(st, LdJetSilu{ulast, H}, th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
+      {
+        KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
+        gemm_nt<P>(st, LdJetSilu{ulast, H}, th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
+      }
     }
-    hipLaunchKernelGGL(k_msg_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
-                       (int)N, C, w->a[l]);
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_FE);
+      hipLaunchKernelGGL(k_msg_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
+                         (int)N, C, w->a[l]);
+    }
     gemm_nt<P>(st, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
     gemm_nt<P>(st, LdSilu{w->q[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->h[l + 1], w->h[l], C, N});
   }
@@ -525,8 +534,11 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
     const LayerOffsets& lo = ctx->lay[l];
     gemm_nt<P>(st, LdPlain{w->mu_h[l + 1], C}, tT + lo.V2, N, C, C, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
     gemm_nt<P>(st, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
-    hipLaunchKernelGGL(k_msg_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
-                       w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_FF);
+      hipLaunchKernelGGL(k_msg_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
+                         w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+    }
   }
   // F_i = + sum_e g_e rhat_e = -dE/dx_i ; a stage reports its contribution to +dE/dx
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, stage ? -1.f : 1.f, 3 * N, F);
@@ -552,8 +564,11 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   const int rpb = 256 / (C / 4);
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
-    hipLaunchKernelGGL(k_msg_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                       w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_BF);
+      hipLaunchKernelGGL(k_msg_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+    }
     gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
     gemm_nt<P>(st, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
     // second-order weight gradients of the update MLP: mu_{h'}^T tdot, mu_q^T adot
@@ -562,8 +577,14 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     if (E > 0) {
       // X = rdot * mu_w (adjoint of the derivative row w').  Chain back through the jets' derivative rows.
       const float* ulast = w->U[d - 2][l];
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluOdd{ulast, H}, E, C, H, grad + lo.W[d - 1])));
-      gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiYZ{w->Y[d - 2][l], w->X2, ulast, H, E});
+      {
+        KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluOdd{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+      }
+      {
+        KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
+        gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiYZ{w->Y[d - 2][l], w->X2, ulast, H, E});
+      }
       if (d == 3) {
         MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluOdd{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
         gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiYZ{w->Y[0][l], w->X, w->U[0][l], H, E});
@@ -620,12 +641,21 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next, C}, LdSilu{w->q[l], C}, N, C, C, grad + lo.V2)));
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_q, C}, LdPlain{w->a[l], C}, N, C, C, grad + lo.V1)));
     gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
-    hipLaunchKernelGGL(k_msg_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                       w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_BE);
+      hipLaunchKernelGGL(k_msg_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+    }
     if (E > 0) {
       const float* ulast = w->U[d - 2][l];
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluEven{ulast, H}, E, C, H, grad + lo.W[d - 1])));
-      gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiLamU{w->X2, ulast, w->Y[d - 2][l], H, E});
+      {
+        KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluEven{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+      }
+      {
+        KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
+        gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiLamU{w->X2, ulast, w->Y[d - 2][l], H, E});
+      }
       if (d == 3) {
         MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluEven{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
         gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiLamU{w->X, w->U[0][l], w->Y[0][l], H, E});
