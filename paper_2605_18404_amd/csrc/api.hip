@@ -17,6 +17,26 @@ void* ctx_alloc(mlip_ctx* ctx, size_t bytes) {
   return p;
 }
 
+// ---- dispatch on the model kind
+#define IS_EQV(ctx) ((ctx)->cfg.model_kind == MLIP_MODEL_EQUIVARIANT)
+static int model_alloc(mlip_ctx* c) { return IS_EQV(c) ? eqv_alloc(c) : inv_alloc(c); }
+static void model_free(mlip_ctx* c) { if (IS_EQV(c)) eqv_free(c); else inv_free(c); }
+static int model_forward_energy(mlip_ctx* c, const float* pos, const int32_t* sp, const float* th, const float* h_in, float* E, float* h_out) {
+  return IS_EQV(c) ? eqv_forward_energy(c, pos, sp, th, h_in, E, h_out) : inv_forward_energy(c, pos, sp, th, h_in, E, h_out);
+}
+static int model_forward_force(mlip_ctx* c, const float* g_out, float* F, float* g_in) {
+  return IS_EQV(c) ? eqv_forward_force(c, g_out, F, g_in) : inv_forward_force(c, g_out, F, g_in);
+}
+static int model_loss(mlip_ctx* c, const float* E, const float* F, const float* Er, const float* Fr, float* loss, float* Ebar, float* v) {
+  return inv_loss(c, E, F, Er, Fr, loss, Ebar, v);
+}
+static int model_backward_force(mlip_ctx* c, const float* v, const float* hd, float* g, float* hdo) {
+  return IS_EQV(c) ? eqv_backward_force(c, v, hd, g, hdo) : inv_backward_force(c, v, hd, g, hdo);
+}
+static int model_backward_energy(mlip_ctx* c, const float* Ebar, const float* lo, float* g, float* li) {
+  return IS_EQV(c) ? eqv_backward_energy(c, Ebar, lo, g, li) : inv_backward_energy(c, Ebar, lo, g, li);
+}
+
 namespace {
 
 struct StepBufs {

@@ -39,6 +39,11 @@ struct StructMeta {
   float L[3];        // orthorhombic cell edges
 };
 
+struct PartialBuf {  // split-k / chunk partial sums, reduced in a fixed order
+  float* buf = nullptr;
+  int64_t cap = 0;  // floats
+};
+
 enum Phase { PH_NONE = 0, PH_GRAPH = 1, PH_FE = 2, PH_FF = 3, PH_BF = 4, PH_BE = 5 };
 
 struct LayerOffsets {  // offsets (in floats) into the flat parameter vector
@@ -90,6 +95,7 @@ struct mlip_ctx {
   float4* d_geo = nullptr;     // [E] unit vector and length of each edge
   void* model_ws = nullptr;    // workspace of the model kind, owned by its translation unit
   void* step_bufs = nullptr;   // cotangent buffers of mlip_train_step
+  PartialBuf partial;
 
   // ---- kernel timer (mlip_kernel_timer_select / _read): event pairs around one kernel's launches
   int timed_kernel = 0;
@@ -127,13 +133,16 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
                 const float* cell, float cutoff, int64_t* n_edges_host);
 int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
 
-// model.hip
-int model_alloc(mlip_ctx* ctx);
-void model_free(mlip_ctx* ctx);
-int model_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params,
-                         const float* h_in, float* E, float* h_out);
-int model_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in);
-int model_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
-               float* Ebar, float* v);
-int model_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out);
-int model_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in);
+// model.hip (invariant model and pipeline stage) / equivariant.hip (l <= 2 model)
+#define MLIP_DECLARE_MODEL(pfx)                                                                                       \
+  int pfx##_alloc(mlip_ctx* ctx);                                                                                     \
+  void pfx##_free(mlip_ctx* ctx);                                                                                     \
+  int pfx##_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params,             \
+                           const float* h_in, float* E, float* h_out);                                                \
+  int pfx##_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in);                                  \
+  int pfx##_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out);        \
+  int pfx##_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in);
+MLIP_DECLARE_MODEL(inv)
+MLIP_DECLARE_MODEL(eqv)
+int inv_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
+             float* Ebar, float* v);

@@ -1,0 +1,575 @@
+// Equivariant (l <= 2) message-passing potential: FE / FF / BF / BE with hand-derived adjoints.
+//
+// Node features h[m][n][c], m = 0..8 the real spherical-harmonic component (l=0 | y,z,x | five
+// l=2), stored component-major so every l block is a plain [(2l+1) N, C] matrix for the per-l
+// channel mixing.  Messages:  m_e = B(rho_e, h_j, Y_e),  B(rho, x, y)[m3] = sum_p rho_p
+// sum_{m1 m2} T^p[m1 m2 m3] x[m1] y[m2]  (T = scaled real Gaunt couplings, gaunt_table.h),
+// rho_e = f_c(r) R(r) in R^{11 x C} the radial filter, carried with its r-derivative rho'_e as
+// a jet.  B is trilinear, so every derivative pass is B or one of its partial contractions:
+//   FE  a_i      = sum_e B(rho, h_j, Y)
+//   FF  mu_h[i] += sum_e B_x^T(rho, PY; mu_a[j])          (P = parity (-1)^l: the opposite edge
+//       F_i      = sum_e s_e rhat_e + J_e^T nu_e            has Y -> PY, Ydot -> P Ydot, same r, rdot)
+//         s_e  = sum_c <mu_a,i , B(rho', h_j, Y)> + <mu_a,j , B(rho', h_i, PY)>
+//         nu_e = sum_c B_y^T(rho, h_j; mu_a,i) + P B_y^T(rho, h_i; mu_a,j),  J = dY/dr_vec
+//   BF  adot_i   = sum_e B(rdot rho', h_j, Y) + B(rho, hdot_j, Y) + B(rho, h_j, Ydot)
+//   BE  lam_h[i]+= sum_e B_x^T(rho, PY; lam_a[j]) + B_x^T(rdot rho', PY; mu_a[j]) + B_x^T(rho, P Ydot; mu_a[j])
+// with the radial adjoints  X_bf[p,c] = rdot f_c t_p(h_j, Y, mu_a,i)  (derivative rows -> BF) and
+// X_be[p,c] = f_c (t_p(h_j,Y,lam_a,i) + t_p(hdot_j,Y,mu_a,i) + t_p(h_j,Ydot,mu_a,i)) + f_c' rdot t_p(h_j,Y,mu_a,i)
+// (value rows -> BE), t_p = the path-p trilinear form; they feed the same GEMM chains as the
+// invariant model's edge MLP.
+#include <algorithm>
+#include <cmath>
+
+#include "gaunt_table.h"
+#include "shared_kernels.h"
+
+namespace {
+
+using gaunt::NPATH;
+
+struct EqvWs {
+  float* paramsT = nullptr;
+  float* jphi = nullptr;  // [E][2][K]
+  float2* env = nullptr;  // [E]
+  std::vector<float*> U;    // [E][2][H]
+  std::vector<float*> Rho;  // [E][2][11 C]
+  std::vector<float*> Y1;   // [E][H]  BF -> BE
+  float* X = nullptr;       // [E][11 C]
+  float* X2 = nullptr;      // [E][H]
+  std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [9][N][C]
+  float* lam_h[2] = {nullptr, nullptr};
+  float* lam_a = nullptr;
+  float* y = nullptr;
+  float* yd = nullptr;
+  float* lam_y = nullptr;
+  float* lam0 = nullptr;  // [N][C] scratch for the readout's adjoint
+  float* eps = nullptr;
+  float* Facc = nullptr;
+  float* v = nullptr;
+  float* Ebar = nullptr;
+};
+inline EqvWs* ws_of(mlip_ctx* ctx) { return (EqvWs*)ctx->model_ws; }
+
+// ------------------------------------------------------------------------------ geometry helpers
+__device__ __forceinline__ void sph_harm(float x, float y, float z, float (&Y)[9]) {
+  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+  Y[0] = 1.f;
+  Y[1] = s3 * y; Y[2] = s3 * z; Y[3] = s3 * x;
+  Y[4] = s15 * x * y; Y[5] = s15 * y * z; Y[6] = 0.5f * s5 * (3.f * z * z - 1.f); Y[7] = s15 * x * z;
+  Y[8] = 0.5f * s15 * (x * x - y * y);
+}
+// w = sum_m nu[m] grad_u Y_m  (polynomial gradient at the unit vector u)
+__device__ __forceinline__ float3 sph_grad_T(float x, float y, float z, const float (&nu)[9]) {
+  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+  float3 w;
+  w.x = s3 * nu[3] + s15 * (y * nu[4] + z * nu[7] + x * nu[8]);
+  w.y = s3 * nu[1] + s15 * (x * nu[4] + z * nu[5] - y * nu[8]);
+  w.z = s3 * nu[2] + s15 * (y * nu[5] + x * nu[7]) + 3.f * s5 * z * nu[6];
+  return w;
+}
+// Ydot = (dY/dr_vec) d = grad_u Y . d_perp / r,  d_perp = d - u (u.d)
+__device__ __forceinline__ void sph_dot(float x, float y, float z, float r, float3 d, float (&Yd)[9]) {
+  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+  float ud = x * d.x + y * d.y + z * d.z;
+  float inv = 1.f / r;
+  float px = (d.x - x * ud) * inv, py = (d.y - y * ud) * inv, pz = (d.z - z * ud) * inv;
+  Yd[0] = 0.f;
+  Yd[1] = s3 * py; Yd[2] = s3 * pz; Yd[3] = s3 * px;
+  Yd[4] = s15 * (y * px + x * py);
+  Yd[5] = s15 * (z * py + y * pz);
+  Yd[6] = 3.f * s5 * z * pz;
+  Yd[7] = s15 * (z * px + x * pz);
+  Yd[8] = s15 * (x * px - y * py);
+}
+__device__ __forceinline__ void parity(const float (&a)[9], float (&b)[9]) {
+#pragma unroll
+  for (int m = 0; m < 9; ++m) b[m] = (m >= 1 && m <= 3) ? -a[m] : a[m];
+}
+__device__ __forceinline__ void load9(const float* __restrict__ t, int64_t NC, int64_t off, float (&x)[9]) {
+#pragma unroll
+  for (int m = 0; m < 9; ++m) x[m] = t[m * NC + off];
+}
+__device__ __forceinline__ void load_rho(const float* __restrict__ row, int C, int c, float (&rho)[NPATH]) {
+#pragma unroll
+  for (int p = 0; p < NPATH; ++p) rho[p] = row[p * C + c];
+}
+
+struct RowChan {
+  int row, c;
+  bool active;
+};
+__device__ __forceinline__ RowChan row_chan(int N, int C) {
+  int rpb = 256 / C;
+  int rl = threadIdx.x / C;
+  RowChan t;
+  t.c = threadIdx.x % C;
+  t.row = blockIdx.x * rpb + rl;
+  t.active = (rl < rpb) && (t.row < N);
+  return t;
+}
+
+// ------------------------------------------------------------------------------ edge kernels
+__global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const float* __restrict__ Rho,
+                                               const float* __restrict__ h, int N, int C, float* __restrict__ a) {
+  RowChan t = row_chan(N, C);
+  if (!t.active) return;
+  const int64_t NC = (int64_t)N * C;
+  float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    float4 g = geo[e];
+    float Y[9], x[9], rho[NPATH];
+    sph_harm(g.x, g.y, g.z, Y);
+    load9(h, NC, (int64_t)j * C + t.c, x);
+    load_rho(Rho + (int64_t)(2 * e) * NPATH * C, C, t.c, rho);
+    gaunt::tp_fwd(rho, x, Y, acc);
+  }
+#pragma unroll
+  for (int m = 0; m < 9; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
+}
+
+__global__ void __launch_bounds__(256) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const float* __restrict__ Rho,
+                                               const float* __restrict__ h, const float* __restrict__ mu_a,
+                                               const float* __restrict__ mu_h_next, int N, int C,
+                                               float* __restrict__ mu_h, float* __restrict__ Facc) {
+  __shared__ float3 red[256];
+  RowChan t = row_chan(N, C);
+  float3 f = make_float3(0.f, 0.f, 0.f);
+  if (t.active) {
+    const int64_t NC = (int64_t)N * C;
+    const int64_t io = (int64_t)t.row * C + t.c;
+    float acc[9], xi[9], mi[9];
+    load9(mu_h_next, NC, io, acc);
+    load9(h, NC, io, xi);
+    load9(mu_a, NC, io, mi);
+    const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+    for (int e = e0; e < e1; ++e) {
+      int j = sender[e];
+      float4 g = geo[e];
+      float Y[9], PY[9], xj[9], mj[9], rho[NPATH], rhop[NPATH];
+      sph_harm(g.x, g.y, g.z, Y);
+      parity(Y, PY);
+      const int64_t jo = (int64_t)j * C + t.c;
+      load9(h, NC, jo, xj);
+      load9(mu_a, NC, jo, mj);
+      const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
+      load_rho(rrow, C, t.c, rho);
+      load_rho(rrow + NPATH * C, C, t.c, rhop);
+      gaunt::tp_adj_x(rho, PY, mj, acc);
+      float t1[NPATH], t2[NPATH];
+      gaunt::tp_paths(xj, Y, mi, t1);
+      gaunt::tp_paths(xi, PY, mj, t2);
+      float s = 0.f;
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) s += rhop[p] * (t1[p] + t2[p]);
+      float nu[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, nu2[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      gaunt::tp_adj_y(rho, xj, mi, nu);
+      gaunt::tp_adj_y(rho, xi, mj, nu2);
+#pragma unroll
+      for (int m = 0; m < 9; ++m) nu[m] += (m >= 1 && m <= 3) ? -nu2[m] : nu2[m];
+      float3 w = sph_grad_T(g.x, g.y, g.z, nu);
+      float uw = g.x * w.x + g.y * w.y + g.z * w.z;
+      float inv = 1.f / g.w;
+      f.x += s * g.x + (w.x - g.x * uw) * inv;
+      f.y += s * g.y + (w.y - g.y * uw) * inv;
+      f.z += s * g.z + (w.z - g.z * uw) * inv;
+    }
+#pragma unroll
+    for (int m = 0; m < 9; ++m) mu_h[m * NC + io] = acc[m];
+  }
+  red[threadIdx.x] = f;
+  __syncthreads();
+  if (t.active && t.c == 0) {
+    float3 s = make_float3(0.f, 0.f, 0.f);
+    for (int k = 0; k < C; ++k) {
+      float3 x = red[threadIdx.x + k];
+      s.x += x.x; s.y += x.y; s.z += x.z;
+    }
+    Facc[3 * t.row] += s.x;
+    Facc[3 * t.row + 1] += s.y;
+    Facc[3 * t.row + 2] += s.z;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const float2* __restrict__ env,
+                                               const float* __restrict__ Rho, const float* __restrict__ h,
+                                               const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                               const float* __restrict__ v, int N, int C, float* __restrict__ ad,
+                                               float* __restrict__ X) {
+  RowChan t = row_chan(N, C);
+  if (!t.active) return;
+  const int64_t NC = (int64_t)N * C;
+  const int64_t io = (int64_t)t.row * C + t.c;
+  float mi[9];
+  load9(mu_a, NC, io, mi);
+  float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    float4 g = geo[e];
+    float3 dv = make_float3(v[3 * j] - v[3 * t.row], v[3 * j + 1] - v[3 * t.row + 1], v[3 * j + 2] - v[3 * t.row + 2]);
+    float rd = g.x * dv.x + g.y * dv.y + g.z * dv.z;
+    float Y[9], Yd[9], xj[9], xdj[9], rho[NPATH], rr[NPATH];
+    sph_harm(g.x, g.y, g.z, Y);
+    sph_dot(g.x, g.y, g.z, g.w, dv, Yd);
+    const int64_t jo = (int64_t)j * C + t.c;
+    load9(h, NC, jo, xj);
+    load9(hd, NC, jo, xdj);
+    const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
+    load_rho(rrow, C, t.c, rho);
+    load_rho(rrow + NPATH * C, C, t.c, rr);
+#pragma unroll
+    for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
+    gaunt::tp_fwd(rr, xj, Y, acc);
+    gaunt::tp_fwd(rho, xdj, Y, acc);
+    gaunt::tp_fwd(rho, xj, Yd, acc);
+    float tp[NPATH];
+    gaunt::tp_paths(xj, Y, mi, tp);
+    const float s = rd * env[e].x;
+    float* xrow = X + (int64_t)e * NPATH * C + t.c;
+#pragma unroll
+    for (int p = 0; p < NPATH; ++p) xrow[p * C] = s * tp[p];
+  }
+#pragma unroll
+  for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
+}
+
+__global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const float2* __restrict__ env,
+                                               const float* __restrict__ Rho, const float* __restrict__ h,
+                                               const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                               const float* __restrict__ lam_a, const float* __restrict__ v,
+                                               const float* __restrict__ lam_h_next, int N, int C,
+                                               float* __restrict__ lam_h, float* __restrict__ X) {
+  RowChan t = row_chan(N, C);
+  if (!t.active) return;
+  const int64_t NC = (int64_t)N * C;
+  const int64_t io = (int64_t)t.row * C + t.c;
+  float mi[9], li[9], acc[9];
+  load9(mu_a, NC, io, mi);
+  load9(lam_a, NC, io, li);
+  load9(lam_h_next, NC, io, acc);
+  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  for (int e = e0; e < e1; ++e) {
+    int j = sender[e];
+    float4 g = geo[e];
+    float3 dv = make_float3(v[3 * j] - v[3 * t.row], v[3 * j + 1] - v[3 * t.row + 1], v[3 * j + 2] - v[3 * t.row + 2]);
+    float rd = g.x * dv.x + g.y * dv.y + g.z * dv.z;
+    float Y[9], Yd[9], PY[9], PYd[9], xj[9], xdj[9], lj[9], mj[9], rho[NPATH], rr[NPATH];
+    sph_harm(g.x, g.y, g.z, Y);
+    sph_dot(g.x, g.y, g.z, g.w, dv, Yd);
+    parity(Y, PY);
+    parity(Yd, PYd);
+    const int64_t jo = (int64_t)j * C + t.c;
+    load9(h, NC, jo, xj);
+    load9(hd, NC, jo, xdj);
+    load9(lam_a, NC, jo, lj);
+    load9(mu_a, NC, jo, mj);
+    const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
+    load_rho(rrow, C, t.c, rho);
+    load_rho(rrow + NPATH * C, C, t.c, rr);
+#pragma unroll
+    for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
+    gaunt::tp_adj_x(rho, PY, lj, acc);
+    gaunt::tp_adj_x(rr, PY, mj, acc);
+    gaunt::tp_adj_x(rho, PYd, mj, acc);
+    float t1[NPATH], t2[NPATH], t3[NPATH], t4[NPATH];
+    gaunt::tp_paths(xj, Y, li, t1);
+    gaunt::tp_paths(xdj, Y, mi, t2);
+    gaunt::tp_paths(xj, Yd, mi, t3);
+    gaunt::tp_paths(xj, Y, mi, t4);
+    const float2 cc = env[e];
+    const float s = cc.y * rd;
+    float* xrow = X + (int64_t)e * NPATH * C + t.c;
+#pragma unroll
+    for (int p = 0; p < NPATH; ++p) xrow[p * C] = cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p];
+  }
+#pragma unroll
+  for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
+}
+
+// h0[m=0] = emb[species], other components zero
+__global__ void k_embed_l0(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C,
+                           float* __restrict__ h) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= 9 * N * C) return;
+  int64_t m = idx / (N * C), r = idx % (N * C);
+  h[idx] = (m == 0) ? emb[(int64_t)species[r / C] * C + (r % C)] : 0.f;
+}
+
+// ------------------------------------------------------------------------------ phases
+constexpr int LOFF[3] = {0, 1, 4};
+
+template <typename P>
+int fe_impl(mlip_ctx* ctx, float* E_out) {
+  EqvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const float* th = ctx->d_params;
+  auto tr = [&](int64_t off, int rows, int cols) {
+    hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
+  };
+  for (int l = 0; l < L; ++l) {
+    tr(ctx->lay[l].W[1], PC, H);
+    for (int k = 0; k < 3; ++k) tr(ctx->lay[l].Wl[k], C, C);
+  }
+  tr(ctx->off_U, C, C);
+  if (E > 0)
+    hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
+                       ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
+  hipLaunchKernelGGL(k_embed_l0, dim3(nblk(9 * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);
+  const int rpb = 256 / C;
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    if (E > 0) {
+      {
+        KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
+        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[l], H, 2 * E});
+      }
+      KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
+      gemm_nt<P>(st, LdJetSilu{w->U[l], H}, th + lo.W[1], 2 * E, PC, H, EpiOmega{w->Rho[l], w->env, PC, 2 * E});
+    }
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_FE);
+      hipLaunchKernelGGL(k_tp_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+                         w->h[l], (int)N, C, w->a[l]);
+    }
+    for (int k = 0; k < 3; ++k) {
+      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+      gemm_nt<P>(st, LdPlain{w->a[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
+    }
+  }
+  gemm_nt<P>(st, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
+  hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
+  hipLaunchKernelGGL(k_struct_sum, dim3(ctx->B), dim3(256), 0, st, w->eps, ctx->d_meta, E_out);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int ff_impl(mlip_ctx* ctx, float* F) {
+  EqvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, NC = N * cf.channels;
+  const int C = cf.channels, L = cf.n_layers;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  // mu_h^L: l = 0 block from the readout, zero elsewhere
+  hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->mu_h[L] + NC, 0.f, 8 * NC);
+  gemm_nt<P>(st, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
+  hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
+  const int rpb = 256 / C;
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    for (int k = 0; k < 3; ++k) {
+      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+      gemm_nt<P>(st, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
+    }
+    KernelTimer kt(ctx, MLIP_K_MSG_FF);
+    hipLaunchKernelGGL(k_tp_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+                       w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+  }
+  hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int bf_impl(mlip_ctx* ctx, float* grad) {
+  EqvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  hipLaunchKernelGGL(k_fill, dim3(nblk(9 * NC)), dim3(256), 0, st, w->hd[0], 0.f, 9 * NC);
+  const int rpb = 256 / C;
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_BF);
+      hipLaunchKernelGGL(k_tp_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+    }
+    for (int k = 0; k < 3; ++k) {
+      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+      gemm_nt<P>(st, LdPlain{w->ad[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1] + o, C}, LdPlain{w->ad[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
+    }
+    if (E > 0) {
+      {
+        KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, LdJetSiluOdd{w->U[l], H}, E, PC, H, grad + lo.W[1])));
+      }
+      {
+        KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
+        gemm_nt<P>(st, LdPlain{w->X, PC}, tT + lo.W[1], E, H, PC, EpiYZ{w->Y1[l], w->X2, w->U[l], H, E});
+      }
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+    }
+  }
+  gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
+  MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
+  {
+    const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
+    hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, len, ctx->partial.buf);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
+  }
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+template <typename P>
+int be_impl(mlip_ctx* ctx, float* grad) {
+  EqvWs* w = ws_of(ctx);
+  const mlip_config& cf = ctx->cfg;
+  hipStream_t st = ctx->stream;
+  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const float* th = ctx->d_params;
+  const float* tT = w->paramsT;
+  int cur = 0;
+  hipLaunchKernelGGL(k_lam_y, dim3(nblk(NC)), dim3(256), 0, st, w->y, w->yd, th + ctx->off_wo, w->Ebar, ctx->d_atom_struct, N, C, w->lam_y);
+  {
+    const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
+    hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, len, ctx->partial.buf);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
+  }
+  MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
+  hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->lam_h[cur] + NC, 0.f, 8 * NC);
+  gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
+  const int rpb = 256 / C;
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& lo = ctx->lay[l];
+    float* lh_next = w->lam_h[cur];
+    float* lh = w->lam_h[cur ^ 1];
+    for (int k = 0; k < 3; ++k) {
+      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+      gemm_nt<P>(st, LdPlain{lh_next + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->lam_a + o, C, rows});
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next + o, C}, LdPlain{w->a[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
+    }
+    {
+      KernelTimer kt(ctx, MLIP_K_MSG_BE);
+      hipLaunchKernelGGL(k_tp_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+    }
+    if (E > 0) {
+      {
+        KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, LdJetSiluEven{w->U[l], H}, E, PC, H, grad + lo.W[1])));
+      }
+      {
+        KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
+        gemm_nt<P>(st, LdPlain{w->X, PC}, tT + lo.W[1], E, H, PC, EpiLamU{w->X2, w->U[l], w->Y1[l], H, E});
+      }
+      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+    }
+    cur ^= 1;
+  }
+  {
+    const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks), S = cf.n_species;
+    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, chunks, S), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, S, len, ctx->partial.buf);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk((int64_t)S * C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)S * C, grad + ctx->off_emb);
+  }
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
+}  // namespace
+
+// =================================================================================== interface
+int eqv_alloc(mlip_ctx* ctx) {
+  const mlip_config& cf = ctx->cfg;
+  const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
+  EqvWs* w = new EqvWs();
+  ctx->model_ws = w;
+  bool ok = true;
+  auto A = [&](int64_t n) { float* p = alloc_n<float>(ctx, n); ok &= (p != nullptr); return p; };
+  ok &= (ctx->d_pos = alloc_n<float>(ctx, 3 * N)) != nullptr;
+  ok &= (ctx->d_params = alloc_n<float>(ctx, ctx->n_params)) != nullptr;
+  ok &= (ctx->d_species = alloc_n<int32_t>(ctx, N)) != nullptr;
+  ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
+  w->paramsT = A(ctx->n_params);
+  w->jphi = A(2 * E * K);
+  ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
+  w->X = A(E * PC);
+  w->X2 = A(E * H);
+  const int64_t NC9 = 9 * N * C;
+  for (int l = 0; l < L; ++l) {
+    w->U.push_back(A(2 * E * H));
+    w->Rho.push_back(A(2 * E * PC));
+    w->Y1.push_back(A(E * H));
+    w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
+  }
+  for (int l = 0; l <= L; ++l) { w->h.push_back(A(NC9)); w->mu_h.push_back(A(NC9)); w->hd.push_back(A(NC9)); }
+  w->lam_h[0] = A(NC9); w->lam_h[1] = A(NC9); w->lam_a = A(NC9);
+  w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
+  w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
+  int64_t cap = 0;
+  auto need = [&](int64_t rows, int cols, int64_t R) {
+    const bool narrow = cols <= 32;
+    int bm = narrow ? 128 : (rows > 64 ? 128 : 64), bn = narrow ? 32 : (rows > 64 ? 128 : 64);
+    cap = std::max<int64_t>(cap, (int64_t)pick_splits(rows, cols, R, bm, bn) * rows * cols);
+  };
+  need(PC, H, E); need(H, K, E); need(C, C, 5 * N);
+  cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);
+  ctx->partial.cap = cap;
+  ctx->partial.buf = A(cap);
+  return ok ? MLIP_OK : MLIP_E_HIP;
+}
+
+void eqv_free(mlip_ctx* ctx) {
+  delete ws_of(ctx);
+  ctx->model_ws = nullptr;
+}
+
+#define DISPATCH(fn, ...) (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16 ? fn<gemm::Bf16>(__VA_ARGS__) : fn<gemm::Fp32>(__VA_ARGS__))
+
+int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float*,
+                       float* E, float*) {
+  if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: build the graph first");
+  if (!pos || !params || !species || !E) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: null pointer");
+  hipStream_t st = ctx->stream;
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_species, species, sizeof(int32_t) * ctx->N, hipMemcpyDeviceToDevice, st));
+  MLIP_TRY(DISPATCH(fe_impl, ctx, E));
+  ctx->phase = PH_FE;
+  return MLIP_OK;
+}
+
+int eqv_forward_force(mlip_ctx* ctx, const float*, float* F, float*) {
+  if (ctx->phase < PH_FE) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_force: run forward_energy first");
+  if (!F) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_force: null pointer");
+  MLIP_TRY(DISPATCH(ff_impl, ctx, F));
+  ctx->phase = PH_FF;
+  return MLIP_OK;
+}
+
+int eqv_backward_force(mlip_ctx* ctx, const float* v, const float*, float* grad, float*) {
+  if (ctx->phase < PH_FF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_force: run forward_force first");
+  if (!v || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_force: null pointer");
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->v, v, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, ctx->stream));
+  MLIP_TRY(DISPATCH(bf_impl, ctx, grad));
+  ctx->phase = PH_BF;
+  return MLIP_OK;
+}
+
+int eqv_backward_energy(mlip_ctx* ctx, const float* Ebar, const float*, float* grad, float*) {
+  if (ctx->phase < PH_BF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_energy: run backward_force first");
+  if (!Ebar || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_energy: null pointer");
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->Ebar, Ebar, sizeof(float) * ctx->B, hipMemcpyDeviceToDevice, ctx->stream));
+  MLIP_TRY(DISPATCH(be_impl, ctx, grad));
+  ctx->phase = PH_BE;
+  return MLIP_OK;
+}

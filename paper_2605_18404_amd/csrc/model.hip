@@ -17,9 +17,7 @@
 #include <algorithm>
 #include <cmath>
 
-#include "common.h"
-#include "functors.h"
-#include "gemm.h"
+#include "shared_kernels.h"
 
 namespace {
 
@@ -46,65 +44,11 @@ struct InvWs {
   float* Facc = nullptr;    // [N,3]
   float* v = nullptr;       // [N,3] copy taken at BF
   float* Ebar = nullptr;    // [B]
-  float* partial = nullptr;
-  int64_t partial_cap = 0;
 };
 
 inline InvWs* ws_of(mlip_ctx* ctx) { return (InvWs*)ctx->model_ws; }
 
 // ------------------------------------------------------------------------------ small kernels
-__global__ void k_transpose(const float* __restrict__ src, float* __restrict__ dst, int rows, int cols) {
-  __shared__ float tile[32][33];
-  int c = blockIdx.x * 32 + threadIdx.x;
-  for (int r = blockIdx.y * 32 + threadIdx.y; r < min(rows, (int)(blockIdx.y + 1) * 32); r += 8)
-    if (c < cols) tile[r - blockIdx.y * 32][threadIdx.x] = src[(int64_t)r * cols + c];
-  __syncthreads();
-  int r2 = blockIdx.y * 32 + threadIdx.x;
-  for (int c2 = blockIdx.x * 32 + threadIdx.y; c2 < min(cols, (int)(blockIdx.x + 1) * 32); c2 += 8)
-    if (r2 < rows) dst[(int64_t)c2 * rows + r2] = tile[threadIdx.x][c2 - blockIdx.x * 32];
-}
-
-// Edge geometry and featurisation: unit vector, length, Gaussian basis jets, envelope jet.
-__global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
-                                const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
-                                const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta, int64_t E,
-                                int K, float rc, float4* __restrict__ geo, float2* __restrict__ env,
-                                float* __restrict__ jphi) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= E * K) return;
-  int64_t e = idx / K;
-  int k = (int)(idx % K);
-  int i = receiver[e], j = sender[e], c = code[e];
-  const StructMeta& m = meta[atom_struct[i]];
-  float sx = (float)(c / 9 - 1) * m.L[0], sy = (float)((c / 3) % 3 - 1) * m.L[1], sz = (float)(c % 3 - 1) * m.L[2];
-  float dx = (pos[3 * j] - pos[3 * i]) + sx;
-  float dy = (pos[3 * j + 1] - pos[3 * i + 1]) + sy;
-  float dz = (pos[3 * j + 2] - pos[3 * i + 2]) + sz;
-  float r = sqrtf(dx * dx + dy * dy + dz * dz);
-  float dmu = rc / (float)(K - 1);
-  float gamma = 0.5f / (dmu * dmu);
-  float t = r - (float)k * dmu;
-  float p = expf(-gamma * t * t);
-  jphi[(2 * e) * K + k] = p;
-  jphi[(2 * e + 1) * K + k] = -2.f * gamma * t * p;
-  if (k == 0) {
-    float inv = 1.f / r;
-    geo[e] = make_float4(dx * inv, dy * inv, dz * inv, r);
-    float w = 3.14159265358979323846f / rc;
-    float sn, cs;
-    sincosf(w * r, &sn, &cs);
-    env[e] = make_float2(0.5f * (1.f + cs), -0.5f * w * sn);
-  }
-}
-
-__global__ void k_embed(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C,
-                        float* __restrict__ h) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= N * C) return;
-  int64_t i = idx / C;
-  h[idx] = emb[(int64_t)species[i] * C + (idx % C)];
-}
-
 // Row-parallel gather kernels.  A row (receiver atom) is handled by TPR = C/4 threads, one
 // float4 of channels each; a block of 256 threads holds 256/TPR rows.
 struct RowThread {
@@ -252,198 +196,6 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
     *reinterpret_cast<float4*>(X + (int64_t)e * C + c0) = x;
   }
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
-}
-
-// eps_i = sum_c w_o[c] silu(y[i,c]); one wave per atom, fixed reduction order.
-__global__ void __launch_bounds__(256) k_atom_energy(const float* __restrict__ y, const float* __restrict__ wo, int N,
-                                                     int C, float* __restrict__ eps) {
-  int lane = threadIdx.x & 63;
-  int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= N) return;
-  float s = 0.f;
-  for (int c = lane; c < C; c += 64) s += wo[c] * silu(y[(int64_t)i * C + c]);
-  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-  if (lane == 0) eps[i] = s;
-}
-
-__global__ void __launch_bounds__(256) k_struct_sum(const float* __restrict__ eps, const StructMeta* __restrict__ meta,
-                                                    float* __restrict__ E) {
-  __shared__ float red[256];
-  const StructMeta& m = meta[blockIdx.x];
-  float s = 0.f;
-  for (int i = m.atom_begin + threadIdx.x; i < m.atom_end; i += 256) s += eps[i];
-  red[threadIdx.x] = s;
-  __syncthreads();
-  for (int off = 128; off > 0; off >>= 1) {
-    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) E[blockIdx.x] = red[0];
-}
-
-// Column sums over atoms in two deterministic stages: part[chunk][c] = sum over the chunk's
-// atoms of f(i, c) (64 channels x 4 atom lanes per block), then k_reduce_partials.
-// MODE 0: silu'(y) * yd     MODE 1: Ebar[struct(i)] * silu(y)
-template <int MODE>
-__global__ void __launch_bounds__(256) k_wo_grad(const float* __restrict__ y, const float* __restrict__ yd,
-                                                 const float* __restrict__ Ebar, const int32_t* __restrict__ atom_struct,
-                                                 int N, int C, int chunk_len, float* __restrict__ part) {
-  __shared__ float red[4][64];
-  int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  int al = threadIdx.x >> 6;
-  int i0 = blockIdx.y * chunk_len, i1 = min(N, i0 + chunk_len);
-  float s = 0.f;
-  if (c < C)
-    for (int i = i0 + al; i < i1; i += 4) {
-      float yy = y[(int64_t)i * C + c];
-      s += (MODE == 0) ? dsilu(yy) * yd[(int64_t)i * C + c] : Ebar[atom_struct[i]] * silu(yy);
-    }
-  red[al][threadIdx.x & 63] = s;
-  __syncthreads();
-  if (al == 0 && c < C)
-    part[(int64_t)blockIdx.y * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
-}
-
-__global__ void k_lam_y(const float* __restrict__ y, const float* __restrict__ yd, const float* __restrict__ wo,
-                        const float* __restrict__ Ebar, const int32_t* __restrict__ atom_struct, int64_t N, int C,
-                        float* __restrict__ lam_y) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= N * C) return;
-  int64_t i = idx / C;
-  int c = (int)(idx % C);
-  float d1, d2;
-  dsilu12(y[idx], d1, d2);
-  lam_y[idx] = wo[c] * (Ebar[atom_struct[i]] * d1 + d2 * yd[idx]);
-}
-
-// part[chunk][z][c] = sum over the chunk's atoms of species z of lam_h0[i][c].
-__global__ void __launch_bounds__(256) k_emb_grad(const float* __restrict__ lam_h0, const int32_t* __restrict__ species,
-                                                  int N, int C, int S, int chunk_len, float* __restrict__ part) {
-  __shared__ float red[4][64];
-  int z = blockIdx.z;
-  int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  int al = threadIdx.x >> 6;
-  int i0 = blockIdx.y * chunk_len, i1 = min(N, i0 + chunk_len);
-  float s = 0.f;
-  if (c < C)
-    for (int i = i0 + al; i < i1; i += 4)
-      if (species[i] == z) s += lam_h0[(int64_t)i * C + c];
-  red[al][threadIdx.x & 63] = s;
-  __syncthreads();
-  if (al == 0 && c < C)
-    part[((int64_t)blockIdx.y * S + z) * C + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
-}
-
-__global__ void k_scale3(const float* __restrict__ src, float s, int64_t n, float* __restrict__ dst) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < n) dst[idx] = s * src[idx];
-}
-
-__global__ void k_fill(float* __restrict__ p, float val, int64_t n) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < n) p[idx] = val;
-}
-
-// grad[i] += sum_z part[z][i]: 64 elements x 4 split groups per block, fixed summation order.
-__global__ void __launch_bounds__(256) k_reduce_partials(const float* __restrict__ part, int splits, int64_t n,
-                                                         float* __restrict__ grad) {
-  __shared__ float red[4][64];
-  const int lane = threadIdx.x & 63, zg = threadIdx.x >> 6;
-  const int64_t idx = (int64_t)blockIdx.x * 64 + lane;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  if (idx < n) {
-    int z = zg;
-    for (; z + 12 < splits; z += 16) {
-      s0 += part[(int64_t)z * n + idx];
-      s1 += part[(int64_t)(z + 4) * n + idx];
-      s2 += part[(int64_t)(z + 8) * n + idx];
-      s3 += part[(int64_t)(z + 12) * n + idx];
-    }
-    for (; z < splits; z += 4) s0 += part[(int64_t)z * n + idx];
-  }
-  red[zg][lane] = (s0 + s1) + (s2 + s3);
-  __syncthreads();
-  if (zg == 0 && idx < n) grad[idx] += (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
-}
-
-// Loss, one block: deterministic tree.  loss = mean_s (E-Eref)^2 + fw * mean (F-Fref)^2.
-__global__ void __launch_bounds__(1024) k_loss(const float* __restrict__ E, const float* __restrict__ Eref, int B,
-                                               const float* __restrict__ F, const float* __restrict__ Fref, int64_t n3,
-                                               float fw, float* __restrict__ loss) {
-  __shared__ float red[1024];
-  float se = 0.f, sf = 0.f;
-  for (int s = threadIdx.x; s < B; s += 1024) {
-    float d = E[s] - Eref[s];
-    se += d * d;
-  }
-  for (int64_t k = threadIdx.x; k < n3; k += 1024) {
-    float d = F[k] - Fref[k];
-    sf += d * d;
-  }
-  red[threadIdx.x] = se / (float)B + fw * sf / (float)n3;
-  __syncthreads();
-  for (int off = 512; off > 0; off >>= 1) {
-    if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) loss[0] = red[0];
-}
-
-__global__ void k_loss_cotangents(const float* __restrict__ E, const float* __restrict__ Eref, int B,
-                                  const float* __restrict__ F, const float* __restrict__ Fref, int64_t n3, float fw,
-                                  float* __restrict__ Ebar, float* __restrict__ v) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < B) Ebar[idx] = 2.f * (E[idx] - Eref[idx]) / (float)B;
-  if (idx < n3) v[idx] = -2.f * fw * (F[idx] - Fref[idx]) / (float)n3;
-}
-
-inline unsigned nblk(int64_t n, int b = 256) { return (unsigned)((n + b - 1) / b); }
-inline int atom_chunks(int64_t N) { return (int)std::max<int64_t>(1, std::min<int64_t>(128, N / 32)); }
-
-template <typename T>
-T* alloc_n(mlip_ctx* ctx, int64_t n) {
-  return (T*)ctx_alloc(ctx, (size_t)std::max<int64_t>(n, 1) * sizeof(T));
-}
-
-// ------------------------------------------------------------------------------ GEMM wrappers
-// D[M][N] = A[M][K] * W[N][K]^T with loader / epilogue functors; tile chosen from N.
-template <typename P, typename LdA, typename Epi>
-void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
-  LdPlain b{W, K};
-  const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
-  if (N > 64 && tiles128 >= 512)
-    gemm::launch<P, 2, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
-  else
-    gemm::launch<P, 1, 1, 2, 2, true>(st, a, b, epi, M, N, K, 1);
-}
-
-int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
-  int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
-  int64_t s = std::max<int64_t>(1, 768 / tiles);
-  s = std::min<int64_t>(s, std::max<int64_t>(1, K / 256));
-  return (int)std::min<int64_t>(s, 768);
-}
-
-// grad[Nout][Kout] += A^T B, A [R][Nout], B [R][Kout] given by loaders (reduction over R rows).
-template <typename P, typename LdA, typename LdB>
-int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
-  InvWs* w = ws_of(ctx);
-  hipStream_t st = ctx->stream;
-  if (R <= 0) return MLIP_OK;
-  const bool narrow = Kout <= 32;
-  const int bm = narrow ? 128 : (Nout > 64 ? 128 : 64), bn = narrow ? 32 : (Nout > 64 ? 128 : 64);
-  int splits = pick_splits(Nout, Kout, R, bm, bn);
-  while ((int64_t)splits * Nout * Kout > w->partial_cap && splits > 1) --splits;
-  EpiPartial epi{w->partial, Kout, Nout};
-  if (narrow)
-    gemm::launch<P, 1, 1, 4, 1, false>(st, a, b, epi, Nout, Kout, R, splits);
-  else if (Nout > 64)
-    gemm::launch<P, 2, 2, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
-  else
-    gemm::launch<P, 1, 1, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
-  int64_t n = (int64_t)Nout * Kout;
-  hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n, 64)), dim3(256), 0, st, w->partial, splits, n, grad);
-  return MLIP_OK;
 }
 
 // ------------------------------------------------------------------------------ phases
@@ -601,8 +353,8 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
     {
       const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
-      hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, len, w->partial);
-      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)C, grad + ctx->off_wo);
+      hipLaunchKernelGGL(k_wo_grad<0>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, w->yd, nullptr, nullptr, (int)N, C, len, ctx->partial.buf);
+      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
     }
   }
   MLIP_HIP_CHECK(ctx, hipGetLastError());
@@ -626,8 +378,8 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     hipLaunchKernelGGL(k_lam_y, dim3(nblk(N * C)), dim3(256), 0, st, w->y, w->yd, th + ctx->off_wo, w->Ebar, ctx->d_atom_struct, N, C, w->lam_y);
     {
       const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
-      hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, len, w->partial);
-      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)C, grad + ctx->off_wo);
+      hipLaunchKernelGGL(k_wo_grad<1>, dim3((C + 63) / 64, chunks), dim3(256), 0, st, w->y, nullptr, w->Ebar, ctx->d_atom_struct, (int)N, C, len, ctx->partial.buf);
+      hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
     }
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
     gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
@@ -670,8 +422,8 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(lam_in, w->lam_h[cur], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   else {
     const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks), S = cf.n_species;
-    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, chunks, S), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, S, len, w->partial);
-    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk((int64_t)S * C, 64)), dim3(256), 0, st, w->partial, chunks, (int64_t)S * C, grad + ctx->off_emb);
+    hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, chunks, S), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, S, len, ctx->partial.buf);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk((int64_t)S * C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)S * C, grad + ctx->off_emb);
   }
   MLIP_HIP_CHECK(ctx, hipGetLastError());
   return MLIP_OK;
@@ -680,7 +432,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
 }  // namespace
 
 // =================================================================================== interface
-int model_alloc(mlip_ctx* ctx) {
+int inv_alloc(mlip_ctx* ctx) {
   const mlip_config& cf = ctx->cfg;
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
@@ -726,20 +478,20 @@ int model_alloc(mlip_ctx* ctx) {
   };
   need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);  // atom-chunk partials
-  w->partial_cap = cap;
-  w->partial = A(cap);
+  ctx->partial.cap = cap;
+  ctx->partial.buf = A(cap);
   if (!ok) return MLIP_E_HIP;
   return MLIP_OK;
 }
 
-void model_free(mlip_ctx* ctx) {
+void inv_free(mlip_ctx* ctx) {
   delete ws_of(ctx);
   ctx->model_ws = nullptr;
 }
 
 #define DISPATCH(fn, ...) (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16 ? fn<gemm::Bf16>(__VA_ARGS__) : fn<gemm::Fp32>(__VA_ARGS__))
 
-int model_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
+int inv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
                          float* E, float* h_out) {
   const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
   if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: build the graph first");
@@ -754,7 +506,7 @@ int model_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species
   return MLIP_OK;
 }
 
-int model_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
+int inv_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
   if (ctx->phase < PH_FE) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_force: run forward_energy first");
   if (!F || (stage && (!g_out || !g_in))) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_force: missing tensor for this model kind");
@@ -763,7 +515,7 @@ int model_forward_force(mlip_ctx* ctx, const float* g_out, float* F, float* g_in
   return MLIP_OK;
 }
 
-int model_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
+int inv_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref, const float* F_ref, float* loss,
                float* Ebar, float* v) {
   if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "loss: no batch");
   if (!E || !F || !E_ref || !F_ref || !loss || !Ebar || !v) MLIP_FAIL(ctx, MLIP_E_INVALID, "loss: null pointer");
@@ -775,7 +527,7 @@ int model_loss(mlip_ctx* ctx, const float* E, const float* F, const float* E_ref
   return MLIP_OK;
 }
 
-int model_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out) {
+int inv_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, float* grad, float* hdot_out) {
   const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
   if (ctx->phase < PH_FF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_force: run forward_force first");
   if (!v || !grad || (stage && !hdot_out)) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_force: missing tensor for this model kind");
@@ -785,7 +537,7 @@ int model_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, fl
   return MLIP_OK;
 }
 
-int model_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in) {
+int inv_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad, float* lam_in) {
   const bool stage = ctx->cfg.model_kind == MLIP_MODEL_STAGE;
   if (ctx->phase < PH_BF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_energy: run backward_force first");
   if (!grad || (stage ? (!lam_out || !lam_in) : !Ebar)) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_energy: missing tensor for this model kind");
