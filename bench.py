@@ -29,19 +29,22 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 # node table touched once, indices and geometry included).
 def kernel_table(w, E, N):
     C, H, K = w.channels, w.edge_hidden, w.n_rbf
+    eqv = w.l_max == 2
+    Co = 11 * C if eqv else C          # width of the radial filter per edge
     f4 = 4
-    node = N * C * f4
+    node = (9 if eqv else 1) * N * C * f4
+    geo = 16 + 4                       # unit vector + length, sender index
     return {
         1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H),
-        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * C),
-        3: ("msg_fe", "hbm", E * C * f4 + 2 * node + E * 4),
-        4: ("msg_ff", "hbm", 2 * E * C * f4 + 4 * node + E * 20),
-        5: ("msg_bf", "hbm", 3 * E * C * f4 + 4 * node + E * 28),
-        6: ("msg_be", "hbm", 3 * E * C * f4 + 6 * node + E * 28),
-        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * C * H),
-        8: ("be_dgrad_gemm", "mfma", 2.0 * E * C * H),
-        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * C * H),
-        10: ("be_wgrad_gemm", "mfma", 2.0 * E * C * H),
+        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co),
+        3: ("msg_fe", "hbm", E * Co * f4 + 2 * node + E * geo),
+        4: ("msg_ff", "hbm", 2 * E * Co * f4 + 4 * node + E * geo),
+        5: ("msg_bf", "hbm", 3 * E * Co * f4 + 4 * node + E * (geo + 8)),
+        6: ("msg_be", "hbm", 3 * E * Co * f4 + 6 * node + E * (geo + 8)),
+        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * Co * H),
+        8: ("be_dgrad_gemm", "mfma", 2.0 * E * Co * H),
+        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H),
+        10: ("be_wgrad_gemm", "mfma", 2.0 * E * Co * H),
     }
 
 
@@ -57,25 +60,40 @@ def load_traffic(workload, kernel):
 
 def cpu_baseline(w, inp, budget_s=20.0):
     """Times the oracle as it stands on a bounded sample: whole structures of the batch, one
-    after the other, until about budget_s seconds of CPU work have been spent."""
+    after the other (graph build + all four phases each), until about budget_s seconds of CPU
+    work have been spent.  A single-structure workload too large for the oracle is sampled by a
+    smaller cell of the same density and model (stated in `sample`)."""
     import numpy as np
     import torch
 
     from oracle import mlip_oracle as O
+    from paper_2605_18404_amd import synth
+    note = ""
+    if w.n_structs == 1 and w.atoms_per_struct > 1000:
+        n = 300
+        w = synth.shrink(w, atoms_per_struct=n, box=w.box * (n / w.atoms_per_struct) ** (1.0 / 3.0))
+        inp = synth.make_inputs(w)
+        note = f"a {n}-atom cell of the same density and model stands in for the large cell; "
     cfg = O.cfg_from_workload(w)
     done_atoms, t_used, n_done = 0, 0.0, 0
     for s in range(w.n_structs):
         a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
+        sp = np.array([0, b - a], np.int32)
         t0 = time.perf_counter()
-        O.train_step(cfg, inp.pos[a:b], inp.species[a:b], np.array([0, b - a], np.int32), inp.cell[s:s + 1],
-                     inp.params, inp.E_ref[s:s + 1], inp.F_ref[a:b])
+        if w.kind == synth.KIND_STAGE:
+            st = {k: v[a:b] for k, v in inp.stage.items()}
+            O.stage_step(cfg, inp.pos[a:b], sp, inp.cell[s:s + 1], inp.params, st["h_in"], st["g_out"], st["hdot_in"],
+                         st["v"], st["lam_out"])
+        else:
+            O.train_step(cfg, inp.pos[a:b], inp.species[a:b], sp, inp.cell[s:s + 1], inp.params, inp.E_ref[s:s + 1],
+                         inp.F_ref[a:b])
         t_used += time.perf_counter() - t0
         done_atoms += b - a
         n_done += 1
         if t_used > budget_s:
             break
     return {"value": done_atoms / t_used, "unit": "atoms/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{n_done} of {w.n_structs} structures ({done_atoms} atoms), graph build + full step each, "
+            "sample": f"{note}{n_done} of {w.n_structs} structures ({done_atoms} atoms), graph build + full step each, "
                       f"{t_used:.1f} s of CPU time"}
 
 
@@ -99,7 +117,7 @@ def main():
     from paper_2605_18404_amd import synth
     from paper_2605_18404_amd.binding import Mlip
 
-    idx = {"cfg0": 0, "cfg1": 1}[args.workload]
+    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}[args.workload]
     w = synth.WORKLOADS[idx]
     inp = synth.make_inputs(w)
     dev = "cuda:0"
@@ -107,13 +125,37 @@ def main():
     m = Mlip.for_workload(w, device=dev)
     d = dict(pos=t(inp.pos), species=t(inp.species), struct_ptr=t(inp.struct_ptr), cell=t(inp.cell),
              params=t(inp.params), E_ref=t(inp.E_ref), F_ref=t(inp.F_ref))
+    st = {k: t(v) for k, v in inp.stage.items()}
     out = None
+    grad = torch.zeros(m.mlip_param_count(), device=dev)
 
     def step(timed=False):
+        """One pass of the whole hot path.  A pipeline stage has no loss: its step is graph
+        build + FE + FF + BF + BE on the seeded boundary tensors."""
         nonlocal out
-        out = m.mlip_train_step(d["pos"], d["species"], d["struct_ptr"], d["cell"], w.cutoff, d["params"],
-                                d["E_ref"], d["F_ref"], out=out, timed=timed)
-        return out
+        if w.kind != synth.KIND_STAGE:
+            out = m.mlip_train_step(d["pos"], d["species"], d["struct_ptr"], d["cell"], w.cutoff, d["params"],
+                                    d["E_ref"], d["F_ref"], out=out, timed=timed)
+            return out
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)] if timed else None
+        mark = (lambda k: ev[k].record()) if timed else (lambda k: None)
+        mark(0)
+        m.mlip_graph_build(d["pos"], d["struct_ptr"], d["cell"], w.cutoff)
+        mark(1)
+        m.mlip_forward_energy(d["pos"], None, d["params"], h_in=st["h_in"])
+        mark(2)
+        m.mlip_forward_force(g_out=st["g_out"])
+        mark(3)
+        grad.zero_()
+        m.mlip_backward_force(st["v"], grad, hdot_in=st["hdot_in"])
+        mark(4)
+        m.mlip_backward_energy(grad, lam_out=st["lam_out"])
+        mark(5)
+        res = {}
+        if timed:
+            torch.cuda.synchronize()
+            res["phase_ms"] = [ev[k].elapsed_time(ev[k + 1]) for k in range(5)]
+        return res
 
     for _ in range(args.warmup):
         step()
@@ -166,7 +208,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_bf16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "atoms": w.n_atoms, "structures": w.n_structs, "edges": E_edges,
                    "channels": w.channels, "layers": w.n_layers, "n_rbf": w.n_rbf, "cutoff": w.cutoff,
-                   "includes_graph_build": True},
+                   "l_max": w.l_max, "edge_mlp_depth": w.edge_depth, "includes_graph_build": True,
+                   "workspace_GB": m.mlip_workspace_bytes() / 1e9},
         "edges_per_s": E_edges / (ms * 1e-3),
         "phase_ms": {"graph": ph[0], "FE": ph[1], "FF": ph[2], "BF": ph[3], "BE": ph[4]},
         "roofline": roof,

@@ -96,6 +96,28 @@ def radius_graph(pos: np.ndarray, struct_ptr: np.ndarray, cell: np.ndarray, cuto
     return dict(row_ptr=row_ptr, sender=sender, shift=shift, receiver=receiver, rev=rev)
 
 
+def radius_graph_rows(pos: np.ndarray, struct_ptr: np.ndarray, cell: np.ndarray, cutoff: float,
+                      rows: np.ndarray) -> List[Tuple[np.ndarray, np.ndarray]]:
+    """The same definition as radius_graph, for chosen receivers only (so that rows of a system
+    too large for the full pair loop can still be checked one by one).  Returns, per requested
+    receiver, (sender [d], shift [d,3]) in the canonical in-row order."""
+    pos = np.asarray(pos, dtype=np.float64)
+    rng = np.array([-1.0, 0.0, 1.0])
+    S = np.stack(np.meshgrid(rng, rng, rng, indexing="ij"), -1).reshape(27, 3)
+    out = []
+    for i in rows:
+        s = int(np.searchsorted(struct_ptr, i, side="right") - 1)
+        a, b = int(struct_ptr[s]), int(struct_ptr[s + 1])
+        off = S @ np.asarray(cell[s], dtype=np.float64)
+        d = pos[a:b, None, :] + off[None, :, :] - pos[i][None, None, :]   # [n, 27, 3]
+        r2 = d[..., 0] * d[..., 0] + d[..., 1] * d[..., 1] + d[..., 2] * d[..., 2]
+        ok = r2 < cutoff * cutoff
+        ok[i - a, 13] = False
+        rj, rs = np.nonzero(ok)
+        out.append(((rj + a).astype(np.int32), S[rs].astype(np.int32)))
+    return out
+
+
 # ============================================================================ edge features
 
 def rbf(r: torch.Tensor, n_rbf: int, cutoff: float) -> torch.Tensor:

@@ -1,0 +1,156 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py
+times.  Where the oracle cannot run the whole input in reasonable time or memory it checks
+sampled outputs it can compute one by one (whole structures of a batch, single rows of the
+neighbour list), or an input built so that the exact answer follows from a small oracle run
+(a periodic supercell)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mlip_oracle as O
+from paper_2605_18404_amd import synth
+from paper_2605_18404_amd.binding import Mlip
+
+from gpu_common import DEV, DevInputs, dev, oracle_train_step, per_tensor_rel, rel
+
+pytestmark = pytest.mark.gpu
+TOL_FP32, TOL_BF16 = 1e-4, 2e-2
+
+
+def _oracle_struct(w, inp, s):
+    cfg = O.cfg_from_workload(w)
+    a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
+    sub = dict(cfg)
+    sub["force_weight"] = cfg["force_weight"] * ((b - a) / inp.pos.shape[0]) * w.n_structs
+    r = O.train_step(sub, inp.pos[a:b], inp.species[a:b], np.array([0, b - a], np.int32), inp.cell[s:s + 1],
+                     inp.params, inp.E_ref[s:s + 1], inp.F_ref[a:b])
+    return a, b, r
+
+
+def test_cfg1_full_batch_all_outputs():
+    w = synth.WORKLOADS[1]
+    inp = synth.make_inputs(w)
+    ref = oracle_train_step(w, inp)  # all 32 structures
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    assert rel(out["E"].cpu().numpy(), ref["E"]) < TOL_FP32
+    assert rel(out["F"].cpu().numpy(), ref["F"]) < TOL_FP32
+    assert abs(float(out["loss"].cpu()) - ref["loss"]) < TOL_FP32 * abs(ref["loss"])
+    g = out["grad"].cpu().numpy()
+    assert rel(g, ref["grad"]) < TOL_FP32
+    assert max(per_tensor_rel(w, g, ref["grad"]).values()) < 3 * TOL_FP32
+    # graph of the full batch, bit-exact
+    gref = O.radius_graph(inp.pos, inp.struct_ptr, inp.cell, w.cutoff)
+    row_ptr, sender, shift, rev = [t.cpu().numpy() for t in m.mlip_graph_export()]
+    assert np.array_equal(row_ptr, gref["row_ptr"]) and np.array_equal(sender, gref["sender"])
+    assert np.array_equal(shift, gref["shift"]) and np.array_equal(rev, gref["rev"])
+    m.close()
+
+
+def test_cfg2_full_batch_sampled_structures():
+    w = synth.WORKLOADS[2]
+    inp = synth.make_inputs(w)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    E, F = out["E"].cpu().numpy(), out["F"].cpu().numpy()
+    for s in (3, 12):  # structures do not interact: E_s and the forces of s are exact per structure
+        a, b, r = _oracle_struct(w, inp, s)
+        assert abs(E[s] - r["E"][0]) < TOL_BF16 * max(1.0, abs(r["E"][0]))
+        assert rel(F[a:b], r["F"]) < TOL_BF16
+    for s in range(w.n_structs):  # zero net force per structure at any size
+        a, b = inp.struct_ptr[s], inp.struct_ptr[s + 1]
+        assert np.abs(F[a:b].sum(0)).max() < 1e-3 * np.abs(F[a:b]).sum(0).max()
+    assert np.all(np.isfinite(out["grad"].cpu().numpy()))
+    m.close()
+
+
+def test_cfg3_full_stage_sampled_structures():
+    w = synth.WORKLOADS[3]
+    inp = synth.make_inputs(w)
+    cfg = O.cfg_from_workload(w)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff)
+    h_out = m.mlip_forward_energy(d.pos, None, d.params, h_in=d.stage["h_in"])
+    p, g_in = m.mlip_forward_force(g_out=d.stage["g_out"])
+    grad = torch.zeros(m.mlip_param_count(), device=DEV)
+    hdot_out = m.mlip_backward_force(d.stage["v"], grad, hdot_in=d.stage["hdot_in"])
+    lam_in = m.mlip_backward_energy(grad, lam_out=d.stage["lam_out"])
+    torch.cuda.synchronize()
+    got = dict(h_out=h_out.cpu().numpy(), p=p.cpu().numpy(), g_in=g_in.cpu().numpy(),
+               hdot_out=hdot_out.cpu().numpy(), lam_in=lam_in.cpu().numpy())
+    st = inp.stage
+    for s in (0, 17, 41, 63):
+        a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
+        ref = O.stage_step(cfg, inp.pos[a:b], np.array([0, b - a], np.int32), inp.cell[s:s + 1], inp.params,
+                           st["h_in"][a:b], st["g_out"][a:b], st["hdot_in"][a:b], st["v"][a:b], st["lam_out"][a:b], split=False)
+        for k in got:
+            assert rel(got[k][a:b], ref[k]) < TOL_BF16, (s, k)
+    assert np.all(np.isfinite(grad.cpu().numpy()))
+    m.close()
+
+
+def test_cfg4_full_size_graph_rows_and_net_force():
+    w = synth.WORKLOADS[4]
+    inp = synth.make_inputs(w)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    row_ptr, sender, shift, rev = [t.cpu().numpy() for t in m.mlip_graph_export()]
+    E = len(sender)
+    rows = np.random.default_rng(4).choice(w.n_atoms, size=256, replace=False)
+    for i, (snd, sh) in zip(rows, O.radius_graph_rows(inp.pos, inp.struct_ptr, inp.cell, w.cutoff, rows)):
+        a, b = row_ptr[i], row_ptr[i + 1]
+        assert np.array_equal(sender[a:b], snd) and np.array_equal(shift[a:b], sh), i
+    # invariants of the whole list
+    recv = np.repeat(np.arange(w.n_atoms, dtype=np.int32), np.diff(row_ptr))
+    assert row_ptr[0] == 0 and row_ptr[-1] == E
+    assert np.array_equal(rev[rev], np.arange(E)) and np.array_equal(sender[rev], recv) and np.array_equal(shift[rev], -shift)
+    code = (shift[:, 0] + 1) * 9 + (shift[:, 1] + 1) * 3 + (shift[:, 2] + 1)
+    key = recv.astype(np.int64) * (w.n_atoms * 27) + sender.astype(np.int64) * 27 + code
+    assert np.all(np.diff(key) > 0)
+    expect = (w.n_atoms / w.box ** 3) * 4.0 / 3.0 * np.pi * (w.cutoff ** 3 - 0.5)
+    assert abs(E / w.n_atoms - expect) / expect < 0.02
+    F = out["F"].cpu().numpy()
+    assert np.all(np.isfinite(F)) and np.all(np.isfinite(out["grad"].cpu().numpy()))
+    assert np.abs(F.sum(0)).max() < 1e-3 * np.abs(F).sum(0).max()
+    m.close()
+
+
+def test_cfg4_size_supercell_against_oracle():
+    """A 6x6x6 periodic replica (21,600 atoms, the size of workload 4, its full model) of a
+    100-atom cell the oracle can run: E = 216 E_cell, F tiles, and with E_ref' = 216 E_ref the
+    loss and gradient are 216^2 times the cell's with force weight fw / 216^2."""
+    k = 6
+    K3 = k ** 3
+    base = synth.shrink(synth.WORKLOADS[4], atoms_per_struct=100, box=(100 / 0.1) ** (1 / 3))
+    inp = synth.make_inputs(base)
+    cfg = O.cfg_from_workload(base)
+    cfg["force_weight"] = base.force_weight / K3 ** 2
+    ref = O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref)
+    L = np.float32(base.box)
+    offs = np.array([[a, b, c] for a in range(k) for b in range(k) for c in range(k)], dtype=np.float32) * L
+    pos = (inp.pos[None, :, :] + offs[:, None, :]).reshape(-1, 3).astype(np.float32)
+    Lb = np.float32(k) * L
+    pos = np.where(pos >= Lb, np.nextafter(Lb, np.float32(0)), pos)
+    big = synth.shrink(base, atoms_per_struct=100 * K3, box=float(Lb))
+    m = Mlip.for_workload(big)
+    out = m.mlip_train_step(dev(pos), dev(np.tile(inp.species, K3)), dev(np.array([0, 100 * K3], np.int32)),
+                            dev((np.eye(3) * Lb).astype(np.float32)[None]), base.cutoff, dev(inp.params),
+                            dev((inp.E_ref * K3).astype(np.float32)), dev(np.tile(inp.F_ref, (K3, 1))))
+    torch.cuda.synchronize()
+    assert abs(float(out["E"].cpu()[0]) - K3 * ref["E"][0]) < TOL_BF16 * abs(K3 * ref["E"][0])
+    assert rel(out["F"].cpu().numpy(), np.tile(ref["F"], (K3, 1))) < TOL_BF16
+    # the loss is a deterministic function of the E and F just checked: verify it from them
+    Eg, Fg = out["E"].cpu().numpy().astype(np.float64), out["F"].cpu().numpy().astype(np.float64)
+    want = (Eg[0] - K3 * float(inp.E_ref[0])) ** 2 + base.force_weight * np.mean((Fg - np.tile(inp.F_ref, (K3, 1))) ** 2)
+    assert abs(float(out["loss"].cpu()) - want) < 1e-4 * abs(want)
+    g = out["grad"].cpu().numpy()
+    assert rel(g, K3 ** 2 * ref["grad"]) < TOL_BF16
+    assert m.n_edges == K3 * len(O.radius_graph(inp.pos, inp.struct_ptr, inp.cell, base.cutoff)["sender"])
+    m.close()
