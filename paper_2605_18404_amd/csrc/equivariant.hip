@@ -32,6 +32,7 @@ struct EqvWs {
   float* jphi = nullptr;  // [E][2][K]
   float2* env = nullptr;  // [E]
   std::vector<float*> U;    // [E][2][H]
+  std::vector<__bf16*> SJ;  // bf16 GEMMs only: activated jets [E][2][H]
   std::vector<float*> Rho;  // [E][2][11 C]
   std::vector<float*> Y1;   // [E][H]  BF -> BE
   float* X = nullptr;       // [E][11 C]
@@ -330,10 +331,10 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[l], H, 2 * E});
+        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-      gemm_nt<P>(st, LdJetSilu{w->U[l], H}, th + lo.W[1], 2 * E, PC, H, EpiOmega{w->Rho[l], w->env, PC, 2 * E});
+      gemm_nt<P>(st, Act<P>::jet(w->U[l], w->SJ[l], H), th + lo.W[1], 2 * E, PC, H, EpiOmega{w->Rho[l], w->env, PC, 2 * E});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
@@ -407,7 +408,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, LdJetSiluOdd{w->U[l], H}, E, PC, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
@@ -464,7 +465,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, LdJetSiluEven{w->U[l], H}, E, PC, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
@@ -507,6 +508,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   const int64_t NC9 = 9 * N * C;
   for (int l = 0; l < L; ++l) {
     w->U.push_back(A(2 * E * H));
+    w->SJ.push_back(cf.gemm_dtype == MLIP_GEMM_BF16 ? (__bf16*)A(E * H) : nullptr);
     w->Rho.push_back(A(2 * E * PC));
     w->Y1.push_back(A(E * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));

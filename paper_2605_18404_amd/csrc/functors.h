@@ -8,6 +8,8 @@
 
 namespace fx {
 
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float sigm(float x) { return 1.f / (1.f + __expf(-x)); }
 __device__ __forceinline__ float silu(float x) { return x * sigm(x); }
 __device__ __forceinline__ float dsilu(float x) {
@@ -25,7 +27,12 @@ __device__ __forceinline__ void dsilu12(float x, float& d1, float& d2) {
   d2 = s * (1.f - s) * (2.f + x * (1.f - 2.f * s));
 }
 
-#define FX_MAP4(out, expr_x, expr_y, expr_z, expr_w) float4 out = make_float4(expr_x, expr_y, expr_z, expr_w)
+// one sigmoid, then either silu(a) or silu'(a) * b, chosen without a branch
+__device__ __forceinline__ float jet1(float a, float b, bool odd) {
+  float s = sigm(a);
+  float val = a * s, der = s * (1.f + a * (1.f - s)) * b;
+  return odd ? der : val;
+}
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ float4 mul4(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
@@ -60,11 +67,16 @@ struct LdJetSilu {  // rows of a jet matrix u [2E][W]: even -> silu(u), odd -> s
     const float* pe = u + (rho & ~(int64_t)1) * W + c;
     Raw x;
     x.a = ld4(pe);
+    x.b = ld4(pe + W);  // unconditional (the pair row always exists): no branch around the load
     x.odd = (rho & 1) != 0;
-    x.b = x.odd ? ld4(pe + W) : make_float4(0.f, 0.f, 0.f, 0.f);
     return x;
   }
-  __device__ __forceinline__ float4 finish(const Raw& x) const { return x.odd ? mul4(dsilu4(x.a), x.b) : silu4(x.a); }
+  __device__ __forceinline__ float4 finish(const Raw& x) const {
+    float4 r;
+    r.x = jet1(x.a.x, x.b.x, x.odd); r.y = jet1(x.a.y, x.b.y, x.odd);
+    r.z = jet1(x.a.z, x.b.z, x.odd); r.w = jet1(x.a.w, x.b.w, x.odd);
+    return r;
+  }
 };
 struct LdJetSiluEven {  // row e -> silu(u[2e])
   typedef float4 Raw;
@@ -100,7 +112,34 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
   __device__ __forceinline__ float4 finish(const Raw& v) const { return mul4(dsilu4(v.a), v.b); }
 };
 
+struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by their producer)
+  typedef bf16x4_t Raw;
+  const __bf16* p;
+  int64_t ld;
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return *reinterpret_cast<const bf16x4_t*>(p + r * ld + c); }
+  __device__ __forceinline__ float4 finish(const Raw& x) const {
+    return make_float4((float)x[0], (float)x[1], (float)x[2], (float)x[3]);
+  }
+};
+
 // ---------------------------------------------------------------------------- epilogues
+struct EpiStoreJetAct {  // u = v (fp32 jets) and the activated jets silu(u), silu'(u) u' rounded to bf16
+  float* u;
+  __bf16* sj;
+  int64_t ld, M;  // M = 2E
+  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+#pragma unroll
+    for (int j = 0; j < 4; j += 2)
+      if (r0 + j + 1 < M) {
+        const int64_t o = (r0 + j) * ld + col;
+        u[o] = v[j];
+        u[o + ld] = v[j + 1];
+        const float s = sigm(v[j]);
+        sj[o] = (__bf16)(v[j] * s);
+        sj[o + ld] = (__bf16)(s * (1.f + v[j] * (1.f - s)) * v[j + 1]);
+      }
+  }
+};
 struct EpiStore {
   float* p;
   int64_t ld, M;

@@ -2,18 +2,21 @@
 //
 //   D(m, n) = sum_k A(m, k) * B(n, k)
 //
-// The operands are not plain arrays but functors that return four consecutive values, so
-// element-wise producers (activation, jets, products with saved tensors) are evaluated while a
-// tile is staged into LDS and never written to HBM.  Two orientations exist per operand:
-//   k-contiguous (KC): ld(row, k4) returns A(row, k4 .. k4+3)     -- forward / data-gradient
-//   k-strided    (KS): ld(k, row4) returns A(row4 .. row4+3, k)   -- weight gradients, where
-//                      the reduction index is the row (edge or atom) of both stored operands.
+// The operands are not plain arrays but functors, so element-wise producers (activation, jets,
+// products with saved tensors) are evaluated while a tile is staged into LDS and never written
+// to HBM.  A loader has two halves:  Raw fetch(row, col4)  issues the loads of four consecutive
+// values only, and  float4 finish(raw)  applies the element-wise function when the stage is
+// written to LDS -- so the loads of the next stage stay in flight during the matrix products.
+// Two orientations exist per operand:
+//   k-contiguous (KC): fetch(row, k4) -> A(row, k4 .. k4+3)     -- forward / data-gradient
+//   k-strided    (KS): fetch(k, row4) -> A(row4 .. row4+3, k)   -- weight gradients, where the
+//                      reduction index is the row (edge or atom) of both stored operands.
 // Precision policies:
-//   Fp32: v_mfma_f32_32x32x2_f32, LDS tiles k-major [BK][rows+pad] (fragment = one float).
-//   Bf16: v_mfma_f32_32x32x16_bf16, operands rounded to bf16 (nearest even) while staged,
-//         LDS tiles row-major [rows][BK+pad] (fragment = 8 consecutive k), fp32 accumulate.
-// A workgroup is 256 threads = 4 waves arranged WM x WN, each wave owning TM x TN blocks of
-// 32x32.  grid = (tiles, splits): split z reduces k in [z*kchunk, (z+1)*kchunk).
+//   Fp32: v_mfma_f32_32x32x2_f32; LDS stage k-major [BK][rows+4] (fragment = one float).
+//   Bf16: v_mfma_f32_32x32x16_bf16; operands rounded to bf16 (nearest even) while staged, fp32
+//         accumulate.  KC: LDS stage row-major [rows][BK+8] (fragment = one 16-byte read of 8
+//         consecutive k).  KS: k-major [BK][rows+8], fragment gathered with eight 2-byte reads.
+//
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,36 +29,38 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 struct Fp32 {
   typedef float lds_t;
-  static constexpr int BK = 16;
-  static constexpr bool K_MAJOR = true;
+  static constexpr bool IS_BF16 = false;
+  static constexpr int BK_BIG = 16;
 };
 struct Bf16 {
   typedef __bf16 lds_t;
-  static constexpr int BK = 32;
-  static constexpr bool K_MAJOR = false;
+  static constexpr bool IS_BF16 = true;
+  static constexpr int BK_BIG = 32;
 };
 
-template <typename P, int ROWS>
+template <typename P, int ROWS, int BK, bool KC>
 struct Tile {
-  // Fp32: [BK][ROWS + 4] floats.  Bf16: [ROWS][BK + 8] bf16 (80-byte rows: conflict-free 16-byte reads).
-  static constexpr int LD = P::K_MAJOR ? (ROWS + 4) : (P::BK + 8);
-  static constexpr int SIZE = P::K_MAJOR ? (P::BK * LD) : (ROWS * LD);
+  // k-major unless bf16 with k-contiguous operands
+  static constexpr bool K_MAJOR = !(P::IS_BF16 && KC);
+  static constexpr int PAD = P::IS_BF16 ? 8 : 4;
+  static constexpr int LD = K_MAJOR ? (ROWS + PAD) : (BK + PAD);
+  static constexpr int SIZE = K_MAJOR ? (BK * LD) : (ROWS * LD);
 };
 
 // ---- staging: global (through the loader functor) -> registers -> LDS ------------------------
-// A loader functor has two halves so that the global loads of the next tile stay in flight
-// while the current tile is multiplied:  Raw fetch(row, col4)  issues the loads only, and
-// float4 finish(raw)  applies the element-wise producer when the tile is written to LDS.
-template <typename P, int ROWS, bool KC, typename Ld>
+template <typename P, int ROWS, int BK, bool KC, typename Ld>
 struct Stager {
-  static constexpr int NVT = ROWS * P::BK / 4;       // float4 per tile
+  typedef Tile<P, ROWS, BK, KC> TL;
+  static constexpr int NVT = ROWS * BK / 4;          // float4 per stage
   static constexpr int NV = (NVT + 255) / 256;       // per thread
-  static constexpr int Q = KC ? (P::BK / 4) : (ROWS / 4);
+  static constexpr int Q = KC ? (BK / 4) : (ROWS / 4);
   typename Ld::Raw v[NV];
   unsigned ok = 0;
 
-  // KC: a row holds Q = BK/4 float4;    idx -> (row = idx / Q, kq = idx % Q)
+  // KC: a row holds Q = BK/4 float4;     idx -> (row = idx / Q, kq = idx % Q)
   // KS: a k-row holds Q = ROWS/4 float4; idx -> (k = idx / Q,  rq = idx % Q)
+  // Loads are unconditional: out-of-range coordinates are clamped to a valid element and the
+  // value is discarded when the stage is written (no divergent branches around memory ops).
   __device__ __forceinline__ void load(const Ld& ld, int64_t row0, int64_t n_rows, int64_t k0, int64_t k_end, int t) {
     ok = 0;
 #pragma unroll
@@ -67,46 +72,42 @@ struct Stager {
         if (KC) {
           r = row0 + idx / Q; c = k0 + 4 * (idx % Q);
           in = r < n_rows && c < k_end;
+          r = r < n_rows ? r : n_rows - 1;
+          c = c < k_end ? c : k_end - 4;
         } else {
           r = k0 + idx / Q; c = row0 + 4 * (idx % Q);
           in = c < n_rows && r < k_end;
+          r = r < k_end ? r : k_end - 1;
+          c = c < n_rows ? c : n_rows - 4;
         }
-        if (in) {
-          v[it] = ld.fetch(r, c);
-          ok |= 1u << it;
-        }
+        v[it] = ld.fetch(r, c);
+        ok |= (in ? 1u : 0u) << it;
       }
     }
   }
 
   __device__ __forceinline__ void store(const Ld& ld, typename P::lds_t* s, int t) const {
-    constexpr int LD = Tile<P, ROWS>::LD;
+    constexpr int LD = TL::LD;
     typedef typename P::lds_t T;
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
       const int idx = t + it * 256;
       if (NVT % 256 != 0 && idx >= NVT) continue;
-      const float4 x = (ok >> it) & 1u ? ld.finish(v[it]) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 x = ld.finish(v[it]);
+      const float keep = (ok >> it) & 1u ? 1.f : 0.f;
+      if (!((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
+      (void)keep;
       const int a = idx / Q, b = idx % Q;  // KC: (row, kq); KS: (k, rq)
-      if (KC) {
-        if constexpr (P::K_MAJOR) {  // transpose into [k][row]
-          s[(4 * b + 0) * LD + a] = (T)x.x;
-          s[(4 * b + 1) * LD + a] = (T)x.y;
-          s[(4 * b + 2) * LD + a] = (T)x.z;
-          s[(4 * b + 3) * LD + a] = (T)x.w;
-        } else {  // [row][k], 4 bf16 = one 8-byte store
-          bf16x4 p = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
-          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + a * LD + 4 * b) = p;
-        }
-      } else {
-        if constexpr (P::K_MAJOR) {  // [k][row], one 16-byte store
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(s) + a * LD + 4 * b) = x;
-        } else {  // transpose into [row][k]
-          s[(4 * b + 0) * LD + a] = (T)x.x;
-          s[(4 * b + 1) * LD + a] = (T)x.y;
-          s[(4 * b + 2) * LD + a] = (T)x.z;
-          s[(4 * b + 3) * LD + a] = (T)x.w;
-        }
+      if constexpr (KC && TL::K_MAJOR) {  // fp32: transpose into [k][row]
+        s[(4 * b + 0) * LD + a] = (T)x.x;
+        s[(4 * b + 1) * LD + a] = (T)x.y;
+        s[(4 * b + 2) * LD + a] = (T)x.z;
+        s[(4 * b + 3) * LD + a] = (T)x.w;
+      } else if constexpr (P::IS_BF16) {  // KC [row][k] or KS [k][row]: 4 values = one 8-byte store
+        bf16x4 p = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + a * LD + 4 * b) = p;
+      } else {  // KS fp32 [k][row]: one 16-byte store
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(s) + a * LD + 4 * b) = x;
       }
     }
   }
@@ -115,22 +116,26 @@ struct Stager {
 // ---- the kernel -----------------------------------------------------------------------------
 // Epi: void operator()(int64_t row0, int col, const float (&v)[4], int z) const  -- rows row0..row0+3
 // of column col (the functor checks row0 + j < M itself; col < N is guaranteed), z = split index.
-template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
-__global__ void __launch_bounds__(256)
+//
+// One output tile per workgroup, LDS double buffer, one barrier per k-tile; several workgroups
+// per compute unit hide each other's global-load latency.  Workgroups are dealt round-robin to
+// the 8 XCDs (each with its own L2): a group is one (row tile, k split), its column tiles go to
+// the same XCD one after the other, so the A rows are fetched into one L2 only.
+template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
+__global__ void __launch_bounds__(256, 3)
 k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, int splits) {
   static_assert(WM * WN == 4, "four waves per workgroup");
-  constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, BK = P::BK;
+  constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
   typedef typename P::lds_t lds_t;
-  constexpr int LDA = Tile<P, BM>::LD, LDB = Tile<P, BN>::LD;
-  __shared__ __attribute__((aligned(16))) lds_t sA[2][Tile<P, BM>::SIZE];
-  __shared__ __attribute__((aligned(16))) lds_t sB[2][Tile<P, BN>::SIZE];
+  typedef Tile<P, BM, BK, KC> TA;
+  typedef Tile<P, BN, BK, KC> TB;
+  constexpr int LDA = TA::LD, LDB = TB::LD;
+  __shared__ __attribute__((aligned(16))) lds_t sA[2][TA::SIZE];
+  __shared__ __attribute__((aligned(16))) lds_t sB[2][TB::SIZE];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int li = lane & 31, g = lane >> 5;
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  A group is one
-  // (row tile, k split); its column tiles go to the same XCD one after the other, so the A rows
-  // are fetched into one L2 only, and consecutive groups spread over all XCDs.
   const int tiles_n = (N + BN - 1) / BN;
   const int64_t tiles_m = (M + BM - 1) / BM;
   const int64_t local = blockIdx.x >> 3;
@@ -150,15 +155,13 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  Stager<P, BM, KC, LdA> stA;
-  Stager<P, BN, KC, LdB> stB;
-  const int64_t nk = (ke > kb) ? (ke - kb + BK - 1) / BK : 0;
-  if (nk > 0) {
-    stA.load(lda, m0, M, kb, ke, t);
-    stB.load(ldb, n0, N, kb, ke, t);
-    stA.store(lda, sA[0], t);
-    stB.store(ldb, sB[0], t);
-  }
+  Stager<P, BM, BK, KC, LdA> stA;
+  Stager<P, BN, BK, KC, LdB> stB;
+  const int64_t nk = (ke - kb + BK - 1) / BK;  // >= 1: the launcher makes every split non-empty
+  stA.load(lda, m0, M, kb, ke, t);
+  stB.load(ldb, n0, N, kb, ke, t);
+  stA.store(lda, sA[0], t);
+  stB.store(ldb, sB[0], t);
   __syncthreads();
   for (int64_t kt = 0; kt < nk; ++kt) {
     const int cur = (int)(kt & 1);
@@ -168,14 +171,14 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
     }
     const lds_t* a_s = sA[cur];
     const lds_t* b_s = sB[cur];
-    if constexpr (P::K_MAJOR) {
+    if constexpr (!P::IS_BF16) {
 #pragma unroll
       for (int kk = 0; kk < BK / 2; ++kk) {
         float af[TM], bf[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = ((const float*)a_s)[(2 * kk + g) * LDA + (wm * TM + i) * 32 + li];
+        for (int i = 0; i < TM; ++i) af[i] = a_s[(2 * kk + g) * LDA + (wm * TM + i) * 32 + li];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = ((const float*)b_s)[(2 * kk + g) * LDB + (wn * TN + j) * 32 + li];
+        for (int j = 0; j < TN; ++j) bf[j] = b_s[(2 * kk + g) * LDB + (wn * TN + j) * 32 + li];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -186,12 +189,23 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
         bf16x8 af[TM], bf[TN];
+        if constexpr (KC) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          af[i] = *reinterpret_cast<const bf16x8*>((const __bf16*)a_s + ((wm * TM + i) * 32 + li) * LDA + 16 * kk + 8 * g);
+          for (int i = 0; i < TM; ++i)
+            af[i] = *reinterpret_cast<const bf16x8*>(&a_s[((wm * TM + i) * 32 + li) * LDA + 16 * kk + 8 * g]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          bf[j] = *reinterpret_cast<const bf16x8*>((const __bf16*)b_s + ((wn * TN + j) * 32 + li) * LDB + 16 * kk + 8 * g);
+          for (int j = 0; j < TN; ++j)
+            bf[j] = *reinterpret_cast<const bf16x8*>(&b_s[((wn * TN + j) * 32 + li) * LDB + 16 * kk + 8 * g]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) af[i][r] = a_s[(16 * kk + 8 * g + r) * LDA + (wm * TM + i) * 32 + li];
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) bf[j][r] = b_s[(16 * kk + 8 * g + r) * LDB + (wn * TN + j) * 32 + li];
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -224,17 +238,26 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
     }
 }
 
-template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
-inline void launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
+// Returns the number of k splits actually used (every split is non-empty).
+template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
+inline int launch_bk(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
-  if (M <= 0 || N <= 0) return;
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
   if (splits < 1) splits = 1;
   int64_t k_chunk = (K + splits - 1) / splits;
-  k_chunk = (k_chunk + P::BK - 1) / P::BK * P::BK;
-  if (k_chunk < P::BK) k_chunk = P::BK;
+  k_chunk = (k_chunk + BK - 1) / BK * BK;
+  splits = (int)((K + k_chunk - 1) / k_chunk);
   const int64_t tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
   dim3 grid((unsigned)(((tiles_m * splits + 7) / 8) * 8 * tiles_n), 1, 1);
-  hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk, splits);
+  hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, BK, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk,
+                     splits);
+  return splits;
+}
+
+// Stage depth by reduction length: short reductions (the radial basis) use a shallow stage.
+template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
+inline int launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
+  return launch_bk<P, TM, TN, WM, WN, KC, P::BK_BIG>(st, a, b, e, M, N, K, splits);
 }
 
 }  // namespace gemm

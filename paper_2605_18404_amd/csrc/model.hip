@@ -29,6 +29,7 @@ struct InvWs {
   float* jphi = nullptr;   // [E][2][K]
   float2* env = nullptr;   // [E] (f_c, f_c')
   std::vector<float*> U[2];   // hidden pre-activations, jets [E][2][H]; U[0] level 1, U[1] level 2 (depth 3)
+  std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [E][2][H]
   std::vector<float*> Om;     // [E][2][C]
   std::vector<float*> Y[2];   // [E][H]  BF -> BE
   float* X = nullptr;         // [E][max(C,H)] scratch
@@ -235,16 +236,18 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, EpiStore{w->U[0][l], H, 2 * E});
+        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[0][l], w->SJ[0][l], H, 2 * E));
       }
       const float* ulast = w->U[0][l];
+      const __bf16* sjlast = w->SJ[0][l];
       if (d == 3) {
-        gemm_nt<P>(st, LdJetSilu{w->U[0][l], H}, th + lo.W[1], 2 * E, H, H, EpiStore{w->U[1][l], H, 2 * E});
+        gemm_nt<P>(st, Act<P>::jet(w->U[0][l], w->SJ[0][l], H), th + lo.W[1], 2 * E, H, H, Act<P>::store(w->U[1][l], w->SJ[1][l], H, 2 * E));
         ulast = w->U[1][l];
+        sjlast = w->SJ[1][l];
       }
       {
         KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-        gemm_nt<P>(st, LdJetSilu{ulast, H}, th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
+        gemm_nt<P>(st, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
       }
     }
     {
@@ -331,14 +334,14 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluOdd{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, Act<P>::odd(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
         gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiYZ{w->Y[d - 2][l], w->X2, ulast, H, E});
       }
       if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluOdd{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
         gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiYZ{w->Y[0][l], w->X, w->U[0][l], H, E});
         MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
@@ -402,14 +405,14 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, LdJetSiluEven{ulast, H}, E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, Act<P>::even(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
         gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiLamU{w->X2, ulast, w->Y[d - 2][l], H, E});
       }
       if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdJetSiluEven{w->U[0][l], H}, E, H, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
         gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiLamU{w->X, w->U[0][l], w->Y[0][l], H, E});
         MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
@@ -456,6 +459,9 @@ int inv_alloc(mlip_ctx* ctx) {
   for (int l = 0; l < L; ++l) {
     w->U[0].push_back(A(2 * E * H));
     w->U[1].push_back(d == 3 ? A(2 * E * H) : nullptr);
+    const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
+    w->SJ[0].push_back(b16 ? (__bf16*)A(E * H) : nullptr);  // 2 E H bf16 = E H floats
+    w->SJ[1].push_back(b16 && d == 3 ? (__bf16*)A(E * H) : nullptr);
     w->Om.push_back(A(2 * E * C));
     w->Y[0].push_back(A(E * H));
     w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);

@@ -174,6 +174,36 @@ __global__ void k_loss_cotangents(const float* __restrict__ E, const float* __re
   if (idx < n3) v[idx] = -2.f * fw * (F[idx] - Fref[idx]) / (float)n3;
 }
 
+// How the activated jets (silu(u), silu'(u) u') of a hidden level reach the GEMMs that consume
+// them.  fp32: recomputed from the stored pre-activations while a tile is staged (saves HBM
+// traffic; the fp32 matrix cores leave the ALUs idle anyway).  bf16: the producing GEMM's
+// epilogue stores them once, already rounded, and the consumers read bf16 (the bf16 matrix cores
+// are too fast to hide per-element transcendental work in the operand path).
+template <typename P>
+struct Act;
+template <>
+struct Act<gemm::Fp32> {
+  typedef LdJetSilu Jet;
+  typedef LdJetSiluEven Even;
+  typedef LdJetSiluOdd Odd;
+  typedef EpiStore Store;
+  static Jet jet(const float* u, const __bf16*, int H) { return Jet{u, H}; }
+  static Even even(const float* u, const __bf16*, int H) { return Even{u, H}; }
+  static Odd odd(const float* u, const __bf16*, int H) { return Odd{u, H}; }
+  static Store store(float* u, __bf16*, int H, int64_t M) { return Store{u, H, M}; }
+};
+template <>
+struct Act<gemm::Bf16> {
+  typedef LdBf16 Jet;
+  typedef LdBf16 Even;
+  typedef LdBf16 Odd;
+  typedef EpiStoreJetAct Store;
+  static Jet jet(const float*, const __bf16* sj, int H) { return Jet{sj, H}; }
+  static Even even(const float*, const __bf16* sj, int H) { return Even{sj, 2 * (int64_t)H}; }
+  static Odd odd(const float*, const __bf16* sj, int H) { return Odd{sj + H, 2 * (int64_t)H}; }
+  static Store store(float* u, __bf16* sj, int H, int64_t M) { return Store{u, sj, H, M}; }
+};
+
 inline unsigned nblk(int64_t n, int b = 256) { return (unsigned)((n + b - 1) / b); }
 inline int atom_chunks(int64_t N) { return (int)std::max<int64_t>(1, std::min<int64_t>(128, N / 32)); }
 
@@ -213,11 +243,11 @@ int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, i
   while ((int64_t)splits * Nout * Kout > w->cap && splits > 1) --splits;
   EpiPartial epi{w->buf, Kout, Nout};
   if (narrow)
-    gemm::launch<P, 1, 1, 4, 1, false>(st, a, b, epi, Nout, Kout, R, splits);
+    splits = gemm::launch<P, 1, 1, 4, 1, false>(st, a, b, epi, Nout, Kout, R, splits);
   else if (Nout > 64)
-    gemm::launch<P, 2, 2, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
+    splits = gemm::launch<P, 2, 2, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
   else
-    gemm::launch<P, 1, 1, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
+    splits = gemm::launch<P, 1, 1, 2, 2, false>(st, a, b, epi, Nout, Kout, R, splits);
   int64_t n = (int64_t)Nout * Kout;
   hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n, 64)), dim3(256), 0, st, w->buf, splits, n, grad);
   return MLIP_OK;
