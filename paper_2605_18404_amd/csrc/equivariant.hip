@@ -104,7 +104,7 @@ __device__ __forceinline__ RowChan row_chan(int N, int C) {
   int rl = threadIdx.x / C;
   RowChan t;
   t.c = threadIdx.x % C;
-  t.row = blockIdx.x * rpb + rl;
+  t.row = xcd_block() * rpb + rl;
   t.active = (rl < rpb) && (t.row < N);
   return t;
 }
@@ -338,7 +338,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_tp_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+      hipLaunchKernelGGL(k_tp_fe, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
                          w->h[l], (int)N, C, w->a[l]);
     }
     for (int k = 0; k < 3; ++k) {
@@ -374,7 +374,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
       gemm_nt<P>(st, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    hipLaunchKernelGGL(k_tp_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+    hipLaunchKernelGGL(k_tp_ff, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
                        w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
@@ -397,7 +397,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_tp_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL(k_tp_bf, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
     }
     for (int k = 0; k < 3; ++k) {
@@ -459,7 +459,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_tp_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL(k_tp_be, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
     }
     if (E > 0) {

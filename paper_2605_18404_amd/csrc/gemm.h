@@ -31,11 +31,13 @@ struct Fp32 {
   typedef float lds_t;
   static constexpr bool IS_BF16 = false;
   static constexpr int BK_BIG = 16;
+  static constexpr int WAVES = 3;  // workgroups (= waves per SIMD) the register budget is set for
 };
 struct Bf16 {
   typedef __bf16 lds_t;
   static constexpr bool IS_BF16 = true;
   static constexpr int BK_BIG = 32;
+  static constexpr int WAVES = 3;
 };
 
 template <typename P, int ROWS, int BK, bool KC>
@@ -122,7 +124,7 @@ struct Stager {
 // the 8 XCDs (each with its own L2): a group is one (row tile, k split), its column tiles go to
 // the same XCD one after the other, so the A rows are fetched into one L2 only.
 template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, P::WAVES)
 k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, int splits) {
   static_assert(WM * WN == 4, "four waves per workgroup");
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;

@@ -61,7 +61,7 @@ __device__ __forceinline__ RowThread row_thread(int N, int CQ) {
   int rl = threadIdx.x / CQ;
   RowThread t;
   t.cq = threadIdx.x % CQ;
-  t.row = blockIdx.x * rpb + rl;
+  t.row = xcd_block() * rpb + rl;
   t.active = (rl < rpb) && (t.row < N);
   return t;
 }
@@ -252,7 +252,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_msg_fe, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
+      hipLaunchKernelGGL(k_msg_fe, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
                          (int)N, C, w->a[l]);
     }
     gemm_nt<P>(st, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
@@ -291,7 +291,7 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
     gemm_nt<P>(st, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
-      hipLaunchKernelGGL(k_msg_ff, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
+      hipLaunchKernelGGL(k_msg_ff, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
                          w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
     }
   }
@@ -321,7 +321,7 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_msg_bf, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL(k_msg_bf, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
     }
     gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
@@ -398,7 +398,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_msg_be, dim3(nblk(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL(k_msg_be, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
     }
     if (E > 0) {

@@ -204,6 +204,15 @@ struct Act<gemm::Bf16> {
   static Store store(float* u, __bf16* sj, int H, int64_t M) { return Store{u, sj, H, M}; }
 };
 
+// Row-parallel gather kernels: workgroups are dealt round-robin to the 8 XCDs, so XCD x takes
+// the x-th contiguous eighth of the row blocks -- consecutive receivers (atoms of one structure,
+// spatial neighbours) share senders, and their node-table rows then stay in one XCD's L2.
+__device__ __forceinline__ int xcd_block() {
+  const int per_xcd = gridDim.x >> 3;  // the grid is a multiple of 8
+  return (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+}
+inline unsigned nblk8(int64_t n, int b) { return (unsigned)(((n + b - 1) / b + 7) / 8 * 8); }
+
 inline unsigned nblk(int64_t n, int b = 256) { return (unsigned)((n + b - 1) / b); }
 inline int atom_chunks(int64_t N) { return (int)std::max<int64_t>(1, std::min<int64_t>(128, N / 32)); }
 
