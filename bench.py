@@ -214,6 +214,13 @@ def main():
         "phase_ms": {"graph": ph[0], "FE": ph[1], "FF": ph[2], "BF": ph[3], "BE": ph[4]},
         "roofline": roof,
     }
+    if w.kind == synth.KIND_STAGE:
+        # the stage's measured phase times in the paper's closed-form bubble model (Sec. 4.2)
+        from paper_2605_18404_amd import wavek_model
+        fe, ff, bf, be = ph[1], ph[2], ph[3], ph[4]
+        line["wavek_bubble_model_ms"] = {
+            "naive_per_microbatch": wavek_model.naive_bubble(fe, ff, bf, be),
+            **{f"P{P}_Nmb32_k{k}": wavek_model.wavek_bubbles(fe, ff, bf, be, P, 32, k) for P in (4, 8) for k in (P, 2 * P, 32)}}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(line))

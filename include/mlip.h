@@ -161,6 +161,21 @@ int mlip_kernel_timer_select(mlip_ctx* ctx, int kernel_id);
 int mlip_copy_probe(mlip_ctx* ctx, float* dst, const float* src, int64_t n_floats);
 int mlip_kernel_timer_read(mlip_ctx* ctx, int64_t* launches_host, float* total_ms_host);
 
+/* Graph-aware rescheduling (Appendix A.2, Algorithm 1): HOST routine, host pointers only.
+ * Repacks the n_graphs graphs of a global batch (sizes_host[g] = atom count) into n_mb
+ * micro-batches: graphs sorted by size descending (ties: lower index first), each placed into
+ * the micro-batch of currently smallest total size (ties: lowest micro-batch index); every
+ * micro-batch is then shuffled (Fisher-Yates from the last position down, draw t of micro-batch
+ * j = splitmix64-finaliser(key(seed, stream j) + (t+1) * 0x9E3779B97F4A7C15) mod (t+1), key =
+ * finaliser(seed xor j * 0x9E3779B97F4A7C15)) and tagged MLIP_GARS_COMM_FREE iff its largest
+ * graph is at most (total size) / d_gp, else MLIP_GARS_DIST.
+ * Outputs: mb_ptr_host[n_mb+1], order_host[n_graphs] (graph indices, grouped by micro-batch in
+ * shuffled order), type_host[n_mb].  Returns MLIP_E_INVALID on null pointers, negative sizes,
+ * n_mb < 1 or d_gp < 1. */
+enum { MLIP_GARS_COMM_FREE = 0, MLIP_GARS_DIST = 1 };
+int mlip_gars_pack(const int32_t* sizes_host, int64_t n_graphs, int32_t n_mb, int32_t d_gp, uint64_t seed,
+                   int32_t* mb_ptr_host, int32_t* order_host, int32_t* type_host);
+
 #ifdef __cplusplus
 }
 #endif

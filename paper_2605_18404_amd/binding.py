@@ -63,6 +63,7 @@ def load():
     lib.mlip_kernel_timer_select.argtypes = [P, I32]
     lib.mlip_kernel_timer_read.argtypes = [P, C.POINTER(I64), C.POINTER(C.c_float)]
     lib.mlip_copy_probe.argtypes = [P, P, P, I64]
+    lib.mlip_gars_pack.argtypes = [P, I64, I32, I32, C.c_uint64, P, P, P]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
     lib.mlip_loss.argtypes = [P, P, P, P, P, P, P, P]
@@ -81,6 +82,23 @@ def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
     if dtype is not None and t.dtype != dtype:
         raise ValueError(f"expected {dtype}, got {t.dtype}")
     return t.data_ptr()
+
+
+def mlip_gars_pack(sizes, n_mb: int, d_gp: int, seed: int):
+    """Host routine (no GPU): sizes = int32 numpy array of atom counts.
+    Returns (mb_ptr [n_mb+1], order [M], type [n_mb]) as int32 numpy arrays."""
+    import numpy as np
+    lib = load()
+    sizes = np.ascontiguousarray(sizes, dtype=np.int32)
+    M = sizes.shape[0]
+    mb_ptr = np.zeros(n_mb + 1, np.int32)
+    order = np.zeros(max(M, 1), np.int32)
+    typ = np.zeros(n_mb, np.int32)
+    s = lib.mlip_gars_pack(sizes.ctypes.data, M, n_mb, d_gp, C.c_uint64(seed), mb_ptr.ctypes.data, order.ctypes.data,
+                           typ.ctypes.data)
+    if s != 0:
+        raise MlipError(s, "mlip_gars_pack: invalid argument")
+    return mb_ptr, order[:M], typ
 
 
 class Mlip:

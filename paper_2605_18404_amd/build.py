@@ -9,13 +9,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmlip.so")
-SOURCES = ["api.hip", "graph.hip", "model.hip", "equivariant.hip"]
+SOURCES = ["api.hip", "graph.hip", "model.hip", "equivariant.hip", "gars.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+    obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

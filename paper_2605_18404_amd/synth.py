@@ -267,3 +267,23 @@ def make_inputs(w: Workload) -> Inputs:
         stage["v"] = normal(w.seed, STREAM_V, 0, N * 3).astype(np.float32).reshape(N, 3)
         stage["lam_out"] = normal(w.seed, STREAM_LAM_OUT, 0, N * C).astype(np.float32).reshape(N, C)
     return Inputs(w, pos, species, struct_ptr, cell, draw_params(w), E_ref, F_ref, stage)
+
+
+# ----------------------------------------------------------------------------- graph sizes
+
+def draw_graph_sizes(seed: int, total_atoms: int = 12800, median: float = 53.0, mean: float = 85.0,
+                     max_size: int = 905) -> np.ndarray:
+    """Atom counts of the graphs of one global batch: log-normal with the median and mean of the
+    paper's mixed dataset (Appendix A.1, Table 3: mean 85, P50 53, max 905), truncated to
+    [1, max_size], drawn until the batch holds total_atoms atoms (12,800 in Sec. 5.1)."""
+    sigma = np.sqrt(2.0 * np.log(mean / median))
+    out, tot, ctr = [], 0, 0
+    while tot < total_atoms:
+        z = normal(seed, 11, ctr, 64)
+        ctr += 64
+        for s in np.clip(np.rint(median * np.exp(sigma * z)), 1, max_size).astype(np.int64):
+            out.append(int(s))
+            tot += int(s)
+            if tot >= total_atoms:
+                break
+    return np.array(out, dtype=np.int32)

@@ -144,6 +144,32 @@ def test_train_step_parity(name):
     m.close()
 
 
+def test_train_step_on_a_gars_micro_batch():
+    """A ragged micro-batch as Algorithm 1 (Appendix A.2) packs it from the paper's graph-size mix:
+    structures of very different sizes in one call."""
+    from paper_2605_18404_amd.binding import mlip_gars_pack
+    sizes = synth.draw_graph_sizes(7)
+    mb_ptr, order, _ = mlip_gars_pack(sizes, 32, 2, 7)
+    graphs = order[mb_ptr[5]:mb_ptr[6]]
+    ns = [max(2, int(sizes[g])) for g in graphs]
+    w = synth.shrink(synth.WORKLOADS[1], channels=32, edge_hidden=32, n_layers=2, n_structs=len(ns), atoms_per_struct=1)
+    boxes = [max(6.2, (n / 0.08) ** (1 / 3)) for n in ns]
+    pos = np.concatenate([synth.make_structure(w.seed, s, n, L, w.cutoff) for s, (n, L) in enumerate(zip(ns, boxes))])
+    N = pos.shape[0]
+    sp = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+    cell = np.stack([np.eye(3, dtype=np.float32) * np.float32(L) for L in boxes])
+    inp = synth.Inputs(w, pos, synth.draw_species(w.seed, N, w.n_species, w.species_dist), sp, cell, synth.draw_params(w),
+                       synth.normal(w.seed, 4, 0, len(ns)).astype(np.float32),
+                       (0.1 * synth.normal(w.seed, 5, 0, 3 * N)).astype(np.float32).reshape(N, 3))
+    ref = oracle_train_step(w, inp)
+    m = Mlip.for_workload(w, max_atoms=N, max_structs=len(ns), max_edges=int(N * 120))
+    d = DevInputs(inp)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    _check_step(w, inp, out, ref, TOL_FP32)
+    m.close()
+
+
 @pytest.mark.parametrize("which", ["invariant", "equivariant"])
 def test_phase_calls_and_gradient_split(which):
     """FE, FF, loss, BF, BE one by one; BF's and BE's shares of the gradient against the oracle's split (Eq. 2)."""
