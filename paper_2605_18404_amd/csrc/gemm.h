@@ -96,9 +96,7 @@ struct Stager {
       const int idx = t + it * 256;
       if (NVT % 256 != 0 && idx >= NVT) continue;
       float4 x = ld.finish(v[it]);
-      const float keep = (ok >> it) & 1u ? 1.f : 0.f;
       if (!((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
-      (void)keep;
       const int a = idx / Q, b = idx % Q;  // KC: (row, kq); KS: (k, rq)
       if constexpr (KC && TL::K_MAJOR) {  // fp32: transpose into [k][row]
         s[(4 * b + 0) * LD + a] = (T)x.x;
