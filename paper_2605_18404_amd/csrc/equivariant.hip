@@ -195,12 +195,13 @@ __global__ void __launch_bounds__(256) k_tp_ff(const int32_t* __restrict__ row_p
   }
 }
 
+template <typename TX>
 __global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
                                                const float* __restrict__ Rho, const float* __restrict__ h,
                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                const float* __restrict__ v, int N, int C, float* __restrict__ ad,
-                                               float* __restrict__ X) {
+                                               TX* __restrict__ X) {
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -231,21 +232,22 @@ __global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_p
     float tp[NPATH];
     gaunt::tp_paths(xj, Y, mi, tp);
     const float s = rd * env[e].x;
-    float* xrow = X + (int64_t)e * NPATH * C + t.c;
+    TX* xrow = X + (int64_t)e * NPATH * C + t.c;
 #pragma unroll
-    for (int p = 0; p < NPATH; ++p) xrow[p * C] = s * tp[p];
+    for (int p = 0; p < NPATH; ++p) xrow[p * C] = (TX)(s * tp[p]);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
 }
 
+template <typename TX>
 __global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
                                                const float* __restrict__ Rho, const float* __restrict__ h,
                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                const float* __restrict__ lam_a, const float* __restrict__ v,
                                                const float* __restrict__ lam_h_next, int N, int C,
-                                               float* __restrict__ lam_h, float* __restrict__ X) {
+                                               float* __restrict__ lam_h, TX* __restrict__ X) {
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -285,9 +287,9 @@ __global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_p
     gaunt::tp_paths(xj, Y, mi, t4);
     const float2 cc = env[e];
     const float s = cc.y * rd;
-    float* xrow = X + (int64_t)e * NPATH * C + t.c;
+    TX* xrow = X + (int64_t)e * NPATH * C + t.c;
 #pragma unroll
-    for (int p = 0; p < NPATH; ++p) xrow[p * C] = cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p];
+    for (int p = 0; p < NPATH; ++p) xrow[p * C] = (TX)(cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p]);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
@@ -391,14 +393,17 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
+  typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
+  TX* X = reinterpret_cast<TX*>(w->X);
+  TX* X2 = reinterpret_cast<TX*>(w->X2);
   hipLaunchKernelGGL(k_fill, dim3(nblk(9 * NC)), dim3(256), 0, st, w->hd[0], 0.f, 9 * NC);
   const int rpb = 256 / C;
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_tp_bf, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+      hipLaunchKernelGGL(k_tp_bf<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
@@ -408,13 +413,13 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(st, LdPlain{w->X, PC}, tT + lo.W[1], E, H, PC, EpiYZ{w->Y1[l], w->X2, w->U[l], H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, PC), tT + lo.W[1], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
       }
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
   }
   gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
@@ -437,6 +442,9 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
+  typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
+  TX* X = reinterpret_cast<TX*>(w->X);
+  TX* X2 = reinterpret_cast<TX*>(w->X2);
   int cur = 0;
   hipLaunchKernelGGL(k_lam_y, dim3(nblk(NC)), dim3(256), 0, st, w->y, w->yd, th + ctx->off_wo, w->Ebar, ctx->d_atom_struct, N, C, w->lam_y);
   {
@@ -459,19 +467,19 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_tp_be, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+      hipLaunchKernelGGL(k_tp_be<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, PC}, Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(st, LdPlain{w->X, PC}, tT + lo.W[1], E, H, PC, EpiLamU{w->X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, PC), tT + lo.W[1], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
       }
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
     cur ^= 1;
   }

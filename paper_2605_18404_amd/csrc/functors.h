@@ -35,6 +35,11 @@ __device__ __forceinline__ float jet1(float a, float b, bool odd) {
 }
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st4(__bf16* p, float4 v) {
+  bf16x4_t b = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+  *reinterpret_cast<bf16x4_t*>(p) = b;
+}
 __device__ __forceinline__ float4 mul4(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
 __device__ __forceinline__ float4 silu4(float4 a) { return make_float4(silu(a.x), silu(a.y), silu(a.z), silu(a.w)); }
 __device__ __forceinline__ float4 dsilu4(float4 a) { return make_float4(dsilu(a.x), dsilu(a.y), dsilu(a.z), dsilu(a.w)); }
@@ -188,9 +193,10 @@ struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
       }
   }
 };
-struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld])
+template <typename TZ>
+struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld]); Z only ever feeds matrix products
   float* Y;
-  float* Z;
+  TZ* Z;
   const float* u;
   int64_t ld, M;
   __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
@@ -199,12 +205,13 @@ struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld])
       if (r0 + j < M) {
         int64_t o = (r0 + j) * ld + col;
         Y[o] = v[j];
-        Z[o] = dsilu(u[2 * (r0 + j) * ld + col]) * v[j];
+        Z[o] = (TZ)(dsilu(u[2 * (r0 + j) * ld + col]) * v[j]);
       }
   }
 };
-struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y
-  float* out;
+template <typename TZ>
+struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y; out only ever feeds matrix products
+  TZ* out;
   const float* u;
   const float* Y;
   int64_t ld, M;
@@ -216,7 +223,7 @@ struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y
         const float* pu = u + 2 * (r0 + j) * ld + col;
         float d1, d2;
         dsilu12(pu[0], d1, d2);
-        out[o] = d1 * v[j] + d2 * pu[ld] * Y[o];
+        out[o] = (TZ)(d1 * v[j] + d2 * pu[ld] * Y[o]);
       }
   }
 };

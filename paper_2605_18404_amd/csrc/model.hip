@@ -134,12 +134,13 @@ __device__ __forceinline__ float rdot_of(const float4& ge, const float* __restri
   return ge.x * (v[3 * j] - v[3 * i]) + ge.y * (v[3 * j + 1] - v[3 * i + 1]) + ge.z * (v[3 * j + 2] - v[3 * i + 2]);
 }
 
+template <typename TX>
 __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const float* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                 const float* __restrict__ v, int N, int C, float* __restrict__ ad,
-                                                float* __restrict__ X) {
+                                                TX* __restrict__ X) {
   RowThread t = row_thread(N, C / 4);
   if (!t.active) return;
   const int c0 = 4 * t.cq;
@@ -158,18 +159,19 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
     fma4s(acc, rd, wp, hj);
     fma4(acc, w, hdj);
     float s = rd * c;
-    *reinterpret_cast<float4*>(X + (int64_t)e * C + c0) = make_float4(s * hj.x * mai.x, s * hj.y * mai.y, s * hj.z * mai.z, s * hj.w * mai.w);
+    st4(X + (int64_t)e * C + c0, make_float4(s * hj.x * mai.x, s * hj.y * mai.y, s * hj.z * mai.z, s * hj.w * mai.w));
   }
   *reinterpret_cast<float4*>(ad + ro) = acc;
 }
 
+template <typename TX>
 __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const float* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                 const float* __restrict__ lam_a, const float* __restrict__ v,
                                                 const float* __restrict__ lam_h_next, int N, int C,
-                                                float* __restrict__ lam_h, float* __restrict__ X) {
+                                                float* __restrict__ lam_h, TX* __restrict__ X) {
   RowThread t = row_thread(N, C / 4);
   if (!t.active) return;
   const int c0 = 4 * t.cq;
@@ -194,7 +196,7 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
     x.y = cc.x * (hj.y * lai.y + hdj.y * mai.y) + s * hj.y * mai.y;
     x.z = cc.x * (hj.z * lai.z + hdj.z * mai.z) + s * hj.z * mai.z;
     x.w = cc.x * (hj.w * lai.w + hdj.w * mai.w) + s * hj.w * mai.w;
-    *reinterpret_cast<float4*>(X + (int64_t)e * C + c0) = x;
+    st4(X + (int64_t)e * C + c0, x);
   }
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
 }
@@ -311,6 +313,9 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
+  typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
+  TX* X = reinterpret_cast<TX*>(w->X);
+  TX* X2 = reinterpret_cast<TX*>(w->X2);
   const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
   if (stage && hdot_in)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->hd[0], hdot_in, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
@@ -321,8 +326,8 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_msg_bf, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], w->X);
+      hipLaunchKernelGGL(k_msg_bf<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
     gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
     gemm_nt<P>(st, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
@@ -334,18 +339,18 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, Act<P>::odd(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::odd(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiYZ{w->Y[d - 2][l], w->X2, ulast, H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiYZ<TX>{w->Y[d - 2][l], X2, ulast, H, E});
       }
       if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiYZ{w->Y[0][l], w->X, w->U[0][l], H, E});
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        gemm_nt<P>(st, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
       }
     }
   }
@@ -373,6 +378,9 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
+  typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
+  TX* X = reinterpret_cast<TX*>(w->X);
+  TX* X2 = reinterpret_cast<TX*>(w->X2);
   const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
   int cur = 0;
   if (stage) {
@@ -398,25 +406,25 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_msg_be, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, w->X);
+      hipLaunchKernelGGL(k_msg_be<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
     if (E > 0) {
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, C}, Act<P>::even(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::even(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(st, LdPlain{w->X, C}, tT + lo.W[d - 1], E, H, C, EpiLamU{w->X2, ulast, w->Y[d - 2][l], H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[d - 2][l], H, E});
       }
       if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(st, LdPlain{w->X2, H}, tT + lo.W[1], E, H, H, EpiLamU{w->X, w->U[0][l], w->Y[0][l], H, E});
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        gemm_nt<P>(st, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
-        MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->X2, H}, LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
       }
     }
     cur ^= 1;

@@ -187,6 +187,9 @@ struct Act<gemm::Fp32> {
   typedef LdJetSiluEven Even;
   typedef LdJetSiluOdd Odd;
   typedef EpiStore Store;
+  typedef float xop_t;  // element type of the edge tensors that only feed matrix products
+  typedef LdPlain XLd;
+  static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
   static Jet jet(const float* u, const __bf16*, int H) { return Jet{u, H}; }
   static Even even(const float* u, const __bf16*, int H) { return Even{u, H}; }
   static Odd odd(const float* u, const __bf16*, int H) { return Odd{u, H}; }
@@ -198,6 +201,9 @@ struct Act<gemm::Bf16> {
   typedef LdBf16 Even;
   typedef LdBf16 Odd;
   typedef EpiStoreJetAct Store;
+  typedef __bf16 xop_t;  // rounded once by the producer: half the bytes, no conversion in the operand path
+  typedef LdBf16 XLd;
+  static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
   static Jet jet(const float*, const __bf16* sj, int H) { return Jet{sj, H}; }
   static Even even(const float*, const __bf16* sj, int H) { return Even{sj, 2 * (int64_t)H}; }
   static Odd odd(const float*, const __bf16* sj, int H) { return Odd{sj + H, 2 * (int64_t)H}; }
