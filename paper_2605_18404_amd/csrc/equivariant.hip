@@ -33,9 +33,12 @@ struct EqvWs {
   float2* env = nullptr;  // [E]
   std::vector<float*> U;    // [E][2][H]
   std::vector<__bf16*> SJ;  // bf16 GEMMs only: activated jets [E][2][H]
-  std::vector<float*> Rho;  // [E][2][11 C]
+  std::vector<float*> Rho;  // [E][2][C][12]: per channel the 11 path filters + one pad, operand precision (fp32 or bf16)
+  std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [12 C][H]
+  std::vector<float*> WpT;  // and their transpose [H][12 C]
+  float* gWp = nullptr;     // [12 C][H] weight gradient in the regrouped row order
   std::vector<float*> Y1;   // [E][H]  BF -> BE
-  float* X = nullptr;       // [E][11 C]
+  float* X = nullptr;       // [E][C][12], operand precision
   float* X2 = nullptr;      // [E][H]
   std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [9][N][C]
   float* lam_h[2] = {nullptr, nullptr};
@@ -90,9 +93,41 @@ __device__ __forceinline__ void load9(const float* __restrict__ t, int64_t NC, i
 #pragma unroll
   for (int m = 0; m < 9; ++m) x[m] = t[m * NC + off];
 }
-__device__ __forceinline__ void load_rho(const float* __restrict__ row, int C, int c, float (&rho)[NPATH]) {
-#pragma unroll
-  for (int p = 0; p < NPATH; ++p) rho[p] = row[p * C + c];
+// The filter jets and their adjoints are stored per edge as [C][NPP]: the 11 path values of one
+// channel are contiguous (plus one zero pad), so a thread moves them with three wide accesses
+// instead of eleven narrow ones.
+constexpr int NPP = 12;
+__device__ __forceinline__ void load_rho(const float* __restrict__ row, int c, float (&rho)[NPATH]) {
+  const float4* q = reinterpret_cast<const float4*>(row + c * NPP);
+  const float4 a = q[0], b = q[1], d = q[2];
+  rho[0] = a.x; rho[1] = a.y; rho[2] = a.z; rho[3] = a.w;
+  rho[4] = b.x; rho[5] = b.y; rho[6] = b.z; rho[7] = b.w;
+  rho[8] = d.x; rho[9] = d.y; rho[10] = d.z;
+}
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ void load_rho(const __bf16* __restrict__ row, int c, float (&rho)[NPATH]) {
+  const uint2* q = reinterpret_cast<const uint2*>(row + c * NPP);
+  const uint2 a = q[0], b = q[1], d = q[2];
+  rho[0] = bf_lo(a.x); rho[1] = bf_hi(a.x); rho[2] = bf_lo(a.y); rho[3] = bf_hi(a.y);
+  rho[4] = bf_lo(b.x); rho[5] = bf_hi(b.x); rho[6] = bf_lo(b.y); rho[7] = bf_hi(b.y);
+  rho[8] = bf_lo(d.x); rho[9] = bf_hi(d.x); rho[10] = bf_lo(d.y);
+}
+__device__ __forceinline__ void store_paths(float* __restrict__ row, int c, const float (&x)[NPATH]) {
+  float4* q = reinterpret_cast<float4*>(row + c * NPP);
+  q[0] = make_float4(x[0], x[1], x[2], x[3]);
+  q[1] = make_float4(x[4], x[5], x[6], x[7]);
+  q[2] = make_float4(x[8], x[9], x[10], 0.f);
+}
+__device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
+  __bf16 a = (__bf16)lo, b = (__bf16)hi;
+  return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+}
+__device__ __forceinline__ void store_paths(__bf16* __restrict__ row, int c, const float (&x)[NPATH]) {
+  uint2* q = reinterpret_cast<uint2*>(row + c * NPP);
+  q[0] = make_uint2(bf_pack(x[0], x[1]), bf_pack(x[2], x[3]));
+  q[1] = make_uint2(bf_pack(x[4], x[5]), bf_pack(x[6], x[7]));
+  q[2] = make_uint2(bf_pack(x[8], x[9]), bf_pack(x[10], 0.f));
 }
 
 struct RowChan {
@@ -110,8 +145,9 @@ __device__ __forceinline__ RowChan row_chan(int N, int C) {
 }
 
 // ------------------------------------------------------------------------------ edge kernels
+template <typename TF>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const float* __restrict__ Rho,
+                                               const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
   RowChan t = row_chan(N, C);
   if (!t.active) return;
@@ -124,15 +160,16 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
     float Y[9], x[9], rho[NPATH];
     sph_harm(g.x, g.y, g.z, Y);
     load9(h, NC, (int64_t)j * C + t.c, x);
-    load_rho(Rho + (int64_t)(2 * e) * NPATH * C, C, t.c, rho);
+    load_rho(Rho + (int64_t)(2 * e) * NPP * C, t.c, rho);
     gaunt::tp_fwd(rho, x, Y, acc);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
 }
 
-__global__ void __launch_bounds__(256) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const float* __restrict__ Rho,
+template <typename TF>
+__global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                const float* __restrict__ h, const float* __restrict__ mu_a,
                                                const float* __restrict__ mu_h_next, int N, int C,
                                                float* __restrict__ mu_h, float* __restrict__ Facc) {
@@ -156,9 +193,9 @@ __global__ void __launch_bounds__(256) k_tp_ff(const int32_t* __restrict__ row_p
       const int64_t jo = (int64_t)j * C + t.c;
       load9(h, NC, jo, xj);
       load9(mu_a, NC, jo, mj);
-      const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
-      load_rho(rrow, C, t.c, rho);
-      load_rho(rrow + NPATH * C, C, t.c, rhop);
+      const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+      load_rho(rrow, t.c, rho);
+      load_rho(rrow + NPP * C, t.c, rhop);
       gaunt::tp_adj_x(rho, PY, mj, acc);
       float t1[NPATH], t2[NPATH];
       gaunt::tp_paths(xj, Y, mi, t1);
@@ -195,10 +232,10 @@ __global__ void __launch_bounds__(256) k_tp_ff(const int32_t* __restrict__ row_p
   }
 }
 
-template <typename TX>
-__global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+template <typename TX, typename TF>
+__global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
-                                               const float* __restrict__ Rho, const float* __restrict__ h,
+                                               const TF* __restrict__ Rho, const float* __restrict__ h,
                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                const float* __restrict__ v, int N, int C, float* __restrict__ ad,
                                                TX* __restrict__ X) {
@@ -221,9 +258,9 @@ __global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_p
     const int64_t jo = (int64_t)j * C + t.c;
     load9(h, NC, jo, xj);
     load9(hd, NC, jo, xdj);
-    const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
-    load_rho(rrow, C, t.c, rho);
-    load_rho(rrow + NPATH * C, C, t.c, rr);
+    const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+    load_rho(rrow, t.c, rho);
+    load_rho(rrow + NPP * C, t.c, rr);
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
     gaunt::tp_fwd(rr, xj, Y, acc);
@@ -232,18 +269,18 @@ __global__ void __launch_bounds__(256) k_tp_bf(const int32_t* __restrict__ row_p
     float tp[NPATH];
     gaunt::tp_paths(xj, Y, mi, tp);
     const float s = rd * env[e].x;
-    TX* xrow = X + (int64_t)e * NPATH * C + t.c;
 #pragma unroll
-    for (int p = 0; p < NPATH; ++p) xrow[p * C] = (TX)(s * tp[p]);
+    for (int p = 0; p < NPATH; ++p) tp[p] *= s;
+    store_paths(X + (int64_t)e * NPP * C, t.c, tp);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
 }
 
-template <typename TX>
-__global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+template <typename TX, typename TF>
+__global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
-                                               const float* __restrict__ Rho, const float* __restrict__ h,
+                                               const TF* __restrict__ Rho, const float* __restrict__ h,
                                                const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                const float* __restrict__ lam_a, const float* __restrict__ v,
                                                const float* __restrict__ lam_h_next, int N, int C,
@@ -272,9 +309,9 @@ __global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_p
     load9(hd, NC, jo, xdj);
     load9(lam_a, NC, jo, lj);
     load9(mu_a, NC, jo, mj);
-    const float* rrow = Rho + (int64_t)(2 * e) * NPATH * C;
-    load_rho(rrow, C, t.c, rho);
-    load_rho(rrow + NPATH * C, C, t.c, rr);
+    const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+    load_rho(rrow, t.c, rho);
+    load_rho(rrow + NPP * C, t.c, rr);
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
     gaunt::tp_adj_x(rho, PY, lj, acc);
@@ -287,12 +324,30 @@ __global__ void __launch_bounds__(256) k_tp_be(const int32_t* __restrict__ row_p
     gaunt::tp_paths(xj, Y, mi, t4);
     const float2 cc = env[e];
     const float s = cc.y * rd;
-    TX* xrow = X + (int64_t)e * NPATH * C + t.c;
 #pragma unroll
-    for (int p = 0; p < NPATH; ++p) xrow[p * C] = (TX)(cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p]);
+    for (int p = 0; p < NPATH; ++p) t1[p] = cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p];
+    store_paths(X + (int64_t)e * NPP * C, t.c, t1);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
+}
+
+// Filter weights W [11 C][H] (row p C + c) regrouped to the stored order of the filter jets:
+// Wp [(c 12 + p)][H], zero rows for the pad, and the transpose WpT [H][12 C].
+__global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, float* __restrict__ Wp, float* __restrict__ WpT) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)NPP * C * H) return;
+  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
+  const float val = p < NPATH ? W[((int64_t)p * C + c) * H + hh] : 0.f;
+  Wp[idx] = val;
+  WpT[(int64_t)hh * NPP * C + r] = val;
+}
+// grad[(p C + c)][H] += g[(c 12 + p)][H]
+__global__ void k_regroup_add(const float* __restrict__ g, int C, int H, float* __restrict__ grad) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)NPP * C * H) return;
+  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
+  if (p < NPATH) grad[((int64_t)p * C + c) * H + hh] += g[idx];
 }
 
 // h0[m=0] = emb[species], other components zero
@@ -312,14 +367,15 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
-  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   auto tr = [&](int64_t off, int rows, int cols) {
     hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
   };
   for (int l = 0; l < L; ++l) {
-    tr(ctx->lay[l].W[1], PC, H);
+    hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, w->Wp[l], w->WpT[l]);
     for (int k = 0; k < 3; ++k) tr(ctx->lay[l].Wl[k], C, C);
   }
   tr(ctx->off_U, C, C);
@@ -336,11 +392,11 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
         gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-      gemm_nt<P>(st, Act<P>::jet(w->U[l], w->SJ[l], H), th + lo.W[1], 2 * E, PC, H, EpiOmega{w->Rho[l], w->env, PC, 2 * E});
+      gemm_nt<P>(st, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PC, 2 * E});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_tp_fe, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+      hipLaunchKernelGGL(k_tp_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                          w->h[l], (int)N, C, w->a[l]);
     }
     for (int k = 0; k < 3; ++k) {
@@ -360,6 +416,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, NC = N * cf.channels;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
@@ -376,7 +433,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
       gemm_nt<P>(st, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    hipLaunchKernelGGL(k_tp_ff, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Rho[l],
+    hipLaunchKernelGGL(k_tp_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                        w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
@@ -389,8 +446,9 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
-  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
   typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
@@ -402,8 +460,8 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_tp_bf<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
+      hipLaunchKernelGGL((k_tp_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
@@ -413,11 +471,13 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
+        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, PC), tT + lo.W[1], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -438,8 +498,9 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
-  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
   typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
@@ -467,17 +528,19 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_tp_be<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Rho[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
+      hipLaunchKernelGGL((k_tp_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, grad + lo.W[1])));
+        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, PC), tT + lo.W[1], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(st, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -498,7 +561,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
 int eqv_alloc(mlip_ctx* ctx) {
   const mlip_config& cf = ctx->cfg;
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
-  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPATH * C;
+  const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
   EqvWs* w = new EqvWs();
   ctx->model_ws = w;
@@ -511,13 +574,19 @@ int eqv_alloc(mlip_ctx* ctx) {
   w->paramsT = A(ctx->n_params);
   w->jphi = A(2 * E * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
-  w->X = A(E * PC);
-  w->X2 = A(E * H);
+  const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
+  // tensors held in the operand precision: half the floats when that is bf16
+  auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
+  w->X = AH(E * PC);
+  w->gWp = A((int64_t)PC * H);
+  w->X2 = AH(E * H);
   const int64_t NC9 = 9 * N * C;
   for (int l = 0; l < L; ++l) {
     w->U.push_back(A(2 * E * H));
-    w->SJ.push_back(cf.gemm_dtype == MLIP_GEMM_BF16 ? (__bf16*)A(E * H) : nullptr);
-    w->Rho.push_back(A(2 * E * PC));
+    w->SJ.push_back(b16 ? (__bf16*)A(E * H) : nullptr);
+    w->Rho.push_back(AH(2 * E * PC));
+    w->Wp.push_back(A((int64_t)PC * H));
+    w->WpT.push_back(A((int64_t)PC * H));
     w->Y1.push_back(A(E * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
   }

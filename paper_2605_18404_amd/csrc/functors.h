@@ -35,6 +35,10 @@ __device__ __forceinline__ float jet1(float a, float b, bool odd) {
 }
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 ld4(const __bf16* p) {
+  bf16x4_t b = *reinterpret_cast<const bf16x4_t*>(p);
+  return make_float4((float)b[0], (float)b[1], (float)b[2], (float)b[3]);
+}
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ void st4(__bf16* p, float4 v) {
   bf16x4_t b = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
@@ -164,8 +168,9 @@ struct EpiAddStore {  // p = add + v
       if (r0 + j < M) p[(r0 + j) * ld + col] = add[(r0 + j) * ld + col] + v[j];
   }
 };
+template <typename TO>
 struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  env[e] = (c, c')
-  float* out;
+  TO* out;
   const float2* env;
   int64_t ld, M;  // M = 2E
   __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
@@ -173,8 +178,8 @@ struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  en
     for (int j = 0; j < 4; j += 2)
       if (r0 + j + 1 < M) {
         float2 c = env[(r0 + j) >> 1];
-        out[(r0 + j) * ld + col] = c.x * v[j];
-        out[(r0 + j + 1) * ld + col] = c.y * v[j] + c.x * v[j + 1];
+        out[(r0 + j) * ld + col] = (TO)(c.x * v[j]);
+        out[(r0 + j + 1) * ld + col] = (TO)(c.y * v[j] + c.x * v[j + 1]);
       }
   }
 };

@@ -30,9 +30,9 @@ struct InvWs {
   float2* env = nullptr;   // [E] (f_c, f_c')
   std::vector<float*> U[2];   // hidden pre-activations, jets [E][2][H]; U[0] level 1, U[1] level 2 (depth 3)
   std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [E][2][H]
-  std::vector<float*> Om;     // [E][2][C]
+  std::vector<float*> Om;     // [E][2][C], in the operand precision (fp32 or bf16)
   std::vector<float*> Y[2];   // [E][H]  BF -> BE
-  float* X = nullptr;         // [E][max(C,H)] scratch
+  float* X = nullptr;         // [E][max(C,H)] scratch, operand precision
   float* X2 = nullptr;
   std::vector<float*> h, a, q, mu_h, mu_a, mu_q, mu_t, hd, ad, qd;
   float* lam_h[2] = {nullptr, nullptr};
@@ -72,8 +72,9 @@ __device__ __forceinline__ void fma4s(float4& acc, float s, float4 a, float4 b) 
   acc.x += s * a.x * b.x; acc.y += s * a.y * b.y; acc.z += s * a.z * b.z; acc.w += s * a.w * b.w;
 }
 
+template <typename TF>
 __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                                const float* __restrict__ Om, const float* __restrict__ h, int N, int C,
+                                                const TF* __restrict__ Om, const float* __restrict__ h, int N, int C,
                                                 float* __restrict__ a) {
   RowThread t = row_thread(N, C / 4);
   if (!t.active) return;
@@ -88,8 +89,9 @@ __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_
   *reinterpret_cast<float4*>(a + (int64_t)t.row * C + c0) = acc;
 }
 
+template <typename TF>
 __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                                const float4* __restrict__ geo, const float* __restrict__ Om,
+                                                const float4* __restrict__ geo, const TF* __restrict__ Om,
                                                 const float* __restrict__ h, const float* __restrict__ mu_a,
                                                 const float* __restrict__ mu_h_next, int N, int C,
                                                 float* __restrict__ mu_h, float* __restrict__ Facc) {
@@ -134,10 +136,10 @@ __device__ __forceinline__ float rdot_of(const float4& ge, const float* __restri
   return ge.x * (v[3 * j] - v[3 * i]) + ge.y * (v[3 * j + 1] - v[3 * i + 1]) + ge.z * (v[3 * j + 2] - v[3 * i + 2]);
 }
 
-template <typename TX>
+template <typename TX, typename TF>
 __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
-                                                const float* __restrict__ Om, const float* __restrict__ h,
+                                                const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                 const float* __restrict__ v, int N, int C, float* __restrict__ ad,
                                                 TX* __restrict__ X) {
@@ -164,10 +166,10 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
   *reinterpret_cast<float4*>(ad + ro) = acc;
 }
 
-template <typename TX>
+template <typename TX, typename TF>
 __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
-                                                const float* __restrict__ Om, const float* __restrict__ h,
+                                                const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                 const float* __restrict__ lam_a, const float* __restrict__ v,
                                                 const float* __restrict__ lam_h_next, int N, int C,
@@ -207,6 +209,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -249,12 +252,12 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
       }
       {
         KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-        gemm_nt<P>(st, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega{w->Om[l], w->env, C, 2 * E});
+        gemm_nt<P>(st, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Om[l]), w->env, C, 2 * E});
       }
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_msg_fe, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->Om[l], w->h[l],
+      hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
                          (int)N, C, w->a[l]);
     }
     gemm_nt<P>(st, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
@@ -276,6 +279,7 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
@@ -293,7 +297,7 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
     gemm_nt<P>(st, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
-      hipLaunchKernelGGL(k_msg_ff, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->Om[l],
+      hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
                          w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
     }
   }
@@ -309,6 +313,7 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -326,8 +331,8 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL(k_msg_bf<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
+      hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
     gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
     gemm_nt<P>(st, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
@@ -374,6 +379,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -406,8 +412,8 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL(k_msg_be<TX>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         w->Om[l], w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
+      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
     if (E > 0) {
       const float* ulast = w->U[d - 2][l];
@@ -462,15 +468,17 @@ int inv_alloc(mlip_ctx* ctx) {
   w->jphi = A(2 * E * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
   const int64_t Wmax = std::max(C, H);
-  w->X = A(E * Wmax);
-  w->X2 = A(E * Wmax);
+  const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
+  // tensors held in the operand precision: half the floats when that is bf16
+  auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
+  w->X = AH(E * Wmax);
+  w->X2 = AH(E * Wmax);
   for (int l = 0; l < L; ++l) {
     w->U[0].push_back(A(2 * E * H));
     w->U[1].push_back(d == 3 ? A(2 * E * H) : nullptr);
-    const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
     w->SJ[0].push_back(b16 ? (__bf16*)A(E * H) : nullptr);  // 2 E H bf16 = E H floats
     w->SJ[1].push_back(b16 && d == 3 ? (__bf16*)A(E * H) : nullptr);
-    w->Om.push_back(A(2 * E * C));
+    w->Om.push_back(AH(2 * E * C));
     w->Y[0].push_back(A(E * H));
     w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);
     w->a.push_back(A(N * C)); w->q.push_back(A(N * C));

@@ -187,6 +187,7 @@ struct Act<gemm::Fp32> {
   typedef LdJetSiluEven Even;
   typedef LdJetSiluOdd Odd;
   typedef EpiStore Store;
+  typedef float flt_t;  // element type of the stored radial-filter jets
   typedef float xop_t;  // element type of the edge tensors that only feed matrix products
   typedef LdPlain XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
@@ -201,6 +202,7 @@ struct Act<gemm::Bf16> {
   typedef LdBf16 Even;
   typedef LdBf16 Odd;
   typedef EpiStoreJetAct Store;
+  typedef __bf16 flt_t;  // the filter jets are outputs of a bf16 product: kept in bf16, as a mixed-precision linear layer would
   typedef __bf16 xop_t;  // rounded once by the producer: half the bytes, no conversion in the operand path
   typedef LdBf16 XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
