@@ -10,14 +10,18 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmlip.so")
 SOURCES = ["api.hip", "graph.hip", "model.hip", "equivariant.hip", "gars.cpp"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# The neighbour search decides r < r_c in fp32 and must take the same decision as a plain
+# multiply-then-add evaluation: no fused multiply-add there.  The model kernels may fuse.
+NO_FMA = {"graph.hip"}
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    contract = "-ffp-contract=off" if src in NO_FMA else "-ffp-contract=fast"
+    cmd = ["hipcc", *FLAGS, contract, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
