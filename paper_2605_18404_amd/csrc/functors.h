@@ -132,40 +132,49 @@ struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by the
 };
 
 // ---------------------------------------------------------------------------- epilogues
+// operator()(r, col, a, b, z): a holds columns col..col+3 of output row r (even, in range) and b
+// the same columns of row r + 1, which the functor must skip when r + 1 == M unless the rows
+// come in pairs (jets: M = 2E).  z is the k-split index.
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float4 scale4(float s, float4 a) { return make_float4(s * a.x, s * a.y, s * a.z, s * a.w); }
+
 struct EpiStoreJetAct {  // u = v (fp32 jets) and the activated jets silu(u), silu'(u) u' rounded to bf16
   float* u;
   __bf16* sj;
   int64_t ld, M;  // M = 2E
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    const int64_t o = r * ld + col;
+    st4(u + o, a);
+    st4(u + o + ld, b);
+    const float x[4] = {a.x, a.y, a.z, a.w}, xd[4] = {b.x, b.y, b.z, b.w};
+    float val[4], der[4];
 #pragma unroll
-    for (int j = 0; j < 4; j += 2)
-      if (r0 + j + 1 < M) {
-        const int64_t o = (r0 + j) * ld + col;
-        u[o] = v[j];
-        u[o + ld] = v[j + 1];
-        const float s = sigm(v[j]);
-        sj[o] = (__bf16)(v[j] * s);
-        sj[o + ld] = (__bf16)(s * (1.f + v[j] * (1.f - s)) * v[j + 1]);
-      }
+    for (int j = 0; j < 4; ++j) {
+      const float s = sigm(x[j]);
+      val[j] = x[j] * s;
+      der[j] = s * (1.f + x[j] * (1.f - s)) * xd[j];
+    }
+    st4(sj + o, make_float4(val[0], val[1], val[2], val[3]));
+    st4(sj + o + ld, make_float4(der[0], der[1], der[2], der[3]));
   }
 };
 struct EpiStore {
   float* p;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) p[(r0 + j) * ld + col] = v[j];
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    const int64_t o = r * ld + col;
+    st4(p + o, a);
+    if (r + 1 < M) st4(p + o + ld, b);
   }
 };
 struct EpiAddStore {  // p = add + v
   float* p;
   const float* add;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) p[(r0 + j) * ld + col] = add[(r0 + j) * ld + col] + v[j];
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    const int64_t o = r * ld + col;
+    st4(p + o, add4(ld4(add + o), a));
+    if (r + 1 < M) st4(p + o + ld, add4(ld4(add + o + ld), b));
   }
 };
 template <typename TO>
@@ -173,14 +182,11 @@ struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  en
   TO* out;
   const float2* env;
   int64_t ld, M;  // M = 2E
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; j += 2)
-      if (r0 + j + 1 < M) {
-        float2 c = env[(r0 + j) >> 1];
-        out[(r0 + j) * ld + col] = (TO)(c.x * v[j]);
-        out[(r0 + j + 1) * ld + col] = (TO)(c.y * v[j] + c.x * v[j + 1]);
-      }
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    const float2 c = env[r >> 1];
+    const int64_t o = r * ld + col;
+    st4(out + o, scale4(c.x, a));
+    st4(out + o + ld, add4(scale4(c.y, a), scale4(c.x, b)));
   }
 };
 struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
@@ -188,14 +194,13 @@ struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
   float* mu_q;
   const float* q;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) {
-        int64_t o = (r0 + j) * ld + col;
-        mu_t[o] = v[j];
-        mu_q[o] = dsilu(q[o]) * v[j];
-      }
+  __device__ __forceinline__ void one(int64_t o, const float4& v) const {
+    st4(mu_t + o, v);
+    st4(mu_q + o, mul4(dsilu4(ld4(q + o)), v));
+  }
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    one(r * ld + col, a);
+    if (r + 1 < M) one((r + 1) * ld + col, b);
   }
 };
 template <typename TZ>
@@ -204,32 +209,42 @@ struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld]); Z only ever fe
   TZ* Z;
   const float* u;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) {
-        int64_t o = (r0 + j) * ld + col;
-        Y[o] = v[j];
-        Z[o] = (TZ)(dsilu(u[2 * (r0 + j) * ld + col]) * v[j]);
-      }
+  __device__ __forceinline__ void one(int64_t r, int col, const float4& v) const {
+    const int64_t o = r * ld + col;
+    st4(Y + o, v);
+    st4(Z + o, mul4(dsilu4(ld4(u + 2 * o - col)), v));  // u row 2r: 2 r ld + col
+  }
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    one(r, col, a);
+    if (r + 1 < M) one(r + 1, col, b);
   }
 };
+__device__ __forceinline__ float4 lam4(float4 u0, float4 u1, float4 y, float4 v) {  // silu'(u0) v + silu''(u0) u1 y
+  const float a0[4] = {u0.x, u0.y, u0.z, u0.w}, a1[4] = {u1.x, u1.y, u1.z, u1.w}, yy[4] = {y.x, y.y, y.z, y.w},
+              vv[4] = {v.x, v.y, v.z, v.w};
+  float a[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float d1, d2;
+    dsilu12(a0[j], d1, d2);
+    a[j] = d1 * vv[j] + d2 * a1[j] * yy[j];
+  }
+  return make_float4(a[0], a[1], a[2], a[3]);
+}
 template <typename TZ>
 struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y; out only ever feeds matrix products
   TZ* out;
   const float* u;
   const float* Y;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) {
-        int64_t o = (r0 + j) * ld + col;
-        const float* pu = u + 2 * (r0 + j) * ld + col;
-        float d1, d2;
-        dsilu12(pu[0], d1, d2);
-        out[o] = (TZ)(d1 * v[j] + d2 * pu[ld] * Y[o]);
-      }
+  __device__ __forceinline__ void one(int64_t r, int col, const float4& v) const {
+    const int64_t o = r * ld + col;
+    const float* pu = u + 2 * r * ld + col;
+    st4(out + o, lam4(ld4(pu), ld4(pu + ld), ld4(Y + o), v));
+  }
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    one(r, col, a);
+    if (r + 1 < M) one(r + 1, col, b);
   }
 };
 struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
@@ -238,24 +253,21 @@ struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
   const float* qd;
   const float* mu_t;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) {
-        int64_t o = (r0 + j) * ld + col;
-        float d1, d2;
-        dsilu12(q[o], d1, d2);
-        out[o] = d1 * v[j] + d2 * qd[o] * mu_t[o];
-      }
+  __device__ __forceinline__ void one(int64_t o, const float4& v) const {
+    st4(out + o, lam4(ld4(q + o), ld4(qd + o), ld4(mu_t + o), v));
+  }
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
+    one(r * ld + col, a);
+    if (r + 1 < M) one((r + 1) * ld + col, b);
   }
 };
 struct EpiPartial {  // split-k partial sums: part[z][row][col]
   float* part;
   int64_t ld, M;
-  __device__ __forceinline__ void operator()(int64_t r0, int col, const float (&v)[4], int z) const {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (r0 + j < M) part[((int64_t)z * M + r0 + j) * ld + col] = v[j];
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int z) const {
+    const int64_t o = ((int64_t)z * M + r) * ld + col;
+    st4(part + o, a);
+    if (r + 1 < M) st4(part + o + ld, b);
   }
 };
 

@@ -114,8 +114,8 @@ struct Stager {
 };
 
 // ---- the kernel -----------------------------------------------------------------------------
-// Epi: void operator()(int64_t row0, int col, const float (&v)[4], int z) const  -- rows row0..row0+3
-// of column col (the functor checks row0 + j < M itself; col < N is guaranteed), z = split index.
+// Epi: void operator()(int64_t row, int col, float4 a, float4 b, int z) const  -- columns col..col+3
+// of rows row (even, < M) and row + 1 (the functor checks row + 1 < M), z = split index.
 //
 // One output tile per workgroup, LDS double buffer, one barrier per k-tile; several workgroups
 // per compute unit hide each other's global-load latency.  Workgroups are dealt round-robin to
@@ -130,8 +130,13 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
   typedef Tile<P, BM, BK, KC> TA;
   typedef Tile<P, BN, BK, KC> TB;
   constexpr int LDA = TA::LD, LDB = TB::LD;
-  __shared__ __attribute__((aligned(16))) lds_t sA[2][TA::SIZE];
-  __shared__ __attribute__((aligned(16))) lds_t sB[2][TB::SIZE];
+  // operand stages (two of each) and, after the k loop, the per-wave output slabs share one array
+  constexpr int EW = 32 * TN, ELD = EW + 4;  // a wave's output slab: 32 rows x EW columns, padded
+  constexpr int STAGE_BYTES = 2 * (TA::SIZE + TB::SIZE) * (int)sizeof(lds_t);
+  constexpr int SLAB_BYTES = 4 * 32 * ELD * (int)sizeof(float);
+  __shared__ __attribute__((aligned(16))) char smem[STAGE_BYTES > SLAB_BYTES ? STAGE_BYTES : SLAB_BYTES];
+  lds_t(*sA)[TA::SIZE] = reinterpret_cast<lds_t(*)[TA::SIZE]>(smem);
+  lds_t(*sB)[TB::SIZE] = reinterpret_cast<lds_t(*)[TB::SIZE]>(smem + 2 * TA::SIZE * sizeof(lds_t));
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
@@ -219,23 +224,33 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
     }
     __syncthreads();
   }
-  // accumulator q of a 32x32 block: row = 8*(q/4) + 4*g + q%4, column = lane % 32
+  // Epilogue through LDS.  Accumulator q of a 32x32 block is row 8*(q/4) + 4*g + q%4, column
+  // lane % 32: one value per row per lane.  Each wave writes a 32-row slab of its sub-tile to its
+  // own LDS region and reads it back so that a lane holds two consecutive rows x four consecutive
+  // columns -- the functor then moves 16 bytes per access and a row's lanes cover whole lines.
+  // (Every wave has passed the k loop's last barrier, so the operand stages are dead.)
+  float* eb = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
+  constexpr int LPR = EW / 4;     // lanes across the slab's columns
+  constexpr int PPP = 64 / LPR;   // row pairs per pass
+  const int ecol = 4 * (lane % LPR), epair = lane / LPR;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + (wn * TN + j) * 32 + li;
-      if (col < N) {
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int qq = 0; qq < 4; ++qq) {
-          const int64_t row0 = m0 + (wm * TM + i) * 32 + 8 * qq + 4 * g;
-          if (row0 < M) {
-            float v[4] = {acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]};
-            epi(row0, col, v, z);
-          }
-        }
-      }
+      for (int q = 0; q < 16; ++q) eb[(8 * (q / 4) + 4 * g + q % 4) * ELD + j * 32 + li] = acc[i][j][q];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int ps = 0; ps < 16 / PPP; ++ps) {
+      const int rl = 2 * (ps * PPP + epair);
+      const float4 a = *reinterpret_cast<const float4*>(&eb[rl * ELD + ecol]);
+      const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
+      const int64_t row = m0 + (wm * TM + i) * 32 + rl;
+      const int col = n0 + wn * EW + ecol;
+      if (row < M && col < N) epi(row, col, a, b, z);
     }
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 // Returns the number of k splits actually used (every split is non-empty).
