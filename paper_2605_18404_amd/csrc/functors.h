@@ -27,13 +27,6 @@ __device__ __forceinline__ void dsilu12(float x, float& d1, float& d2) {
   d2 = s * (1.f - s) * (2.f + x * (1.f - 2.f * s));
 }
 
-// one sigmoid, then either silu(a) or silu'(a) * b, chosen without a branch
-__device__ __forceinline__ float jet1(float a, float b, bool odd) {
-  float s = sigm(a);
-  float val = a * s, der = s * (1.f + a * (1.f - s)) * b;
-  return odd ? der : val;
-}
-
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ float4 ld4(const __bf16* p) {
   bf16x4_t b = *reinterpret_cast<const bf16x4_t*>(p);
@@ -52,9 +45,9 @@ __device__ __forceinline__ float4 dsilu4(float4 a) { return make_float4(dsilu(a.
 // fetch() only issues loads (so they overlap the matrix products of the current tile),
 // finish() applies the element-wise function when the tile is staged.
 struct Raw2 { float4 a, b; };
-struct Raw2f { float4 a, b; bool odd; };
 
 struct LdPlain {  // p[row * ld + col]
+  static constexpr bool PAIRED = false;
   typedef float4 Raw;
   const float* p;
   int64_t ld;
@@ -62,32 +55,37 @@ struct LdPlain {  // p[row * ld + col]
   __device__ __forceinline__ float4 finish(const Raw& x) const { return x; }
 };
 struct LdSilu {  // silu(p[row * ld + col])
+  static constexpr bool PAIRED = false;
   typedef float4 Raw;
   const float* p;
   int64_t ld;
   __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return ld4(p + r * ld + c); }
   __device__ __forceinline__ float4 finish(const Raw& x) const { return silu4(x); }
 };
-struct LdJetSilu {  // rows of a jet matrix u [2E][W]: even -> silu(u), odd -> silu'(u_even) * u_odd
-  typedef Raw2f Raw;
+struct LdJetSilu {  // jet matrix u [2E][W]: row 2e -> silu(u[2e]), row 2e+1 -> silu'(u[2e]) * u[2e+1], both at once
+  static constexpr bool PAIRED = true;
+  typedef Raw2 Raw;
   const float* u;
   int64_t W;
-  __device__ __forceinline__ Raw fetch(int64_t rho, int64_t c) const {
-    const float* pe = u + (rho & ~(int64_t)1) * W + c;
-    Raw x;
-    x.a = ld4(pe);
-    x.b = ld4(pe + W);  // unconditional (the pair row always exists): no branch around the load
-    x.odd = (rho & 1) != 0;
-    return x;
+  __device__ __forceinline__ Raw fetch(int64_t r_even, int64_t c) const {
+    const float* pe = u + r_even * W + c;
+    return Raw{ld4(pe), ld4(pe + W)};
   }
-  __device__ __forceinline__ float4 finish(const Raw& x) const {
-    float4 r;
-    r.x = jet1(x.a.x, x.b.x, x.odd); r.y = jet1(x.a.y, x.b.y, x.odd);
-    r.z = jet1(x.a.z, x.b.z, x.odd); r.w = jet1(x.a.w, x.b.w, x.odd);
-    return r;
+  __device__ __forceinline__ void finish(const Raw& x, float4& val, float4& der) const {
+    const float a[4] = {x.a.x, x.a.y, x.a.z, x.a.w}, b[4] = {x.b.x, x.b.y, x.b.z, x.b.w};
+    float v[4], d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float s = sigm(a[j]);
+      v[j] = a[j] * s;
+      d[j] = s * (1.f + a[j] * (1.f - s)) * b[j];
+    }
+    val = make_float4(v[0], v[1], v[2], v[3]);
+    der = make_float4(d[0], d[1], d[2], d[3]);
   }
 };
 struct LdJetSiluEven {  // row e -> silu(u[2e])
+  static constexpr bool PAIRED = false;
   typedef float4 Raw;
   const float* u;
   int64_t W;
@@ -95,6 +93,7 @@ struct LdJetSiluEven {  // row e -> silu(u[2e])
   __device__ __forceinline__ float4 finish(const Raw& x) const { return silu4(x); }
 };
 struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
+  static constexpr bool PAIRED = false;
   typedef Raw2 Raw;
   const float* u;
   int64_t W;
@@ -105,6 +104,7 @@ struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
   __device__ __forceinline__ float4 finish(const Raw& x) const { return mul4(dsilu4(x.a), x.b); }
 };
 struct LdDsiluMul {  // silu'(q[row]) * x[row]
+  static constexpr bool PAIRED = false;
   typedef Raw2 Raw;
   const float* q;
   const float* x;
@@ -113,6 +113,7 @@ struct LdDsiluMul {  // silu'(q[row]) * x[row]
   __device__ __forceinline__ float4 finish(const Raw& v) const { return mul4(dsilu4(v.a), v.b); }
 };
 struct LdMuY {  // w_o[col] * silu'(y[row, col])
+  static constexpr bool PAIRED = false;
   typedef Raw2 Raw;
   const float* y;
   const float* wo;
@@ -122,6 +123,7 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
 };
 
 struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by their producer)
+  static constexpr bool PAIRED = false;
   typedef bf16x4_t Raw;
   const __bf16* p;
   int64_t ld;

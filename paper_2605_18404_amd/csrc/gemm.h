@@ -50,16 +50,22 @@ struct Tile {
 };
 
 // ---- staging: global (through the loader functor) -> registers -> LDS ------------------------
+// A loader with PAIRED = true (k-contiguous only) produces rows 2e and 2e+1 of a jet together:
+// Raw fetch(row_even, col4), void finish(raw, float4& even, float4& odd) -- one set of loads and
+// one evaluation of the shared sub-expressions for both rows.
 template <typename P, int ROWS, int BK, bool KC, typename Ld>
 struct Stager {
   typedef Tile<P, ROWS, BK, KC> TL;
-  static constexpr int NVT = ROWS * BK / 4;          // float4 per stage
+  static constexpr bool PR = Ld::PAIRED;
+  static_assert(!PR || KC, "paired loaders are k-contiguous");
+  static constexpr int RPI = PR ? 2 : 1;             // rows per item
+  static constexpr int NVT = ROWS / RPI * BK / 4;    // items per stage (float4 each, two if paired)
   static constexpr int NV = (NVT + 255) / 256;       // per thread
   static constexpr int Q = KC ? (BK / 4) : (ROWS / 4);
   typename Ld::Raw v[NV];
   unsigned ok = 0;
 
-  // KC: a row holds Q = BK/4 float4;     idx -> (row = idx / Q, kq = idx % Q)
+  // KC: a row holds Q = BK/4 float4;     idx -> (row = RPI * (idx / Q), kq = idx % Q)
   // KS: a k-row holds Q = ROWS/4 float4; idx -> (k = idx / Q,  rq = idx % Q)
   // Loads are unconditional: out-of-range coordinates are clamped to a valid element and the
   // value is discarded when the stage is written (no divergent branches around memory ops).
@@ -72,9 +78,9 @@ struct Stager {
         int64_t r, c;
         bool in;
         if (KC) {
-          r = row0 + idx / Q; c = k0 + 4 * (idx % Q);
+          r = row0 + RPI * (idx / Q); c = k0 + 4 * (idx % Q);
           in = r < n_rows && c < k_end;
-          r = r < n_rows ? r : n_rows - 1;
+          r = r < n_rows ? r : n_rows - RPI;  // paired: the row count is even
           c = c < k_end ? c : k_end - 4;
         } else {
           r = k0 + idx / Q; c = row0 + 4 * (idx % Q);
@@ -95,19 +101,37 @@ struct Stager {
     for (int it = 0; it < NV; ++it) {
       const int idx = t + it * 256;
       if (NVT % 256 != 0 && idx >= NVT) continue;
-      float4 x = ld.finish(v[it]);
-      if (!((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
-      const int a = idx / Q, b = idx % Q;  // KC: (row, kq); KS: (k, rq)
-      if constexpr (KC && TL::K_MAJOR) {  // fp32: transpose into [k][row]
-        s[(4 * b + 0) * LD + a] = (T)x.x;
-        s[(4 * b + 1) * LD + a] = (T)x.y;
-        s[(4 * b + 2) * LD + a] = (T)x.z;
-        s[(4 * b + 3) * LD + a] = (T)x.w;
-      } else if constexpr (P::IS_BF16) {  // KC [row][k] or KS [k][row]: 4 values = one 8-byte store
-        bf16x4 p = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
-        *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + a * LD + 4 * b) = p;
-      } else {  // KS fp32 [k][row]: one 16-byte store
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(s) + a * LD + 4 * b) = x;
+      const int a = idx / Q, b = idx % Q;  // KC: (row or row pair, kq); KS: (k, rq)
+      if constexpr (PR) {
+        float4 x, y;
+        ld.finish(v[it], x, y);
+        if (!((ok >> it) & 1u)) x = y = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (TL::K_MAJOR) {  // fp32 [k][row]: rows 2a, 2a+1 are neighbours -> 8-byte stores
+          float* f = reinterpret_cast<float*>(s);
+          *reinterpret_cast<float2*>(f + (4 * b + 0) * LD + 2 * a) = make_float2(x.x, y.x);
+          *reinterpret_cast<float2*>(f + (4 * b + 1) * LD + 2 * a) = make_float2(x.y, y.y);
+          *reinterpret_cast<float2*>(f + (4 * b + 2) * LD + 2 * a) = make_float2(x.z, y.z);
+          *reinterpret_cast<float2*>(f + (4 * b + 3) * LD + 2 * a) = make_float2(x.w, y.w);
+        } else {  // bf16 [row][k]
+          bf16x4 p0 = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
+          bf16x4 p1 = {(__bf16)y.x, (__bf16)y.y, (__bf16)y.z, (__bf16)y.w};
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + (2 * a) * LD + 4 * b) = p0;
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + (2 * a + 1) * LD + 4 * b) = p1;
+        }
+      } else {
+        float4 x = ld.finish(v[it]);
+        if (!((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (KC && TL::K_MAJOR) {  // fp32: transpose into [k][row]
+          s[(4 * b + 0) * LD + a] = (T)x.x;
+          s[(4 * b + 1) * LD + a] = (T)x.y;
+          s[(4 * b + 2) * LD + a] = (T)x.z;
+          s[(4 * b + 3) * LD + a] = (T)x.w;
+        } else if constexpr (P::IS_BF16) {  // KC [row][k] or KS [k][row]: 4 values = one 8-byte store
+          bf16x4 p = {(__bf16)x.x, (__bf16)x.y, (__bf16)x.z, (__bf16)x.w};
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(s) + a * LD + 4 * b) = p;
+        } else {  // KS fp32 [k][row]: one 16-byte store
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(s) + a * LD + 4 * b) = x;
+        }
       }
     }
   }
