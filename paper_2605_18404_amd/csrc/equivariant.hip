@@ -37,6 +37,8 @@ struct EqvWs {
   std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [12 C][H]
   std::vector<float*> WpT;  // and their transpose [H][12 C]
   float* gWp = nullptr;     // [12 C][H] weight gradient in the regrouped row order
+  float* cy = nullptr;      // [E][84] coupling coefficient x harmonic of the edge direction
+  float* cyd = nullptr;     // [E][84] the same with the directional derivative of the harmonics (BF, BE)
   std::vector<float*> Y1;   // [E][H]  BF -> BE
   float* X = nullptr;       // [E][C][12], operand precision
   float* X2 = nullptr;      // [E][H]
@@ -145,35 +147,92 @@ __device__ __forceinline__ RowChan row_chan(int N, int C) {
 }
 
 // ------------------------------------------------------------------------------ edge kernels
-template <typename TF>
+// One thread per (receiver row, channel); a row's edges are walked in order.  Every coupling term
+// T^p[m1,m2,m3] Y[m2] is the same for all channels of an edge, so the products cy[n] =
+// T_n Y[m2_n] (and cyd[n] with the directional derivative of Y) are tabulated once per edge and
+// each term costs one multiply-add here.  With UNI (C a multiple of 64) all lanes of a wave
+// share the row: the edge index is made wave-uniform, and the per-edge tables, indices and
+// geometry then arrive through scalar loads.
+using gaunt::CY_LD;
+using gaunt::NNZ;
+using gaunt::NSLOT;
+
+template <bool UNI>
+__device__ __forceinline__ int uni(int x) { return UNI ? __builtin_amdgcn_readfirstlane(x) : x; }
+
+// UNI: the 64 lanes fetch the edge's table with two coalesced loads and publish it in the
+// wave's own LDS slot, from where every lane reads the entries it needs as broadcasts.  (LDS
+// operations of one wave execute in order, so the next edge's copy cannot overtake the reads.)
+struct TabRegs { float a, b; };
+__device__ __forceinline__ TabRegs tab_fetch(const float* __restrict__ src, int lane) {
+  TabRegs r;
+  r.a = src[lane];
+  r.b = src[64 + lane];  // runs into the next edge's table (the allocation is padded): no branch
+  return r;
+}
+__device__ __forceinline__ void tab_publish(const TabRegs& r, float* slot, int lane) {
+  slot[lane] = r.a;
+  slot[64 + lane] = r.b;
+  __builtin_amdgcn_wave_barrier();
+}
+
+// S[slot (p, m3)] (+)= sum_n cy[n] x[m1_n]
+template <bool ACC>
+__device__ __forceinline__ void contract_x(const float* __restrict__ cy, const float (&x)[9], float (&S)[NSLOT]) {
+#pragma unroll
+  for (int n = 0; n < NNZ; ++n) {
+    const int sl = gaunt::ENT_SLOT[n];
+    if (!ACC && (n == 0 || gaunt::ENT_SLOT[n > 0 ? n - 1 : 0] != sl))
+      S[sl] = cy[n] * x[gaunt::ENT_M1[n]];
+    else
+      S[sl] = fmaf(cy[n], x[gaunt::ENT_M1[n]], S[sl]);
+  }
+}
+// out[m1] += sum_n cy[n] R[slot_n]
+__device__ __forceinline__ void adj_x_from(const float* __restrict__ cy, const float (&R)[NSLOT], float (&out)[9]) {
+#pragma unroll
+  for (int n = 0; n < NNZ; ++n) out[gaunt::ENT_M1[n]] = fmaf(cy[n], R[gaunt::ENT_SLOT[n]], out[gaunt::ENT_M1[n]]);
+}
+
+template <typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const TF* __restrict__ Rho,
+                                               const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
   RowChan t = row_chan(N, C);
-  if (!t.active) return;
+  if (!t.active) return;  // no workgroup barrier below
   const int64_t NC = (int64_t)N * C;
   float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  __shared__ float tabs[4][128];
+  float* slot = tabs[threadIdx.x >> 6];
+  const int lane = threadIdx.x & 63;
+  const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
+  int jn = e0 < e1 ? sender[e0] : 0;
   for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    float4 g = geo[e];
-    float Y[9], x[9], rho[NPATH];
-    sph_harm(g.x, g.y, g.z, Y);
+    const int j = jn;
+    jn = sender[e + 1 < e1 ? e + 1 : e];  // next edge's sender: its gathers need not wait for an index
+    float x[9], rho[NPATH], S[NSLOT];
+    const float* cy = cyt + (int64_t)e * CY_LD;
+    TabRegs tr;
+    if constexpr (UNI) tr = tab_fetch(cy, lane);
     load9(h, NC, (int64_t)j * C + t.c, x);
     load_rho(Rho + (int64_t)(2 * e) * NPP * C, t.c, rho);
-    gaunt::tp_fwd(rho, x, Y, acc);
+    if constexpr (UNI) { tab_publish(tr, slot, lane); cy = slot; }
+    contract_x<false>(cy, x, S);
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) acc[gaunt::SLOT_M3[sl]] = fmaf(rho[gaunt::SLOT_P[sl]], S[sl], acc[gaunt::SLOT_M3[sl]]);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
 }
 
-template <typename TF>
+template <typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const TF* __restrict__ Rho,
-                                               const float* __restrict__ h, const float* __restrict__ mu_a,
-                                               const float* __restrict__ mu_h_next, int N, int C,
-                                               float* __restrict__ mu_h, float* __restrict__ Facc) {
+                                                  const float4* __restrict__ geo, const TF* __restrict__ Rho,
+                                                  const float* __restrict__ cyt, const float* __restrict__ h,
+                                                  const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
+                                                  int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
   __shared__ float3 red[256];
+  __shared__ float tabs[4][128];
   RowChan t = row_chan(N, C);
   float3 f = make_float3(0.f, 0.f, 0.f);
   if (t.active) {
@@ -183,26 +242,42 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
     load9(mu_h_next, NC, io, acc);
     load9(h, NC, io, xi);
     load9(mu_a, NC, io, mi);
-    const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+    float* slot = tabs[threadIdx.x >> 6];
+    const int lane = threadIdx.x & 63;
+    const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
+    int jn = e0 < e1 ? sender[e0] : 0;
     for (int e = e0; e < e1; ++e) {
-      int j = sender[e];
-      float4 g = geo[e];
-      float Y[9], PY[9], xj[9], mj[9], rho[NPATH], rhop[NPATH];
-      sph_harm(g.x, g.y, g.z, Y);
-      parity(Y, PY);
+      const int j = jn;
+      jn = sender[e + 1 < e1 ? e + 1 : e];
+      const float4 g = geo[e];
+      const float* cy = cyt + (int64_t)e * CY_LD;
+      TabRegs tr;
+      if constexpr (UNI) tr = tab_fetch(cy, lane);
+      float xj[9], mj[9], rho[NPATH], rhop[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
       load9(h, NC, jo, xj);
       load9(mu_a, NC, jo, mj);
       const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
       load_rho(rrow, t.c, rho);
       load_rho(rrow + NPP * C, t.c, rhop);
-      gaunt::tp_adj_x(rho, PY, mj, acc);
-      float t1[NPATH], t2[NPATH];
-      gaunt::tp_paths(xj, Y, mi, t1);
-      gaunt::tp_paths(xi, PY, mj, t2);
-      float s = 0.f;
+      if constexpr (UNI) { tab_publish(tr, slot, lane); cy = slot; }
+      {  // the message this atom sends back along the reversed edge: couplings of -u
+        float R[NSLOT];
 #pragma unroll
-      for (int p = 0; p < NPATH; ++p) s += rhop[p] * (t1[p] + t2[p]);
+        for (int sl = 0; sl < NSLOT; ++sl) R[sl] = gaunt::PATH_SIGN[gaunt::SLOT_P[sl]] * rho[gaunt::SLOT_P[sl]] * mj[gaunt::SLOT_M3[sl]];
+        adj_x_from(cy, R, acc);
+      }
+      float s = 0.f;
+      {  // radial part of the force: rho' (t(x_j, Y, mu_i) + t(x_i, PY, mu_j))
+        float S1[NSLOT], S2[NSLOT];
+        contract_x<false>(cy, xj, S1);
+        contract_x<false>(cy, xi, S2);
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl) {
+          const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
+          s = fmaf(rhop[p], fmaf(gaunt::PATH_SIGN[p] * mj[m3], S2[sl], mi[m3] * S1[sl]), s);
+        }
+      }
       float nu[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, nu2[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       gaunt::tp_adj_y(rho, xj, mi, nu);
       gaunt::tp_adj_y(rho, xi, mj, nu2);
@@ -232,13 +307,14 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
   }
 }
 
-template <typename TX, typename TF>
+template <typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const float2* __restrict__ env,
-                                               const TF* __restrict__ Rho, const float* __restrict__ h,
-                                               const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                               const float* __restrict__ v, int N, int C, float* __restrict__ ad,
-                                               TX* __restrict__ X) {
+                                                  const float2* __restrict__ env,
+                                                  const TF* __restrict__ Rho, const float* __restrict__ cyt,
+                                                  const float* __restrict__ cydt, const float* __restrict__ h,
+                                                  const float* __restrict__ hd, const float* __restrict__ mu_a, int N, int C,
+                                                  float* __restrict__ ad,
+                                                  TX* __restrict__ X) {
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -246,28 +322,42 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
   float mi[9];
   load9(mu_a, NC, io, mi);
   float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  __shared__ float tabs[4][2][128];
+  float* slot = tabs[threadIdx.x >> 6][0];
+  float* slotd = tabs[threadIdx.x >> 6][1];
+  const int lane = threadIdx.x & 63;
+  const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
+  int jn = e0 < e1 ? sender[e0] : 0;
   for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    float4 g = geo[e];
-    float3 dv = make_float3(v[3 * j] - v[3 * t.row], v[3 * j + 1] - v[3 * t.row + 1], v[3 * j + 2] - v[3 * t.row + 2]);
-    float rd = g.x * dv.x + g.y * dv.y + g.z * dv.z;
-    float Y[9], Yd[9], xj[9], xdj[9], rho[NPATH], rr[NPATH];
-    sph_harm(g.x, g.y, g.z, Y);
-    sph_dot(g.x, g.y, g.z, g.w, dv, Yd);
+    const int j = jn;
+    jn = sender[e + 1 < e1 ? e + 1 : e];
+    const float* cy = cyt + (int64_t)e * CY_LD;
+    const float* cyd = cydt + (int64_t)e * CY_LD;
+    TabRegs tr, trd;
+    if constexpr (UNI) { tr = tab_fetch(cy, lane); trd = tab_fetch(cyd, lane); }
+    float xj[9], xdj[9], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
     load9(h, NC, jo, xj);
     load9(hd, NC, jo, xdj);
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
+    if constexpr (UNI) { tab_publish(tr, slot, lane); tab_publish(trd, slotd, lane); cy = slot; cyd = slotd; }
+    const float rd = cyd[NNZ];  // u . (v_sender - v_receiver), stored behind the table
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
-    gaunt::tp_fwd(rr, xj, Y, acc);
-    gaunt::tp_fwd(rho, xdj, Y, acc);
-    gaunt::tp_fwd(rho, xj, Yd, acc);
-    float tp[NPATH];
-    gaunt::tp_paths(xj, Y, mi, tp);
+    // d/dt of the message: (rdot rho') T x Y + rho T xdot Y + rho T x Ydot
+    float S1[NSLOT], S23[NSLOT];
+    contract_x<false>(cy, xj, S1);
+    contract_x<false>(cy, xdj, S23);
+    contract_x<true>(cyd, xj, S23);
+    float tp[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) {
+      const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
+      acc[m3] = fmaf(rr[p], S1[sl], fmaf(rho[p], S23[sl], acc[m3]));
+      tp[p] = fmaf(mi[m3], S1[sl], tp[p]);
+    }
     const float s = rd * env[e].x;
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) tp[p] *= s;
@@ -277,14 +367,14 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
   for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
 }
 
-template <typename TX, typename TF>
+template <typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                               const float4* __restrict__ geo, const float2* __restrict__ env,
-                                               const TF* __restrict__ Rho, const float* __restrict__ h,
-                                               const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                               const float* __restrict__ lam_a, const float* __restrict__ v,
-                                               const float* __restrict__ lam_h_next, int N, int C,
-                                               float* __restrict__ lam_h, TX* __restrict__ X) {
+                                                  const float2* __restrict__ env,
+                                                  const TF* __restrict__ Rho, const float* __restrict__ cyt,
+                                                  const float* __restrict__ cydt, const float* __restrict__ h,
+                                                  const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                                  const float* __restrict__ lam_a, const float* __restrict__ lam_h_next, int N, int C,
+                                                  float* __restrict__ lam_h, TX* __restrict__ X) {
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -293,17 +383,20 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
   load9(mu_a, NC, io, mi);
   load9(lam_a, NC, io, li);
   load9(lam_h_next, NC, io, acc);
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
+  __shared__ float tabs[4][2][128];
+  float* slot = tabs[threadIdx.x >> 6][0];
+  float* slotd = tabs[threadIdx.x >> 6][1];
+  const int lane = threadIdx.x & 63;
+  const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
+  int jn = e0 < e1 ? sender[e0] : 0;
   for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    float4 g = geo[e];
-    float3 dv = make_float3(v[3 * j] - v[3 * t.row], v[3 * j + 1] - v[3 * t.row + 1], v[3 * j + 2] - v[3 * t.row + 2]);
-    float rd = g.x * dv.x + g.y * dv.y + g.z * dv.z;
-    float Y[9], Yd[9], PY[9], PYd[9], xj[9], xdj[9], lj[9], mj[9], rho[NPATH], rr[NPATH];
-    sph_harm(g.x, g.y, g.z, Y);
-    sph_dot(g.x, g.y, g.z, g.w, dv, Yd);
-    parity(Y, PY);
-    parity(Yd, PYd);
+    const int j = jn;
+    jn = sender[e + 1 < e1 ? e + 1 : e];
+    const float* cy = cyt + (int64_t)e * CY_LD;
+    const float* cyd = cydt + (int64_t)e * CY_LD;
+    TabRegs tr, trd;
+    if constexpr (UNI) { tr = tab_fetch(cy, lane); trd = tab_fetch(cyd, lane); }
+    float xj[9], xdj[9], lj[9], mj[9], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
     load9(h, NC, jo, xj);
     load9(hd, NC, jo, xdj);
@@ -312,25 +405,76 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
+    if constexpr (UNI) { tab_publish(tr, slot, lane); tab_publish(trd, slotd, lane); cy = slot; cyd = slotd; }
+    const float rd = cyd[NNZ];  // u . (v_sender - v_receiver), stored behind the table
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
-    gaunt::tp_adj_x(rho, PY, lj, acc);
-    gaunt::tp_adj_x(rr, PY, mj, acc);
-    gaunt::tp_adj_x(rho, PYd, mj, acc);
-    float t1[NPATH], t2[NPATH], t3[NPATH], t4[NPATH];
-    gaunt::tp_paths(xj, Y, li, t1);
-    gaunt::tp_paths(xdj, Y, mi, t2);
-    gaunt::tp_paths(xj, Yd, mi, t3);
-    gaunt::tp_paths(xj, Y, mi, t4);
+    {  // adjoint of the sender's features along the reversed edge (couplings of -u)
+      float R[NSLOT];
+#pragma unroll
+      for (int sl = 0; sl < NSLOT; ++sl) {
+        const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
+        R[sl] = gaunt::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
+      }
+      adj_x_from(cy, R, acc);
+#pragma unroll
+      for (int sl = 0; sl < NSLOT; ++sl) R[sl] = gaunt::PATH_SIGN[gaunt::SLOT_P[sl]] * rho[gaunt::SLOT_P[sl]] * mj[gaunt::SLOT_M3[sl]];
+      adj_x_from(cyd, R, acc);
+    }
+    // adjoint of the filter jets: value row  c (t(x,Y,lam) + t(xdot,Y,mu) + t(x,Ydot,mu)) + c' rdot t(x,Y,mu)
+    float S1[NSLOT], S23[NSLOT];
+    contract_x<false>(cy, xj, S1);
+    contract_x<false>(cy, xdj, S23);
+    contract_x<true>(cyd, xj, S23);
+    float ta[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, t4[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) {
+      const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
+      ta[p] = fmaf(li[m3], S1[sl], fmaf(mi[m3], S23[sl], ta[p]));
+      t4[p] = fmaf(mi[m3], S1[sl], t4[p]);
+    }
     const float2 cc = env[e];
     const float s = cc.y * rd;
 #pragma unroll
-    for (int p = 0; p < NPATH; ++p) t1[p] = cc.x * (t1[p] + t2[p] + t3[p]) + s * t4[p];
-    store_paths(X + (int64_t)e * NPP * C, t.c, t1);
+    for (int p = 0; p < NPATH; ++p) ta[p] = fmaf(cc.x, ta[p], s * t4[p]);
+    store_paths(X + (int64_t)e * NPP * C, t.c, ta);
   }
 #pragma unroll
   for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
 }
+
+// Per-edge tables of coupling coefficient x harmonic: cy[e][n] = T_n Y_{m2_n}(u_e), and, with
+// WITH_DOT, cyd[e][n] = T_n Ydot_{m2_n} for the displacement rate v_sender - v_receiver,
+// followed (entry NNZ) by the rate of change of the edge length, u . (v_sender - v_receiver).
+template <bool WITH_DOT>
+__global__ void k_edge_cy(const float4* __restrict__ geo, const int32_t* __restrict__ sender,
+                          const int32_t* __restrict__ receiver, const float* __restrict__ v, int64_t E,
+                          float* __restrict__ out) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= E * CY_LD) return;
+  const int64_t e = idx / CY_LD;
+  const int n = (int)(idx % CY_LD);
+  const float4 g = geo[e];
+  float Y[9];
+  float val = 0.f;
+  if (WITH_DOT) {
+    const int j = sender[e], i = receiver[e];
+    const float3 dv = make_float3(v[3 * j] - v[3 * i], v[3 * j + 1] - v[3 * i + 1], v[3 * j + 2] - v[3 * i + 2]);
+    sph_dot(g.x, g.y, g.z, g.w, dv, Y);
+    if (n == NNZ) val = g.x * dv.x + g.y * dv.y + g.z * dv.z;  // rate of change of the edge length
+  } else {
+    sph_harm(g.x, g.y, g.z, Y);
+  }
+  if (n < NNZ) {
+    const int m2 = gaunt::ENT_M2_DEV[n];
+    float y = Y[0];
+#pragma unroll
+    for (int m = 1; m < 9; ++m) y = (m2 == m) ? Y[m] : y;
+    val = gaunt::ENT_COEF_DEV[n] * y;
+  }
+  out[idx] = val;
+}
+
 
 // Filter weights W [11 C][H] (row p C + c) regrouped to the stored order of the filter jets:
 // Wp [(c 12 + p)][H], zero rows for the pad, and the transpose WpT [H][12 C].
@@ -382,8 +526,11 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   if (E > 0)
     hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
                        ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
+  if (E > 0)
+    hipLaunchKernelGGL(k_edge_cy<false>, dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
   hipLaunchKernelGGL(k_embed_l0, dim3(nblk(9 * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);
   const int rpb = 256 / C;
+  const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     if (E > 0) {
@@ -396,8 +543,9 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_tp_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
-                         w->h[l], (int)N, C, w->a[l]);
+      auto kern = uni ? k_tp_fe<TF, true> : k_tp_fe<TF, false>;
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Rho[l]),
+                         w->cy, w->h[l], (int)N, C, w->a[l]);
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
@@ -426,6 +574,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   gemm_nt<P>(st, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
   hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
   const int rpb = 256 / C;
+  const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     for (int k = 0; k < 3; ++k) {
@@ -433,8 +582,9 @@ int ff_impl(mlip_ctx* ctx, float* F) {
       gemm_nt<P>(st, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    hipLaunchKernelGGL(k_tp_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
-                       w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+    auto kern = uni ? k_tp_ff<TF, true> : k_tp_ff<TF, false>;
+    hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
+                       w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
   MLIP_HIP_CHECK(ctx, hipGetLastError());
@@ -455,13 +605,17 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   TX* X = reinterpret_cast<TX*>(w->X);
   TX* X2 = reinterpret_cast<TX*>(w->X2);
   hipLaunchKernelGGL(k_fill, dim3(nblk(9 * NC)), dim3(256), 0, st, w->hd[0], 0.f, 9 * NC);
+  if (E > 0)  // harmonics' rate of change under the displacement rate v: used by this phase and by BE
+    hipLaunchKernelGGL(k_edge_cy<true>, dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, w->v, E, w->cyd);
   const int rpb = 256 / C;
+  const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL((k_tp_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         reinterpret_cast<const TF*>(w->Rho[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
+      auto kern = uni ? k_tp_bf<TX, TF, true> : k_tp_bf<TX, TF, false>;
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
@@ -517,6 +671,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->lam_h[cur] + NC, 0.f, 8 * NC);
   gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   const int rpb = 256 / C;
+  const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
@@ -528,8 +683,9 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL((k_tp_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
-                         reinterpret_cast<const TF*>(w->Rho[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
+      auto kern = uni ? k_tp_be<TX, TF, true> : k_tp_be<TX, TF, false>;
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
     if (E > 0) {
       {
@@ -579,6 +735,8 @@ int eqv_alloc(mlip_ctx* ctx) {
   auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
   w->X = AH(E * PC);
   w->gWp = A((int64_t)PC * H);
+  w->cy = A(E * gaunt::CY_LD + 64);  // + 64: the cooperative fetch of the last edge's table reads 128 floats
+  w->cyd = A(E * gaunt::CY_LD + 64);
   w->X2 = AH(E * H);
   const int64_t NC9 = 9 * N * C;
   for (int l = 0; l < L; ++l) {
