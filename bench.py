@@ -32,15 +32,16 @@ def kernel_table(w, E, N):
     eqv = w.l_max == 2
     Co = 11 * C if eqv else C          # width of the radial filter per edge
     f4 = 4
+    fj = 2 if w.gemm_bf16 else 4       # filter jets and their adjoints are held in the operand precision
     node = (9 if eqv else 1) * N * C * f4
     geo = 16 + 4                       # unit vector + length, sender index
     return {
         1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H),
         2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co),
-        3: ("msg_fe", "hbm", E * Co * f4 + 2 * node + E * geo),
-        4: ("msg_ff", "hbm", 2 * E * Co * f4 + 4 * node + E * geo),
-        5: ("msg_bf", "hbm", 3 * E * Co * f4 + 4 * node + E * (geo + 8)),
-        6: ("msg_be", "hbm", 3 * E * Co * f4 + 6 * node + E * (geo + 8)),
+        3: ("msg_fe", "hbm", E * Co * fj + 2 * node + E * geo),
+        4: ("msg_ff", "hbm", 2 * E * Co * fj + 4 * node + E * geo),
+        5: ("msg_bf", "hbm", 3 * E * Co * fj + 4 * node + E * (geo + 8)),
+        6: ("msg_be", "hbm", 3 * E * Co * fj + 6 * node + E * (geo + 8)),
         7: ("bf_dgrad_gemm", "mfma", 2.0 * E * Co * H),
         8: ("be_dgrad_gemm", "mfma", 2.0 * E * Co * H),
         9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H),
