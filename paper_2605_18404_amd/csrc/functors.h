@@ -48,6 +48,7 @@ struct Raw2 { float4 a, b; };
 
 struct LdPlain {  // p[row * ld + col]
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef float4 Raw;
   const float* p;
   int64_t ld;
@@ -56,6 +57,7 @@ struct LdPlain {  // p[row * ld + col]
 };
 struct LdSilu {  // silu(p[row * ld + col])
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef float4 Raw;
   const float* p;
   int64_t ld;
@@ -64,6 +66,7 @@ struct LdSilu {  // silu(p[row * ld + col])
 };
 struct LdJetSilu {  // jet matrix u [2E][W]: row 2e -> silu(u[2e]), row 2e+1 -> silu'(u[2e]) * u[2e+1], both at once
   static constexpr bool PAIRED = true;
+  static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* u;
   int64_t W;
@@ -86,6 +89,7 @@ struct LdJetSilu {  // jet matrix u [2E][W]: row 2e -> silu(u[2e]), row 2e+1 -> 
 };
 struct LdJetSiluEven {  // row e -> silu(u[2e])
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef float4 Raw;
   const float* u;
   int64_t W;
@@ -94,6 +98,7 @@ struct LdJetSiluEven {  // row e -> silu(u[2e])
 };
 struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* u;
   int64_t W;
@@ -105,6 +110,7 @@ struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
 };
 struct LdDsiluMul {  // silu'(q[row]) * x[row]
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* q;
   const float* x;
@@ -114,6 +120,7 @@ struct LdDsiluMul {  // silu'(q[row]) * x[row]
 };
 struct LdMuY {  // w_o[col] * silu'(y[row, col])
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* y;
   const float* wo;
@@ -124,6 +131,7 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
 
 struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by their producer)
   static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 4;
   typedef bf16x4_t Raw;
   const __bf16* p;
   int64_t ld;
@@ -131,6 +139,18 @@ struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by the
   __device__ __forceinline__ float4 finish(const Raw& x) const {
     return make_float4((float)x[0], (float)x[1], (float)x[2], (float)x[3]);
   }
+};
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+struct LdBf16x8 {  // the same matrix fetched eight values (16 bytes) at a time and staged without conversion;
+                   // needs ld, the extent along the contiguous index and the base address in multiples of 8 values
+  static constexpr bool PAIRED = false;
+  static constexpr int WIDTH = 8;
+  typedef bf16x8_t Raw;
+  const __bf16* p;
+  int64_t ld;
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const { return *reinterpret_cast<const bf16x8_t*>(p + r * ld + c); }
+  __device__ __forceinline__ Raw finish(const Raw& x) const { return x; }
 };
 
 // ---------------------------------------------------------------------------- epilogues

@@ -50,6 +50,7 @@ struct Tile {
 };
 
 // ---- staging: global (through the loader functor) -> registers -> LDS ------------------------
+// A loader has WIDTH = 4 (float4 items, converted while staged) or 8 (raw bf16, copied as is).
 // A loader with PAIRED = true (k-contiguous only) produces rows 2e and 2e+1 of a jet together:
 // Raw fetch(row_even, col4), void finish(raw, float4& even, float4& odd) -- one set of loads and
 // one evaluation of the shared sub-expressions for both rows.
@@ -59,9 +60,11 @@ struct Stager {
   static constexpr bool PR = Ld::PAIRED;
   static_assert(!PR || KC, "paired loaders are k-contiguous");
   static constexpr int RPI = PR ? 2 : 1;             // rows per item
-  static constexpr int NVT = ROWS / RPI * BK / 4;    // items per stage (float4 each, two if paired)
+  static constexpr int VW = Ld::WIDTH;               // values per item along the contiguous index
+  static_assert(VW == 4 || (VW == 8 && P::IS_BF16 && !PR), "eight-wide items are raw bf16");
+  static constexpr int NVT = ROWS / RPI * BK / VW;   // items per stage (two rows each if paired)
   static constexpr int NV = (NVT + 255) / 256;       // per thread
-  static constexpr int Q = KC ? (BK / 4) : (ROWS / 4);
+  static constexpr int Q = KC ? (BK / VW) : (ROWS / VW);
   typename Ld::Raw v[NV];
   unsigned ok = 0;
 
@@ -78,15 +81,15 @@ struct Stager {
         int64_t r, c;
         bool in;
         if (KC) {
-          r = row0 + RPI * (idx / Q); c = k0 + 4 * (idx % Q);
+          r = row0 + RPI * (idx / Q); c = k0 + VW * (idx % Q);
           in = r < n_rows && c < k_end;
           r = r < n_rows ? r : n_rows - RPI;  // paired: the row count is even
-          c = c < k_end ? c : k_end - 4;
+          c = c < k_end ? c : k_end - VW;
         } else {
-          r = k0 + idx / Q; c = row0 + 4 * (idx % Q);
+          r = k0 + idx / Q; c = row0 + VW * (idx % Q);
           in = c < n_rows && r < k_end;
           r = r < k_end ? r : k_end - 1;
-          c = c < n_rows ? c : n_rows - 4;
+          c = c < n_rows ? c : n_rows - VW;
         }
         v[it] = ld.fetch(r, c);
         ok |= (in ? 1u : 0u) << it;
@@ -102,7 +105,11 @@ struct Stager {
       const int idx = t + it * 256;
       if (NVT % 256 != 0 && idx >= NVT) continue;
       const int a = idx / Q, b = idx % Q;  // KC: (row or row pair, kq); KS: (k, rq)
-      if constexpr (PR) {
+      if constexpr (VW == 8) {  // raw bf16, KC [row][k] or KS [k][row]: one 16-byte store, no conversion
+        bf16x8 x = ld.finish(v[it]);
+        if (!((ok >> it) & 1u)) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(s) + a * LD + 8 * b) = x;
+      } else if constexpr (PR) {
         float4 x, y;
         ld.finish(v[it], x, y);
         if (!((ok >> it) & 1u)) x = y = make_float4(0.f, 0.f, 0.f, 0.f);

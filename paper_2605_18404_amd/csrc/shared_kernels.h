@@ -3,6 +3,7 @@
 // internal linkage.
 #pragma once
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "functors.h"
@@ -232,13 +233,25 @@ T* alloc_n(mlip_ctx* ctx, int64_t n) {
 // ------------------------------------------------------------------------------ GEMM wrappers
 // D[M][N] = A[M][K] * W[N][K]^T with loader / epilogue functors; tile chosen from N.
 template <typename P, typename LdA, typename Epi>
-void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
+void gemm_nt_as(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
   LdPlain b{W, K};
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   if (N > 64 && tiles128 >= 512)
     gemm::launch<P, 2, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
   else
     gemm::launch<P, 1, 1, 2, 2, true>(st, a, b, epi, M, N, K, 1);
+}
+// A bf16 operand is fetched 16 bytes at a time when its leading dimension, its extent along the
+// contiguous index and its base address allow it.
+inline bool wide_ok(const LdBf16& l, int64_t extent) {
+  return l.ld % 8 == 0 && extent % 8 == 0 && (reinterpret_cast<uintptr_t>(l.p) & 15) == 0;
+}
+template <typename P, typename LdA, typename Epi>
+void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
+  if constexpr (std::is_same<LdA, LdBf16>::value) {
+    if (wide_ok(a, K)) return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, W, M, N, K, epi);
+  }
+  gemm_nt_as<P>(st, a, W, M, N, K, epi);
 }
 
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
@@ -250,7 +263,7 @@ int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
 
 // grad[Nout][Kout] += A^T B, A [R][Nout], B [R][Kout] given by loaders (reduction over R rows).
 template <typename P, typename LdA, typename LdB>
-int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
+int gemm_wgrad_as(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
   const PartialBuf* w = &ctx->partial;
   hipStream_t st = ctx->stream;
   if (R <= 0) return MLIP_OK;
@@ -270,6 +283,24 @@ int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, i
   return MLIP_OK;
 }
 
+
+template <typename P, typename LdA, typename LdB>
+int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
+  constexpr bool A16 = std::is_same<LdA, LdBf16>::value, B16 = std::is_same<LdB, LdBf16>::value;
+  bool wa = false, wb = false;
+  if constexpr (A16) wa = wide_ok(a, Nout);
+  if constexpr (B16) wb = wide_ok(b, Kout);
+  if constexpr (A16 && B16) {
+    if (wa && wb) return gemm_wgrad_as<P>(ctx, LdBf16x8{a.p, a.ld}, LdBf16x8{b.p, b.ld}, R, Nout, Kout, grad);
+  }
+  if constexpr (A16) {
+    if (wa) return gemm_wgrad_as<P>(ctx, LdBf16x8{a.p, a.ld}, b, R, Nout, Kout, grad);
+  }
+  if constexpr (B16) {
+    if (wb) return gemm_wgrad_as<P>(ctx, a, LdBf16x8{b.p, b.ld}, R, Nout, Kout, grad);
+  }
+  return gemm_wgrad_as<P>(ctx, a, b, R, Nout, Kout, grad);
+}
 
 // Edge geometry and featurisation: unit vector, length, Gaussian basis jets, envelope jet.
 __global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
