@@ -96,6 +96,10 @@ struct mlip_ctx {
   void* model_ws = nullptr;    // workspace of the model kind, owned by its translation unit
   void* step_bufs = nullptr;   // cotangent buffers of mlip_train_step
   PartialBuf partial;
+  // bf16 products only: weight arrays mirrored in bf16 (refreshed once per forward pass), so that
+  // the matrix at f32 + k is also available, already rounded, at b16 + k
+  struct Shadow { const float* f32; __bf16* b16; int64_t n; };
+  std::vector<Shadow> shadows;
 
   // ---- kernel timer (mlip_kernel_timer_select / _read): event pairs around one kernel's launches
   int timed_kernel = 0;

@@ -523,6 +523,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     for (int k = 0; k < 3; ++k) tr(ctx->lay[l].Wl[k], C, C);
   }
   tr(ctx->off_U, C, C);
+  if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights, their transposes and the regrouped filters
   if (E > 0)
     hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
                        ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
@@ -536,10 +537,10 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
+        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-      gemm_nt<P>(st, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PC, 2 * E});
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PC, 2 * E});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
@@ -549,10 +550,10 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(st, LdPlain{w->a[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
+      gemm_nt<P>(ctx, LdPlain{w->a[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
   }
-  gemm_nt<P>(st, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
+  gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
   hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
   hipLaunchKernelGGL(k_struct_sum, dim3(ctx->B), dim3(256), 0, st, w->eps, ctx->d_meta, E_out);
   MLIP_HIP_CHECK(ctx, hipGetLastError());
@@ -571,7 +572,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   const float* tT = w->paramsT;
   // mu_h^L: l = 0 block from the readout, zero elsewhere
   hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->mu_h[L] + NC, 0.f, 8 * NC);
-  gemm_nt<P>(st, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
+  gemm_nt<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
   hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
@@ -579,7 +580,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
     const LayerOffsets& lo = ctx->lay[l];
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(st, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
+      gemm_nt<P>(ctx, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = uni ? k_tp_ff<TF, true> : k_tp_ff<TF, false>;
@@ -619,7 +620,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(st, LdPlain{w->ad[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
+      gemm_nt<P>(ctx, LdPlain{w->ad[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
       MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1] + o, C}, LdPlain{w->ad[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
     }
     if (E > 0) {
@@ -631,12 +632,12 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
   }
-  gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
+  gemm_nt<P>(ctx, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
   MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
   {
     const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
@@ -669,7 +670,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   }
   MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
   hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->lam_h[cur] + NC, 0.f, 8 * NC);
-  gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
+  gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = L - 1; l >= 0; --l) {
@@ -678,7 +679,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     float* lh = w->lam_h[cur ^ 1];
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(st, LdPlain{lh_next + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->lam_a + o, C, rows});
+      gemm_nt<P>(ctx, LdPlain{lh_next + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->lam_a + o, C, rows});
       MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next + o, C}, LdPlain{w->a[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
     }
     {
@@ -696,7 +697,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -728,6 +729,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_species = alloc_n<int32_t>(ctx, N)) != nullptr;
   ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
   w->paramsT = A(ctx->n_params);
+  if (cf.gemm_dtype == MLIP_GEMM_BF16) ok &= add_shadow(ctx, ctx->d_params, ctx->n_params) && add_shadow(ctx, w->paramsT, ctx->n_params);
   w->jphi = A(2 * E * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
   const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
@@ -745,6 +747,7 @@ int eqv_alloc(mlip_ctx* ctx) {
     w->Rho.push_back(AH(2 * E * PC));
     w->Wp.push_back(A((int64_t)PC * H));
     w->WpT.push_back(A((int64_t)PC * H));
+    if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
     w->Y1.push_back(A(E * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
   }

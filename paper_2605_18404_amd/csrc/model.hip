@@ -226,6 +226,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     tr(lo.V2, C, C);
   }
   if (!stage) tr(ctx->off_U, C, C);
+  if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights and of their transposes
 
   if (E > 0)
     hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
@@ -241,18 +242,18 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(st, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[0][l], w->SJ[0][l], H, 2 * E));
+        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[0][l], w->SJ[0][l], H, 2 * E));
       }
       const float* ulast = w->U[0][l];
       const __bf16* sjlast = w->SJ[0][l];
       if (d == 3) {
-        gemm_nt<P>(st, Act<P>::jet(w->U[0][l], w->SJ[0][l], H), th + lo.W[1], 2 * E, H, H, Act<P>::store(w->U[1][l], w->SJ[1][l], H, 2 * E));
+        gemm_nt<P>(ctx, Act<P>::jet(w->U[0][l], w->SJ[0][l], H), th + lo.W[1], 2 * E, H, H, Act<P>::store(w->U[1][l], w->SJ[1][l], H, 2 * E));
         ulast = w->U[1][l];
         sjlast = w->SJ[1][l];
       }
       {
         KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-        gemm_nt<P>(st, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Om[l]), w->env, C, 2 * E});
+        gemm_nt<P>(ctx, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Om[l]), w->env, C, 2 * E});
       }
     }
     {
@@ -260,13 +261,13 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
       hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
                          (int)N, C, w->a[l]);
     }
-    gemm_nt<P>(st, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
-    gemm_nt<P>(st, LdSilu{w->q[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->h[l + 1], w->h[l], C, N});
+    gemm_nt<P>(ctx, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
+    gemm_nt<P>(ctx, LdSilu{w->q[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->h[l + 1], w->h[l], C, N});
   }
   if (stage) {
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_out, w->h[L], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   } else {
-    gemm_nt<P>(st, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
+    gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
     hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
     hipLaunchKernelGGL(k_struct_sum, dim3(ctx->B), dim3(256), 0, st, w->eps, ctx->d_meta, E_out);
   }
@@ -288,13 +289,13 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   if (stage)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->mu_h[L], g_out, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   else  // mu_y = w_o silu'(y);  mu_h^L = mu_y U
-    gemm_nt<P>(st, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
+    gemm_nt<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
   hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
   const int rpb = 256 / (C / 4);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
-    gemm_nt<P>(st, LdPlain{w->mu_h[l + 1], C}, tT + lo.V2, N, C, C, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
-    gemm_nt<P>(st, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
+    gemm_nt<P>(ctx, LdPlain{w->mu_h[l + 1], C}, tT + lo.V2, N, C, C, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
+    gemm_nt<P>(ctx, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
       hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
@@ -334,8 +335,8 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
       hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
-    gemm_nt<P>(st, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
-    gemm_nt<P>(st, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
+    gemm_nt<P>(ctx, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
+    gemm_nt<P>(ctx, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
     // second-order weight gradients of the update MLP: mu_{h'}^T tdot, mu_q^T adot
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1], C}, LdDsiluMul{w->q[l], w->qd[l], C}, N, C, C, grad + lo.V2)));
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_q[l], C}, LdPlain{w->ad[l], C}, N, C, C, grad + lo.V1)));
@@ -348,11 +349,11 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiYZ<TX>{w->Y[d - 2][l], X2, ulast, H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiYZ<TX>{w->Y[d - 2][l], X2, ulast, H, E});
       }
       if (d == 3) {
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(st, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
@@ -362,7 +363,7 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   if (stage) {
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(hdot_out, w->hd[L], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   } else {
-    gemm_nt<P>(st, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
+    gemm_nt<P>(ctx, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
     MLIP_TRY((gemm_wgrad<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, LdPlain{w->hd[L], C}, N, C, C, grad + ctx->off_U)));
     {
       const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks);
@@ -399,17 +400,17 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
       hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
     }
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
-    gemm_nt<P>(st, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
+    gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   }
   const int rpb = 256 / (C / 4);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
     float* lh = w->lam_h[cur ^ 1];
-    gemm_nt<P>(st, LdPlain{lh_next, C}, tT + lo.V2, N, C, C, EpiLamQ{w->lam_q, w->q[l], w->qd[l], w->mu_t[l], C, N});
+    gemm_nt<P>(ctx, LdPlain{lh_next, C}, tT + lo.V2, N, C, C, EpiLamQ{w->lam_q, w->q[l], w->qd[l], w->mu_t[l], C, N});
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next, C}, LdSilu{w->q[l], C}, N, C, C, grad + lo.V2)));
     MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_q, C}, LdPlain{w->a[l], C}, N, C, C, grad + lo.V1)));
-    gemm_nt<P>(st, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
+    gemm_nt<P>(ctx, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
@@ -423,11 +424,11 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(st, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[d - 2][l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[d - 2][l], H, E});
       }
       if (d == 3) {
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(st, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
       } else {
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
@@ -465,6 +466,7 @@ int inv_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_species = alloc_n<int32_t>(ctx, N)) != nullptr;
   ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
   w->paramsT = A(ctx->n_params);
+  if (cf.gemm_dtype == MLIP_GEMM_BF16) ok &= add_shadow(ctx, ctx->d_params, ctx->n_params) && add_shadow(ctx, w->paramsT, ctx->n_params);
   w->jphi = A(2 * E * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
   const int64_t Wmax = std::max(C, H);

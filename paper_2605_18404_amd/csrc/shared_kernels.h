@@ -232,9 +232,29 @@ T* alloc_n(mlip_ctx* ctx, int64_t n) {
 
 // ------------------------------------------------------------------------------ GEMM wrappers
 // D[M][N] = A[M][K] * W[N][K]^T with loader / epilogue functors; tile chosen from N.
-template <typename P, typename LdA, typename Epi>
-void gemm_nt_as(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
-  LdPlain b{W, K};
+// ---- bf16 mirrors of the weights
+__global__ void k_to_bf16(const float* __restrict__ src, __bf16* __restrict__ dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = (__bf16)src[i];
+}
+inline bool add_shadow(mlip_ctx* ctx, const float* f32, int64_t n) {
+  __bf16* b = (__bf16*)ctx_alloc(ctx, (size_t)std::max<int64_t>(n, 1) * sizeof(__bf16));
+  if (!b) return false;
+  ctx->shadows.push_back({f32, b, n});
+  return true;
+}
+inline void refresh_shadows(mlip_ctx* ctx) {
+  for (const auto& sh : ctx->shadows)
+    hipLaunchKernelGGL(k_to_bf16, dim3((unsigned)((sh.n + 255) / 256)), dim3(256), 0, ctx->stream, sh.f32, sh.b16, sh.n);
+}
+inline const __bf16* shadow_of(const mlip_ctx* ctx, const float* p) {
+  for (const auto& sh : ctx->shadows)
+    if (p >= sh.f32 && p < sh.f32 + sh.n) return sh.b16 + (p - sh.f32);
+  return nullptr;
+}
+
+template <typename P, typename LdA, typename LdB, typename Epi>
+void gemm_nt_as(hipStream_t st, const LdA& a, const LdB& b, int64_t M, int N, int K, const Epi& epi) {
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   if (N > 64 && tiles128 >= 512)
     gemm::launch<P, 2, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
@@ -246,12 +266,23 @@ void gemm_nt_as(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, 
 inline bool wide_ok(const LdBf16& l, int64_t extent) {
   return l.ld % 8 == 0 && extent % 8 == 0 && (reinterpret_cast<uintptr_t>(l.p) & 15) == 0;
 }
+// D[M][N] = A[M][K] W[N][K]^T through the epilogue.  In bf16 mode the weights come from their
+// bf16 mirror when one is registered.
 template <typename P, typename LdA, typename Epi>
-void gemm_nt(hipStream_t st, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
-  if constexpr (std::is_same<LdA, LdBf16>::value) {
-    if (wide_ok(a, K)) return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, W, M, N, K, epi);
+void gemm_nt(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int K, const Epi& epi) {
+  hipStream_t st = ctx->stream;
+  if constexpr (P::IS_BF16) {
+    const __bf16* W16 = shadow_of(ctx, W);
+    const bool wb = W16 && wide_ok(LdBf16{W16, K}, K);
+    if constexpr (std::is_same<LdA, LdBf16>::value) {
+      if (wide_ok(a, K)) {
+        if (wb) return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, M, N, K, epi);
+        return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdPlain{W, K}, M, N, K, epi);
+      }
+    }
+    if (wb) return gemm_nt_as<P>(st, a, LdBf16x8{W16, K}, M, N, K, epi);
   }
-  gemm_nt_as<P>(st, a, W, M, N, K, epi);
+  gemm_nt_as<P>(st, a, LdPlain{W, K}, M, N, K, epi);
 }
 
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
