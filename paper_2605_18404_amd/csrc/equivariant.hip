@@ -512,6 +512,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
+  static_assert(sizeof(TF) == (P::IS_BF16 ? 2 : 4) && sizeof(typename Act<P>::xop_t) == sizeof(TF), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;

@@ -115,10 +115,15 @@ def train_cases():
         "cfg1_depth3_small": (synth.shrink(W[1], n_structs=2, atoms_per_struct=48, box=(48 / 0.08) ** (1 / 3) + 4.0, edge_depth=3, channels=64, edge_hidden=96), TOL_FP32),
         "cfg0_odd_sizes": (synth.shrink(W[0], channels=20, edge_hidden=36, n_rbf=12, atoms_per_struct=50, n_structs=3, n_layers=3), TOL_FP32),
         "cfg1_2structs_bf16": (synth.shrink(W[1], n_structs=2, gemm_bf16=True), TOL_BF16),
+        # widths that are multiples of 4 but not of 8: bf16 operands take the 8-byte staging path
+        "cfg0_odd_sizes_bf16": (synth.shrink(W[0], channels=36, edge_hidden=44, n_rbf=12, atoms_per_struct=50, n_structs=3,
+                                             n_layers=3, gemm_bf16=True), TOL_BF16),
         "eqv_tiny_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8, edge_hidden=8,
                                        n_rbf=8, n_layers=2, gemm_bf16=False), TOL_FP32),
         "eqv_multi_image_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
                                               edge_hidden=16, n_rbf=8, n_layers=3, gemm_bf16=False), TOL_FP32),
+        "eqv_multi_image_bf16": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                              edge_hidden=20, n_rbf=8, n_layers=3, gemm_bf16=True), TOL_BF16),
         "cfg2_2structs_fp32": (synth.shrink(W[2], n_structs=2, gemm_bf16=False), TOL_FP32),
         "cfg2_2structs_bf16": (synth.shrink(W[2], n_structs=2), TOL_BF16),
         "cfg4_shape_300atoms_bf16": (synth.shrink(W[4], atoms_per_struct=300, box=(300 / 0.1) ** (1 / 3), n_layers=2), TOL_BF16),
