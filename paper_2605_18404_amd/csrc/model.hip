@@ -72,6 +72,39 @@ __device__ __forceinline__ void fma4s(float4& acc, float s, float4 a, float4 b) 
   acc.x += s * a.x * b.x; acc.y += s * a.y * b.y; acc.z += s * a.z * b.z; acc.w += s * a.w * b.w;
 }
 
+// The four message kernels walk a receiver row's edges in order.  An edge needs its sender index
+// before it can gather the sender's node rows: two dependent memory round trips per edge if done
+// naively (counters showed the waves waiting 92 % of the time).  So the loops are software
+// pipelined in blocks of D edges: the sender indices are fetched two blocks ahead and all operands
+// of the next block are requested before the current block's arithmetic.  Indices past the row's
+// end are clamped to its last edge (a valid, redundant load), so no branch surrounds a load; only
+// the arithmetic and the stores of the tail are guarded.
+template <int D, typename In, typename Fetch, typename Use>
+__device__ __forceinline__ void walk_row(const int32_t* __restrict__ sender, int e0, int e1, Fetch fetch, Use use) {
+  if (e0 >= e1) return;
+  const int last = e1 - 1;
+  auto clamp = [&](int e) { return e < last ? e : last; };
+  In cur[D];
+  int jn[D];
+#pragma unroll
+  for (int k = 0; k < D; ++k) cur[k] = fetch(clamp(e0 + k), sender[clamp(e0 + k)]);
+#pragma unroll
+  for (int k = 0; k < D; ++k) jn[k] = sender[clamp(e0 + D + k)];
+  for (int e = e0; e < e1; e += D) {
+    In nxt[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) nxt[k] = fetch(clamp(e + D + k), jn[k]);
+#pragma unroll
+    for (int k = 0; k < D; ++k) jn[k] = sender[clamp(e + 2 * D + k)];
+#pragma unroll
+    for (int k = 0; k < D; ++k)
+      if (e + k < e1) use(e + k, cur[k]);
+#pragma unroll
+    for (int k = 0; k < D; ++k) cur[k] = nxt[k];
+  }
+}
+
+struct InFe { float4 w, hj; };
 template <typename TF>
 __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const TF* __restrict__ Om, const float* __restrict__ h, int N, int C,
@@ -80,15 +113,14 @@ __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_
   if (!t.active) return;
   const int c0 = 4 * t.cq;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
-#pragma unroll 4
-  for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    fma4(acc, ld4(Om + (int64_t)(2 * e) * C + c0), ld4(h + (int64_t)j * C + c0));
-  }
+  walk_row<4, InFe>(
+      sender, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int e, int j) { return InFe{ld4(Om + (int64_t)(2 * e) * C + c0), ld4(h + (int64_t)j * C + c0)}; },
+      [&](int, const InFe& c) { fma4(acc, c.w, c.hj); });
   *reinterpret_cast<float4*>(a + (int64_t)t.row * C + c0) = acc;
 }
 
+struct InFf { float4 w, wp, hj, maj, ge; };
 template <typename TF>
 __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const TF* __restrict__ Om,
@@ -104,18 +136,23 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
     const int64_t ro = (int64_t)t.row * C + c0;
     float4 acc = ld4(mu_h_next + ro);
     const float4 hi = ld4(h + ro), mai = ld4(mu_a + ro);
-    const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
-#pragma unroll 2
-    for (int e = e0; e < e1; ++e) {
-      int j = sender[e];
-      float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
-      float4 hj = ld4(h + (int64_t)j * C + c0), maj = ld4(mu_a + (int64_t)j * C + c0);
-      fma4(acc, w, maj);
-      float g = wp.x * (hj.x * mai.x + hi.x * maj.x) + wp.y * (hj.y * mai.y + hi.y * maj.y) +
-                wp.z * (hj.z * mai.z + hi.z * maj.z) + wp.w * (hj.w * mai.w + hi.w * maj.w);
-      float4 ge = geo[e];
-      f.x += g * ge.x; f.y += g * ge.y; f.z += g * ge.z;
-    }
+    walk_row<2, InFf>(
+        sender, row_ptr[t.row], row_ptr[t.row + 1],
+        [&](int e, int j) {
+          InFf x;
+          x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
+          x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+          x.hj = ld4(h + (int64_t)j * C + c0);
+          x.maj = ld4(mu_a + (int64_t)j * C + c0);
+          x.ge = geo[e];
+          return x;
+        },
+        [&](int, const InFf& c) {
+          fma4(acc, c.w, c.maj);
+          const float g = c.wp.x * (c.hj.x * mai.x + hi.x * c.maj.x) + c.wp.y * (c.hj.y * mai.y + hi.y * c.maj.y) +
+                          c.wp.z * (c.hj.z * mai.z + hi.z * c.maj.z) + c.wp.w * (c.hj.w * mai.w + hi.w * c.maj.w);
+          f.x += g * c.ge.x; f.y += g * c.ge.y; f.z += g * c.ge.z;
+        });
     *reinterpret_cast<float4*>(mu_h + ro) = acc;
   }
   red[threadIdx.x] = f;
@@ -132,10 +169,7 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
   }
 }
 
-__device__ __forceinline__ float rdot_of(const float4& ge, const float* __restrict__ v, int i, int j) {
-  return ge.x * (v[3 * j] - v[3 * i]) + ge.y * (v[3 * j + 1] - v[3 * i + 1]) + ge.z * (v[3 * j + 2] - v[3 * i + 2]);
-}
-
+struct InBf { float4 w, wp, hj, hdj, ge; float c, v0, v1, v2; };
 template <typename TX, typename TF>
 __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
@@ -149,23 +183,31 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
   const int64_t ro = (int64_t)t.row * C + c0;
   const float4 mai = ld4(mu_a + ro);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
-#pragma unroll 2
-  for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    float4 ge = geo[e];
-    float rd = rdot_of(ge, v, t.row, j);
-    float c = env[e].x;
-    float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
-    float4 hj = ld4(h + (int64_t)j * C + c0), hdj = ld4(hd + (int64_t)j * C + c0);
-    fma4s(acc, rd, wp, hj);
-    fma4(acc, w, hdj);
-    float s = rd * c;
-    st4(X + (int64_t)e * C + c0, make_float4(s * hj.x * mai.x, s * hj.y * mai.y, s * hj.z * mai.z, s * hj.w * mai.w));
-  }
+  const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
+  walk_row<2, InBf>(
+      sender, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int e, int j) {
+        InBf x;
+        x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
+        x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+        x.hj = ld4(h + (int64_t)j * C + c0);
+        x.hdj = ld4(hd + (int64_t)j * C + c0);
+        x.ge = geo[e];
+        x.c = env[e].x;
+        x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+        return x;
+      },
+      [&](int e, const InBf& c) {
+        const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
+        fma4s(acc, rd, c.wp, c.hj);
+        fma4(acc, c.w, c.hdj);
+        const float s = rd * c.c;
+        st4(X + (int64_t)e * C + c0, make_float4(s * c.hj.x * mai.x, s * c.hj.y * mai.y, s * c.hj.z * mai.z, s * c.hj.w * mai.w));
+      });
   *reinterpret_cast<float4*>(ad + ro) = acc;
 }
 
+struct InBe { float4 w, wp, hj, hdj, laj, maj, ge; float2 cc; float v0, v1, v2; };
 template <typename TX, typename TF>
 __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
@@ -180,26 +222,32 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
   const int64_t ro = (int64_t)t.row * C + c0;
   const float4 mai = ld4(mu_a + ro), lai = ld4(lam_a + ro);
   float4 acc = ld4(lam_h_next + ro);
-  const int e0 = row_ptr[t.row], e1 = row_ptr[t.row + 1];
-#pragma unroll 2
-  for (int e = e0; e < e1; ++e) {
-    int j = sender[e];
-    float4 ge = geo[e];
-    float rd = rdot_of(ge, v, t.row, j);
-    float2 cc = env[e];
-    float4 w = ld4(Om + (int64_t)(2 * e) * C + c0), wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
-    const int64_t jo = (int64_t)j * C + c0;
-    float4 hj = ld4(h + jo), hdj = ld4(hd + jo), laj = ld4(lam_a + jo), maj = ld4(mu_a + jo);
-    fma4(acc, w, laj);
-    fma4s(acc, rd, wp, maj);
-    float s = cc.y * rd;
-    float4 x;
-    x.x = cc.x * (hj.x * lai.x + hdj.x * mai.x) + s * hj.x * mai.x;
-    x.y = cc.x * (hj.y * lai.y + hdj.y * mai.y) + s * hj.y * mai.y;
-    x.z = cc.x * (hj.z * lai.z + hdj.z * mai.z) + s * hj.z * mai.z;
-    x.w = cc.x * (hj.w * lai.w + hdj.w * mai.w) + s * hj.w * mai.w;
-    st4(X + (int64_t)e * C + c0, x);
-  }
+  const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
+  walk_row<2, InBe>(
+      sender, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int e, int j) {
+        InBe x;
+        x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
+        x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+        const int64_t jo = (int64_t)j * C + c0;
+        x.hj = ld4(h + jo); x.hdj = ld4(hd + jo); x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
+        x.ge = geo[e];
+        x.cc = env[e];
+        x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+        return x;
+      },
+      [&](int e, const InBe& c) {
+        const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
+        fma4(acc, c.w, c.laj);
+        fma4s(acc, rd, c.wp, c.maj);
+        const float s = c.cc.y * rd;
+        float4 x;
+        x.x = c.cc.x * (c.hj.x * lai.x + c.hdj.x * mai.x) + s * c.hj.x * mai.x;
+        x.y = c.cc.x * (c.hj.y * lai.y + c.hdj.y * mai.y) + s * c.hj.y * mai.y;
+        x.z = c.cc.x * (c.hj.z * lai.z + c.hdj.z * mai.z) + s * c.hj.z * mai.z;
+        x.w = c.cc.x * (c.hj.w * lai.w + c.hdj.w * mai.w) + s * c.hj.w * mai.w;
+        st4(X + (int64_t)e * C + c0, x);
+      });
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
 }
 
