@@ -288,7 +288,7 @@ void gemm_nt(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int 
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
   int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
   int64_t s = std::max<int64_t>(1, 768 / tiles);
-  s = std::min<int64_t>(s, std::max<int64_t>(1, K / 256));
+  s = std::min<int64_t>(s, std::max<int64_t>(1, K / 64));
   return (int)std::min<int64_t>(s, 768);
 }
 
