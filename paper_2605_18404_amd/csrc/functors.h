@@ -161,6 +161,7 @@ __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(
 __device__ __forceinline__ float4 scale4(float s, float4 a) { return make_float4(s * a.x, s * a.y, s * a.z, s * a.w); }
 
 struct EpiStoreJetAct {  // u = v (fp32 jets) and the activated jets silu(u), silu'(u) u' rounded to bf16
+  static constexpr bool FOLD = false;
   float* u;
   __bf16* sj;
   int64_t ld, M;  // M = 2E
@@ -181,6 +182,7 @@ struct EpiStoreJetAct {  // u = v (fp32 jets) and the activated jets silu(u), si
   }
 };
 struct EpiStore {
+  static constexpr bool FOLD = false;
   float* p;
   int64_t ld, M;
   __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
@@ -190,6 +192,7 @@ struct EpiStore {
   }
 };
 struct EpiAddStore {  // p = add + v
+  static constexpr bool FOLD = false;
   float* p;
   const float* add;
   int64_t ld, M;
@@ -201,6 +204,7 @@ struct EpiAddStore {  // p = add + v
 };
 template <typename TO>
 struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  env[e] = (c, c')
+  static constexpr bool FOLD = false;
   TO* out;
   const float2* env;
   int64_t ld, M;  // M = 2E
@@ -212,6 +216,7 @@ struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  en
   }
 };
 struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
+  static constexpr bool FOLD = false;
   float* mu_t;
   float* mu_q;
   const float* q;
@@ -227,6 +232,7 @@ struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
 };
 template <typename TZ>
 struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld]); Z only ever feeds matrix products
+  static constexpr bool FOLD = false;
   float* Y;
   TZ* Z;
   const float* u;
@@ -255,6 +261,7 @@ __device__ __forceinline__ float4 lam4(float4 u0, float4 u1, float4 y, float4 v)
 }
 template <typename TZ>
 struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y; out only ever feeds matrix products
+  static constexpr bool FOLD = false;
   TZ* out;
   const float* u;
   const float* Y;
@@ -270,6 +277,7 @@ struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y; out only ever feeds matr
   }
 };
 struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
+  static constexpr bool FOLD = false;
   float* out;
   const float* q;
   const float* qd;
@@ -284,6 +292,7 @@ struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
   }
 };
 struct EpiPartial {  // split-k partial sums: part[z][row][col]
+  static constexpr bool FOLD = false;
   float* part;
   int64_t ld, M;
   __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int z) const {
@@ -291,6 +300,50 @@ struct EpiPartial {  // split-k partial sums: part[z][row][col]
     st4(part + o, a);
     if (r + 1 < M) st4(part + o + ld, b);
   }
+};
+
+// ---- folding epilogues: besides their element-wise work they hand the kernel a tile Z of values
+// (columns col..col+3 of rows r, r+1) whose product with a narrow per-row matrix B (<= 32 columns)
+// the kernel accumulates on the fly:  part[tile][c][k] = sum_{rows of the tile} Z[row][c] B[row][k].
+// This replaces a separate weight-gradient pass that would re-read Z from HBM (and, for Z that
+// nothing else needs, its store).  fold_b(row, k) returns B[row][k], zero outside the matrix.
+struct FoldB {
+  const float* b;  // B[row * ldb + k]
+  int ldb, K;      // K <= 32
+  float* part;     // [row tiles][N][K]
+};
+template <typename TZ>
+struct EpiYZFold {  // Y = v stored; Z = silu'(u[2e]) v folded with B
+  static constexpr bool FOLD = true;
+  float* Y;
+  const float* u;
+  int64_t ld, M;
+  FoldB f;
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int, float4& za, float4& zb) const {
+    const int64_t o = r * ld + col;
+    st4(Y + o, a);
+    za = mul4(dsilu4(ld4(u + 2 * o - col)), a);
+    if (r + 1 < M) {
+      st4(Y + o + ld, b);
+      zb = mul4(dsilu4(ld4(u + 2 * (o + ld) - col)), b);
+    }
+  }
+  __device__ __forceinline__ float fold_b(int64_t row, int k) const { return (row < M && k < f.K) ? f.b[row * f.ldb + k] : 0.f; }
+};
+template <typename TZ>
+struct EpiLamUFold {  // silu'(u) v + silu''(u) u' Y folded with B, not stored
+  static constexpr bool FOLD = true;
+  const float* u;
+  const float* Y;
+  int64_t ld, M;
+  FoldB f;
+  __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int, float4& za, float4& zb) const {
+    const int64_t o = r * ld + col;
+    const float* pu = u + 2 * r * ld + col;
+    za = lam4(ld4(pu), ld4(pu + ld), ld4(Y + o), a);
+    if (r + 1 < M) zb = lam4(ld4(pu + 2 * ld), ld4(pu + 3 * ld), ld4(Y + o + ld), b);
+  }
+  __device__ __forceinline__ float fold_b(int64_t row, int k) const { return (row < M && k < f.K) ? f.b[row * f.ldb + k] : 0.f; }
 };
 
 }  // namespace fx

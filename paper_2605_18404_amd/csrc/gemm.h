@@ -260,12 +260,30 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
   // own LDS region and reads it back so that a lane holds two consecutive rows x four consecutive
   // columns -- the functor then moves 16 bytes per access and a row's lanes cover whole lines.
   // (Every wave has passed the k loop's last barrier, so the operand stages are dead.)
+  // A folding functor (Epi::FOLD, fp32 products) returns a tile Z instead of storing it; Z goes
+  // back into the slab and Z^T B (B: <= 32 columns, one row per output row) is accumulated with
+  // MFMA over the slab's 32 rows: the slab is exactly the k-major operand layout for that product.
   float* eb = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
   constexpr int LPR = EW / 4;     // lanes across the slab's columns
   constexpr int PPP = 64 / LPR;   // row pairs per pass
   const int ecol = 4 * (lane % LPR), epair = lane / LPR;
+  constexpr bool FOLD = Epi::FOLD;
+  static_assert(!FOLD || !P::IS_BF16, "folding epilogues are fp32 products");
+  floatx16 gacc[FOLD ? TN : 1];
+  if constexpr (FOLD) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) gacc[j][q] = 0.f;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    float bv[FOLD ? 16 : 1];  // FOLD: this lane's B values for the slab's 32 rows, requested early
+    if constexpr (FOLD) {
+      const int64_t rbase = m0 + (wm * TM + i) * 32;
+#pragma unroll
+      for (int kk = 0; kk < 16; ++kk) bv[kk] = epi.fold_b(rbase + 2 * kk + g, li);
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -278,9 +296,50 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
       const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
       const int64_t row = m0 + (wm * TM + i) * 32 + rl;
       const int col = n0 + wn * EW + ecol;
-      if (row < M && col < N) epi(row, col, a, b, z);
+      if constexpr (FOLD) {
+        float4 za = make_float4(0.f, 0.f, 0.f, 0.f), zb = za;  // rows / columns outside the matrix contribute nothing
+        if (row < M && col < N) epi(row, col, a, b, z, za, zb);
+        *reinterpret_cast<float4*>(&eb[rl * ELD + ecol]) = za;  // the lane's own 2 x 4 patch
+        *reinterpret_cast<float4*>(&eb[(rl + 1) * ELD + ecol]) = zb;
+      } else {
+        if (row < M && col < N) epi(row, col, a, b, z);
+      }
+    }
+    if constexpr (FOLD) {
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int kk = 0; kk < 16; ++kk)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          gacc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(eb[(2 * kk + g) * ELD + j * 32 + li], bv[kk], gacc[j], 0, 0, 0);
     }
     __builtin_amdgcn_wave_barrier();
+  }
+  if constexpr (FOLD) {
+    // the WM waves that own the same columns add their blocks (fixed order), then one partial per
+    // workgroup: part[row tile][n0 + column][k]
+    static_assert(WM == 2 || WM == 1, "fold: one or two waves along the rows");
+    float* red = reinterpret_cast<float*>(smem);
+    __syncthreads();
+    if (WM == 2 && wm == 1) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) red[((wn * TN + j) * 16 + q) * 64 + lane] = gacc[j][q];
+    }
+    __syncthreads();
+    if (wm == 0) {
+      const int64_t tile = m0 / BM;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          float v = gacc[j][q];
+          if (WM == 2) v += red[((wn * TN + j) * 16 + q) * 64 + lane];
+          const int c = n0 + wn * EW + j * 32 + 8 * (q / 4) + 4 * g + q % 4;
+          if (c < N && li < epi.f.K) epi.f.part[(tile * N + c) * epi.f.K + li] = v;
+        }
+    }
   }
 }
 

@@ -396,17 +396,28 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::odd(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
-      {
+      // The last data-gradient product of the chain feeds only the gradient of the first edge
+      // matrix, Z^T phi' (K columns): fp32 folds that product into the epilogue (Z never reaches HBM).
+      const bool fold = !P::IS_BF16 && fold_ok(ctx, E, H, K);
+      const FoldB fb{w->jphi + K, 2 * K, K, nullptr};
+      if (d == 2) {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiYZ<TX>{w->Y[d - 2][l], X2, ulast, H, E});
-      }
-      if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+        if constexpr (!P::IS_BF16) {
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiYZFold<TX>{w->Y[0][l], ulast, H, E, fb}, grad + lo.W[0]);
+        }
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiYZ<TX>{w->Y[0][l], X2, ulast, H, E});
       } else {
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+        {
+          KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
+          gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[2], E, H, C, EpiYZ<TX>{w->Y[1][l], X2, ulast, H, E});
+        }
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        if constexpr (!P::IS_BF16) {
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZFold<TX>{w->Y[0][l], w->U[0][l], H, E, fb}, grad + lo.W[0]);
+        }
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
       }
+      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
   }
   if (stage) {
@@ -471,17 +482,27 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::even(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
       }
-      {
+      // as in BF: the last product of the chain is folded with phi (value rows) in fp32
+      const bool fold = !P::IS_BF16 && fold_ok(ctx, E, H, K);
+      const FoldB fb{w->jphi, 2 * K, K, nullptr};
+      if (d == 2) {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[d - 1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[d - 2][l], H, E});
-      }
-      if (d == 3) {
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
-        gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+        if constexpr (!P::IS_BF16) {
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiLamUFold<TX>{ulast, w->Y[0][l], H, E, fb}, grad + lo.W[0]);
+        }
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[0][l], H, E});
       } else {
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+        {
+          KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
+          gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[2], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[1][l], H, E});
+        }
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        if constexpr (!P::IS_BF16) {
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamUFold<TX>{w->U[0][l], w->Y[0][l], H, E, fb}, grad + lo.W[0]);
+        }
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
       }
+      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
     cur ^= 1;
   }
@@ -551,6 +572,7 @@ int inv_alloc(mlip_ctx* ctx) {
   };
   need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);  // atom-chunk partials
+  if (cf.gemm_dtype == MLIP_GEMM_FP32 && K <= 32) cap = std::max<int64_t>(cap, fold_partial_floats(E, H, K));  // folded first-matrix gradient
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);
   if (!ok) return MLIP_E_HIP;

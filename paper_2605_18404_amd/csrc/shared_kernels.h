@@ -285,6 +285,62 @@ void gemm_nt(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int 
   gemm_nt_as<P>(st, a, LdPlain{W, K}, M, N, K, epi);
 }
 
+// part2[g][i] = sum of part[z][i] over the g-th of G contiguous ranges of z (fixed order)
+__global__ void __launch_bounds__(256) k_reduce_ranges(const float* __restrict__ part, int splits, int64_t n, int G,
+                                                       float* __restrict__ part2) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int gi = blockIdx.y;
+  if (idx >= n) return;
+  const int per = (splits + G - 1) / G;
+  const int z0 = gi * per, z1 = min(splits, z0 + per);
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int z = z0;
+  for (; z + 3 < z1; z += 4) {
+    s0 += part[(int64_t)z * n + idx];
+    s1 += part[(int64_t)(z + 1) * n + idx];
+    s2 += part[(int64_t)(z + 2) * n + idx];
+    s3 += part[(int64_t)(z + 3) * n + idx];
+  }
+  for (; z < z1; ++z) s0 += part[(int64_t)z * n + idx];
+  part2[(int64_t)gi * n + idx] = (s0 + s1) + (s2 + s3);
+}
+
+// Floats of partial-sum space a folded product over R rows with N x Kb outputs needs (row tiles of
+// 64 in the worst case, plus the second reduction stage).
+constexpr int FOLD_GROUPS = 64;
+inline int64_t fold_partial_floats(int64_t R, int N, int Kb) { return ((R + 63) / 64 + FOLD_GROUPS) * (int64_t)N * Kb; }
+inline bool fold_ok(const mlip_ctx* ctx, int64_t R, int N, int Kb) {
+  return Kb <= 32 && fold_partial_floats(R, N, Kb) <= ctx->partial.cap;
+}
+
+// D = A W^T through a folding epilogue (fp32 products): besides D's element-wise consumers, the
+// product Z^T B of the epilogue's tile values with the narrow matrix B is accumulated per row tile
+// and added to gradB[N][Kb].  The functor's FoldB.part is pointed at the context's partial buffer.
+template <typename P, typename LdA, typename Epi>
+void gemm_nt_fold(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int K, Epi epi, float* gradB) {
+  static_assert(!P::IS_BF16, "folding epilogues are fp32 products");
+  hipStream_t st = ctx->stream;
+  epi.f.part = ctx->partial.buf;
+  const int Kb = epi.f.K;
+  const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+  int64_t tiles_m;
+  if (N > 64 && tiles128 >= 512) {
+    gemm::launch<P, 2, 2, 2, 2, true>(st, a, LdPlain{W, K}, epi, M, N, K, 1);
+    tiles_m = (M + 127) / 128;
+  } else {
+    gemm::launch<P, 1, 1, 2, 2, true>(st, a, LdPlain{W, K}, epi, M, N, K, 1);
+    tiles_m = (M + 63) / 64;
+  }
+  const int64_t n = (int64_t)N * Kb;
+  if (tiles_m > 4 * FOLD_GROUPS) {  // two stages, so that the reduction has enough workgroups
+    float* part2 = ctx->partial.buf + tiles_m * n;
+    hipLaunchKernelGGL(k_reduce_ranges, dim3(nblk(n), FOLD_GROUPS), dim3(256), 0, st, ctx->partial.buf, (int)tiles_m, n, FOLD_GROUPS, part2);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n, 64)), dim3(256), 0, st, part2, FOLD_GROUPS, n, gradB);
+  } else {
+    hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(n, 64)), dim3(256), 0, st, ctx->partial.buf, (int)tiles_m, n, gradB);
+  }
+}
+
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
   int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
   int64_t s = std::max<int64_t>(1, 768 / tiles);
