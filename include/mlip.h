@@ -69,7 +69,9 @@ typedef struct {
   int32_t edge_mlp_depth;   /* 2 or 3 */
   int32_t l_max;            /* 0 (invariant, stage) or 2 (equivariant) */
   int32_t gemm_dtype;       /* MLIP_GEMM_FP32, or MLIP_GEMM_BF16: both operands of every matrix
-                               product rounded to bf16 (nearest even), fp32 accumulation */
+                               product rounded to bf16 (nearest even), fp32 accumulation; the
+                               radial-filter jets (outputs of such a product) are also kept in
+                               bf16; node features, pre-activations and all sums stay fp32 */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */

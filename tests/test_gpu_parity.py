@@ -114,6 +114,9 @@ def train_cases():
         "cfg1_2structs": (synth.shrink(W[1], n_structs=2), TOL_FP32),
         "cfg1_depth3_small": (synth.shrink(W[1], n_structs=2, atoms_per_struct=48, box=(48 / 0.08) ** (1 / 3) + 4.0, edge_depth=3, channels=64, edge_hidden=96), TOL_FP32),
         "cfg0_odd_sizes": (synth.shrink(W[0], channels=20, edge_hidden=36, n_rbf=12, atoms_per_struct=50, n_structs=3, n_layers=3), TOL_FP32),
+        # more than 32 radial basis functions: the first-matrix gradient takes the separate product, not the folded one
+        "cfg1_small_K40": (synth.shrink(W[1], n_structs=2, atoms_per_struct=48, box=(48 / 0.08) ** (1 / 3) + 4.0, n_rbf=40,
+                                        channels=64, edge_hidden=64), TOL_FP32),
         "cfg1_2structs_bf16": (synth.shrink(W[1], n_structs=2, gemm_bf16=True), TOL_BF16),
         # widths that are multiples of 4 but not of 8: bf16 operands take the 8-byte staging path
         "cfg0_odd_sizes_bf16": (synth.shrink(W[0], channels=36, edge_hidden=44, n_rbf=12, atoms_per_struct=50, n_structs=3,
