@@ -182,7 +182,8 @@ def gaunt_tensors() -> List[torch.Tensor]:
 def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
     """Views into the flat float vector.  Layout (row-major [out, in], concatenated):
     whole models start with emb[S,C] and end with U[C,C], w_o[C]; each layer holds
-    invariant  W1[H,K], W2[C,H]  (depth 3: W1[H,K], W2[H,H], W3[C,H]),  V1[C,C], V2[C,C];
+    invariant  W1[H,K], W2[C,H]  (depth 3: W1[H,K], W2[H,H], W3[C,H]),  V1[C,C], V2[C,C]
+    (with n_experts > 0: expert banks V1[n_experts,C,C], V2[n_experts,C,C]);
     equivariant W1[H,K], W2[11 C,H] (row = path*C + channel), Wl0, Wl1, Wl2 [C,C];
     a stage holds the layer blocks only."""
     C, H, K, S = cfg["channels"], cfg["edge_hidden"], cfg["n_rbf"], cfg["n_species"]
@@ -200,7 +201,8 @@ def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
                 names += [(f"l{l}.W2", (H, H)), (f"l{l}.W3", (C, H))]
             else:
                 names.append((f"l{l}.W2", (C, H)))
-            names += [(f"l{l}.V1", (C, C)), (f"l{l}.V2", (C, C))]
+            vshape = (cfg["n_experts"], C, C) if cfg.get("n_experts", 0) > 0 else (C, C)
+            names += [(f"l{l}.V1", vshape), (f"l{l}.V2", vshape)]
     if kind != "stage":
         names += [("U", (C, C)), ("w_o", (C,))]
     out, off = {}, 0
@@ -233,8 +235,27 @@ class _SplitLinear(torch.autograd.Function):
 class _Lin:
     """Applies named weights; in split mode every linear map goes through _SplitLinear."""
 
-    def __init__(self, P: Dict[str, torch.Tensor], P_ff: Optional[Dict[str, torch.Tensor]] = None):
-        self.P, self.P_ff = P, P_ff
+    def __init__(self, P: Dict[str, torch.Tensor], P_ff: Optional[Dict[str, torch.Tensor]] = None,
+                 alpha: Optional[torch.Tensor] = None):
+        self.P, self.P_ff, self.alpha = P, P_ff, alpha
+        self.sid: Optional[torch.Tensor] = None  # structure of each atom (set by the model functions)
+
+    def mole(self, x: torch.Tensor, name: str) -> torch.Tensor:
+        """Mixture of linear experts (Sec. 5.1, "Models"): for every structure s the expert matrices of
+        the bank are averaged with that structure's coefficients, W_s = sum_k alpha[s,k] W_k, and the
+        temporary W_s is applied to the structure's atoms like any dense matrix."""
+        B = self.alpha.shape[0]
+        W = torch.einsum("bk,kij->bij", self.alpha, self.P[name])
+        Wf = None if self.P_ff is None else torch.einsum("bk,kij->bij", self.alpha, self.P_ff[name])
+        out = []
+        for b in range(B):
+            xb = x[self.sid == b]
+            out.append(xb @ W[b].t() if Wf is None else _SplitLinear.apply(xb, W[b], Wf[b]))
+        return torch.cat(out, dim=0)  # atoms are stored structure by structure
+
+    def node(self, x: torch.Tensor, name: str) -> torch.Tensor:
+        """The update MLP's matrices: expert banks when coefficients were given, else dense."""
+        return self.mole(x, name) if self.alpha is not None else self(x, name)
 
     def __call__(self, x: torch.Tensor, name: str) -> torch.Tensor:
         W = self.P[name]
@@ -275,7 +296,7 @@ def invariant_layer(h, l, lin: _Lin, cfg, snd, rcv, r):
         w = lin(t, f"l{l}.W2")
     m = envelope(r, cfg["cutoff"])[:, None] * w * h[snd]
     a = torch.zeros_like(h).index_add(0, rcv, m)
-    return h + lin(silu(lin(a, f"l{l}.V1")), f"l{l}.V2")
+    return h + lin.node(silu(lin.node(a, f"l{l}.V1")), f"l{l}.V2")
 
 
 def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
@@ -304,6 +325,7 @@ def energy(x, species, graph, cell, struct_ptr, lin: _Lin, cfg) -> torch.Tensor:
     N = x.shape[0]
     B = len(struct_ptr) - 1
     sid = torch.repeat_interleave(torch.arange(B), torch.as_tensor(np.diff(struct_ptr), dtype=torch.long))
+    lin.sid = sid
     snd, rcv, rv, r = edge_vectors(x, graph, cell, sid)
     emb = lin.P["emb"][torch.as_tensor(species, dtype=torch.long)]
     if cfg["kind"] == "equivariant":
@@ -329,20 +351,22 @@ def _t(a, grad=False):
 
 
 def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
-               graph: Optional[Dict] = None, split: bool = False) -> Dict[str, np.ndarray]:
+               graph: Optional[Dict] = None, split: bool = False, alpha=None) -> Dict[str, np.ndarray]:
     """One training step of the whole model: returns loss, E [B], F [N,3], grad [n_params]
-    (= dL/dtheta), and with split=True also grad_bf / grad_be, the BF and BE shares."""
+    (= dL/dtheta), and with split=True also grad_bf / grad_be, the BF and BE shares.
+    alpha [B, n_experts]: mixing coefficients of the expert banks (cfg["n_experts"] > 0)."""
     if graph is None:
         graph = radius_graph(pos, struct_ptr, cell, cfg["cutoff"])
     x = _t(pos, True)
     cellt = _t(cell)
     theta = _t(params, True)
     P = unpack_params(theta, cfg)
+    al = None if alpha is None else _t(alpha)
     if split:
         theta_ff = _t(params, True)
-        lin = _Lin(P, unpack_params(theta_ff, cfg))
+        lin = _Lin(P, unpack_params(theta_ff, cfg), alpha=al)
     else:
-        lin = _Lin(P)
+        lin = _Lin(P, alpha=al)
     E = energy(x, species, graph, cellt, struct_ptr, lin, cfg)
     (dEdx,) = torch.autograd.grad(E.sum(), x, create_graph=True)
     F = -dEdx
@@ -359,11 +383,11 @@ def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
     return out
 
 
-def energy_only(cfg, pos, species, struct_ptr, cell, params, graph=None) -> np.ndarray:
+def energy_only(cfg, pos, species, struct_ptr, cell, params, graph=None, alpha=None) -> np.ndarray:
     if graph is None:
         graph = radius_graph(pos, struct_ptr, cell, cfg["cutoff"])
     with torch.no_grad():
-        lin = _Lin(unpack_params(_t(params), cfg))
+        lin = _Lin(unpack_params(_t(params), cfg), alpha=None if alpha is None else _t(alpha))
         return energy(_t(pos), species, graph, _t(cell), struct_ptr, lin, cfg).numpy()
 
 
@@ -430,4 +454,5 @@ def cfg_from_workload(w) -> Dict:
     kind = {0: "invariant", 1: "equivariant", 2: "stage"}[int(w.kind)]
     return dict(kind=kind, channels=w.channels, edge_hidden=w.edge_hidden, n_rbf=w.n_rbf,
                 n_species=w.n_species, n_layers=w.n_layers, edge_depth=w.edge_depth,
-                cutoff=float(w.cutoff), force_weight=float(w.force_weight))
+                cutoff=float(w.cutoff), force_weight=float(w.force_weight),
+                n_experts=int(getattr(w, "n_experts", 0)))

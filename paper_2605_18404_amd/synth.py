@@ -18,7 +18,7 @@ channels, layers) rather than the chemistry.
 from __future__ import annotations
 
 from dataclasses import dataclass, field, replace
-from typing import Dict, List, Tuple
+from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
@@ -28,6 +28,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 
 STREAM_POS, STREAM_SPECIES, STREAM_PARAMS, STREAM_EREF, STREAM_FREF = 1, 2, 3, 4, 5
 STREAM_H_IN, STREAM_G_OUT, STREAM_HDOT_IN, STREAM_V, STREAM_LAM_OUT = 6, 7, 8, 9, 10
+STREAM_ALPHA = 12  # (11 is taken by the graph-size recipe)
 
 BASE_SEED = 18404000
 
@@ -85,6 +86,7 @@ class Workload:
     gemm_bf16: bool
     force_weight: float = 10.0
     min_dist: float = 1.0
+    n_experts: int = 0        # > 0: the update MLP's matrices are banks of this many experts (invariant model)
 
     @property
     def seed(self) -> int:
@@ -203,8 +205,9 @@ def param_shapes(w: Workload) -> List[Tuple[str, Tuple[int, ...], int, int]]:
                 out.append((f"l{l}.W3", (C, H), H, C))
             else:
                 out.append((f"l{l}.W2", (C, H), H, C))
-            out.append((f"l{l}.V1", (C, C), C, C))
-            out.append((f"l{l}.V2", (C, C), C, C))
+            vshape = (w.n_experts, C, C) if w.n_experts > 0 else (C, C)
+            out.append((f"l{l}.V1", vshape, C, C))
+            out.append((f"l{l}.V2", vshape, C, C))
     if w.kind != KIND_STAGE:
         out.append(("U", (C, C), C, C))
         out.append(("w_o", (C,), C, 1))
@@ -248,6 +251,7 @@ class Inputs:
     E_ref: np.ndarray        # [B] f32
     F_ref: np.ndarray        # [N,3] f32
     stage: Dict[str, np.ndarray] = field(default_factory=dict)  # h_in, g_out, hdot_in, v, lam_out
+    alpha: Optional[np.ndarray] = None  # [B, n_experts] f32 mixing coefficients (rows sum to 1), n_experts > 0
 
 
 def make_inputs(w: Workload) -> Inputs:
@@ -266,7 +270,12 @@ def make_inputs(w: Workload) -> Inputs:
         stage["hdot_in"] = normal(w.seed, STREAM_HDOT_IN, 0, N * C).astype(np.float32).reshape(N, C)
         stage["v"] = normal(w.seed, STREAM_V, 0, N * 3).astype(np.float32).reshape(N, 3)
         stage["lam_out"] = normal(w.seed, STREAM_LAM_OUT, 0, N * C).astype(np.float32).reshape(N, C)
-    return Inputs(w, pos, species, struct_ptr, cell, draw_params(w), E_ref, F_ref, stage)
+    alpha = None
+    if w.n_experts > 0:
+        # stands in for a router's output: positive coefficients, one set per structure, summing to 1
+        a = np.exp(normal(w.seed, STREAM_ALPHA, 0, B * w.n_experts).reshape(B, w.n_experts))
+        alpha = (a / a.sum(axis=1, keepdims=True)).astype(np.float32)
+    return Inputs(w, pos, species, struct_ptr, cell, draw_params(w), E_ref, F_ref, stage, alpha)
 
 
 # ----------------------------------------------------------------------------- graph sizes

@@ -1,0 +1,135 @@
+"""Pins for the oracle's mixture-of-linear-experts update MLP (Sec. 5.1 "Models": expert matrices
+combined by weighted averaging into one temporary linear map per structure).
+
+None of these re-types the oracle's merge: they compare against the dense model run with
+matrices merged here by hand, against linearity of the gradient in the coefficients, and against
+central finite differences of the loss."""
+import numpy as np
+import pytest
+
+from oracle import mlip_oracle as O
+from paper_2605_18404_amd import synth
+
+
+def tiny(n_experts, **kw):
+    d = dict(n_structs=2, atoms_per_struct=9, box=7.0, cutoff=3.5, n_rbf=6, channels=4, edge_hidden=5, n_layers=2,
+             n_species=3, n_experts=n_experts)
+    d.update(kw)
+    return synth.shrink(synth.WORKLOADS[1], **d)
+
+
+def step(w, inp, params=None, alpha="inp", **kw):
+    cfg = O.cfg_from_workload(w)
+    a = inp.alpha if isinstance(alpha, str) else alpha
+    return O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params if params is None else params,
+                        inp.E_ref, inp.F_ref, alpha=a, **kw)
+
+
+def dense_params_from(w, inp, alpha_row):
+    """Flat parameter vector of the dense model whose V matrices are the bank merged with alpha_row."""
+    wd = synth.shrink(w, n_experts=0)
+    src, dst = synth.param_slices(w), synth.param_slices(wd)
+    out = np.zeros(synth.param_count(wd), np.float64)
+    for name, (off, shape) in dst.items():
+        o2, s2 = src[name]
+        blk = inp.params[o2:o2 + int(np.prod(s2))].astype(np.float64).reshape(s2)
+        if len(s2) == 3:  # a bank [n_experts, C, C]
+            blk = sum(float(alpha_row[k]) * blk[k] for k in range(s2[0]))
+        out[off:off + blk.size] = blk.ravel()
+    return wd, out
+
+
+def one_structure(w, inp, s):
+    n = w.atoms_per_struct
+    w1 = synth.shrink(w, n_structs=1)
+    sub = synth.Inputs(w1, inp.pos[s * n:(s + 1) * n], inp.species[s * n:(s + 1) * n], np.array([0, n], np.int32),
+                       inp.cell[s:s + 1], inp.params, inp.E_ref[s:s + 1], inp.F_ref[s * n:(s + 1) * n], {},
+                       None if inp.alpha is None else inp.alpha[s:s + 1])
+    return w1, sub
+
+
+def test_layout_and_coefficients():
+    w = tiny(3)
+    inp = synth.make_inputs(w)
+    C = w.channels
+    assert synth.param_slices(w)["l0.V1"][1] == (3, C, C)
+    assert synth.param_count(w) - synth.param_count(synth.shrink(w, n_experts=0)) == 2 * w.n_layers * 2 * C * C
+    assert inp.alpha.shape == (2, 3) and np.all(inp.alpha > 0)
+    np.testing.assert_allclose(inp.alpha.sum(1), 1.0, rtol=1e-6)
+
+
+def test_single_expert_is_the_dense_model():
+    w = tiny(1)
+    inp = synth.make_inputs(w)
+    np.testing.assert_array_equal(inp.alpha, 1.0)
+    wd = synth.shrink(w, n_experts=0)  # same flat vector: a bank of one matrix is that matrix
+    a = step(w, inp)
+    cfg = O.cfg_from_workload(wd)
+    b = O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref)
+    for k in ("E", "F", "grad"):
+        np.testing.assert_allclose(a[k], b[k], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("s", [0, 1])
+def test_equals_dense_model_with_hand_merged_matrices(s):
+    """Per structure: energies, forces and the gradient chain rule dL/dV_k = alpha_k dL/dW_merged."""
+    w = tiny(3)
+    inp = synth.make_inputs(w)
+    w1, sub = one_structure(w, inp, s)
+    got = step(w1, sub)
+    wd, pd = dense_params_from(w1, sub, sub.alpha[0])
+    ref = O.train_step(O.cfg_from_workload(wd), sub.pos, sub.species, sub.struct_ptr, sub.cell, pd, sub.E_ref, sub.F_ref)
+    np.testing.assert_allclose(got["E"], ref["E"], rtol=1e-11)
+    np.testing.assert_allclose(got["F"], ref["F"], rtol=1e-9, atol=1e-12)
+    src, dst = synth.param_slices(w1), synth.param_slices(wd)
+    for name, (off, shape) in dst.items():
+        o2, s2 = src[name]
+        g_dense = ref["grad"][off:off + int(np.prod(shape))].reshape(shape)
+        g_got = got["grad"][o2:o2 + int(np.prod(s2))].reshape(s2)
+        if len(s2) == 3:
+            for k in range(s2[0]):
+                np.testing.assert_allclose(g_got[k], float(sub.alpha[0, k]) * g_dense, rtol=1e-9, atol=1e-13)
+        else:
+            np.testing.assert_allclose(g_got, g_dense, rtol=1e-9, atol=1e-13)
+
+
+def test_one_hot_coefficients_select_one_expert_per_structure():
+    w = tiny(3)
+    inp = synth.make_inputs(w)
+    alpha = np.array([[0, 0, 1], [1, 0, 0]], np.float32)
+    got = step(w, inp, alpha=alpha)
+    for s, k in ((0, 2), (1, 0)):
+        w1, sub = one_structure(w, inp, s)
+        wd, pd = dense_params_from(w1, sub, np.eye(3)[k])
+        ref = O.energy_only(O.cfg_from_workload(wd), sub.pos, sub.species, sub.struct_ptr, sub.cell, pd)
+        np.testing.assert_allclose(got["E"][s], ref[0], rtol=1e-11)
+
+
+def test_batch_is_the_sum_of_its_structures():
+    """Structures do not interact, each sees only its own coefficients."""
+    w = tiny(2)
+    inp = synth.make_inputs(w)
+    got = step(w, inp)
+    for s in range(2):
+        w1, sub = one_structure(w, inp, s)
+        np.testing.assert_allclose(step(w1, sub)["E"][0], got["E"][s], rtol=1e-11)
+
+
+def test_gradient_against_finite_differences_and_split():
+    w = tiny(2)
+    inp = synth.make_inputs(w)
+    r = step(w, inp, split=True)
+    np.testing.assert_allclose(r["grad_bf"] + r["grad_be"], r["grad"], rtol=1e-12, atol=1e-15)
+    off, shape = synth.param_slices(w)["l1.V2"]
+    p64 = inp.params.astype(np.float64)
+    rng = np.random.default_rng(0)
+    for idx in rng.choice(int(np.prod(shape)), 4, replace=False):
+        i = off + int(idx)
+        h = 1e-5
+        pp, pm = p64.copy(), p64.copy()
+        pp[i] += h
+        pm[i] -= h
+        fd = (step(w, inp, params=pp)["loss"] - step(w, inp, params=pm)["loss"]) / (2 * h)
+        assert abs(fd - r["grad"][i]) <= 1e-6 * max(1.0, abs(fd)), (i, fd, r["grad"][i])
+    # the second-order share is not identically zero for the banks: the update MLP sits inside dE/dx
+    assert np.abs(r["grad_bf"][off:off + int(np.prod(shape))]).max() > 0
