@@ -72,6 +72,9 @@ typedef struct {
                                product rounded to bf16 (nearest even), fp32 accumulation; the
                                radial-filter jets (outputs of such a product) are also kept in
                                bf16; node features, pre-activations and all sums stay fp32 */
+  int32_t n_experts;        /* 0: dense.  > 0 (invariant whole model only): the two matrices of every
+                               layer's update MLP are banks [n_experts][C][C] in the parameter vector,
+                               merged per structure with mlip_set_expert_weights' coefficients */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */
@@ -109,6 +112,16 @@ int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_stru
 /* Copies the current graph into caller buffers (any may be NULL): row_ptr[N+1], sender[E],
  * shift[E,3] (int32 components in {-1,0,1}), rev[E] (index of the opposite edge j <- i, -S). */
 int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+
+/* Mixture of linear experts (Sec. 5.1 "Models": expert weight matrices combined by weighted
+ * averaging into a temporary linear map).  alpha: device pointer [n_structs][n_experts], row s =
+ * the coefficients of structure s, copied into the context asynchronously on the stream.  The
+ * next mlip_forward_energy merges every bank per structure, W_s = sum_k alpha[s][k] W_k, and all
+ * four phases use W_s for the atoms of s; BF and BE add alpha[s][k] * dL/dW_s into expert k's
+ * slice of grad_params.  Required before mlip_forward_energy / mlip_train_step when the context
+ * has n_experts > 0 (MLIP_E_STATE otherwise), with n_structs equal to the graph's; MLIP_E_INVALID
+ * for a dense context.  The gradient with respect to alpha is not produced. */
+int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs);
 
 /* FE.  Whole model: h^0 = emb[species], E[B] written.  Stage: h_in[N,C] read, h_out[N,C]
  * written, species and E may be NULL.  pos and params are copied into the context, so the

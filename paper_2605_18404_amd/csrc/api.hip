@@ -60,8 +60,9 @@ int layout_params(mlip_ctx* ctx) {
     } else {
       if (c.edge_mlp_depth == 3) { lo.W[1] = off; off += H * H; lo.W[2] = off; off += C * H; }
       else { lo.W[1] = off; off += C * H; lo.W[2] = -1; }
-      lo.V1 = off; off += C * C;
-      lo.V2 = off; off += C * C;
+      const int64_t banks = c.n_experts > 0 ? c.n_experts : 1;  // expert banks [n_experts][C][C]
+      lo.V1 = off; off += banks * C * C;
+      lo.V2 = off; off += banks * C * C;
     }
   }
   if (c.model_kind != MLIP_MODEL_STAGE) { ctx->off_U = off; off += C * C; ctx->off_wo = off; off += C; }
@@ -85,6 +86,8 @@ const char* check_config(const mlip_config& c) {
     return "l_max must be 2 (edge_mlp_depth 2) for the equivariant model and 0 otherwise";
   if (c.model_kind != MLIP_MODEL_STAGE && c.n_species < 1) return "n_species must be positive";
   if (c.gemm_dtype != MLIP_GEMM_FP32 && c.gemm_dtype != MLIP_GEMM_BF16) return "gemm_dtype must be 0 or 1";
+  if (c.n_experts < 0 || c.n_experts > 1024) return "n_experts must be in [0, 1024]";
+  if (c.n_experts > 0 && c.model_kind != MLIP_MODEL_INVARIANT) return "expert banks are built for the invariant whole model only";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
   if (c.max_atoms > 50000000 || c.max_edges > 2000000000LL) return "capacity too large for 32-bit indices";
@@ -140,6 +143,16 @@ int mlip_graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const fl
                      const float* cell, float cutoff, int64_t* n_edges_host) {
   if (!ctx) return MLIP_E_INVALID;
   return graph_build(ctx, n_atoms, n_structs, pos, struct_ptr, cell, cutoff, n_edges_host);
+}
+
+int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (ctx->cfg.n_experts <= 0) MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weights: the context has no expert banks");
+  if (!alpha || n_structs < 1 || n_structs > ctx->cfg.max_structs) MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weights: bad arguments");
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_alpha, alpha, sizeof(float) * (size_t)n_structs * ctx->cfg.n_experts,
+                                     hipMemcpyDeviceToDevice, ctx->stream));
+  ctx->alpha_structs = n_structs;
+  return MLIP_OK;
 }
 
 int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host) {

@@ -49,6 +49,7 @@ struct Raw2 { float4 a, b; };
 struct LdPlain {  // p[row * ld + col]
   static constexpr bool PAIRED = false;
   static constexpr int WIDTH = 4;
+  __device__ __forceinline__ void shift(int64_t elems) { p += elems; }  // another matrix of a stack
   typedef float4 Raw;
   const float* p;
   int64_t ld;
@@ -57,6 +58,7 @@ struct LdPlain {  // p[row * ld + col]
 };
 struct LdSilu {  // silu(p[row * ld + col])
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef float4 Raw;
   const float* p;
@@ -66,6 +68,7 @@ struct LdSilu {  // silu(p[row * ld + col])
 };
 struct LdJetSilu {  // jet matrix u [2E][W]: row 2e -> silu(u[2e]), row 2e+1 -> silu'(u[2e]) * u[2e+1], both at once
   static constexpr bool PAIRED = true;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* u;
@@ -89,6 +92,7 @@ struct LdJetSilu {  // jet matrix u [2E][W]: row 2e -> silu(u[2e]), row 2e+1 -> 
 };
 struct LdJetSiluEven {  // row e -> silu(u[2e])
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef float4 Raw;
   const float* u;
@@ -98,6 +102,7 @@ struct LdJetSiluEven {  // row e -> silu(u[2e])
 };
 struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* u;
@@ -110,6 +115,7 @@ struct LdJetSiluOdd {  // row e -> silu'(u[2e]) * u[2e+1]
 };
 struct LdDsiluMul {  // silu'(q[row]) * x[row]
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* q;
@@ -120,6 +126,7 @@ struct LdDsiluMul {  // silu'(q[row]) * x[row]
 };
 struct LdMuY {  // w_o[col] * silu'(y[row, col])
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef Raw2 Raw;
   const float* y;
@@ -131,6 +138,7 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
 
 struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by their producer)
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   typedef bf16x4_t Raw;
   const __bf16* p;
@@ -145,6 +153,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 struct LdBf16x8 {  // the same matrix fetched eight values (16 bytes) at a time and staged without conversion;
                    // needs ld, the extent along the contiguous index and the base address in multiples of 8 values
   static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 8;
   typedef bf16x8_t Raw;
   const __bf16* p;

@@ -152,9 +152,22 @@ struct Stager {
 // per compute unit hide each other's global-load latency.  Workgroups are dealt round-robin to
 // the 8 XCDs (each with its own L2): a group is one (row tile, k split), its column tiles go to
 // the same XCD one after the other, so the A rows are fetched into one L2 only.
+// Optional structure-wise variants (all pointers null = plain product):
+//   row_groups  (k-contiguous products): row tile t covers rows [row_groups[t].x, row_groups[t].y) of
+//               one group (a structure) and multiplies by that group's own B matrix, found
+//               b_stride elements further per group index row_groups[t].z; n_row_tiles entries.
+//   k_ranges    (k-strided products, one split per group): split z reduces over rows
+//               [k_ranges[z], k_ranges[z+1]); an empty range yields a zero partial.
+struct Groups {
+  const int4* row_groups = nullptr;
+  int64_t n_row_tiles = 0;
+  int64_t b_stride = 0;
+  const int32_t* k_ranges = nullptr;
+};
+
 template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
 __global__ void __launch_bounds__(256, P::WAVES)
-k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, int splits) {
+k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chunk, int splits, Groups grp) {
   static_assert(WM * WN == 4, "four waves per workgroup");
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
   typedef typename P::lds_t lds_t;
@@ -173,15 +186,26 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
   const int wm = wave / WN, wn = wave % WN;
   const int li = lane & 31, g = lane >> 5;
   const int tiles_n = (N + BN - 1) / BN;
-  const int64_t tiles_m = (M + BM - 1) / BM;
+  const int64_t tiles_m = grp.row_groups ? grp.n_row_tiles : (M_all + BM - 1) / BM;
   const int64_t local = blockIdx.x >> 3;
   const int64_t group = (local / tiles_n) * 8 + (blockIdx.x & 7);
   if (group >= tiles_m * splits) return;  // uniform for the workgroup, before any barrier
   const int z = (int)(group / tiles_m);
-  const int64_t m0 = (group % tiles_m) * BM;
+  int64_t m0 = (group % tiles_m) * BM, M = M_all;
+  if (grp.row_groups) {  // this tile's rows end with its structure; its B matrix is the structure's
+    const int4 rg = grp.row_groups[group % tiles_m];
+    m0 = rg.x;
+    M = rg.y;
+    epi.M = M;  // the functor's own bound for the second row of a pair is the tile's, too
+    ldb.shift((int64_t)rg.z * grp.b_stride);
+  }
   const int n0 = (int)(local % tiles_n) * BN;
-  const int64_t kb = (int64_t)z * k_chunk;
-  const int64_t ke = (kb + k_chunk < K) ? kb + k_chunk : K;
+  int64_t kb = (int64_t)z * k_chunk;
+  int64_t ke = (kb + k_chunk < K) ? kb + k_chunk : K;
+  if (grp.k_ranges) {
+    kb = grp.k_ranges[z];
+    ke = grp.k_ranges[z + 1];
+  }
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -193,11 +217,13 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
 
   Stager<P, BM, BK, KC, LdA> stA;
   Stager<P, BN, BK, KC, LdB> stB;
-  const int64_t nk = (ke - kb + BK - 1) / BK;  // >= 1: the launcher makes every split non-empty
-  stA.load(lda, m0, M, kb, ke, t);
-  stB.load(ldb, n0, N, kb, ke, t);
-  stA.store(lda, sA[0], t);
-  stB.store(ldb, sB[0], t);
+  const int64_t nk = (ke - kb + BK - 1) / BK;  // >= 1 except for an empty k range (then the tile is zero)
+  if (nk > 0) {                                // uniform for the workgroup
+    stA.load(lda, m0, M, kb, ke, t);
+    stB.load(ldb, n0, N, kb, ke, t);
+    stA.store(lda, sA[0], t);
+    stB.store(ldb, sB[0], t);
+  }
   __syncthreads();
   for (int64_t kt = 0; kt < nk; ++kt) {
     const int cur = (int)(kt & 1);
@@ -345,24 +371,27 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int64_t K, int64_t k_chunk, 
 
 // Returns the number of k splits actually used (every split is non-empty).
 template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
-inline int launch_bk(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
+inline int launch_bk(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits,
+                     const Groups& grp = Groups()) {
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
   if (M <= 0 || N <= 0 || K <= 0) return 0;
   if (splits < 1) splits = 1;
   int64_t k_chunk = (K + splits - 1) / splits;
   k_chunk = (k_chunk + BK - 1) / BK * BK;
-  splits = (int)((K + k_chunk - 1) / k_chunk);
-  const int64_t tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
+  if (!grp.k_ranges) splits = (int)((K + k_chunk - 1) / k_chunk);  // with k ranges: one split per range, as given
+  const int64_t tiles_n = (N + BN - 1) / BN, tiles_m = grp.row_groups ? grp.n_row_tiles : (M + BM - 1) / BM;
+  if (tiles_m <= 0) return 0;
   dim3 grid((unsigned)(((tiles_m * splits + 7) / 8) * 8 * tiles_n), 1, 1);
   hipLaunchKernelGGL((k_gemm<P, TM, TN, WM, WN, KC, BK, LdA, LdB, Epi>), grid, dim3(256), 0, st, a, b, e, M, N, K, k_chunk,
-                     splits);
+                     splits, grp);
   return splits;
 }
 
 // Stage depth by reduction length: short reductions (the radial basis) use a shallow stage.
 template <typename P, int TM, int TN, int WM, int WN, bool KC, typename LdA, typename LdB, typename Epi>
-inline int launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits) {
-  return launch_bk<P, TM, TN, WM, WN, KC, P::BK_BIG>(st, a, b, e, M, N, K, splits);
+inline int launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int64_t K, int splits,
+                  const Groups& grp = Groups()) {
+  return launch_bk<P, TM, TN, WM, WN, KC, P::BK_BIG>(st, a, b, e, M, N, K, splits, grp);
 }
 
 }  // namespace gemm

@@ -243,6 +243,11 @@ int graph_alloc(mlip_ctx* ctx) {
   bool ok = true;
   ok &= (ctx->d_meta = alloc_n<StructMeta>(ctx, B)) != nullptr;
   ok &= (ctx->d_atom_struct = alloc_n<int32_t>(ctx, N)) != nullptr;
+  if (ctx->cfg.n_experts > 0) {  // per-structure products of the expert banks
+    ok &= (ctx->d_alpha = alloc_n<float>(ctx, (int64_t)B * ctx->cfg.n_experts)) != nullptr;
+    ok &= (ctx->d_row_groups = alloc_n<int4>(ctx, N / 64 + B + 1)) != nullptr;
+    ok &= (ctx->d_struct_ptr = alloc_n<int32_t>(ctx, B + 1)) != nullptr;
+  }
   ok &= (ctx->d_atom_bin = alloc_n<int32_t>(ctx, N)) != nullptr;
   ok &= (ctx->d_bin_count = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
   ok &= (ctx->d_bin_start = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
@@ -313,6 +318,18 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
   const int n_bins = (int)bins;
 
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_meta, ctx->h_meta.data(), sizeof(StructMeta) * B, hipMemcpyHostToDevice, st));
+  if (ctx->cfg.n_experts > 0) {
+    // row tiles of at most 64 atoms, none straddling two structures (each structure has its own merged matrices)
+    ctx->h_row_groups.clear();
+    for (int s = 0; s < B; ++s)
+      for (int r = ctx->h_struct_ptr[s]; r < ctx->h_struct_ptr[s + 1]; r += 64)
+        ctx->h_row_groups.push_back(make_int4(r, std::min(r + 64, ctx->h_struct_ptr[s + 1]), s, 0));
+    ctx->n_row_groups = (int64_t)ctx->h_row_groups.size();  // <= N / 64 + B
+    if (ctx->n_row_groups > 0)
+      MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_row_groups, ctx->h_row_groups.data(), sizeof(int4) * ctx->n_row_groups,
+                                         hipMemcpyHostToDevice, st));
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_struct_ptr, struct_ptr, sizeof(int32_t) * (B + 1), hipMemcpyDeviceToDevice, st));
+  }
   MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_count, 0, sizeof(int32_t) * (n_bins + 1), st));
   MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_cursor, 0, sizeof(int32_t) * (n_bins + 1), st));
   MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_flag, 0, sizeof(int32_t) * 4, st));

@@ -32,6 +32,7 @@ struct InvWs {
   std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [E][2][H]
   std::vector<float*> Om;     // [E][2][C], in the operand precision (fp32 or bf16)
   std::vector<float*> Y[2];   // [E][H]  BF -> BE
+  std::vector<float*> Vm[2], VmT[2];  // expert banks merged per structure: [B][C][C] of V1 / V2 per layer, and transposed
   float* X = nullptr;         // [E][max(C,H)] scratch, operand precision
   float* X2 = nullptr;
   std::vector<float*> h, a, q, mu_h, mu_a, mu_q, mu_t, hd, ad, qd;
@@ -251,6 +252,26 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
 }
 
+// The update MLP's matrices V1 (which = 0) / V2 (which = 1) of layer l: dense, or merged per
+// structure from expert banks (then every product is structure-wise).
+template <typename P, typename LdA, typename Epi>
+void node_mm(mlip_ctx* ctx, int l, int which, bool transposed, const LdA& a, const Epi& epi) {
+  InvWs* w = ws_of(ctx);
+  const int C = ctx->cfg.channels;
+  const int64_t off = which ? ctx->lay[l].V2 : ctx->lay[l].V1;
+  if (ctx->cfg.n_experts > 0)
+    gemm_nt_grouped<P>(ctx, a, (transposed ? w->VmT : w->Vm)[which][l], ctx->N, C, C, epi);
+  else
+    gemm_nt<P>(ctx, a, (transposed ? w->paramsT : ctx->d_params) + off, ctx->N, C, C, epi);
+}
+template <typename P, typename LdA, typename LdB>
+int node_wgrad(mlip_ctx* ctx, int l, int which, const LdA& a, const LdB& b, float* grad) {
+  const int C = ctx->cfg.channels;
+  float* g = grad + (which ? ctx->lay[l].V2 : ctx->lay[l].V1);
+  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, ctx->N, C, C, g);
+  return gemm_wgrad<P>(ctx, a, b, ctx->N, C, C, g);
+}
+
 // ------------------------------------------------------------------------------ phases
 template <typename P>
 int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
@@ -271,8 +292,14 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     if (d == 3) { tr(lo.W[1], H, H); tr(lo.W[2], C, H); } else { tr(lo.W[1], C, H); }
-    tr(lo.V1, C, C);
-    tr(lo.V2, C, C);
+    if (cf.n_experts > 0) {
+      const dim3 grid(nblk((int64_t)C * C), (unsigned)((ctx->B + 15) / 16));
+      hipLaunchKernelGGL(k_merge_experts, grid, dim3(256), 0, st, ctx->d_alpha, th + lo.V1, ctx->B, cf.n_experts, C, w->Vm[0][l], w->VmT[0][l]);
+      hipLaunchKernelGGL(k_merge_experts, grid, dim3(256), 0, st, ctx->d_alpha, th + lo.V2, ctx->B, cf.n_experts, C, w->Vm[1][l], w->VmT[1][l]);
+    } else {
+      tr(lo.V1, C, C);
+      tr(lo.V2, C, C);
+    }
   }
   if (!stage) tr(ctx->off_U, C, C);
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights and of their transposes
@@ -310,8 +337,8 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
       hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
                          (int)N, C, w->a[l]);
     }
-    gemm_nt<P>(ctx, LdPlain{w->a[l], C}, th + lo.V1, N, C, C, EpiStore{w->q[l], C, N});
-    gemm_nt<P>(ctx, LdSilu{w->q[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->h[l + 1], w->h[l], C, N});
+    node_mm<P>(ctx, l, 0, false, LdPlain{w->a[l], C}, EpiStore{w->q[l], C, N});
+    node_mm<P>(ctx, l, 1, false, LdSilu{w->q[l], C}, EpiAddStore{w->h[l + 1], w->h[l], C, N});
   }
   if (stage) {
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_out, w->h[L], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
@@ -343,8 +370,8 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   const int rpb = 256 / (C / 4);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
-    gemm_nt<P>(ctx, LdPlain{w->mu_h[l + 1], C}, tT + lo.V2, N, C, C, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
-    gemm_nt<P>(ctx, LdPlain{w->mu_q[l], C}, tT + lo.V1, N, C, C, EpiStore{w->mu_a[l], C, N});
+    node_mm<P>(ctx, l, 1, true, LdPlain{w->mu_h[l + 1], C}, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
+    node_mm<P>(ctx, l, 0, true, LdPlain{w->mu_q[l], C}, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
       hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
@@ -384,11 +411,11 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
       hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
-    gemm_nt<P>(ctx, LdPlain{w->ad[l], C}, th + lo.V1, N, C, C, EpiStore{w->qd[l], C, N});
-    gemm_nt<P>(ctx, LdDsiluMul{w->q[l], w->qd[l], C}, th + lo.V2, N, C, C, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
+    node_mm<P>(ctx, l, 0, false, LdPlain{w->ad[l], C}, EpiStore{w->qd[l], C, N});
+    node_mm<P>(ctx, l, 1, false, LdDsiluMul{w->q[l], w->qd[l], C}, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
     // second-order weight gradients of the update MLP: mu_{h'}^T tdot, mu_q^T adot
-    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1], C}, LdDsiluMul{w->q[l], w->qd[l], C}, N, C, C, grad + lo.V2)));
-    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_q[l], C}, LdPlain{w->ad[l], C}, N, C, C, grad + lo.V1)));
+    MLIP_TRY((node_wgrad<P>(ctx, l, 1, LdPlain{w->mu_h[l + 1], C}, LdDsiluMul{w->q[l], w->qd[l], C}, grad)));
+    MLIP_TRY((node_wgrad<P>(ctx, l, 0, LdPlain{w->mu_q[l], C}, LdPlain{w->ad[l], C}, grad)));
     if (E > 0) {
       // X = rdot * mu_w (adjoint of the derivative row w').  Chain back through the jets' derivative rows.
       const float* ulast = w->U[d - 2][l];
@@ -467,10 +494,10 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
     float* lh = w->lam_h[cur ^ 1];
-    gemm_nt<P>(ctx, LdPlain{lh_next, C}, tT + lo.V2, N, C, C, EpiLamQ{w->lam_q, w->q[l], w->qd[l], w->mu_t[l], C, N});
-    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next, C}, LdSilu{w->q[l], C}, N, C, C, grad + lo.V2)));
-    MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_q, C}, LdPlain{w->a[l], C}, N, C, C, grad + lo.V1)));
-    gemm_nt<P>(ctx, LdPlain{w->lam_q, C}, tT + lo.V1, N, C, C, EpiStore{w->lam_a, C, N});
+    node_mm<P>(ctx, l, 1, true, LdPlain{lh_next, C}, EpiLamQ{w->lam_q, w->q[l], w->qd[l], w->mu_t[l], C, N});
+    MLIP_TRY((node_wgrad<P>(ctx, l, 1, LdPlain{lh_next, C}, LdSilu{w->q[l], C}, grad)));
+    MLIP_TRY((node_wgrad<P>(ctx, l, 0, LdPlain{w->lam_q, C}, LdPlain{w->a[l], C}, grad)));
+    node_mm<P>(ctx, l, 0, true, LdPlain{w->lam_q, C}, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
@@ -553,6 +580,8 @@ int inv_alloc(mlip_ctx* ctx) {
     w->Om.push_back(AH(2 * E * C));
     w->Y[0].push_back(A(E * H));
     w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);
+    if (cf.n_experts > 0)
+      for (int k = 0; k < 2; ++k) { w->Vm[k].push_back(A(B * C * C)); w->VmT[k].push_back(A(B * C * C)); }
     w->a.push_back(A(N * C)); w->q.push_back(A(N * C));
     w->mu_a.push_back(A(N * C)); w->mu_q.push_back(A(N * C)); w->mu_t.push_back(A(N * C));
     w->ad.push_back(A(N * C)); w->qd.push_back(A(N * C));
@@ -572,6 +601,7 @@ int inv_alloc(mlip_ctx* ctx) {
   };
   need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);  // atom-chunk partials
+  if (cf.n_experts > 0) cap = std::max<int64_t>(cap, B * (int64_t)C * C);  // one weight-gradient partial per structure
   if (cf.gemm_dtype == MLIP_GEMM_FP32 && K <= 32) cap = std::max<int64_t>(cap, fold_partial_floats(E, H, K));  // folded first-matrix gradient
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);
@@ -592,6 +622,8 @@ int inv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
   if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: build the graph first");
   if (!pos || !params) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: null pos or params");
   if (stage ? (!h_in || !h_out) : (!species || !E)) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: missing tensor for this model kind");
+  if (ctx->cfg.n_experts > 0 && ctx->alpha_structs != ctx->B)
+    MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: set the expert coefficients of this batch's structures first (mlip_set_expert_weights)");
   hipStream_t st = ctx->stream;
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));

@@ -389,6 +389,108 @@ int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, i
   return gemm_wgrad_as<P>(ctx, a, b, R, Nout, Kout, grad);
 }
 
+// ---- mixture of linear experts (Sec. 5.1 "Models"): the expert matrices of a bank are averaged
+// per structure into one temporary matrix, W_s = sum_k alpha[s][k] W_k, which is then used like
+// any dense matrix on the atoms of s.
+// Wm[s][i] and its transpose WmT[s][(i % C) * C + i / C], i < C*C.  Block: 256 entries x 16 structures.
+__global__ void __launch_bounds__(256) k_merge_experts(const float* __restrict__ alpha, const float* __restrict__ bank,
+                                                       int B, int Ke, int C, float* __restrict__ Wm,
+                                                       float* __restrict__ WmT) {
+  __shared__ float al[16][64];
+  const int64_t n = (int64_t)C * C, i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int s0 = blockIdx.y * 16;
+  float acc[16];
+#pragma unroll
+  for (int ss = 0; ss < 16; ++ss) acc[ss] = 0.f;
+  for (int k0 = 0; k0 < Ke; k0 += 64) {
+    __syncthreads();
+    for (int q = threadIdx.x; q < 16 * 64; q += 256) {
+      const int ss = q / 64, kk = q % 64;
+      al[ss][kk] = (s0 + ss < B && k0 + kk < Ke) ? alpha[(int64_t)(s0 + ss) * Ke + k0 + kk] : 0.f;
+    }
+    __syncthreads();
+    if (i < n) {
+      const int kn = min(64, Ke - k0);
+      for (int kk = 0; kk < kn; ++kk) {
+        const float v = bank[(int64_t)(k0 + kk) * n + i];
+#pragma unroll
+        for (int ss = 0; ss < 16; ++ss) acc[ss] = fmaf(al[ss][kk], v, acc[ss]);
+      }
+    }
+  }
+  if (i < n) {
+    const int64_t it = (i % C) * C + i / C;
+#pragma unroll
+    for (int ss = 0; ss < 16; ++ss)
+      if (s0 + ss < B) {
+        Wm[(int64_t)(s0 + ss) * n + i] = acc[ss];
+        WmT[(int64_t)(s0 + ss) * n + it] = acc[ss];
+      }
+  }
+}
+// grad_bank[k][i] += sum_s alpha[s][k] part[s][i]  (structures in order: deterministic).
+// Block: 256 entries x 16 experts.
+__global__ void __launch_bounds__(256) k_expert_grad(const float* __restrict__ alpha, const float* __restrict__ part, int B,
+                                                     int Ke, int64_t n, float* __restrict__ grad_bank) {
+  __shared__ float al[64][16];
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int k0 = blockIdx.y * 16;
+  float acc[16];
+#pragma unroll
+  for (int kk = 0; kk < 16; ++kk) acc[kk] = 0.f;
+  for (int s0 = 0; s0 < B; s0 += 64) {
+    __syncthreads();
+    for (int q = threadIdx.x; q < 64 * 16; q += 256) {
+      const int ss = q / 16, kk = q % 16;
+      al[ss][kk] = (s0 + ss < B && k0 + kk < Ke) ? alpha[(int64_t)(s0 + ss) * Ke + k0 + kk] : 0.f;
+    }
+    __syncthreads();
+    if (i < n) {
+      const int sn = min(64, B - s0);
+      for (int ss = 0; ss < sn; ++ss) {
+        const float p = part[(int64_t)(s0 + ss) * n + i];
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) acc[kk] = fmaf(al[ss][kk], p, acc[kk]);
+      }
+    }
+  }
+  if (i < n) {
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk)
+      if (k0 + kk < Ke) grad_bank[(int64_t)(k0 + kk) * n + i] += acc[kk];
+  }
+}
+
+// D = A W_s^T with the merged matrix of each row's structure (Wm [B][N*K]); 64-row tiles that end
+// with their structure (the context's row-group table).
+template <typename P, typename LdA, typename Epi>
+void gemm_nt_grouped(mlip_ctx* ctx, const LdA& a, const float* Wm, int64_t M, int N, int K, const Epi& epi) {
+  gemm::Groups g;
+  g.row_groups = ctx->d_row_groups;
+  g.n_row_tiles = ctx->n_row_groups;
+  g.b_stride = (int64_t)N * K;
+  gemm::launch<P, 1, 1, 2, 2, true>(ctx->stream, a, LdPlain{Wm, K}, epi, M, N, K, 1, g);
+}
+// Expert-bank gradient: one weight-gradient partial per structure (split z = structure z's
+// atoms), then grad_bank[k] += sum_s alpha[s][k] partial[s].
+template <typename P, typename LdA, typename LdB>
+int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad_bank) {
+  const int B = ctx->B, Ke = ctx->cfg.n_experts;
+  const int64_t n = (int64_t)Nout * Kout;
+  if (R <= 0 || B <= 0) return MLIP_OK;
+  if ((int64_t)B * n > ctx->partial.cap) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "expert gradient: partial buffer too small");
+  gemm::Groups g;
+  g.k_ranges = ctx->d_struct_ptr;
+  EpiPartial epi{ctx->partial.buf, Kout, Nout};
+  if (Nout > 64)
+    gemm::launch<P, 2, 2, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B, g);
+  else
+    gemm::launch<P, 1, 1, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B, g);
+  hipLaunchKernelGGL(k_expert_grad, dim3(nblk(n), (Ke + 15) / 16), dim3(256), 0, ctx->stream, ctx->d_alpha, ctx->partial.buf, B,
+                     Ke, n, grad_bank);
+  return MLIP_OK;
+}
+
 // Edge geometry and featurisation: unit vector, length, Gaussian basis jets, envelope jet.
 __global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
                                 const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,

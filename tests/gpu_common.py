@@ -32,6 +32,7 @@ class DevInputs:
         self.struct_ptr, self.cell = dev(inp.struct_ptr), dev(inp.cell)
         self.params, self.E_ref, self.F_ref = dev(inp.params), dev(inp.E_ref), dev(inp.F_ref)
         self.stage = {k: dev(v) for k, v in inp.stage.items()}
+        self.alpha = None if inp.alpha is None else dev(inp.alpha)
 
 
 def oracle_train_step(w, inp, split=False):
@@ -52,7 +53,8 @@ def oracle_train_step(w, inp, split=False):
         sub = dict(cfg)
         sub["force_weight"] = cfg["force_weight"] * (n / N) * B
         r = O.train_step(sub, inp.pos[a:b], inp.species[a:b], np.array([0, n], np.int32), inp.cell[s:s + 1],
-                         inp.params, inp.E_ref[s:s + 1], inp.F_ref[a:b], split=split)
+                         inp.params, inp.E_ref[s:s + 1], inp.F_ref[a:b], split=split,
+                         alpha=None if inp.alpha is None else inp.alpha[s:s + 1])
         E[s] = r["E"][0]
         F[a:b] = r["F"]
         loss += r["loss"] / B

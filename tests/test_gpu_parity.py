@@ -178,6 +178,84 @@ def test_train_step_on_a_gars_micro_batch():
     m.close()
 
 
+def mole_cases():
+    W = synth.WORKLOADS
+    return {
+        # three row tiles per structure, 5 experts (not a multiple of the kernels' blocks of 16)
+        "cfg1_3structs_5experts": (synth.shrink(W[1], n_structs=3, n_experts=5), TOL_FP32),
+        "cfg1_small_20experts_bf16": (synth.shrink(W[1], n_structs=4, atoms_per_struct=48, box=(48 / 0.08) ** (1 / 3) + 4.0,
+                                                   channels=64, edge_hidden=64, n_experts=20, gemm_bf16=True), TOL_BF16),
+    }
+
+
+@pytest.mark.parametrize("name", list(mole_cases()))
+def test_mixture_of_linear_experts_parity(name):
+    """Expert banks merged per structure (Sec. 5.1 "Models"): whole step against the oracle, BF/BE shares
+    of the bank gradients, and the state check of the coefficients."""
+    w, tol = mole_cases()[name]
+    inp = synth.make_inputs(w)
+    ref = oracle_train_step(w, inp, split=True)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    with pytest.raises(MlipError) as e:  # coefficients not set yet
+        m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    assert e.value.code == -4
+    m.mlip_set_expert_weights(d.alpha)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    _check_step(w, inp, out, ref, tol)
+    # phase by phase: the two shares of the gradient (Eq. 2), banks included
+    m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff)
+    E = m.mlip_forward_energy(d.pos, d.species, d.params)
+    F = m.mlip_forward_force()
+    _, Ebar, v = m.mlip_loss(E, F, d.E_ref, d.F_ref)
+    g_bf = torch.zeros(m.mlip_param_count(), device=DEV)
+    g_be = torch.zeros_like(g_bf)
+    m.mlip_backward_force(v, g_bf)
+    m.mlip_backward_energy(g_be, Ebar=Ebar)
+    torch.cuda.synchronize()
+    assert rel(g_bf.cpu().numpy(), ref["grad_bf"]) < tol
+    assert rel(g_be.cpu().numpy(), ref["grad_be"]) < tol
+    m.close()
+
+
+def test_mixture_of_linear_experts_ragged_batch_and_errors():
+    """Structures of 1, 70 and 5 atoms (one of them spans two row tiles), and the entry point's error paths."""
+    ns = [1, 70, 5]
+    w = synth.shrink(synth.WORKLOADS[1], channels=32, edge_hidden=32, n_layers=2, n_structs=len(ns), atoms_per_struct=1,
+                     n_experts=3)
+    boxes = [max(6.2, (n / 0.08) ** (1 / 3)) for n in ns]
+    pos = np.concatenate([synth.make_structure(w.seed, s, n, L, w.cutoff) for s, (n, L) in enumerate(zip(ns, boxes))])
+    N = pos.shape[0]
+    sp = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+    cell = np.stack([np.eye(3, dtype=np.float32) * np.float32(L) for L in boxes])
+    a = np.exp(synth.normal(w.seed, synth.STREAM_ALPHA, 0, len(ns) * 3).reshape(len(ns), 3))
+    inp = synth.Inputs(w, pos, synth.draw_species(w.seed, N, w.n_species, w.species_dist), sp, cell, synth.draw_params(w),
+                       synth.normal(w.seed, 4, 0, len(ns)).astype(np.float32),
+                       (0.1 * synth.normal(w.seed, 5, 0, 3 * N)).astype(np.float32).reshape(N, 3), {},
+                       (a / a.sum(1, keepdims=True)).astype(np.float32))
+    ref = oracle_train_step(w, inp)
+    m = Mlip.for_workload(w, max_atoms=N, max_structs=len(ns), max_edges=int(N * 120))
+    d = DevInputs(inp)
+    m.mlip_set_expert_weights(d.alpha)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    _check_step(w, inp, out, ref, TOL_FP32)
+    with pytest.raises(MlipError) as e:  # more structures than the context holds
+        m.mlip_set_expert_weights(torch.ones(len(ns) + 1, 3, device=DEV))
+    assert e.value.code == -1
+    m.mlip_set_expert_weights(d.alpha[:2].contiguous())  # coefficients for another batch size: the step refuses
+    with pytest.raises(MlipError) as e:
+        m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    assert e.value.code == -4
+    m.close()
+    dense = Mlip.for_workload(synth.shrink(w, n_experts=0), max_atoms=N, max_structs=len(ns), max_edges=int(N * 120))
+    with pytest.raises(MlipError) as e:
+        dense.mlip_set_expert_weights(d.alpha)
+    assert e.value.code == -1
+    dense.close()
+
+
 @pytest.mark.parametrize("which", ["invariant", "equivariant"])
 def test_phase_calls_and_gradient_split(which):
     """FE, FF, loss, BF, BE one by one; BF's and BE's shares of the gradient against the oracle's split (Eq. 2)."""
