@@ -118,8 +118,10 @@ def main():
     from paper_2605_18404_amd import synth
     from paper_2605_18404_amd.binding import Mlip
 
-    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4}[args.workload]
+    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg1_mole128": 1}[args.workload]
     w = synth.WORKLOADS[idx]
+    if args.workload == "cfg1_mole128":  # the bench batch with UMA's 128-expert banks in the update MLP (Table 4)
+        w = synth.shrink(w, n_experts=128, name="cfg1_invariant_batch_mole128")
     inp = synth.make_inputs(w)
     dev = "cuda:0"
     t = lambda a: torch.as_tensor(np.ascontiguousarray(a)).to(dev)
@@ -127,6 +129,8 @@ def main():
     d = dict(pos=t(inp.pos), species=t(inp.species), struct_ptr=t(inp.struct_ptr), cell=t(inp.cell),
              params=t(inp.params), E_ref=t(inp.E_ref), F_ref=t(inp.F_ref))
     st = {k: t(v) for k, v in inp.stage.items()}
+    if w.n_experts > 0:
+        m.mlip_set_expert_weights(t(inp.alpha))
     out = None
     grad = torch.zeros(m.mlip_param_count(), device=dev)
 
@@ -209,7 +213,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_bf16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "atoms": w.n_atoms, "structures": w.n_structs, "edges": E_edges,
                    "channels": w.channels, "layers": w.n_layers, "n_rbf": w.n_rbf, "cutoff": w.cutoff,
-                   "l_max": w.l_max, "edge_mlp_depth": w.edge_depth, "includes_graph_build": True,
+                   "l_max": w.l_max, "edge_mlp_depth": w.edge_depth, "n_experts": w.n_experts, "includes_graph_build": True,
                    "workspace_GB": m.mlip_workspace_bytes() / 1e9},
         "edges_per_s": E_edges / (ms * 1e-3),
         "phase_ms": {"graph": ph[0], "FE": ph[1], "FF": ph[2], "BF": ph[3], "BE": ph[4]},

@@ -49,6 +49,25 @@ def test_cfg1_full_batch_all_outputs():
     m.close()
 
 
+def test_cfg1_full_batch_128_experts():
+    """The bench batch with the update MLP as banks of 128 experts (Table 4: UMA's expert count),
+    all 32 structures against the oracle."""
+    w = synth.shrink(synth.WORKLOADS[1], n_experts=128)
+    inp = synth.make_inputs(w)
+    ref = oracle_train_step(w, inp)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    m.mlip_set_expert_weights(d.alpha)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    assert rel(out["E"].cpu().numpy(), ref["E"]) < TOL_FP32
+    assert rel(out["F"].cpu().numpy(), ref["F"]) < TOL_FP32
+    g = out["grad"].cpu().numpy()
+    assert rel(g, ref["grad"]) < TOL_FP32
+    assert max(per_tensor_rel(w, g, ref["grad"]).values()) < 3 * TOL_FP32
+    m.close()
+
+
 def test_cfg2_full_batch_sampled_structures():
     w = synth.WORKLOADS[2]
     inp = synth.make_inputs(w)
