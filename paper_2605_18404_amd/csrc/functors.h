@@ -10,7 +10,9 @@ namespace fx {
 
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float sigm(float x) { return 1.f / (1.f + __expf(-x)); }
+// hardware reciprocal (1 ulp): an IEEE division would expand into about ten more instructions, and vector
+// instructions in the matrix-product loops take issue slots away from the matrix pipeline
+__device__ __forceinline__ float sigm(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 __device__ __forceinline__ float silu(float x) { return x * sigm(x); }
 __device__ __forceinline__ float dsilu(float x) {
   float s = sigm(x);

@@ -234,18 +234,29 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chu
     const lds_t* a_s = sA[cur];
     const lds_t* b_s = sB[cur];
     if constexpr (!P::IS_BF16) {
+      // fragments of step kk+1 are read from LDS before the products of step kk are issued, so the
+      // LDS latency hides behind the matrix pipeline instead of stalling the wave every step
+      float af[2][TM], bf[2][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[0][i] = a_s[g * LDA + (wm * TM + i) * 32 + li];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[0][j] = b_s[g * LDB + (wn * TN + j) * 32 + li];
 #pragma unroll
       for (int kk = 0; kk < BK / 2; ++kk) {
-        float af[TM], bf[TN];
+        const int c = kk & 1, nx = c ^ 1;
+        if (kk + 1 < BK / 2) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = a_s[(2 * kk + g) * LDA + (wm * TM + i) * 32 + li];
+          for (int i = 0; i < TM; ++i) af[nx][i] = a_s[(2 * kk + 2 + g) * LDA + (wm * TM + i) * 32 + li];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = b_s[(2 * kk + g) * LDB + (wn * TN + j) * 32 + li];
+          for (int j = 0; j < TN; ++j) bf[nx][j] = b_s[(2 * kk + 2 + g) * LDB + (wn * TN + j) * 32 + li];
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads above the products (the scheduler would sink them)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[c][i], bf[c][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
