@@ -72,6 +72,10 @@ struct Stager {
   // KS: a k-row holds Q = ROWS/4 float4; idx -> (k = idx / Q,  rq = idx % Q)
   // Loads are unconditional: out-of-range coordinates are clamped to a valid element and the
   // value is discarded when the stage is written (no divergent branches around memory ops).
+  // FULL: the caller guarantees that the whole stage lies inside the matrix (interior tile, reduction
+  // length a multiple of BK): no clamping, no validity mask -- vector instructions saved here are
+  // issue slots returned to the matrix pipeline.
+  template <bool FULL>
   __device__ __forceinline__ void load(const Ld& ld, int64_t row0, int64_t n_rows, int64_t k0, int64_t k_end, int t) {
     ok = 0;
 #pragma unroll
@@ -79,24 +83,29 @@ struct Stager {
       const int idx = t + it * 256;
       if (NVT % 256 == 0 || idx < NVT) {
         int64_t r, c;
-        bool in;
+        bool in = true;
         if (KC) {
           r = row0 + RPI * (idx / Q); c = k0 + VW * (idx % Q);
-          in = r < n_rows && c < k_end;
-          r = r < n_rows ? r : n_rows - RPI;  // paired: the row count is even
-          c = c < k_end ? c : k_end - VW;
+          if (!FULL) {
+            in = r < n_rows && c < k_end;
+            r = r < n_rows ? r : n_rows - RPI;  // paired: the row count is even
+            c = c < k_end ? c : k_end - VW;
+          }
         } else {
           r = k0 + idx / Q; c = row0 + VW * (idx % Q);
-          in = c < n_rows && r < k_end;
-          r = r < k_end ? r : k_end - 1;
-          c = c < n_rows ? c : n_rows - VW;
+          if (!FULL) {
+            in = c < n_rows && r < k_end;
+            r = r < k_end ? r : k_end - 1;
+            c = c < n_rows ? c : n_rows - VW;
+          }
         }
         v[it] = ld.fetch(r, c);
-        ok |= (in ? 1u : 0u) << it;
+        if (!FULL) ok |= (in ? 1u : 0u) << it;
       }
     }
   }
 
+  template <bool FULL>
   __device__ __forceinline__ void store(const Ld& ld, typename P::lds_t* s, int t) const {
     constexpr int LD = TL::LD;
     typedef typename P::lds_t T;
@@ -107,12 +116,12 @@ struct Stager {
       const int a = idx / Q, b = idx % Q;  // KC: (row or row pair, kq); KS: (k, rq)
       if constexpr (VW == 8) {  // raw bf16, KC [row][k] or KS [k][row]: one 16-byte store, no conversion
         bf16x8 x = ld.finish(v[it]);
-        if (!((ok >> it) & 1u)) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (!FULL && !((ok >> it) & 1u)) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
         *reinterpret_cast<bf16x8*>(reinterpret_cast<__bf16*>(s) + a * LD + 8 * b) = x;
       } else if constexpr (PR) {
         float4 x, y;
         ld.finish(v[it], x, y);
-        if (!((ok >> it) & 1u)) x = y = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!FULL && !((ok >> it) & 1u)) x = y = make_float4(0.f, 0.f, 0.f, 0.f);
         if constexpr (TL::K_MAJOR) {  // fp32 [k][row]: rows 2a, 2a+1 are neighbours -> 8-byte stores
           float* f = reinterpret_cast<float*>(s);
           *reinterpret_cast<float2*>(f + (4 * b + 0) * LD + 2 * a) = make_float2(x.x, y.x);
@@ -127,7 +136,7 @@ struct Stager {
         }
       } else {
         float4 x = ld.finish(v[it]);
-        if (!((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!FULL && !((ok >> it) & 1u)) x = make_float4(0.f, 0.f, 0.f, 0.f);
         if constexpr (KC && TL::K_MAJOR) {  // fp32: transpose into [k][row]
           s[(4 * b + 0) * LD + a] = (T)x.x;
           s[(4 * b + 1) * LD + a] = (T)x.y;
@@ -218,19 +227,34 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chu
   Stager<P, BM, BK, KC, LdA> stA;
   Stager<P, BN, BK, KC, LdB> stB;
   const int64_t nk = (ke - kb + BK - 1) / BK;  // >= 1 except for an empty k range (then the tile is zero)
-  if (nk > 0) {                                // uniform for the workgroup
-    stA.load(lda, m0, M, kb, ke, t);
-    stB.load(ldb, n0, N, kb, ke, t);
-    stA.store(lda, sA[0], t);
-    stB.store(ldb, sB[0], t);
+  // interior tile with whole k-tiles: the stages need neither clamping nor masking (uniform choice)
+  const bool full = (m0 + BM <= M) && (n0 + BN <= N) && ((ke - kb) % BK == 0);
+  auto fetch_stage = [&](int64_t k0) {
+    if (full) {
+      stA.template load<true>(lda, m0, M, k0, ke, t);
+      stB.template load<true>(ldb, n0, N, k0, ke, t);
+    } else {
+      stA.template load<false>(lda, m0, M, k0, ke, t);
+      stB.template load<false>(ldb, n0, N, k0, ke, t);
+    }
+  };
+  auto write_stage = [&](int buf) {
+    if (full) {
+      stA.template store<true>(lda, sA[buf], t);
+      stB.template store<true>(ldb, sB[buf], t);
+    } else {
+      stA.template store<false>(lda, sA[buf], t);
+      stB.template store<false>(ldb, sB[buf], t);
+    }
+  };
+  if (nk > 0) {  // uniform for the workgroup
+    fetch_stage(kb);
+    write_stage(0);
   }
   __syncthreads();
   for (int64_t kt = 0; kt < nk; ++kt) {
     const int cur = (int)(kt & 1);
-    if (kt + 1 < nk) {
-      stA.load(lda, m0, M, kb + (kt + 1) * BK, ke, t);
-      stB.load(ldb, n0, N, kb + (kt + 1) * BK, ke, t);
-    }
+    if (kt + 1 < nk) fetch_stage(kb + (kt + 1) * BK);
     const lds_t* a_s = sA[cur];
     const lds_t* b_s = sB[cur];
     if constexpr (!P::IS_BF16) {
@@ -286,10 +310,7 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chu
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
       }
     }
-    if (kt + 1 < nk) {
-      stA.store(lda, sA[cur ^ 1], t);
-      stB.store(ldb, sB[cur ^ 1], t);
-    }
+    if (kt + 1 < nk) write_stage(cur ^ 1);
     __syncthreads();
   }
   // Epilogue through LDS.  Accumulator q of a 32x32 block is row 8*(q/4) + 4*g + q%4, column
