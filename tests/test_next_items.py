@@ -76,9 +76,46 @@ def test_gars_library_edge_cases():
         mlip_gars_pack(np.array([3, 1], np.int32), 0, 2, 0)
 
 
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def golden_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
 def test_graph_size_recipe_matches_table_3():
+    """The log-normal recipe against the statistics the paper prints for its mixed dataset (Table 3):
+    median and mean are matched by construction, the tail of a three-dataset mixture only roughly."""
+    t3 = {k: float(v) for k, v in golden_rows("table3_graph_sizes.txt")}
     s = np.concatenate([synth.draw_graph_sizes(k, total_atoms=200000) for k in range(3)])
-    assert abs(np.median(s) - 53) < 4 and abs(s.mean() - 85) < 6 and s.max() <= 905 and s.min() >= 1
+    assert abs(np.median(s) - t3["p50"]) < 4 and abs(s.mean() - t3["mean"]) < 6
+    assert s.max() <= t3["max"] and s.min() >= 1
+    assert abs(np.percentile(s, 90) - t3["p90"]) < 0.2 * t3["p90"]
+    assert abs(np.percentile(s, 99) - t3["p99"]) < 0.25 * t3["p99"]
+
+
+def test_bubble_model_on_every_row_of_table_5():
+    """The printed phase profile (Table 5): the ratios in parentheses follow from the milliseconds, the
+    partial order t_FE < t_FF < t_BE < t_BF holds, the naive schedule's bubble (Sec. 3) is positive, and the
+    three closed forms of Sec. 4.2 are mutually consistent (stage-doubled = half of intra + inter) and shrink
+    with the unit size k."""
+    rows = golden_rows("table5_phase_times.txt")
+    assert [r[0] for r in rows] == ["eSEN-220M", "eSEN-100M", "UMA-2.3B", "UMA-1.2B"]
+    for r in rows:
+        fe, ff, be, bf, rff, rbe, rbf = map(float, r[1:])
+        assert abs(ff / fe - rff) < 0.006 and abs(be / fe - rbe) < 0.006 and abs(bf / fe - rbf) < 0.006
+        assert fe < ff < be < bf
+        assert W.naive_bubble(fe, ff, bf, be) > 0
+        prev = None
+        for k in (8, 16, 32):
+            b = W.wavek_bubbles(fe, ff, bf, be, P=8, n_mb=32, k=k)
+            assert abs(b["stage_doubled"] - 0.5 * (b["intra_unit"] + b["inter_unit"])) < 1e-9
+            assert all(v >= -1e-12 for v in b.values())
+            if prev is not None:
+                assert all(b[key] < prev[key] for key in b)
+            prev = b
+        assert W.wavek_bubbles(fe, ff, bf, be, P=8, n_mb=32, k=32)["inter_unit"] == 0.0  # a single unit has no successor
 
 
 # ------------------------------------------------------------------ WaveK bubble model
