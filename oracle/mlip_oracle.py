@@ -184,7 +184,8 @@ def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
     whole models start with emb[S,C] and end with U[C,C], w_o[C]; each layer holds
     invariant  W1[H,K], W2[C,H]  (depth 3: W1[H,K], W2[H,H], W3[C,H]),  V1[C,C], V2[C,C]
     (with n_experts > 0: expert banks V1[n_experts,C,C], V2[n_experts,C,C]);
-    equivariant W1[H,K], W2[11 C,H] (row = path*C + channel), Wl0, Wl1, Wl2 [C,C];
+    equivariant W1[H,K], W2[11 C,H] (row = path*C + channel), Wl0, Wl1, Wl2 [C,C]
+    (with n_experts > 0: banks [n_experts,C,C]);
     a stage holds the layer blocks only."""
     C, H, K, S = cfg["channels"], cfg["edge_hidden"], cfg["n_rbf"], cfg["n_species"]
     kind = cfg["kind"]
@@ -195,7 +196,8 @@ def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
         names.append((f"l{l}.W1", (H, K)))
         if kind == "equivariant":
             names.append((f"l{l}.W2", (len(PATHS) * C, H)))
-            names += [(f"l{l}.Wl{k}", (C, C)) for k in range(3)]
+            wshape = (cfg["n_experts"], C, C) if cfg.get("n_experts", 0) > 0 else (C, C)
+            names += [(f"l{l}.Wl{k}", wshape) for k in range(3)]
         else:
             if cfg["edge_depth"] == 3:
                 names += [(f"l{l}.W2", (H, H)), (f"l{l}.W3", (C, H))]
@@ -315,7 +317,7 @@ def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
         parts[l3] = parts[l3] + R[:, p, :, None] * tp
     m = envelope(r, cfg["cutoff"])[:, None, None] * torch.cat(parts, dim=2)
     a = torch.zeros_like(h).index_add(0, rcv, m)
-    upd = [lin(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(3)]
+    upd = [lin.node(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(3)]
     return h + torch.cat(upd, dim=2)
 
 

@@ -86,7 +86,7 @@ class Workload:
     gemm_bf16: bool
     force_weight: float = 10.0
     min_dist: float = 1.0
-    n_experts: int = 0        # > 0: the update MLP's matrices are banks of this many experts (invariant model)
+    n_experts: int = 0        # > 0: the node-level matrices of every layer (update MLP / per-l mixing) are banks of this many experts
 
     @property
     def seed(self) -> int:
@@ -197,7 +197,7 @@ def param_shapes(w: Workload) -> List[Tuple[str, Tuple[int, ...], int, int]]:
             out.append((f"l{l}.W1", (H, K), K, H))
             out.append((f"l{l}.W2", (N_PATHS_LMAX2 * C, H), H, N_PATHS_LMAX2 * C))
             for lam in range(3):
-                out.append((f"l{l}.Wl{lam}", (C, C), C, C))
+                out.append((f"l{l}.Wl{lam}", (w.n_experts, C, C) if w.n_experts > 0 else (C, C), C, C))
         else:
             out.append((f"l{l}.W1", (H, K), K, H))
             if w.edge_depth == 3:

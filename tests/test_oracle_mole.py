@@ -11,11 +11,13 @@ from oracle import mlip_oracle as O
 from paper_2605_18404_amd import synth
 
 
-def tiny(n_experts, **kw):
+def tiny(n_experts, equivariant=False, **kw):
     d = dict(n_structs=2, atoms_per_struct=9, box=7.0, cutoff=3.5, n_rbf=6, channels=4, edge_hidden=5, n_layers=2,
              n_species=3, n_experts=n_experts)
+    if equivariant:
+        d.update(channels=3, edge_hidden=4, atoms_per_struct=7)
     d.update(kw)
-    return synth.shrink(synth.WORKLOADS[1], **d)
+    return synth.shrink(synth.WORKLOADS[2 if equivariant else 1], **d)
 
 
 def step(w, inp, params=None, alpha="inp", **kw):
@@ -58,8 +60,9 @@ def test_layout_and_coefficients():
     np.testing.assert_allclose(inp.alpha.sum(1), 1.0, rtol=1e-6)
 
 
-def test_single_expert_is_the_dense_model():
-    w = tiny(1)
+@pytest.mark.parametrize("eqv", [False, True])
+def test_single_expert_is_the_dense_model(eqv):
+    w = tiny(1, eqv)
     inp = synth.make_inputs(w)
     np.testing.assert_array_equal(inp.alpha, 1.0)
     wd = synth.shrink(w, n_experts=0)  # same flat vector: a bank of one matrix is that matrix
@@ -70,10 +73,10 @@ def test_single_expert_is_the_dense_model():
         np.testing.assert_allclose(a[k], b[k], rtol=1e-12, atol=1e-14)
 
 
-@pytest.mark.parametrize("s", [0, 1])
-def test_equals_dense_model_with_hand_merged_matrices(s):
+@pytest.mark.parametrize("s,eqv", [(0, False), (1, False), (1, True)])
+def test_equals_dense_model_with_hand_merged_matrices(s, eqv):
     """Per structure: energies, forces and the gradient chain rule dL/dV_k = alpha_k dL/dW_merged."""
-    w = tiny(3)
+    w = tiny(3, eqv)
     inp = synth.make_inputs(w)
     w1, sub = one_structure(w, inp, s)
     got = step(w1, sub)
@@ -115,12 +118,13 @@ def test_batch_is_the_sum_of_its_structures():
         np.testing.assert_allclose(step(w1, sub)["E"][0], got["E"][s], rtol=1e-11)
 
 
-def test_gradient_against_finite_differences_and_split():
-    w = tiny(2)
+@pytest.mark.parametrize("eqv", [False, True])
+def test_gradient_against_finite_differences_and_split(eqv):
+    w = tiny(2, eqv)
     inp = synth.make_inputs(w)
     r = step(w, inp, split=True)
     np.testing.assert_allclose(r["grad_bf"] + r["grad_be"], r["grad"], rtol=1e-12, atol=1e-15)
-    off, shape = synth.param_slices(w)["l1.V2"]
+    off, shape = synth.param_slices(w)["l0.Wl1" if eqv else "l1.V2"]
     p64 = inp.params.astype(np.float64)
     rng = np.random.default_rng(0)
     for idx in rng.choice(int(np.prod(shape)), 4, replace=False):
