@@ -72,9 +72,10 @@ typedef struct {
                                product rounded to bf16 (nearest even), fp32 accumulation; the
                                radial-filter jets (outputs of such a product) are also kept in
                                bf16; node features, pre-activations and all sums stay fp32 */
-  int32_t n_experts;        /* 0: dense.  > 0 (invariant whole model only): the two matrices of every
-                               layer's update MLP are banks [n_experts][C][C] in the parameter vector,
-                               merged per structure with mlip_set_expert_weights' coefficients */
+  int32_t n_experts;        /* 0: dense.  > 0 (whole models only): the node-level matrices of every layer
+                               (invariant: the update MLP's two; equivariant: the three per-l mixing
+                               matrices) are banks [n_experts][C][C] in the parameter vector, merged
+                               per structure with mlip_set_expert_weights' coefficients */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */

@@ -56,7 +56,8 @@ int layout_params(mlip_ctx* ctx) {
     if (c.model_kind == MLIP_MODEL_EQUIVARIANT) {
       lo.W[1] = off; off += MLIP_NPATH * C * H;
       lo.W[2] = -1;
-      for (int k = 0; k < 3; ++k) { lo.Wl[k] = off; off += C * C; }
+      const int64_t banks = c.n_experts > 0 ? c.n_experts : 1;  // expert banks [n_experts][C][C]
+      for (int k = 0; k < 3; ++k) { lo.Wl[k] = off; off += banks * C * C; }
     } else {
       if (c.edge_mlp_depth == 3) { lo.W[1] = off; off += H * H; lo.W[2] = off; off += C * H; }
       else { lo.W[1] = off; off += C * H; lo.W[2] = -1; }
@@ -87,7 +88,7 @@ const char* check_config(const mlip_config& c) {
   if (c.model_kind != MLIP_MODEL_STAGE && c.n_species < 1) return "n_species must be positive";
   if (c.gemm_dtype != MLIP_GEMM_FP32 && c.gemm_dtype != MLIP_GEMM_BF16) return "gemm_dtype must be 0 or 1";
   if (c.n_experts < 0 || c.n_experts > 1024) return "n_experts must be in [0, 1024]";
-  if (c.n_experts > 0 && c.model_kind != MLIP_MODEL_INVARIANT) return "expert banks are built for the invariant whole model only";
+  if (c.n_experts > 0 && c.model_kind == MLIP_MODEL_STAGE) return "expert banks are built for the whole models only";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
   if (c.max_atoms > 50000000 || c.max_edges > 2000000000LL) return "capacity too large for 32-bit indices";

@@ -105,9 +105,10 @@ struct mlip_ctx {
   float* d_alpha = nullptr;        // [max_structs][n_experts] coefficients (mlip_set_expert_weights)
   int32_t alpha_structs = -1;      // how many rows of d_alpha are set
   int4* d_row_groups = nullptr;    // row tiles of 64 atoms that never straddle a structure: (first, end, structure, 0)
-  int64_t n_row_groups = 0;
   std::vector<int4> h_row_groups;
-  int32_t* d_struct_ptr = nullptr; // [max_structs + 1] device copy of the graph's struct_ptr
+  std::vector<int32_t> h_k_ranges;
+  int32_t* d_struct_ptr = nullptr; // [copies * max_structs + 1] first row of every (copy, structure) block, then the end
+  int64_t n_row_groups = 0;        // row tiles per copy of the atom rows
 
   // ---- kernel timer (mlip_kernel_timer_select / _read): event pairs around one kernel's launches
   int timed_kernel = 0;

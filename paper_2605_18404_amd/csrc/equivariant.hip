@@ -37,6 +37,7 @@ struct EqvWs {
   std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [12 C][H]
   std::vector<float*> WpT;  // and their transpose [H][12 C]
   float* gWp = nullptr;     // [12 C][H] weight gradient in the regrouped row order
+  std::vector<float*> Wm[3], WmT[3];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
   float* cy = nullptr;      // [E][84] coupling coefficient x harmonic of the edge direction
   float* cyd = nullptr;     // [E][84] the same with the directional derivative of the harmonics (BF, BE)
   std::vector<float*> Y1;   // [E][H]  BF -> BE
@@ -503,6 +504,27 @@ __global__ void k_embed_l0(const float* __restrict__ emb, const int32_t* __restr
   h[idx] = (m == 0) ? emb[(int64_t)species[r / C] * C + (r % C)] : 0.f;
 }
 
+// The mixing matrix of degree k in layer l acting on the [(2k+1) N, C] block at offset o: dense, or
+// merged per structure from an expert bank (then every product is structure-wise).
+template <typename P, typename LdA, typename Epi>
+void mix_mm(mlip_ctx* ctx, int l, int k, bool transposed, const LdA& a, const Epi& epi) {
+  EqvWs* w = ws_of(ctx);
+  const int C = ctx->cfg.channels;
+  const int64_t rows = (2 * k + 1) * ctx->N;
+  if (ctx->cfg.n_experts > 0)
+    gemm_nt_grouped<P>(ctx, a, (transposed ? w->WmT : w->Wm)[k][l], rows, C, C, epi, 2 * k + 1);
+  else
+    gemm_nt<P>(ctx, a, (transposed ? w->paramsT : ctx->d_params) + ctx->lay[l].Wl[k], rows, C, C, epi);
+}
+template <typename P, typename LdA, typename LdB>
+int mix_wgrad(mlip_ctx* ctx, int l, int k, const LdA& a, const LdB& b, float* grad) {
+  const int C = ctx->cfg.channels;
+  const int64_t rows = (2 * k + 1) * ctx->N;
+  float* g = grad + ctx->lay[l].Wl[k];
+  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, rows, C, C, g, 2 * k + 1);
+  return gemm_wgrad<P>(ctx, a, b, rows, C, C, g);
+}
+
 // ------------------------------------------------------------------------------ phases
 constexpr int LOFF[3] = {0, 1, 4};
 
@@ -521,7 +543,13 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   };
   for (int l = 0; l < L; ++l) {
     hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, w->Wp[l], w->WpT[l]);
-    for (int k = 0; k < 3; ++k) tr(ctx->lay[l].Wl[k], C, C);
+    for (int k = 0; k < 3; ++k) {
+      if (cf.n_experts > 0)
+        hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
+                           th + ctx->lay[l].Wl[k], ctx->B, cf.n_experts, C, w->Wm[k][l], w->WmT[k][l]);
+      else
+        tr(ctx->lay[l].Wl[k], C, C);
+    }
   }
   tr(ctx->off_U, C, C);
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights, their transposes and the regrouped filters
@@ -551,7 +579,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(ctx, LdPlain{w->a[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
+      mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
   }
   gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
@@ -581,7 +609,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
     const LayerOffsets& lo = ctx->lay[l];
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(ctx, LdPlain{w->mu_h[l + 1] + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->mu_a[l] + o, C, rows});
+      mix_mm<P>(ctx, l, k, true, LdPlain{w->mu_h[l + 1] + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = uni ? k_tp_ff<TF, true> : k_tp_ff<TF, false>;
@@ -621,8 +649,8 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(ctx, LdPlain{w->ad[l] + o, C}, th + lo.Wl[k], rows, C, C, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->mu_h[l + 1] + o, C}, LdPlain{w->ad[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
+      mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
+      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{w->mu_h[l + 1] + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
     if (E > 0) {
       {
@@ -680,8 +708,8 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     float* lh = w->lam_h[cur ^ 1];
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      gemm_nt<P>(ctx, LdPlain{lh_next + o, C}, tT + lo.Wl[k], rows, C, C, EpiStore{w->lam_a + o, C, rows});
-      MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{lh_next + o, C}, LdPlain{w->a[l] + o, C}, rows, C, C, grad + lo.Wl[k])));
+      mix_mm<P>(ctx, l, k, true, LdPlain{lh_next + o, C}, EpiStore{w->lam_a + o, C, rows});
+      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lh_next + o, C}, LdPlain{w->a[l] + o, C}, grad)));
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
@@ -751,6 +779,8 @@ int eqv_alloc(mlip_ctx* ctx) {
     if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
     w->Y1.push_back(A(E * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
+    if (cf.n_experts > 0)
+      for (int k = 0; k < 3; ++k) { w->Wm[k].push_back(A(B * C * C)); w->WmT[k].push_back(A(B * C * C)); }
   }
   for (int l = 0; l <= L; ++l) { w->h.push_back(A(NC9)); w->mu_h.push_back(A(NC9)); w->hd.push_back(A(NC9)); }
   w->lam_h[0] = A(NC9); w->lam_h[1] = A(NC9); w->lam_a = A(NC9);
@@ -764,6 +794,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   };
   need(PC, H, E); need(H, K, E); need(C, C, 5 * N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);
+  if (cf.n_experts > 0) cap = std::max<int64_t>(cap, 5 * B * (int64_t)C * C);  // one weight-gradient partial per (component, structure)
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);
   return ok ? MLIP_OK : MLIP_E_HIP;
@@ -780,6 +811,8 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
                        float* E, float*) {
   if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: build the graph first");
   if (!pos || !params || !species || !E) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_energy: null pointer");
+  if (ctx->cfg.n_experts > 0 && ctx->alpha_structs != ctx->B)
+    MLIP_FAIL(ctx, MLIP_E_STATE, "forward_energy: set the expert coefficients of this batch's structures first (mlip_set_expert_weights)");
   hipStream_t st = ctx->stream;
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));

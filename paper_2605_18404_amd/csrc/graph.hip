@@ -245,8 +245,10 @@ int graph_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_atom_struct = alloc_n<int32_t>(ctx, N)) != nullptr;
   if (ctx->cfg.n_experts > 0) {  // per-structure products of the expert banks
     ok &= (ctx->d_alpha = alloc_n<float>(ctx, (int64_t)B * ctx->cfg.n_experts)) != nullptr;
-    ok &= (ctx->d_row_groups = alloc_n<int4>(ctx, N / 64 + B + 1)) != nullptr;
-    ok &= (ctx->d_struct_ptr = alloc_n<int32_t>(ctx, B + 1)) != nullptr;
+    // the equivariant model stacks up to five copies of the atom rows (components m of one l)
+    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 5 : 1;
+    ok &= (ctx->d_row_groups = alloc_n<int4>(ctx, copies * (N / 64 + B + 1))) != nullptr;
+    ok &= (ctx->d_struct_ptr = alloc_n<int32_t>(ctx, copies * B + 1)) != nullptr;
   }
   ok &= (ctx->d_atom_bin = alloc_n<int32_t>(ctx, N)) != nullptr;
   ok &= (ctx->d_bin_count = alloc_n<int32_t>(ctx, ctx->max_bins + 1)) != nullptr;
@@ -320,15 +322,24 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_meta, ctx->h_meta.data(), sizeof(StructMeta) * B, hipMemcpyHostToDevice, st));
   if (ctx->cfg.n_experts > 0) {
     // row tiles of at most 64 atoms, none straddling two structures (each structure has its own merged matrices)
+    // The equivariant model multiplies [(2l+1) N, C] matrices (component-major copies of the atom rows):
+    // copy m of the tables is shifted by m N rows; a product over 2l+1 copies uses the first 2l+1.
+    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 5 : 1;
     ctx->h_row_groups.clear();
-    for (int s = 0; s < B; ++s)
-      for (int r = ctx->h_struct_ptr[s]; r < ctx->h_struct_ptr[s + 1]; r += 64)
-        ctx->h_row_groups.push_back(make_int4(r, std::min(r + 64, ctx->h_struct_ptr[s + 1]), s, 0));
-    ctx->n_row_groups = (int64_t)ctx->h_row_groups.size();  // <= N / 64 + B
-    if (ctx->n_row_groups > 0)
-      MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_row_groups, ctx->h_row_groups.data(), sizeof(int4) * ctx->n_row_groups,
+    ctx->h_k_ranges.assign((size_t)copies * B + 1, 0);
+    for (int m = 0; m < copies; ++m)
+      for (int s = 0; s < B; ++s) {
+        ctx->h_k_ranges[(size_t)m * B + s] = (int32_t)(m * N + ctx->h_struct_ptr[s]);
+        for (int r = ctx->h_struct_ptr[s]; r < ctx->h_struct_ptr[s + 1]; r += 64)
+          ctx->h_row_groups.push_back(make_int4((int)(m * N + r), (int)(m * N + std::min(r + 64, ctx->h_struct_ptr[s + 1])), s, 0));
+      }
+    ctx->h_k_ranges[(size_t)copies * B] = (int32_t)(copies * N);
+    ctx->n_row_groups = (int64_t)ctx->h_row_groups.size() / copies;  // per copy: <= N / 64 + B
+    if (!ctx->h_row_groups.empty())
+      MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_row_groups, ctx->h_row_groups.data(), sizeof(int4) * ctx->h_row_groups.size(),
                                          hipMemcpyHostToDevice, st));
-    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_struct_ptr, struct_ptr, sizeof(int32_t) * (B + 1), hipMemcpyDeviceToDevice, st));
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_struct_ptr, ctx->h_k_ranges.data(), sizeof(int32_t) * ctx->h_k_ranges.size(),
+                                       hipMemcpyHostToDevice, st));
   }
   MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_count, 0, sizeof(int32_t) * (n_bins + 1), st));
   MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_bin_cursor, 0, sizeof(int32_t) * (n_bins + 1), st));

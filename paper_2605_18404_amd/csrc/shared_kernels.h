@@ -430,23 +430,26 @@ __global__ void __launch_bounds__(256) k_merge_experts(const float* __restrict__
 }
 // grad_bank[k][i] += sum_s alpha[s][k] part[s][i]  (structures in order: deterministic).
 // Block: 256 entries x 16 experts.
+// part holds `copies` blocks of B partials (block m = component copy m of the atom rows); partial
+// z belongs to structure z % B.
 __global__ void __launch_bounds__(256) k_expert_grad(const float* __restrict__ alpha, const float* __restrict__ part, int B,
-                                                     int Ke, int64_t n, float* __restrict__ grad_bank) {
+                                                     int copies, int Ke, int64_t n, float* __restrict__ grad_bank) {
   __shared__ float al[64][16];
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int k0 = blockIdx.y * 16;
   float acc[16];
 #pragma unroll
   for (int kk = 0; kk < 16; ++kk) acc[kk] = 0.f;
-  for (int s0 = 0; s0 < B; s0 += 64) {
+  const int Z = B * copies;
+  for (int s0 = 0; s0 < Z; s0 += 64) {
     __syncthreads();
     for (int q = threadIdx.x; q < 64 * 16; q += 256) {
       const int ss = q / 16, kk = q % 16;
-      al[ss][kk] = (s0 + ss < B && k0 + kk < Ke) ? alpha[(int64_t)(s0 + ss) * Ke + k0 + kk] : 0.f;
+      al[ss][kk] = (s0 + ss < Z && k0 + kk < Ke) ? alpha[(int64_t)((s0 + ss) % B) * Ke + k0 + kk] : 0.f;
     }
     __syncthreads();
     if (i < n) {
-      const int sn = min(64, B - s0);
+      const int sn = min(64, Z - s0);
       for (int ss = 0; ss < sn; ++ss) {
         const float p = part[(int64_t)(s0 + ss) * n + i];
 #pragma unroll
@@ -462,32 +465,34 @@ __global__ void __launch_bounds__(256) k_expert_grad(const float* __restrict__ a
 }
 
 // D = A W_s^T with the merged matrix of each row's structure (Wm [B][N*K]); 64-row tiles that end
-// with their structure (the context's row-group table).
+// with their structure (the context's row-group table).  copies: A stacks that many copies of the
+// atom rows (the 2l+1 components of an equivariant block), M = copies * N_atoms.
 template <typename P, typename LdA, typename Epi>
-void gemm_nt_grouped(mlip_ctx* ctx, const LdA& a, const float* Wm, int64_t M, int N, int K, const Epi& epi) {
+void gemm_nt_grouped(mlip_ctx* ctx, const LdA& a, const float* Wm, int64_t M, int N, int K, const Epi& epi, int copies = 1) {
   gemm::Groups g;
   g.row_groups = ctx->d_row_groups;
-  g.n_row_tiles = ctx->n_row_groups;
+  g.n_row_tiles = ctx->n_row_groups * copies;
   g.b_stride = (int64_t)N * K;
   gemm::launch<P, 1, 1, 2, 2, true>(ctx->stream, a, LdPlain{Wm, K}, epi, M, N, K, 1, g);
 }
 // Expert-bank gradient: one weight-gradient partial per structure (split z = structure z's
 // atoms), then grad_bank[k] += sum_s alpha[s][k] partial[s].
 template <typename P, typename LdA, typename LdB>
-int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad_bank) {
+int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad_bank,
+                       int copies = 1) {
   const int B = ctx->B, Ke = ctx->cfg.n_experts;
   const int64_t n = (int64_t)Nout * Kout;
   if (R <= 0 || B <= 0) return MLIP_OK;
-  if ((int64_t)B * n > ctx->partial.cap) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "expert gradient: partial buffer too small");
+  if ((int64_t)B * copies * n > ctx->partial.cap) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "expert gradient: partial buffer too small");
   gemm::Groups g;
   g.k_ranges = ctx->d_struct_ptr;
   EpiPartial epi{ctx->partial.buf, Kout, Nout};
   if (Nout > 64)
-    gemm::launch<P, 2, 2, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B, g);
+    gemm::launch<P, 2, 2, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B * copies, g);
   else
-    gemm::launch<P, 1, 1, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B, g);
+    gemm::launch<P, 1, 1, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B * copies, g);
   hipLaunchKernelGGL(k_expert_grad, dim3(nblk(n), (Ke + 15) / 16), dim3(256), 0, ctx->stream, ctx->d_alpha, ctx->partial.buf, B,
-                     Ke, n, grad_bank);
+                     copies, Ke, n, grad_bank);
   return MLIP_OK;
 }
 

@@ -185,6 +185,10 @@ def mole_cases():
         "cfg1_3structs_5experts": (synth.shrink(W[1], n_structs=3, n_experts=5), TOL_FP32),
         "cfg1_small_20experts_bf16": (synth.shrink(W[1], n_structs=4, atoms_per_struct=48, box=(48 / 0.08) ** (1 / 3) + 4.0,
                                                    channels=64, edge_hidden=64, n_experts=20, gemm_bf16=True), TOL_BF16),
+        # equivariant model: banks for the three per-l mixing matrices, rows stacked over the 2l+1 components
+        "eqv_tiny_4experts_fp32": (synth.shrink(W[2], n_structs=3, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
+                                                edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False, n_experts=4), TOL_FP32),
+        "cfg2_2structs_6experts_bf16": (synth.shrink(W[2], n_structs=2, n_experts=6), TOL_BF16),
     }
 
 
