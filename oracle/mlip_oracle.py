@@ -49,35 +49,51 @@ SL = [slice(0, 1), slice(1, 4), slice(4, 9)]  # components of l = 0, 1, 2 inside
 
 # ============================================================================ neighbour list
 
+def lattice_images(lat: np.ndarray, cutoff: float) -> np.ndarray:
+    """Image shifts S (integer triples, in shift-code order) that a radius graph of one structure
+    has to visit.  A structure whose cell matrix is all zeros is a molecule in vacuum: only
+    S = 0.  Otherwise the rows of `lat` are the lattice vectors of a general (triclinic) cell
+    and the 27 nearest images suffice as long as the cutoff does not exceed any of the three
+    perpendicular heights V / |a_b x a_c| of the cell (for a diagonal cell: its edges)."""
+    lat = np.asarray(lat, dtype=np.float64)
+    if not lat.any():
+        return np.zeros((1, 3))
+    vol = abs(np.linalg.det(lat))
+    assert vol > 0.0, "singular cell"
+    heights = [vol / np.linalg.norm(np.cross(lat[(a + 1) % 3], lat[(a + 2) % 3])) for a in range(3)]
+    assert cutoff <= min(heights) + 1e-12, "cutoff longer than a cell height"
+    rng = np.array([-1.0, 0.0, 1.0])
+    return np.stack(np.meshgrid(rng, rng, rng, indexing="ij"), -1).reshape(27, 3)  # code order
+
+
 def radius_graph(pos: np.ndarray, struct_ptr: np.ndarray, cell: np.ndarray, cutoff: float,
                  chunk: int = 64) -> Dict[str, np.ndarray]:
-    """Periodic radius graph by brute force over all atom pairs and the 27 nearest images.
+    """Radius graph by brute force over all atom pairs of a structure and the images
+    lattice_images() lists (27 for a periodic cell, general lattice; 1 for a molecule).
 
     Edge (i <- j, S) exists iff |x_j + S.cell - x_i| < cutoff and (j, S) != (i, 0), i and j
-    in the same structure.  Requires cutoff <= every cell edge (so |S| <= 1 covers all
-    images).  Edges are grouped by receiver i (global atom index) and ordered inside a row
-    by (sender j, then shift code (Sx+1)*9 + (Sy+1)*3 + (Sz+1)); that order is unique.
-    Returns row_ptr [N+1], sender [E], shift [E,3], receiver [E], rev [E] with rev[e] the
-    index of the opposite edge (j <- i, -S).
+    in the same structure.  Edges are grouped by receiver i (global atom index) and ordered
+    inside a row by (sender j, then shift code (Sx+1)*9 + (Sy+1)*3 + (Sz+1)); that order is
+    unique.  Returns row_ptr [N+1], sender [E], shift [E,3], receiver [E], rev [E] with
+    rev[e] the index of the opposite edge (j <- i, -S).
     """
     pos = np.asarray(pos, dtype=np.float64)
     N = pos.shape[0]
-    rng = np.array([-1.0, 0.0, 1.0])
-    S = np.stack(np.meshgrid(rng, rng, rng, indexing="ij"), -1).reshape(27, 3)  # code order
     recv_l, send_l, shift_l = [], [], []
     for s in range(len(struct_ptr) - 1):
         a, b = int(struct_ptr[s]), int(struct_ptr[s + 1])
         lat = np.asarray(cell[s], dtype=np.float64)
-        assert cutoff <= np.linalg.norm(lat, axis=1).min() + 1e-12, "cutoff longer than a cell edge"
-        off = S @ lat  # [27,3]
+        S = lattice_images(lat, cutoff)
+        zero = int(np.nonzero((S == 0).all(1))[0][0])
+        off = S @ lat  # [n_images,3]
         x = pos[a:b]
         for i0 in range(0, b - a, chunk):
             xi = x[i0:i0 + chunk]
-            d = x[None, :, None, :] + off[None, None, :, :] - xi[:, None, None, :]  # [ci, n, 27, 3]
+            d = x[None, :, None, :] + off[None, None, :, :] - xi[:, None, None, :]  # [ci, n, images, 3]
             r2 = d[..., 0] * d[..., 0] + d[..., 1] * d[..., 1] + d[..., 2] * d[..., 2]
             ok = r2 < cutoff * cutoff
             ii = np.arange(xi.shape[0])
-            ok[ii, ii + i0, 13] = False  # the atom itself, zero shift
+            ok[ii, ii + i0, zero] = False  # the atom itself, zero shift
             ri, rj, rs = np.nonzero(ok)  # C order: i, then j, then code -> already canonical
             recv_l.append(ri + i0 + a)
             send_l.append(rj + a)
@@ -102,17 +118,17 @@ def radius_graph_rows(pos: np.ndarray, struct_ptr: np.ndarray, cell: np.ndarray,
     too large for the full pair loop can still be checked one by one).  Returns, per requested
     receiver, (sender [d], shift [d,3]) in the canonical in-row order."""
     pos = np.asarray(pos, dtype=np.float64)
-    rng = np.array([-1.0, 0.0, 1.0])
-    S = np.stack(np.meshgrid(rng, rng, rng, indexing="ij"), -1).reshape(27, 3)
     out = []
     for i in rows:
         s = int(np.searchsorted(struct_ptr, i, side="right") - 1)
         a, b = int(struct_ptr[s]), int(struct_ptr[s + 1])
-        off = S @ np.asarray(cell[s], dtype=np.float64)
-        d = pos[a:b, None, :] + off[None, :, :] - pos[i][None, None, :]   # [n, 27, 3]
+        lat = np.asarray(cell[s], dtype=np.float64)
+        S = lattice_images(lat, cutoff)
+        off = S @ lat
+        d = pos[a:b, None, :] + off[None, :, :] - pos[i][None, None, :]   # [n, images, 3]
         r2 = d[..., 0] * d[..., 0] + d[..., 1] * d[..., 1] + d[..., 2] * d[..., 2]
         ok = r2 < cutoff * cutoff
-        ok[i - a, 13] = False
+        ok[i - a, int(np.nonzero((S == 0).all(1))[0][0])] = False
         rj, rs = np.nonzero(ok)
         out.append(((rj + a).astype(np.int32), S[rs].astype(np.int32)))
     return out

@@ -29,6 +29,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 STREAM_POS, STREAM_SPECIES, STREAM_PARAMS, STREAM_EREF, STREAM_FREF = 1, 2, 3, 4, 5
 STREAM_H_IN, STREAM_G_OUT, STREAM_HDOT_IN, STREAM_V, STREAM_LAM_OUT = 6, 7, 8, 9, 10
 STREAM_ALPHA = 12  # (11 is taken by the graph-size recipe)
+STREAM_CELL = 13
 
 BASE_SEED = 18404000
 
@@ -86,6 +87,7 @@ class Workload:
     gemm_bf16: bool
     force_weight: float = 10.0
     min_dist: float = 1.0
+    cell_kind: str = "cubic"  # "cubic" | "triclinic" (sheared lattice, per structure) | "free" (molecule in vacuum: zero cell)
     n_experts: int = 0        # > 0: the node-level matrices of every layer (update MLP / per-l mixing) are banks of this many experts
 
     @property
@@ -165,6 +167,74 @@ def make_structure(seed: int, struct_index: int, n: int, box: float, cutoff: flo
     # coarse spatial order (part of the input): cells of edge >= 3 Angstrom, z-major
     nb = max(1, int(box / 3.0))
     b = np.minimum((pts / box * nb).astype(np.int64), nb - 1)
+    key = (b[:, 2] * nb + b[:, 1]) * nb + b[:, 0]
+    order = np.argsort(key, kind="stable")
+    return pts[order].astype(np.float32)
+
+
+def make_lattice(w: "Workload", struct_index: int) -> np.ndarray:
+    """Cell matrix (rows = lattice vectors, float32) of one structure.  "triclinic": the cube of
+    edge `box` sheared by seeded amounts of up to 0.3 box (volume unchanged, all perpendicular
+    heights stay above 0.9 box); "free": zeros, which marks a molecule in vacuum."""
+    if w.cell_kind == "cubic":
+        return (np.eye(3) * w.box).astype(np.float32)
+    if w.cell_kind == "free":
+        return np.zeros((3, 3), np.float32)
+    if w.cell_kind != "triclinic":
+        raise ValueError(w.cell_kind)
+    t = 2.0 * uniform(w.seed, STREAM_CELL, 3 * struct_index, 3) - 1.0
+    lat = np.eye(3) * w.box
+    lat[1, 0] = 0.3 * w.box * t[0]
+    lat[2, 0] = 0.2 * w.box * t[1]
+    lat[2, 1] = 0.25 * w.box * t[2]
+    return lat.astype(np.float32)
+
+
+def make_structure_general(seed: int, struct_index: int, n: int, lat: np.ndarray, box: float, cutoff: float,
+                           min_dist: float = 1.0, shell: float = 1e-4) -> np.ndarray:
+    """Random sequential insertion for a general lattice (rows of `lat`) or, with lat = 0, for a
+    molecule in vacuum inside a cube of edge `box` whose corner sits at a seeded offset (so that
+    coordinates of either sign occur).  Same rejection rules as make_structure; periodic
+    candidates keep fractional coordinates 0.1 % clear of the cell faces, so that "inside the
+    cell" has the same answer in float32 and float64.  Returns float32 [n,3] in a coarse
+    spatial order."""
+    lat64 = np.asarray(lat, dtype=np.float32).astype(np.float64)
+    periodic = bool(lat64.any())
+    if periodic:
+        rng = np.array([-1.0, 0.0, 1.0])
+        img = np.stack(np.meshgrid(rng, rng, rng, indexing="ij"), -1).reshape(27, 3) @ lat64
+        origin = np.zeros(3)
+    else:
+        img = np.zeros((1, 3))
+        origin = (40.0 * uniform(seed, STREAM_CELL, (1 << 20) + 3 * struct_index, 3) - 20.0).astype(np.float32).astype(np.float64)
+    pts = np.zeros((n, 3), dtype=np.float64)
+    frac = np.zeros((n, 3), dtype=np.float64)
+    placed = 0
+    cand = 0
+    base = struct_index * (1 << 32)
+    chunk = 256
+    while placed < n:
+        u = uniform(seed, STREAM_POS, base + 3 * cand, 3 * chunk).reshape(chunk, 3)
+        if periodic:
+            u = 1e-3 + u * (1.0 - 2e-3)
+            xyz = (u @ lat64).astype(np.float32).astype(np.float64)
+        else:
+            xyz = (origin + u * box).astype(np.float32).astype(np.float64)
+        for k in range(chunk):
+            cand += 1
+            p = xyz[k]
+            if placed:
+                d = (pts[:placed, None, :] + img[None, :, :]) - p[None, None, :]
+                dist = np.sqrt((d * d).sum(-1)).reshape(-1)
+                if dist.min() < min_dist or np.any(np.abs(dist - cutoff) < shell):
+                    continue
+            pts[placed] = p
+            frac[placed] = u[k]
+            placed += 1
+            if placed == n:
+                break
+    nb = max(1, int(box / 3.0))
+    b = np.minimum((frac * nb).astype(np.int64), nb - 1)
     key = (b[:, 2] * nb + b[:, 1]) * nb + b[:, 0]
     order = np.argsort(key, kind="stable")
     return pts[order].astype(np.float32)
@@ -256,10 +326,14 @@ class Inputs:
 
 def make_inputs(w: Workload) -> Inputs:
     B, n, N = w.n_structs, w.atoms_per_struct, w.n_atoms
-    pos = np.concatenate([make_structure(w.seed, s, n, w.box, w.cutoff, w.min_dist) for s in range(B)], 0)
+    if w.cell_kind == "cubic":
+        pos = np.concatenate([make_structure(w.seed, s, n, w.box, w.cutoff, w.min_dist) for s in range(B)], 0)
+        cell = np.tile((np.eye(3) * w.box).astype(np.float32)[None], (B, 1, 1))
+    else:
+        cell = np.stack([make_lattice(w, s) for s in range(B)])
+        pos = np.concatenate([make_structure_general(w.seed, s, n, cell[s], w.box, w.cutoff, w.min_dist) for s in range(B)], 0)
     species = draw_species(w.seed, N, w.n_species, w.species_dist)
     struct_ptr = (np.arange(B + 1, dtype=np.int64) * n).astype(np.int32)
-    cell = np.tile((np.eye(3) * w.box).astype(np.float32)[None], (B, 1, 1))
     E_ref = normal(w.seed, STREAM_EREF, 0, B).astype(np.float32)
     F_ref = (0.1 * normal(w.seed, STREAM_FREF, 0, 3 * N)).astype(np.float32).reshape(N, 3)
     stage: Dict[str, np.ndarray] = {}
