@@ -48,12 +48,12 @@ typedef struct mlip_ctx mlip_ctx;
 
 typedef enum {
   MLIP_OK = 0,
-  MLIP_E_INVALID = -1,     /* null pointer, non-positive size, cutoff <= 0 or > a cell edge, bad order of calls' arguments */
+  MLIP_E_INVALID = -1,     /* null pointer, non-positive size, cutoff <= 0 or > a cell height, singular cell, bad order of calls' arguments */
   MLIP_E_CAPACITY = -2,    /* more atoms / structures / edges than the context was created for */
-  MLIP_E_UNSUPPORTED = -3, /* non-orthorhombic cell, unsupported model shape */
+  MLIP_E_UNSUPPORTED = -3, /* unsupported model shape or option */
   MLIP_E_STATE = -4,       /* phase called out of order (FE -> FF -> BF -> BE) or without a graph */
   MLIP_E_HIP = -5,         /* a HIP runtime call failed */
-  MLIP_E_POSITION = -6     /* a position lies outside [0, L) of its cell, or is not finite (found at graph build) */
+  MLIP_E_POSITION = -6     /* a position lies outside its cell, or is not finite (found at graph build) */
 } mlip_status;
 
 enum { MLIP_MODEL_INVARIANT = 0, MLIP_MODEL_EQUIVARIANT = 1, MLIP_MODEL_STAGE = 2 };
@@ -95,13 +95,20 @@ const char* mlip_last_error(const mlip_ctx* ctx);
 /* Bytes of device memory held by the context. */
 int64_t mlip_workspace_bytes(const mlip_ctx* ctx);
 
-/* Periodic radius graph (cell-list binning, receiver-sorted CSR).
+/* Radius graph of a batch of structures (cell-list binning, receiver-sorted CSR).
  * Edge e = (i <- j, S) exists iff |x_j + S.cell - x_i|^2 < cutoff^2 in float32 (differences
- * first, then the shift, then the three squares summed left to right, no fused multiply-add)
- * and (j, S) != (i, 0); i, j in the same structure.  Rows are receivers in global atom order;
- * inside a row edges are ordered by (sender, then (Sx+1)*9 + (Sy+1)*3 + (Sz+1)).
+ * first, then the shift S.cell = (Sx a1 + Sy a2) + Sz a3 rounded after every operation, then the
+ * three squares summed left to right, no fused multiply-add) and (j, S) != (i, 0); i, j in the
+ * same structure.  Rows are receivers in global atom order; inside a row edges are ordered by
+ * (sender, then (Sx+1)*9 + (Sy+1)*3 + (Sz+1)).
  *   pos[N,3], struct_ptr[B+1] (atom ranges of the structures), cell[B,3,3] (rows = lattice
- *   vectors; must be orthorhombic, i.e. diagonal, with cutoff <= every edge).
+ *   vectors a1, a2, a3 of each structure).  Per structure the cell is one of
+ *   - diagonal (orthorhombic): positions in [0, L_a) exactly, cutoff <= every edge L_a;
+ *   - a general non-singular lattice (triclinic, either handedness): fractional coordinates
+ *     x . cell^-1 in [0, 1] (evaluated in float32, 1e-5 slack), cutoff (1 + 1e-4) <= every
+ *     perpendicular height V / |a_b x a_c| (so that S in {-1, 0, 1}^3 covers the cutoff sphere);
+ *   - all zeros: a molecule in vacuum, no images (S = 0), positions anywhere (finite).
+ *   A cell with some but not all lattice vectors zero (a slab or wire) is refused as singular.
  * Synchronous: reads struct_ptr and cell back to validate them and returns the edge count in
  * *n_edges_host.  On MLIP_E_CAPACITY *n_edges_host holds the count that was needed.
  * The graph stays in the context until the next build. */

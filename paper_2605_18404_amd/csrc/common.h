@@ -32,11 +32,15 @@
 constexpr int MLIP_NPATH = 11;  // (l1,l2,l3), l <= 2, triangle rule, even parity
 
 // Per-structure record used by the graph kernels (built on the host at graph build).
+enum CellKind { CELL_ORTHO = 0, CELL_TRICLINIC = 1, CELL_FREE = 2 };
 struct StructMeta {
   int32_t atom_begin, atom_end;
   int32_t nb[3];     // bins per axis
   int32_t bin_base;  // first global bin of this structure
-  float L[3];        // orthorhombic cell edges
+  int32_t kind;      // CellKind: diagonal cell, general lattice, or a molecule in vacuum (zero cell)
+  float lat[9];      // rows = lattice vectors (all zero for a molecule)
+  float inv[9];      // binning coordinate f_a = sum_b (x_b - origin_b) inv[3 b + a], in [0, 1) inside the cell / bounding box
+  float origin[3];   // zero for periodic cells; corner of the bounding box of a molecule
 };
 
 struct PartialBuf {  // split-k / chunk partial sums, reduced in a fixed order
@@ -83,6 +87,7 @@ struct mlip_ctx {
   int32_t* d_rev = nullptr;           // [max_edges]
   int32_t* d_scan_tmp = nullptr;      // block sums for the scans
   int32_t* d_flag = nullptr;          // device error flag
+  float* d_bounds = nullptr;          // [max_structs][6] bounding boxes (min xyz, max xyz), molecules only
   int64_t max_bins = 0;
   std::vector<StructMeta> h_meta;
   std::vector<int32_t> h_struct_ptr;

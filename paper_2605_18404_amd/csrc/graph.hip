@@ -95,6 +95,45 @@ __device__ __forceinline__ int bin_coord(float x, float L, int nb) {
   return b < 0 ? 0 : (b >= nb ? nb - 1 : b);
 }
 
+__device__ __forceinline__ int bin_of_fraction(float f, int nb) {
+  int b = (int)floorf(f * (float)nb);
+  return b < 0 ? 0 : (b >= nb ? nb - 1 : b);
+}
+
+// Fractional coordinates may leave [0, 1] by this much before a position counts as outside its
+// (general) cell; the bins are wide enough to absorb it.
+constexpr float FRAC_TOL = 1e-5f;
+
+// Bounding box of every structure's atoms (one block per structure); used for molecules, whose
+// bins are laid over the box.  NaNs are skipped here and reported by the binning kernel.
+__global__ void __launch_bounds__(256) k_bounds(const float* __restrict__ pos, const int32_t* __restrict__ struct_ptr,
+                                                float* __restrict__ bounds) {
+  __shared__ float red[6][256];
+  const int s = blockIdx.x, t = threadIdx.x;
+  const int a = struct_ptr[s], b = struct_ptr[s + 1];
+  float lo[3] = {INFINITY, INFINITY, INFINITY}, hi[3] = {-INFINITY, -INFINITY, -INFINITY};
+  for (int i = a + t; i < b; i += 256)
+    for (int c = 0; c < 3; ++c) {
+      float x = pos[3 * (int64_t)i + c];
+      lo[c] = fminf(lo[c], x);
+      hi[c] = fmaxf(hi[c], x);
+    }
+  for (int c = 0; c < 3; ++c) {
+    red[c][t] = lo[c];
+    red[3 + c][t] = hi[c];
+  }
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (t < off)
+      for (int c = 0; c < 3; ++c) {
+        red[c][t] = fminf(red[c][t], red[c][t + off]);
+        red[3 + c][t] = fmaxf(red[3 + c][t], red[3 + c][t + off]);
+      }
+    __syncthreads();
+  }
+  if (t < 6) bounds[6 * s + t] = red[t][0];
+}
+
 __global__ void k_bin_count(const float* __restrict__ pos, const StructMeta* __restrict__ meta, int B, int N,
                             int32_t* __restrict__ atom_struct, int32_t* __restrict__ atom_bin,
                             int32_t* __restrict__ bin_count, int32_t* __restrict__ flag) {
@@ -103,11 +142,30 @@ __global__ void k_bin_count(const float* __restrict__ pos, const StructMeta* __r
   int s = struct_of_atom(meta, B, i);
   StructMeta m = meta[s];
   float x = pos[3 * i], y = pos[3 * i + 1], z = pos[3 * i + 2];
-  bool ok = (x >= 0.f) && (x < m.L[0]) && (y >= 0.f) && (y < m.L[1]) && (z >= 0.f) && (z < m.L[2]);
-  if (!ok) atomicOr(flag, 1);  // also catches NaN
-  int bx = ok ? bin_coord(x, m.L[0], m.nb[0]) : 0;
-  int by = ok ? bin_coord(y, m.L[1], m.nb[1]) : 0;
-  int bz = ok ? bin_coord(z, m.L[2], m.nb[2]) : 0;
+  bool ok;
+  int bx, by, bz;
+  if (m.kind == CELL_ORTHO) {
+    const float Lx = m.lat[0], Ly = m.lat[4], Lz = m.lat[8];
+    ok = (x >= 0.f) && (x < Lx) && (y >= 0.f) && (y < Ly) && (z >= 0.f) && (z < Lz);  // also catches NaN
+    bx = ok ? bin_coord(x, Lx, m.nb[0]) : 0;
+    by = ok ? bin_coord(y, Ly, m.nb[1]) : 0;
+    bz = ok ? bin_coord(z, Lz, m.nb[2]) : 0;
+  } else {
+    const float rx = x - m.origin[0], ry = y - m.origin[1], rz = z - m.origin[2];
+    const float f0 = (rx * m.inv[0] + ry * m.inv[3]) + rz * m.inv[6];
+    const float f1 = (rx * m.inv[1] + ry * m.inv[4]) + rz * m.inv[7];
+    const float f2 = (rx * m.inv[2] + ry * m.inv[5]) + rz * m.inv[8];
+    if (m.kind == CELL_TRICLINIC)
+      ok = (f0 >= -FRAC_TOL) && (f0 <= 1.f + FRAC_TOL) && (f1 >= -FRAC_TOL) && (f1 <= 1.f + FRAC_TOL) &&
+           (f2 >= -FRAC_TOL) && (f2 <= 1.f + FRAC_TOL);
+    else  // a molecule may sit anywhere; its bins cover its bounding box
+      ok = (fabsf(x) <= 3.0e38f) && (fabsf(y) <= 3.0e38f) && (fabsf(z) <= 3.0e38f) && (fabsf(f0) <= 2.f) &&
+           (fabsf(f1) <= 2.f) && (fabsf(f2) <= 2.f);
+    bx = ok ? bin_of_fraction(f0, m.nb[0]) : 0;
+    by = ok ? bin_of_fraction(f1, m.nb[1]) : 0;
+    bz = ok ? bin_of_fraction(f2, m.nb[2]) : 0;
+  }
+  if (!ok) atomicOr(flag, 1);
   int g = m.bin_base + (bz * m.nb[1] + by) * m.nb[0] + bx;
   atom_struct[i] = s;
   atom_bin[i] = g;
@@ -151,16 +209,22 @@ __global__ void __launch_bounds__(256) k_neighbours(const float* __restrict__ po
   int bx = g % m.nb[0], by = (g / m.nb[0]) % m.nb[1], bz = g / (m.nb[0] * m.nb[1]);
   int count = 0;
   int out_base = FILL ? row_ptr[i] : 0;
+  const bool no_images = m.kind == CELL_FREE;
   for (int o = 0; o < 27; ++o) {
     int ox = o / 9 - 1, oy = (o / 3) % 3 - 1, oz = o % 3 - 1;
     // unwrapped bin coordinate -> wrapped bin + image shift (floor division)
     int ux = bx + ox, uy = by + oy, uz = bz + oz;
+    if (no_images && (ux < 0 || ux >= m.nb[0] || uy < 0 || uy >= m.nb[1] || uz < 0 || uz >= m.nb[2])) continue;  // wave-uniform
     int Sx = (ux < 0) ? -1 : (ux >= m.nb[0] ? 1 : 0);
     int Sy = (uy < 0) ? -1 : (uy >= m.nb[1] ? 1 : 0);
     int Sz = (uz < 0) ? -1 : (uz >= m.nb[2] ? 1 : 0);
     int wx = ux - Sx * m.nb[0], wy = uy - Sy * m.nb[1], wz = uz - Sz * m.nb[2];
     int gb = m.bin_base + (wz * m.nb[1] + wy) * m.nb[0] + wx;
-    float sx = (float)Sx * m.L[0], sy = (float)Sy * m.L[1], sz = (float)Sz * m.L[2];
+    // S . cell, rounded after every operation (the products are exact); a diagonal cell gives S_a L_a
+    const float fx = (float)Sx, fy = (float)Sy, fz = (float)Sz;
+    float sx = __fadd_rn(__fadd_rn(__fmul_rn(fx, m.lat[0]), __fmul_rn(fy, m.lat[3])), __fmul_rn(fz, m.lat[6]));
+    float sy = __fadd_rn(__fadd_rn(__fmul_rn(fx, m.lat[1]), __fmul_rn(fy, m.lat[4])), __fmul_rn(fz, m.lat[7]));
+    float sz = __fadd_rn(__fadd_rn(__fmul_rn(fx, m.lat[2]), __fmul_rn(fy, m.lat[5])), __fmul_rn(fz, m.lat[8]));
     int code = (Sx + 1) * 9 + (Sy + 1) * 3 + (Sz + 1);
     int b0 = bin_start[gb], b1 = bin_start[gb + 1];
     for (int t0 = b0; t0 < b1; t0 += 64) {
@@ -265,6 +329,7 @@ int graph_alloc(mlip_ctx* ctx) {
   int64_t scan_blocks = (std::max(N, ctx->max_bins) + SCAN_TILE) / SCAN_TILE + 1;
   ok &= (ctx->d_scan_tmp = alloc_n<int32_t>(ctx, scan_blocks)) != nullptr;
   ok &= (ctx->d_flag = alloc_n<int32_t>(ctx, 4)) != nullptr;
+  ok &= (ctx->d_bounds = alloc_n<float>(ctx, 6 * B)) != nullptr;
   return ok ? MLIP_OK : MLIP_E_HIP;
 }
 
@@ -290,23 +355,85 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
   ctx->h_meta.resize(B);
   if (ctx->h_struct_ptr[0] != 0 || ctx->h_struct_ptr[B] != N)
     MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: struct_ptr must start at 0 and end at n_atoms");
-  int64_t bins = 0;
+  bool any_free = false;
   for (int s = 0; s < B; ++s) {
     StructMeta& m = ctx->h_meta[s];
     m.atom_begin = ctx->h_struct_ptr[s];
     m.atom_end = ctx->h_struct_ptr[s + 1];
     if (m.atom_end < m.atom_begin) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: struct_ptr must be non-decreasing");
     const float* c = &ctx->h_cell[(size_t)s * 9];
+    bool all_zero = true, diagonal = true;
     for (int a = 0; a < 3; ++a)
-      for (int b = 0; b < 3; ++b)
-        if (a != b && c[3 * a + b] != 0.f) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "graph_build: only orthorhombic (diagonal) cells are supported");
+      for (int b = 0; b < 3; ++b) {
+        if (!std::isfinite(c[3 * a + b])) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell entries must be finite");
+        if (c[3 * a + b] != 0.f) {
+          all_zero = false;
+          if (a != b) diagonal = false;
+        }
+      }
+    m.kind = all_zero ? CELL_FREE : (diagonal ? CELL_ORTHO : CELL_TRICLINIC);
+    any_free |= all_zero;
+  }
+  std::vector<float> h_bounds;
+  if (any_free) {  // molecules: bins are laid over the bounding box, which only the device can see
+    h_bounds.resize((size_t)B * 6);
+    hipLaunchKernelGGL(k_bounds, dim3(B), dim3(256), 0, st, pos, struct_ptr, ctx->d_bounds);
+    MLIP_HIP_CHECK(ctx, hipGetLastError());
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(h_bounds.data(), ctx->d_bounds, sizeof(float) * 6 * B, hipMemcpyDeviceToHost, st));
+    MLIP_HIP_CHECK(ctx, hipStreamSynchronize(st));
+  }
+  int64_t bins = 0;
+  for (int s = 0; s < B; ++s) {
+    StructMeta& m = ctx->h_meta[s];
+    const float* c = &ctx->h_cell[(size_t)s * 9];
+    for (int k = 0; k < 9; ++k) m.lat[k] = c[k], m.inv[k] = 0.f;
+    m.origin[0] = m.origin[1] = m.origin[2] = 0.f;
     int64_t cap = std::max<int64_t>(8, 2 * (int64_t)(m.atom_end - m.atom_begin));
-    for (int a = 0; a < 3; ++a) {
-      m.L[a] = c[4 * a];
-      if (!(m.L[a] > 0.f) || !std::isfinite(m.L[a])) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell edge must be positive");
-      if (cutoff > m.L[a]) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a cell edge");
-      // bins at least (1 + 1e-5) r_c wide, so rounding in the bin assignment cannot lose a neighbour
-      m.nb[a] = std::max(1, (int)std::floor((double)m.L[a] / ((double)cutoff * (1.0 + 1e-5))));
+    if (m.kind == CELL_ORTHO) {
+      for (int a = 0; a < 3; ++a) {
+        const float L = c[4 * a];
+        if (!(L > 0.f)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell edge must be positive");
+        if (cutoff > L) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a cell edge");
+        // bins at least (1 + 1e-5) r_c wide, so rounding in the bin assignment cannot lose a neighbour
+        m.nb[a] = std::max(1, (int)std::floor((double)L / ((double)cutoff * (1.0 + 1e-5))));
+        m.inv[4 * a] = 1.f / L;
+      }
+    } else if (m.kind == CELL_TRICLINIC) {
+      // general lattice: bins are slabs between lattice planes; their width is the perpendicular
+      // height V / |a_b x a_c| divided by the bin count
+      double A[3][3], X[3][3];
+      for (int a = 0; a < 3; ++a)
+        for (int b = 0; b < 3; ++b) A[a][b] = c[3 * a + b];
+      for (int a = 0; a < 3; ++a) {  // X[a] = a_{a+1} x a_{a+2}
+        const double* u = A[(a + 1) % 3];
+        const double* v = A[(a + 2) % 3];
+        X[a][0] = u[1] * v[2] - u[2] * v[1];
+        X[a][1] = u[2] * v[0] - u[0] * v[2];
+        X[a][2] = u[0] * v[1] - u[1] * v[0];
+      }
+      const double det = A[0][0] * X[0][0] + A[0][1] * X[0][1] + A[0][2] * X[0][2];
+      double scale = 1.0;
+      for (int a = 0; a < 3; ++a) scale *= std::sqrt(A[a][0] * A[a][0] + A[a][1] * A[a][1] + A[a][2] * A[a][2]);
+      if (!(std::fabs(det) > 1e-6 * scale)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell is singular (or partly periodic, which is not supported)");
+      for (int a = 0; a < 3; ++a) {
+        const double height = std::fabs(det) / std::sqrt(X[a][0] * X[a][0] + X[a][1] * X[a][1] + X[a][2] * X[a][2]);
+        // the 27 nearest images cover the cutoff sphere only up to the smallest height; the margins
+        // leave room for the rounding of the float32 fractional coordinates
+        if ((double)cutoff * (1.0 + 1e-4) > height) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a perpendicular height of the cell");
+        m.nb[a] = std::min(128, std::max(1, (int)std::floor(height / ((double)cutoff * (1.0 + 2e-3)))));
+        for (int b = 0; b < 3; ++b) m.inv[3 * b + a] = (float)(X[a][b] / det);  // column a of the inverse
+      }
+    } else {
+      const int n_at = m.atom_end - m.atom_begin;
+      for (int a = 0; a < 3; ++a) {
+        float lo = n_at > 0 ? h_bounds[(size_t)6 * s + a] : 0.f, hi = n_at > 0 ? h_bounds[(size_t)6 * s + 3 + a] : 0.f;
+        if (!(std::isfinite(lo) && std::isfinite(hi) && hi - lo <= 1e30f))
+          MLIP_FAIL(ctx, MLIP_E_POSITION, "graph_build: a position is not finite");
+        const double extent = std::max((double)hi - (double)lo, (double)cutoff) * (1.0 + 1e-3);
+        m.nb[a] = std::max(1, (int)std::floor(extent / ((double)cutoff * (1.0 + 2e-3))));
+        m.origin[a] = lo;
+        m.inv[4 * a] = (float)(1.0 / extent);
+      }
     }
     // coarser bins are still correct: cap the bin count near the atom count
     while ((int64_t)m.nb[0] * m.nb[1] * m.nb[2] > cap) {

@@ -508,7 +508,11 @@ __global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __
   int k = (int)(idx % K);
   int i = receiver[e], j = sender[e], c = code[e];
   const StructMeta& m = meta[atom_struct[i]];
-  float sx = (float)(c / 9 - 1) * m.L[0], sy = (float)((c / 3) % 3 - 1) * m.L[1], sz = (float)(c % 3 - 1) * m.L[2];
+  // image shift S . cell (rows = lattice vectors); zero for a molecule, S_a L_a for a diagonal cell
+  const float Sx = (float)(c / 9 - 1), Sy = (float)((c / 3) % 3 - 1), Sz = (float)(c % 3 - 1);
+  float sx = (Sx * m.lat[0] + Sy * m.lat[3]) + Sz * m.lat[6];
+  float sy = (Sx * m.lat[1] + Sy * m.lat[4]) + Sz * m.lat[7];
+  float sz = (Sx * m.lat[2] + Sy * m.lat[5]) + Sz * m.lat[8];
   float dx = (pos[3 * j] - pos[3 * i]) + sx;
   float dy = (pos[3 * j + 1] - pos[3 * i + 1]) + sy;
   float dz = (pos[3 * j + 2] - pos[3 * i + 2]) + sz;

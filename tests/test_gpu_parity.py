@@ -25,6 +25,13 @@ def graph_cases():
         "cfg3_2structs_multi_image": synth.shrink(W[3], n_structs=2),
         "cfg4_2000atoms_many_bins": synth.shrink(W[4], atoms_per_struct=2000, box=(2000 / 0.1) ** (1 / 3)),
         "one_bin_edge_case": synth.shrink(W[0], box=5.0, atoms_per_struct=20, cutoff=5.0),
+        # general lattices (a different shear per structure) and molecules in vacuum
+        "cfg1_3structs_triclinic": synth.shrink(W[1], n_structs=3, cell_kind="triclinic"),
+        "cfg3_2structs_triclinic_multi_image": synth.shrink(W[3], n_structs=2, cell_kind="triclinic"),
+        "cfg4_2000atoms_triclinic_many_bins": synth.shrink(W[4], atoms_per_struct=2000, box=(2000 / 0.1) ** (1 / 3), cell_kind="triclinic"),
+        "cfg1_3structs_molecules": synth.shrink(W[1], n_structs=3, cell_kind="free"),
+        "cfg4_2000atoms_molecule": synth.shrink(W[4], atoms_per_struct=2000, box=(2000 / 0.1) ** (1 / 3), cell_kind="free"),
+        "two_atom_molecules": synth.shrink(W[0], n_structs=4, atoms_per_struct=2, box=3.0, cell_kind="free"),
     }
 
 
@@ -64,6 +71,38 @@ def test_graph_ragged_batch_and_empty_structure():
     m.close()
 
 
+def test_graph_mixed_cell_kinds_in_one_batch():
+    """A cubic cell, a molecule, a sheared cell, an empty molecule, a left-handed sheared cell and a
+    single atom in vacuum, in one call."""
+    rc = 5.0
+    base = synth.shrink(synth.WORKLOADS[1], n_structs=1, cutoff=rc)
+    parts = [synth.shrink(base, atoms_per_struct=40, box=10.5), synth.shrink(base, atoms_per_struct=33, box=9.0, cell_kind="free"),
+             synth.shrink(base, atoms_per_struct=70, box=12.0, cell_kind="triclinic"), None,
+             synth.shrink(base, atoms_per_struct=25, box=8.0, cell_kind="triclinic", index=7), synth.shrink(base, atoms_per_struct=1, box=3.0, cell_kind="free")]
+    pos, cell, sizes = [], [], []
+    for k, w in enumerate(parts):
+        if w is None:
+            pos.append(np.zeros((0, 3), np.float32)), cell.append(np.zeros((3, 3), np.float32)), sizes.append(0)
+            continue
+        i = synth.make_inputs(w)
+        c, x = i.cell[0].copy(), i.pos.copy()
+        if k == 4:  # swap two lattice vectors: same lattice, same atoms, negative determinant
+            c = c[[1, 0, 2]]
+        pos.append(x), cell.append(c), sizes.append(len(x))
+    pos, cell = np.concatenate(pos), np.stack(cell)
+    sp = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    ref = O.radius_graph(pos, sp, cell, rc)
+    assert np.linalg.det(cell[4].astype(np.float64)) < 0 and len(ref["sender"]) > 1000
+    m = Mlip(model_kind=0, channels=8, n_layers=1, n_rbf=8, edge_hidden=8, n_species=2, cutoff=rc,
+             max_atoms=256, max_structs=8, max_edges=40000)
+    n_edges = m.mlip_graph_build(dev(pos), dev(sp), dev(cell), rc)
+    row_ptr, sender, shift, rev = [t.cpu().numpy() for t in m.mlip_graph_export()]
+    assert n_edges == len(ref["sender"])
+    assert np.array_equal(row_ptr, ref["row_ptr"]) and np.array_equal(sender, ref["sender"])
+    assert np.array_equal(shift, ref["shift"]) and np.array_equal(rev, ref["rev"])
+    m.close()
+
+
 def test_graph_error_paths():
     w = synth.WORKLOADS[0]
     inp = synth.make_inputs(w)
@@ -86,11 +125,34 @@ def test_graph_error_paths():
     with pytest.raises(MlipError) as e:
         m.mlip_graph_build(bad, d.struct_ptr, d.cell, w.cutoff)
     assert e.value.code == -6
+    slab = d.cell.clone()
+    slab[0, 2, 2] = 0.0  # two lattice vectors only: refused as singular
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(d.pos, d.struct_ptr, slab, w.cutoff)
+    assert e.value.code == -1
+    flat = d.cell.clone()
+    flat[0, 1] = flat[0, 0] * 0.5  # a2 parallel to a1
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(d.pos, d.struct_ptr, flat, w.cutoff)
+    assert e.value.code == -1
     tri = d.cell.clone()
-    tri[0, 1, 0] = 0.5
+    tri[0, 1, 0] = 11.0  # a2 = (11, 12, 0): the height along a1 drops to 8.8, and most atoms are now outside the cell
     with pytest.raises(MlipError) as e:
         m.mlip_graph_build(d.pos, d.struct_ptr, tri, w.cutoff)
-    assert e.value.code == -3
+    assert e.value.code == -6
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(d.pos, d.struct_ptr, tri, 9.5)  # below every edge length, above that height
+    assert e.value.code == -1
+    free = torch.zeros_like(d.cell)
+    bad = d.pos.clone()
+    bad[7, 2] = float("inf")
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(bad, d.struct_ptr, free, w.cutoff)
+    assert e.value.code == -6
+    bad[7, 2] = float("nan")
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(bad, d.struct_ptr, free, w.cutoff)
+    assert e.value.code == -6
     with pytest.raises(MlipError) as e:  # phases out of order
         m.mlip_forward_force()
     assert e.value.code == -4
@@ -130,6 +192,13 @@ def train_cases():
         "cfg2_2structs_fp32": (synth.shrink(W[2], n_structs=2, gemm_bf16=False), TOL_FP32),
         "cfg2_2structs_bf16": (synth.shrink(W[2], n_structs=2), TOL_BF16),
         "cfg4_shape_300atoms_bf16": (synth.shrink(W[4], atoms_per_struct=300, box=(300 / 0.1) ** (1 / 3), n_layers=2), TOL_BF16),
+        # general lattices and molecules in vacuum: the image shift S . cell enters every edge vector
+        "cfg1_2structs_triclinic": (synth.shrink(W[1], n_structs=2, cell_kind="triclinic"), TOL_FP32),
+        "cfg1_2structs_molecules": (synth.shrink(W[1], n_structs=2, cell_kind="free"), TOL_FP32),
+        "eqv_multi_image_triclinic_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                                        edge_hidden=16, n_rbf=8, n_layers=3, gemm_bf16=False, cell_kind="triclinic"), TOL_FP32),
+        "cfg2_2structs_molecules_fp32": (synth.shrink(W[2], n_structs=2, cell_kind="free", gemm_bf16=False), TOL_FP32),
+        "cfg1_2structs_molecules_bf16": (synth.shrink(W[1], n_structs=2, cell_kind="free", gemm_bf16=True), TOL_BF16),
     }
 
 
