@@ -343,9 +343,10 @@ void gemm_nt_fold(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N,
 
 int pick_splits(int64_t rows_out, int cols_out, int64_t K, int bm, int bn) {
   int64_t tiles = ((rows_out + bm - 1) / bm) * ((cols_out + bn - 1) / bn);
-  int64_t s = std::max<int64_t>(1, 768 / tiles);
+  // 512 workgroups = one resident round of this kernel (two per compute unit); more leave a partly filled second round
+  int64_t s = std::max<int64_t>(1, 512 / tiles);
   s = std::min<int64_t>(s, std::max<int64_t>(1, K / 64));
-  return (int)std::min<int64_t>(s, 768);
+  return (int)std::min<int64_t>(s, 512);
 }
 
 // grad[Nout][Kout] += A^T B, A [R][Nout], B [R][Kout] given by loaders (reduction over R rows).
