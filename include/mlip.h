@@ -184,6 +184,23 @@ int mlip_kernel_timer_select(mlip_ctx* ctx, int kernel_id);
 int mlip_copy_probe(mlip_ctx* ctx, float* dst, const float* src, int64_t n_floats);
 int mlip_kernel_timer_read(mlip_ctx* ctx, int64_t* launches_host, float* total_ms_host);
 
+/* Optimizer step (Table 2, runtime-control instruction "OS"; it follows the summation of the BF
+ * and BE parameter gradients, Sec. 3).  The paper names no optimizer: this is AdamW.  In place,
+ * asynchronous on the context's stream, float32 arithmetic:
+ *   g = grad_scale * grad;  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *   params <- params - lr * ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *                             + weight_decay * params )
+ * params, grad, m, v: device float32 [n] (m and v zero before step 1; the four arrays must not
+ * overlap); step counts from 1; hyper_host is a host pointer, read before the call returns.
+ * grad_scale folds a gradient average (e.g. 1 / number of accumulated micro-batches) into the pass.
+ * MLIP_E_INVALID: null pointer, n < 0, step < 1, beta outside [0, 1), negative eps or weight_decay,
+ * non-finite values.  n = 0 is a no-op.  Needs no graph and does not touch the context's state. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay, grad_scale;
+} mlip_adamw;
+int mlip_optimizer_step(mlip_ctx* ctx, int64_t n, float* params, const float* grad, float* m, float* v,
+                        int32_t step, const mlip_adamw* hyper_host);
+
 /* Graph-aware rescheduling (Appendix A.2, Algorithm 1): HOST routine, host pointers only.
  * Repacks the n_graphs graphs of a global batch (sizes_host[g] = atom count) into n_mb
  * micro-batches: graphs sorted by size descending (ties: lower index first), each placed into

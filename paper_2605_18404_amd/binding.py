@@ -35,6 +35,11 @@ class mlip_config(C.Structure):
                 ("max_atoms", C.c_int64), ("max_structs", C.c_int64), ("max_edges", C.c_int64)]
 
 
+class mlip_adamw(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("grad_scale", C.c_float)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -65,6 +70,7 @@ def load():
     lib.mlip_copy_probe.argtypes = [P, P, P, I64]
     lib.mlip_gars_pack.argtypes = [P, I64, I32, I32, C.c_uint64, P, P, P]
     lib.mlip_set_expert_weights.argtypes = [P, P, I32]
+    lib.mlip_optimizer_step.argtypes = [P, I64, P, P, P, P, I32, C.POINTER(mlip_adamw)]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
     lib.mlip_loss.argtypes = [P, P, P, P, P, P, P, P]
@@ -199,6 +205,16 @@ class Mlip:
     def mlip_set_expert_weights(self, alpha):
         """alpha: device tensor [n_structs, n_experts] float32."""
         self._check(self.lib.mlip_set_expert_weights(self.ctx, _ptr(alpha, torch.float32), int(alpha.shape[0])))
+
+    def mlip_optimizer_step(self, params, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                            grad_scale=1.0):
+        """In-place AdamW update of device float32 vectors params, m, v from grad."""
+        n = params.numel()
+        if not (grad.numel() == n and m.numel() == n and v.numel() == n):
+            raise ValueError("params, grad, m and v must have the same number of elements")
+        h = mlip_adamw(lr, beta1, beta2, eps, weight_decay, grad_scale)
+        self._check(self.lib.mlip_optimizer_step(self.ctx, n, _ptr(params, torch.float32), _ptr(grad, torch.float32),
+                                                 _ptr(m, torch.float32), _ptr(v, torch.float32), int(step), C.byref(h)))
 
     def mlip_forward_energy(self, pos, species, params, h_in=None):
         f = dict(device=self.device, dtype=torch.float32)
