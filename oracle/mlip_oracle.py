@@ -25,7 +25,8 @@ listed with each function.
 
 Pins (tests/test_oracle_*.py): neighbour list vs a k-d tree and lattice coordination
 numbers; spherical harmonics vs scipy; Gaunt tensors vs selection rules and rotation
-equivariance; E invariances and closed forms; F vs central differences of E; dL/dtheta
+equivariance; E invariances and closed forms (the gated update also against the linear one
+with halved matrices when its gate scalars vanish); F vs central differences of E; dL/dtheta
 vs central differences of L; BF+BE = total; stage outputs vs central differences of the
 stage scalar and vs the unsplit model.  No function here is left unpinned.
 """
@@ -334,6 +335,9 @@ def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
     m = envelope(r, cfg["cutoff"])[:, None, None] * torch.cat(parts, dim=2)
     a = torch.zeros_like(h).index_add(0, rcv, m)
     upd = [lin.node(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(3)]
+    if cfg.get("gate", 0):
+        u0 = upd[0]
+        upd = [silu(u0), torch.sigmoid(u0) * upd[1], torch.sigmoid(u0) * upd[2]]
     return h + torch.cat(upd, dim=2)
 
 
@@ -473,4 +477,4 @@ def cfg_from_workload(w) -> Dict:
     return dict(kind=kind, channels=w.channels, edge_hidden=w.edge_hidden, n_rbf=w.n_rbf,
                 n_species=w.n_species, n_layers=w.n_layers, edge_depth=w.edge_depth,
                 cutoff=float(w.cutoff), force_weight=float(w.force_weight),
-                n_experts=int(getattr(w, "n_experts", 0)))
+                n_experts=int(getattr(w, "n_experts", 0)), gate=int(getattr(w, "gate", 0)))

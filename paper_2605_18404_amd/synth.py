@@ -88,6 +88,7 @@ class Workload:
     force_weight: float = 10.0
     min_dist: float = 1.0
     cell_kind: str = "cubic"  # "cubic" | "triclinic" (sheared lattice, per structure) | "free" (molecule in vacuum: zero cell)
+    gate: int = 0             # 1 (equivariant model): gated nonlinearity in the node update instead of the linear residual
     n_experts: int = 0        # > 0: the node-level matrices of every layer (update MLP / per-l mixing) are banks of this many experts
 
     @property
