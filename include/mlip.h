@@ -76,6 +76,9 @@ typedef struct {
                                (invariant: the update MLP's two; equivariant: the three per-l mixing
                                matrices) are banks [n_experts][C][C] in the parameter vector, merged
                                per structure with mlip_set_expert_weights' coefficients */
+  int32_t gate;             /* 0: the equivariant node update is linear, h += W^(l) a.  1 (equivariant model
+                               only): gated nonlinearity, with u = W^(l) a per channel
+                               h_0 += silu(u_0), h_lm += sigmoid(u_0) u_lm for l = 1, 2 */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */

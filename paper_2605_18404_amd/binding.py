@@ -31,7 +31,7 @@ class mlip_config(C.Structure):
     _fields_ = [("model_kind", C.c_int32), ("n_species", C.c_int32), ("channels", C.c_int32),
                 ("n_layers", C.c_int32), ("n_rbf", C.c_int32), ("edge_hidden", C.c_int32),
                 ("edge_mlp_depth", C.c_int32), ("l_max", C.c_int32), ("gemm_dtype", C.c_int32),
-                ("n_experts", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
+                ("n_experts", C.c_int32), ("gate", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
                 ("max_atoms", C.c_int64), ("max_structs", C.c_int64), ("max_edges", C.c_int64)]
 
 
@@ -113,14 +113,14 @@ class Mlip:
 
     def __init__(self, *, model_kind: int, channels: int, n_layers: int, n_rbf: int, edge_hidden: int,
                  edge_mlp_depth: int = 2, l_max: int = 0, n_species: int = 1, gemm_bf16: bool = False,
-                 n_experts: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
+                 n_experts: int = 0, gate: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
                  device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
         self.lib = load()
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self.cfg = mlip_config(model_kind, n_species, channels, n_layers, n_rbf, edge_hidden, edge_mlp_depth, l_max,
-                               1 if gemm_bf16 else 0, n_experts, cutoff, force_weight, max_atoms, max_structs, max_edges)
+                               1 if gemm_bf16 else 0, n_experts, gate, cutoff, force_weight, max_atoms, max_structs, max_edges)
         self.ctx = C.c_void_p()
         s = self.lib.mlip_create(C.byref(self.cfg), C.c_void_p(self.stream.cuda_stream), C.byref(self.ctx))
         if s != 0:
@@ -140,7 +140,7 @@ class Mlip:
             max_edges = int(w.n_atoms * (deg * 1.15 + 8))
         args = dict(model_kind=w.kind, channels=w.channels, n_layers=w.n_layers, n_rbf=w.n_rbf,
                     edge_hidden=w.edge_hidden, edge_mlp_depth=w.edge_depth, l_max=w.l_max, n_species=w.n_species,
-                    gemm_bf16=w.gemm_bf16, n_experts=getattr(w, "n_experts", 0), cutoff=w.cutoff, force_weight=w.force_weight, max_atoms=w.n_atoms,
+                    gemm_bf16=w.gemm_bf16, n_experts=getattr(w, "n_experts", 0), gate=getattr(w, "gate", 0), cutoff=w.cutoff, force_weight=w.force_weight, max_atoms=w.n_atoms,
                     max_structs=w.n_structs, max_edges=max_edges)
         args.update(kw)
         return cls(**args)

@@ -89,6 +89,8 @@ const char* check_config(const mlip_config& c) {
   if (c.gemm_dtype != MLIP_GEMM_FP32 && c.gemm_dtype != MLIP_GEMM_BF16) return "gemm_dtype must be 0 or 1";
   if (c.n_experts < 0 || c.n_experts > 1024) return "n_experts must be in [0, 1024]";
   if (c.n_experts > 0 && c.model_kind == MLIP_MODEL_STAGE) return "expert banks are built for the whole models only";
+  if (c.gate != 0 && c.gate != 1) return "gate must be 0 or 1";
+  if (c.gate == 1 && c.model_kind != MLIP_MODEL_EQUIVARIANT) return "the gated update belongs to the equivariant model";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
   if (c.max_atoms > 50000000 || c.max_edges > 2000000000LL) return "capacity too large for 32-bit indices";

@@ -44,6 +44,8 @@ struct EqvWs {
   float* X = nullptr;       // [E][C][12], operand precision
   float* X2 = nullptr;      // [E][H]
   std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [9][N][C]
+  std::vector<float*> u, mu_u, ud;  // gated update only, [9][N][C]: pre-activations W a, their FF cotangents, their BF tangents
+  float* lam_u = nullptr;           // gated update only: BE adjoint of the pre-activations
   float* lam_h[2] = {nullptr, nullptr};
   float* lam_a = nullptr;
   float* y = nullptr;
@@ -525,6 +527,79 @@ int mix_wgrad(mlip_ctx* ctx, int l, int k, const LdA& a, const LdB& b, float* gr
   return gemm_wgrad<P>(ctx, a, b, rows, C, C, g);
 }
 
+// ------------------------------------------------------------------------------ gated node update
+// cfg.gate: with u = W a (per l) the update is z_0 = silu(u_0), z_m = sigmoid(u_0) u_m for the eight
+// l = 1, 2 components m of the same channel, h' = h + z.  One thread per (atom, channel); arrays are
+// [9][N][C], component-major.  The four kernels are the map itself, its transpose applied to a
+// cotangent (FF), its tangent map (BF), and for BE the transpose applied to lambda plus the derivative
+// with respect to u of <ud, J(u)^T mu> (ud: BF's tangent of u, mu: FF's cotangent of z).
+struct GateFn {
+  float s, ds, dds, f1, f2;  // sigmoid, its first and second derivative; silu', silu''
+};
+__device__ __forceinline__ GateFn gate_fn(float u0) {
+  GateFn g;
+  g.s = sigm(u0);
+  g.ds = g.s * (1.f - g.s);
+  g.dds = g.ds * (1.f - 2.f * g.s);
+  g.f1 = g.s + u0 * g.ds;
+  g.f2 = 2.f * g.ds + u0 * g.dds;
+  return g;
+}
+
+__global__ void k_gate_fe(const float* __restrict__ u, const float* __restrict__ h_in, float* __restrict__ h_out, int64_t NC) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= NC) return;
+  const float u0 = u[idx];
+  const float s = sigm(u0);
+  h_out[idx] = h_in[idx] + u0 * s;
+#pragma unroll
+  for (int m = 1; m < 9; ++m) h_out[m * NC + idx] = h_in[m * NC + idx] + s * u[m * NC + idx];
+}
+
+__global__ void k_gate_ff(const float* __restrict__ u, const float* __restrict__ mu, float* __restrict__ mu_u, int64_t NC) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= NC) return;
+  const GateFn g = gate_fn(u[idx]);
+  float dot = 0.f;
+#pragma unroll
+  for (int m = 1; m < 9; ++m) {
+    const float mm = mu[m * NC + idx];
+    dot += u[m * NC + idx] * mm;
+    mu_u[m * NC + idx] = g.s * mm;
+  }
+  mu_u[idx] = g.f1 * mu[idx] + g.ds * dot;
+}
+
+__global__ void k_gate_bf(const float* __restrict__ u, const float* __restrict__ ud, const float* __restrict__ hd_in,
+                          float* __restrict__ hd_out, int64_t NC) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= NC) return;
+  const GateFn g = gate_fn(u[idx]);
+  const float ud0 = ud[idx];
+  hd_out[idx] = hd_in[idx] + g.f1 * ud0;
+#pragma unroll
+  for (int m = 1; m < 9; ++m)
+    hd_out[m * NC + idx] = hd_in[m * NC + idx] + (g.ds * ud0 * u[m * NC + idx] + g.s * ud[m * NC + idx]);
+}
+
+__global__ void k_gate_be(const float* __restrict__ u, const float* __restrict__ ud, const float* __restrict__ mu,
+                          const float* __restrict__ lam, float* __restrict__ lam_u, int64_t NC) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= NC) return;
+  const GateFn g = gate_fn(u[idx]);
+  const float ud0 = ud[idx];
+  float u_lam = 0.f, u_mu = 0.f, ud_mu = 0.f;
+#pragma unroll
+  for (int m = 1; m < 9; ++m) {
+    const float um = u[m * NC + idx], mm = mu[m * NC + idx], lm = lam[m * NC + idx];
+    u_lam += um * lm;
+    u_mu += um * mm;
+    ud_mu += ud[m * NC + idx] * mm;
+    lam_u[m * NC + idx] = g.s * lm + ud0 * g.ds * mm;
+  }
+  lam_u[idx] = g.f1 * lam[idx] + g.ds * u_lam + ud0 * (g.f2 * mu[idx] + g.dds * u_mu) + g.ds * ud_mu;
+}
+
 // ------------------------------------------------------------------------------ phases
 constexpr int LOFF[3] = {0, 1, 4};
 
@@ -538,6 +613,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
+  const bool gate = cf.gate != 0;
   auto tr = [&](int64_t off, int rows, int cols) {
     hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
   };
@@ -579,8 +655,12 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
+      if (gate)
+        mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiStore{w->u[l] + o, C, rows});
+      else
+        mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
+    if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC);
   }
   gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
   hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
@@ -598,6 +678,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   const int64_t N = ctx->N, NC = N * cf.channels;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
+  const bool gate = cf.gate != 0;
   const float* tT = w->paramsT;
   // mu_h^L: l = 0 block from the readout, zero elsewhere
   hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->mu_h[L] + NC, 0.f, 8 * NC);
@@ -607,9 +688,14 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
+    const float* mu_z = w->mu_h[l + 1];  // cotangent of the update's output; through the gate it becomes that of W a
+    if (gate) {
+      hipLaunchKernelGGL(k_gate_ff, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->mu_h[l + 1], w->mu_u[l], NC);
+      mu_z = w->mu_u[l];
+    }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      mix_mm<P>(ctx, l, k, true, LdPlain{w->mu_h[l + 1] + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
+      mix_mm<P>(ctx, l, k, true, LdPlain{mu_z + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = uni ? k_tp_ff<TF, true> : k_tp_ff<TF, false>;
@@ -630,6 +716,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
+  const bool gate = cf.gate != 0;
   const float* tT = w->paramsT;
   typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
   TX* X = reinterpret_cast<TX*>(w->X);
@@ -649,9 +736,13 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
-      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{w->mu_h[l + 1] + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
+      if (gate)
+        mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiStore{w->ud[l] + o, C, rows});
+      else
+        mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
+      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{(gate ? w->mu_u[l] : w->mu_h[l + 1]) + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
+    if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC);
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
@@ -686,6 +777,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
+  const bool gate = cf.gate != 0;
   const float* tT = w->paramsT;
   typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
   TX* X = reinterpret_cast<TX*>(w->X);
@@ -706,10 +798,15 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
     float* lh = w->lam_h[cur ^ 1];
+    const float* lam_z = lh_next;  // adjoint of the update's output; through the gate it becomes that of W a
+    if (gate) {
+      hipLaunchKernelGGL(k_gate_be, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->mu_h[l + 1], lh_next, w->lam_u, NC);
+      lam_z = w->lam_u;
+    }
     for (int k = 0; k < 3; ++k) {
       const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
-      mix_mm<P>(ctx, l, k, true, LdPlain{lh_next + o, C}, EpiStore{w->lam_a + o, C, rows});
-      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lh_next + o, C}, LdPlain{w->a[l] + o, C}, grad)));
+      mix_mm<P>(ctx, l, k, true, LdPlain{lam_z + o, C}, EpiStore{w->lam_a + o, C, rows});
+      MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lam_z + o, C}, LdPlain{w->a[l] + o, C}, grad)));
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
@@ -779,11 +876,13 @@ int eqv_alloc(mlip_ctx* ctx) {
     if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
     w->Y1.push_back(A(E * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
+    if (cf.gate) { w->u.push_back(A(NC9)); w->mu_u.push_back(A(NC9)); w->ud.push_back(A(NC9)); }
     if (cf.n_experts > 0)
       for (int k = 0; k < 3; ++k) { w->Wm[k].push_back(A(B * C * C)); w->WmT[k].push_back(A(B * C * C)); }
   }
   for (int l = 0; l <= L; ++l) { w->h.push_back(A(NC9)); w->mu_h.push_back(A(NC9)); w->hd.push_back(A(NC9)); }
   w->lam_h[0] = A(NC9); w->lam_h[1] = A(NC9); w->lam_a = A(NC9);
+  if (cf.gate) w->lam_u = A(NC9);
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
   int64_t cap = 0;

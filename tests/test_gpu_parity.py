@@ -292,6 +292,63 @@ def test_mixture_of_linear_experts_parity(name):
     m.close()
 
 
+def gate_cases():
+    W = synth.WORKLOADS
+    tiny = dict(n_structs=2, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8, edge_hidden=8, n_rbf=8, n_layers=2)
+    return {
+        "eqv_tiny_gate_fp32": (synth.shrink(W[2], gemm_bf16=False, gate=1, **tiny), TOL_FP32),
+        "eqv_multi_image_gate_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                                   edge_hidden=16, n_rbf=8, n_layers=3, gemm_bf16=False, gate=1), TOL_FP32),
+        "cfg2_2structs_gate_fp32": (synth.shrink(W[2], n_structs=2, gemm_bf16=False, gate=1), TOL_FP32),
+        "cfg2_2structs_gate_bf16": (synth.shrink(W[2], n_structs=2, gate=1), TOL_BF16),
+        "eqv_tiny_gate_4experts_fp32": (synth.shrink(W[2], gemm_bf16=False, gate=1, n_experts=4, **dict(tiny, n_structs=3)), TOL_FP32),
+    }
+
+
+@pytest.mark.parametrize("name", list(gate_cases()))
+def test_gated_equivariant_update_parity(name):
+    """Gated nonlinearity in the equivariant node update: whole step against the oracle, and phase by phase
+    the BF and BE shares of the gradient (the gate has second-order terms of its own in both)."""
+    w, tol = gate_cases()[name]
+    inp = synth.make_inputs(w)
+    ref = oracle_train_step(w, inp, split=True)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    if w.n_experts > 0:
+        m.mlip_set_expert_weights(d.alpha)
+    out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    _check_step(w, inp, out, ref, tol)
+    m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff)
+    E = m.mlip_forward_energy(d.pos, d.species, d.params)
+    F = m.mlip_forward_force()
+    _, Ebar, v = m.mlip_loss(E, F, d.E_ref, d.F_ref)
+    g_bf = torch.zeros(m.mlip_param_count(), device=DEV)
+    g_be = torch.zeros_like(g_bf)
+    m.mlip_backward_force(v, g_bf)
+    m.mlip_backward_energy(g_be, Ebar=Ebar)
+    torch.cuda.synchronize()
+    assert rel(g_bf.cpu().numpy(), ref["grad_bf"]) < tol
+    assert rel(g_be.cpu().numpy(), ref["grad_be"]) < tol
+    m.close()
+    # the ungated context on the same inputs gives a different energy: the flag reaches the kernels
+    m0 = Mlip.for_workload(synth.shrink(w, gate=0))
+    if w.n_experts > 0:
+        m0.mlip_set_expert_weights(d.alpha)
+    out0 = m0.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    assert rel(out0["E"].cpu().numpy(), ref["E"]) > 10 * tol
+    m0.close()
+
+
+def test_gate_is_refused_outside_the_equivariant_model():
+    with pytest.raises(MlipError) as e:
+        Mlip.for_workload(synth.shrink(synth.WORKLOADS[0], gate=1))
+    assert e.value.code == -1
+    with pytest.raises(MlipError) as e:
+        Mlip.for_workload(synth.shrink(synth.WORKLOADS[2], n_structs=1, gate=2))
+    assert e.value.code == -1
+
+
 def test_mixture_of_linear_experts_ragged_batch_and_errors():
     """Structures of 1, 70 and 5 atoms (one of them spans two row tiles), and the entry point's error paths."""
     ns = [1, 70, 5]
