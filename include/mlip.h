@@ -64,7 +64,7 @@ typedef struct {
   int32_t n_species;        /* S (ignored for a stage) */
   int32_t channels;         /* C, multiple of 4 */
   int32_t n_layers;
-  int32_t n_rbf;            /* K >= 2, multiple of 4 */
+  int32_t n_rbf;            /* K: multiple of 4 in [4, 1024] */
   int32_t edge_hidden;      /* H, multiple of 4 */
   int32_t edge_mlp_depth;   /* 2 or 3 */
   int32_t l_max;            /* 0 (invariant, stage) or 2 (equivariant) */

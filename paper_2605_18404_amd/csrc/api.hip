@@ -80,7 +80,7 @@ const char* check_config(const mlip_config& c) {
   if (c.model_kind < 0 || c.model_kind > 2) return "model_kind must be 0, 1 or 2";
   if (c.channels < 4 || c.channels % 4 || c.channels > 1024) return "channels must be a multiple of 4 in [4, 1024]";
   if (c.edge_hidden < 4 || c.edge_hidden % 4) return "edge_hidden must be a positive multiple of 4";
-  if (c.n_rbf < 4 || c.n_rbf % 4) return "n_rbf must be a positive multiple of 4";
+  if (c.n_rbf < 4 || c.n_rbf % 4 || c.n_rbf > 1024) return "n_rbf must be a multiple of 4 in [4, 1024]";
   if (c.n_layers < 1 || c.n_layers > 64) return "n_layers must be in [1, 64]";
   if (c.edge_mlp_depth != 2 && c.edge_mlp_depth != 3) return "edge_mlp_depth must be 2 or 3";
   if (c.model_kind == MLIP_MODEL_EQUIVARIANT ? (c.l_max != 2 || c.edge_mlp_depth != 2) : (c.l_max != 0))

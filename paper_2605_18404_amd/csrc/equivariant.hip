@@ -630,8 +630,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   tr(ctx->off_U, C, C);
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights, their transposes and the regrouped filters
   if (E > 0)
-    hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
-                       ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
+    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->jphi);
   if (E > 0)
     hipLaunchKernelGGL(k_edge_cy<false>, dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
   hipLaunchKernelGGL(k_embed_l0, dim3(nblk(9 * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);

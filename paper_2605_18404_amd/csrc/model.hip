@@ -305,8 +305,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights and of their transposes
 
   if (E > 0)
-    hipLaunchKernelGGL(k_edge_features, dim3(nblk(E * K)), dim3(256), 0, st, ctx->d_pos, ctx->d_sender, ctx->d_receiver,
-                       ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, cf.cutoff, ctx->d_geo, w->env, w->jphi);
+    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->jphi);
   if (stage)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->h[0], h_in, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   else

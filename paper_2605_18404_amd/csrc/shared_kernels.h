@@ -498,15 +498,16 @@ int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int
 }
 
 // Edge geometry and featurisation: unit vector, length, Gaussian basis jets, envelope jet.
-__global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
-                                const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
-                                const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta, int64_t E,
-                                int K, float rc, float4* __restrict__ geo, float2* __restrict__ env,
-                                float* __restrict__ jphi) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= E * K) return;
-  int64_t e = idx / K;
-  int k = (int)(idx % K);
+// A thread writes four consecutive basis functions of one edge (16-byte stores); an edge takes
+// 2^qshift >= K/4 threads, so edge and quad indices come from shifts, not divisions.
+__global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
+                                                       const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
+                                                       const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta,
+                                                       int64_t E, int K, int qshift, float rc, float4* __restrict__ geo,
+                                                       float2* __restrict__ env, float* __restrict__ jphi) {
+  const int q = threadIdx.x & ((1 << qshift) - 1);
+  const int64_t e = (int64_t)blockIdx.x * (256 >> qshift) + (threadIdx.x >> qshift);
+  if (e >= E || 4 * q >= K) return;
   int i = receiver[e], j = sender[e], c = code[e];
   const StructMeta& m = meta[atom_struct[i]];
   // image shift S . cell (rows = lattice vectors); zero for a molecule, S_a L_a for a diagonal cell
@@ -520,11 +521,16 @@ __global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __
   float r = sqrtf(dx * dx + dy * dy + dz * dz);
   float dmu = rc / (float)(K - 1);
   float gamma = 0.5f / (dmu * dmu);
-  float t = r - (float)k * dmu;
-  float p = expf(-gamma * t * t);
-  jphi[(2 * e) * K + k] = p;
-  jphi[(2 * e + 1) * K + k] = -2.f * gamma * t * p;
-  if (k == 0) {
+  float p[4], d[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    float t = r - (float)(4 * q + u) * dmu;
+    p[u] = expf(-gamma * t * t);
+    d[u] = -2.f * gamma * t * p[u];
+  }
+  *reinterpret_cast<float4*>(jphi + (2 * e) * K + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
+  *reinterpret_cast<float4*>(jphi + (2 * e + 1) * K + 4 * q) = make_float4(d[0], d[1], d[2], d[3]);
+  if (q == 0) {
     float inv = 1.f / r;
     geo[e] = make_float4(dx * inv, dy * inv, dz * inv, r);
     float w = 3.14159265358979323846f / rc;
@@ -532,6 +538,14 @@ __global__ void k_edge_features(const float* __restrict__ pos, const int32_t* __
     sincosf(w * r, &sn, &cs);
     env[e] = make_float2(0.5f * (1.f + cs), -0.5f * w * sn);
   }
+}
+
+inline void launch_edge_features(mlip_ctx* ctx, int64_t E, int K, float rc, float2* env, float* jphi) {
+  int qshift = 0;
+  while ((4 << qshift) < K) ++qshift;  // 2^qshift threads per edge, K <= 1024
+  const int64_t per_block = 256 >> qshift;
+  hipLaunchKernelGGL(k_edge_features, dim3((unsigned)((E + per_block - 1) / per_block)), dim3(256), 0, ctx->stream, ctx->d_pos,
+                     ctx->d_sender, ctx->d_receiver, ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, qshift, rc, ctx->d_geo, env, jphi);
 }
 
 
