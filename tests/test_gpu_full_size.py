@@ -27,8 +27,10 @@ def _oracle_struct(w, inp, s):
     return a, b, r
 
 
-def test_cfg1_full_batch_all_outputs():
-    w = synth.WORKLOADS[1]
+@pytest.mark.parametrize("cell_kind", ["cubic", "triclinic", "free"])
+def test_cfg1_full_batch_all_outputs(cell_kind):
+    """The bench batch, and the same batch in sheared cells and as molecules in vacuum."""
+    w = synth.shrink(synth.WORKLOADS[1], cell_kind=cell_kind)
     inp = synth.make_inputs(w)
     ref = oracle_train_step(w, inp)  # all 32 structures
     m = Mlip.for_workload(w)
