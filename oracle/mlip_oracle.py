@@ -376,14 +376,15 @@ def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
                graph: Optional[Dict] = None, split: bool = False, alpha=None) -> Dict[str, np.ndarray]:
     """One training step of the whole model: returns loss, E [B], F [N,3], grad [n_params]
     (= dL/dtheta), and with split=True also grad_bf / grad_be, the BF and BE shares.
-    alpha [B, n_experts]: mixing coefficients of the expert banks (cfg["n_experts"] > 0)."""
+    alpha [B, n_experts]: mixing coefficients of the expert banks (cfg["n_experts"] > 0); then
+    grad_alpha = dL/dalpha is returned too."""
     if graph is None:
         graph = radius_graph(pos, struct_ptr, cell, cfg["cutoff"])
     x = _t(pos, True)
     cellt = _t(cell)
     theta = _t(params, True)
     P = unpack_params(theta, cfg)
-    al = None if alpha is None else _t(alpha)
+    al = None if alpha is None else _t(alpha, True)
     if split:
         theta_ff = _t(params, True)
         lin = _Lin(P, unpack_params(theta_ff, cfg), alpha=al)
@@ -394,14 +395,17 @@ def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
     F = -dEdx
     L = loss_fn(E, F, _t(E_ref), _t(F_ref), cfg["force_weight"])
     out = dict(E=E.detach().numpy(), F=F.detach().numpy(), loss=float(L.detach()))
+    wrt = [theta] + ([theta_ff] if split else []) + ([al] if al is not None else [])
+    gs = list(torch.autograd.grad(L, wrt, allow_unused=True))
+    if al is not None:  # dL/dalpha [B, n_experts]: what a router producing the coefficients would receive
+        out["grad_alpha"] = gs.pop().numpy()
     if split:
-        g_be, g_bf = torch.autograd.grad(L, [theta, theta_ff], allow_unused=True)
+        g_be, g_bf = gs
         g_bf = torch.zeros_like(theta) if g_bf is None else g_bf
         out["grad_be"], out["grad_bf"] = g_be.numpy(), g_bf.numpy()
         out["grad"] = out["grad_be"] + out["grad_bf"]
     else:
-        (g,) = torch.autograd.grad(L, theta)
-        out["grad"] = g.numpy()
+        out["grad"] = gs[0].numpy()
     return out
 
 

@@ -137,3 +137,44 @@ def test_gradient_against_finite_differences_and_split(eqv):
         assert abs(fd - r["grad"][i]) <= 1e-6 * max(1.0, abs(fd)), (i, fd, r["grad"][i])
     # the second-order share is not identically zero for the banks: the update MLP sits inside dE/dx
     assert np.abs(r["grad_bf"][off:off + int(np.prod(shape))]).max() > 0
+
+
+@pytest.mark.parametrize("eqv", [False, True])
+def test_coefficient_gradient_is_the_inner_product_of_expert_and_merged_matrix_gradient(eqv):
+    """dL/dalpha[s,k] = sum over banks <dL/dW_s, W_k>, with dL/dW_s taken from the dense model run on
+    structure s with hand-merged matrices; and against central differences."""
+    w = tiny(3, eqv)
+    inp = synth.make_inputs(w)
+    got = step(w, inp)
+    assert got["grad_alpha"].shape == (2, 3)
+    B = w.n_structs
+    for s in range(B):
+        w1, sub = one_structure(w, inp, s)
+        wd, pd = dense_params_from(w1, sub, sub.alpha[0])
+        cfg = O.cfg_from_workload(wd)
+        cfg["force_weight"] = cfg["force_weight"] / B   # the batch's force mean runs over B times as many atoms
+        src, dst = synth.param_slices(w1), synth.param_slices(wd)
+        # In the batch loss the structure's energy term carries 1/B and its force term is unchanged by the
+        # reweighting above: dense gradient of (full loss) minus (1 - 1/B) times that of the energy term alone.
+        r_full = O.train_step(cfg, sub.pos, sub.species, sub.struct_ptr, sub.cell, pd, sub.E_ref, sub.F_ref)
+        E_s = r_full["E"][0]
+        r_eonly = O.train_step(dict(cfg, force_weight=0.0), sub.pos, sub.species, sub.struct_ptr, sub.cell, pd, sub.E_ref, sub.F_ref)
+        g_dense = r_full["grad"] - r_eonly["grad"] * (1.0 - 1.0 / B)
+        want = np.zeros(3)
+        for name, (off, shape) in dst.items():
+            o2, s2 = src[name]
+            if len(s2) != 3:
+                continue
+            G = g_dense[off:off + int(np.prod(shape))].reshape(shape)
+            bank = inp.params[o2:o2 + int(np.prod(s2))].astype(np.float64).reshape(s2)
+            want += np.einsum("ij,kij->k", G, bank)
+        np.testing.assert_allclose(got["grad_alpha"][s], want, rtol=1e-8, atol=1e-12)
+        assert abs(E_s - got["E"][s]) < 1e-10 * max(1.0, abs(E_s))
+    a64 = inp.alpha.astype(np.float64)
+    for (s, k) in ((0, 1), (1, 2)):
+        h = 1e-6
+        ap, am = a64.copy(), a64.copy()
+        ap[s, k] += h
+        am[s, k] -= h
+        fd = (step(w, inp, alpha=ap)["loss"] - step(w, inp, alpha=am)["loss"]) / (2 * h)
+        assert abs(fd - got["grad_alpha"][s, k]) <= 1e-6 * max(1.0, abs(fd))
