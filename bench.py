@@ -131,6 +131,8 @@ def main():
     st = {k: t(v) for k, v in inp.stage.items()}
     if w.n_experts > 0:
         m.mlip_set_expert_weights(t(inp.alpha))
+        grad_alpha = torch.zeros(w.n_structs, w.n_experts, device=dev)
+        m.mlip_set_expert_weight_grad(grad_alpha)  # the step then also yields the router's gradient dL/dalpha
     out = None
     grad = torch.zeros(m.mlip_param_count(), device=dev)
 

@@ -133,6 +133,13 @@ int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t*
  * has n_experts > 0 (MLIP_E_STATE otherwise), with n_structs equal to the graph's; MLIP_E_INVALID
  * for a dense context.  The gradient with respect to alpha is not produced. */
 int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs);
+/* Optional gradient with respect to those coefficients (what a router producing them would be
+ * trained with): dL/dalpha[s][k] = sum over the banks of <dL/dW_s, W_k>.  grad_alpha: device pointer
+ * [n_structs][n_experts] float32, or NULL to switch it off again (the default; nothing is computed
+ * then).  While set, mlip_backward_force and mlip_backward_energy ADD their shares to it, as they do
+ * for grad_params (the caller zeroes it), and mlip_train_step zeroes it itself before its two
+ * backward phases.  The caller keeps the buffer alive and sized for the batches it builds. */
+int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha);
 
 /* FE.  Whole model: h^0 = emb[species], E[B] written.  Stage: h_in[N,C] read, h_out[N,C]
  * written, species and E may be NULL.  pos and params are copied into the context, so the

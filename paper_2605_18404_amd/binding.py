@@ -70,6 +70,7 @@ def load():
     lib.mlip_copy_probe.argtypes = [P, P, P, I64]
     lib.mlip_gars_pack.argtypes = [P, I64, I32, I32, C.c_uint64, P, P, P]
     lib.mlip_set_expert_weights.argtypes = [P, P, I32]
+    lib.mlip_set_expert_weight_grad.argtypes = [P, P]
     lib.mlip_optimizer_step.argtypes = [P, I64, P, P, P, P, I32, C.POINTER(mlip_adamw)]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
@@ -205,6 +206,11 @@ class Mlip:
     def mlip_set_expert_weights(self, alpha):
         """alpha: device tensor [n_structs, n_experts] float32."""
         self._check(self.lib.mlip_set_expert_weights(self.ctx, _ptr(alpha, torch.float32), int(alpha.shape[0])))
+
+    def mlip_set_expert_weight_grad(self, grad_alpha):
+        """grad_alpha: device tensor [n_structs, n_experts] float32 that BF and BE add dL/dalpha to, or None."""
+        self._check(self.lib.mlip_set_expert_weight_grad(self.ctx, _ptr(grad_alpha, torch.float32)))
+        self._grad_alpha = grad_alpha  # keep the tensor alive while the library holds its address
 
     def mlip_optimizer_step(self, params, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
                             grad_scale=1.0):

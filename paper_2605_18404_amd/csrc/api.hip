@@ -158,6 +158,13 @@ int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs
   return MLIP_OK;
 }
 
+int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (ctx->cfg.n_experts <= 0) MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weight_grad: the context has no expert banks");
+  ctx->d_grad_alpha = grad_alpha;
+  return MLIP_OK;
+}
+
 int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host) {
   if (!ctx) return MLIP_E_INVALID;
   if (ctx->phase < PH_GRAPH) return MLIP_E_STATE;
@@ -255,6 +262,9 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
   if (s == MLIP_OK) s = model_loss(ctx, E, F, E_ref, F_ref, loss, sb->Ebar, sb->v);
   if (s == MLIP_OK && timed) hipEventRecord(ev[3], st);
   if (s == MLIP_OK && hipMemsetAsync(grad_params, 0, sizeof(float) * ctx->n_params, st) != hipSuccess) s = MLIP_E_HIP;
+  if (s == MLIP_OK && ctx->d_grad_alpha &&
+      hipMemsetAsync(ctx->d_grad_alpha, 0, sizeof(float) * (size_t)ctx->B * ctx->cfg.n_experts, st) != hipSuccess)
+    s = MLIP_E_HIP;
   if (s == MLIP_OK) s = model_backward_force(ctx, sb->v, nullptr, grad_params, nullptr);
   if (s == MLIP_OK && timed) hipEventRecord(ev[4], st);
   if (s == MLIP_OK) s = model_backward_energy(ctx, sb->Ebar, nullptr, grad_params, nullptr);

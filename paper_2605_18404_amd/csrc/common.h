@@ -109,6 +109,7 @@ struct mlip_ctx {
   // ---- mixture of linear experts (n_experts > 0)
   float* d_alpha = nullptr;        // [max_structs][n_experts] coefficients (mlip_set_expert_weights)
   int32_t alpha_structs = -1;      // how many rows of d_alpha are set
+  float* d_grad_alpha = nullptr;   // caller's buffer [B][n_experts] for dL/dalpha, or null (mlip_set_expert_weight_grad)
   int4* d_row_groups = nullptr;    // row tiles of 64 atoms that never straddle a structure: (first, end, structure, 0)
   std::vector<int4> h_row_groups;
   std::vector<int32_t> h_k_ranges;

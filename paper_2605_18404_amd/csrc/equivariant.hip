@@ -523,7 +523,7 @@ int mix_wgrad(mlip_ctx* ctx, int l, int k, const LdA& a, const LdB& b, float* gr
   const int C = ctx->cfg.channels;
   const int64_t rows = (2 * k + 1) * ctx->N;
   float* g = grad + ctx->lay[l].Wl[k];
-  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, rows, C, C, g, 2 * k + 1);
+  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, rows, C, C, g, ctx->d_params + ctx->lay[l].Wl[k], 2 * k + 1);
   return gemm_wgrad<P>(ctx, a, b, rows, C, C, g);
 }
 
@@ -892,7 +892,8 @@ int eqv_alloc(mlip_ctx* ctx) {
   };
   need(PC, H, E); need(H, K, E); need(C, C, 5 * N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);
-  if (cf.n_experts > 0) cap = std::max<int64_t>(cap, 5 * B * (int64_t)C * C);  // one weight-gradient partial per (component, structure)
+  if (cf.n_experts > 0)  // one weight-gradient partial per (component, structure), plus the split products of the coefficient gradient
+    cap = std::max<int64_t>(cap, 5 * B * ((int64_t)C * C + 256 * (int64_t)((cf.n_experts + 3) / 4 * 4)));
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);
   return ok ? MLIP_OK : MLIP_E_HIP;

@@ -267,8 +267,9 @@ void node_mm(mlip_ctx* ctx, int l, int which, bool transposed, const LdA& a, con
 template <typename P, typename LdA, typename LdB>
 int node_wgrad(mlip_ctx* ctx, int l, int which, const LdA& a, const LdB& b, float* grad) {
   const int C = ctx->cfg.channels;
-  float* g = grad + (which ? ctx->lay[l].V2 : ctx->lay[l].V1);
-  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, ctx->N, C, C, g);
+  const int64_t off = which ? ctx->lay[l].V2 : ctx->lay[l].V1;
+  float* g = grad + off;
+  if (ctx->cfg.n_experts > 0) return gemm_wgrad_experts<P>(ctx, a, b, ctx->N, C, C, g, ctx->d_params + off);
   return gemm_wgrad<P>(ctx, a, b, ctx->N, C, C, g);
 }
 
@@ -600,7 +601,8 @@ int inv_alloc(mlip_ctx* ctx) {
   };
   need(C, H, E); need(H, H, E); need(H, K, E); need(C, C, N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);  // atom-chunk partials
-  if (cf.n_experts > 0) cap = std::max<int64_t>(cap, B * (int64_t)C * C);  // one weight-gradient partial per structure
+  if (cf.n_experts > 0)  // one weight-gradient partial per structure, plus the split products of the coefficient gradient
+    cap = std::max<int64_t>(cap, B * ((int64_t)C * C + 256 * (int64_t)((cf.n_experts + 3) / 4 * 4)));
   if (cf.gemm_dtype == MLIP_GEMM_FP32 && K <= 32) cap = std::max<int64_t>(cap, fold_partial_floats(E, H, K));  // folded first-matrix gradient
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);

@@ -465,6 +465,31 @@ __global__ void __launch_bounds__(256) k_expert_grad(const float* __restrict__ a
   }
 }
 
+// Coefficient gradient, last step: grad_alpha[s][k] += sum_z part2[z][s][k] (z runs over k-splits and
+// component copies); part2 rows are padded to ldp columns.  64 entries x 4 groups of z per block, four
+// independent running sums per thread, combined in a fixed order.
+__global__ void __launch_bounds__(256) k_alpha_reduce(const float* __restrict__ part2, int Z, int B, int Ke, int ldp,
+                                                      float* __restrict__ grad_alpha) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, zg = threadIdx.x >> 6;
+  const int idx = blockIdx.x * 64 + lane;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (idx < B * Ke) {
+    const int64_t base = (int64_t)(idx / Ke) * ldp + idx % Ke, stride = (int64_t)B * ldp;
+    int z = zg;
+    for (; z + 12 < Z; z += 16) {
+      s0 += part2[z * stride + base];
+      s1 += part2[(z + 4) * stride + base];
+      s2 += part2[(z + 8) * stride + base];
+      s3 += part2[(z + 12) * stride + base];
+    }
+    for (; z < Z; z += 4) s0 += part2[z * stride + base];
+  }
+  red[zg][lane] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (zg == 0 && idx < B * Ke) grad_alpha[idx] += (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
 // D = A W_s^T with the merged matrix of each row's structure (Wm [B][N*K]); 64-row tiles that end
 // with their structure (the context's row-group table).  copies: A stacks that many copies of the
 // atom rows (the 2l+1 components of an equivariant block), M = copies * N_atoms.
@@ -478,9 +503,10 @@ void gemm_nt_grouped(mlip_ctx* ctx, const LdA& a, const float* Wm, int64_t M, in
 }
 // Expert-bank gradient: one weight-gradient partial per structure (split z = structure z's
 // atoms), then grad_bank[k] += sum_s alpha[s][k] partial[s].
+// bank: the expert matrices themselves (for the coefficient gradient, when the caller asked for it).
 template <typename P, typename LdA, typename LdB>
 int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad_bank,
-                       int copies = 1) {
+                       const float* bank, int copies = 1) {
   const int B = ctx->B, Ke = ctx->cfg.n_experts;
   const int64_t n = (int64_t)Nout * Kout;
   if (R <= 0 || B <= 0) return MLIP_OK;
@@ -494,6 +520,19 @@ int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int
     gemm::launch<P, 1, 1, 2, 2, false>(ctx->stream, a, b, epi, Nout, Kout, R, B * copies, g);
   hipLaunchKernelGGL(k_expert_grad, dim3(nblk(n), (Ke + 15) / 16), dim3(256), 0, ctx->stream, ctx->d_alpha, ctx->partial.buf, B,
                      copies, Ke, n, grad_bank);
+  if (ctx->d_grad_alpha) {
+    // dL/dalpha[s][k] = sum over copies of <partial[m B + s], W_k>: the product [B copies, n] x [Ke, n]^T over
+    // the n matrix entries, split along n; always in fp32 (it is tiny)
+    const int ldp = (Ke + 3) / 4 * 4;
+    const int64_t rows = (int64_t)B * copies;
+    const int splits = (int)std::min<int64_t>(128, std::max<int64_t>(1, n / 64));
+    float* part2 = ctx->partial.buf + rows * n;
+    if (rows * n + (int64_t)splits * rows * ldp > ctx->partial.cap) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "coefficient gradient: partial buffer too small");
+    const int used = gemm::launch<gemm::Fp32, 1, 1, 2, 2, true>(ctx->stream, LdPlain{ctx->partial.buf, n}, LdPlain{bank, n},
+                                                                EpiPartial{part2, ldp, rows}, rows, Ke, n, splits);
+    // part2 is [split][copy][structure][ldp]: splits and copies are summed together
+    hipLaunchKernelGGL(k_alpha_reduce, dim3(nblk((int64_t)B * Ke, 64)), dim3(256), 0, ctx->stream, part2, used * copies, B, Ke, ldp, ctx->d_grad_alpha);
+  }
   return MLIP_OK;
 }
 

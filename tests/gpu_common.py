@@ -45,6 +45,7 @@ def oracle_train_step(w, inp, split=False):
     keys = ["grad"] + (["grad_bf", "grad_be"] if split else [])
     g = {k: np.zeros(inp.params.shape[0]) for k in keys}
     loss = 0.0
+    grad_alpha = None if inp.alpha is None else np.zeros(inp.alpha.shape)
     for s in range(B):
         a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
         # the batch loss is mean_s(.) + fw * mean over all 3N components: rescale a single
@@ -60,7 +61,11 @@ def oracle_train_step(w, inp, split=False):
         loss += r["loss"] / B
         for k in keys:
             g[k] += r[k] / B
+        if grad_alpha is not None:
+            grad_alpha[s] = r["grad_alpha"][0] / B
     out = dict(E=E, F=F, loss=loss)
+    if grad_alpha is not None:
+        out["grad_alpha"] = grad_alpha
     out.update(g)
     return out
 

@@ -277,6 +277,15 @@ def test_mixture_of_linear_experts_parity(name):
     out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
     torch.cuda.synchronize()
     _check_step(w, inp, out, ref, tol)
+    # the same step with the coefficient gradient switched on: same outputs bit for bit, plus dL/dalpha
+    ga = torch.full((w.n_structs, w.n_experts), 7.0, device=DEV)  # train_step zeroes it itself
+    m.mlip_set_expert_weight_grad(ga)
+    out2 = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
+    torch.cuda.synchronize()
+    assert torch.equal(out2["grad"], out["grad"]) and torch.equal(out2["E"], out["E"])
+    assert rel(ga.cpu().numpy(), ref["grad_alpha"]) < tol
+    assert np.abs(ga.cpu().numpy() - ref["grad_alpha"]).max() < 3 * tol * np.abs(ref["grad_alpha"]).max()
+    m.mlip_set_expert_weight_grad(None)
     # phase by phase: the two shares of the gradient (Eq. 2), banks included
     m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff)
     E = m.mlip_forward_energy(d.pos, d.species, d.params)
