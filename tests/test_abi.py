@@ -61,3 +61,31 @@ def test_generator_is_deterministic_and_bounded():
     assert set(np.unique(a.species)) <= set(range(w.n_species))
     n = synth.normal(1, 2, 0, 20000)
     assert abs(n.mean()) < 0.03 and abs(n.std() - 1) < 0.03
+
+
+def test_header_is_plain_c_and_matches_the_binding_structs(tmp_path):
+    """The header compiles as C99 on its own, and the ctypes mirrors of its structs have the C
+    compiler's sizes and field offsets."""
+    import shutil
+    import subprocess
+    from paper_2605_18404_amd import binding
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    fields = {"mlip_config": [f[0] for f in binding.mlip_config._fields_],
+              "mlip_adamw": [f[0] for f in binding.mlip_adamw._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mlip.h"', 'int main(void) {']
+    for st, fs in fields.items():
+        lines.append(f'  printf("{st} %zu\\n", sizeof({st}));')
+        for f in fs:
+            lines.append(f'  printf("{st}.{f} %zu\\n", offsetof({st}, {f}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "probe.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True, capture_output=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st, cls in (("mlip_config", binding.mlip_config), ("mlip_adamw", binding.mlip_adamw)):
+        assert int(out[st]) == ctypes.sizeof(cls)
+        for f in fields[st]:
+            assert int(out[f"{st}.{f}"]) == getattr(cls, f).offset, (st, f)
