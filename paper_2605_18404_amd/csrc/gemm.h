@@ -15,7 +15,7 @@
 //   Fp32: v_mfma_f32_32x32x2_f32; LDS stage k-major [BK][rows+4] (fragment = one float).
 //   Bf16: v_mfma_f32_32x32x16_bf16; operands rounded to bf16 (nearest even) while staged, fp32
 //         accumulate.  KC: LDS stage row-major [rows][BK+8] (fragment = one 16-byte read of 8
-//         consecutive k).  KS: k-major [BK][rows+8], fragment gathered with eight 2-byte reads.
+//         consecutive k).  KS: k-major [BK][rows+16], fragment = two transposing 8-byte reads.
 //
 #pragma once
 #include <hip/hip_runtime.h>
@@ -26,6 +26,11 @@ namespace gemm {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// ds_read_b64_tr_b16: 8 bytes per lane, exchanged inside groups of 16 lanes (see its use below).
+__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)p);
+}
 
 struct Fp32 {
   typedef float lds_t;
@@ -44,7 +49,9 @@ template <typename P, int ROWS, int BK, bool KC>
 struct Tile {
   // k-major unless bf16 with k-contiguous operands
   static constexpr bool K_MAJOR = !(P::IS_BF16 && KC);
-  static constexpr int PAD = P::IS_BF16 ? 8 : 4;
+  // bf16 k-major: the row pitch is 8 dwords more than a multiple of 32, so the four k rows that one
+  // transposed read touches (16 lanes x 8 bytes) fall into 16 distinct pairs of banks
+  static constexpr int PAD = P::IS_BF16 ? (K_MAJOR ? 16 : 8) : 4;
   static constexpr int LD = K_MAJOR ? (ROWS + PAD) : (BK + PAD);
   static constexpr int SIZE = K_MAJOR ? (BK * LD) : (ROWS * LD);
 };
@@ -294,14 +301,27 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chu
           for (int j = 0; j < TN; ++j)
             bf[j] = *reinterpret_cast<const bf16x8*>(&b_s[((wn * TN + j) * 32 + li) * LDB + 16 * kk + 8 * g]);
         } else {
+          // k-major stage [k][row]: a lane needs eight consecutive k of ONE row.  The transposing LDS read
+          // (ds_read_b64_tr_b16) does that exchange inside groups of 16 lanes: lane s of a group supplies
+          // the address of four consecutive rows at k0 + s/4, starting at row 4 (s % 4), and lane i of the
+          // group receives the values of row i for k0 .. k0+3.  Two such reads make a fragment.
+          const int s16 = lane & 15, rq = ((lane >> 4) & 1) * 16 + 4 * (s16 & 3), kq = 8 * g + (s16 >> 2);
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) af[i][r] = a_s[(16 * kk + 8 * g + r) * LDA + (wm * TM + i) * 32 + li];
+            for (int hf = 0; hf < 2; ++hf) {
+              const bf16x4 v = lds_read_tr(&a_s[(16 * kk + kq + 4 * hf) * LDA + (wm * TM + i) * 32 + rq]);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) af[i][4 * hf + r] = v[r];
+            }
 #pragma unroll
           for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 8; ++r) bf[j][r] = b_s[(16 * kk + 8 * g + r) * LDB + (wn * TN + j) * 32 + li];
+            for (int hf = 0; hf < 2; ++hf) {
+              const bf16x4 v = lds_read_tr(&b_s[(16 * kk + kq + 4 * hf) * LDB + (wn * TN + j) * 32 + rq]);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) bf[j][4 * hf + r] = v[r];
+            }
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
