@@ -76,26 +76,31 @@ def cpu_baseline(w, inp, budget_s=20.0):
         inp = synth.make_inputs(w)
         note = f"a {n}-atom cell of the same density and model stands in for the large cell; "
     cfg = O.cfg_from_workload(w)
-    done_atoms, t_used, n_done = 0, 0.0, 0
-    for s in range(w.n_structs):
-        a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
-        sp = np.array([0, b - a], np.int32)
-        t0 = time.perf_counter()
-        if w.kind == synth.KIND_STAGE:
-            st = {k: v[a:b] for k, v in inp.stage.items()}
-            O.stage_step(cfg, inp.pos[a:b], sp, inp.cell[s:s + 1], inp.params, st["h_in"], st["g_out"], st["hdot_in"],
-                         st["v"], st["lam_out"])
-        else:
-            O.train_step(cfg, inp.pos[a:b], inp.species[a:b], sp, inp.cell[s:s + 1], inp.params, inp.E_ref[s:s + 1],
-                         inp.F_ref[a:b])
-        t_used += time.perf_counter() - t0
-        done_atoms += b - a
-        n_done += 1
+    done_atoms, t_used, n_done, passes = 0, 0.0, 0, 0
+    # whole passes over the batch until about 12 s are spent (at most 10 passes), never beyond budget_s
+    while t_used < 12.0 and passes < 10:
+        for s in range(w.n_structs):
+            a, b = int(inp.struct_ptr[s]), int(inp.struct_ptr[s + 1])
+            sp = np.array([0, b - a], np.int32)
+            t0 = time.perf_counter()
+            if w.kind == synth.KIND_STAGE:
+                st = {k: v[a:b] for k, v in inp.stage.items()}
+                O.stage_step(cfg, inp.pos[a:b], sp, inp.cell[s:s + 1], inp.params, st["h_in"], st["g_out"], st["hdot_in"],
+                             st["v"], st["lam_out"])
+            else:
+                O.train_step(cfg, inp.pos[a:b], inp.species[a:b], sp, inp.cell[s:s + 1], inp.params, inp.E_ref[s:s + 1],
+                             inp.F_ref[a:b], alpha=None if inp.alpha is None else inp.alpha[s:s + 1])
+            t_used += time.perf_counter() - t0
+            done_atoms += b - a
+            n_done += 1
+            if t_used > budget_s:
+                break
+        passes += 1
         if t_used > budget_s:
             break
     return {"value": done_atoms / t_used, "unit": "atoms/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{note}{n_done} of {w.n_structs} structures ({done_atoms} atoms), graph build + full step each, "
-                      f"{t_used:.1f} s of CPU time"}
+            "sample": f"{note}{n_done} structure steps ({passes} pass(es) over the batch's {w.n_structs} structures, {done_atoms} atoms), "
+                      f"graph build + full step each, {t_used:.1f} s of CPU time"}
 
 
 def main():
