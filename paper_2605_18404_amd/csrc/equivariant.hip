@@ -621,7 +621,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, w->Wp[l], w->WpT[l]);
     for (int k = 0; k < 3; ++k) {
       if (cf.n_experts > 0)
-        hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
+        hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C, 64), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
                            th + ctx->lay[l].Wl[k], ctx->B, cf.n_experts, C, w->Wm[k][l], w->WmT[k][l]);
       else
         tr(ctx->lay[l].Wl[k], C, C);

@@ -294,7 +294,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     const LayerOffsets& lo = ctx->lay[l];
     if (d == 3) { tr(lo.W[1], H, H); tr(lo.W[2], C, H); } else { tr(lo.W[1], C, H); }
     if (cf.n_experts > 0) {
-      const dim3 grid(nblk((int64_t)C * C), (unsigned)((ctx->B + 15) / 16));
+      const dim3 grid(nblk((int64_t)C * C, 64), (unsigned)((ctx->B + 15) / 16));
       hipLaunchKernelGGL(k_merge_experts, grid, dim3(256), 0, st, ctx->d_alpha, th + lo.V1, ctx->B, cf.n_experts, C, w->Vm[0][l], w->VmT[0][l]);
       hipLaunchKernelGGL(k_merge_experts, grid, dim3(256), 0, st, ctx->d_alpha, th + lo.V2, ctx->B, cf.n_experts, C, w->Vm[1][l], w->VmT[1][l]);
     } else {

@@ -393,12 +393,16 @@ int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, i
 // ---- mixture of linear experts (Sec. 5.1 "Models"): the expert matrices of a bank are averaged
 // per structure into one temporary matrix, W_s = sum_k alpha[s][k] W_k, which is then used like
 // any dense matrix on the atoms of s.
-// Wm[s][i] and its transpose WmT[s][(i % C) * C + i / C], i < C*C.  Block: 256 entries x 16 structures.
+// Wm[s][i] and its transpose WmT[s][(i % C) * C + i / C], i < C*C.  Block: 64 entries x 16 structures;
+// the experts are dealt to four groups of 64 threads (independent load streams), whose sums are
+// combined in a fixed order.
 __global__ void __launch_bounds__(256) k_merge_experts(const float* __restrict__ alpha, const float* __restrict__ bank,
                                                        int B, int Ke, int C, float* __restrict__ Wm,
                                                        float* __restrict__ WmT) {
   __shared__ float al[16][64];
-  const int64_t n = (int64_t)C * C, i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  __shared__ float red[3][16][64];
+  const int lane = threadIdx.x & 63, kg = threadIdx.x >> 6;
+  const int64_t n = (int64_t)C * C, i = (int64_t)blockIdx.x * 64 + lane;
   const int s0 = blockIdx.y * 16;
   float acc[16];
 #pragma unroll
@@ -412,23 +416,31 @@ __global__ void __launch_bounds__(256) k_merge_experts(const float* __restrict__
     __syncthreads();
     if (i < n) {
       const int kn = min(64, Ke - k0);
-      for (int kk = 0; kk < kn; ++kk) {
+#pragma unroll 4
+      for (int kk = kg; kk < kn; kk += 4) {
         const float v = bank[(int64_t)(k0 + kk) * n + i];
 #pragma unroll
         for (int ss = 0; ss < 16; ++ss) acc[ss] = fmaf(al[ss][kk], v, acc[ss]);
       }
     }
   }
-  if (i < n) {
+  if (kg > 0) {
+#pragma unroll
+    for (int ss = 0; ss < 16; ++ss) red[kg - 1][ss][lane] = acc[ss];
+  }
+  __syncthreads();
+  if (kg == 0 && i < n) {
     const int64_t it = (i % C) * C + i / C;
 #pragma unroll
     for (int ss = 0; ss < 16; ++ss)
       if (s0 + ss < B) {
-        Wm[(int64_t)(s0 + ss) * n + i] = acc[ss];
-        WmT[(int64_t)(s0 + ss) * n + it] = acc[ss];
+        const float v = (acc[ss] + red[0][ss][lane]) + (red[1][ss][lane] + red[2][ss][lane]);
+        Wm[(int64_t)(s0 + ss) * n + i] = v;
+        WmT[(int64_t)(s0 + ss) * n + it] = v;
       }
   }
 }
+
 // grad_bank[k][i] += sum_s alpha[s][k] part[s][i]  (structures in order: deterministic).
 // Block: 256 entries x 16 experts.
 // part holds `copies` blocks of B partials (block m = component copy m of the atom rows); partial
