@@ -50,7 +50,7 @@ typedef enum {
   MLIP_OK = 0,
   MLIP_E_INVALID = -1,     /* null pointer, non-positive size, cutoff <= 0 or > a cell height, singular cell, bad order of calls' arguments */
   MLIP_E_CAPACITY = -2,    /* more atoms / structures / edges than the context was created for */
-  MLIP_E_UNSUPPORTED = -3, /* unsupported model shape or option */
+  MLIP_E_UNSUPPORTED = -3, /* unsupported model shape or option; a cell too skewed for the float32 binning */
   MLIP_E_STATE = -4,       /* phase called out of order (FE -> FF -> BF -> BE) or without a graph */
   MLIP_E_HIP = -5,         /* a HIP runtime call failed */
   MLIP_E_POSITION = -6     /* a position lies outside its cell, or is not finite (found at graph build) */
@@ -109,7 +109,9 @@ int64_t mlip_workspace_bytes(const mlip_ctx* ctx);
  *   - diagonal (orthorhombic): positions in [0, L_a) exactly, cutoff <= every edge L_a;
  *   - a general non-singular lattice (triclinic, either handedness): fractional coordinates
  *     x . cell^-1 in [0, 1] (evaluated in float32, 1e-5 slack), cutoff (1 + 1e-4) <= every
- *     perpendicular height V / |a_b x a_c| (so that S in {-1, 0, 1}^3 covers the cutoff sphere);
+ *     perpendicular height V / |a_b x a_c| (so that S in {-1, 0, 1}^3 covers the cutoff sphere),
+ *     and the longest edge at most 50 times the smallest height (MLIP_E_UNSUPPORTED otherwise:
+ *     reduce the lattice first);
  *   - all zeros: a molecule in vacuum, no images (S = 0), positions anywhere (finite).
  *   A cell with some but not all lattice vectors zero (a slab or wire) is refused as singular.
  * Synchronous: reads struct_ptr and cell back to validate them and returns the edge count in

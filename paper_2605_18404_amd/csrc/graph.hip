@@ -415,14 +415,21 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
       double scale = 1.0;
       for (int a = 0; a < 3; ++a) scale *= std::sqrt(A[a][0] * A[a][0] + A[a][1] * A[a][1] + A[a][2] * A[a][2]);
       if (!(std::fabs(det) > 1e-6 * scale)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell is singular (or partly periodic, which is not supported)");
+      double longest = 0.0, lowest = 1e300;
       for (int a = 0; a < 3; ++a) {
         const double height = std::fabs(det) / std::sqrt(X[a][0] * X[a][0] + X[a][1] * X[a][1] + X[a][2] * X[a][2]);
+        longest = std::max(longest, std::sqrt(A[a][0] * A[a][0] + A[a][1] * A[a][1] + A[a][2] * A[a][2]));
+        lowest = std::min(lowest, height);
         // the 27 nearest images cover the cutoff sphere only up to the smallest height; the margins
         // leave room for the rounding of the float32 fractional coordinates
         if ((double)cutoff * (1.0 + 1e-4) > height) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a perpendicular height of the cell");
-        m.nb[a] = std::min(128, std::max(1, (int)std::floor(height / ((double)cutoff * (1.0 + 2e-3)))));
+        // at most 32 slabs per axis: a slab is then >= 6e-5 wider (in fractional units) than the cutoff needs
+        m.nb[a] = std::min(32, std::max(1, (int)std::floor(height / ((double)cutoff * (1.0 + 2e-3)))));
         for (int b = 0; b < 3; ++b) m.inv[3 * b + a] = (float)(X[a][b] / det);  // column a of the inverse
       }
+      // A float32 fractional coordinate is off by up to ~5e-7 (longest edge / smallest height); beyond a ratio
+      // of 50 that would eat the slabs' margin, so such a cell has to be reduced by the caller first.
+      if (longest > 50.0 * lowest) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "graph_build: cell too skewed for float32 binning (reduce the lattice first)");
     } else {
       const int n_at = m.atom_end - m.atom_begin;
       for (int a = 0; a < 3; ++a) {

@@ -143,6 +143,12 @@ def test_graph_error_paths():
     with pytest.raises(MlipError) as e:
         m.mlip_graph_build(d.pos, d.struct_ptr, tri, 9.5)  # below every edge length, above that height
     assert e.value.code == -1
+    needle = d.cell.clone()
+    needle[0, 0, 0] = 700.0  # 700 x 12 x 12: longest edge more than 50 smallest heights
+    needle[0, 1, 0] = 1.0
+    with pytest.raises(MlipError) as e:
+        m.mlip_graph_build(d.pos, d.struct_ptr, needle, w.cutoff)
+    assert e.value.code == -3
     free = torch.zeros_like(d.cell)
     bad = d.pos.clone()
     bad[7, 2] = float("inf")
