@@ -394,8 +394,9 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
         const float L = c[4 * a];
         if (!(L > 0.f)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cell edge must be positive");
         if (cutoff > L) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff exceeds a cell edge");
-        // bins at least (1 + 1e-5) r_c wide, so rounding in the bin assignment cannot lose a neighbour
-        m.nb[a] = std::max(1, (int)std::floor((double)L / ((double)cutoff * (1.0 + 1e-5))));
+        // bins at least (1 + 1e-4) r_c wide and at most 256 per axis: the float32 bin coordinate x / L * nb
+        // is off by < 3e-7 nb, which then cannot separate two atoms closer than r_c by more than one bin
+        m.nb[a] = std::min(256, std::max(1, (int)std::floor((double)L / ((double)cutoff * (1.0 + 1e-4)))));
         m.inv[4 * a] = 1.f / L;
       }
     } else if (m.kind == CELL_TRICLINIC) {
