@@ -198,6 +198,10 @@ def train_cases():
         "cfg2_2structs_fp32": (synth.shrink(W[2], n_structs=2, gemm_bf16=False), TOL_FP32),
         "cfg2_2structs_bf16": (synth.shrink(W[2], n_structs=2), TOL_BF16),
         "cfg4_shape_300atoms_bf16": (synth.shrink(W[4], atoms_per_struct=300, box=(300 / 0.1) ** (1 / 3), n_layers=2), TOL_BF16),
+        # the widest model the configuration check admits for the invariant kind (one receiver row per workgroup),
+        # hidden width and basis size that are multiples of 4 only
+        "max_channels_1024": (synth.shrink(W[0], channels=1024, edge_hidden=260, n_rbf=68, atoms_per_struct=12, n_structs=2,
+                                           box=6.0, cutoff=3.0, n_layers=1), TOL_FP32),
         # general lattices and molecules in vacuum: the image shift S . cell enters every edge vector
         "cfg1_2structs_triclinic": (synth.shrink(W[1], n_structs=2, cell_kind="triclinic"), TOL_FP32),
         "cfg1_2structs_molecules": (synth.shrink(W[1], n_structs=2, cell_kind="free"), TOL_FP32),
@@ -264,6 +268,9 @@ def mole_cases():
         "eqv_tiny_4experts_fp32": (synth.shrink(W[2], n_structs=3, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
                                                 edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False, n_experts=4), TOL_FP32),
         "cfg2_2structs_6experts_bf16": (synth.shrink(W[2], n_structs=2, n_experts=6), TOL_BF16),
+        # the largest expert count the configuration check admits
+        "tiny_1024experts": (synth.shrink(W[0], channels=8, edge_hidden=8, n_rbf=8, atoms_per_struct=20, n_structs=3, box=7.0,
+                                          cutoff=3.5, n_experts=1024), TOL_FP32),
     }
 
 
