@@ -202,6 +202,12 @@ def train_cases():
         # hidden width and basis size that are multiples of 4 only
         "max_channels_1024": (synth.shrink(W[0], channels=1024, edge_hidden=260, n_rbf=68, atoms_per_struct=12, n_structs=2,
                                            box=6.0, cutoff=3.0, n_layers=1), TOL_FP32),
+        # equivariant model at its widest (256 channels: one receiver row per workgroup) and at a width that is
+        # neither a multiple of 64 nor a divisor of the workgroup size
+        "eqv_max_channels_256": (synth.shrink(W[2], channels=256, edge_hidden=32, n_rbf=8, atoms_per_struct=14, n_structs=2, box=6.0,
+                                              cutoff=3.2, n_layers=1, gemm_bf16=False), TOL_FP32),
+        "eqv_channels_96_bf16": (synth.shrink(W[2], channels=96, edge_hidden=40, n_rbf=8, atoms_per_struct=14, n_structs=2, box=6.0,
+                                              cutoff=3.2, n_layers=2), TOL_BF16),
         # general lattices and molecules in vacuum: the image shift S . cell enters every edge vector
         "cfg1_2structs_triclinic": (synth.shrink(W[1], n_structs=2, cell_kind="triclinic"), TOL_FP32),
         "cfg1_2structs_molecules": (synth.shrink(W[1], n_structs=2, cell_kind="free"), TOL_FP32),
