@@ -202,6 +202,9 @@ def train_cases():
         # hidden width and basis size that are multiples of 4 only
         "max_channels_1024": (synth.shrink(W[0], channels=1024, edge_hidden=260, n_rbf=68, atoms_per_struct=12, n_structs=2,
                                            box=6.0, cutoff=3.0, n_layers=1), TOL_FP32),
+        # many tiny structures in one batch (per-structure tables, sums and loss terms)
+        "300_structures_of_3_atoms": (synth.shrink(W[0], n_structs=300, atoms_per_struct=3, box=4.5, cutoff=3.0, channels=16,
+                                                   edge_hidden=16, n_rbf=8), TOL_FP32),
         # equivariant model at its widest (256 channels: one receiver row per workgroup) and at a width that is
         # neither a multiple of 64 nor a divisor of the workgroup size
         "eqv_max_channels_256": (synth.shrink(W[2], channels=256, edge_hidden=32, n_rbf=8, atoms_per_struct=14, n_structs=2, box=6.0,
@@ -274,6 +277,8 @@ def mole_cases():
         "eqv_tiny_4experts_fp32": (synth.shrink(W[2], n_structs=3, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
                                                 edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False, n_experts=4), TOL_FP32),
         "cfg2_2structs_6experts_bf16": (synth.shrink(W[2], n_structs=2, n_experts=6), TOL_BF16),
+        "300_structures_7experts": (synth.shrink(W[0], n_structs=300, atoms_per_struct=3, box=4.5, cutoff=3.0, channels=16,
+                                                 edge_hidden=16, n_rbf=8, n_experts=7), TOL_FP32),
         # the largest expert count the configuration check admits
         "tiny_1024experts": (synth.shrink(W[0], channels=8, edge_hidden=8, n_rbf=8, atoms_per_struct=20, n_structs=3, box=7.0,
                                           cutoff=3.5, n_experts=1024), TOL_FP32),
