@@ -468,6 +468,9 @@ def stage_cases():
         "stage_fp32_small": (synth.shrink(W[3], channels=64, edge_hidden=64, gemm_bf16=False, **small), TOL_FP32),
         "stage_fp32_C512": (synth.shrink(W[3], gemm_bf16=False, n_layers=2, **small), TOL_FP32),
         "stage_bf16_C512_2structs": (synth.shrink(W[3], n_structs=2), TOL_BF16),
+        # a stage on sheared cells and on molecules; hidden width different from the channel count
+        "stage_fp32_triclinic": (synth.shrink(W[3], channels=64, edge_hidden=96, gemm_bf16=False, cell_kind="triclinic", **small), TOL_FP32),
+        "stage_bf16_molecules": (synth.shrink(W[3], channels=64, edge_hidden=96, cell_kind="free", **small), TOL_BF16),
     }
 
 
