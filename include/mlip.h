@@ -80,7 +80,8 @@ typedef struct {
   int32_t gemm_dtype;       /* MLIP_GEMM_FP32, or MLIP_GEMM_BF16: both operands of every matrix
                                product rounded to bf16 (nearest even), fp32 accumulation; the
                                radial-filter jets (outputs of such a product) are also kept in
-                               bf16; node features, pre-activations and all sums stay fp32 */
+                               bf16 unless filter_fp32 is set; node features, pre-activations and
+                               all sums stay fp32 */
   int32_t n_experts;        /* 0: dense.  > 0 (whole models only): the node-level matrices of every layer
                                (invariant: the update MLP's two; equivariant: the three per-l mixing
                                matrices) are banks [n_experts][C][C] in the parameter vector, merged
@@ -88,6 +89,10 @@ typedef struct {
   int32_t gate;             /* 0: the equivariant node update is linear, h += W^(l) a.  1 (equivariant model
                                only): gated nonlinearity, with u = W^(l) a per channel
                                h_0 += silu(u_0), h_lm += sigmoid(u_0) u_lm for l = 1, 2 */
+  int32_t filter_fp32;      /* bf16 mode only (ignored otherwise).  0: the radial-filter jets f_c w(r) -- outputs of a
+                               bf16 product, consumed element-wise by the message kernels -- are stored in bf16, as a
+                               mixed-precision linear layer returns them (half the bytes of the largest edge tensor).
+                               1: they are stored in fp32, so that bf16 rounding touches matrix-product operands only */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */
@@ -123,6 +128,8 @@ int64_t mlip_workspace_bytes(const mlip_ctx* ctx);
  *     reduce the lattice first);
  *   - all zeros: a molecule in vacuum, no images (S = 0), positions anywhere (finite).
  *   A cell with some but not all lattice vectors zero (a slab or wire) is refused as singular.
+ * cutoff must equal mlip_config.cutoff (MLIP_E_INVALID otherwise): the radial basis and the envelope
+ * of the context's model live on [0, mlip_config.cutoff], so the edge set has to end there too.
  * Synchronous: reads struct_ptr and cell back to validate them and returns the edge count in
  * *n_edges_host.  On MLIP_E_CAPACITY *n_edges_host holds the count that was needed.
  * The graph stays in the context until the next build. */
@@ -132,8 +139,20 @@ int mlip_graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const fl
 /* Sizes of the current graph, written to host integers (any may be NULL).  Does not wait. */
 int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host);
 /* Copies the current graph into caller buffers (any may be NULL): row_ptr[N+1], sender[E],
- * shift[E,3] (int32 components in {-1,0,1}), rev[E] (index of the opposite edge j <- i, -S). */
+ * shift[E,3] (int32 components in {-1,0,1}), rev[E] (index of the opposite edge j <- i, -S).
+ * Asking for rev makes the call synchronous (it checks mlip_input_status first). */
 int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+
+/* Deferred input diagnostics.  Bad inputs that only a kernel can see, after the graph build's own
+ * read-back, never fault the GPU and cannot fail the asynchronous call that met them: the kernel keeps
+ * its accesses in bounds and raises a device flag.  This call waits for the stream (synchronous) and
+ * reports, for the work enqueued since the last graph build:
+ *   MLIP_E_INVALID   a species index outside [0, n_species) (it was clamped into range);
+ *   MLIP_E_POSITION  two atoms of one structure at the same place (an edge of length zero, whose
+ *                    direction was set to zero), or an edge without its opposite edge;
+ * MLIP_OK otherwise.  Results of a step that reports an error here are not meaningful.
+ * mlip_train_step with phase timing (already synchronous) ends with this check. */
+int mlip_input_status(mlip_ctx* ctx);
 
 /* Mixture of linear experts (Sec. 5.1 "Models": expert weight matrices combined by weighted
  * averaging into a temporary linear map).  alpha: device pointer [n_structs][n_experts], row s =
@@ -149,8 +168,10 @@ int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs
  * [n_structs][n_experts] float32, or NULL to switch it off again (the default; nothing is computed
  * then).  While set, mlip_backward_force and mlip_backward_energy ADD their shares to it, as they do
  * for grad_params (the caller zeroes it), and mlip_train_step zeroes it itself before its two
- * backward phases.  The caller keeps the buffer alive and sized for the batches it builds. */
-int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha);
+ * backward phases.  n_structs = the number of rows the buffer holds (1 .. max_structs, MLIP_E_INVALID
+ * otherwise; ignored with NULL): a later batch with more structures than that makes the backward
+ * phases return MLIP_E_CAPACITY instead of writing past the buffer.  The caller keeps it alive. */
+int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha, int32_t n_structs);
 
 /* FE.  Whole model: h^0 = emb[species], E[B] written.  Stage: h_in[N,C] read, h_out[N,C]
  * written, species and E may be NULL.  pos and params are copied into the context, so the

@@ -28,7 +28,9 @@ numbers; spherical harmonics vs scipy; Gaunt tensors vs selection rules and rota
 equivariance; E invariances and closed forms (the gated update also against the linear one
 with halved matrices when its gate scalars vanish); F vs central differences of E; dL/dtheta
 vs central differences of L; BF+BE = total; stage outputs vs central differences of the
-stage scalar and vs the unsplit model.  No function here is left unpinned.
+stage scalar and vs the unsplit model; radius_graph_rows row by row vs radius_graph and a k-d tree;
+one equivariant layer vs explicit loops with couplings integrated from the harmonics' polynomials;
+energy_streamed vs energy_only.  No function here is left unpinned.
 """
 from __future__ import annotations
 
@@ -303,8 +305,8 @@ def edge_vectors(x: torch.Tensor, graph: Dict, cell: torch.Tensor, struct_of_ato
     return snd, rcv, rv, r
 
 
-def invariant_layer(h, l, lin: _Lin, cfg, snd, rcv, r):
-    """h_i <- h_i + V2 silu(V1 a_i),  a_i = sum_{e: i<-j} f_c(r_e) * w_e (.) h_j,
+def invariant_messages(h, l, lin: _Lin, cfg, snd, rcv, r):
+    """a_i = sum_{e: i<-j} f_c(r_e) * w_e (.) h_j over the given edges,
     w_e = W2 silu(W1 phi(r_e))  (depth 3: W3 silu(W2 silu(W1 phi))).  No biases."""
     phi = rbf(r, cfg["n_rbf"], cfg["cutoff"])
     t = silu(lin(phi, f"l{l}.W1"))
@@ -314,14 +316,23 @@ def invariant_layer(h, l, lin: _Lin, cfg, snd, rcv, r):
     else:
         w = lin(t, f"l{l}.W2")
     m = envelope(r, cfg["cutoff"])[:, None] * w * h[snd]
-    a = torch.zeros_like(h).index_add(0, rcv, m)
+    return torch.zeros_like(h).index_add(0, rcv, m)
+
+
+def invariant_update(h, a, l, lin: _Lin, cfg):
+    """h_i <- h_i + V2 silu(V1 a_i)."""
     return h + lin.node(silu(lin.node(a, f"l{l}.V1")), f"l{l}.V2")
 
 
-def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
-    """h [N, C, 9].  m_e[c; l3 m3] = f_c(r_e) sum_p R_e[p, c] sum_{m1 m2} T^p[m1 m2 m3]
-    h_j[c; l1 m1] Y_{l2 m2}(r_e / r_e),  R_e = W2 silu(W1 phi(r_e)) reshaped [11, C];
-    a_i = sum_e m_e;  h_i[:, l] <- h_i[:, l] + W^(l) a_i[:, l] (one C x C matrix per l)."""
+def invariant_layer(h, l, lin: _Lin, cfg, snd, rcv, r):
+    """One interaction layer: aggregate the messages of all edges, then update the node features."""
+    return invariant_update(h, invariant_messages(h, l, lin, cfg, snd, rcv, r), l, lin, cfg)
+
+
+def equivariant_messages(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
+    """h [N, C, 9].  a_i = sum_e m_e over the given edges with
+    m_e[c; l3 m3] = f_c(r_e) sum_p R_e[p, c] sum_{m1 m2} T^p[m1 m2 m3] h_j[c; l1 m1] Y_{l2 m2}(r_e / r_e),
+    R_e = W2 silu(W1 phi(r_e)) reshaped [11, C]."""
     C = cfg["channels"]
     phi = rbf(r, cfg["n_rbf"], cfg["cutoff"])
     R = lin(silu(lin(phi, f"l{l}.W1")), f"l{l}.W2").reshape(-1, len(PATHS), C)
@@ -333,12 +344,22 @@ def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
         tp = torch.einsum("abk,eca,eb->eck", T[p], hj[:, :, SL[l1]], Y[:, SL[l2]])
         parts[l3] = parts[l3] + R[:, p, :, None] * tp
     m = envelope(r, cfg["cutoff"])[:, None, None] * torch.cat(parts, dim=2)
-    a = torch.zeros_like(h).index_add(0, rcv, m)
+    return torch.zeros_like(h).index_add(0, rcv, m)
+
+
+def equivariant_update(h, a, l, lin: _Lin, cfg):
+    """h_i[:, l] <- h_i[:, l] + W^(l) a_i[:, l] (one C x C matrix per l, shared over m); with cfg["gate"] the
+    gated form h_0 += silu(u_0), h_lm += sigmoid(u_0) u_lm (l = 1, 2) of u = W^(l) a."""
     upd = [lin.node(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(3)]
     if cfg.get("gate", 0):
         u0 = upd[0]
         upd = [silu(u0), torch.sigmoid(u0) * upd[1], torch.sigmoid(u0) * upd[2]]
     return h + torch.cat(upd, dim=2)
+
+
+def equivariant_layer(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
+    """One interaction layer: aggregate the messages of all edges, then update the node features."""
+    return equivariant_update(h, equivariant_messages(h, l, lin, cfg, snd, rcv, rv, r), l, lin, cfg)
 
 
 def energy(x, species, graph, cell, struct_ptr, lin: _Lin, cfg) -> torch.Tensor:
@@ -415,6 +436,35 @@ def energy_only(cfg, pos, species, struct_ptr, cell, params, graph=None, alpha=N
     with torch.no_grad():
         lin = _Lin(unpack_params(_t(params), cfg), alpha=None if alpha is None else _t(alpha))
         return energy(_t(pos), species, graph, _t(cell), struct_ptr, lin, cfg).numpy()
+
+
+def energy_streamed(cfg, pos, species, struct_ptr, cell, params, graph, edge_chunk: int = 32768) -> np.ndarray:
+    """The same per-structure energies as energy_only, for systems whose per-edge tensors do not fit in
+    memory at once: every layer's aggregate a_i = sum_e m_e is accumulated over consecutive blocks of
+    edges (the sum over edges is the only place where edges meet), then the layer's node update is applied
+    once.  Values only, no derivatives; callers take directional derivatives by central differences."""
+    with torch.no_grad():
+        lin = _Lin(unpack_params(_t(params), cfg))
+        x, cellt = _t(pos), _t(cell)
+        N, B = x.shape[0], len(struct_ptr) - 1
+        sid = torch.repeat_interleave(torch.arange(B), torch.as_tensor(np.diff(struct_ptr), dtype=torch.long))
+        lin.sid = sid
+        n_edges = len(graph["sender"])
+        emb = lin.P["emb"][torch.as_tensor(species, dtype=torch.long)]
+        eqv = cfg["kind"] == "equivariant"
+        h = torch.cat([emb[:, :, None], torch.zeros(N, cfg["channels"], 8, dtype=DT)], dim=2) if eqv else emb
+        for l in range(cfg["n_layers"]):
+            a = torch.zeros_like(h)
+            for e0 in range(0, n_edges, edge_chunk):
+                part = {k: graph[k][e0:e0 + edge_chunk] for k in ("sender", "receiver", "shift")}
+                snd, rcv, rv, r = edge_vectors(x, part, cellt, sid)
+                a += (equivariant_messages(h, l, lin, cfg, snd, rcv, rv, r) if eqv
+                      else invariant_messages(h, l, lin, cfg, snd, rcv, r))
+            h = equivariant_update(h, a, l, lin, cfg) if eqv else invariant_update(h, a, l, lin, cfg)
+        if eqv:
+            h = h[:, :, 0]
+        eps = lin(silu(lin(h, "U")), "w_o")[:, 0]
+        return torch.zeros(B, dtype=DT).index_add(0, sid, eps).numpy()
 
 
 # ============================================================================ pipeline stage

@@ -31,7 +31,7 @@ class mlip_config(C.Structure):
     _fields_ = [("model_kind", C.c_int32), ("n_species", C.c_int32), ("channels", C.c_int32),
                 ("n_layers", C.c_int32), ("n_rbf", C.c_int32), ("edge_hidden", C.c_int32),
                 ("edge_mlp_depth", C.c_int32), ("l_max", C.c_int32), ("gemm_dtype", C.c_int32),
-                ("n_experts", C.c_int32), ("gate", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
+                ("n_experts", C.c_int32), ("gate", C.c_int32), ("filter_fp32", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
                 ("max_atoms", C.c_int64), ("max_structs", C.c_int64), ("max_edges", C.c_int64)]
 
 
@@ -70,7 +70,8 @@ def load():
     lib.mlip_copy_probe.argtypes = [P, P, P, I64]
     lib.mlip_gars_pack.argtypes = [P, I64, I32, I32, C.c_uint64, P, P, P]
     lib.mlip_set_expert_weights.argtypes = [P, P, I32]
-    lib.mlip_set_expert_weight_grad.argtypes = [P, P]
+    lib.mlip_set_expert_weight_grad.argtypes = [P, P, I32]
+    lib.mlip_input_status.argtypes = [P]
     lib.mlip_optimizer_step.argtypes = [P, I64, P, P, P, P, I32, C.POINTER(mlip_adamw)]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
@@ -114,14 +115,14 @@ class Mlip:
 
     def __init__(self, *, model_kind: int, channels: int, n_layers: int, n_rbf: int, edge_hidden: int,
                  edge_mlp_depth: int = 2, l_max: int = 0, n_species: int = 1, gemm_bf16: bool = False,
-                 n_experts: int = 0, gate: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
+                 n_experts: int = 0, gate: int = 0, filter_fp32: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
                  device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
         self.lib = load()
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self.cfg = mlip_config(model_kind, n_species, channels, n_layers, n_rbf, edge_hidden, edge_mlp_depth, l_max,
-                               1 if gemm_bf16 else 0, n_experts, gate, cutoff, force_weight, max_atoms, max_structs, max_edges)
+                               1 if gemm_bf16 else 0, n_experts, gate, filter_fp32, cutoff, force_weight, max_atoms, max_structs, max_edges)
         self.ctx = C.c_void_p()
         s = self.lib.mlip_create(C.byref(self.cfg), C.c_void_p(self.stream.cuda_stream), C.byref(self.ctx))
         if s != 0:
@@ -141,7 +142,7 @@ class Mlip:
             max_edges = int(w.n_atoms * (deg * 1.15 + 8))
         args = dict(model_kind=w.kind, channels=w.channels, n_layers=w.n_layers, n_rbf=w.n_rbf,
                     edge_hidden=w.edge_hidden, edge_mlp_depth=w.edge_depth, l_max=w.l_max, n_species=w.n_species,
-                    gemm_bf16=w.gemm_bf16, n_experts=getattr(w, "n_experts", 0), gate=getattr(w, "gate", 0), cutoff=w.cutoff, force_weight=w.force_weight, max_atoms=w.n_atoms,
+                    gemm_bf16=w.gemm_bf16, n_experts=getattr(w, "n_experts", 0), gate=getattr(w, "gate", 0), filter_fp32=getattr(w, "filter_fp32", 0), cutoff=w.cutoff, force_weight=w.force_weight, max_atoms=w.n_atoms,
                     max_structs=w.n_structs, max_edges=max_edges)
         args.update(kw)
         return cls(**args)
@@ -183,6 +184,10 @@ class Mlip:
         self._check(self.lib.mlip_graph_sizes(self.ctx, C.byref(a), C.byref(b), C.byref(e)))
         return int(a.value), int(b.value), int(e.value)
 
+    def mlip_input_status(self):
+        """Synchronous: raises MlipError if a kernel met a bad species index or coincident atoms."""
+        self._check(self.lib.mlip_input_status(self.ctx))
+
     def mlip_kernel_timer_select(self, kernel_id: int):
         self._check(self.lib.mlip_kernel_timer_select(self.ctx, kernel_id))
 
@@ -209,7 +214,8 @@ class Mlip:
 
     def mlip_set_expert_weight_grad(self, grad_alpha):
         """grad_alpha: device tensor [n_structs, n_experts] float32 that BF and BE add dL/dalpha to, or None."""
-        self._check(self.lib.mlip_set_expert_weight_grad(self.ctx, _ptr(grad_alpha, torch.float32)))
+        n = 0 if grad_alpha is None else int(grad_alpha.shape[0])
+        self._check(self.lib.mlip_set_expert_weight_grad(self.ctx, _ptr(grad_alpha, torch.float32), n))
         self._grad_alpha = grad_alpha  # keep the tensor alive while the library holds its address
 
     def mlip_optimizer_step(self, params, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,

@@ -90,6 +90,7 @@ const char* check_config(const mlip_config& c) {
   if (c.n_experts < 0 || c.n_experts > 1024) return "n_experts must be in [0, 1024]";
   if (c.n_experts > 0 && c.model_kind == MLIP_MODEL_STAGE) return "expert banks are built for the whole models only";
   if (c.gate != 0 && c.gate != 1) return "gate must be 0 or 1";
+  if (c.filter_fp32 != 0 && c.filter_fp32 != 1) return "filter_fp32 must be 0 or 1";
   if (c.gate == 1 && c.model_kind != MLIP_MODEL_EQUIVARIANT) return "the gated update belongs to the equivariant model";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
@@ -158,11 +159,19 @@ int mlip_set_expert_weights(mlip_ctx* ctx, const float* alpha, int32_t n_structs
   return MLIP_OK;
 }
 
-int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha) {
+int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha, int32_t n_structs) {
   if (!ctx) return MLIP_E_INVALID;
   if (ctx->cfg.n_experts <= 0) MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weight_grad: the context has no expert banks");
+  if (grad_alpha && (n_structs < 1 || n_structs > ctx->cfg.max_structs))
+    MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weight_grad: n_structs must be in [1, max_structs]");
   ctx->d_grad_alpha = grad_alpha;
+  ctx->grad_alpha_structs = grad_alpha ? n_structs : 0;
   return MLIP_OK;
+}
+
+int mlip_input_status(mlip_ctx* ctx) {
+  if (!ctx) return MLIP_E_INVALID;
+  return input_status(ctx);
 }
 
 int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_structs_host, int64_t* n_edges_host) {
@@ -250,8 +259,15 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
   hipEvent_t ev[6];
   const bool timed = phase_ms_host != nullptr;
   if (timed) {
-    for (auto& e : ev) MLIP_HIP_CHECK(ctx, hipEventCreate(&e));
-    MLIP_HIP_CHECK(ctx, hipEventRecord(ev[0], st));
+    for (int k = 0; k < 6; ++k)
+      if (hipEventCreate(&ev[k]) != hipSuccess) {  // destroy the ones already made before reporting
+        for (int q = 0; q < k; ++q) hipEventDestroy(ev[q]);
+        MLIP_FAIL(ctx, MLIP_E_HIP, "train_step: hipEventCreate failed");
+      }
+    if (hipEventRecord(ev[0], st) != hipSuccess) {
+      for (auto& e : ev) hipEventDestroy(e);
+      MLIP_FAIL(ctx, MLIP_E_HIP, "train_step: hipEventRecord failed");
+    }
   }
   int64_t n_edges = 0;
   int s = mlip_graph_build(ctx, n_atoms, n_structs, pos, struct_ptr, cell, cutoff, &n_edges);
@@ -262,6 +278,10 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
   if (s == MLIP_OK) s = model_loss(ctx, E, F, E_ref, F_ref, loss, sb->Ebar, sb->v);
   if (s == MLIP_OK && timed) hipEventRecord(ev[3], st);
   if (s == MLIP_OK && hipMemsetAsync(grad_params, 0, sizeof(float) * ctx->n_params, st) != hipSuccess) s = MLIP_E_HIP;
+  if (s == MLIP_OK && ctx->d_grad_alpha && ctx->grad_alpha_structs < ctx->B) {
+    ctx->err = "train_step: the registered coefficient-gradient buffer holds fewer rows than the batch has structures";
+    s = MLIP_E_CAPACITY;
+  }
   if (s == MLIP_OK && ctx->d_grad_alpha &&
       hipMemsetAsync(ctx->d_grad_alpha, 0, sizeof(float) * (size_t)ctx->B * ctx->cfg.n_experts, st) != hipSuccess)
     s = MLIP_E_HIP;
@@ -276,6 +296,7 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
         if (hipEventElapsedTime(&phase_ms_host[k], ev[k], ev[k + 1]) != hipSuccess) s = MLIP_E_HIP;
     }
     for (auto& e : ev) hipEventDestroy(e);
+    if (s == MLIP_OK) s = input_status(ctx);  // the call has waited anyway: report clamped species, coincident atoms
   }
   return s;
 }

@@ -48,6 +48,9 @@ struct PartialBuf {  // split-k / chunk partial sums, reduced in a fixed order
   int64_t cap = 0;  // floats
 };
 
+// bits of the deferred input-diagnostics word (mlip_input_status)
+enum { INPUT_NO_REVERSE_EDGE = 1, INPUT_BAD_SPECIES = 2, INPUT_COINCIDENT = 4 };
+
 enum Phase { PH_NONE = 0, PH_GRAPH = 1, PH_FE = 2, PH_FF = 3, PH_BF = 4, PH_BE = 5 };
 
 struct LayerOffsets {  // offsets (in floats) into the flat parameter vector
@@ -86,7 +89,8 @@ struct mlip_ctx {
   int32_t* d_receiver = nullptr;      // [max_edges]
   int32_t* d_rev = nullptr;           // [max_edges]
   int32_t* d_scan_tmp = nullptr;      // block sums for the scans
-  int32_t* d_flag = nullptr;          // device error flag
+  int32_t* d_flag = nullptr;          // device flags [4]: word 0 = positions outside their cell (read by the graph build);
+                                      // word 1 = deferred input diagnostics (INPUT_* bits, read by input_status)
   float* d_bounds = nullptr;          // [max_structs][6] bounding boxes (min xyz, max xyz), molecules only
   int64_t max_bins = 0;
   std::vector<StructMeta> h_meta;
@@ -110,6 +114,7 @@ struct mlip_ctx {
   float* d_alpha = nullptr;        // [max_structs][n_experts] coefficients (mlip_set_expert_weights)
   int32_t alpha_structs = -1;      // how many rows of d_alpha are set
   float* d_grad_alpha = nullptr;   // caller's buffer [B][n_experts] for dL/dalpha, or null (mlip_set_expert_weight_grad)
+  int32_t grad_alpha_structs = 0;  // rows the caller said that buffer holds
   int4* d_row_groups = nullptr;    // row tiles of 64 atoms that never straddle a structure: (first, end, structure, 0)
   std::vector<int4> h_row_groups;
   std::vector<int32_t> h_k_ranges;
@@ -151,6 +156,9 @@ int graph_alloc(mlip_ctx* ctx);
 int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* struct_ptr,
                 const float* cell, float cutoff, int64_t* n_edges_host);
 int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+int input_status(mlip_ctx* ctx);
+int graph_export_shift(mlip_ctx* ctx, int32_t* shift);
+constexpr int GRAPH_SCAN_TILE = 2048;  // elements per workgroup of the graph build's scans: d_scan_tmp holds one int per tile (+ 2)
 
 // model.hip (invariant model and pipeline stage) / equivariant.hip (l <= 2 model)
 #define MLIP_DECLARE_MODEL(pfx)                                                                                       \

@@ -603,13 +603,12 @@ __global__ void k_gate_be(const float* __restrict__ u, const float* __restrict__
 // ------------------------------------------------------------------------------ phases
 constexpr int LOFF[3] = {0, 1, 4};
 
-template <typename P>
+template <typename P, typename TF>
 int fe_impl(mlip_ctx* ctx, float* E_out) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
-  static_assert(sizeof(TF) == (P::IS_BF16 ? 2 : 4) && sizeof(typename Act<P>::xop_t) == sizeof(TF), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
+  static_assert(sizeof(typename Act<P>::xop_t) == (P::IS_BF16 ? 2 : 4), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -668,12 +667,11 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int ff_impl(mlip_ctx* ctx, float* F) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, NC = N * cf.channels;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
@@ -706,12 +704,11 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int bf_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -767,12 +764,11 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int be_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -869,7 +865,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   for (int l = 0; l < L; ++l) {
     w->U.push_back(A(2 * E * H));
     w->SJ.push_back(b16 ? (__bf16*)A(E * H) : nullptr);
-    w->Rho.push_back(AH(2 * E * PC));
+    w->Rho.push_back(cf.filter_fp32 ? A(2 * E * PC) : AH(2 * E * PC));
     w->Wp.push_back(A((int64_t)PC * H));
     w->WpT.push_back(A((int64_t)PC * H));
     if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
@@ -904,7 +900,11 @@ void eqv_free(mlip_ctx* ctx) {
   ctx->model_ws = nullptr;
 }
 
-#define DISPATCH(fn, ...) (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16 ? fn<gemm::Bf16>(__VA_ARGS__) : fn<gemm::Fp32>(__VA_ARGS__))
+// TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters
+#define DISPATCH(fn, ...)                                                                                        \
+  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                         \
+       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float>(__VA_ARGS__) : fn<gemm::Bf16, __bf16>(__VA_ARGS__))       \
+       : fn<gemm::Fp32, float>(__VA_ARGS__))
 
 int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float*,
                        float* E, float*) {
@@ -915,7 +915,7 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
   hipStream_t st = ctx->stream;
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
-  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_species, species, sizeof(int32_t) * ctx->N, hipMemcpyDeviceToDevice, st));
+  hipLaunchKernelGGL(k_copy_species, dim3(nblk(ctx->N)), dim3(256), 0, st, species, ctx->N, ctx->cfg.n_species, ctx->d_species, ctx->d_flag);
   MLIP_TRY(DISPATCH(fe_impl, ctx, E));
   ctx->phase = PH_FE;
   return MLIP_OK;

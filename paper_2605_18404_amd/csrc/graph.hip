@@ -12,6 +12,7 @@ namespace {
 constexpr int SCAN_BLOCK = 256;
 constexpr int SCAN_ITEMS = 8;  // per thread
 constexpr int SCAN_TILE = SCAN_BLOCK * SCAN_ITEMS;
+static_assert(SCAN_TILE == GRAPH_SCAN_TILE, "common.h states the scan tile for those who size the scan's work array");
 
 // ------------------------------------------------------------------ exclusive scan (int32)
 __global__ void k_scan_block_sums(const int32_t* __restrict__ in, int32_t* __restrict__ block_sums, int64_t n) {
@@ -281,7 +282,7 @@ __global__ void k_reverse_map(const int32_t* __restrict__ row_ptr, const int32_t
     if (k == want) { found = mid; break; }
     if (k < want) lo = mid + 1; else hi = mid - 1;
   }
-  if (found < 0) atomicOr(flag, 2);
+  if (found < 0) atomicOr(flag + 1, INPUT_NO_REVERSE_EDGE);  // deferred status word, read by input_status()
   rev[e] = found;
 }
 
@@ -339,6 +340,9 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
   if (!pos || !struct_ptr || !cell || !n_edges_host) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: null pointer");
   if (n_atoms <= 0 || n_structs <= 0) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: n_atoms and n_structs must be positive");
   if (!(cutoff > 0.f) || !std::isfinite(cutoff)) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff must be positive");
+  // The radial basis and the envelope are laid out on [0, cfg.cutoff]: an edge set cut at any other radius would
+  // give a discontinuous energy (smaller) or edges with a rising envelope beyond its zero (larger).
+  if (cutoff != ctx->cfg.cutoff) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_build: cutoff differs from the cutoff the context's model was created with");
   *n_edges_host = 0;
   if (n_atoms > ctx->cfg.max_atoms) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: n_atoms exceeds max_atoms");
   if (n_structs > ctx->cfg.max_structs) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "graph_build: n_structs exceeds max_structs");
@@ -438,7 +442,8 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
         if (!(std::isfinite(lo) && std::isfinite(hi) && hi - lo <= 1e30f))
           MLIP_FAIL(ctx, MLIP_E_POSITION, "graph_build: a position is not finite");
         const double extent = std::max((double)hi - (double)lo, (double)cutoff) * (1.0 + 1e-3);
-        m.nb[a] = std::max(1, (int)std::floor(extent / ((double)cutoff * (1.0 + 2e-3))));
+        // at most 256 bins per axis (coarser bins are still correct), so neither the count nor the product overflows
+        m.nb[a] = (int)std::min(256.0, std::max(1.0, std::floor(extent / ((double)cutoff * (1.0 + 2e-3)))));
         m.origin[a] = lo;
         m.inv[4 * a] = (float)(1.0 / extent);
       }
@@ -518,18 +523,38 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
   return MLIP_OK;
 }
 
+// Deferred input diagnostics.  Kernels that run after the graph build's last read-back cannot fail the call
+// that launched them (calls are asynchronous); they raise bits in the second word of the device flag instead,
+// and keep every access in bounds.  This reads the word back (synchronous) and turns it into a status.
+int input_status(mlip_ctx* ctx) {
+  if (ctx->phase < PH_GRAPH) return MLIP_OK;
+  int32_t h = 0;
+  MLIP_HIP_CHECK(ctx, hipMemcpyAsync(&h, ctx->d_flag + 1, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+  if (h & INPUT_NO_REVERSE_EDGE) MLIP_FAIL(ctx, MLIP_E_POSITION, "the edge list is not symmetric: an edge has no opposite edge");
+  if (h & INPUT_BAD_SPECIES) MLIP_FAIL(ctx, MLIP_E_INVALID, "a species index is outside [0, n_species) (it was clamped; results are not meaningful)");
+  if (h & INPUT_COINCIDENT) MLIP_FAIL(ctx, MLIP_E_POSITION, "two atoms of a structure coincide (an edge of length zero; its direction was set to zero)");
+  return MLIP_OK;
+}
+
+// shift[E,3] from the stored shift codes of the current graph
+int graph_export_shift(mlip_ctx* ctx, int32_t* shift) {
+  if (ctx->E <= 0) return MLIP_OK;
+  hipLaunchKernelGGL(k_export_shift, dim3((unsigned)((ctx->E + 255) / 256)), dim3(256), 0, ctx->stream, ctx->d_code, ctx->E, shift);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  return MLIP_OK;
+}
+
 int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev) {
   if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "graph_export: no graph has been built");
+  if (rev) MLIP_TRY(input_status(ctx));  // rev = -1 entries must not leave the library unreported
   hipStream_t st = ctx->stream;
   const int64_t E = ctx->E;
   if (row_ptr) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(row_ptr, ctx->d_row_ptr, sizeof(int32_t) * (ctx->N + 1), hipMemcpyDeviceToDevice, st));
   if (E > 0) {
     if (sender) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(sender, ctx->d_sender, sizeof(int32_t) * E, hipMemcpyDeviceToDevice, st));
     if (rev) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(rev, ctx->d_rev, sizeof(int32_t) * E, hipMemcpyDeviceToDevice, st));
-    if (shift) {
-      hipLaunchKernelGGL(k_export_shift, dim3((unsigned)((E + 255) / 256)), dim3(256), 0, st, ctx->d_code, E, shift);
-      MLIP_HIP_CHECK(ctx, hipGetLastError());
-    }
+    if (shift) MLIP_TRY(graph_export_shift(ctx, shift));
   }
   return MLIP_OK;
 }

@@ -274,13 +274,12 @@ int node_wgrad(mlip_ctx* ctx, int l, int which, const LdA& a, const LdB& b, floa
 }
 
 // ------------------------------------------------------------------------------ phases
-template <typename P>
+template <typename P, typename TF>
 int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
-  static_assert(sizeof(TF) == (P::IS_BF16 ? 2 : 4) && sizeof(typename Act<P>::xop_t) == sizeof(TF), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
+  static_assert(sizeof(typename Act<P>::xop_t) == (P::IS_BF16 ? 2 : 4), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -351,12 +350,11 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
@@ -385,12 +383,11 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -462,12 +459,11 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   return MLIP_OK;
 }
 
-template <typename P>
+template <typename P, typename TF>
 int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  typedef typename Act<P>::flt_t TF;  // storage type of the radial-filter jets
   const int64_t N = ctx->N, E = ctx->E;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
@@ -551,7 +547,6 @@ int inv_alloc(mlip_ctx* ctx) {
   const mlip_config& cf = ctx->cfg;
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
-  if (cf.model_kind == MLIP_MODEL_EQUIVARIANT) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: not built into this library yet");
   InvWs* w = new InvWs();
   ctx->model_ws = w;
   w->L = L;
@@ -577,7 +572,7 @@ int inv_alloc(mlip_ctx* ctx) {
     w->U[1].push_back(d == 3 ? A(2 * E * H) : nullptr);
     w->SJ[0].push_back(b16 ? (__bf16*)A(E * H) : nullptr);  // 2 E H bf16 = E H floats
     w->SJ[1].push_back(b16 && d == 3 ? (__bf16*)A(E * H) : nullptr);
-    w->Om.push_back(AH(2 * E * C));
+    w->Om.push_back(cf.filter_fp32 ? A(2 * E * C) : AH(2 * E * C));
     w->Y[0].push_back(A(E * H));
     w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);
     if (cf.n_experts > 0)
@@ -615,7 +610,11 @@ void inv_free(mlip_ctx* ctx) {
   ctx->model_ws = nullptr;
 }
 
-#define DISPATCH(fn, ...) (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16 ? fn<gemm::Bf16>(__VA_ARGS__) : fn<gemm::Fp32>(__VA_ARGS__))
+// TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters
+#define DISPATCH(fn, ...)                                                                                        \
+  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                         \
+       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float>(__VA_ARGS__) : fn<gemm::Bf16, __bf16>(__VA_ARGS__))       \
+       : fn<gemm::Fp32, float>(__VA_ARGS__))
 
 int inv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
                          float* E, float* h_out) {
@@ -628,7 +627,8 @@ int inv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
   hipStream_t st = ctx->stream;
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
-  if (!stage) MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_species, species, sizeof(int32_t) * ctx->N, hipMemcpyDeviceToDevice, st));
+  if (!stage)
+    hipLaunchKernelGGL(k_copy_species, dim3(nblk(ctx->N)), dim3(256), 0, st, species, ctx->N, ctx->cfg.n_species, ctx->d_species, ctx->d_flag);
   MLIP_TRY(DISPATCH(fe_impl, ctx, h_in, E, h_out));
   ctx->phase = PH_FE;
   return MLIP_OK;

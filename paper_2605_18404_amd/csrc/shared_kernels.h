@@ -24,6 +24,21 @@ __global__ void k_transpose(const float* __restrict__ src, float* __restrict__ d
     if (r2 < rows) dst[(int64_t)c2 * rows + r2] = tile[threadIdx.x][c2 - blockIdx.x * 32];
 }
 
+// The context's copy of the species indices, clamped into [0, S): an index outside that range is a
+// caller error that must neither read past the embedding table nor pass silently, so it raises a bit
+// of the deferred input-diagnostics word.
+__global__ void k_copy_species(const int32_t* __restrict__ src, int64_t N, int S, int32_t* __restrict__ dst,
+                               int32_t* __restrict__ flag) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int z = src[i];
+  if (z < 0 || z >= S) {
+    atomicOr(flag + 1, INPUT_BAD_SPECIES);
+    z = z < 0 ? 0 : S - 1;
+  }
+  dst[i] = z;
+}
+
 __global__ void k_embed(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C,
                         float* __restrict__ h) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -188,7 +203,6 @@ struct Act<gemm::Fp32> {
   typedef LdJetSiluEven Even;
   typedef LdJetSiluOdd Odd;
   typedef EpiStore Store;
-  typedef float flt_t;  // element type of the stored radial-filter jets
   typedef float xop_t;  // element type of the edge tensors that only feed matrix products
   typedef LdPlain XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
@@ -203,7 +217,6 @@ struct Act<gemm::Bf16> {
   typedef LdBf16 Even;
   typedef LdBf16 Odd;
   typedef EpiStoreJetAct Store;
-  typedef __bf16 flt_t;  // the filter jets are outputs of a bf16 product: kept in bf16, as a mixed-precision linear layer would
   typedef __bf16 xop_t;  // rounded once by the producer: half the bytes, no conversion in the operand path
   typedef LdBf16 XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
@@ -533,6 +546,7 @@ int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int
   hipLaunchKernelGGL(k_expert_grad, dim3(nblk(n), (Ke + 15) / 16), dim3(256), 0, ctx->stream, ctx->d_alpha, ctx->partial.buf, B,
                      copies, Ke, n, grad_bank);
   if (ctx->d_grad_alpha) {
+    if (ctx->grad_alpha_structs < B) MLIP_FAIL(ctx, MLIP_E_CAPACITY, "coefficient gradient: the registered buffer holds fewer rows than the batch has structures");
     // dL/dalpha[s][k] = sum over copies of <partial[m B + s], W_k>: the product [B copies, n] x [Ke, n]^T over
     // the n matrix entries, split along n; always in fp32 (it is tiny)
     const int ldp = (Ke + 3) / 4 * 4;
@@ -555,7 +569,8 @@ __global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__
                                                        const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
                                                        const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta,
                                                        int64_t E, int K, int qshift, float rc, float4* __restrict__ geo,
-                                                       float2* __restrict__ env, float* __restrict__ jphi) {
+                                                       float2* __restrict__ env, float* __restrict__ jphi,
+                                                       int32_t* __restrict__ flag) {
   const int q = threadIdx.x & ((1 << qshift) - 1);
   const int64_t e = (int64_t)blockIdx.x * (256 >> qshift) + (threadIdx.x >> qshift);
   if (e >= E || 4 * q >= K) return;
@@ -582,7 +597,9 @@ __global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__
   *reinterpret_cast<float4*>(jphi + (2 * e) * K + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
   *reinterpret_cast<float4*>(jphi + (2 * e + 1) * K + 4 * q) = make_float4(d[0], d[1], d[2], d[3]);
   if (q == 0) {
-    float inv = 1.f / r;
+    // two atoms at one place have no direction: report it (deferred input diagnostics) and keep the numbers finite
+    if (!(r > 0.f)) atomicOr(flag + 1, INPUT_COINCIDENT);
+    float inv = r > 0.f ? 1.f / r : 0.f;
     geo[e] = make_float4(dx * inv, dy * inv, dz * inv, r);
     float w = 3.14159265358979323846f / rc;
     float sn, cs;
@@ -596,7 +613,7 @@ inline void launch_edge_features(mlip_ctx* ctx, int64_t E, int K, float rc, floa
   while ((4 << qshift) < K) ++qshift;  // 2^qshift threads per edge, K <= 1024
   const int64_t per_block = 256 >> qshift;
   hipLaunchKernelGGL(k_edge_features, dim3((unsigned)((E + per_block - 1) / per_block)), dim3(256), 0, ctx->stream, ctx->d_pos,
-                     ctx->d_sender, ctx->d_receiver, ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, qshift, rc, ctx->d_geo, env, jphi);
+                     ctx->d_sender, ctx->d_receiver, ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, qshift, rc, ctx->d_geo, env, jphi, ctx->d_flag);
 }
 
 

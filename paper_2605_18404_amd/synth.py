@@ -89,6 +89,7 @@ class Workload:
     min_dist: float = 1.0
     cell_kind: str = "cubic"  # "cubic" | "triclinic" (sheared lattice, per structure) | "free" (molecule in vacuum: zero cell)
     gate: int = 0             # 1 (equivariant model): gated nonlinearity in the node update instead of the linear residual
+    filter_fp32: int = 0      # bf16 workloads: 1 keeps the radial-filter jets in fp32 (rounding touches GEMM operands only)
     n_experts: int = 0        # > 0: the node-level matrices of every layer (update MLP / per-l mixing) are banks of this many experts
 
     @property

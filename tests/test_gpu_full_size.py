@@ -13,6 +13,29 @@ from paper_2605_18404_amd.binding import Mlip
 
 from gpu_common import DEV, DevInputs, dev, oracle_train_step, per_tensor_rel, rel
 
+import json
+import os
+import sys
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+sys.path.insert(0, GOLDEN)
+import probes  # noqa: E402  (seeded probe definitions shared with the script that wrote the stored summaries)
+
+
+def _golden(name):
+    """Stored oracle summary written by tests/golden/make_full_size_goldens.py (oracle only)."""
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+def _check_probes(w, got_vec, want, tol, what):
+    """The whole gradient vector against the stored oracle summary: per tensor a sample of entries
+    element by element and the normwise error estimated from seeded projections; the flat vector too."""
+    err = probes.compare(probes.summarise(w.seed, got_vec, synth.param_slices(w)), want)
+    assert err["flat"] < tol, (what, err["flat"])
+    worst = max((v, k) for k, v in err.items() if k != "flat")
+    assert worst[0] < 3 * tol, (what, worst)
+
 pytestmark = pytest.mark.gpu
 TOL_FP32, TOL_BF16 = 1e-4, 2e-2
 
@@ -85,7 +108,16 @@ def test_cfg2_full_batch_sampled_structures():
     for s in range(w.n_structs):  # zero net force per structure at any size
         a, b = inp.struct_ptr[s], inp.struct_ptr[s + 1]
         assert np.abs(F[a:b].sum(0)).max() < 1e-3 * np.abs(F[a:b]).sum(0).max()
-    assert np.all(np.isfinite(out["grad"].cpu().numpy()))
+    # the whole batch against the stored oracle run of all 16 structures: every energy (relative), every
+    # structure's force norm, the loss, and the full gradient (it passes through the split reductions over all
+    # 296 k edges, which the two-structure cases do not reach)
+    gold = _golden("full_size_cfg2.json")
+    assert rel(E, gold["E"]) < TOL_BF16
+    assert np.max(np.abs(E - np.array(gold["E"])) / np.abs(gold["E"])) < 3 * TOL_BF16
+    fn = [np.linalg.norm(F[inp.struct_ptr[s]:inp.struct_ptr[s + 1]]) for s in range(w.n_structs)]
+    assert rel(fn, gold["F_norm"]) < TOL_BF16
+    assert abs(float(out["loss"].cpu()) - gold["loss"]) < TOL_BF16 * abs(gold["loss"])
+    _check_probes(w, out["grad"].cpu().numpy(), gold["grad"], TOL_BF16, "cfg2 grad")
     m.close()
 
 
@@ -98,9 +130,10 @@ def test_cfg3_full_stage_sampled_structures():
     m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff)
     h_out = m.mlip_forward_energy(d.pos, None, d.params, h_in=d.stage["h_in"])
     p, g_in = m.mlip_forward_force(g_out=d.stage["g_out"])
-    grad = torch.zeros(m.mlip_param_count(), device=DEV)
-    hdot_out = m.mlip_backward_force(d.stage["v"], grad, hdot_in=d.stage["hdot_in"])
-    lam_in = m.mlip_backward_energy(grad, lam_out=d.stage["lam_out"])
+    g_bf = torch.zeros(m.mlip_param_count(), device=DEV)
+    g_be = torch.zeros_like(g_bf)
+    hdot_out = m.mlip_backward_force(d.stage["v"], g_bf, hdot_in=d.stage["hdot_in"])
+    lam_in = m.mlip_backward_energy(g_be, lam_out=d.stage["lam_out"])
     torch.cuda.synchronize()
     got = dict(h_out=h_out.cpu().numpy(), p=p.cpu().numpy(), g_in=g_in.cpu().numpy(),
                hdot_out=hdot_out.cpu().numpy(), lam_in=lam_in.cpu().numpy())
@@ -111,7 +144,11 @@ def test_cfg3_full_stage_sampled_structures():
                            st["h_in"][a:b], st["g_out"][a:b], st["hdot_in"][a:b], st["v"][a:b], st["lam_out"][a:b], split=False)
         for k in got:
             assert rel(got[k][a:b], ref[k]) < TOL_BF16, (s, k)
-    assert np.all(np.isfinite(grad.cpu().numpy()))
+    # both shares of the gradient (Eq. 2) over all 64 structures and 593 k edges against the stored oracle run
+    gold = _golden("full_size_cfg3.json")
+    _check_probes(w, g_bf.cpu().numpy(), gold["grad_bf"], TOL_BF16, "cfg3 grad_bf")
+    _check_probes(w, g_be.cpu().numpy(), gold["grad_be"], TOL_BF16, "cfg3 grad_be")
+    _check_probes(w, (g_bf + g_be).cpu().numpy(), gold["grad"], TOL_BF16, "cfg3 grad")
     m.close()
 
 
