@@ -143,6 +143,26 @@ int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_stru
  * Asking for rev makes the call synchronous (it checks mlip_input_status first). */
 int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
 
+/* For callers that cannot allocate device memory at this point -- code under HIP graph capture set-up,
+ * tight serving loops that rebuild the neighbour list every step, harnesses that forbid hipMalloc: the
+ * radius graph of mlip_graph_build without a context and without any device allocation.  Same edge rule,
+ * same row and in-row order, same kernels; their work arrays live in a file-scope device array of the
+ * library (about 13 MB per GPU, held from the first use on that GPU until the process ends).
+ *   Inputs (device): pos[N,3], struct_ptr[B+1], cell[B,3,3]; hip_stream = the hipStream_t to run on.
+ *   Outputs (device, caller-allocated): row_ptr[N+1], sender[edge_capacity], shift[edge_capacity,3],
+ *   rev[edge_capacity]; *n_edges_host = the edge count E (entries beyond E are not written).
+ * Limits: N <= 16384 atoms, B <= 1024 structures, E <= min(edge_capacity, 1048576); beyond them
+ * MLIP_E_CAPACITY (*n_edges_host then holds the count that was needed if it was the edges), other errors
+ * as mlip_graph_build; mlip_graph_build_static_error() returns the calling thread's last message.
+ * Synchronous like mlip_graph_build (it reads struct_ptr, cell and the edge count back), so it cannot be
+ * recorded into a HIP graph itself.  Calls no hipMalloc / hipFree.  All calls on one GPU share that GPU's
+ * work array: two calls that overlap in time on one GPU (other threads, other streams) race; calls on
+ * different GPUs do not.  Nothing is kept between calls that a later call relies on. */
+int mlip_graph_build_static(int64_t n_atoms, int32_t n_structs, const float* pos, const int32_t* struct_ptr,
+                            const float* cell, float cutoff, void* hip_stream, int64_t edge_capacity,
+                            int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev, int64_t* n_edges_host);
+const char* mlip_graph_build_static_error(void);
+
 /* Deferred input diagnostics.  Bad inputs that only a kernel can see, after the graph build's own
  * read-back, never fault the GPU and cannot fail the asynchronous call that met them: the kernel keeps
  * its accesses in bounds and raises a device flag.  This call waits for the stream (synchronous) and

@@ -72,6 +72,9 @@ def load():
     lib.mlip_set_expert_weights.argtypes = [P, P, I32]
     lib.mlip_set_expert_weight_grad.argtypes = [P, P, I32]
     lib.mlip_input_status.argtypes = [P]
+    lib.mlip_graph_build_static.argtypes = [I64, I32, P, P, P, F, P, I64, P, P, P, P, C.POINTER(I64)]
+    lib.mlip_graph_build_static_error.argtypes = []
+    lib.mlip_graph_build_static_error.restype = C.c_char_p
     lib.mlip_optimizer_step.argtypes = [P, I64, P, P, P, P, I32, C.POINTER(mlip_adamw)]
     lib.mlip_forward_energy.argtypes = [P, P, P, P, P, P, P]
     lib.mlip_forward_force.argtypes = [P, P, P, P]
@@ -108,6 +111,24 @@ def mlip_gars_pack(sizes, n_mb: int, d_gp: int, seed: int):
     if s != 0:
         raise MlipError(s, "mlip_gars_pack: invalid argument")
     return mb_ptr, order[:M], typ
+
+
+def mlip_graph_build_static(pos, struct_ptr, cell, cutoff: float, row_ptr, sender, shift, rev, stream=None) -> int:
+    """Context-free radius graph into the caller's preallocated device tensors (row_ptr [N+1], sender [cap],
+    shift [cap,3], rev [cap], int32).  Allocates nothing on the device.  Returns the edge count."""
+    lib = load()
+    n = C.c_int64(0)
+    st = stream if stream is not None else torch.cuda.current_stream(pos.device)
+    cap = min(sender.shape[0], shift.shape[0], rev.shape[0])
+    s = lib.mlip_graph_build_static(pos.shape[0], struct_ptr.shape[0] - 1, _ptr(pos, torch.float32),
+                                    _ptr(struct_ptr, torch.int32), _ptr(cell, torch.float32), cutoff,
+                                    C.c_void_p(st.cuda_stream), cap, _ptr(row_ptr, torch.int32), _ptr(sender, torch.int32),
+                                    _ptr(shift, torch.int32), _ptr(rev, torch.int32), C.byref(n))
+    if s != 0:
+        e = MlipError(s, lib.mlip_graph_build_static_error().decode())
+        e.n_edges = int(n.value)
+        raise e
+    return int(n.value)
 
 
 class Mlip:

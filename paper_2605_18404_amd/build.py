@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmlip.so")
-SOURCES = ["api.hip", "graph.hip", "model.hip", "equivariant.hip", "optimizer.hip", "gars.cpp"]
+SOURCES = ["api.hip", "graph.hip", "graph_static.hip", "model.hip", "equivariant.hip", "optimizer.hip", "gars.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # The neighbour search decides r < r_c in fp32 and must take the same decision as a plain
