@@ -1,11 +1,24 @@
 """Benchmark of the whole hot path (graph build + FE + FF + loss + BF + BE) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--others cfg0,cfg1,cfg2,cfg3]
+                    [--no-others] [--no-cpu-baseline] [--copy-probe]
 
-Prints ONE JSON line: atoms/s of the full training step on the synthetic workload that stands
-in for the paper's 400-atom micro-batches, per-phase milliseconds, the roofline figures of the
-dominant kernel (timed live with HIP events through the library's own kernel-timing entry
-point) and the float64 CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line.  The headline (`value`, `ms_per_step`, `phase_ms`, `roofline`) is the largest
+single-GPU workload, cfg4: one periodic cell of 20,000 atoms (1.8 M edges) under the l <= 2 equivariant
+model with bf16 matrix products -- the stand-in, at this build's scale, for the paper's 400-atom
+micro-batches.  `per_workload` carries the same measurements (shorter runs) for the other four
+workloads, so that one default run reports all five.  Per workload:
+  * atoms/s and edges/s of the full training step, inputs resident in HBM, graph build included;
+  * per-phase milliseconds from HIP events (graph, FE, FF + loss, BF, BE);
+  * every instrumented kernel's average launch time, measured live with HIP-event pairs recorded by the
+    library on the stream it launches on (mlip_kernel_timer_select / _read);
+  * the roofline figures of the kernel that takes the most time per step (during the timed steps the
+    library's event pairs bracket that kernel's launches): matrix products against the MFMA peak of
+    their operand type; the invariant gather kernels against the HBM peak; the equivariant
+    tensor-product kernels, which are bound by plain fp32 vector arithmetic, against the fp32 vector
+    peak (`bound: "alu"`), with their HBM figures beside it -- both the bytes this build actually
+    streams (materialised filter jets) and the floor of an implementation that would stream none.
+The float64 CPU oracle is timed on a bounded sample of the headline workload (`cpu_baseline`).
 """
 from __future__ import annotations
 
@@ -21,32 +34,50 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_FP32_VALU_TFLOPS = 157.3   # 256 CUs x 128 fp32 FMA lanes x 2 flop x 2.4 GHz
 PEAK_BF16_MFMA_TFLOPS = 2500.0
+NNZ_COUPLINGS = 83              # non-zero entries of the 11 real coupling tensors (l <= 2), counted from the generated table
+N_PATHS = 11
 
 
-# Kernel ids of include/mlip.h and the algorithmic work of one launch (E edges, N atoms):
-# GEMMs in flop (2 x rows x inner x out), gather kernels in HBM bytes (each edge tensor and each
-# node table touched once, indices and geometry included).
 def kernel_table(w, E, N):
+    """Kernel ids of include/mlip.h -> (name, bound, algorithmic work per launch, extra figures).
+    Matrix products: flop = 2 x rows x inner x out.  Invariant gather kernels: HBM bytes, every edge tensor
+    and node table touched once, indices and geometry included.  Equivariant tensor-product kernels: fp32
+    vector flop = 2 (nnz(T) + 9 * 11) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
+    FF, 3 in BF, 4 in BE), with two HBM byte counts beside it: `hbm_streamed` = what this build moves (the
+    materialised filter jets, 12 values per channel and row, and their adjoints) and `hbm_floor` = node
+    tables once plus 20 bytes per edge, what an implementation that recomputed the filters would move."""
     C, H, K = w.channels, w.edge_hidden, w.n_rbf
     eqv = w.l_max == 2
-    Co = 11 * C if eqv else C          # width of the radial filter per edge
+    Co = N_PATHS * C if eqv else C     # width of the radial filter per edge
+    Cs = 12 * C if eqv else C          # stored width (one pad per channel in the equivariant layout)
     f4 = 4
-    fj = 2 if w.gemm_bf16 else 4       # filter jets and their adjoints are held in the operand precision
+    fj = 2 if (w.gemm_bf16 and not getattr(w, "filter_fp32", 0)) else 4   # filter jets
+    fx = 2 if w.gemm_bf16 else 4                                           # their adjoints (matrix-product operands)
     node = (9 if eqv else 1) * N * C * f4
     geo = 16 + 4                       # unit vector + length, sender index
-    return {
-        1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H),
-        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co),
-        3: ("msg_fe", "hbm", E * Co * fj + 2 * node + E * geo),
-        4: ("msg_ff", "hbm", 2 * E * Co * fj + 4 * node + E * geo),
-        5: ("msg_bf", "hbm", 3 * E * Co * fj + 4 * node + E * (geo + 8)),
-        6: ("msg_be", "hbm", 3 * E * Co * fj + 6 * node + E * (geo + 8)),
-        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * Co * H),
-        8: ("be_dgrad_gemm", "mfma", 2.0 * E * Co * H),
-        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H),
-        10: ("be_wgrad_gemm", "mfma", 2.0 * E * Co * H),
+    t = {
+        1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H, {}),
+        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co, {}),
+        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
+        8: ("be_dgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
+        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
+        10: ("be_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
     }
+    streamed = {3: E * Cs * fj + 2 * node + E * geo,
+                4: 2 * E * Cs * fj + 4 * node + E * geo,
+                5: 2 * E * Cs * fj + E * Cs * fx + 4 * node + E * (geo + 8),
+                6: 2 * E * Cs * fj + E * Cs * fx + 6 * node + E * (geo + 8)}
+    tables = {3: 2, 4: 4, 5: 4, 6: 6}
+    names = {3: "msg_fe", 4: "msg_ff", 5: "msg_bf", 6: "msg_be"}
+    for kid in (3, 4, 5, 6):
+        if eqv:
+            flop = 2.0 * (NNZ_COUPLINGS + 9 * N_PATHS) * C * E * (kid - 2)
+            t[kid] = (names[kid], "alu", flop, {"hbm_streamed_bytes": streamed[kid], "hbm_floor_bytes": tables[kid] * node + 20 * E})
+        else:
+            t[kid] = (names[kid], "hbm", streamed[kid], {})
+    return dict(sorted(t.items()))
 
 
 def load_traffic(workload, kernel):
@@ -63,15 +94,17 @@ def cpu_baseline(w, inp, budget_s=20.0):
     """Times the oracle as it stands on a bounded sample: whole structures of the batch, one
     after the other (graph build + all four phases each), until about budget_s seconds of CPU
     work have been spent.  A single-structure workload too large for the oracle is sampled by a
-    smaller cell of the same density and model (stated in `sample`)."""
+    smaller cell of the same density and model (stated in `sample` and in `stand_in`)."""
     import numpy as np
     import torch
 
     from oracle import mlip_oracle as O
     from paper_2605_18404_amd import synth
-    note = ""
+    note, stand_in = "", None
     if w.n_structs == 1 and w.atoms_per_struct > 1000:
         n = 300
+        stand_in = {"atoms": n, "reason": "the oracle's reverse-mode pass over the 20,000-atom cell does not fit in host memory; "
+                                          "same density, same model, periodic cell of 300 atoms"}
         w = synth.shrink(w, atoms_per_struct=n, box=w.box * (n / w.atoms_per_struct) ** (1.0 / 3.0))
         inp = synth.make_inputs(w)
         note = f"a {n}-atom cell of the same density and model stands in for the large cell; "
@@ -98,35 +131,34 @@ def cpu_baseline(w, inp, budget_s=20.0):
         passes += 1
         if t_used > budget_s:
             break
-    return {"value": done_atoms / t_used, "unit": "atoms/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{note}{n_done} structure steps ({passes} pass(es) over the batch's {w.n_structs} structures, {done_atoms} atoms), "
-                      f"graph build + full step each, {t_used:.1f} s of CPU time"}
+    out = {"value": done_atoms / t_used, "unit": "atoms/s", "cores": torch.get_num_threads(), "kind": "oracle",
+           "sample": f"{note}{n_done} structure steps ({passes} pass(es) over the batch's {w.n_structs} structures, {done_atoms} atoms), "
+                     f"graph build + full step each, {t_used:.1f} s of CPU time"}
+    if stand_in:
+        out["stand_in"] = stand_in
+    return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also launch the library's 256 MiB copy kernel once (calibrates rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+WORKLOAD_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg1_mole128": 1}
 
+
+def make_workload(name):
+    from paper_2605_18404_amd import synth
+    w = synth.WORKLOADS[WORKLOAD_INDEX[name]]
+    if name == "cfg1_mole128":  # the invariant batch with UMA's 128-expert banks in the update MLP (Table 4)
+        w = synth.shrink(w, n_experts=128, name="cfg1_invariant_batch_mole128")
+    return w
+
+
+def measure(name, steps, warmup, copy_probe=False):
+    """All measurements of one workload: (result dict, workload, inputs)."""
     import numpy as np
     import torch
 
     from paper_2605_18404_amd import synth
     from paper_2605_18404_amd.binding import Mlip
 
-    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg1_mole128": 1}[args.workload]
-    w = synth.WORKLOADS[idx]
-    if args.workload == "cfg1_mole128":  # the bench batch with UMA's 128-expert banks in the update MLP (Table 4)
-        w = synth.shrink(w, n_experts=128, name="cfg1_invariant_batch_mole128")
+    w = make_workload(name)
     inp = synth.make_inputs(w)
     dev = "cuda:0"
     t = lambda a: torch.as_tensor(np.ascontiguousarray(a)).to(dev)
@@ -169,55 +201,70 @@ def main():
             res["phase_ms"] = [ev[k].elapsed_time(ev[k + 1]) for k in range(5)]
         return res
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
-    if args.copy_probe:
+    if copy_probe:
         src = torch.ones(64 * 1024 * 1024, device=dev, dtype=torch.float32)
         m.mlip_copy_probe(torch.empty_like(src), src)
     torch.cuda.synchronize()
     E_edges, N = m.n_edges, w.n_atoms
     table = kernel_table(w, E_edges, N)
     # which kernel dominates: one untimed step per candidate with the library's event timer
-    per_kernel_us = {}
-    for kid, (name, _, _) in table.items():
+    per_kernel = {}
+    for kid, (kname, _, _, _) in table.items():
         m.mlip_kernel_timer_select(kid)
         step()
         n, tot = m.mlip_kernel_timer_read()
-        per_kernel_us[name] = {"launches_per_step": n, "avg_us": (tot / n * 1e3) if n else 0.0, "ms_per_step": tot}
-    dom = max(table, key=lambda k: per_kernel_us[table[k][0]]["ms_per_step"])
+        per_kernel[kname] = {"launches_per_step": n, "avg_us": (tot / n * 1e3) if n else 0.0, "ms_per_step": tot}
+    dom = max(table, key=lambda k: per_kernel[table[k][0]]["ms_per_step"])
     m.mlip_kernel_timer_select(dom)  # event pairs around its launches during the timed steps
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms = (t1 - t0) * 1e3 / args.steps
+    ms = (t1 - t0) * 1e3 / steps
     n_launch, tot_ms = m.mlip_kernel_timer_read()
     m.mlip_kernel_timer_select(0)
-    name, bound, work = table[dom]
-    avg_s = tot_ms * 1e-3 / max(n_launch, 1)
-    if bound == "mfma":
-        peak, unit = (PEAK_BF16_MFMA_TFLOPS if w.gemm_bf16 else PEAK_FP32_MFMA_TFLOPS), "TFLOP/s"
-        achieved = work / avg_s / 1e12
-    else:
-        peak, unit = PEAK_HBM_GBS, "GB/s"
-        achieved = work / avg_s / 1e9
-    roof = {"kernel": name, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-            "traffic": load_traffic(w.name, name), "avg_launch_us": avg_s * 1e6, "launches_timed": n_launch,
-            "algorithmic_work_per_launch": work, "per_kernel": per_kernel_us}
+
+    def figures(kid, avg_s):
+        kname, bound, work, extra = table[kid]
+        if bound == "mfma":
+            peak, unit = (PEAK_BF16_MFMA_TFLOPS if w.gemm_bf16 else PEAK_FP32_MFMA_TFLOPS), "TFLOP/s"
+            achieved = work / avg_s / 1e12
+        elif bound == "alu":
+            peak, unit = PEAK_FP32_VALU_TFLOPS, "TFLOP/s"
+            achieved = work / avg_s / 1e12
+        else:
+            peak, unit = PEAK_HBM_GBS, "GB/s"
+            achieved = work / avg_s / 1e9
+        r = {"kernel": kname, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+             "traffic": load_traffic(w.name, kname), "avg_launch_us": avg_s * 1e6, "algorithmic_work_per_launch": work}
+        for k, b in extra.items():  # the tensor-product kernels' HBM figures beside their arithmetic ones
+            r[k] = b
+            r[k.replace("_bytes", "_GBs")] = b / avg_s / 1e9
+            r[k.replace("_bytes", "_frac_of_hbm_peak")] = b / avg_s / 1e9 / PEAK_HBM_GBS
+        return r
+
+    roof = figures(dom, tot_ms * 1e-3 / max(n_launch, 1))
+    roof["launches_timed"] = n_launch
+    # every instrumented kernel against its own roofline (from the selection pass: one step each)
+    for kid, (kname, _, _, _) in table.items():
+        if per_kernel[kname]["launches_per_step"]:
+            f = figures(kid, per_kernel[kname]["avg_us"] * 1e-6)
+            per_kernel[kname].update({k: f[k] for k in f if k not in ("kernel", "avg_launch_us")})
+    roof["per_kernel"] = per_kernel
     # per-phase times from HIP events (a separate, synchronous pass: it does not enter `value`)
     ph = np.zeros(5)
-    n_ph = max(3, min(20, args.steps))
+    n_ph = max(3, min(20, steps))
     for _ in range(n_ph):
         ph += np.array(step(timed=True)["phase_ms"])
     ph /= n_ph
-
-    line = {
-        "metric": "atoms/s per FE+FF+BF+BE train step", "value": w.n_atoms / (ms * 1e-3), "unit": "atoms/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_bf16 else "f32", "data": "synthetic",
+    res = {
+        "value": w.n_atoms / (ms * 1e-3), "ms_per_step": ms, "steps": steps, "warmup": warmup,
+        "dtype": "bf16" if w.gemm_bf16 else "f32",
         "config": {"workload": w.name, "atoms": w.n_atoms, "structures": w.n_structs, "edges": E_edges,
                    "channels": w.channels, "layers": w.n_layers, "n_rbf": w.n_rbf, "cutoff": w.cutoff,
                    "l_max": w.l_max, "edge_mlp_depth": w.edge_depth, "n_experts": w.n_experts, "includes_graph_build": True,
@@ -230,11 +277,58 @@ def main():
         # the stage's measured phase times in the paper's closed-form bubble model (Sec. 4.2)
         from paper_2605_18404_amd import wavek_model
         fe, ff, bf, be = ph[1], ph[2], ph[3], ph[4]
-        line["wavek_bubble_model_ms"] = {
+        res["wavek_bubble_model_ms"] = {
             "naive_per_microbatch": wavek_model.naive_bubble(fe, ff, bf, be),
             **{f"P{P}_Nmb32_k{k}": wavek_model.wavek_bubbles(fe, ff, bf, be, P, 32, k) for P in (4, 8) for k in (P, 2 * P, 32)}}
+    m.close()
+    del m, d, st, grad, out
+    torch.cuda.empty_cache()
+    return res, w, inp
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOAD_INDEX))
+    ap.add_argument("--others", default="cfg0,cfg1,cfg2,cfg3",
+                    help="workloads measured with shorter runs and reported under per_workload")
+    ap.add_argument("--no-others", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch the library's 256 MiB copy kernel once (calibrates rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    head, w, inp = measure(args.workload, args.steps, args.warmup, copy_probe=args.copy_probe)
+    line = {
+        "metric": "atoms/s per FE+FF+BF+BE train step", "value": head["value"], "unit": "atoms/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": head["config"], "edges_per_s": head["edges_per_s"], "phase_ms": head["phase_ms"], "roofline": head["roofline"],
+    }
+    if "wavek_bubble_model_ms" in head:
+        line["wavek_bubble_model_ms"] = head["wavek_bubble_model_ms"]
+    if not args.no_others:
+        line["per_workload"] = {}
+        for name in [n for n in args.others.split(",") if n and n != args.workload]:
+            r, _, _ = measure(name, max(5, min(30, args.steps)), max(2, min(5, args.warmup)))
+            roof = r["roofline"]
+            line["per_workload"][name] = {
+                "workload": r["config"]["workload"], "atoms_per_s": r["value"], "edges_per_s": r["edges_per_s"],
+                "ms_per_step": r["ms_per_step"], "steps": r["steps"], "dtype": r["dtype"], "phase_ms": r["phase_ms"],
+                "atoms": r["config"]["atoms"], "edges": r["config"]["edges"], "workspace_GB": r["config"]["workspace_GB"],
+                "dominant_kernel": {k: roof[k] for k in roof if k != "per_kernel"},
+                "per_kernel": roof["per_kernel"],
+                **({"wavek_bubble_model_ms": r["wavek_bubble_model_ms"]} if "wavek_bubble_model_ms" in r else {}),
+            }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, inp)
+        if "stand_in" in line["cpu_baseline"]:
+            line["config"]["cpu_baseline_stand_in"] = line["cpu_baseline"]["stand_in"]
     print(json.dumps(line))
 
 
