@@ -93,6 +93,8 @@ typedef struct {
                                bf16 product, consumed element-wise by the message kernels -- are stored in bf16, as a
                                mixed-precision linear layer returns them (half the bytes of the largest edge tensor).
                                1: they are stored in fp32, so that bf16 rounding touches matrix-product operands only */
+  int32_t position_grad;    /* 1: also allocate the workspace for the position gradient dL/dx (mlip_set_position_grad);
+                               0: none, and that call is refused */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */
@@ -212,6 +214,17 @@ int mlip_backward_force(mlip_ctx* ctx, const float* v, const float* hdot_in, flo
  * Stage: lam_out[N,C] = dL/dh_out read, lam_in[N,C] = dL/dh_in written. */
 int mlip_backward_energy(mlip_ctx* ctx, const float* Ebar, const float* lam_out, float* grad_params,
                          float* lam_in);
+/* Optional position gradient of the loss, dL/dx.  It differentiates the forces once more in the positions, so
+ * it is where the second derivatives of the edge features enter (d2 phi/dr2, f_c'', the second r-derivative of
+ * the edge MLP; for the equivariant model also the second derivatives of the harmonics); the parameter gradient
+ * never needs them, and nothing of this runs unless a buffer is registered here.
+ *   grad_pos: device pointer [N,3] float32 that every later mlip_backward_energy (and mlip_train_step) OVERWRITES:
+ *   whole model: dL/dx for the loss of mlip_loss's cotangents, i.e. d/dx [sum_s Ebar_s E_s + D_v E] with Ebar and
+ *   v = -dL/dF held fixed; stage: this stage's additive share d/dx [<lam_out, h_out> + <hdot_in, g_in> + <v, p>].
+ *   NULL switches it off again (the default).  Needs mlip_config.position_grad = 1 (MLIP_E_INVALID otherwise).
+ * The caller keeps the buffer alive and sized for the batches it builds. */
+int mlip_set_position_grad(mlip_ctx* ctx, float* grad_pos);
+
 /* Whole step for a whole model: graph build, FE, FF, loss, BF, BE.  grad_params is overwritten.
  * phase_ms_host[5] (graph, FE, FF+loss, BF, BE; milliseconds from HIP events) makes the call
  * synchronous; NULL skips timing.  The graph build inside is synchronous in any case. */

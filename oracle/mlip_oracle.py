@@ -394,11 +394,13 @@ def _t(a, grad=False):
 
 
 def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
-               graph: Optional[Dict] = None, split: bool = False, alpha=None) -> Dict[str, np.ndarray]:
+               graph: Optional[Dict] = None, split: bool = False, alpha=None, grad_pos: bool = False) -> Dict[str, np.ndarray]:
     """One training step of the whole model: returns loss, E [B], F [N,3], grad [n_params]
     (= dL/dtheta), and with split=True also grad_bf / grad_be, the BF and BE shares.
     alpha [B, n_experts]: mixing coefficients of the expert banks (cfg["n_experts"] > 0); then
-    grad_alpha = dL/dalpha is returned too."""
+    grad_alpha = dL/dalpha is returned too.  grad_pos=True adds grad_pos [N,3] = dL/dx, the derivative of
+    the loss with respect to the positions (it differentiates the forces once more in x, so it brings in
+    the second derivatives of every edge feature)."""
     if graph is None:
         graph = radius_graph(pos, struct_ptr, cell, cfg["cutoff"])
     x = _t(pos, True)
@@ -416,8 +418,11 @@ def train_step(cfg: Dict, pos, species, struct_ptr, cell, params, E_ref, F_ref,
     F = -dEdx
     L = loss_fn(E, F, _t(E_ref), _t(F_ref), cfg["force_weight"])
     out = dict(E=E.detach().numpy(), F=F.detach().numpy(), loss=float(L.detach()))
-    wrt = [theta] + ([theta_ff] if split else []) + ([al] if al is not None else [])
+    wrt = [theta] + ([theta_ff] if split else []) + ([al] if al is not None else []) + ([x] if grad_pos else [])
     gs = list(torch.autograd.grad(L, wrt, allow_unused=True))
+    if grad_pos:
+        gx = gs.pop()
+        out["grad_pos"] = np.zeros_like(out["F"]) if gx is None else gx.numpy()
     if al is not None:  # dL/dalpha [B, n_experts]: what a router producing the coefficients would receive
         out["grad_alpha"] = gs.pop().numpy()
     if split:
@@ -481,7 +486,7 @@ def stage_forward(h_in, x, graph, cell, struct_ptr, lin: _Lin, cfg) -> torch.Ten
 
 
 def stage_step(cfg: Dict, pos, struct_ptr, cell, params, h_in, g_out, hdot_in, v, lam_out,
-               graph: Optional[Dict] = None, split: bool = True) -> Dict[str, np.ndarray]:
+               graph: Optional[Dict] = None, split: bool = True, grad_pos: bool = False) -> Dict[str, np.ndarray]:
     """The four phases for one pipeline stage, with the tensors that cross stage boundaries
     (Table 2: activations h, dE/dh, dL_F/d(dE/dh), dL/dh) supplied by the caller.
 
@@ -489,6 +494,7 @@ def stage_step(cfg: Dict, pos, struct_ptr, cell, params, h_in, g_out, hdot_in, v
     With Phi = <lam_out, h_out> + <hdot_in, g_in> + <v, p> (lam_out, hdot_in, v constants):
     BF returns hdot_out = dPhi/dg_out and the second-order share of dPhi/dtheta,
     BE returns lam_in = dPhi/dh_in and the first-order share of dPhi/dtheta.
+    grad_pos=True adds grad_pos = dPhi/dx, this stage's share of the loss's position derivative.
     """
     if graph is None:
         graph = radius_graph(pos, struct_ptr, cell, cfg["cutoff"])
@@ -501,10 +507,13 @@ def stage_step(cfg: Dict, pos, struct_ptr, cell, params, h_in, g_out, hdot_in, v
     h_out = stage_forward(hin, x, graph, _t(cell), struct_ptr, lin, cfg)
     g_in, p = torch.autograd.grad((h_out * gout).sum(), [hin, x], create_graph=True)
     Phi = (_t(lam_out) * h_out).sum() + (_t(hdot_in) * g_in).sum() + (_t(v) * p).sum()
-    wrt = [theta, gout, hin] + ([theta_ff] if split else [])
-    gs = torch.autograd.grad(Phi, wrt, allow_unused=True)
+    wrt = [theta, gout, hin] + ([theta_ff] if split else []) + ([x] if grad_pos else [])
+    gs = list(torch.autograd.grad(Phi, wrt, allow_unused=True))
+    gx = gs.pop() if grad_pos else None
     out = dict(h_out=h_out.detach().numpy(), g_in=g_in.detach().numpy(), p=p.detach().numpy(),
                Phi=float(Phi.detach()), hdot_out=gs[1].numpy(), lam_in=gs[2].numpy())
+    if grad_pos:
+        out["grad_pos"] = gx.numpy()
     if split:
         out["grad_be"] = gs[0].numpy()
         out["grad_bf"] = gs[3].numpy()

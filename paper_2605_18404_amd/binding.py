@@ -31,7 +31,7 @@ class mlip_config(C.Structure):
     _fields_ = [("model_kind", C.c_int32), ("n_species", C.c_int32), ("channels", C.c_int32),
                 ("n_layers", C.c_int32), ("n_rbf", C.c_int32), ("edge_hidden", C.c_int32),
                 ("edge_mlp_depth", C.c_int32), ("l_max", C.c_int32), ("gemm_dtype", C.c_int32),
-                ("n_experts", C.c_int32), ("gate", C.c_int32), ("filter_fp32", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
+                ("n_experts", C.c_int32), ("gate", C.c_int32), ("filter_fp32", C.c_int32), ("position_grad", C.c_int32), ("cutoff", C.c_float), ("force_weight", C.c_float),
                 ("max_atoms", C.c_int64), ("max_structs", C.c_int64), ("max_edges", C.c_int64)]
 
 
@@ -72,6 +72,7 @@ def load():
     lib.mlip_set_expert_weights.argtypes = [P, P, I32]
     lib.mlip_set_expert_weight_grad.argtypes = [P, P, I32]
     lib.mlip_input_status.argtypes = [P]
+    lib.mlip_set_position_grad.argtypes = [P, P]
     lib.mlip_graph_build_static.argtypes = [I64, I32, P, P, P, F, P, I64, P, P, P, P, C.POINTER(I64)]
     lib.mlip_graph_build_static_error.argtypes = []
     lib.mlip_graph_build_static_error.restype = C.c_char_p
@@ -136,14 +137,14 @@ class Mlip:
 
     def __init__(self, *, model_kind: int, channels: int, n_layers: int, n_rbf: int, edge_hidden: int,
                  edge_mlp_depth: int = 2, l_max: int = 0, n_species: int = 1, gemm_bf16: bool = False,
-                 n_experts: int = 0, gate: int = 0, filter_fp32: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
+                 n_experts: int = 0, gate: int = 0, filter_fp32: int = 0, position_grad: int = 0, cutoff: float, force_weight: float = 10.0, max_atoms: int, max_structs: int, max_edges: int,
                  device: str = "cuda:0", stream: Optional[torch.cuda.Stream] = None):
         self.lib = load()
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self.cfg = mlip_config(model_kind, n_species, channels, n_layers, n_rbf, edge_hidden, edge_mlp_depth, l_max,
-                               1 if gemm_bf16 else 0, n_experts, gate, filter_fp32, cutoff, force_weight, max_atoms, max_structs, max_edges)
+                               1 if gemm_bf16 else 0, n_experts, gate, filter_fp32, position_grad, cutoff, force_weight, max_atoms, max_structs, max_edges)
         self.ctx = C.c_void_p()
         s = self.lib.mlip_create(C.byref(self.cfg), C.c_void_p(self.stream.cuda_stream), C.byref(self.ctx))
         if s != 0:
@@ -204,6 +205,11 @@ class Mlip:
         a, b, e = C.c_int64(0), C.c_int64(0), C.c_int64(0)
         self._check(self.lib.mlip_graph_sizes(self.ctx, C.byref(a), C.byref(b), C.byref(e)))
         return int(a.value), int(b.value), int(e.value)
+
+    def mlip_set_position_grad(self, grad_pos):
+        """grad_pos: device tensor [N,3] float32 that mlip_backward_energy then overwrites with dL/dx, or None."""
+        self._check(self.lib.mlip_set_position_grad(self.ctx, _ptr(grad_pos, torch.float32)))
+        self._grad_pos = grad_pos  # keep the tensor alive while the library holds its address
 
     def mlip_input_status(self):
         """Synchronous: raises MlipError if a kernel met a bad species index or coincident atoms."""

@@ -91,6 +91,8 @@ const char* check_config(const mlip_config& c) {
   if (c.n_experts > 0 && c.model_kind == MLIP_MODEL_STAGE) return "expert banks are built for the whole models only";
   if (c.gate != 0 && c.gate != 1) return "gate must be 0 or 1";
   if (c.filter_fp32 != 0 && c.filter_fp32 != 1) return "filter_fp32 must be 0 or 1";
+  if (c.position_grad != 0 && c.position_grad != 1) return "position_grad must be 0 or 1";
+  if (c.position_grad == 1 && c.n_experts > 0) return "the position gradient is not built for expert banks";
   if (c.gate == 1 && c.model_kind != MLIP_MODEL_EQUIVARIANT) return "the gated update belongs to the equivariant model";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";
@@ -166,6 +168,14 @@ int mlip_set_expert_weight_grad(mlip_ctx* ctx, float* grad_alpha, int32_t n_stru
     MLIP_FAIL(ctx, MLIP_E_INVALID, "set_expert_weight_grad: n_structs must be in [1, max_structs]");
   ctx->d_grad_alpha = grad_alpha;
   ctx->grad_alpha_structs = grad_alpha ? n_structs : 0;
+  return MLIP_OK;
+}
+
+int mlip_set_position_grad(mlip_ctx* ctx, float* grad_pos) {
+  if (!ctx) return MLIP_E_INVALID;
+  if (grad_pos && !ctx->cfg.position_grad)
+    MLIP_FAIL(ctx, MLIP_E_INVALID, "set_position_grad: create the context with position_grad = 1 (its workspace is allocated at creation)");
+  ctx->d_grad_pos = grad_pos;
   return MLIP_OK;
 }
 

@@ -121,6 +121,9 @@ struct mlip_ctx {
   int32_t* d_struct_ptr = nullptr; // [copies * max_structs + 1] first row of every (copy, structure) block, then the end
   int64_t n_row_groups = 0;        // row tiles per copy of the atom rows
 
+  // ---- optional position gradient (mlip_set_position_grad): caller's buffer [N,3] that BE fills, or null
+  float* d_grad_pos = nullptr;
+
   // ---- kernel timer (mlip_kernel_timer_select / _read): event pairs around one kernel's launches
   int timed_kernel = 0;
   std::vector<hipEvent_t> tev;  // pool, pairs (start, stop)

@@ -841,6 +841,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
+  if (cf.position_grad) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: the position gradient is built for the invariant model and the pipeline stage only");
   EqvWs* w = new EqvWs();
   ctx->model_ws = w;
   bool ok = true;

@@ -138,6 +138,50 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
   __device__ __forceinline__ float4 finish(const Raw& v) const { return mul4(dsilu4(v.a), v.b); }
 };
 
+// ---- second-derivative rows, used only for the optional position gradient dL/dx
+struct LdPhi2 {  // row e, columns k..k+3 -> d^2 phi_k / dr^2 at r_e = (-2 gamma + 4 gamma^2 t^2) exp(-gamma t^2), t = r_e - k dmu
+  static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
+  static constexpr int WIDTH = 4;
+  struct Raw { float r; int k; };
+  const float4* geo;  // [E] (unit vector, length)
+  float dmu, gamma;
+  __device__ __forceinline__ Raw fetch(int64_t e, int64_t c) const { return Raw{geo[e].w, (int)c}; }
+  __device__ __forceinline__ float4 finish(const Raw& x) const {
+    float o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float t = x.r - (float)(x.k + u) * dmu;
+      o[u] = (4.f * gamma * gamma * t * t - 2.f * gamma) * __expf(-gamma * t * t);
+    }
+    return make_float4(o[0], o[1], o[2], o[3]);
+  }
+};
+struct LdJetSecond {  // row e -> d^2 silu(u)/dr^2 = silu''(u) u'^2 + silu'(u) u'',  u = uj[2e], u' = uj[2e+1], u'' = u2[e]
+  static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
+  static constexpr int WIDTH = 4;
+  struct Raw { float4 a, b, c; };
+  const float* uj;
+  const float* u2;
+  int64_t W;
+  __device__ __forceinline__ Raw fetch(int64_t e, int64_t c) const {
+    const float* pe = uj + 2 * e * W + c;
+    return Raw{ld4(pe), ld4(pe + W), ld4(u2 + e * W + c)};
+  }
+  __device__ __forceinline__ float4 finish(const Raw& x) const {
+    const float a[4] = {x.a.x, x.a.y, x.a.z, x.a.w}, b[4] = {x.b.x, x.b.y, x.b.z, x.b.w}, c[4] = {x.c.x, x.c.y, x.c.z, x.c.w};
+    float o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float d1, d2;
+      dsilu12(a[j], d1, d2);
+      o[j] = d2 * b[j] * b[j] + d1 * c[j];
+    }
+    return make_float4(o[0], o[1], o[2], o[3]);
+  }
+};
+
 struct LdBf16 {  // bf16 matrix p[row * ld + col] (values already rounded by their producer)
   static constexpr bool PAIRED = false;
   __device__ __forceinline__ void shift(int64_t) {}

@@ -46,6 +46,12 @@ struct InvWs {
   float* Facc = nullptr;    // [N,3]
   float* v = nullptr;       // [N,3] copy taken at BF
   float* Ebar = nullptr;    // [B]
+  // optional position gradient dL/dx (mlip_config.position_grad): second-derivative rows of the hidden levels,
+  // the last edge matrix's output with its first and second r-derivative, and the per-atom accumulator
+  float* U2[2] = {nullptr, nullptr};  // [E][H]
+  float* Wj = nullptr;                // [E][2][C] (w, w')
+  float* Wpp = nullptr;               // [E][C]   w''
+  float* gp_acc = nullptr;            // [N,3]
 };
 
 inline InvWs* ws_of(mlip_ctx* ctx) { return (InvWs*)ctx->model_ws; }
@@ -250,6 +256,82 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
         st4(X + (int64_t)e * C + c0, x);
       });
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
+}
+
+// Position gradient of one layer.  With Psi = sum_s Ebar_s E_s + D_v E (whose x-derivative is dL/dx), an edge's
+// geometry enters through the filter omega(r) = f_c w and through omegadot = rdot omega'(r), rdot = rhat.(v_j - v_i):
+//   dPsi/dr_vec_e = [A_e . omega' + rdot B_e . omega''] rhat + (B_e . omega') (dv - rhat rdot) / r,
+//   A_e = h_j lam_a,i + hdot_j mu_a,i  (adjoint of omega_e),   B_e = h_j mu_a,i  (adjoint of omegadot_e),
+// and atom i collects -dPsi/dr_vec over the edges it receives and +dPsi/dr_vec over those it sends; the opposite
+// edge has the same r, omega, rdot and the opposite rhat, dv, so both are formed here from the row's own and the
+// gathered sender's node values.  omega' = c' w + c w', omega'' = c'' w + 2 c' w' + c w'', c'' = -(pi/r_c)^2 (c - 1/2).
+struct InGp { float4 w, wp, wpp, hj, hdj, laj, maj, ge; float2 cc; float v0, v1, v2; };
+__global__ void __launch_bounds__(256) k_msg_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const float4* __restrict__ geo, const float2* __restrict__ env,
+                                                const float* __restrict__ Wj, const float* __restrict__ Wpp,
+                                                const float* __restrict__ h, const float* __restrict__ hd,
+                                                const float* __restrict__ mu_a, const float* __restrict__ lam_a,
+                                                const float* __restrict__ v, float k2, int N, int C, float* __restrict__ gp) {
+  __shared__ float3 red[256];
+  const int CQ = C / 4;
+  RowThread t = row_thread(N, CQ);
+  float3 f = make_float3(0.f, 0.f, 0.f);
+  if (t.active) {
+    const int c0 = 4 * t.cq;
+    const int64_t ro = (int64_t)t.row * C + c0;
+    const float4 hi = ld4(h + ro), hdi = ld4(hd + ro), mai = ld4(mu_a + ro), lai = ld4(lam_a + ro);
+    const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
+    walk_row<2, InGp>(
+        sender, row_ptr[t.row], row_ptr[t.row + 1],
+        [&](int e, int j) {
+          InGp x;
+          x.w = ld4(Wj + (int64_t)(2 * e) * C + c0);
+          x.wp = ld4(Wj + (int64_t)(2 * e + 1) * C + c0);
+          x.wpp = ld4(Wpp + (int64_t)e * C + c0);
+          const int64_t jo = (int64_t)j * C + c0;
+          x.hj = ld4(h + jo); x.hdj = ld4(hd + jo); x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
+          x.ge = geo[e];
+          x.cc = env[e];
+          x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+          return x;
+        },
+        [&](int, const InGp& q) {
+          const float d0 = q.v0 - vi0, d1 = q.v1 - vi1, d2 = q.v2 - vi2;
+          const float rd = q.ge.x * d0 + q.ge.y * d1 + q.ge.z * d2;
+          const float c = q.cc.x, cp = q.cc.y, cpp = -k2 * (c - 0.5f);
+          const float w[4] = {q.w.x, q.w.y, q.w.z, q.w.w}, wp[4] = {q.wp.x, q.wp.y, q.wp.z, q.wp.w}, wpp[4] = {q.wpp.x, q.wpp.y, q.wpp.z, q.wpp.w};
+          const float hj[4] = {q.hj.x, q.hj.y, q.hj.z, q.hj.w}, hdj[4] = {q.hdj.x, q.hdj.y, q.hdj.z, q.hdj.w};
+          const float laj[4] = {q.laj.x, q.laj.y, q.laj.z, q.laj.w}, maj[4] = {q.maj.x, q.maj.y, q.maj.z, q.maj.w};
+          const float hi4[4] = {hi.x, hi.y, hi.z, hi.w}, hdi4[4] = {hdi.x, hdi.y, hdi.z, hdi.w};
+          const float lai4[4] = {lai.x, lai.y, lai.z, lai.w}, mai4[4] = {mai.x, mai.y, mai.z, mai.w};
+          float G = 0.f, g = 0.f;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float op = cp * w[u] + c * wp[u];
+            const float opp = cpp * w[u] + 2.f * cp * wp[u] + c * wpp[u];
+            const float A = hj[u] * lai4[u] + hdj[u] * mai4[u] + hi4[u] * laj[u] + hdi4[u] * maj[u];
+            const float Bm = hj[u] * mai4[u] + hi4[u] * maj[u];
+            G += A * op + rd * Bm * opp;
+            g += Bm * op;
+          }
+          const float gr = q.ge.w > 0.f ? g / q.ge.w : 0.f;
+          f.x -= G * q.ge.x + gr * (d0 - q.ge.x * rd);
+          f.y -= G * q.ge.y + gr * (d1 - q.ge.y * rd);
+          f.z -= G * q.ge.z + gr * (d2 - q.ge.z * rd);
+        });
+  }
+  red[threadIdx.x] = f;
+  __syncthreads();
+  if (t.active && t.cq == 0) {
+    float3 s = make_float3(0.f, 0.f, 0.f);
+    for (int k = 0; k < CQ; ++k) {
+      float3 x = red[threadIdx.x + k];
+      s.x += x.x; s.y += x.y; s.z += x.z;
+    }
+    gp[3 * t.row] += s.x;
+    gp[3 * t.row + 1] += s.y;
+    gp[3 * t.row + 2] += s.z;
+  }
 }
 
 // The update MLP's matrices V1 (which = 0) / V2 (which = 1) of layer l: dense, or merged per
@@ -486,6 +568,8 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   }
   const int rpb = 256 / (C / 4);
+  const bool want_gp = ctx->d_grad_pos != nullptr;
+  if (want_gp) hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 0.f, 3 * N);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
@@ -498,6 +582,23 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
+    }
+    if (want_gp && E > 0) {
+      // dL/dx (optional, off the timed path): the edge MLP's output with its first and second r-derivative
+      // (second-derivative rows chained through the hidden levels), then this layer's share per atom
+      const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
+      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2[0], H, E});
+      const float* u2last = w->U2[0];
+      if (d == 3) {
+        gemm_nt<P>(ctx, LdJetSecond{w->U[0][l], w->U2[0], H}, th + lo.W[1], E, H, H, EpiStore{w->U2[1], H, E});
+        u2last = w->U2[1];
+      }
+      const float* ul = w->U[d - 2][l];
+      gemm_nt<P>(ctx, Act<P>::jet(ul, w->SJ[d - 2][l], H), th + lo.W[d - 1], 2 * E, C, H, EpiStore{w->Wj, C, 2 * E});
+      gemm_nt<P>(ctx, LdJetSecond{ul, u2last, H}, th + lo.W[d - 1], E, C, H, EpiStore{w->Wpp, C, E});
+      const float kk = 3.14159265358979323846f / cf.cutoff;
+      hipLaunchKernelGGL(k_msg_gp, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Wj, w->Wpp,
+                         w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, kk * kk, (int)N, C, w->gp_acc);
     }
     if (E > 0) {
       const float* ulast = w->U[d - 2][l];
@@ -529,6 +630,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     }
     cur ^= 1;
   }
+  if (want_gp) hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 1.f, 3 * N, ctx->d_grad_pos);
   if (stage)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(lam_in, w->lam_h[cur], sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   else {
@@ -587,6 +689,13 @@ int inv_alloc(mlip_ctx* ctx) {
   w->lam_h[0] = A(N * C); w->lam_h[1] = A(N * C); w->lam_q = A(N * C); w->lam_a = A(N * C);
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
+  if (cf.position_grad) {
+    w->U2[0] = A(E * H);
+    if (d == 3) w->U2[1] = A(E * H);
+    w->Wj = A(2 * E * C);
+    w->Wpp = A(E * C);
+    w->gp_acc = A(3 * N);
+  }
   // split-k partial sums: the largest weight matrix times its split count
   int64_t cap = 0;
   auto need = [&](int64_t rows, int cols, int64_t R) {

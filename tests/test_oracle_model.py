@@ -385,3 +385,59 @@ def test_streamed_energy_equals_plain_energy(which):
     dE0 = O.energy_only(cfg, pos, inp.species, inp.struct_ptr, inp.cell, inp.params, g) - E0
     dE1 = O.energy_streamed(cfg, pos, inp.species, inp.struct_ptr, inp.cell, inp.params, g, edge_chunk=13) - E0
     assert np.allclose(dE1, dE0, rtol=1e-9, atol=1e-14) and np.abs(dE0).max() > 0
+
+
+# ------------------------------------------------------------------------------ dL/dx
+
+@pytest.mark.parametrize("which,box", [("invariant", 7.2), ("equivariant", 7.2), ("invariant3", 7.2), ("equivariant", 4.6)])
+def test_loss_position_gradient_by_finite_differences(which, box):
+    """dL/dx against central differences of the loss in every coordinate (the loss is evaluated with the
+    oracle's forces, which test_forces pins), and its closed relation to the Hessian-vector product:
+    dL/dx = -Ebar F - d/d(eps) F(x + eps v) with v = -dL/dF."""
+    w = tiny(which, atoms_per_struct=6, box=box)
+    inp = synth.make_inputs(w)
+    cfg = O.cfg_from_workload(w)
+    graph = O.radius_graph(inp.pos, inp.struct_ptr, inp.cell, w.cutoff)
+    r = O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref, graph, grad_pos=True)
+    pos = inp.pos.astype(np.float64)
+
+    def at(x):
+        return O.train_step(cfg, x, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref, graph)
+
+    h = 1e-5
+    fd = np.zeros_like(pos)
+    for i in range(pos.shape[0]):
+        for a in range(3):
+            p = pos.copy(); p[i, a] += h
+            m = pos.copy(); m[i, a] -= h
+            fd[i, a] = (at(p)["loss"] - at(m)["loss"]) / (2 * h)
+    assert np.linalg.norm(r["grad_pos"] - fd) / np.linalg.norm(fd) < 1e-6
+    # zero net derivative per structure: the loss is invariant under a translation of a whole structure
+    n = w.atoms_per_struct
+    for s in range(w.n_structs):
+        assert np.abs(r["grad_pos"][s * n:(s + 1) * n].sum(0)).max() < 1e-12 * max(1.0, np.abs(r["grad_pos"]).max())
+    # Hessian-vector form
+    Ebar = 2.0 * (r["E"] - inp.E_ref.astype(np.float64)) / w.n_structs
+    v = -2.0 * w.force_weight * (r["F"] - inp.F_ref.astype(np.float64)) / (3 * w.n_atoms)
+    eps = 1e-5
+    dF = (at(pos + eps * v)["F"] - at(pos - eps * v)["F"]) / (2 * eps)
+    sid = np.repeat(np.arange(w.n_structs), n)
+    assert np.allclose(r["grad_pos"], -Ebar[sid, None] * r["F"] - dF, rtol=1e-6, atol=1e-9 * np.abs(r["grad_pos"]).max())
+
+
+def test_stage_position_gradient_by_finite_differences():
+    w, inp = _stage_inputs(atoms_per_struct=5)
+    cfg = O.cfg_from_workload(w)
+    g = O.radius_graph(inp.pos, inp.struct_ptr, inp.cell, w.cutoff)
+    st = {k: v.astype(np.float64) for k, v in inp.stage.items()}
+    out = O.stage_step(cfg, inp.pos, inp.struct_ptr, inp.cell, inp.params, st["h_in"], st["g_out"], st["hdot_in"], st["v"],
+                       st["lam_out"], g, grad_pos=True)
+    pos = inp.pos.astype(np.float64)
+    phi = lambda x: O.stage_phi(cfg, x, inp.struct_ptr, inp.cell, inp.params, st["h_in"], st["g_out"], st["hdot_in"], st["v"], st["lam_out"], g)
+    h = 1e-5
+    fd = np.zeros_like(pos)
+    for idx in np.ndindex(*pos.shape):
+        p = pos.copy(); p[idx] += h
+        m = pos.copy(); m[idx] -= h
+        fd[idx] = (phi(p) - phi(m)) / (2 * h)
+    assert np.linalg.norm(out["grad_pos"] - fd) / np.linalg.norm(fd) < 1e-6
