@@ -92,7 +92,6 @@ const char* check_config(const mlip_config& c) {
   if (c.gate != 0 && c.gate != 1) return "gate must be 0 or 1";
   if (c.filter_fp32 != 0 && c.filter_fp32 != 1) return "filter_fp32 must be 0 or 1";
   if (c.position_grad != 0 && c.position_grad != 1) return "position_grad must be 0 or 1";
-  if (c.position_grad == 1 && c.n_experts > 0) return "the position gradient is not built for expert banks";
   if (c.gate == 1 && c.model_kind != MLIP_MODEL_EQUIVARIANT) return "the gated update belongs to the equivariant model";
   if (!(c.cutoff > 0.f)) return "cutoff must be positive";
   if (c.max_atoms < 1 || c.max_structs < 1 || c.max_edges < 1) return "capacities must be positive";

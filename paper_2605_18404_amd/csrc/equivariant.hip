@@ -56,6 +56,11 @@ struct EqvWs {
   float* Facc = nullptr;
   float* v = nullptr;
   float* Ebar = nullptr;
+  // optional position gradient dL/dx (mlip_config.position_grad)
+  float* U2 = nullptr;      // [E][H] second-derivative row of the hidden level
+  float* Rj = nullptr;      // [E][2][C][12] radial weights R and dR/dr (before the envelope), fp32
+  float* Rpp = nullptr;     // [E][C][12] d2R/dr2
+  float* gp_acc = nullptr;  // [N,3]
 };
 inline EqvWs* ws_of(mlip_ctx* ctx) { return (EqvWs*)ctx->model_ws; }
 
@@ -446,6 +451,155 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
   for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
 }
 
+
+// ------------------------------------------------------------------------------ position gradient (optional)
+// d/dr_vec of F(r_vec) = sum_m nu[m] Y_m(r_vec / |r_vec|), differentiated once more along d:
+// with u = r_vec / r, Q(u) = sum_m nu[m] P_m(u) the harmonics' polynomials, g = grad Q(u), H = Hessian of Q
+// (constant for l <= 2), Pi = I - u u^T, delta = Pi d / r:
+//   grad F = Pi g / r,    D_d grad F = [H delta - delta (u.g) - u (delta.g + u.H delta)] / r - Pi g (u.d) / r^2.
+__device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, float r, const float (&nu)[9], float3 d) {
+  const float s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+  const float3 g = sph_grad_T(x, y, z, nu);
+  const float inv = r > 0.f ? 1.f / r : 0.f;
+  const float ud = x * d.x + y * d.y + z * d.z;
+  const float3 dl = make_float3((d.x - x * ud) * inv, (d.y - y * ud) * inv, (d.z - z * ud) * inv);
+  // H: xx = s15 nu8, yy = -s15 nu8, zz = 3 s5 nu6, xy = s15 nu4, yz = s15 nu5, xz = s15 nu7
+  const float hxx = s15 * nu[8], hyy = -s15 * nu[8], hzz = 3.f * s5 * nu[6], hxy = s15 * nu[4], hyz = s15 * nu[5], hxz = s15 * nu[7];
+  const float3 hd = make_float3(hxx * dl.x + hxy * dl.y + hxz * dl.z, hxy * dl.x + hyy * dl.y + hyz * dl.z, hxz * dl.x + hyz * dl.y + hzz * dl.z);
+  const float ug = x * g.x + y * g.y + z * g.z;
+  const float dg = dl.x * g.x + dl.y * g.y + dl.z * g.z;
+  const float uh = x * hd.x + y * hd.y + z * hd.z;
+  const float k = ud * inv * inv;
+  float3 o;
+  o.x = (hd.x - dl.x * ug - x * (dg + uh)) * inv - (g.x - x * ug) * k;
+  o.y = (hd.y - dl.y * ug - y * (dg + uh)) * inv - (g.y - y * ug) * k;
+  o.z = (hd.z - dl.z * ug - z * (dg + uh)) * inv - (g.z - z * ug) * k;
+  return o;
+}
+
+// One layer's share of dPsi/dx, Psi = sum_s Ebar_s E_s + D_v E.  An edge's geometry enters through rho(r) = f_c R(r),
+// rhodot = rdot rho'(r) with rdot = u.(v_j - v_i), Y(u) and Ydot = (dY/dr_vec)(v_j - v_i):
+//   dPsi/dr_vec = [lam_rho.rho' + rdot lam_rhodot.rho''] u + (lam_rhodot.rho') (dv - u rdot)/r + J^T lam_Y + K^T lam_Ydot,
+//   lam_rho = t(h_j, Y; lam_a,i) + t(hdot_j, Y; mu_a,i) + t(h_j, Ydot; mu_a,i),   lam_rhodot = t(h_j, Y; mu_a,i),
+//   lam_Y = B_y^T(rho, h_j; lam_a,i) + B_y^T(rdot rho', h_j; mu_a,i) + B_y^T(rho, hdot_j; mu_a,i),  lam_Ydot = B_y^T(rho, h_j; mu_a,i),
+//   J = dY/dr_vec, K = d(Ydot)/dr_vec (second derivatives of the harmonics, sph_hess_apply).
+// Atom i takes -dPsi/dr_vec of the edges it receives and +dPsi/dr_vec of those it sends; the opposite edge (same r, rdot;
+// u, dv negated; Y -> PY) is formed here too, from the row's own node values and the gathered sender's.
+// One thread per (receiver row, channel), straight-line couplings; off the timed path.
+__global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                               const float4* __restrict__ geo, const float2* __restrict__ env,
+                                               const float* __restrict__ Rj, const float* __restrict__ Rpp,
+                                               const float* __restrict__ h, const float* __restrict__ hd,
+                                               const float* __restrict__ mu_a, const float* __restrict__ lam_a,
+                                               const float* __restrict__ v, float k2, int N, int C, float* __restrict__ gp) {
+  __shared__ float3 red[256];
+  RowChan t = row_chan(N, C);
+  float3 f = make_float3(0.f, 0.f, 0.f);
+  if (t.active) {
+    const int64_t NC = (int64_t)N * C;
+    const int64_t io = (int64_t)t.row * C + t.c;
+    float xi[9], xdi[9], li[9], mi[9];
+    load9(h, NC, io, xi);
+    load9(hd, NC, io, xdi);
+    load9(lam_a, NC, io, li);
+    load9(mu_a, NC, io, mi);
+    const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
+    for (int e = row_ptr[t.row]; e < row_ptr[t.row + 1]; ++e) {
+      const int j = sender[e];
+      const float4 g = geo[e];
+      const float2 cc = env[e];
+      const float3 d = make_float3(v[3 * j] - vi0, v[3 * j + 1] - vi1, v[3 * j + 2] - vi2);
+      const float rd = g.x * d.x + g.y * d.y + g.z * d.z;
+      float xj[9], xdj[9], lj[9], mj[9], R[NPATH], Rp[NPATH], Rq[NPATH];
+      const int64_t jo = (int64_t)j * C + t.c;
+      load9(h, NC, jo, xj);
+      load9(hd, NC, jo, xdj);
+      load9(lam_a, NC, jo, lj);
+      load9(mu_a, NC, jo, mj);
+      load_rho(Rj + (int64_t)(2 * e) * NPP * C, t.c, R);
+      load_rho(Rj + (int64_t)(2 * e + 1) * NPP * C, t.c, Rp);
+      load_rho(Rpp + (int64_t)e * NPP * C, t.c, Rq);
+      const float c = cc.x, cp = cc.y, cq = -k2 * (c - 0.5f);
+      float rho[NPATH], rr[NPATH], r1[NPATH], r2[NPATH];  // rho, rdot rho', rho', rho''
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) {
+        rho[p] = c * R[p];
+        r1[p] = cp * R[p] + c * Rp[p];
+        r2[p] = cq * R[p] + 2.f * cp * Rp[p] + c * Rq[p];
+        rr[p] = rd * r1[p];
+      }
+      float Y[9], Yd[9], PY[9], PYd[9];
+      sph_harm(g.x, g.y, g.z, Y);
+      sph_dot(g.x, g.y, g.z, g.w, d, Yd);
+      parity(Y, PY);
+      parity(Yd, PYd);
+      float lr[NPATH], lrd[NPATH], tmp[NPATH];
+      gaunt::tp_paths(xj, Y, li, lr);
+      gaunt::tp_paths(xdj, Y, mi, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
+      gaunt::tp_paths(xj, Yd, mi, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
+      gaunt::tp_paths(xj, Y, mi, lrd);
+      // the opposite edge: own features, the sender's adjoints, harmonics of -u
+      gaunt::tp_paths(xi, PY, lj, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
+      gaunt::tp_paths(xdi, PY, mj, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
+      gaunt::tp_paths(xi, PYd, mj, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
+      gaunt::tp_paths(xi, PY, mj, tmp);
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) lrd[p] += tmp[p];
+      float rad = 0.f, gg = 0.f;
+#pragma unroll
+      for (int p = 0; p < NPATH; ++p) {
+        rad += lr[p] * r1[p] + lrd[p] * rd * r2[p];
+        gg += lrd[p] * r1[p];
+      }
+      float LY[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, LYd[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      float QY[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, QYd[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      gaunt::tp_adj_y(rho, xj, li, LY);
+      gaunt::tp_adj_y(rr, xj, mi, LY);
+      gaunt::tp_adj_y(rho, xdj, mi, LY);
+      gaunt::tp_adj_y(rho, xj, mi, LYd);
+      gaunt::tp_adj_y(rho, xi, lj, QY);
+      gaunt::tp_adj_y(rr, xi, mj, QY);
+      gaunt::tp_adj_y(rho, xdi, mj, QY);
+      gaunt::tp_adj_y(rho, xi, mj, QYd);
+#pragma unroll
+      for (int m = 0; m < 9; ++m) {
+        const float sg = (m >= 1 && m <= 3) ? -1.f : 1.f;
+        LY[m] += sg * QY[m];
+        LYd[m] += sg * QYd[m];
+      }
+      const float inv = g.w > 0.f ? 1.f / g.w : 0.f;
+      const float3 w = sph_grad_T(g.x, g.y, g.z, LY);
+      const float uw = g.x * w.x + g.y * w.y + g.z * w.z;
+      const float3 hs = sph_hess_apply(g.x, g.y, g.z, g.w, LYd, d);
+      f.x -= rad * g.x + gg * (d.x - g.x * rd) * inv + (w.x - g.x * uw) * inv + hs.x;
+      f.y -= rad * g.y + gg * (d.y - g.y * rd) * inv + (w.y - g.y * uw) * inv + hs.y;
+      f.z -= rad * g.z + gg * (d.z - g.z * rd) * inv + (w.z - g.z * uw) * inv + hs.z;
+    }
+  }
+  red[threadIdx.x] = f;
+  __syncthreads();
+  if (t.active && t.c == 0) {
+    float3 s = make_float3(0.f, 0.f, 0.f);
+    for (int k = 0; k < C; ++k) {
+      float3 x = red[threadIdx.x + k];
+      s.x += x.x; s.y += x.y; s.z += x.z;
+    }
+    gp[3 * t.row] += s.x;
+    gp[3 * t.row + 1] += s.y;
+    gp[3 * t.row + 2] += s.z;
+  }
+}
+
 // Per-edge tables of coupling coefficient x harmonic: cy[e][n] = T_n Y_{m2_n}(u_e), and, with
 // WITH_DOT, cyd[e][n] = T_n Ydot_{m2_n} for the displacement rate v_sender - v_receiver,
 // followed (entry NNZ) by the rate of change of the edge length, u . (v_sender - v_receiver).
@@ -789,6 +943,8 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
+  const bool want_gp = ctx->d_grad_pos != nullptr;
+  if (want_gp) hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 0.f, 3 * N);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     float* lh_next = w->lam_h[cur];
@@ -809,6 +965,16 @@ int be_impl(mlip_ctx* ctx, float* grad) {
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
+    if (want_gp && E > 0) {
+      // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share
+      const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
+      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2, H, E});
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiStore{w->Rj, PC, 2 * E});
+      gemm_nt<P>(ctx, LdJetSecond{w->U[l], w->U2, H}, w->Wp[l], E, PC, H, EpiStore{w->Rpp, PC, E});
+      const float kk = 3.14159265358979323846f / cf.cutoff;
+      hipLaunchKernelGGL(k_tp_gp, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Rj, w->Rpp,
+                         w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, kk * kk, (int)N, C, w->gp_acc);
+    }
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
@@ -824,6 +990,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     cur ^= 1;
   }
+  if (want_gp) hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 1.f, 3 * N, ctx->d_grad_pos);
   {
     const int chunks = atom_chunks(N), len = (int)((N + chunks - 1) / chunks), S = cf.n_species;
     hipLaunchKernelGGL(k_emb_grad, dim3((C + 63) / 64, chunks, S), dim3(256), 0, st, w->lam_h[cur], ctx->d_species, (int)N, C, S, len, ctx->partial.buf);
@@ -841,7 +1008,6 @@ int eqv_alloc(mlip_ctx* ctx) {
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
-  if (cf.position_grad) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: the position gradient is built for the invariant model and the pipeline stage only");
   EqvWs* w = new EqvWs();
   ctx->model_ws = w;
   bool ok = true;
@@ -881,6 +1047,12 @@ int eqv_alloc(mlip_ctx* ctx) {
   if (cf.gate) w->lam_u = A(NC9);
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
+  if (cf.position_grad) {
+    w->U2 = A(E * H);
+    w->Rj = A(2 * E * PC);
+    w->Rpp = A(E * PC);
+    w->gp_acc = A(3 * N);
+  }
   int64_t cap = 0;
   auto need = [&](int64_t rows, int cols, int64_t R) {
     const bool narrow = cols <= 32;

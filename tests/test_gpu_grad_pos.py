@@ -25,7 +25,7 @@ def _oracle_batch(w, inp):
         sub = dict(cfg)
         sub["force_weight"] = cfg["force_weight"] * ((b - a) / N) * B
         r = O.train_step(sub, inp.pos[a:b], inp.species[a:b], np.array([0, b - a], np.int32), inp.cell[s:s + 1], inp.params,
-                         inp.E_ref[s:s + 1], inp.F_ref[a:b], grad_pos=True)
+                         inp.E_ref[s:s + 1], inp.F_ref[a:b], grad_pos=True, alpha=None if inp.alpha is None else inp.alpha[s:s + 1])
         gp[a:b] = r["grad_pos"] / B
         grad += r["grad"] / B
     return gp, grad
@@ -44,6 +44,20 @@ def whole_cases():
         "cfg1_2structs_molecules": (synth.shrink(W[1], n_structs=2, cell_kind="free"), TOL_FP32),
         "cfg1_2structs_bf16": (synth.shrink(W[1], n_structs=2, gemm_bf16=True), TOL_BF16),
         "cfg1_depth3_small_bf16": (synth.shrink(W[1], edge_depth=3, channels=64, edge_hidden=96, gemm_bf16=True, **small), TOL_BF16),
+        "cfg0_5experts": (synth.shrink(W[0], n_structs=3, atoms_per_struct=40, box=10.0, n_experts=5), TOL_FP32),
+        # equivariant model: also the second derivatives of the harmonics
+        "eqv_tiny_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8, edge_hidden=8, n_rbf=8,
+                                       n_layers=2, gemm_bf16=False), TOL_FP32),
+        "eqv_multi_image_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12, edge_hidden=16,
+                                              n_rbf=8, n_layers=3, gemm_bf16=False), TOL_FP32),
+        "eqv_multi_image_triclinic_gate_fp32": (synth.shrink(W[2], n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                                             edge_hidden=16, n_rbf=8, n_layers=3, gemm_bf16=False, cell_kind="triclinic",
+                                                             gate=1), TOL_FP32),
+        "eqv_channels_96_bf16": (synth.shrink(W[2], channels=96, edge_hidden=40, n_rbf=8, atoms_per_struct=14, n_structs=2, box=6.0,
+                                              cutoff=3.2, n_layers=2), TOL_BF16),
+        "cfg2_1struct_fp32": (synth.shrink(W[2], n_structs=1, gemm_bf16=False), TOL_FP32),
+        "cfg2_1struct_bf16": (synth.shrink(W[2], n_structs=1), TOL_BF16),
+        "cfg4_shape_300atoms_bf16": (synth.shrink(W[4], atoms_per_struct=300, box=(300 / 0.1) ** (1 / 3), n_layers=2), TOL_BF16),
     }
 
 
@@ -54,6 +68,8 @@ def test_position_gradient_parity(name):
     gp_ref, grad_ref = _oracle_batch(w, inp)
     m = Mlip.for_workload(w, position_grad=1)
     d = DevInputs(inp)
+    if w.n_experts > 0:
+        m.mlip_set_expert_weights(d.alpha)
     gp = torch.full((w.n_atoms, 3), float("nan"), device=DEV)
     m.mlip_set_position_grad(gp)
     out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
