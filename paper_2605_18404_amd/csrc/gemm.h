@@ -446,4 +446,122 @@ inline int launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int6
   return launch_bk<P, TM, TN, WM, WN, KC, P::BK_BIG>(st, a, b, e, M, N, K, splits, grp);
 }
 
+// ---- row-stripe variant for short reductions (bf16, k-contiguous operands, K <= KMAX) -----------------
+// D(m, n) = sum_k A(m, k) B(n, k) with a reduction so short (the edge MLP's hidden width) that the k loop of
+// the tiled kernel is a handful of iterations and each output tile re-reads its A rows: there the matrix
+// cores wait for operands from the L2.  Here a workgroup owns a stripe of 128 rows: the stripe's A operand
+// (all of K) is staged into LDS once, and the workgroup then walks the column tiles -- per column tile it
+// stages only the B tile (prefetched into registers during the previous tile's products), so the L2 traffic
+// per product halves and the stores of one column tile overlap the products of the next.
+// Both loaders must be raw-bf16 loaders of width 8; N a multiple of 128; K a multiple of 8.
+template <int KMAX, typename LdA, typename LdB, typename Epi>
+__global__ void __launch_bounds__(256, 2)
+k_gemm_stripe(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int K) {
+  static_assert(LdA::WIDTH == 8 && LdB::WIDTH == 8, "raw bf16 operands");
+  constexpr int LD = KMAX + 8;              // row pitch in bf16: 16-byte fragment reads of 8 lanes fall into distinct banks
+  constexpr int ELD = 64 + 4;               // a wave's output slab: 32 rows x 64 columns, padded
+  constexpr int B_BYTES = 128 * LD * 2, SLAB_BYTES = 4 * 32 * ELD * 4;
+  __shared__ __attribute__((aligned(16))) __bf16 sA[128 * LD];
+  __shared__ __attribute__((aligned(16))) char sBraw[B_BYTES > SLAB_BYTES ? B_BYTES : SLAB_BYTES];  // B tile, then the slabs
+  __bf16* sB = reinterpret_cast<__bf16*>(sBraw);
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int li = lane & 31, g = lane >> 5;
+  const int64_t m0 = (int64_t)blockIdx.x * 128;
+  const int Q = K / 8;                      // 16-byte items per row
+  const int items = 128 * Q;                // per operand tile (<= 2048: at most 8 per thread)
+  constexpr int NV = 128 * (KMAX / 8) / 256;
+  // A stripe: rows beyond M are clamped (their outputs are never stored)
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int idx = t + it * 256;
+    if (idx < items) {
+      const int r = idx / Q, q = idx % Q;
+      int64_t row = m0 + r;
+      row = row < M ? row : M - 1;
+      *reinterpret_cast<bf16x8*>(&sA[r * LD + 8 * q]) = lda.finish(lda.fetch(row, 8 * q));
+    }
+  }
+  typename LdB::Raw vb[NV];
+  auto fetch_b = [&](int n0) {
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = t + it * 256;
+      if (idx < items) vb[it] = ldb.fetch(n0 + idx / Q, 8 * (idx % Q));
+    }
+  };
+  const int tiles_n = N / 128;
+  fetch_b(0);
+  float* eb = reinterpret_cast<float*>(sBraw) + wave * (32 * ELD);
+  constexpr int LPR = 16, PPP = 4;          // lanes across a slab's 64 columns, row pairs per pass
+  const int ecol = 4 * (lane % LPR), epair = lane / LPR;
+  for (int jt = 0; jt < tiles_n; ++jt) {
+    const int n0 = jt * 128;
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int idx = t + it * 256;
+      if (idx < items) *reinterpret_cast<bf16x8*>(&sB[(idx / Q) * LD + 8 * (idx % Q)]) = ldb.finish(vb[it]);
+    }
+    __syncthreads();
+    if (jt + 1 < tiles_n) fetch_b(n0 + 128);  // in flight during this tile's products and stores
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+    for (int kk = 0; kk < K / 16; ++kk) {
+      bf16x8 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const bf16x8*>(&sA[((wm * 2 + i) * 32 + li) * LD + 16 * kk + 8 * g]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(&sB[((wn * 2 + j) * 32 + li) * LD + 16 * kk + 8 * g]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    if (K % 16) {  // a last half step of eight k: the upper half of the fragments is zero
+      const int kk = K / 16;
+      bf16x8 af[2], bf[2];
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < 2; ++i) af[i] = g ? zero : *reinterpret_cast<const bf16x8*>(&sA[((wm * 2 + i) * 32 + li) * LD + 16 * kk]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bf[j] = g ? zero : *reinterpret_cast<const bf16x8*>(&sB[((wn * 2 + j) * 32 + li) * LD + 16 * kk]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();  // every wave has read its B fragments: the B region now serves as the output slabs
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) eb[(8 * (q / 4) + 4 * g + q % 4) * ELD + j * 32 + li] = acc[i][j][q];
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int ps = 0; ps < 16 / PPP; ++ps) {
+        const int rl = 2 * (ps * PPP + epair);
+        const float4 a = *reinterpret_cast<const float4*>(&eb[rl * ELD + ecol]);
+        const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
+        const int64_t row = m0 + (wm * 2 + i) * 32 + rl;
+        const int col = n0 + wn * 64 + ecol;
+        if (row < M) epi(row, col, a, b, 0);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();  // slabs read back before the next B tile is written over them
+  }
+}
+
+template <int KMAX, typename LdA, typename LdB, typename Epi>
+inline void launch_stripe(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int K) {
+  if (M <= 0) return;
+  hipLaunchKernelGGL((k_gemm_stripe<KMAX, LdA, LdB, Epi>), dim3((unsigned)((M + 127) / 128)), dim3(256), 0, st, a, b, e, M, N, K);
+}
+
 }  // namespace gemm
