@@ -275,22 +275,28 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
         for (int sl = 0; sl < NSLOT; ++sl) R[sl] = gaunt::PATH_SIGN[gaunt::SLOT_P[sl]] * rho[gaunt::SLOT_P[sl]] * mj[gaunt::SLOT_M3[sl]];
         adj_x_from(cy, R, acc);
       }
-      float s = 0.f;
-      {  // radial part of the force: rho' (t(x_j, Y, mu_i) + t(x_i, PY, mu_j))
-        float S1[NSLOT], S2[NSLOT];
-        contract_x<false>(cy, xj, S1);
-        contract_x<false>(cy, xi, S2);
+      // Force terms.  With W_n = x_j[m1] mu_i[m3] + sign_p x_i[m1] mu_j[m3] per coupling entry n = (p; m1, m2, m3), formed
+      // once, both directions of the edge pair give
+      //   radial:  s = sum_p rho'_p sum_{n in p} (T_n Y[m2]) W_n,      angular:  nu[m2] = sum_p rho_p sum_{n in (p, m2)} T_n W_n
+      // (the opposite edge sees the harmonics of -u, i.e. the path's parity sign).
+      float sp[NPATH], G[gaunt::NYSLOT];
 #pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl) {
-          const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
-          s = fmaf(rhop[p], fmaf(gaunt::PATH_SIGN[p] * mj[m3], S2[sl], mi[m3] * S1[sl]), s);
-        }
+      for (int n = 0; n < NNZ; ++n) {
+        const int sl = gaunt::ENT_SLOT[n], p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl], m1 = gaunt::ENT_M1[n], ys = gaunt::ENT_YSLOT[n];
+        const float W = fmaf(gaunt::PATH_SIGN[p] * xi[m1], mj[m3], xj[m1] * mi[m3]);
+        const bool first_p = n == 0 || gaunt::SLOT_P[gaunt::ENT_SLOT[n > 0 ? n - 1 : 0]] != p;
+        sp[p] = first_p ? cy[n] * W : fmaf(cy[n], W, sp[p]);
+        bool first_y = true;
+#pragma unroll
+        for (int q = 0; q < n; ++q) first_y = first_y && gaunt::ENT_YSLOT[q] != ys;
+        G[ys] = first_y ? gaunt::ENT_COEF[n] * W : fmaf(gaunt::ENT_COEF[n], W, G[ys]);
       }
-      float nu[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, nu2[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      gaunt::tp_adj_y(rho, xj, mi, nu);
-      gaunt::tp_adj_y(rho, xi, mj, nu2);
+      float s = 0.f;
 #pragma unroll
-      for (int m = 0; m < 9; ++m) nu[m] += (m >= 1 && m <= 3) ? -nu2[m] : nu2[m];
+      for (int p = 0; p < NPATH; ++p) s = fmaf(rhop[p], sp[p], s);
+      float nu[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ys = 0; ys < gaunt::NYSLOT; ++ys) nu[gaunt::YSLOT_M2[ys]] = fmaf(rho[gaunt::YSLOT_P[ys]], G[ys], nu[gaunt::YSLOT_M2[ys]]);
       float3 w = sph_grad_T(g.x, g.y, g.z, nu);
       float uw = g.x * w.x + g.y * w.y + g.z * w.z;
       float inv = 1.f / g.w;
@@ -375,6 +381,9 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
   for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
 }
 
+// (Writing the adjoint of the OPPOSITE edge instead -- X[rev(e)] from this row's own features and the sender's adjoints,
+// which halves the gathers and pays off in the invariant model's kernel -- was measured slower here: the rows of X are then
+// written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.)
 template <typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,

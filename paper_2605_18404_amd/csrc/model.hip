@@ -214,9 +214,14 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
   *reinterpret_cast<float4*>(ad + ro) = acc;
 }
 
-struct InBe { float4 w, wp, hj, hdj, laj, maj, ge; float2 cc; float v0, v1, v2; };
+// BE gathers only the sender's adjoints lam_a[j], mu_a[j] (its own lam_h needs them).  The edge-MLP adjoint it writes is
+// that of the OPPOSITE edge (j <- i): X[rev(e)] = c (h_i lam_a,j + hdot_i mu_a,j) + c' rdot h_i mu_a,j needs this row's
+// own features and the same two gathered tables; r, rdot and the envelope are equal on opposite edges.  Every edge is
+// some edge's opposite, so each X row is written exactly once, and half the gathers are gone.
+struct InBe { float4 w, wp, laj, maj, ge; float2 cc; float v0, v1, v2; int er; };
 template <typename TX, typename TF>
 __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+                                                const int32_t* __restrict__ rev,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
@@ -227,7 +232,7 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
   if (!t.active) return;
   const int c0 = 4 * t.cq;
   const int64_t ro = (int64_t)t.row * C + c0;
-  const float4 mai = ld4(mu_a + ro), lai = ld4(lam_a + ro);
+  const float4 hi = ld4(h + ro), hdi = ld4(hd + ro);
   float4 acc = ld4(lam_h_next + ro);
   const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
   walk_row<2, InBe>(
@@ -237,23 +242,24 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
         x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
         x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
         const int64_t jo = (int64_t)j * C + c0;
-        x.hj = ld4(h + jo); x.hdj = ld4(hd + jo); x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
+        x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
         x.ge = geo[e];
         x.cc = env[e];
         x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+        x.er = rev[e];
         return x;
       },
-      [&](int e, const InBe& c) {
+      [&](int, const InBe& c) {
         const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
         fma4(acc, c.w, c.laj);
         fma4s(acc, rd, c.wp, c.maj);
         const float s = c.cc.y * rd;
         float4 x;
-        x.x = c.cc.x * (c.hj.x * lai.x + c.hdj.x * mai.x) + s * c.hj.x * mai.x;
-        x.y = c.cc.x * (c.hj.y * lai.y + c.hdj.y * mai.y) + s * c.hj.y * mai.y;
-        x.z = c.cc.x * (c.hj.z * lai.z + c.hdj.z * mai.z) + s * c.hj.z * mai.z;
-        x.w = c.cc.x * (c.hj.w * lai.w + c.hdj.w * mai.w) + s * c.hj.w * mai.w;
-        st4(X + (int64_t)e * C + c0, x);
+        x.x = c.cc.x * (hi.x * c.laj.x + hdi.x * c.maj.x) + s * hi.x * c.maj.x;
+        x.y = c.cc.x * (hi.y * c.laj.y + hdi.y * c.maj.y) + s * hi.y * c.maj.y;
+        x.z = c.cc.x * (hi.z * c.laj.z + hdi.z * c.maj.z) + s * hi.z * c.maj.z;
+        x.w = c.cc.x * (hi.w * c.laj.w + hdi.w * c.maj.w) + s * hi.w * c.maj.w;
+        if (c.er >= 0) st4(X + (int64_t)c.er * C + c0, x);
       });
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
 }
@@ -580,7 +586,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     node_mm<P>(ctx, l, 0, true, LdPlain{w->lam_q, C}, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_rev, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
     if (want_gp && E > 0) {
