@@ -180,6 +180,47 @@ def test_cfg4_full_size_graph_rows_and_net_force():
     m.close()
 
 
+def test_cfg4_full_size_against_stored_oracle_values():
+    """The seeded 20,000-atom cell itself (not a stand-in): energy, directional derivatives of the energy in the
+    positions (= -F . d) and directional derivatives in the parameters of Psi = Ebar E + D_v E for seeded cotangents
+    (= what BF + BE return for those cotangents, projected), against values the oracle's streamed float64 energy
+    gives by central differences (tests/golden/make_full_size_goldens.py).  A projection of an error vector e on a
+    seeded +-1/sqrt(n) direction is distributed with variance |e|^2 / n, so |e| <= tol |x| is checked as
+    |projection error| <= 4 tol |x| / sqrt(n) -- on the whole vector and on a 64-atom / one-tensor subset."""
+    import make_full_size_goldens as G
+    gold = _golden("full_size_cfg4.json")
+    w = synth.WORKLOADS[4]
+    inp = synth.make_inputs(w)
+    m = Mlip.for_workload(w)
+    d = DevInputs(inp)
+    assert m.mlip_graph_build(d.pos, d.struct_ptr, d.cell, w.cutoff) == gold["n_edges"]
+    E = m.mlip_forward_energy(d.pos, d.species, d.params)
+    F = m.mlip_forward_force()
+    torch.cuda.synchronize()
+    assert abs(float(E.cpu()[0]) - gold["E"]) < TOL_BF16 * abs(gold["E"])
+    Fh = F.cpu().numpy().astype(np.float64)
+    n_params = m.mlip_param_count()
+    D = G.cfg4_directions(w, n_params)
+    for k, dk in enumerate(D["d"]):
+        moved = np.abs(dk).sum(1) > 0
+        scale = np.linalg.norm(Fh[moved]) * np.linalg.norm(dk) / np.sqrt(3 * moved.sum())
+        got = -(Fh * dk).sum()
+        assert abs(got - gold["dE"][k]) < 4 * TOL_BF16 * scale, (k, got, gold["dE"][k], scale)
+    # BF + BE with the stored run's cotangents
+    g = torch.zeros(n_params, device=DEV)
+    m.mlip_backward_force(dev(D["v"].astype(np.float32)), g)
+    m.mlip_backward_energy(g, Ebar=dev(np.array([D["Ebar"]], np.float32)))
+    torch.cuda.synchronize()
+    gh = g.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(gh))
+    for k, tk in enumerate(D["t"]):
+        sel = tk != 0
+        scale = np.linalg.norm(gh[sel]) * np.linalg.norm(tk) / np.sqrt(sel.sum())
+        got = float(gh @ tk)
+        assert abs(got - gold["dPsi"][k]) < 4 * TOL_BF16 * scale, (k, got, gold["dPsi"][k], scale)
+    m.close()
+
+
 def test_cfg4_size_supercell_against_oracle():
     """A 6x6x6 periodic replica (21,600 atoms, the size of workload 4, its full model) of a
     100-atom cell the oracle can run: E = 216 E_cell, F tiles, and with E_ref' = 216 E_ref the
