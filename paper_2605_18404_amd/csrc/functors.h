@@ -264,7 +264,16 @@ struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  en
   const float2* env;
   int64_t ld, M;  // M = 2E
   __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
-    const float2 c = env[r >> 1];
+    apply(r, col, a, b, env[r >> 1]);
+  }
+  // The functor's only load depends on the row alone.  A kernel that keeps its rows while it walks the columns
+  // fetches it once, ahead of all stores: a load issued after stores cannot be waited for without waiting for
+  // those stores' acknowledgements too (one in-order counter for vector memory operations), which would put a
+  // store round trip into every pass of the epilogue.
+  typedef float2 RowIn;
+  __device__ __forceinline__ RowIn row_in(int64_t r) const { return env[r >> 1]; }
+  __device__ static __forceinline__ void row_in_arrived(const RowIn& c) { asm volatile("" ::"v"(c.x), "v"(c.y)); }
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, const RowIn& c) const {
     const int64_t o = r * ld + col;
     st4(out + o, scale4(c.x, a));
     st4(out + o + ld, add4(scale4(c.y, a), scale4(c.x, b)));

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace gemm {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -446,122 +448,166 @@ inline int launch(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int6
   return launch_bk<P, TM, TN, WM, WN, KC, P::BK_BIG>(st, a, b, e, M, N, K, splits, grp);
 }
 
-// ---- row-stripe variant for short reductions (bf16, k-contiguous operands, K <= KMAX) -----------------
+// ---- row-stripe variant for short reductions (bf16, k-contiguous operands, K = 64 or 128) ---------------
 // D(m, n) = sum_k A(m, k) B(n, k) with a reduction so short (the edge MLP's hidden width) that the k loop of
 // the tiled kernel is a handful of iterations and each output tile re-reads its A rows: there the matrix
 // cores wait for operands from the L2.  Here a workgroup owns a stripe of 128 rows: the stripe's A operand
 // (all of K) is staged into LDS once, and the workgroup then walks the column tiles -- per column tile it
 // stages only the B tile (prefetched into registers during the previous tile's products), so the L2 traffic
 // per product halves and the stores of one column tile overlap the products of the next.
-// Both loaders must be raw-bf16 loaders of width 8; N a multiple of 128; K a multiple of 8.
-template <int KMAX, typename LdA, typename LdB, typename Epi>
-__global__ void __launch_bounds__(256, 2)
-k_gemm_stripe(LdA lda, LdB ldb, Epi epi, int64_t M, int N, int K) {
-  static_assert(LdA::WIDTH == 8 && LdB::WIDTH == 8, "raw bf16 operands");
-  constexpr int LD = KMAX + 8;              // row pitch in bf16: 16-byte fragment reads of 8 lanes fall into distinct banks
-  constexpr int ELD = 64 + 4;               // a wave's output slab: 32 rows x 64 columns, padded
-  constexpr int B_BYTES = 128 * LD * 2, SLAB_BYTES = 4 * 32 * ELD * 4;
-  __shared__ __attribute__((aligned(16))) __bf16 sA[128 * LD];
-  __shared__ __attribute__((aligned(16))) char sBraw[B_BYTES > SLAB_BYTES ? B_BYTES : SLAB_BYTES];  // B tile, then the slabs
-  __bf16* sB = reinterpret_cast<__bf16*>(sBraw);
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int li = lane & 31, g = lane >> 5;
-  const int64_t m0 = (int64_t)blockIdx.x * 128;
-  const int Q = K / 8;                      // 16-byte items per row
-  const int items = 128 * Q;                // per operand tile (<= 2048: at most 8 per thread)
-  constexpr int NV = 128 * (KMAX / 8) / 256;
-  // A stripe: rows beyond M are clamped (their outputs are never stored)
-#pragma unroll
-  for (int it = 0; it < NV; ++it) {
-    const int idx = t + it * 256;
-    if (idx < items) {
-      const int r = idx / Q, q = idx % Q;
-      int64_t row = m0 + r;
-      row = row < M ? row : M - 1;
-      *reinterpret_cast<bf16x8*>(&sA[r * LD + 8 * q]) = lda.finish(lda.fetch(row, 8 * q));
-    }
-  }
-  typename LdB::Raw vb[NV];
-  auto fetch_b = [&](int n0) {
-#pragma unroll
-    for (int it = 0; it < NV; ++it) {
-      const int idx = t + it * 256;
-      if (idx < items) vb[it] = ldb.fetch(n0 + idx / Q, 8 * (idx % Q));
-    }
-  };
-  const int tiles_n = N / 128;
-  fetch_b(0);
-  float* eb = reinterpret_cast<float*>(sBraw) + wave * (32 * ELD);
-  constexpr int LPR = 16, PPP = 4;          // lanes across a slab's 64 columns, row pairs per pass
-  const int ecol = 4 * (lane % LPR), epair = lane / LPR;
-  for (int jt = 0; jt < tiles_n; ++jt) {
-    const int n0 = jt * 128;
-#pragma unroll
-    for (int it = 0; it < NV; ++it) {
-      const int idx = t + it * 256;
-      if (idx < items) *reinterpret_cast<bf16x8*>(&sB[(idx / Q) * LD + 8 * (idx % Q)]) = ldb.finish(vb[it]);
-    }
-    __syncthreads();
-    if (jt + 1 < tiles_n) fetch_b(n0 + 128);  // in flight during this tile's products and stores
-    floatx16 acc[2][2];
+// Both loaders must be raw-bf16 loaders of width 8; N a multiple of 128; K a template constant.
+//
+// Vector memory operations retire through one in-order counter, so a wait for a load also waits for every store
+// issued before it, and a wait the compiler cannot count exactly (a store under a branch, a loop header that
+// joins two paths) becomes a wait for everything.  The walk over the column tiles is therefore straight-line
+// code per tile (K and the trip counts are template constants, the ragged last stripe has a body of its own),
+// and the only wait for the prefetched B tile sits at the end of the tile, behind a fixed number of stores:
+// it covers the loads and the previous tile's stores, not this tile's.
+
+// Workgroup barrier for LDS hand-overs only: waits for this wave's LDS operations, then s_barrier
+// (__syncthreads() also fences global memory, i.e. waits for the acknowledgement of every outstanding store).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// An epilogue functor may declare row-wise inputs (type RowIn, row_in(row), apply(row, col, a, b, in)) that a kernel
+// can fetch ahead of its stores; functors without them are called as they are.
+template <typename Epi, typename = void>
+struct RowInputs {
+  struct type {};
+  __device__ static __forceinline__ type get(const Epi&, int64_t) { return type{}; }
+  __device__ static __forceinline__ void arrived(const type&) {}
+  __device__ static __forceinline__ void apply(const Epi& e, int64_t r, int col, const float4& a, const float4& b, const type&) { e(r, col, a, b, 0); }
+};
+template <typename Epi>
+struct RowInputs<Epi, std::void_t<typename Epi::RowIn>> {
+  typedef typename Epi::RowIn type;
+  __device__ static __forceinline__ type get(const Epi& e, int64_t r) { return e.row_in(r); }
+  // a use the compiler must wait for: placed ahead of a loop it keeps the wait for these loads out of the loop
+  __device__ static __forceinline__ void arrived(const type& in) { Epi::row_in_arrived(in); }
+  __device__ static __forceinline__ void apply(const Epi& e, int64_t r, int col, const float4& a, const float4& b, const type& in) { e.apply(r, col, a, b, in); }
+};
+
+template <int K, typename LdA, typename LdB, typename Epi>
+struct Stripe {
+  static constexpr int LD = K + 8;          // row pitch in bf16: 16-byte fragment reads of 16 lanes fall into distinct banks
+  static constexpr int ELD = 64 + 8;        // a wave's output slab: 32 rows x 64 columns; the pitch puts the two
+                                            // half-waves of an accumulator write (four rows apart) on disjoint banks
+  static constexpr int A_BYTES = 128 * LD * 2, B_BYTES = 128 * LD * 2, SLAB_BYTES = 4 * 32 * ELD * 4;
+  static constexpr int BS_BYTES = B_BYTES > SLAB_BYTES ? B_BYTES : SLAB_BYTES;
+  static constexpr int Q = K / 8;           // 16-byte items per row
+  static constexpr int NV = 128 * Q / 256;  // items per thread and operand tile
+  static constexpr int LPR = 16, PPP = 4;   // lanes across a slab's 64 columns, row pairs per pass
+  typedef typename RowInputs<Epi>::type RowIn;
+
+  // FULL: all 128 rows of the stripe exist (no row guards, hence no branches around the stores)
+  template <bool FULL>
+  __device__ static __forceinline__ void tiles(const LdB& ldb, const Epi& epi, int64_t M, int N, int64_t m0,
+                                              const __bf16* sA, char* sBraw) {
+    __bf16* sB = reinterpret_cast<__bf16*>(sBraw);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, g = lane >> 5;
+    float* eb = reinterpret_cast<float*>(sBraw) + wave * (32 * ELD);
+    const int ecol = 4 * (lane % LPR), epair = lane / LPR;
+    // the epilogue's row-wise inputs of the eight row pairs this lane finishes, fetched once for all column tiles
+    RowIn rin[2][16 / PPP];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-    for (int kk = 0; kk < K / 16; ++kk) {
-      bf16x8 af[2], bf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const bf16x8*>(&sA[((wm * 2 + i) * 32 + li) * LD + 16 * kk + 8 * g]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(&sB[((wn * 2 + j) * 32 + li) * LD + 16 * kk + 8 * g]);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    if (K % 16) {  // a last half step of eight k: the upper half of the fragments is zero
-      const int kk = K / 16;
-      bf16x8 af[2], bf[2];
-      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = g ? zero : *reinterpret_cast<const bf16x8*>(&sA[((wm * 2 + i) * 32 + li) * LD + 16 * kk]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = g ? zero : *reinterpret_cast<const bf16x8*>(&sB[((wn * 2 + j) * 32 + li) * LD + 16 * kk]);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();  // every wave has read its B fragments: the B region now serves as the output slabs
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) eb[(8 * (q / 4) + 4 * g + q % 4) * ELD + j * 32 + li] = acc[i][j][q];
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
       for (int ps = 0; ps < 16 / PPP; ++ps) {
-        const int rl = 2 * (ps * PPP + epair);
-        const float4 a = *reinterpret_cast<const float4*>(&eb[rl * ELD + ecol]);
-        const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
-        const int64_t row = m0 + (wm * 2 + i) * 32 + rl;
-        const int col = n0 + wn * 64 + ecol;
-        if (row < M) epi(row, col, a, b, 0);
+        const int64_t row = m0 + (wm * 2 + i) * 32 + 2 * (ps * PPP + epair);
+        rin[i][ps] = RowInputs<Epi>::get(epi, FULL || row < M ? row : M - 2);
       }
-      __builtin_amdgcn_wave_barrier();
+    typename LdB::Raw vb[NV];
+#pragma unroll
+    for (int it = 0; it < NV; ++it) vb[it] = ldb.fetch((t + it * 256) / Q, 8 * ((t + it * 256) % Q));
+#pragma unroll
+    for (int it = 0; it < NV; ++it)
+      *reinterpret_cast<bf16x8*>(&sB[((t + it * 256) / Q) * LD + 8 * ((t + it * 256) % Q)]) = ldb.finish(vb[it]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int ps = 0; ps < 16 / PPP; ++ps) RowInputs<Epi>::arrived(rin[i][ps]);
+    const int tiles_n = N / 128;
+    for (int jt = 0; jt < tiles_n; ++jt) {
+      const int n0 = jt * 128;
+      lds_barrier();                          // the B tile (and, the first time, the A stripe) is in LDS
+      const int nn = jt + 1 < tiles_n ? n0 + 128 : n0;  // the last tile re-fetches itself: same instruction count on every trip
+#pragma unroll
+      for (int it = 0; it < NV; ++it) vb[it] = ldb.fetch(nn + (t + it * 256) / Q, 8 * ((t + it * 256) % Q));
+      floatx16 acc[2][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < K / 16; ++kk) {
+        bf16x8 af[2], bf[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const bf16x8*>(&sA[((wm * 2 + i) * 32 + li) * LD + 16 * kk + 8 * g]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(&sB[((wn * 2 + j) * 32 + li) * LD + 16 * kk + 8 * g]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+      }
+      lds_barrier();  // every wave has read its B fragments: the B region now serves as the output slabs
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) eb[(8 * (q / 4) + 4 * g + q % 4) * ELD + j * 32 + li] = acc[i][j][q];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ps = 0; ps < 16 / PPP; ++ps) {
+          const int rl = 2 * (ps * PPP + epair);
+          const float4 a = *reinterpret_cast<const float4*>(&eb[rl * ELD + ecol]);
+          const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
+          const int64_t row = m0 + (wm * 2 + i) * 32 + rl;
+          const int col = n0 + wn * 64 + ecol;
+          if (FULL || row < M) RowInputs<Epi>::apply(epi, row, col, a, b, rin[i][ps]);
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+      lds_barrier();  // slabs read back: the next B tile goes over them
+#pragma unroll
+      for (int it = 0; it < NV; ++it)
+        *reinterpret_cast<bf16x8*>(&sB[((t + it * 256) / Q) * LD + 8 * ((t + it * 256) % Q)]) = ldb.finish(vb[it]);
     }
-    __syncthreads();  // slabs read back before the next B tile is written over them
   }
+};
+
+template <int K, typename LdA, typename LdB, typename Epi>
+__global__ void __launch_bounds__(256, 2)
+k_gemm_stripe(LdA lda, LdB ldb, Epi epi, int64_t M, int N) {
+  static_assert(LdA::WIDTH == 8 && LdB::WIDTH == 8, "raw bf16 operands");
+  static_assert(K % 16 == 0 && (128 * (K / 8)) % 256 == 0, "whole k steps, whole staging passes");
+  typedef Stripe<K, LdA, LdB, Epi> S;
+  __shared__ __attribute__((aligned(16))) __bf16 sA[128 * S::LD];
+  __shared__ __attribute__((aligned(16))) char sBraw[S::BS_BYTES];  // B tile, then the slabs
+  const int t = threadIdx.x;
+  const int64_t m0 = (int64_t)blockIdx.x * 128;
+  // A stripe: rows beyond M are clamped (their outputs are never stored)
+#pragma unroll
+  for (int it = 0; it < S::NV; ++it) {
+    const int idx = t + it * 256;
+    const int r = idx / S::Q, q = idx % S::Q;
+    int64_t row = m0 + r;
+    row = row < M ? row : M - 1;
+    *reinterpret_cast<bf16x8*>(&sA[r * S::LD + 8 * q]) = lda.finish(lda.fetch(row, 8 * q));
+  }
+  if (m0 + 128 <= M) S::template tiles<true>(ldb, epi, M, N, m0, sA, sBraw);
+  else S::template tiles<false>(ldb, epi, M, N, m0, sA, sBraw);
 }
 
-template <int KMAX, typename LdA, typename LdB, typename Epi>
-inline void launch_stripe(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N, int K) {
+// K must equal the template constant, N be a multiple of 128 and M even (rows come in pairs).
+template <int K, typename LdA, typename LdB, typename Epi>
+inline void launch_stripe(hipStream_t st, const LdA& a, const LdB& b, const Epi& e, int64_t M, int N) {
   if (M <= 0) return;
-  hipLaunchKernelGGL((k_gemm_stripe<KMAX, LdA, LdB, Epi>), dim3((unsigned)((M + 127) / 128)), dim3(256), 0, st, a, b, e, M, N, K);
+  hipLaunchKernelGGL((k_gemm_stripe<K, LdA, LdB, Epi>), dim3((unsigned)((M + 127) / 128)), dim3(256), 0, st, a, b, e, M, N);
 }
 
 }  // namespace gemm

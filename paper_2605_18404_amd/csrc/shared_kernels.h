@@ -290,9 +290,9 @@ void gemm_nt(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int 
     if constexpr (std::is_same<LdA, LdBf16>::value) {
       if (wide_ok(a, K)) {
         // short reduction, many column tiles: the row-stripe kernel (A staged once per 128 rows)
-        if (wb && K <= 128 && N % 128 == 0 && N >= 256 && M >= 128 * 256) {
-          if (K <= 64) return gemm::launch_stripe<64>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N, K);
-          return gemm::launch_stripe<128>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N, K);
+        if (wb && (K == 64 || K == 128) && N % 128 == 0 && N >= 256 && M >= 128 * 256 && M % 2 == 0) {
+          if (K == 64) return gemm::launch_stripe<64>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
+          return gemm::launch_stripe<128>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
         }
         if (wb) return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, M, N, K, epi);
         return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdPlain{W, K}, M, N, K, epi);
