@@ -256,6 +256,21 @@ struct EpiAddStore {  // p = add + v
     st4(p + o, add4(ld4(add + o), a));
     if (r + 1 < M) st4(p + o + ld, add4(ld4(add + o + ld), b));
   }
+  struct In { float4 a, b; };
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int col) const {
+    const int64_t o = r * ld + col;
+    In in;
+    in.a = ld4(add + o);
+    in.b = (FULL || r + 1 < M) ? ld4(add + o + ld) : in.a;
+    return in;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& in) const {
+    const int64_t o = r * ld + col;
+    st4(p + o, add4(in.a, a));
+    if (FULL || r + 1 < M) st4(p + o + ld, add4(in.b, b));
+  }
 };
 template <typename TO>
 struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  env[e] = (c, c')
@@ -271,6 +286,11 @@ struct EpiOmega {  // jets (w, w') -> radial filter jets (c w, c' w + c w'),  en
   // those stores' acknowledgements too (one in-order counter for vector memory operations), which would put a
   // store round trip into every pass of the epilogue.
   typedef float2 RowIn;
+  typedef float2 In;
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int) const { return env[r >> 1]; }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& c) const { apply(r, col, a, b, c); }
   __device__ __forceinline__ RowIn row_in(int64_t r) const { return env[r >> 1]; }
   __device__ static __forceinline__ void row_in_arrived(const RowIn& c) { asm volatile("" ::"v"(c.x), "v"(c.y)); }
   __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, const RowIn& c) const {
@@ -293,6 +313,25 @@ struct EpiMuT {  // mu_t = v, mu_q = silu'(q) v
     one(r * ld + col, a);
     if (r + 1 < M) one((r + 1) * ld + col, b);
   }
+  struct In { float4 a, b; };
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int col) const {
+    const int64_t o = r * ld + col;
+    In in;
+    in.a = ld4(q + o);
+    in.b = (FULL || r + 1 < M) ? ld4(q + o + ld) : in.a;
+    return in;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& in) const {
+    const int64_t o = r * ld + col;
+    st4(mu_t + o, a);
+    st4(mu_q + o, mul4(dsilu4(in.a), a));
+    if (FULL || r + 1 < M) {
+      st4(mu_t + o + ld, b);
+      st4(mu_q + o + ld, mul4(dsilu4(in.b), b));
+    }
+  }
 };
 template <typename TZ>
 struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld]); Z only ever feeds matrix products
@@ -309,6 +348,25 @@ struct EpiYZ {  // Y = v, Z = silu'(u[2e]) v   (u jets [2E][ld]); Z only ever fe
   __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
     one(r, col, a);
     if (r + 1 < M) one(r + 1, col, b);
+  }
+  struct In { float4 a, b; };
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int col) const {
+    const float* pu = u + 2 * r * ld + col;  // u rows 2r and 2(r + 1)
+    In in;
+    in.a = ld4(pu);
+    in.b = (FULL || r + 1 < M) ? ld4(pu + 2 * ld) : in.a;
+    return in;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& in) const {
+    const int64_t o = r * ld + col;
+    st4(Y + o, a);
+    st4(Z + o, mul4(dsilu4(in.a), a));
+    if (FULL || r + 1 < M) {
+      st4(Y + o + ld, b);
+      st4(Z + o + ld, mul4(dsilu4(in.b), b));
+    }
   }
 };
 __device__ __forceinline__ float4 lam4(float4 u0, float4 u1, float4 y, float4 v) {  // silu'(u0) v + silu''(u0) u1 y
@@ -339,6 +397,27 @@ struct EpiLamU {  // out = silu'(u) v + silu''(u) u' Y; out only ever feeds matr
     one(r, col, a);
     if (r + 1 < M) one(r + 1, col, b);
   }
+  struct In { float4 u0[2], u1[2], y[2]; };
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int col) const {
+    const float* pu = u + 2 * r * ld + col;
+    const float* py = Y + r * ld + col;
+    const bool two = FULL || r + 1 < M;
+    In in;
+    in.u0[0] = ld4(pu);
+    in.u1[0] = ld4(pu + ld);
+    in.y[0] = ld4(py);
+    in.u0[1] = two ? ld4(pu + 2 * ld) : in.u0[0];
+    in.u1[1] = two ? ld4(pu + 3 * ld) : in.u1[0];
+    in.y[1] = two ? ld4(py + ld) : in.y[0];
+    return in;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& in) const {
+    const int64_t o = r * ld + col;
+    st4(out + o, lam4(in.u0[0], in.u1[0], in.y[0], a));
+    if (FULL || r + 1 < M) st4(out + o + ld, lam4(in.u0[1], in.u1[1], in.y[1], b));
+  }
 };
 struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
   static constexpr bool FOLD = false;
@@ -353,6 +432,21 @@ struct EpiLamQ {  // out = silu'(q) v + silu''(q) qd mu_t
   __device__ __forceinline__ void operator()(int64_t r, int col, const float4& a, const float4& b, int) const {
     one(r * ld + col, a);
     if (r + 1 < M) one((r + 1) * ld + col, b);
+  }
+  struct In { float4 q[2], qd[2], mt[2]; };
+  template <bool FULL>
+  __device__ __forceinline__ In fetch(int64_t r, int col) const {
+    const int64_t o = r * ld + col, o2 = (FULL || r + 1 < M) ? o + ld : o;
+    In in;
+    in.q[0] = ld4(q + o); in.qd[0] = ld4(qd + o); in.mt[0] = ld4(mu_t + o);
+    in.q[1] = ld4(q + o2); in.qd[1] = ld4(qd + o2); in.mt[1] = ld4(mu_t + o2);
+    return in;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void apply(int64_t r, int col, const float4& a, const float4& b, int, const In& in) const {
+    const int64_t o = r * ld + col;
+    st4(out + o, lam4(in.q[0], in.qd[0], in.mt[0], a));
+    if (FULL || r + 1 < M) st4(out + o + ld, lam4(in.q[1], in.qd[1], in.mt[1], b));
   }
 };
 struct EpiPartial {  // split-k partial sums: part[z][row][col]

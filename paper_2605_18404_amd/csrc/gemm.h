@@ -162,6 +162,26 @@ struct Stager {
   }
 };
 
+// Epilogue functors with loads declare them apart from their stores: a type In, fetch<FULL>(row, col) returning the
+// values rows row, row + 1 need (FULL: row + 1 exists) and apply<FULL>(row, col, a, b, z, in).  Functors without loads
+// are called as they are.
+template <typename Epi, typename = void>
+struct EpiIO {
+  struct In {};
+  template <bool FULL>
+  __device__ static __forceinline__ In fetch(const Epi&, int64_t, int) { return In{}; }
+  template <bool FULL>
+  __device__ static __forceinline__ void apply(const Epi& e, int64_t r, int col, const float4& a, const float4& b, int z, const In&) { e(r, col, a, b, z); }
+};
+template <typename Epi>
+struct EpiIO<Epi, std::void_t<typename Epi::In>> {
+  typedef typename Epi::In In;
+  template <bool FULL>
+  __device__ static __forceinline__ In fetch(const Epi& e, int64_t r, int col) { return e.template fetch<FULL>(r, col); }
+  template <bool FULL>
+  __device__ static __forceinline__ void apply(const Epi& e, int64_t r, int col, const float4& a, const float4& b, int z, const In& in) { e.template apply<FULL>(r, col, a, b, z, in); }
+};
+
 // ---- the kernel -----------------------------------------------------------------------------
 // Epi: void operator()(int64_t row, int col, float4 a, float4 b, int z) const  -- columns col..col+3
 // of rows row (even, < M) and row + 1 (the functor checks row + 1 < M), z = split index.
@@ -355,6 +375,48 @@ k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chu
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int q = 0; q < 16; ++q) gacc[j][q] = 0.f;
+  }
+  if constexpr (!FOLD) {
+    // Plain epilogues.  A functor's loads (EpiIO::fetch) run two passes ahead of its stores (EpiIO::apply): vector
+    // memory operations retire in issue order, so a wait for loads issued behind a pass's stores would also wait for
+    // those stores' acknowledgements -- a store round trip per pass.  Interior tiles take a branch-free body, in which
+    // the compiler can count exactly which operations a wait has to cover.
+    auto run = [&](auto full_tag) {
+      constexpr bool FULLT = decltype(full_tag)::value;
+      constexpr int NPI = 16 / PPP, NP = TM * NPI, AHEAD = NP < 2 ? NP : 2;
+      typedef EpiIO<Epi> IO;
+      typename IO::In in[NP];
+      auto fetch = [&](int pz) {
+        const int rl = 2 * ((pz % NPI) * PPP + epair);
+        const int64_t row = m0 + (wm * TM + pz / NPI) * 32 + rl;
+        const int col = n0 + wn * EW + ecol;
+        if (FULLT || (row < M && col < N)) in[pz] = IO::template fetch<FULLT>(epi, row, col);
+      };
+#pragma unroll
+      for (int pz = 0; pz < AHEAD; ++pz) fetch(pz);
+#pragma unroll
+      for (int pz = 0; pz < NP; ++pz) {
+        const int i = pz / NPI, ps = pz % NPI;
+        if (ps == 0) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) eb[(8 * (q / 4) + 4 * g + q % 4) * ELD + j * 32 + li] = acc[i][j][q];
+          __builtin_amdgcn_wave_barrier();
+        }
+        if (pz + AHEAD < NP) fetch(pz + AHEAD);
+        const int rl = 2 * (ps * PPP + epair);
+        const float4 a = *reinterpret_cast<const float4*>(&eb[rl * ELD + ecol]);
+        const float4 b = *reinterpret_cast<const float4*>(&eb[(rl + 1) * ELD + ecol]);
+        const int64_t row = m0 + (wm * TM + i) * 32 + rl;
+        const int col = n0 + wn * EW + ecol;
+        if (FULLT || (row < M && col < N)) IO::template apply<FULLT>(epi, row, col, a, b, z, in[pz]);
+        if (ps == NPI - 1) __builtin_amdgcn_wave_barrier();
+      }
+    };
+    if ((m0 + BM <= M) && (n0 + BN <= N)) run(std::true_type());
+    else run(std::false_type());
+    return;
   }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
