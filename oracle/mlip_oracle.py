@@ -19,7 +19,7 @@ forward product and one used by the product in its backward rule; the gradient w
 respect to the first copy is BE's share, with respect to the second BF's share.
 
 The paper gives no model equations (it trains third-party UMA / eSEN models); the models
-here are the invariant and the l<=2 equivariant message-passing potentials defined in the
+here are the invariant and the equivariant (l <= 2, optionally l <= 3) message-passing potentials defined in the
 docstrings below, and the readings taken where the benchmark spec leaves a choice are
 listed with each function.
 
@@ -30,7 +30,9 @@ with halved matrices when its gate scalars vanish); F vs central differences of 
 vs central differences of L; BF+BE = total; stage outputs vs central differences of the
 stage scalar and vs the unsplit model; radius_graph_rows row by row vs radius_graph and a k-d tree;
 one equivariant layer vs explicit loops with couplings integrated from the harmonics' polynomials;
-energy_streamed vs energy_only.  No function here is left unpinned.
+energy_streamed vs energy_only; the l_max = 3 extension: degree-3 harmonics vs scipy and the addition theorem,
+all 23 couplings vs sphere means of typed polynomials, one layer by explicit loops, F and dL/dtheta by central
+differences.  No function here is left unpinned.
 """
 from __future__ import annotations
 
@@ -42,12 +44,22 @@ import torch
 
 DT = torch.float64
 
-PATHS: List[Tuple[int, int, int]] = [
-    (l1, l2, l3)
-    for l1 in range(3) for l2 in range(3) for l3 in range(3)
-    if abs(l1 - l2) <= l3 <= l1 + l2 and (l1 + l2 + l3) % 2 == 0
-]  # 11 paths, ordered by (l1, l2, l3)
-SL = [slice(0, 1), slice(1, 4), slice(4, 9)]  # components of l = 0, 1, 2 inside the 9-vector
+def paths_of(l_max: int) -> List[Tuple[int, int, int]]:
+    """The coupling paths (l1, l2, l3) with every degree <= l_max that satisfy the triangle rule and have even
+    l1 + l2 + l3, ordered by (l1, l2, l3): 11 paths for l_max = 2, 23 for l_max = 3."""
+    return [(l1, l2, l3)
+            for l1 in range(l_max + 1) for l2 in range(l_max + 1) for l3 in range(l_max + 1)
+            if abs(l1 - l2) <= l3 <= l1 + l2 and (l1 + l2 + l3) % 2 == 0]
+
+
+PATHS: List[Tuple[int, int, int]] = paths_of(2)
+# components of degree l inside the (l_max + 1)^2-vector of node features / harmonics
+SL = [slice(0, 1), slice(1, 4), slice(4, 9), slice(9, 16)]
+
+
+def lmax_of(cfg: Dict) -> int:
+    """Highest degree of the equivariant model's features (2 unless the model description says 3)."""
+    return int(cfg.get("l_max", 2) or 2)
 
 
 # ============================================================================ neighbour list
@@ -152,32 +164,38 @@ def envelope(r: torch.Tensor, cutoff: float) -> torch.Tensor:
     return 0.5 * (1.0 + torch.cos(math.pi * r / cutoff))
 
 
-def real_sph_harm(u: torch.Tensor) -> torch.Tensor:
-    """Real spherical harmonics l = 0, 1, 2 of unit vectors u [.., 3] -> [.., 9].
+def real_sph_harm(u: torch.Tensor, l_max: int = 2) -> torch.Tensor:
+    """Real spherical harmonics l = 0..l_max (2 or 3) of unit vectors u [.., 3] -> [.., (l_max + 1)^2].
 
     Component normalisation (mean of Y^2 over the sphere is 1, so sum_m Y_lm^2 = 2l+1);
     order inside l is m = -l..l, which for l = 1 is (y, z, x).
     """
     x, y, z = u[..., 0], u[..., 1], u[..., 2]
     s3, s15, s5 = math.sqrt(3.0), math.sqrt(15.0), math.sqrt(5.0)
-    return torch.stack([
+    comps = [
         torch.ones_like(x),
         s3 * y, s3 * z, s3 * x,
         s15 * x * y, s15 * y * z, 0.5 * s5 * (3.0 * z * z - 1.0), s15 * x * z, 0.5 * s15 * (x * x - y * y),
-    ], dim=-1)
+    ]
+    if l_max >= 3:
+        a, b, c, d = math.sqrt(35.0 / 8.0), math.sqrt(105.0), math.sqrt(21.0 / 8.0), 0.5 * math.sqrt(7.0)
+        comps += [
+            a * y * (3.0 * x * x - y * y), b * x * y * z, c * y * (5.0 * z * z - 1.0), d * z * (5.0 * z * z - 3.0),
+            c * x * (5.0 * z * z - 1.0), 0.5 * b * z * (x * x - y * y), a * x * (x * x - 3.0 * y * y),
+        ]
+    return torch.stack(comps, dim=-1)
 
 
-_GAUNT_CACHE: Optional[List[torch.Tensor]] = None
+_GAUNT_CACHE: Dict[int, List[torch.Tensor]] = {}
 
 
-def gaunt_tensors() -> List[torch.Tensor]:
-    """T^p[m1, m2, m3] for the 11 paths p = (l1, l2, l3): the real Gaunt integral
+def gaunt_tensors(l_max: int = 2) -> List[torch.Tensor]:
+    """T^p[m1, m2, m3] for the paths p = (l1, l2, l3) of paths_of(l_max): the real Gaunt integral
     (1/4pi) Int Y_l1m1 Y_l2m2 Y_l3m3 dOmega, evaluated by a quadrature that is exact for the
-    degree-6 integrand (Gauss-Legendre in cos(theta) x uniform in the azimuth), then scaled
+    integrand of degree <= 9 (Gauss-Legendre in cos(theta) x uniform in the azimuth), then scaled
     by a positive factor per path so that the sum of squares is 2 l3 + 1."""
-    global _GAUNT_CACHE
-    if _GAUNT_CACHE is not None:
-        return _GAUNT_CACHE
+    if l_max in _GAUNT_CACHE:
+        return _GAUNT_CACHE[l_max]
     ct, wt = np.polynomial.legendre.leggauss(8)
     nphi = 16
     ph = (np.arange(nphi) + 0.5) * (2.0 * math.pi / nphi)
@@ -185,14 +203,14 @@ def gaunt_tensors() -> List[torch.Tensor]:
     W = np.repeat(wt[:, None], nphi, 1) * (2.0 * math.pi / nphi) / (4.0 * math.pi)
     st = np.sqrt(1.0 - CT * CT)
     u = torch.tensor(np.stack([st * np.cos(PH), st * np.sin(PH), CT], -1).reshape(-1, 3), dtype=DT)
-    Y = real_sph_harm(u)
+    Y = real_sph_harm(u, l_max)
     w = torch.tensor(W.reshape(-1), dtype=DT)
     out = []
-    for (l1, l2, l3) in PATHS:
+    for (l1, l2, l3) in paths_of(l_max):
         G = torch.einsum("q,qa,qb,qc->abc", w, Y[:, SL[l1]], Y[:, SL[l2]], Y[:, SL[l3]])
         G = torch.where(G.abs() < 1e-13, torch.zeros_like(G), G)
         out.append(G * math.sqrt((2 * l3 + 1) / float((G * G).sum())))
-    _GAUNT_CACHE = out
+    _GAUNT_CACHE[l_max] = out
     return out
 
 
@@ -203,7 +221,7 @@ def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
     whole models start with emb[S,C] and end with U[C,C], w_o[C]; each layer holds
     invariant  W1[H,K], W2[C,H]  (depth 3: W1[H,K], W2[H,H], W3[C,H]),  V1[C,C], V2[C,C]
     (with n_experts > 0: expert banks V1[n_experts,C,C], V2[n_experts,C,C]);
-    equivariant W1[H,K], W2[11 C,H] (row = path*C + channel), Wl0, Wl1, Wl2 [C,C]
+    equivariant W1[H,K], W2[n_paths C,H] (row = path*C + channel; 11 paths, 23 with l_max = 3), Wl0 .. Wl{l_max} [C,C]
     (with n_experts > 0: banks [n_experts,C,C]);
     a stage holds the layer blocks only."""
     C, H, K, S = cfg["channels"], cfg["edge_hidden"], cfg["n_rbf"], cfg["n_species"]
@@ -214,9 +232,9 @@ def unpack_params(flat: torch.Tensor, cfg: Dict) -> Dict[str, torch.Tensor]:
     for l in range(cfg["n_layers"]):
         names.append((f"l{l}.W1", (H, K)))
         if kind == "equivariant":
-            names.append((f"l{l}.W2", (len(PATHS) * C, H)))
+            names.append((f"l{l}.W2", (len(paths_of(lmax_of(cfg))) * C, H)))
             wshape = (cfg["n_experts"], C, C) if cfg.get("n_experts", 0) > 0 else (C, C)
-            names += [(f"l{l}.Wl{k}", wshape) for k in range(3)]
+            names += [(f"l{l}.Wl{k}", wshape) for k in range(lmax_of(cfg) + 1)]
         else:
             if cfg["edge_depth"] == 3:
                 names += [(f"l{l}.W2", (H, H)), (f"l{l}.W3", (C, H))]
@@ -330,17 +348,19 @@ def invariant_layer(h, l, lin: _Lin, cfg, snd, rcv, r):
 
 
 def equivariant_messages(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
-    """h [N, C, 9].  a_i = sum_e m_e over the given edges with
+    """h [N, C, (l_max + 1)^2].  a_i = sum_e m_e over the given edges with
     m_e[c; l3 m3] = f_c(r_e) sum_p R_e[p, c] sum_{m1 m2} T^p[m1 m2 m3] h_j[c; l1 m1] Y_{l2 m2}(r_e / r_e),
-    R_e = W2 silu(W1 phi(r_e)) reshaped [11, C]."""
+    R_e = W2 silu(W1 phi(r_e)) reshaped [n_paths, C]."""
     C = cfg["channels"]
+    lm = lmax_of(cfg)
+    paths = paths_of(lm)
     phi = rbf(r, cfg["n_rbf"], cfg["cutoff"])
-    R = lin(silu(lin(phi, f"l{l}.W1")), f"l{l}.W2").reshape(-1, len(PATHS), C)
-    Y = real_sph_harm(rv / r[:, None])
+    R = lin(silu(lin(phi, f"l{l}.W1")), f"l{l}.W2").reshape(-1, len(paths), C)
+    Y = real_sph_harm(rv / r[:, None], lm)
     hj = h[snd]
-    T = gaunt_tensors()
-    parts = [torch.zeros(hj.shape[0], C, 2 * k + 1, dtype=DT) for k in range(3)]
-    for p, (l1, l2, l3) in enumerate(PATHS):
+    T = gaunt_tensors(lm)
+    parts = [torch.zeros(hj.shape[0], C, 2 * k + 1, dtype=DT) for k in range(lm + 1)]
+    for p, (l1, l2, l3) in enumerate(paths):
         tp = torch.einsum("abk,eca,eb->eck", T[p], hj[:, :, SL[l1]], Y[:, SL[l2]])
         parts[l3] = parts[l3] + R[:, p, :, None] * tp
     m = envelope(r, cfg["cutoff"])[:, None, None] * torch.cat(parts, dim=2)
@@ -349,11 +369,11 @@ def equivariant_messages(h, l, lin: _Lin, cfg, snd, rcv, rv, r):
 
 def equivariant_update(h, a, l, lin: _Lin, cfg):
     """h_i[:, l] <- h_i[:, l] + W^(l) a_i[:, l] (one C x C matrix per l, shared over m); with cfg["gate"] the
-    gated form h_0 += silu(u_0), h_lm += sigmoid(u_0) u_lm (l = 1, 2) of u = W^(l) a."""
-    upd = [lin.node(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(3)]
+    gated form h_0 += silu(u_0), h_lm += sigmoid(u_0) u_lm (l >= 1) of u = W^(l) a."""
+    upd = [lin.node(a[:, :, SL[k]].transpose(1, 2), f"l{l}.Wl{k}").transpose(1, 2) for k in range(lmax_of(cfg) + 1)]
     if cfg.get("gate", 0):
         u0 = upd[0]
-        upd = [silu(u0), torch.sigmoid(u0) * upd[1], torch.sigmoid(u0) * upd[2]]
+        upd = [silu(u0)] + [torch.sigmoid(u0) * uk for uk in upd[1:]]
     return h + torch.cat(upd, dim=2)
 
 
@@ -372,7 +392,7 @@ def energy(x, species, graph, cell, struct_ptr, lin: _Lin, cfg) -> torch.Tensor:
     snd, rcv, rv, r = edge_vectors(x, graph, cell, sid)
     emb = lin.P["emb"][torch.as_tensor(species, dtype=torch.long)]
     if cfg["kind"] == "equivariant":
-        h = torch.cat([emb[:, :, None], torch.zeros(N, cfg["channels"], 8, dtype=DT)], dim=2)
+        h = torch.cat([emb[:, :, None], torch.zeros(N, cfg["channels"], (lmax_of(cfg) + 1) ** 2 - 1, dtype=DT)], dim=2)
         for l in range(cfg["n_layers"]):
             h = equivariant_layer(h, l, lin, cfg, snd, rcv, rv, r)
         h = h[:, :, 0]
@@ -457,7 +477,7 @@ def energy_streamed(cfg, pos, species, struct_ptr, cell, params, graph, edge_chu
         n_edges = len(graph["sender"])
         emb = lin.P["emb"][torch.as_tensor(species, dtype=torch.long)]
         eqv = cfg["kind"] == "equivariant"
-        h = torch.cat([emb[:, :, None], torch.zeros(N, cfg["channels"], 8, dtype=DT)], dim=2) if eqv else emb
+        h = torch.cat([emb[:, :, None], torch.zeros(N, cfg["channels"], (lmax_of(cfg) + 1) ** 2 - 1, dtype=DT)], dim=2) if eqv else emb
         for l in range(cfg["n_layers"]):
             a = torch.zeros_like(h)
             for e0 in range(0, n_edges, edge_chunk):
@@ -540,4 +560,5 @@ def cfg_from_workload(w) -> Dict:
     return dict(kind=kind, channels=w.channels, edge_hidden=w.edge_hidden, n_rbf=w.n_rbf,
                 n_species=w.n_species, n_layers=w.n_layers, edge_depth=w.edge_depth,
                 cutoff=float(w.cutoff), force_weight=float(w.force_weight),
-                n_experts=int(getattr(w, "n_experts", 0)), gate=int(getattr(w, "gate", 0)))
+                n_experts=int(getattr(w, "n_experts", 0)), gate=int(getattr(w, "gate", 0)),
+                l_max=int(getattr(w, "l_max", 0)))

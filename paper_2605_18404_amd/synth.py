@@ -37,6 +37,12 @@ KIND_INVARIANT, KIND_EQUIVARIANT, KIND_STAGE = 0, 1, 2
 N_PATHS_LMAX2 = 11  # (l1,l2,l3) with l<=2, triangle rule, l1+l2+l3 even
 
 
+def n_paths(l_max: int) -> int:
+    """Number of coupling paths (l1, l2, l3), every degree <= l_max, triangle rule, l1 + l2 + l3 even (11 for 2, 23 for 3)."""
+    return sum(1 for l1 in range(l_max + 1) for l2 in range(l_max + 1) for l3 in range(l_max + 1)
+               if abs(l1 - l2) <= l3 <= l1 + l2 and (l1 + l2 + l3) % 2 == 0)
+
+
 def _finalise(z: np.ndarray) -> np.ndarray:
     z = z ^ (z >> np.uint64(30))
     z = z * _M1
@@ -267,8 +273,9 @@ def param_shapes(w: Workload) -> List[Tuple[str, Tuple[int, ...], int, int]]:
     for l in range(w.n_layers):
         if w.kind == KIND_EQUIVARIANT:
             out.append((f"l{l}.W1", (H, K), K, H))
-            out.append((f"l{l}.W2", (N_PATHS_LMAX2 * C, H), H, N_PATHS_LMAX2 * C))
-            for lam in range(3):
+            npth = n_paths(w.l_max)
+            out.append((f"l{l}.W2", (npth * C, H), H, npth * C))
+            for lam in range(w.l_max + 1):
                 out.append((f"l{l}.Wl{lam}", (w.n_experts, C, C) if w.n_experts > 0 else (C, C), C, C))
         else:
             out.append((f"l{l}.W1", (H, K), K, H))

@@ -1,0 +1,258 @@
+"""Pins for the oracle's l_max = 3 extension of the equivariant model (harmonics of degree 3, the 23 coupling
+paths, one layer by explicit loops, derivatives by central differences).  CPU only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+from scipy.spatial.transform import Rotation
+from scipy.special import sph_harm_y
+
+from oracle import mlip_oracle as O
+from paper_2605_18404_amd import synth
+
+
+def _rand_unit(n, seed=0):
+    v = np.random.default_rng(seed).normal(size=(n, 3))
+    return v / np.linalg.norm(v, axis=1, keepdims=True)
+
+
+# ------------------------------------------------------------------ harmonics of degree 3
+
+def test_degree3_harmonics_match_scipy_and_keep_the_lower_degrees():
+    u = _rand_unit(60, 2)
+    theta, phi = np.arccos(u[:, 2]), np.arctan2(u[:, 1], u[:, 0])
+    got = O.real_sph_harm(torch.tensor(u), 3).numpy()
+    assert got.shape == (60, 16)
+    assert np.array_equal(got[:, :9], O.real_sph_harm(torch.tensor(u)).numpy())
+    for col, m in zip(range(9, 16), range(-3, 4)):
+        Yc = sph_harm_y(3, abs(m), theta, phi)  # orthonormal, Condon-Shortley phase
+        ref = Yc.real if m == 0 else math.sqrt(2) * (-1) ** m * (Yc.real if m > 0 else Yc.imag)
+        assert np.allclose(got[:, col], math.sqrt(4 * math.pi) * ref, atol=1e-13), m
+
+
+def test_addition_theorem_for_degree3():
+    # sum_m Y_3m(u) Y_3m(v) = 7 P_3(u.v),  P_3(t) = (5 t^3 - 3 t) / 2
+    u, v = _rand_unit(40, 3), _rand_unit(40, 4)
+    Yu = O.real_sph_harm(torch.tensor(u), 3).numpy()[:, O.SL[3]]
+    Yv = O.real_sph_harm(torch.tensor(v), 3).numpy()[:, O.SL[3]]
+    t = (u * v).sum(1)
+    assert np.allclose((Yu * Yv).sum(1), 7.0 * 0.5 * (5 * t ** 3 - 3 * t), atol=1e-12)
+    assert np.allclose((Yu ** 2).sum(1), 7.0)
+
+
+# ------------------------------------------------------------------ couplings
+
+def _dfact(n):
+    return 1 if n <= 0 else n * _dfact(n - 2)
+
+
+def _mono_mean(a, b, c):
+    """Mean of x^a y^b z^c over the unit sphere."""
+    if a % 2 or b % 2 or c % 2:
+        return 0.0
+    return _dfact(a - 1) * _dfact(b - 1) * _dfact(c - 1) / _dfact(a + b + c + 1)
+
+
+def _harmonic_polys():
+    """The sixteen real harmonics of degree <= 3 as {(a, b, c): coefficient} in x^a y^b z^c, typed from their textbook
+    (cubic-harmonic) forms with 1 = x^2 + y^2 + z^2 put in where a form is inhomogeneous:
+    degree 3, m = -3..3: sqrt(35/8) y (3x^2 - y^2); sqrt105 xyz; sqrt(21/8) y (4z^2 - x^2 - y^2);
+    (sqrt7/2) z (2z^2 - 3x^2 - 3y^2); sqrt(21/8) x (4z^2 - x^2 - y^2); (sqrt105/2) z (x^2 - y^2); sqrt(35/8) x (x^2 - 3y^2)."""
+    s3, s15, s5 = math.sqrt(3), math.sqrt(15), math.sqrt(5)
+    a, b, c, d = math.sqrt(35 / 8), math.sqrt(105), math.sqrt(21 / 8), math.sqrt(7) / 2
+    return [
+        {(0, 0, 0): 1.0},
+        {(0, 1, 0): s3}, {(0, 0, 1): s3}, {(1, 0, 0): s3},
+        {(1, 1, 0): s15}, {(0, 1, 1): s15}, {(0, 0, 2): s5, (2, 0, 0): -0.5 * s5, (0, 2, 0): -0.5 * s5}, {(1, 0, 1): s15},
+        {(2, 0, 0): 0.5 * s15, (0, 2, 0): -0.5 * s15},
+        {(2, 1, 0): 3 * a, (0, 3, 0): -a},
+        {(1, 1, 1): b},
+        {(0, 1, 2): 4 * c, (2, 1, 0): -c, (0, 3, 0): -c},
+        {(0, 0, 3): 2 * d, (2, 0, 1): -3 * d, (0, 2, 1): -3 * d},
+        {(1, 0, 2): 4 * c, (3, 0, 0): -c, (1, 2, 0): -c},
+        {(2, 0, 1): 0.5 * b, (0, 2, 1): -0.5 * b},
+        {(3, 0, 0): a, (1, 2, 0): -3 * a},
+    ]
+
+
+_OFF = [0, 1, 4, 9]
+
+
+def _hand_couplings():
+    Y = _harmonic_polys()
+    out = {}
+    for l1, l2, l3 in itertools.product(range(4), repeat=3):
+        if not (abs(l1 - l2) <= l3 <= l1 + l2) or (l1 + l2 + l3) % 2:
+            continue
+        T = np.zeros((2 * l1 + 1, 2 * l2 + 1, 2 * l3 + 1))
+        for m1, m2, m3 in np.ndindex(*T.shape):
+            tot = 0.0
+            for (e1, c1), (e2, c2), (e3, c3) in itertools.product(Y[_OFF[l1] + m1].items(), Y[_OFF[l2] + m2].items(),
+                                                                  Y[_OFF[l3] + m3].items()):
+                tot += c1 * c2 * c3 * _mono_mean(e1[0] + e2[0] + e3[0], e1[1] + e2[1] + e3[1], e1[2] + e2[2] + e3[2])
+            T[m1, m2, m3] = tot
+        out[(l1, l2, l3)] = T * math.sqrt((2 * l3 + 1) / (T ** 2).sum())
+    return out
+
+
+def test_typed_polynomials_are_the_oracles_harmonics():
+    u = _rand_unit(10, 7)
+    Y = O.real_sph_harm(torch.tensor(u), 3).numpy()
+    for m, p in enumerate(_harmonic_polys()):
+        val = sum(co * u[:, 0] ** a * u[:, 1] ** b * u[:, 2] ** c for (a, b, c), co in p.items())
+        assert np.allclose(Y[:, m], val, atol=1e-13), m
+
+
+def test_paths_and_couplings_for_lmax3():
+    paths = O.paths_of(3)
+    assert len(paths) == 23 and paths == sorted(paths)
+    assert [p for p in paths if max(p) <= 2] == O.PATHS  # the l <= 2 paths keep their relative order
+    G = O.gaunt_tensors(3)
+    T = _hand_couplings()
+    assert sorted(T) == paths
+    for p, key in enumerate(paths):
+        assert G[p].shape == tuple(2 * l + 1 for l in key)
+        assert np.allclose(G[p].numpy(), T[key], atol=1e-12), key
+    # couplings with the constant harmonic are the identity (orthonormality of the degree-3 harmonics)
+    assert np.allclose(T[(0, 3, 3)][0], np.eye(7), atol=1e-13)
+    assert np.allclose(T[(3, 0, 3)][:, 0, :], np.eye(7), atol=1e-13)
+    assert np.allclose(T[(3, 3, 0)][:, :, 0], np.eye(7) / math.sqrt(7), atol=1e-13)
+    # typed values: <Y_1z Y_20 Y_30> = (sqrt3 sqrt5 sqrt7 / 4) <z (3z^2 - 1)(5z^3 - 3z)> = (sqrt105/4)(15/7 - 14/5 + 1) = 3 sqrt105/35,
+    # <Y_1x Y_20 Y_31> = (sqrt3 sqrt5 sqrt(21/8) / 2) <x^2 (3z^2 - 1)(5z^2 - 1)> = (3/2) sqrt(35/8) (15/35 - 8/15 + 1/3);
+    # in the ratio of two entries of one path the path's scale drops out
+    ratio = (3 * math.sqrt(105) / 35) / (1.5 * math.sqrt(35 / 8) * (15 / 35 - 8 / 15 + 1 / 3))
+    assert abs(T[(1, 2, 3)][1, 2, 3] / T[(1, 2, 3)][2, 2, 4] - ratio) < 1e-12 and T[(1, 2, 3)][1, 2, 3] > 0
+    # exchanging the first two factors of the integrand transposes the coupling
+    assert np.allclose(T[(3, 3, 2)], T[(3, 3, 2)].transpose(1, 0, 2), atol=1e-13)
+    assert np.allclose(T[(1, 2, 3)], T[(2, 1, 3)].transpose(1, 0, 2), atol=1e-13)
+
+
+def _wigner(l, R, n=60):
+    u = _rand_unit(n, 5)
+    A = O.real_sph_harm(torch.tensor(u), 3).numpy()[:, O.SL[l]]
+    Bm = O.real_sph_harm(torch.tensor(u @ R.T), 3).numpy()[:, O.SL[l]]
+    D = np.linalg.lstsq(A, Bm, rcond=None)[0].T
+    assert np.allclose(A @ D.T, Bm, atol=1e-11)
+    return D
+
+
+def test_all_23_couplings_are_rotation_equivariant():
+    R = Rotation.from_rotvec([0.3, -1.1, 0.7]).as_matrix()
+    D = [_wigner(l, R) for l in range(4)]
+    rng = np.random.default_rng(3)
+    for p, (l1, l2, l3) in enumerate(O.paths_of(3)):
+        a, b = rng.normal(size=2 * l1 + 1), rng.normal(size=2 * l2 + 1)
+        t = O.gaunt_tensors(3)[p].numpy()
+        out = np.einsum("abk,a,b->k", t, a, b)
+        assert np.allclose(np.einsum("abk,a,b->k", t, D[l1] @ a, D[l2] @ b), D[l3] @ out, atol=1e-10), (l1, l2, l3)
+
+
+# ------------------------------------------------------------------ one layer by explicit loops
+
+def _tiny(**kw):
+    d = dict(n_structs=1, atoms_per_struct=3, box=5.0, cutoff=3.0, n_rbf=5, channels=2, edge_hidden=3, n_layers=1, n_species=2,
+             l_max=3)
+    d.update(kw)
+    return synth.shrink(synth.WORKLOADS[2], **d)
+
+
+def _hand_layer(w, inp, pos, g, h, drop_path=None):
+    C, K, rc = w.channels, w.n_rbf, w.cutoff
+    P = {k: inp.params[o:o + int(np.prod(s))].reshape(s).astype(np.float64) for k, (o, s) in synth.param_slices(w).items()}
+    T = _hand_couplings()
+    paths = sorted(T)
+    Ypoly = _harmonic_polys()
+    sil = lambda t: t / (1.0 + np.exp(-t))
+    cell = inp.cell[0].astype(np.float64)
+    a = np.zeros((3, C, 16))
+    for e in range(len(g["sender"])):
+        i, j, S = int(g["receiver"][e]), int(g["sender"][e]), g["shift"][e].astype(np.float64)
+        rv = pos[j] + S @ cell - pos[i]
+        r = math.sqrt(rv @ rv)
+        u = rv / r
+        Y = [sum(co * u[0] ** ea * u[1] ** eb * u[2] ** ec for (ea, eb, ec), co in p.items()) for p in Ypoly]
+        phi = np.array([math.exp(-0.5 * ((r - k * rc / (K - 1)) / (rc / (K - 1))) ** 2) for k in range(K)])
+        fc = 0.5 * (1.0 + math.cos(math.pi * r / rc))
+        R = (P["l0.W2"] @ sil(P["l0.W1"] @ phi)).reshape(23, C)
+        for c in range(C):
+            for p, (l1, l2, l3) in enumerate(paths):
+                if p == drop_path:
+                    continue
+                for m1, m2, m3 in np.ndindex(2 * l1 + 1, 2 * l2 + 1, 2 * l3 + 1):
+                    a[i, c, _OFF[l3] + m3] += fc * R[p, c] * T[(l1, l2, l3)][m1, m2, m3] * h[j, c, _OFF[l1] + m1] * Y[_OFF[l2] + m2]
+    out = h.copy()
+    for i in range(3):
+        for l in range(4):
+            for m in range(2 * l + 1):
+                out[i, :, _OFF[l] + m] += P[f"l0.Wl{l}"] @ a[i, :, _OFF[l] + m]
+    return out
+
+
+def test_single_lmax3_layer_by_hand():
+    w = _tiny()
+    inp = synth.make_inputs(w)
+    cfg = O.cfg_from_workload(w)
+    assert cfg["l_max"] == 3
+    pos = np.array([[0.4, 0.9, 1.1], [2.2, 1.4, 0.3], [4.5, 0.2, 4.6]])
+    g = O.radius_graph(pos, inp.struct_ptr, inp.cell, w.cutoff)
+    assert len(g["sender"]) >= 6
+    h = np.random.default_rng(11).normal(size=(3, w.channels, 16))
+    lin = O._Lin(O.unpack_params(torch.tensor(inp.params, dtype=torch.float64), cfg))
+    sid = torch.zeros(3, dtype=torch.long)
+    lin.sid = sid
+    snd, rcv, rv, r = O.edge_vectors(torch.tensor(pos), g, torch.tensor(inp.cell, dtype=torch.float64), sid)
+    got = O.equivariant_layer(torch.tensor(h), 0, lin, cfg, snd, rcv, rv, r).numpy()
+    want = _hand_layer(w, inp, pos, g, h)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-14)
+    scale = np.abs(want - h).max()
+    for p in range(23):  # every path matters
+        assert np.abs(_hand_layer(w, inp, pos, g, h, drop_path=p) - want).max() > 1e-5 * scale, p
+
+
+# ------------------------------------------------------------------ model level
+
+def _step(w, inp, **kw):
+    return O.train_step(O.cfg_from_workload(w), kw.get("pos", inp.pos), inp.species, inp.struct_ptr, inp.cell, kw.get("params", inp.params),
+                        inp.E_ref, inp.F_ref)
+
+
+@pytest.mark.parametrize("gate", [0, 1])
+def test_lmax3_energy_is_invariant_and_forces_rotate(gate):
+    w = _tiny(atoms_per_struct=10, box=20.0, cutoff=4.0, cell_kind="free", n_layers=2, channels=3, gate=gate)
+    inp = synth.make_inputs(w)
+    r0 = _step(w, inp)
+    assert np.abs(r0["F"]).max() > 0
+    R = Rotation.from_rotvec([0.4, 0.9, -0.5]).as_matrix()
+    c = inp.pos.mean(0)
+    r1 = _step(w, inp, pos=((inp.pos - c) @ R.T + c))
+    # (the step takes float32 positions, so the rotated input is rounded: agreement to that rounding)
+    assert np.allclose(r1["E"], r0["E"], rtol=1e-6, atol=1e-8)
+    assert np.allclose(r1["F"], r0["F"] @ R.T, rtol=1e-4, atol=1e-6 * np.abs(r0["F"]).max())
+    assert len(inp.params) == synth.param_count(w)
+
+
+def test_lmax3_force_and_gradient_by_central_differences():
+    w = _tiny(atoms_per_struct=8, box=6.0, cutoff=3.0, n_layers=2, channels=2)
+    inp = synth.make_inputs(w)
+    cfg = O.cfg_from_workload(w)
+    r0 = _step(w, inp)
+    g = O.radius_graph(inp.pos, inp.struct_ptr, inp.cell, w.cutoff)
+    rng = np.random.default_rng(5)
+    d = rng.normal(size=inp.pos.shape)
+    eps = 1e-5
+    Ep = O.energy_only(cfg, inp.pos.astype(np.float64) + eps * d, inp.species, inp.struct_ptr, inp.cell, inp.params, graph=g).sum()
+    Em = O.energy_only(cfg, inp.pos.astype(np.float64) - eps * d, inp.species, inp.struct_ptr, inp.cell, inp.params, graph=g).sum()
+    assert abs((Ep - Em) / (2 * eps) + (r0["F"] * d).sum()) < 1e-6 * max(1.0, np.abs(r0["F"]).max())
+    t = rng.normal(size=inp.params.shape)
+    h = 1e-5
+    Lp = _step(w, inp, params=inp.params.astype(np.float64) + h * t)["loss"]
+    Lm = _step(w, inp, params=inp.params.astype(np.float64) - h * t)["loss"]
+    want = (Lp - Lm) / (2 * h)
+    got = float((r0["grad"] * t).sum())
+    assert abs(got - want) < 1e-6 * max(1.0, abs(want)), (got, want)
+    # the two shares of Eq. 2 add up to the unsplit gradient, and the second-order share is not empty
+    rs = O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref, split=True)
+    assert np.allclose(rs["grad_bf"] + rs["grad_be"], r0["grad"], rtol=1e-10, atol=1e-13)
+    assert np.abs(rs["grad_bf"]).max() > 0
