@@ -1,6 +1,6 @@
 """Benchmark of the whole hot path (graph build + FE + FF + loss + BF + BE) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--others cfg0,cfg1,cfg2,cfg3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--others cfg0,cfg1,cfg2,cfg3,cfg2_lmax3]
                     [--no-others] [--no-cpu-baseline] [--copy-probe]
 
 Prints ONE JSON line.  The headline (`value`, `ms_per_step`, `phase_ms`, `roofline`) is the largest
@@ -36,26 +36,28 @@ PEAK_HBM_GBS = 8000.0
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_FP32_VALU_TFLOPS = 157.3   # 256 CUs x 128 fp32 FMA lanes x 2 flop x 2.4 GHz
 PEAK_BF16_MFMA_TFLOPS = 2500.0
-NNZ_COUPLINGS = 83              # non-zero entries of the 11 real coupling tensors (l <= 2), counted from the generated table
-N_PATHS = 11
+# per l_max of the equivariant model: (non-zero entries of the real coupling tensors, counted from the generated table;
+# coupling paths; components of a feature vector; path values per channel as stored)
+COUPLINGS = {2: (83, 11, 9, 12), 3: (353, 23, 16, 24)}
 
 
 def kernel_table(w, E, N):
     """Kernel ids of include/mlip.h -> (name, bound, algorithmic work per launch, extra figures).
     Matrix products: flop = 2 x rows x inner x out.  Invariant gather kernels: HBM bytes, every edge tensor
     and node table touched once, indices and geometry included.  Equivariant tensor-product kernels: fp32
-    vector flop = 2 (nnz(T) + 9 * 11) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
-    FF, 3 in BF, 4 in BE), with two HBM byte counts beside it: `hbm_streamed` = what this build moves (the
-    materialised filter jets, 12 values per channel and row, and their adjoints) and `hbm_floor` = node
+    vector flop = 2 (nnz(T) + components * paths) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
+    FF, 3 in BF, 4 in BE; 83 + 9 * 11 for l <= 2, 353 + 16 * 23 for l <= 3), with two HBM byte counts beside it:
+    `hbm_streamed` = what this build moves (the materialised filter jets, 12 (24) values per channel and row, and their adjoints) and `hbm_floor` = node
     tables once plus 20 bytes per edge, what an implementation that recomputed the filters would move."""
     C, H, K = w.channels, w.edge_hidden, w.n_rbf
-    eqv = w.l_max == 2
-    Co = N_PATHS * C if eqv else C     # width of the radial filter per edge
-    Cs = 12 * C if eqv else C          # stored width (one pad per channel in the equivariant layout)
+    eqv = w.l_max >= 2
+    nnz, n_paths, n_comp, n_stored = COUPLINGS[w.l_max] if eqv else (0, 1, 1, 1)
+    Co = n_paths * C if eqv else C     # width of the radial filter per edge
+    Cs = n_stored * C if eqv else C    # stored width (one pad per channel in the equivariant layout)
     f4 = 4
     fj = 2 if (w.gemm_bf16 and not getattr(w, "filter_fp32", 0)) else 4   # filter jets
     fx = 2 if w.gemm_bf16 else 4                                           # their adjoints (matrix-product operands)
-    node = (9 if eqv else 1) * N * C * f4
+    node = n_comp * N * C * f4
     geo = 16 + 4                       # unit vector + length, sender index
     t = {
         1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H, {}),
@@ -73,7 +75,7 @@ def kernel_table(w, E, N):
     names = {3: "msg_fe", 4: "msg_ff", 5: "msg_bf", 6: "msg_be"}
     for kid in (3, 4, 5, 6):
         if eqv:
-            flop = 2.0 * (NNZ_COUPLINGS + 9 * N_PATHS) * C * E * (kid - 2)
+            flop = 2.0 * (nnz + n_comp * n_paths) * C * E * (kid - 2)
             t[kid] = (names[kid], "alu", flop, {"hbm_streamed_bytes": streamed[kid], "hbm_floor_bytes": tables[kid] * node + 20 * E})
         else:
             t[kid] = (names[kid], "hbm", streamed[kid], {})
@@ -139,7 +141,7 @@ def cpu_baseline(w, inp, budget_s=20.0):
     return out
 
 
-WORKLOAD_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg1_mole128": 1}
+WORKLOAD_INDEX = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg1_mole128": 1, "cfg2_lmax3": 2}
 
 
 def make_workload(name):
@@ -147,6 +149,8 @@ def make_workload(name):
     w = synth.WORKLOADS[WORKLOAD_INDEX[name]]
     if name == "cfg1_mole128":  # the invariant batch with UMA's 128-expert banks in the update MLP (Table 4)
         w = synth.shrink(w, n_experts=128, name="cfg1_invariant_batch_mole128")
+    if name == "cfg2_lmax3":    # the equivariant batch with features up to degree 3 (16 components, 23 coupling paths)
+        w = synth.shrink(w, l_max=3, name="cfg2_equivariant_batch_lmax3")
     return w
 
 
@@ -292,7 +296,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOAD_INDEX))
-    ap.add_argument("--others", default="cfg0,cfg1,cfg2,cfg3",
+    ap.add_argument("--others", default="cfg0,cfg1,cfg2,cfg3,cfg2_lmax3",
                     help="workloads measured with shorter runs and reported under per_workload")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -76,7 +76,7 @@ typedef struct {
   int32_t n_rbf;            /* K: multiple of 4 in [4, 1024] */
   int32_t edge_hidden;      /* H, multiple of 4 */
   int32_t edge_mlp_depth;   /* 2 or 3 */
-  int32_t l_max;            /* 0 (invariant, stage) or 2 (equivariant) */
+  int32_t l_max;            /* 0 (invariant, stage); 2 or 3 (equivariant: features up to that degree, 9 / 16 components, 11 / 23 coupling paths) */
   int32_t gemm_dtype;       /* MLIP_GEMM_FP32, or MLIP_GEMM_BF16: both operands of every matrix
                                product rounded to bf16 (nearest even), fp32 accumulation; the
                                radial-filter jets (outputs of such a product) are also kept in
@@ -94,7 +94,8 @@ typedef struct {
                                mixed-precision linear layer returns them (half the bytes of the largest edge tensor).
                                1: they are stored in fp32, so that bf16 rounding touches matrix-product operands only */
   int32_t position_grad;    /* 1: also allocate the workspace for the position gradient dL/dx (mlip_set_position_grad);
-                               0: none, and that call is refused */
+                               0: none, and that call is refused.  Not available with l_max = 3 (mlip_create returns
+                               MLIP_E_UNSUPPORTED): the second derivatives of the degree-3 harmonics are not built */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */

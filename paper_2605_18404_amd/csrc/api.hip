@@ -54,10 +54,10 @@ int layout_params(mlip_ctx* ctx) {
     LayerOffsets& lo = ctx->lay[l];
     lo.W[0] = off; off += H * K;
     if (c.model_kind == MLIP_MODEL_EQUIVARIANT) {
-      lo.W[1] = off; off += MLIP_NPATH * C * H;
+      lo.W[1] = off; off += (int64_t)mlip_npath(c.l_max) * C * H;
       lo.W[2] = -1;
       const int64_t banks = c.n_experts > 0 ? c.n_experts : 1;  // expert banks [n_experts][C][C]
-      for (int k = 0; k < 3; ++k) { lo.Wl[k] = off; off += banks * C * C; }
+      for (int k = 0; k <= c.l_max; ++k) { lo.Wl[k] = off; off += banks * C * C; }
     } else {
       if (c.edge_mlp_depth == 3) { lo.W[1] = off; off += H * H; lo.W[2] = off; off += C * H; }
       else { lo.W[1] = off; off += C * H; lo.W[2] = -1; }
@@ -83,8 +83,8 @@ const char* check_config(const mlip_config& c) {
   if (c.n_rbf < 4 || c.n_rbf % 4 || c.n_rbf > 1024) return "n_rbf must be a multiple of 4 in [4, 1024]";
   if (c.n_layers < 1 || c.n_layers > 64) return "n_layers must be in [1, 64]";
   if (c.edge_mlp_depth != 2 && c.edge_mlp_depth != 3) return "edge_mlp_depth must be 2 or 3";
-  if (c.model_kind == MLIP_MODEL_EQUIVARIANT ? (c.l_max != 2 || c.edge_mlp_depth != 2) : (c.l_max != 0))
-    return "l_max must be 2 (edge_mlp_depth 2) for the equivariant model and 0 otherwise";
+  if (c.model_kind == MLIP_MODEL_EQUIVARIANT ? ((c.l_max != 2 && c.l_max != 3) || c.edge_mlp_depth != 2) : (c.l_max != 0))
+    return "l_max must be 2 or 3 (edge_mlp_depth 2) for the equivariant model and 0 otherwise";
   if (c.model_kind != MLIP_MODEL_STAGE && c.n_species < 1) return "n_species must be positive";
   if (c.gemm_dtype != MLIP_GEMM_FP32 && c.gemm_dtype != MLIP_GEMM_BF16) return "gemm_dtype must be 0 or 1";
   if (c.n_experts < 0 || c.n_experts > 1024) return "n_experts must be in [0, 1024]";

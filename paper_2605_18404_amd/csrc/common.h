@@ -29,7 +29,14 @@
     if (_s != MLIP_OK) return _s; \
   } while (0)
 
-constexpr int MLIP_NPATH = 11;  // (l1,l2,l3), l <= 2, triangle rule, even parity
+// number of coupling paths (l1, l2, l3): every degree <= l_max, triangle rule, even parity (11 for l_max 2, 23 for 3)
+inline int mlip_npath(int l_max) {
+  int n = 0;
+  for (int a = 0; a <= l_max; ++a)
+    for (int b = 0; b <= l_max; ++b)
+      for (int c = (a > b ? a - b : b - a); c <= a + b && c <= l_max; ++c) n += ((a + b + c) % 2 == 0);
+  return n;
+}
 
 // Per-structure record used by the graph kernels (built on the host at graph build).
 enum CellKind { CELL_ORTHO = 0, CELL_TRICLINIC = 1, CELL_FREE = 2 };
@@ -56,7 +63,7 @@ enum Phase { PH_NONE = 0, PH_GRAPH = 1, PH_FE = 2, PH_FF = 3, PH_BF = 4, PH_BE =
 struct LayerOffsets {  // offsets (in floats) into the flat parameter vector
   int64_t W[3];        // edge MLP matrices (W[2] unused for depth 2)
   int64_t V1, V2;      // invariant update
-  int64_t Wl[3];       // equivariant per-l mixing
+  int64_t Wl[4];       // equivariant per-l mixing (l = 0..l_max)
 };
 
 struct mlip_ctx {

@@ -1,10 +1,12 @@
-// Equivariant (l <= 2) message-passing potential: FE / FF / BF / BE with hand-derived adjoints.
+// Equivariant message-passing potential (features up to degree l_max = 2 or 3): FE / FF / BF / BE with
+// hand-derived adjoints.  Everything that depends on l_max -- component and path counts, coupling
+// tables, the harmonics -- comes from G = gaunt::Tab<l_max>; kernels and phases are templates on G.
 //
-// Node features h[m][n][c], m = 0..8 the real spherical-harmonic component (l=0 | y,z,x | five
-// l=2), stored component-major so every l block is a plain [(2l+1) N, C] matrix for the per-l
+// Node features h[m][n][c], m = 0..NM-1 the real spherical-harmonic component (l=0 | y,z,x | five
+// l=2 | seven l=3), stored component-major so every l block is a plain [(2l+1) N, C] matrix for the per-l
 // channel mixing.  Messages:  m_e = B(rho_e, h_j, Y_e),  B(rho, x, y)[m3] = sum_p rho_p
 // sum_{m1 m2} T^p[m1 m2 m3] x[m1] y[m2]  (T = scaled real Gaunt couplings, gaunt_table.h),
-// rho_e = f_c(r) R(r) in R^{11 x C} the radial filter, carried with its r-derivative rho'_e as
+// rho_e = f_c(r) R(r) in R^{NPATH x C} the radial filter, carried with its r-derivative rho'_e as
 // a jet.  B is trilinear, so every derivative pass is B or one of its partial contractions:
 //   FE  a_i      = sum_e B(rho, h_j, Y)
 //   FF  mu_h[i] += sum_e B_x^T(rho, PY; mu_a[j])          (P = parity (-1)^l: the opposite edge
@@ -25,26 +27,24 @@
 
 namespace {
 
-using gaunt::NPATH;
-
 struct EqvWs {
   float* paramsT = nullptr;
   float* jphi = nullptr;  // [E][2][K]
   float2* env = nullptr;  // [E]
   std::vector<float*> U;    // [E][2][H]
   std::vector<__bf16*> SJ;  // bf16 GEMMs only: activated jets [E][2][H]
-  std::vector<float*> Rho;  // [E][2][C][12]: per channel the 11 path filters + one pad, operand precision (fp32 or bf16)
-  std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [12 C][H]
-  std::vector<float*> WpT;  // and their transpose [H][12 C]
-  float* gWp = nullptr;     // [12 C][H] weight gradient in the regrouped row order
-  std::vector<float*> Wm[3], WmT[3];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
-  float* cy = nullptr;      // [E][84] coupling coefficient x harmonic of the edge direction
-  float* cyd = nullptr;     // [E][84] the same with the directional derivative of the harmonics (BF, BE)
+  std::vector<float*> Rho;  // [E][2][C][NPP]: per channel the NPATH path filters + padding, operand precision (fp32 or bf16)
+  std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [NPP C][H]
+  std::vector<float*> WpT;  // and their transpose [H][NPP C]
+  float* gWp = nullptr;     // [NPP C][H] weight gradient in the regrouped row order
+  std::vector<float*> Wm[4], WmT[4];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
+  float* cy = nullptr;      // [E][CY_LD] coupling coefficient x harmonic of the edge direction
+  float* cyd = nullptr;     // [E][CY_LD] the same with the directional derivative of the harmonics (BF, BE)
   std::vector<float*> Y1;   // [E][H]  BF -> BE
-  float* X = nullptr;       // [E][C][12], operand precision
+  float* X = nullptr;       // [E][C][NPP], operand precision
   float* X2 = nullptr;      // [E][H]
-  std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [9][N][C]
-  std::vector<float*> u, mu_u, ud;  // gated update only, [9][N][C]: pre-activations W a, their FF cotangents, their BF tangents
+  std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [NM][N][C]
+  std::vector<float*> u, mu_u, ud;  // gated update only, [NM][N][C]: pre-activations W a, their FF cotangents, their BF tangents
   float* lam_u = nullptr;           // gated update only: BE adjoint of the pre-activations
   float* lam_h[2] = {nullptr, nullptr};
   float* lam_a = nullptr;
@@ -65,79 +65,130 @@ struct EqvWs {
 inline EqvWs* ws_of(mlip_ctx* ctx) { return (EqvWs*)ctx->model_ws; }
 
 // ------------------------------------------------------------------------------ geometry helpers
-__device__ __forceinline__ void sph_harm(float x, float y, float z, float (&Y)[9]) {
-  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+// Degree-3 harmonics (component normalisation, m = -3..3):  c35 y(3x^2 - y^2), c105 xyz, c21 y(5z^2 - 1), c7 z(5z^2 - 3),
+// c21 x(5z^2 - 1), (c105/2) z(x^2 - y^2), c35 x(x^2 - 3y^2).  Gradients below are those of these forms as polynomials;
+// every use projects them onto the tangent plane of the unit sphere, where the choice of form does not matter.
+constexpr float S3 = 1.7320508075688772f, S15 = 3.872983346207417f, S5 = 2.23606797749979f;
+constexpr float C35 = 2.0916500663351889f, C105 = 10.246950765959598f, C21 = 1.6201851746019651f, C7 = 1.3228756555322954f;
+
+template <int NM>
+__device__ __forceinline__ void sph_harm(float x, float y, float z, float (&Y)[NM]) {
   Y[0] = 1.f;
-  Y[1] = s3 * y; Y[2] = s3 * z; Y[3] = s3 * x;
-  Y[4] = s15 * x * y; Y[5] = s15 * y * z; Y[6] = 0.5f * s5 * (3.f * z * z - 1.f); Y[7] = s15 * x * z;
-  Y[8] = 0.5f * s15 * (x * x - y * y);
+  Y[1] = S3 * y; Y[2] = S3 * z; Y[3] = S3 * x;
+  Y[4] = S15 * x * y; Y[5] = S15 * y * z; Y[6] = 0.5f * S5 * (3.f * z * z - 1.f); Y[7] = S15 * x * z;
+  Y[8] = 0.5f * S15 * (x * x - y * y);
+  if constexpr (NM == 16) {
+    const float f = 5.f * z * z - 1.f;
+    Y[9] = C35 * y * (3.f * x * x - y * y);
+    Y[10] = C105 * x * y * z;
+    Y[11] = C21 * y * f;
+    Y[12] = C7 * z * (f - 2.f);
+    Y[13] = C21 * x * f;
+    Y[14] = 0.5f * C105 * z * (x * x - y * y);
+    Y[15] = C35 * x * (x * x - 3.f * y * y);
+  }
 }
 // w = sum_m nu[m] grad_u Y_m  (polynomial gradient at the unit vector u)
-__device__ __forceinline__ float3 sph_grad_T(float x, float y, float z, const float (&nu)[9]) {
-  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+template <int NM>
+__device__ __forceinline__ float3 sph_grad_T(float x, float y, float z, const float (&nu)[NM]) {
   float3 w;
-  w.x = s3 * nu[3] + s15 * (y * nu[4] + z * nu[7] + x * nu[8]);
-  w.y = s3 * nu[1] + s15 * (x * nu[4] + z * nu[5] - y * nu[8]);
-  w.z = s3 * nu[2] + s15 * (y * nu[5] + x * nu[7]) + 3.f * s5 * z * nu[6];
+  w.x = S3 * nu[3] + S15 * (y * nu[4] + z * nu[7] + x * nu[8]);
+  w.y = S3 * nu[1] + S15 * (x * nu[4] + z * nu[5] - y * nu[8]);
+  w.z = S3 * nu[2] + S15 * (y * nu[5] + x * nu[7]) + 3.f * S5 * z * nu[6];
+  if constexpr (NM == 16) {
+    const float f = 5.f * z * z - 1.f, q = x * x - y * y;
+    w.x += C35 * (6.f * x * y * nu[9] + 3.f * q * nu[15]) + C105 * (y * z * nu[10] + x * z * nu[14]) + C21 * f * nu[13];
+    w.y += C35 * (3.f * q * nu[9] - 6.f * x * y * nu[15]) + C105 * (x * z * nu[10] - y * z * nu[14]) + C21 * f * nu[11];
+    w.z += C105 * (x * y * nu[10] + 0.5f * q * nu[14]) + 10.f * C21 * z * (y * nu[11] + x * nu[13]) + C7 * (15.f * z * z - 3.f) * nu[12];
+  }
   return w;
 }
 // Ydot = (dY/dr_vec) d = grad_u Y . d_perp / r,  d_perp = d - u (u.d)
-__device__ __forceinline__ void sph_dot(float x, float y, float z, float r, float3 d, float (&Yd)[9]) {
-  const float s3 = 1.7320508075688772f, s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+template <int NM>
+__device__ __forceinline__ void sph_dot(float x, float y, float z, float r, float3 d, float (&Yd)[NM]) {
   float ud = x * d.x + y * d.y + z * d.z;
   float inv = 1.f / r;
   float px = (d.x - x * ud) * inv, py = (d.y - y * ud) * inv, pz = (d.z - z * ud) * inv;
   Yd[0] = 0.f;
-  Yd[1] = s3 * py; Yd[2] = s3 * pz; Yd[3] = s3 * px;
-  Yd[4] = s15 * (y * px + x * py);
-  Yd[5] = s15 * (z * py + y * pz);
-  Yd[6] = 3.f * s5 * z * pz;
-  Yd[7] = s15 * (z * px + x * pz);
-  Yd[8] = s15 * (x * px - y * py);
+  Yd[1] = S3 * py; Yd[2] = S3 * pz; Yd[3] = S3 * px;
+  Yd[4] = S15 * (y * px + x * py);
+  Yd[5] = S15 * (z * py + y * pz);
+  Yd[6] = 3.f * S5 * z * pz;
+  Yd[7] = S15 * (z * px + x * pz);
+  Yd[8] = S15 * (x * px - y * py);
+  if constexpr (NM == 16) {
+    const float f = 5.f * z * z - 1.f, q = x * x - y * y;
+    Yd[9] = C35 * (6.f * x * y * px + 3.f * q * py);
+    Yd[10] = C105 * (y * z * px + x * z * py + x * y * pz);
+    Yd[11] = C21 * (f * py + 10.f * y * z * pz);
+    Yd[12] = C7 * (15.f * z * z - 3.f) * pz;
+    Yd[13] = C21 * (f * px + 10.f * x * z * pz);
+    Yd[14] = C105 * (x * z * px - y * z * py + 0.5f * q * pz);
+    Yd[15] = C35 * (3.f * q * px - 6.f * x * y * py);
+  }
 }
 __device__ __forceinline__ void parity(const float (&a)[9], float (&b)[9]) {
 #pragma unroll
   for (int m = 0; m < 9; ++m) b[m] = (m >= 1 && m <= 3) ? -a[m] : a[m];
 }
-__device__ __forceinline__ void load9(const float* __restrict__ t, int64_t NC, int64_t off, float (&x)[9]) {
+template <int NM>
+__device__ __forceinline__ void loadm(const float* __restrict__ t, int64_t NC, int64_t off, float (&x)[NM]) {
 #pragma unroll
-  for (int m = 0; m < 9; ++m) x[m] = t[m * NC + off];
+  for (int m = 0; m < NM; ++m) x[m] = t[m * NC + off];
 }
-// The filter jets and their adjoints are stored per edge as [C][NPP]: the 11 path values of one
-// channel are contiguous (plus one zero pad), so a thread moves them with three wide accesses
-// instead of eleven narrow ones.
-constexpr int NPP = 12;
-__device__ __forceinline__ void load_rho(const float* __restrict__ row, int c, float (&rho)[NPATH]) {
-  const float4* q = reinterpret_cast<const float4*>(row + c * NPP);
-  const float4 a = q[0], b = q[1], d = q[2];
-  rho[0] = a.x; rho[1] = a.y; rho[2] = a.z; rho[3] = a.w;
-  rho[4] = b.x; rho[5] = b.y; rho[6] = b.z; rho[7] = b.w;
-  rho[8] = d.x; rho[9] = d.y; rho[10] = d.z;
-}
+// The filter jets and their adjoints are stored per edge as [C][NPP]: the NPATH path values of one channel are
+// contiguous (padded to a multiple of four), so a thread moves them with a few wide accesses instead of NPATH narrow ones.
 __device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-__device__ __forceinline__ void load_rho(const __bf16* __restrict__ row, int c, float (&rho)[NPATH]) {
-  const uint2* q = reinterpret_cast<const uint2*>(row + c * NPP);
-  const uint2 a = q[0], b = q[1], d = q[2];
-  rho[0] = bf_lo(a.x); rho[1] = bf_hi(a.x); rho[2] = bf_lo(a.y); rho[3] = bf_hi(a.y);
-  rho[4] = bf_lo(b.x); rho[5] = bf_hi(b.x); rho[6] = bf_lo(b.y); rho[7] = bf_hi(b.y);
-  rho[8] = bf_lo(d.x); rho[9] = bf_hi(d.x); rho[10] = bf_lo(d.y);
-}
-__device__ __forceinline__ void store_paths(float* __restrict__ row, int c, const float (&x)[NPATH]) {
-  float4* q = reinterpret_cast<float4*>(row + c * NPP);
-  q[0] = make_float4(x[0], x[1], x[2], x[3]);
-  q[1] = make_float4(x[4], x[5], x[6], x[7]);
-  q[2] = make_float4(x[8], x[9], x[10], 0.f);
-}
 __device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
   __bf16 a = (__bf16)lo, b = (__bf16)hi;
   return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
 }
+template <int NPATH>
+__device__ __forceinline__ void load_rho(const float* __restrict__ row, int c, float (&rho)[NPATH]) {
+  constexpr int NPP = (NPATH + 3) / 4 * 4;
+  const float4* q = reinterpret_cast<const float4*>(row + c * NPP);
+#pragma unroll
+  for (int k = 0; k < NPP / 4; ++k) {
+    const float4 a = q[k];
+    const float v[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (4 * k + j < NPATH) rho[4 * k + j] = v[j];
+  }
+}
+template <int NPATH>
+__device__ __forceinline__ void load_rho(const __bf16* __restrict__ row, int c, float (&rho)[NPATH]) {
+  constexpr int NPP = (NPATH + 3) / 4 * 4;
+  const uint2* q = reinterpret_cast<const uint2*>(row + c * NPP);
+#pragma unroll
+  for (int k = 0; k < NPP / 4; ++k) {
+    const uint2 a = q[k];
+    const float v[4] = {bf_lo(a.x), bf_hi(a.x), bf_lo(a.y), bf_hi(a.y)};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (4 * k + j < NPATH) rho[4 * k + j] = v[j];
+  }
+}
+template <int NPATH>
+__device__ __forceinline__ void store_paths(float* __restrict__ row, int c, const float (&x)[NPATH]) {
+  constexpr int NPP = (NPATH + 3) / 4 * 4;
+  float4* q = reinterpret_cast<float4*>(row + c * NPP);
+#pragma unroll
+  for (int k = 0; k < NPP / 4; ++k)
+    q[k] = make_float4(x[4 * k], 4 * k + 1 < NPATH ? x[4 * k + 1 < NPATH ? 4 * k + 1 : 0] : 0.f, 4 * k + 2 < NPATH ? x[4 * k + 2 < NPATH ? 4 * k + 2 : 0] : 0.f,
+                       4 * k + 3 < NPATH ? x[4 * k + 3 < NPATH ? 4 * k + 3 : 0] : 0.f);
+}
+template <int NPATH>
 __device__ __forceinline__ void store_paths(__bf16* __restrict__ row, int c, const float (&x)[NPATH]) {
+  constexpr int NPP = (NPATH + 3) / 4 * 4;
   uint2* q = reinterpret_cast<uint2*>(row + c * NPP);
-  q[0] = make_uint2(bf_pack(x[0], x[1]), bf_pack(x[2], x[3]));
-  q[1] = make_uint2(bf_pack(x[4], x[5]), bf_pack(x[6], x[7]));
-  q[2] = make_uint2(bf_pack(x[8], x[9]), bf_pack(x[10], 0.f));
+#pragma unroll
+  for (int k = 0; k < NPP / 4; ++k) {
+    const float b1 = 4 * k + 1 < NPATH ? x[4 * k + 1 < NPATH ? 4 * k + 1 : 0] : 0.f, b2 = 4 * k + 2 < NPATH ? x[4 * k + 2 < NPATH ? 4 * k + 2 : 0] : 0.f,
+                b3 = 4 * k + 3 < NPATH ? x[4 * k + 3 < NPATH ? 4 * k + 3 : 0] : 0.f;
+    q[k] = make_uint2(bf_pack(x[4 * k], b1), bf_pack(b2, b3));
+  }
 }
 
 struct RowChan {
@@ -161,56 +212,59 @@ __device__ __forceinline__ RowChan row_chan(int N, int C) {
 // each term costs one multiply-add here.  With UNI (C a multiple of 64) all lanes of a wave
 // share the row: the edge index is made wave-uniform, and the per-edge tables, indices and
 // geometry then arrive through scalar loads.
-using gaunt::CY_LD;
-using gaunt::NNZ;
-using gaunt::NSLOT;
-
 template <bool UNI>
 __device__ __forceinline__ int uni(int x) { return UNI ? __builtin_amdgcn_readfirstlane(x) : x; }
 
-// UNI: the 64 lanes fetch the edge's table with two coalesced loads and publish it in the
+// UNI: the 64 lanes fetch the edge's table with TAB_LOADS coalesced loads and publish it in the
 // wave's own LDS slot, from where every lane reads the entries it needs as broadcasts.  (LDS
 // operations of one wave execute in order, so the next edge's copy cannot overtake the reads.)
-struct TabRegs { float a, b; };
-__device__ __forceinline__ TabRegs tab_fetch(const float* __restrict__ src, int lane) {
-  TabRegs r;
-  r.a = src[lane];
-  r.b = src[64 + lane];  // runs into the next edge's table (the allocation is padded): no branch
+template <typename G>
+struct TabRegs { float v[G::TAB_LOADS]; };
+template <typename G>
+__device__ __forceinline__ TabRegs<G> tab_fetch(const float* __restrict__ src, int lane) {
+  TabRegs<G> r;
+#pragma unroll
+  for (int k = 0; k < G::TAB_LOADS; ++k) r.v[k] = src[64 * k + lane];  // runs into the next edge's table (the allocation is padded): no branch
   return r;
 }
-__device__ __forceinline__ void tab_publish(const TabRegs& r, float* slot, int lane) {
-  slot[lane] = r.a;
-  slot[64 + lane] = r.b;
+template <typename G>
+__device__ __forceinline__ void tab_publish(const TabRegs<G>& r, float* slot, int lane) {
+#pragma unroll
+  for (int k = 0; k < G::TAB_LOADS; ++k) slot[64 * k + lane] = r.v[k];
   __builtin_amdgcn_wave_barrier();
 }
 
-// S[slot (p, m3)] (+)= sum_n cy[n] x[m1_n]
-template <bool ACC>
-__device__ __forceinline__ void contract_x(const float* __restrict__ cy, const float (&x)[9], float (&S)[NSLOT]) {
+// The coupling entries n = (p; m1, m2, m3) are ordered by slot (p, m3), so a slot's entries are consecutive: sums over a
+// slot's entries are kept in one register and handed on at the slot's last entry (ENT_SFIRST / ENT_SLAST), and a value that
+// belongs to the slot is formed at its first entry.  No array over the slots is ever held.
+template <int N>
+__device__ __forceinline__ void zero(float (&x)[N]) {
 #pragma unroll
-  for (int n = 0; n < NNZ; ++n) {
-    const int sl = gaunt::ENT_SLOT[n];
-    if (!ACC && (n == 0 || gaunt::ENT_SLOT[n > 0 ? n - 1 : 0] != sl))
-      S[sl] = cy[n] * x[gaunt::ENT_M1[n]];
-    else
-      S[sl] = fmaf(cy[n], x[gaunt::ENT_M1[n]], S[sl]);
+  for (int k = 0; k < N; ++k) x[k] = 0.f;
+}
+// f(integral_constant<int, k>) for k = B..E-1, in order: the loops over the coupling entries index register arrays through
+// tables, so every index must be a constant -- a loop the compiler leaves rolled would turn those arrays into scratch memory.
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (E - B == 1) {
+    f(std::integral_constant<int, B>{});
+  } else if constexpr (E - B > 1) {
+    static_for<B, (B + E) / 2>(f);
+    static_for<(B + E) / 2, E>(f);
   }
 }
-// out[m1] += sum_n cy[n] R[slot_n]
-__device__ __forceinline__ void adj_x_from(const float* __restrict__ cy, const float (&R)[NSLOT], float (&out)[9]) {
-#pragma unroll
-  for (int n = 0; n < NNZ; ++n) out[gaunt::ENT_M1[n]] = fmaf(cy[n], R[gaunt::ENT_SLOT[n]], out[gaunt::ENT_M1[n]]);
-}
 
-template <typename TF, bool UNI>
+template <typename G, typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD;
   RowChan t = row_chan(N, C);
   if (!t.active) return;  // no workgroup barrier below
   const int64_t NC = (int64_t)N * C;
-  float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  __shared__ float tabs[4][128];
+  float acc[NM];
+  zero(acc);
+  __shared__ float tabs[4][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6];
   const int lane = threadIdx.x & 63;
   const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
@@ -218,38 +272,43 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
   for (int e = e0; e < e1; ++e) {
     const int j = jn;
     jn = sender[e + 1 < e1 ? e + 1 : e];  // next edge's sender: its gathers need not wait for an index
-    float x[9], rho[NPATH], S[NSLOT];
+    float x[NM], rho[NPATH];
     const float* cy = cyt + (int64_t)e * CY_LD;
-    TabRegs tr;
-    if constexpr (UNI) tr = tab_fetch(cy, lane);
-    load9(h, NC, (int64_t)j * C + t.c, x);
+    TabRegs<G> tr;
+    if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
+    loadm(h, NC, (int64_t)j * C + t.c, x);
     load_rho(Rho + (int64_t)(2 * e) * NPP * C, t.c, rho);
-    if constexpr (UNI) { tab_publish(tr, slot, lane); cy = slot; }
-    contract_x<false>(cy, x, S);
-#pragma unroll
-    for (int sl = 0; sl < NSLOT; ++sl) acc[gaunt::SLOT_M3[sl]] = fmaf(rho[gaunt::SLOT_P[sl]], S[sl], acc[gaunt::SLOT_M3[sl]]);
+    if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
+    float S = 0.f;  // sum_n cy[n] x[m1_n] over the entries of one slot
+    static_for<0, G::NNZ>([&](auto n_) {
+      constexpr int n = decltype(n_)::value;
+      constexpr int sl = G::ENT_SLOT[n];
+      S = G::ENT_SFIRST[n] ? cy[n] * x[G::ENT_M1[n]] : fmaf(cy[n], x[G::ENT_M1[n]], S);
+      if (G::ENT_SLAST[n]) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], S, acc[G::SLOT_M3[sl]]);
+    });
   }
 #pragma unroll
-  for (int m = 0; m < 9; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
+  for (int m = 0; m < NM; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
 }
 
-template <typename TF, bool UNI>
+template <typename G, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
                                                   const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
                                                   int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   __shared__ float3 red[256];
-  __shared__ float tabs[4][128];
+  __shared__ float tabs[4][64 * G::TAB_LOADS];
   RowChan t = row_chan(N, C);
   float3 f = make_float3(0.f, 0.f, 0.f);
   if (t.active) {
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
-    float acc[9], xi[9], mi[9];
-    load9(mu_h_next, NC, io, acc);
-    load9(h, NC, io, xi);
-    load9(mu_a, NC, io, mi);
+    float acc[NM], xi[NM], mi[NM];
+    loadm(mu_h_next, NC, io, acc);
+    loadm(h, NC, io, xi);
+    loadm(mu_a, NC, io, mi);
     float* slot = tabs[threadIdx.x >> 6];
     const int lane = threadIdx.x & 63;
     const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
@@ -259,44 +318,63 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       jn = sender[e + 1 < e1 ? e + 1 : e];
       const float4 g = geo[e];
       const float* cy = cyt + (int64_t)e * CY_LD;
-      TabRegs tr;
-      if constexpr (UNI) tr = tab_fetch(cy, lane);
-      float xj[9], mj[9], rho[NPATH], rhop[NPATH];
+      TabRegs<G> tr;
+      if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
+      float xj[NM], mj[NM], rho[NPATH], rhop[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
-      load9(h, NC, jo, xj);
-      load9(mu_a, NC, jo, mj);
+      loadm(h, NC, jo, xj);
+      loadm(mu_a, NC, jo, mj);
       const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
       load_rho(rrow, t.c, rho);
       load_rho(rrow + NPP * C, t.c, rhop);
-      if constexpr (UNI) { tab_publish(tr, slot, lane); cy = slot; }
+      if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
       {  // the message this atom sends back along the reversed edge: couplings of -u
-        float R[NSLOT];
-#pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl) R[sl] = gaunt::PATH_SIGN[gaunt::SLOT_P[sl]] * rho[gaunt::SLOT_P[sl]] * mj[gaunt::SLOT_M3[sl]];
-        adj_x_from(cy, R, acc);
+        float R = 0.f;
+        static_for<0, G::NNZ>([&](auto n_) {
+          constexpr int n = decltype(n_)::value;
+          constexpr int sl = G::ENT_SLOT[n];
+          if (G::ENT_SFIRST[n]) R = G::PATH_SIGN[G::SLOT_P[sl]] * rho[G::SLOT_P[sl]] * mj[G::SLOT_M3[sl]];
+          acc[G::ENT_M1[n]] = fmaf(cy[n], R, acc[G::ENT_M1[n]]);
+        });
       }
       // Force terms.  With W_n = x_j[m1] mu_i[m3] + sign_p x_i[m1] mu_j[m3] per coupling entry n = (p; m1, m2, m3), formed
       // once, both directions of the edge pair give
       //   radial:  s = sum_p rho'_p sum_{n in p} (T_n Y[m2]) W_n,      angular:  nu[m2] = sum_p rho_p sum_{n in (p, m2)} T_n W_n
       // (the opposite edge sees the harmonics of -u, i.e. the path's parity sign).
-      float sp[NPATH], G[gaunt::NYSLOT];
-#pragma unroll
-      for (int n = 0; n < NNZ; ++n) {
-        const int sl = gaunt::ENT_SLOT[n], p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl], m1 = gaunt::ENT_M1[n], ys = gaunt::ENT_YSLOT[n];
-        const float W = fmaf(gaunt::PATH_SIGN[p] * xi[m1], mj[m3], xj[m1] * mi[m3]);
-        const bool first_p = n == 0 || gaunt::SLOT_P[gaunt::ENT_SLOT[n > 0 ? n - 1 : 0]] != p;
-        sp[p] = first_p ? cy[n] * W : fmaf(cy[n], W, sp[p]);
-        bool first_y = true;
-#pragma unroll
-        for (int q = 0; q < n; ++q) first_y = first_y && gaunt::ENT_YSLOT[q] != ys;
-        G[ys] = first_y ? gaunt::ENT_COEF[n] * W : fmaf(gaunt::ENT_COEF[n], W, G[ys]);
-      }
       float s = 0.f;
+      float nu[NM];
+      zero(nu);
+      if constexpr (G::LMAX == 2) {
+        // few entries: the per-path and per-(path, m2) sums are kept side by side while the entries are walked in table order,
+        // the order in which the loop above has left the table's values in registers
+        float sp[NPATH], Gy[G::NYSLOT];
+        static_for<0, G::NNZ>([&](auto n_) {
+          constexpr int n = decltype(n_)::value;
+          constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n], ys = G::ENT_YSLOT[n];
+          const float W = fmaf(G::PATH_SIGN[p] * xi[m1], mj[m3], xj[m1] * mi[m3]);
+          sp[p] = G::ENT_PFIRST[n] ? cy[n] * W : fmaf(cy[n], W, sp[p]);
+          Gy[ys] = G::ENT_YFIRST[n] ? G::ENT_COEF[n] * W : fmaf(G::ENT_COEF[n], W, Gy[ys]);
+        });
 #pragma unroll
-      for (int p = 0; p < NPATH; ++p) s = fmaf(rhop[p], sp[p], s);
-      float nu[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < NPATH; ++p) s = fmaf(rhop[p], sp[p], s);
 #pragma unroll
-      for (int ys = 0; ys < gaunt::NYSLOT; ++ys) nu[gaunt::YSLOT_M2[ys]] = fmaf(rho[gaunt::YSLOT_P[ys]], G[ys], nu[gaunt::YSLOT_M2[ys]]);
+        for (int ys = 0; ys < G::NYSLOT; ++ys) nu[G::YSLOT_M2[ys]] = fmaf(rho[G::YSLOT_P[ys]], Gy[ys], nu[G::YSLOT_M2[ys]]);
+      } else {
+        // many entries: they are walked in the order (path, m2), in which the runs of one (path, m2) pair and of one path are
+        // consecutive, so both sums stay in one register each; the table is read again rather than kept from the loop above
+        asm volatile("" ::: "memory");
+        float sp = 0.f, gy = 0.f;
+        static_for<0, G::NNZ>([&](auto k_) {
+          constexpr int k = decltype(k_)::value;
+          constexpr int n = G::YORD[k];
+          constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n], m2 = G::ENT_M2[n];
+          const float W = fmaf(G::PATH_SIGN[p] * xi[m1], mj[m3], xj[m1] * mi[m3]);
+          sp = G::YORD_PFIRST[k] ? cy[n] * W : fmaf(cy[n], W, sp);
+          gy = G::YORD_YFIRST[k] ? G::ENT_COEF[n] * W : fmaf(G::ENT_COEF[n], W, gy);
+          if (G::YORD_YLAST[k]) nu[m2] = fmaf(rho[p], gy, nu[m2]);
+          if (G::YORD_PLAST[k]) s = fmaf(rhop[p], sp, s);
+        });
+      }
       float3 w = sph_grad_T(g.x, g.y, g.z, nu);
       float uw = g.x * w.x + g.y * w.y + g.z * w.z;
       float inv = 1.f / g.w;
@@ -305,7 +383,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       f.z += s * g.z + (w.z - g.z * uw) * inv;
     }
 #pragma unroll
-    for (int m = 0; m < 9; ++m) mu_h[m * NC + io] = acc[m];
+    for (int m = 0; m < NM; ++m) mu_h[m * NC + io] = acc[m];
   }
   red[threadIdx.x] = f;
   __syncthreads();
@@ -321,7 +399,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
   }
 }
 
-template <typename TX, typename TF, bool UNI>
+template <typename G, typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -329,14 +407,16 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a, int N, int C,
                                                   float* __restrict__ ad,
                                                   TX* __restrict__ X) {
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
   const int64_t io = (int64_t)t.row * C + t.c;
-  float mi[9];
-  load9(mu_a, NC, io, mi);
-  float acc[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  __shared__ float tabs[4][2][128];
+  float mi[NM];
+  loadm(mu_a, NC, io, mi);
+  float acc[NM];
+  zero(acc);
+  __shared__ float tabs[4][2][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6][0];
   float* slotd = tabs[threadIdx.x >> 6][1];
   const int lane = threadIdx.x & 63;
@@ -347,44 +427,49 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     jn = sender[e + 1 < e1 ? e + 1 : e];
     const float* cy = cyt + (int64_t)e * CY_LD;
     const float* cyd = cydt + (int64_t)e * CY_LD;
-    TabRegs tr, trd;
-    if constexpr (UNI) { tr = tab_fetch(cy, lane); trd = tab_fetch(cyd, lane); }
-    float xj[9], xdj[9], rho[NPATH], rr[NPATH];
+    TabRegs<G> tr, trd;
+    if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
+    float xj[NM], xdj[NM], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
-    load9(h, NC, jo, xj);
-    load9(hd, NC, jo, xdj);
+    loadm(h, NC, jo, xj);
+    loadm(hd, NC, jo, xdj);
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
-    if constexpr (UNI) { tab_publish(tr, slot, lane); tab_publish(trd, slotd, lane); cy = slot; cyd = slotd; }
+    if constexpr (UNI) { tab_publish<G>(tr, slot, lane); tab_publish<G>(trd, slotd, lane); cy = slot; cyd = slotd; }
     const float rd = cyd[NNZ];  // u . (v_sender - v_receiver), stored behind the table
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
-    // d/dt of the message: (rdot rho') T x Y + rho T xdot Y + rho T x Ydot
-    float S1[NSLOT], S23[NSLOT];
-    contract_x<false>(cy, xj, S1);
-    contract_x<false>(cy, xdj, S23);
-    contract_x<true>(cyd, xj, S23);
-    float tp[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int sl = 0; sl < NSLOT; ++sl) {
-      const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
-      acc[m3] = fmaf(rr[p], S1[sl], fmaf(rho[p], S23[sl], acc[m3]));
-      tp[p] = fmaf(mi[m3], S1[sl], tp[p]);
-    }
+    // d/dt of the message: (rdot rho') T x Y + rho T xdot Y + rho T x Ydot; per slot S1 = sum cy x, S23 = sum cy xdot + cyd x
+    float tp[NPATH];
+    zero(tp);
+    float S1 = 0.f, S23 = 0.f;
+    static_for<0, G::NNZ>([&](auto n_) {
+      constexpr int n = decltype(n_)::value;
+      constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n];
+      S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
+      S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
+      S23 = fmaf(cyd[n], xj[m1], S23);
+      if (G::ENT_SLAST[n]) {
+        acc[m3] = fmaf(rr[p], S1, fmaf(rho[p], S23, acc[m3]));
+        tp[p] = fmaf(mi[m3], S1, tp[p]);
+      }
+    });
     const float s = rd * env[e].x;
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) tp[p] *= s;
     store_paths(X + (int64_t)e * NPP * C, t.c, tp);
   }
 #pragma unroll
-  for (int m = 0; m < 9; ++m) ad[m * NC + io] = acc[m];
+  for (int m = 0; m < NM; ++m) ad[m * NC + io] = acc[m];
 }
 
 // (Writing the adjoint of the OPPOSITE edge instead -- X[rev(e)] from this row's own features and the sender's adjoints,
 // which halves the gathers and pays off in the invariant model's kernel -- was measured slower here: the rows of X are then
-// written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.)
-template <typename TX, typename TF, bool UNI>
+// written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.
+// Holding an edge's row of X back for one trip of the loop, so that its stores follow the next edge's loads, changed nothing:
+// two waves per SIMD already cover the store acknowledgements.)
+template <typename G, typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -392,15 +477,16 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                   const float* __restrict__ lam_a, const float* __restrict__ lam_h_next, int N, int C,
                                                   float* __restrict__ lam_h, TX* __restrict__ X) {
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
   const int64_t io = (int64_t)t.row * C + t.c;
-  float mi[9], li[9], acc[9];
-  load9(mu_a, NC, io, mi);
-  load9(lam_a, NC, io, li);
-  load9(lam_h_next, NC, io, acc);
-  __shared__ float tabs[4][2][128];
+  float mi[NM], li[NM], acc[NM];
+  loadm(mu_a, NC, io, mi);
+  loadm(lam_a, NC, io, li);
+  loadm(lam_h_next, NC, io, acc);
+  __shared__ float tabs[4][2][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6][0];
   float* slotd = tabs[threadIdx.x >> 6][1];
   const int lane = threadIdx.x & 63;
@@ -411,45 +497,44 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     jn = sender[e + 1 < e1 ? e + 1 : e];
     const float* cy = cyt + (int64_t)e * CY_LD;
     const float* cyd = cydt + (int64_t)e * CY_LD;
-    TabRegs tr, trd;
-    if constexpr (UNI) { tr = tab_fetch(cy, lane); trd = tab_fetch(cyd, lane); }
-    float xj[9], xdj[9], lj[9], mj[9], rho[NPATH], rr[NPATH];
+    TabRegs<G> tr, trd;
+    if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
+    float xj[NM], xdj[NM], lj[NM], mj[NM], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
-    load9(h, NC, jo, xj);
-    load9(hd, NC, jo, xdj);
-    load9(lam_a, NC, jo, lj);
-    load9(mu_a, NC, jo, mj);
+    loadm(h, NC, jo, xj);
+    loadm(hd, NC, jo, xdj);
+    loadm(lam_a, NC, jo, lj);
+    loadm(mu_a, NC, jo, mj);
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
-    if constexpr (UNI) { tab_publish(tr, slot, lane); tab_publish(trd, slotd, lane); cy = slot; cyd = slotd; }
+    if constexpr (UNI) { tab_publish<G>(tr, slot, lane); tab_publish<G>(trd, slotd, lane); cy = slot; cyd = slotd; }
     const float rd = cyd[NNZ];  // u . (v_sender - v_receiver), stored behind the table
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
-    {  // adjoint of the sender's features along the reversed edge (couplings of -u)
-      float R[NSLOT];
-#pragma unroll
-      for (int sl = 0; sl < NSLOT; ++sl) {
-        const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
-        R[sl] = gaunt::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
+    // Per slot: R1, R2 = what the reversed edge (couplings of -u) hands back to this atom's features through cy and cyd;
+    // S1 = sum cy x, S23 = sum cy xdot + cyd x feed the adjoint of the filter jets:
+    // value row  c (t(x,Y,lam) + t(xdot,Y,mu) + t(x,Ydot,mu)) + c' rdot t(x,Y,mu)
+    float ta[NPATH], t4[NPATH];
+    zero(ta);
+    zero(t4);
+    float R1 = 0.f, R2 = 0.f, S1 = 0.f, S23 = 0.f;
+    static_for<0, G::NNZ>([&](auto n_) {
+      constexpr int n = decltype(n_)::value;
+      constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n];
+      if (G::ENT_SFIRST[n]) {
+        R2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
+        R1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
       }
-      adj_x_from(cy, R, acc);
-#pragma unroll
-      for (int sl = 0; sl < NSLOT; ++sl) R[sl] = gaunt::PATH_SIGN[gaunt::SLOT_P[sl]] * rho[gaunt::SLOT_P[sl]] * mj[gaunt::SLOT_M3[sl]];
-      adj_x_from(cyd, R, acc);
-    }
-    // adjoint of the filter jets: value row  c (t(x,Y,lam) + t(xdot,Y,mu) + t(x,Ydot,mu)) + c' rdot t(x,Y,mu)
-    float S1[NSLOT], S23[NSLOT];
-    contract_x<false>(cy, xj, S1);
-    contract_x<false>(cy, xdj, S23);
-    contract_x<true>(cyd, xj, S23);
-    float ta[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, t4[NPATH] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int sl = 0; sl < NSLOT; ++sl) {
-      const int p = gaunt::SLOT_P[sl], m3 = gaunt::SLOT_M3[sl];
-      ta[p] = fmaf(li[m3], S1[sl], fmaf(mi[m3], S23[sl], ta[p]));
-      t4[p] = fmaf(mi[m3], S1[sl], t4[p]);
-    }
+      acc[m1] = fmaf(cyd[n], R2, fmaf(cy[n], R1, acc[m1]));
+      S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
+      S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
+      S23 = fmaf(cyd[n], xj[m1], S23);
+      if (G::ENT_SLAST[n]) {
+        ta[p] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[p]));
+        t4[p] = fmaf(mi[m3], S1, t4[p]);
+      }
+    });
     const float2 cc = env[e];
     const float s = cc.y * rd;
 #pragma unroll
@@ -457,7 +542,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     store_paths(X + (int64_t)e * NPP * C, t.c, ta);
   }
 #pragma unroll
-  for (int m = 0; m < 9; ++m) lam_h[m * NC + io] = acc[m];
+  for (int m = 0; m < NM; ++m) lam_h[m * NC + io] = acc[m];
 }
 
 
@@ -494,7 +579,9 @@ __device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, floa
 //   J = dY/dr_vec, K = d(Ydot)/dr_vec (second derivatives of the harmonics, sph_hess_apply).
 // Atom i takes -dPsi/dr_vec of the edges it receives and +dPsi/dr_vec of those it sends; the opposite edge (same r, rdot;
 // u, dv negated; Y -> PY) is formed here too, from the row's own node values and the gathered sender's.
-// One thread per (receiver row, channel), straight-line couplings; off the timed path.
+// One thread per (receiver row, channel), straight-line couplings; off the timed path.  Built for l_max = 2 only
+// (the second derivatives of the degree-3 harmonics are not constant; a context with l_max = 3 refuses position_grad).
+constexpr int NPATH = gaunt::Tab<2>::NPATH, NPP = gaunt::Tab<2>::NPP;
 __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
                                                const float* __restrict__ Rj, const float* __restrict__ Rpp,
@@ -508,10 +595,10 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
     float xi[9], xdi[9], li[9], mi[9];
-    load9(h, NC, io, xi);
-    load9(hd, NC, io, xdi);
-    load9(lam_a, NC, io, li);
-    load9(mu_a, NC, io, mi);
+    loadm(h, NC, io, xi);
+    loadm(hd, NC, io, xdi);
+    loadm(lam_a, NC, io, li);
+    loadm(mu_a, NC, io, mi);
     const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
     for (int e = row_ptr[t.row]; e < row_ptr[t.row + 1]; ++e) {
       const int j = sender[e];
@@ -521,10 +608,10 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
       const float rd = g.x * d.x + g.y * d.y + g.z * d.z;
       float xj[9], xdj[9], lj[9], mj[9], R[NPATH], Rp[NPATH], Rq[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
-      load9(h, NC, jo, xj);
-      load9(hd, NC, jo, xdj);
-      load9(lam_a, NC, jo, lj);
-      load9(mu_a, NC, jo, mj);
+      loadm(h, NC, jo, xj);
+      loadm(hd, NC, jo, xdj);
+      loadm(lam_a, NC, jo, lj);
+      loadm(mu_a, NC, jo, mj);
       load_rho(Rj + (int64_t)(2 * e) * NPP * C, t.c, R);
       load_rho(Rj + (int64_t)(2 * e + 1) * NPP * C, t.c, Rp);
       load_rho(Rpp + (int64_t)e * NPP * C, t.c, Rq);
@@ -612,16 +699,17 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
 // Per-edge tables of coupling coefficient x harmonic: cy[e][n] = T_n Y_{m2_n}(u_e), and, with
 // WITH_DOT, cyd[e][n] = T_n Ydot_{m2_n} for the displacement rate v_sender - v_receiver,
 // followed (entry NNZ) by the rate of change of the edge length, u . (v_sender - v_receiver).
-template <bool WITH_DOT>
+template <typename G, bool WITH_DOT>
 __global__ void k_edge_cy(const float4* __restrict__ geo, const int32_t* __restrict__ sender,
                           const int32_t* __restrict__ receiver, const float* __restrict__ v, int64_t E,
                           float* __restrict__ out) {
+  constexpr int NM = G::NM, NNZ = G::NNZ, CY_LD = G::CY_LD;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= E * CY_LD) return;
   const int64_t e = idx / CY_LD;
   const int n = (int)(idx % CY_LD);
   const float4 g = geo[e];
-  float Y[9];
+  float Y[NM];
   float val = 0.f;
   if (WITH_DOT) {
     const int j = sender[e], i = receiver[e];
@@ -632,19 +720,19 @@ __global__ void k_edge_cy(const float4* __restrict__ geo, const int32_t* __restr
     sph_harm(g.x, g.y, g.z, Y);
   }
   if (n < NNZ) {
-    const int m2 = gaunt::ENT_M2_DEV[n];
+    const int m2 = gaunt::ent_m2_dev<G::LMAX>(n);
     float y = Y[0];
 #pragma unroll
-    for (int m = 1; m < 9; ++m) y = (m2 == m) ? Y[m] : y;
-    val = gaunt::ENT_COEF_DEV[n] * y;
+    for (int m = 1; m < NM; ++m) y = (m2 == m) ? Y[m] : y;
+    val = gaunt::ent_coef_dev<G::LMAX>(n) * y;
   }
   out[idx] = val;
 }
 
 
-// Filter weights W [11 C][H] (row p C + c) regrouped to the stored order of the filter jets:
-// Wp [(c 12 + p)][H], zero rows for the pad, and the transpose WpT [H][12 C].
-__global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, float* __restrict__ Wp, float* __restrict__ WpT) {
+// Filter weights W [NPATH C][H] (row p C + c) regrouped to the stored order of the filter jets:
+// Wp [(c NPP + p)][H], zero rows for the pad, and the transpose WpT [H][NPP C].
+__global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, int NPATH, int NPP, float* __restrict__ Wp, float* __restrict__ WpT) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)NPP * C * H) return;
   const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
@@ -652,8 +740,8 @@ __global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, floa
   Wp[idx] = val;
   WpT[(int64_t)hh * NPP * C + r] = val;
 }
-// grad[(p C + c)][H] += g[(c 12 + p)][H]
-__global__ void k_regroup_add(const float* __restrict__ g, int C, int H, float* __restrict__ grad) {
+// grad[(p C + c)][H] += g[(c NPP + p)][H]
+__global__ void k_regroup_add(const float* __restrict__ g, int C, int H, int NPATH, int NPP, float* __restrict__ grad) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)NPP * C * H) return;
   const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
@@ -661,10 +749,10 @@ __global__ void k_regroup_add(const float* __restrict__ g, int C, int H, float* 
 }
 
 // h0[m=0] = emb[species], other components zero
-__global__ void k_embed_l0(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C,
+__global__ void k_embed_l0(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C, int NM,
                            float* __restrict__ h) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= 9 * N * C) return;
+  if (idx >= NM * N * C) return;
   int64_t m = idx / (N * C), r = idx % (N * C);
   h[idx] = (m == 0) ? emb[(int64_t)species[r / C] * C + (r % C)] : 0.f;
 }
@@ -691,9 +779,9 @@ int mix_wgrad(mlip_ctx* ctx, int l, int k, const LdA& a, const LdB& b, float* gr
 }
 
 // ------------------------------------------------------------------------------ gated node update
-// cfg.gate: with u = W a (per l) the update is z_0 = silu(u_0), z_m = sigmoid(u_0) u_m for the eight
-// l = 1, 2 components m of the same channel, h' = h + z.  One thread per (atom, channel); arrays are
-// [9][N][C], component-major.  The four kernels are the map itself, its transpose applied to a
+// cfg.gate: with u = W a (per l) the update is z_0 = silu(u_0), z_m = sigmoid(u_0) u_m for the NM - 1
+// l >= 1 components m of the same channel, h' = h + z.  One thread per (atom, channel); arrays are
+// [NM][N][C], component-major.  The four kernels are the map itself, its transpose applied to a
 // cotangent (FF), its tangent map (BF), and for BE the transpose applied to lambda plus the derivative
 // with respect to u of <ud, J(u)^T mu> (ud: BF's tangent of u, mu: FF's cotangent of z).
 struct GateFn {
@@ -709,23 +797,21 @@ __device__ __forceinline__ GateFn gate_fn(float u0) {
   return g;
 }
 
-__global__ void k_gate_fe(const float* __restrict__ u, const float* __restrict__ h_in, float* __restrict__ h_out, int64_t NC) {
+__global__ void k_gate_fe(const float* __restrict__ u, const float* __restrict__ h_in, float* __restrict__ h_out, int64_t NC, int NM) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= NC) return;
   const float u0 = u[idx];
   const float s = sigm(u0);
   h_out[idx] = h_in[idx] + u0 * s;
-#pragma unroll
-  for (int m = 1; m < 9; ++m) h_out[m * NC + idx] = h_in[m * NC + idx] + s * u[m * NC + idx];
+  for (int m = 1; m < NM; ++m) h_out[m * NC + idx] = h_in[m * NC + idx] + s * u[m * NC + idx];
 }
 
-__global__ void k_gate_ff(const float* __restrict__ u, const float* __restrict__ mu, float* __restrict__ mu_u, int64_t NC) {
+__global__ void k_gate_ff(const float* __restrict__ u, const float* __restrict__ mu, float* __restrict__ mu_u, int64_t NC, int NM) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= NC) return;
   const GateFn g = gate_fn(u[idx]);
   float dot = 0.f;
-#pragma unroll
-  for (int m = 1; m < 9; ++m) {
+  for (int m = 1; m < NM; ++m) {
     const float mm = mu[m * NC + idx];
     dot += u[m * NC + idx] * mm;
     mu_u[m * NC + idx] = g.s * mm;
@@ -734,26 +820,24 @@ __global__ void k_gate_ff(const float* __restrict__ u, const float* __restrict__
 }
 
 __global__ void k_gate_bf(const float* __restrict__ u, const float* __restrict__ ud, const float* __restrict__ hd_in,
-                          float* __restrict__ hd_out, int64_t NC) {
+                          float* __restrict__ hd_out, int64_t NC, int NM) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= NC) return;
   const GateFn g = gate_fn(u[idx]);
   const float ud0 = ud[idx];
   hd_out[idx] = hd_in[idx] + g.f1 * ud0;
-#pragma unroll
-  for (int m = 1; m < 9; ++m)
+  for (int m = 1; m < NM; ++m)
     hd_out[m * NC + idx] = hd_in[m * NC + idx] + (g.ds * ud0 * u[m * NC + idx] + g.s * ud[m * NC + idx]);
 }
 
 __global__ void k_gate_be(const float* __restrict__ u, const float* __restrict__ ud, const float* __restrict__ mu,
-                          const float* __restrict__ lam, float* __restrict__ lam_u, int64_t NC) {
+                          const float* __restrict__ lam, float* __restrict__ lam_u, int64_t NC, int NM) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= NC) return;
   const GateFn g = gate_fn(u[idx]);
   const float ud0 = ud[idx];
   float u_lam = 0.f, u_mu = 0.f, ud_mu = 0.f;
-#pragma unroll
-  for (int m = 1; m < 9; ++m) {
+  for (int m = 1; m < NM; ++m) {
     const float um = u[m * NC + idx], mm = mu[m * NC + idx], lm = lam[m * NC + idx];
     u_lam += um * lm;
     u_mu += um * mm;
@@ -764,15 +848,14 @@ __global__ void k_gate_be(const float* __restrict__ u, const float* __restrict__
 }
 
 // ------------------------------------------------------------------------------ phases
-constexpr int LOFF[3] = {0, 1, 4};
-
-template <typename P, typename TF>
+template <typename P, typename TF, typename G>
 int fe_impl(mlip_ctx* ctx, float* E_out) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   static_assert(sizeof(typename Act<P>::xop_t) == (P::IS_BF16 ? 2 : 4), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   const bool gate = cf.gate != 0;
@@ -780,8 +863,8 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
   };
   for (int l = 0; l < L; ++l) {
-    hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, w->Wp[l], w->WpT[l]);
-    for (int k = 0; k < 3; ++k) {
+    hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, NPATH, NPP, w->Wp[l], w->WpT[l]);
+    for (int k = 0; k <= LMAX; ++k) {
       if (cf.n_experts > 0)
         hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C, 64), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
                            th + ctx->lay[l].Wl[k], ctx->B, cf.n_experts, C, w->Wm[k][l], w->WmT[k][l]);
@@ -794,8 +877,8 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   if (E > 0)
     launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->jphi);
   if (E > 0)
-    hipLaunchKernelGGL(k_edge_cy<false>, dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
-  hipLaunchKernelGGL(k_embed_l0, dim3(nblk(9 * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);
+    hipLaunchKernelGGL((k_edge_cy<G, false>), dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
+  hipLaunchKernelGGL(k_embed_l0, dim3(nblk(NM * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, NM, w->h[0]);
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
@@ -810,18 +893,18 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      auto kern = uni ? k_tp_fe<TF, true> : k_tp_fe<TF, false>;
+      auto kern = uni ? k_tp_fe<G, TF, true> : k_tp_fe<G, TF, false>;
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Rho[l]),
                          w->cy, w->h[l], (int)N, C, w->a[l]);
     }
-    for (int k = 0; k < 3; ++k) {
-      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+    for (int k = 0; k <= LMAX; ++k) {
+      const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       if (gate)
         mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiStore{w->u[l] + o, C, rows});
       else
         mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
-    if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC);
+    if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC, NM);
   }
   gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
   hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
@@ -830,18 +913,19 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   return MLIP_OK;
 }
 
-template <typename P, typename TF>
+template <typename P, typename TF, typename G>
 int ff_impl(mlip_ctx* ctx, float* F) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
+  constexpr int NM = G::NM, LMAX = G::LMAX;
   const int64_t N = ctx->N, NC = N * cf.channels;
   const int C = cf.channels, L = cf.n_layers;
   const float* th = ctx->d_params;
   const bool gate = cf.gate != 0;
   const float* tT = w->paramsT;
   // mu_h^L: l = 0 block from the readout, zero elsewhere
-  hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->mu_h[L] + NC, 0.f, 8 * NC);
+  hipLaunchKernelGGL(k_fill, dim3(nblk((NM - 1) * NC)), dim3(256), 0, st, w->mu_h[L] + NC, 0.f, (NM - 1) * NC);
   gemm_nt<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
   hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
   const int rpb = 256 / C;
@@ -850,15 +934,15 @@ int ff_impl(mlip_ctx* ctx, float* F) {
     const LayerOffsets& lo = ctx->lay[l];
     const float* mu_z = w->mu_h[l + 1];  // cotangent of the update's output; through the gate it becomes that of W a
     if (gate) {
-      hipLaunchKernelGGL(k_gate_ff, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->mu_h[l + 1], w->mu_u[l], NC);
+      hipLaunchKernelGGL(k_gate_ff, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->mu_h[l + 1], w->mu_u[l], NC, NM);
       mu_z = w->mu_u[l];
     }
-    for (int k = 0; k < 3; ++k) {
-      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+    for (int k = 0; k <= LMAX; ++k) {
+      const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       mix_mm<P>(ctx, l, k, true, LdPlain{mu_z + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    auto kern = uni ? k_tp_ff<TF, true> : k_tp_ff<TF, false>;
+    auto kern = uni ? k_tp_ff<G, TF, true> : k_tp_ff<G, TF, false>;
     hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                        w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
@@ -867,12 +951,13 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   return MLIP_OK;
 }
 
-template <typename P, typename TF>
+template <typename P, typename TF, typename G>
 int bf_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   const bool gate = cf.gate != 0;
@@ -880,34 +965,34 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   typedef typename Act<P>::xop_t TX;  // X and X2 only feed matrix products: stored in the operand precision
   TX* X = reinterpret_cast<TX*>(w->X);
   TX* X2 = reinterpret_cast<TX*>(w->X2);
-  hipLaunchKernelGGL(k_fill, dim3(nblk(9 * NC)), dim3(256), 0, st, w->hd[0], 0.f, 9 * NC);
+  hipLaunchKernelGGL(k_fill, dim3(nblk(NM * NC)), dim3(256), 0, st, w->hd[0], 0.f, NM * NC);
   if (E > 0)  // harmonics' rate of change under the displacement rate v: used by this phase and by BE
-    hipLaunchKernelGGL(k_edge_cy<true>, dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, w->v, E, w->cyd);
+    hipLaunchKernelGGL((k_edge_cy<G, true>), dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, w->v, E, w->cyd);
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      auto kern = uni ? k_tp_bf<TX, TF, true> : k_tp_bf<TX, TF, false>;
+      auto kern = uni ? k_tp_bf<G, TX, TF, true> : k_tp_bf<G, TX, TF, false>;
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
-    for (int k = 0; k < 3; ++k) {
-      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+    for (int k = 0; k <= LMAX; ++k) {
+      const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       if (gate)
         mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiStore{w->ud[l] + o, C, rows});
       else
         mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{(gate ? w->mu_u[l] : w->mu_h[l + 1]) + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
-    if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC);
+    if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC, NM);
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, NPATH, NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
@@ -927,12 +1012,13 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   return MLIP_OK;
 }
 
-template <typename P, typename TF>
+template <typename P, typename TF, typename G>
 int be_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
   const bool gate = cf.gate != 0;
@@ -948,7 +1034,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     hipLaunchKernelGGL(k_reduce_partials, dim3(nblk(C, 64)), dim3(256), 0, st, ctx->partial.buf, chunks, (int64_t)C, grad + ctx->off_wo);
   }
   MLIP_TRY((gemm_wgrad<P>(ctx, LdPlain{w->lam_y, C}, LdPlain{w->h[L], C}, N, C, C, grad + ctx->off_U)));
-  hipLaunchKernelGGL(k_fill, dim3(nblk(8 * NC)), dim3(256), 0, st, w->lam_h[cur] + NC, 0.f, 8 * NC);
+  hipLaunchKernelGGL(k_fill, dim3(nblk((NM - 1) * NC)), dim3(256), 0, st, w->lam_h[cur] + NC, 0.f, (NM - 1) * NC);
   gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
@@ -960,21 +1046,21 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     float* lh = w->lam_h[cur ^ 1];
     const float* lam_z = lh_next;  // adjoint of the update's output; through the gate it becomes that of W a
     if (gate) {
-      hipLaunchKernelGGL(k_gate_be, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->mu_h[l + 1], lh_next, w->lam_u, NC);
+      hipLaunchKernelGGL(k_gate_be, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->mu_h[l + 1], lh_next, w->lam_u, NC, NM);
       lam_z = w->lam_u;
     }
-    for (int k = 0; k < 3; ++k) {
-      const int64_t o = LOFF[k] * NC, rows = (2 * k + 1) * N;
+    for (int k = 0; k <= LMAX; ++k) {
+      const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       mix_mm<P>(ctx, l, k, true, LdPlain{lam_z + o, C}, EpiStore{w->lam_a + o, C, rows});
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lam_z + o, C}, LdPlain{w->a[l] + o, C}, grad)));
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      auto kern = uni ? k_tp_be<TX, TF, true> : k_tp_be<TX, TF, false>;
+      auto kern = uni ? k_tp_be<G, TX, TF, true> : k_tp_be<G, TX, TF, false>;
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
-    if (want_gp && E > 0) {
+    if constexpr (LMAX == 2) if (want_gp && E > 0) {
       // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share
       const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
       gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2, H, E});
@@ -989,7 +1075,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, NPATH, NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
@@ -1015,8 +1101,14 @@ int be_impl(mlip_ctx* ctx, float* grad) {
 int eqv_alloc(mlip_ctx* ctx) {
   const mlip_config& cf = ctx->cfg;
   const int64_t N = cf.max_atoms, E = cf.max_edges, B = cf.max_structs;
+  const int lmax = cf.l_max;
+  const int NM = (lmax + 1) * (lmax + 1);
+  const int NPP = lmax == 3 ? gaunt::Tab<3>::NPP : gaunt::Tab<2>::NPP;
+  const int CY_LD = lmax == 3 ? gaunt::Tab<3>::CY_LD : gaunt::Tab<2>::CY_LD;
+  const int TAB = 64 * (lmax == 3 ? gaunt::Tab<3>::TAB_LOADS : gaunt::Tab<2>::TAB_LOADS);
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
+  if (lmax == 3 && cf.position_grad) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: the position gradient is built for l_max = 2 only");
   EqvWs* w = new EqvWs();
   ctx->model_ws = w;
   bool ok = true;
@@ -1034,10 +1126,10 @@ int eqv_alloc(mlip_ctx* ctx) {
   auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
   w->X = AH(E * PC);
   w->gWp = A((int64_t)PC * H);
-  w->cy = A(E * gaunt::CY_LD + 64);  // + 64: the cooperative fetch of the last edge's table reads 128 floats
-  w->cyd = A(E * gaunt::CY_LD + 64);
+  w->cy = A(E * CY_LD + TAB);  // + TAB: the cooperative fetch of the last edge's table reads TAB floats from its start
+  w->cyd = A(E * CY_LD + TAB);
   w->X2 = AH(E * H);
-  const int64_t NC9 = 9 * N * C;
+  const int64_t NC9 = (int64_t)NM * N * C;  // a node table: all components
   for (int l = 0; l < L; ++l) {
     w->U.push_back(A(2 * E * H));
     w->SJ.push_back(b16 ? (__bf16*)A(E * H) : nullptr);
@@ -1049,7 +1141,7 @@ int eqv_alloc(mlip_ctx* ctx) {
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
     if (cf.gate) { w->u.push_back(A(NC9)); w->mu_u.push_back(A(NC9)); w->ud.push_back(A(NC9)); }
     if (cf.n_experts > 0)
-      for (int k = 0; k < 3; ++k) { w->Wm[k].push_back(A(B * C * C)); w->WmT[k].push_back(A(B * C * C)); }
+      for (int k = 0; k <= lmax; ++k) { w->Wm[k].push_back(A(B * C * C)); w->WmT[k].push_back(A(B * C * C)); }
   }
   for (int l = 0; l <= L; ++l) { w->h.push_back(A(NC9)); w->mu_h.push_back(A(NC9)); w->hd.push_back(A(NC9)); }
   w->lam_h[0] = A(NC9); w->lam_h[1] = A(NC9); w->lam_a = A(NC9);
@@ -1068,10 +1160,10 @@ int eqv_alloc(mlip_ctx* ctx) {
     int bm = narrow ? 128 : (rows > 64 ? 128 : 64), bn = narrow ? 32 : (rows > 64 ? 128 : 64);
     cap = std::max<int64_t>(cap, (int64_t)pick_splits(rows, cols, R, bm, bn) * rows * cols);
   };
-  need(PC, H, E); need(H, K, E); need(C, C, 5 * N);
+  need(PC, H, E); need(H, K, E); need(C, C, (2 * lmax + 1) * N);
   cap = std::max<int64_t>(cap, (int64_t)128 * std::max(1, cf.n_species) * C);
   if (cf.n_experts > 0)  // one weight-gradient partial per (component, structure), plus the split products of the coefficient gradient
-    cap = std::max<int64_t>(cap, 5 * B * ((int64_t)C * C + 256 * (int64_t)((cf.n_experts + 3) / 4 * 4)));
+    cap = std::max<int64_t>(cap, (2 * lmax + 1) * B * ((int64_t)C * C + 256 * (int64_t)((cf.n_experts + 3) / 4 * 4)));
   ctx->partial.cap = cap;
   ctx->partial.buf = A(cap);
   return ok ? MLIP_OK : MLIP_E_HIP;
@@ -1082,11 +1174,14 @@ void eqv_free(mlip_ctx* ctx) {
   ctx->model_ws = nullptr;
 }
 
-// TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters
-#define DISPATCH(fn, ...)                                                                                        \
-  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                         \
-       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float>(__VA_ARGS__) : fn<gemm::Bf16, __bf16>(__VA_ARGS__))       \
-       : fn<gemm::Fp32, float>(__VA_ARGS__))
+// TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters;
+// G = the coupling tables of the context's l_max
+#define DISPATCH_G(fn, G, ...)                                                                                      \
+  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                            \
+       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float, G>(__VA_ARGS__) : fn<gemm::Bf16, __bf16, G>(__VA_ARGS__))    \
+       : fn<gemm::Fp32, float, G>(__VA_ARGS__))
+#define DISPATCH(fn, ...) \
+  (ctx->cfg.l_max == 3 ? DISPATCH_G(fn, gaunt::Tab<3>, __VA_ARGS__) : DISPATCH_G(fn, gaunt::Tab<2>, __VA_ARGS__))
 
 int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float*,
                        float* E, float*) {

@@ -310,8 +310,8 @@ int graph_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_atom_struct = alloc_n<int32_t>(ctx, N)) != nullptr;
   if (ctx->cfg.n_experts > 0) {  // per-structure products of the expert banks
     ok &= (ctx->d_alpha = alloc_n<float>(ctx, (int64_t)B * ctx->cfg.n_experts)) != nullptr;
-    // the equivariant model stacks up to five copies of the atom rows (components m of one l)
-    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 5 : 1;
+    // the equivariant model stacks up to 2 l_max + 1 copies of the atom rows (components m of one l)
+    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 2 * ctx->cfg.l_max + 1 : 1;
     ok &= (ctx->d_row_groups = alloc_n<int4>(ctx, copies * (N / 64 + B + 1))) != nullptr;
     ok &= (ctx->d_struct_ptr = alloc_n<int32_t>(ctx, copies * B + 1)) != nullptr;
   }
@@ -464,7 +464,7 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
     // row tiles of at most 64 atoms, none straddling two structures (each structure has its own merged matrices)
     // The equivariant model multiplies [(2l+1) N, C] matrices (component-major copies of the atom rows):
     // copy m of the tables is shifted by m N rows; a product over 2l+1 copies uses the first 2l+1.
-    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 5 : 1;
+    const int copies = ctx->cfg.model_kind == MLIP_MODEL_EQUIVARIANT ? 2 * ctx->cfg.l_max + 1 : 1;
     ctx->h_row_groups.clear();
     ctx->h_k_ranges.assign((size_t)copies * B + 1, 0);
     for (int m = 0; m < copies; ++m)

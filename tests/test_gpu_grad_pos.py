@@ -122,3 +122,13 @@ def test_position_gradient_needs_its_workspace():
     assert e.value.code == -1
     m.mlip_set_position_grad(None)  # switching off is always accepted
     m.close()
+
+
+def test_position_gradient_is_refused_for_degree3_features():
+    # the second derivatives of the degree-3 harmonics are not built: creating such a context fails with "unsupported"
+    w = synth.shrink(synth.WORKLOADS[2], l_max=3, n_structs=1, atoms_per_struct=8, box=6.0, cutoff=3.0, channels=8, edge_hidden=8,
+                     n_rbf=8, n_layers=1, gemm_bf16=False)
+    with pytest.raises(MlipError) as e:
+        Mlip.for_workload(w, position_grad=1)
+    assert e.value.code == -3
+    Mlip.for_workload(w).close()  # without the option the same model is fine

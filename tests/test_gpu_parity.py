@@ -264,6 +264,20 @@ def train_cases():
         "cfg1_2structs_bf16_fp32filters": (synth.shrink(W[1], n_structs=2, gemm_bf16=True, filter_fp32=1), TOL_BF16),
         "eqv_channels_96_bf16_fp32filters": (synth.shrink(W[2], channels=96, edge_hidden=40, n_rbf=8, atoms_per_struct=14, n_structs=2,
                                                           box=6.0, cutoff=3.2, n_layers=2, filter_fp32=1), TOL_BF16),
+        # features up to degree 3 (16 components, 23 coupling paths): a narrow model (lanes of a wave spread over rows),
+        # widths that are multiples of 64 (a wave per row: tables through LDS), periodic images, bf16, gate, expert banks
+        "eqv_lmax3_tiny_fp32": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
+                                             edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False), TOL_FP32),
+        "eqv_lmax3_multi_image_bf16": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                                    edge_hidden=20, n_rbf=8, n_layers=3, gemm_bf16=True), TOL_BF16),
+        "eqv_lmax3_channels_64_fp32": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=14, box=6.0, cutoff=3.2, channels=64,
+                                                    edge_hidden=32, n_rbf=8, n_layers=2, gemm_bf16=False), TOL_FP32),
+        "eqv_lmax3_channels_128_bf16": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=40, box=8.0, cutoff=3.5, channels=128,
+                                                     edge_hidden=64, n_rbf=16, n_layers=2, gemm_bf16=True), TOL_BF16),
+        "eqv_lmax3_triclinic_gate_fp32": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5, channels=12,
+                                                       edge_hidden=16, n_rbf=8, n_layers=2, gemm_bf16=False, cell_kind="triclinic", gate=1), TOL_FP32),
+        "eqv_lmax3_molecules_fp32": (synth.shrink(W[2], l_max=3, n_structs=3, atoms_per_struct=12, box=6.0, cutoff=3.5, channels=16,
+                                                  edge_hidden=16, n_rbf=8, n_layers=2, gemm_bf16=False, cell_kind="free"), TOL_FP32),
     }
 
 
@@ -339,6 +353,8 @@ def mole_cases():
         "eqv_tiny_4experts_fp32": (synth.shrink(W[2], n_structs=3, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
                                                 edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False, n_experts=4), TOL_FP32),
         "cfg2_2structs_6experts_bf16": (synth.shrink(W[2], n_structs=2, n_experts=6), TOL_BF16),
+        "eqv_lmax3_tiny_4experts_fp32": (synth.shrink(W[2], l_max=3, n_structs=3, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8,
+                                                      edge_hidden=8, n_rbf=8, n_layers=2, gemm_bf16=False, n_experts=4), TOL_FP32),
         "300_structures_7experts": (synth.shrink(W[0], n_structs=300, atoms_per_struct=3, box=4.5, cutoff=3.0, channels=16,
                                                  edge_hidden=16, n_rbf=8, n_experts=7), TOL_FP32),
         # the largest expert count the configuration check admits
@@ -481,10 +497,11 @@ def test_mixture_of_linear_experts_ragged_batch_and_errors():
     dense.close()
 
 
-@pytest.mark.parametrize("which", ["invariant", "equivariant"])
+@pytest.mark.parametrize("which", ["invariant", "equivariant", "equivariant_lmax3"])
 def test_phase_calls_and_gradient_split(which):
     """FE, FF, loss, BF, BE one by one; BF's and BE's shares of the gradient against the oracle's split (Eq. 2)."""
-    w = synth.WORKLOADS[0] if which == "invariant" else train_cases()["eqv_tiny_fp32"][0]
+    w = {"invariant": synth.WORKLOADS[0], "equivariant": train_cases()["eqv_tiny_fp32"][0],
+         "equivariant_lmax3": train_cases()["eqv_lmax3_tiny_fp32"][0]}[which]
     inp = synth.make_inputs(w)
     ref = oracle_train_step(w, inp, split=True)
     m = Mlip.for_workload(w)
