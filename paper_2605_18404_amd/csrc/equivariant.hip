@@ -449,7 +449,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
       constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n];
       S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
       S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
-      S23 = fmaf(cyd[n], xj[m1], S23);
+      if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
       if (G::ENT_SLAST[n]) {
         acc[m3] = fmaf(rr[p], S1, fmaf(rho[p], S23, acc[m3]));
         tp[p] = fmaf(mi[m3], S1, tp[p]);
@@ -526,10 +526,11 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
         R2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
         R1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
       }
-      acc[m1] = fmaf(cyd[n], R2, fmaf(cy[n], R1, acc[m1]));
+      acc[m1] = fmaf(cy[n], R1, acc[m1]);
+      if constexpr (G::ENT_M2[n] != 0) acc[m1] = fmaf(cyd[n], R2, acc[m1]);
       S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
       S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
-      S23 = fmaf(cyd[n], xj[m1], S23);
+      if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
       if (G::ENT_SLAST[n]) {
         ta[p] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[p]));
         t4[p] = fmaf(mi[m3], S1, t4[p]);

@@ -204,7 +204,7 @@ struct Groups {
 };
 
 template <typename P, int TM, int TN, int WM, int WN, bool KC, int BK, typename LdA, typename LdB, typename Epi>
-__global__ void __launch_bounds__(256, P::WAVES)
+__global__ void __launch_bounds__(256, (TM * TN >= 8 ? 2 : P::WAVES))
 k_gemm(LdA lda, LdB ldb, Epi epi, int64_t M_all, int N, int64_t K, int64_t k_chunk, int splits, Groups grp) {
   static_assert(WM * WN == 4, "four waves per workgroup");
   constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;

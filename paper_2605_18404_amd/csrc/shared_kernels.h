@@ -269,6 +269,11 @@ inline const __bf16* shadow_of(const mlip_ctx* ctx, const float* p) {
 template <typename P, typename LdA, typename LdB, typename Epi>
 void gemm_nt_as(hipStream_t st, const LdA& a, const LdB& b, int64_t M, int N, int K, const Epi& epi) {
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+  // long reductions over raw bf16 operands: 256 x 128 tiles (128 x 64 per wave) stage a third fewer bytes through LDS per
+  // matrix instruction (LDS takes 64 bytes per clock in, 256 out, and is what bounds these kernels)
+  if constexpr (P::IS_BF16 && LdA::WIDTH == 8 && LdB::WIDTH == 8) {
+    if (N % 128 == 0 && K >= 256 && tiles128 >= 2048) return (void)gemm::launch<P, 4, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
+  }
   if (N > 64 && tiles128 >= 512)
     gemm::launch<P, 2, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
   else
