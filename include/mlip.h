@@ -94,8 +94,7 @@ typedef struct {
                                mixed-precision linear layer returns them (half the bytes of the largest edge tensor).
                                1: they are stored in fp32, so that bf16 rounding touches matrix-product operands only */
   int32_t position_grad;    /* 1: also allocate the workspace for the position gradient dL/dx (mlip_set_position_grad);
-                               0: none, and that call is refused.  Not available with l_max = 3 (mlip_create returns
-                               MLIP_E_UNSUPPORTED): the second derivatives of the degree-3 harmonics are not built */
+                               0: none, and that call is refused */
   float cutoff;             /* r_c, Angstrom */
   float force_weight;       /* weight of the force term of the loss */
   int64_t max_atoms;        /* capacities the workspace is sized for */

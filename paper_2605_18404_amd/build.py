@@ -9,7 +9,10 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmlip.so")
-SOURCES = ["api.hip", "graph.hip", "graph_static.hip", "model.hip", "equivariant.hip", "optimizer.hip", "gars.cpp"]
+# (source, object name, extra flags); the equivariant model is compiled once per l_max (two objects, side by side)
+SOURCES = [("equivariant.hip", "equivariant_l3", ["-DMLIP_EQV_LMAX=3"]), ("equivariant.hip", "equivariant_l2", ["-DMLIP_EQV_LMAX=2"]),
+           ("model.hip", "model", []), ("api.hip", "api", []), ("graph.hip", "graph", []), ("graph_static.hip", "graph_static", []),
+           ("optimizer.hip", "optimizer", []), ("gars.cpp", "gars", [])]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # The neighbour search decides r < r_c in fp32 and must take the same decision as a plain
@@ -17,11 +20,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 NO_FMA = {"graph.hip"}
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
+def _compile(item) -> str:
+    src, name, extra = item
+    obj = os.path.join(HERE, "_build", name + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
     contract = "-ffp-contract=off" if src in NO_FMA else "-ffp-contract=fast"
-    cmd = ["hipcc", *FLAGS, contract, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *extra, contract, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")

@@ -25,6 +25,14 @@
 #include "gaunt_table.h"
 #include "shared_kernels.h"
 
+// This file is compiled twice, with MLIP_EQV_LMAX = 2 and = 3: each object instantiates the kernels for one set of
+// coupling tables (the two compile side by side).  The l_max = 2 object also holds the model's interface functions,
+// which hand a context with l_max = 3 to eqv_phase_lmax3 in the other object.
+#ifndef MLIP_EQV_LMAX
+#define MLIP_EQV_LMAX 2
+#endif
+int eqv_phase_lmax3(mlip_ctx* ctx, int phase, float* out);
+
 namespace {
 
 struct EqvWs {
@@ -126,10 +134,6 @@ __device__ __forceinline__ void sph_dot(float x, float y, float z, float r, floa
     Yd[14] = C105 * (x * z * px - y * z * py + 0.5f * q * pz);
     Yd[15] = C35 * (3.f * q * px - 6.f * x * y * py);
   }
-}
-__device__ __forceinline__ void parity(const float (&a)[9], float (&b)[9]) {
-#pragma unroll
-  for (int m = 0; m < 9; ++m) b[m] = (m >= 1 && m <= 3) ? -a[m] : a[m];
 }
 template <int NM>
 __device__ __forceinline__ void loadm(const float* __restrict__ t, int64_t NC, int64_t off, float (&x)[NM]) {
@@ -549,17 +553,27 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
 
 // ------------------------------------------------------------------------------ position gradient (optional)
 // d/dr_vec of F(r_vec) = sum_m nu[m] Y_m(r_vec / |r_vec|), differentiated once more along d:
-// with u = r_vec / r, Q(u) = sum_m nu[m] P_m(u) the harmonics' polynomials, g = grad Q(u), H = Hessian of Q
-// (constant for l <= 2), Pi = I - u u^T, delta = Pi d / r:
+// with u = r_vec / r, Q(u) = sum_m nu[m] P_m(u) the harmonics' polynomials (the forms sph_grad_T differentiates),
+// g = grad Q(u), H = Hessian of Q at u (constant for l <= 2, linear in u for the degree-3 terms), Pi = I - u u^T,
+// delta = Pi d / r:
 //   grad F = Pi g / r,    D_d grad F = [H delta - delta (u.g) - u (delta.g + u.H delta)] / r - Pi g (u.d) / r^2.
-__device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, float r, const float (&nu)[9], float3 d) {
-  const float s15 = 3.872983346207417f, s5 = 2.23606797749979f;
+template <int NM>
+__device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, float r, const float (&nu)[NM], float3 d) {
   const float3 g = sph_grad_T(x, y, z, nu);
   const float inv = r > 0.f ? 1.f / r : 0.f;
   const float ud = x * d.x + y * d.y + z * d.z;
   const float3 dl = make_float3((d.x - x * ud) * inv, (d.y - y * ud) * inv, (d.z - z * ud) * inv);
   // H: xx = s15 nu8, yy = -s15 nu8, zz = 3 s5 nu6, xy = s15 nu4, yz = s15 nu5, xz = s15 nu7
-  const float hxx = s15 * nu[8], hyy = -s15 * nu[8], hzz = 3.f * s5 * nu[6], hxy = s15 * nu[4], hyz = s15 * nu[5], hxz = s15 * nu[7];
+  float hxx = S15 * nu[8], hyy = -S15 * nu[8], hzz = 3.f * S5 * nu[6], hxy = S15 * nu[4], hyz = S15 * nu[5], hxz = S15 * nu[7];
+  if constexpr (NM == 16) {
+    // second derivatives of  c35 y(3x^2 - y^2), c105 xyz, c21 y(5z^2 - 1), c7 z(5z^2 - 3), c21 x(5z^2 - 1), (c105/2) z(x^2 - y^2), c35 x(x^2 - 3y^2)
+    hxx += 6.f * C35 * (y * nu[9] + x * nu[15]) + C105 * z * nu[14];
+    hyy += -6.f * C35 * (y * nu[9] + x * nu[15]) - C105 * z * nu[14];
+    hzz += 10.f * C21 * (y * nu[11] + x * nu[13]) + 30.f * C7 * z * nu[12];
+    hxy += 6.f * C35 * (x * nu[9] - y * nu[15]) + C105 * z * nu[10];
+    hyz += C105 * (x * nu[10] - y * nu[14]) + 10.f * C21 * z * nu[11];
+    hxz += C105 * (y * nu[10] + x * nu[14]) + 10.f * C21 * z * nu[13];
+  }
   const float3 hd = make_float3(hxx * dl.x + hxy * dl.y + hxz * dl.z, hxy * dl.x + hyy * dl.y + hyz * dl.z, hxz * dl.x + hyz * dl.y + hzz * dl.z);
   const float ug = x * g.x + y * g.y + z * g.z;
   const float dg = dl.x * g.x + dl.y * g.y + dl.z * g.z;
@@ -580,22 +594,22 @@ __device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, floa
 //   J = dY/dr_vec, K = d(Ydot)/dr_vec (second derivatives of the harmonics, sph_hess_apply).
 // Atom i takes -dPsi/dr_vec of the edges it receives and +dPsi/dr_vec of those it sends; the opposite edge (same r, rdot;
 // u, dv negated; Y -> PY) is formed here too, from the row's own node values and the gathered sender's.
-// One thread per (receiver row, channel), straight-line couplings; off the timed path.  Built for l_max = 2 only
-// (the second derivatives of the degree-3 harmonics are not constant; a context with l_max = 3 refuses position_grad).
-constexpr int NPATH = gaunt::Tab<2>::NPATH, NPP = gaunt::Tab<2>::NPP;
+// One thread per (receiver row, channel), couplings straight from the entry tables; off the timed path.
+template <typename G>
 __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
                                                const float* __restrict__ Rj, const float* __restrict__ Rpp,
                                                const float* __restrict__ h, const float* __restrict__ hd,
                                                const float* __restrict__ mu_a, const float* __restrict__ lam_a,
                                                const float* __restrict__ v, float k2, int N, int C, float* __restrict__ gp) {
+  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP;
   __shared__ float3 red[256];
   RowChan t = row_chan(N, C);
   float3 f = make_float3(0.f, 0.f, 0.f);
   if (t.active) {
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
-    float xi[9], xdi[9], li[9], mi[9];
+    float xi[NM], xdi[NM], li[NM], mi[NM];
     loadm(h, NC, io, xi);
     loadm(hd, NC, io, xdi);
     loadm(lam_a, NC, io, li);
@@ -607,7 +621,7 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
       const float2 cc = env[e];
       const float3 d = make_float3(v[3 * j] - vi0, v[3 * j + 1] - vi1, v[3 * j + 2] - vi2);
       const float rd = g.x * d.x + g.y * d.y + g.z * d.z;
-      float xj[9], xdj[9], lj[9], mj[9], R[NPATH], Rp[NPATH], Rq[NPATH];
+      float xj[NM], xdj[NM], lj[NM], mj[NM], R[NPATH], Rp[NPATH], Rq[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
       loadm(h, NC, jo, xj);
       loadm(hd, NC, jo, xdj);
@@ -625,54 +639,43 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
         r2[p] = cq * R[p] + 2.f * cp * Rp[p] + c * Rq[p];
         rr[p] = rd * r1[p];
       }
-      float Y[9], Yd[9], PY[9], PYd[9];
+      float Y[NM], Yd[NM], PY[NM], PYd[NM];
       sph_harm(g.x, g.y, g.z, Y);
       sph_dot(g.x, g.y, g.z, g.w, d, Yd);
-      parity(Y, PY);
-      parity(Yd, PYd);
-      float lr[NPATH], lrd[NPATH], tmp[NPATH];
-      gaunt::tp_paths(xj, Y, li, lr);
-      gaunt::tp_paths(xdj, Y, mi, tmp);
 #pragma unroll
-      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
-      gaunt::tp_paths(xj, Yd, mi, tmp);
-#pragma unroll
-      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
-      gaunt::tp_paths(xj, Y, mi, lrd);
-      // the opposite edge: own features, the sender's adjoints, harmonics of -u
-      gaunt::tp_paths(xi, PY, lj, tmp);
-#pragma unroll
-      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
-      gaunt::tp_paths(xdi, PY, mj, tmp);
-#pragma unroll
-      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
-      gaunt::tp_paths(xi, PYd, mj, tmp);
-#pragma unroll
-      for (int p = 0; p < NPATH; ++p) lr[p] += tmp[p];
-      gaunt::tp_paths(xi, PY, mj, tmp);
-#pragma unroll
-      for (int p = 0; p < NPATH; ++p) lrd[p] += tmp[p];
+      for (int m = 0; m < NM; ++m) {
+        PY[m] = G::M_SIGN[m] * Y[m];
+        PYd[m] = G::M_SIGN[m] * Yd[m];
+      }
+      // One walk over the coupling entries n = (p; m1, m2, m3) forms the path-wise trilinear forms t_p and the adjoints of the
+      // harmonics B_y^T of this edge and of the opposite edge (own features, the sender's adjoints, harmonics of -u):
+      //   lr = lam_rho, lrd = lam_rhodot (both edges summed);  LY, LYd = lam_Y, lam_Ydot of this edge, QY, QYd of the opposite one
+      float lr[NPATH], lrd[NPATH], LY[NM], LYd[NM], QY[NM], QYd[NM];
+      zero(lr); zero(lrd); zero(LY); zero(LYd); zero(QY); zero(QYd);
+      static_for<0, G::NNZ>([&](auto n_) {
+        constexpr int n = decltype(n_)::value;
+        constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n], m2 = G::ENT_M2[n];
+        const float co = G::ENT_COEF[n];
+        const float a_l = xj[m1] * li[m3] + xdj[m1] * mi[m3], a_m = xj[m1] * mi[m3];  // this edge
+        const float b_l = xi[m1] * lj[m3] + xdi[m1] * mj[m3], b_m = xi[m1] * mj[m3];  // the opposite edge
+        lr[p] += co * (a_l * Y[m2] + a_m * Yd[m2] + b_l * PY[m2] + b_m * PYd[m2]);
+        lrd[p] += co * (a_m * Y[m2] + b_m * PY[m2]);
+        const float q = rho[p] * co, qr = rr[p] * co;
+        LY[m2] += q * a_l + qr * a_m;
+        LYd[m2] += q * a_m;
+        QY[m2] += q * b_l + qr * b_m;
+        QYd[m2] += q * b_m;
+      });
       float rad = 0.f, gg = 0.f;
 #pragma unroll
       for (int p = 0; p < NPATH; ++p) {
         rad += lr[p] * r1[p] + lrd[p] * rd * r2[p];
         gg += lrd[p] * r1[p];
       }
-      float LY[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, LYd[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      float QY[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, QYd[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      gaunt::tp_adj_y(rho, xj, li, LY);
-      gaunt::tp_adj_y(rr, xj, mi, LY);
-      gaunt::tp_adj_y(rho, xdj, mi, LY);
-      gaunt::tp_adj_y(rho, xj, mi, LYd);
-      gaunt::tp_adj_y(rho, xi, lj, QY);
-      gaunt::tp_adj_y(rr, xi, mj, QY);
-      gaunt::tp_adj_y(rho, xdi, mj, QY);
-      gaunt::tp_adj_y(rho, xi, mj, QYd);
 #pragma unroll
-      for (int m = 0; m < 9; ++m) {
-        const float sg = (m >= 1 && m <= 3) ? -1.f : 1.f;
-        LY[m] += sg * QY[m];
-        LYd[m] += sg * QYd[m];
+      for (int m = 0; m < NM; ++m) {
+        LY[m] += G::M_SIGN[m] * QY[m];
+        LYd[m] += G::M_SIGN[m] * QYd[m];
       }
       const float inv = g.w > 0.f ? 1.f / g.w : 0.f;
       const float3 w = sph_grad_T(g.x, g.y, g.z, LY);
@@ -1061,14 +1064,14 @@ int be_impl(mlip_ctx* ctx, float* grad) {
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
-    if constexpr (LMAX == 2) if (want_gp && E > 0) {
+    if (want_gp && E > 0) {
       // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share
       const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
       gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2, H, E});
       gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiStore{w->Rj, PC, 2 * E});
       gemm_nt<P>(ctx, LdJetSecond{w->U[l], w->U2, H}, w->Wp[l], E, PC, H, EpiStore{w->Rpp, PC, E});
       const float kk = 3.14159265358979323846f / cf.cutoff;
-      hipLaunchKernelGGL(k_tp_gp, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Rj, w->Rpp,
+      hipLaunchKernelGGL(k_tp_gp<G>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Rj, w->Rpp,
                          w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, kk * kk, (int)N, C, w->gp_acc);
     }
     if (E > 0) {
@@ -1098,6 +1101,23 @@ int be_impl(mlip_ctx* ctx, float* grad) {
 
 }  // namespace
 
+#if MLIP_EQV_LMAX == 3
+// The four phases for a context with l_max = 3 (called from the interface functions in the l_max = 2 object).
+int eqv_phase_lmax3(mlip_ctx* ctx, int phase, float* out) {
+  typedef gaunt::Tab<3> G;
+#define EQV3(fn)                                                                                            \
+  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                    \
+       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float, G>(ctx, out) : fn<gemm::Bf16, __bf16, G>(ctx, out))  \
+       : fn<gemm::Fp32, float, G>(ctx, out))
+  switch (phase) {
+    case 0: return EQV3(fe_impl);
+    case 1: return EQV3(ff_impl);
+    case 2: return EQV3(bf_impl);
+    default: return EQV3(be_impl);
+  }
+#undef EQV3
+}
+#else
 // =================================================================================== interface
 int eqv_alloc(mlip_ctx* ctx) {
   const mlip_config& cf = ctx->cfg;
@@ -1109,7 +1129,6 @@ int eqv_alloc(mlip_ctx* ctx) {
   const int TAB = 64 * (lmax == 3 ? gaunt::Tab<3>::TAB_LOADS : gaunt::Tab<2>::TAB_LOADS);
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   if (C > 256) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: channels must not exceed 256");
-  if (lmax == 3 && cf.position_grad) MLIP_FAIL(ctx, MLIP_E_UNSUPPORTED, "equivariant model: the position gradient is built for l_max = 2 only");
   EqvWs* w = new EqvWs();
   ctx->model_ws = w;
   bool ok = true;
@@ -1176,13 +1195,14 @@ void eqv_free(mlip_ctx* ctx) {
 }
 
 // TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters;
-// G = the coupling tables of the context's l_max
+// G = the coupling tables of this object's l_max
 #define DISPATCH_G(fn, G, ...)                                                                                      \
   (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                            \
        ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float, G>(__VA_ARGS__) : fn<gemm::Bf16, __bf16, G>(__VA_ARGS__))    \
        : fn<gemm::Fp32, float, G>(__VA_ARGS__))
-#define DISPATCH(fn, ...) \
-  (ctx->cfg.l_max == 3 ? DISPATCH_G(fn, gaunt::Tab<3>, __VA_ARGS__) : DISPATCH_G(fn, gaunt::Tab<2>, __VA_ARGS__))
+enum { EQV_FE, EQV_FF, EQV_BF, EQV_BE };
+#define DISPATCH(fn, which, ...) \
+  (ctx->cfg.l_max == 3 ? eqv_phase_lmax3(ctx, which, __VA_ARGS__) : DISPATCH_G(fn, gaunt::Tab<2>, ctx, __VA_ARGS__))
 
 int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float*,
                        float* E, float*) {
@@ -1194,7 +1214,7 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
   hipLaunchKernelGGL(k_copy_species, dim3(nblk(ctx->N)), dim3(256), 0, st, species, ctx->N, ctx->cfg.n_species, ctx->d_species, ctx->d_flag);
-  MLIP_TRY(DISPATCH(fe_impl, ctx, E));
+  MLIP_TRY(DISPATCH(fe_impl, EQV_FE, E));
   ctx->phase = PH_FE;
   return MLIP_OK;
 }
@@ -1202,7 +1222,7 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
 int eqv_forward_force(mlip_ctx* ctx, const float*, float* F, float*) {
   if (ctx->phase < PH_FE) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_force: run forward_energy first");
   if (!F) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_force: null pointer");
-  MLIP_TRY(DISPATCH(ff_impl, ctx, F));
+  MLIP_TRY(DISPATCH(ff_impl, EQV_FF, F));
   ctx->phase = PH_FF;
   return MLIP_OK;
 }
@@ -1211,7 +1231,7 @@ int eqv_backward_force(mlip_ctx* ctx, const float* v, const float*, float* grad,
   if (ctx->phase < PH_FF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_force: run forward_force first");
   if (!v || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_force: null pointer");
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->v, v, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, ctx->stream));
-  MLIP_TRY(DISPATCH(bf_impl, ctx, grad));
+  MLIP_TRY(DISPATCH(bf_impl, EQV_BF, grad));
   ctx->phase = PH_BF;
   return MLIP_OK;
 }
@@ -1220,7 +1240,8 @@ int eqv_backward_energy(mlip_ctx* ctx, const float* Ebar, const float*, float* g
   if (ctx->phase < PH_BF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_energy: run backward_force first");
   if (!Ebar || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_energy: null pointer");
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->Ebar, Ebar, sizeof(float) * ctx->B, hipMemcpyDeviceToDevice, ctx->stream));
-  MLIP_TRY(DISPATCH(be_impl, ctx, grad));
+  MLIP_TRY(DISPATCH(be_impl, EQV_BE, grad));
   ctx->phase = PH_BE;
   return MLIP_OK;
 }
+#endif  // MLIP_EQV_LMAX

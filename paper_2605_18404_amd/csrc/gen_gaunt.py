@@ -168,52 +168,6 @@ def emit_tab(lmax, L):
     return PATHS, T
 
 
-def emit_straight_line(T, L):
-    """l <= 2 only: the four trilinear contractions as straight-line code (the position-gradient kernel uses them)."""
-    L.append("// out[m3] += sum_p rho[p] sum_{m1 m2} T^p x[m1] y[m2]")
-    L.append("__device__ __forceinline__ void tp_fwd(const float (&rho)[11], const float (&x)[9], const float (&y)[9], float (&out)[9]) {")
-    for p, t in enumerate(T):
-        by = {}
-        for (a, b, c), g in t.items():
-            by.setdefault(c, []).append((a, b, g))
-        for c, terms in sorted(by.items()):
-            expr = " + ".join(f"{f(g)} * x[{a}] * y[{b}]" for a, b, g in terms)
-            L.append(f"  out[{c}] += rho[{p}] * ({expr});")
-    L.append("}")
-    L.append("// out[m1] += sum_p rho[p] sum_{m2 m3} T^p y[m2] mu[m3]")
-    L.append("__device__ __forceinline__ void tp_adj_x(const float (&rho)[11], const float (&y)[9], const float (&mu)[9], float (&out)[9]) {")
-    for p, t in enumerate(T):
-        by = {}
-        for (a, b, c), g in t.items():
-            by.setdefault(a, []).append((b, c, g))
-        for a, terms in sorted(by.items()):
-            expr = " + ".join(f"{f(g)} * y[{b}] * mu[{c}]" for b, c, g in terms)
-            L.append(f"  out[{a}] += rho[{p}] * ({expr});")
-    L.append("}")
-    L.append("// out[m2] += sum_p rho[p] sum_{m1 m3} T^p x[m1] mu[m3]")
-    L.append("__device__ __forceinline__ void tp_adj_y(const float (&rho)[11], const float (&x)[9], const float (&mu)[9], float (&out)[9]) {")
-    for p, t in enumerate(T):
-        by = {}
-        for (a, b, c), g in t.items():
-            by.setdefault(b, []).append((a, c, g))
-        for b, terms in sorted(by.items()):
-            expr = " + ".join(f"{f(g)} * x[{a}] * mu[{c}]" for a, c, g in terms)
-            L.append(f"  out[{b}] += rho[{p}] * ({expr});")
-    L.append("}")
-    L.append("// t[p] = sum_{m1 m2 m3} T^p x[m1] y[m2] mu[m3]")
-    L.append("__device__ __forceinline__ void tp_paths(const float (&x)[9], const float (&y)[9], const float (&mu)[9], float (&t)[11]) {")
-    for p, t in enumerate(T):
-        by = {}
-        for (a, b, c), g in t.items():
-            by.setdefault(c, []).append((a, b, g))
-        parts = []
-        for c, terms in sorted(by.items()):
-            expr = " + ".join(f"{f(g)} * x[{a}] * y[{b}]" for a, b, g in terms)
-            parts.append(f"mu[{c}] * ({expr})")
-        L.append(f"  t[{p}] = " + "\n       + ".join(parts) + ";")
-    L.append("}")
-
-
 def emit():
     L = []
     L.append("// GENERATED by gen_gaunt.py -- do not edit.  Real Gaunt couplings of the even-parity paths (l1, l2, l3) with every")
@@ -225,7 +179,7 @@ def emit():
     L.append("#include <hip/hip_runtime.h>")
     L.append("namespace gaunt {")
     L.append("template <int LMAX>\nstruct Tab;")
-    _, T2 = emit_tab(2, L)
+    emit_tab(2, L)
     emit_tab(3, L)
     L.append("template <int LMAX> __device__ __forceinline__ int ent_m2_dev(int n);")
     L.append("template <> __device__ __forceinline__ int ent_m2_dev<2>(int n) { return ENT_M2_DEV_2[n]; }")
@@ -233,7 +187,6 @@ def emit():
     L.append("template <int LMAX> __device__ __forceinline__ float ent_coef_dev(int n);")
     L.append("template <> __device__ __forceinline__ float ent_coef_dev<2>(int n) { return ENT_COEF_DEV_2[n]; }")
     L.append("template <> __device__ __forceinline__ float ent_coef_dev<3>(int n) { return ENT_COEF_DEV_3[n]; }")
-    emit_straight_line(T2, L)
     L.append("}  // namespace gaunt")
     return "\n".join(L) + "\n"
 

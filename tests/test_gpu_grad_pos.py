@@ -58,6 +58,14 @@ def whole_cases():
         "cfg2_1struct_fp32": (synth.shrink(W[2], n_structs=1, gemm_bf16=False), TOL_FP32),
         "cfg2_1struct_bf16": (synth.shrink(W[2], n_structs=1), TOL_BF16),
         "cfg4_shape_300atoms_bf16": (synth.shrink(W[4], atoms_per_struct=300, box=(300 / 0.1) ** (1 / 3), n_layers=2), TOL_BF16),
+        # features up to degree 3: the Hessian of the degree-3 harmonics depends on the direction
+        "eqv_lmax3_tiny_fp32": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=20, box=7.5, cutoff=3.5, channels=8, edge_hidden=8,
+                                             n_rbf=8, n_layers=2, gemm_bf16=False), TOL_FP32),
+        "eqv_lmax3_multi_image_triclinic_gate_fp32": (synth.shrink(W[2], l_max=3, n_structs=2, atoms_per_struct=16, box=5.0, cutoff=3.5,
+                                                                   channels=12, edge_hidden=16, n_rbf=8, n_layers=2, gemm_bf16=False,
+                                                                   cell_kind="triclinic", gate=1), TOL_FP32),
+        "eqv_lmax3_channels_64_bf16": (synth.shrink(W[2], l_max=3, channels=64, edge_hidden=40, n_rbf=8, atoms_per_struct=14, n_structs=2,
+                                                    box=6.0, cutoff=3.2, n_layers=2), TOL_BF16),
     }
 
 
@@ -122,13 +130,3 @@ def test_position_gradient_needs_its_workspace():
     assert e.value.code == -1
     m.mlip_set_position_grad(None)  # switching off is always accepted
     m.close()
-
-
-def test_position_gradient_is_refused_for_degree3_features():
-    # the second derivatives of the degree-3 harmonics are not built: creating such a context fails with "unsupported"
-    w = synth.shrink(synth.WORKLOADS[2], l_max=3, n_structs=1, atoms_per_struct=8, box=6.0, cutoff=3.0, channels=8, edge_hidden=8,
-                     n_rbf=8, n_layers=1, gemm_bf16=False)
-    with pytest.raises(MlipError) as e:
-        Mlip.for_workload(w, position_grad=1)
-    assert e.value.code == -3
-    Mlip.for_workload(w).close()  # without the option the same model is fine
