@@ -1,9 +1,9 @@
 """Writes the stored oracle summaries the full-size GPU tests compare against.  Calls only the
 oracle, the seeded input generator and the probe definitions; never the HIP path.
 
-    python tests/golden/make_full_size_goldens.py cfg2 cfg3 cfg4
+    python tests/golden/make_full_size_goldens.py cfg2 cfg2_lmax3 cfg3 cfg4
 
-cfg2 (16 x 256 atoms, equivariant) and cfg3 (64 x 128 atoms, pipeline stage at width 512): the
+cfg2 (16 x 256 atoms, equivariant; cfg2_lmax3: the same batch with features up to degree 3) and cfg3 (64 x 128 atoms, pipeline stage at width 512): the
 oracle runs every structure of the batch (structures do not interact); stored are E, the loss, and
 probes.summarise() of the parameter gradient (cfg3: of BF's and BE's shares separately).  Minutes of
 CPU time -- too long for a GPU test, hence stored.
@@ -71,8 +71,9 @@ def _write(name, obj):
     print("wrote", path, os.path.getsize(path), "bytes", flush=True)
 
 
-def make_cfg2():
-    w = synth.WORKLOADS[2]
+def make_cfg2(l_max=2):
+    w = synth.WORKLOADS[2] if l_max == 2 else synth.shrink(synth.WORKLOADS[2], l_max=l_max)
+    tag = "cfg2" if l_max == 2 else "cfg2_lmax%d" % l_max
     inp = synth.make_inputs(w)
     cfg = O.cfg_from_workload(w)
     B, N = w.n_structs, w.n_atoms
@@ -88,10 +89,10 @@ def make_cfg2():
         E[s], F[a:b] = r["E"][0], r["F"]
         loss += r["loss"] / B
         grad += r["grad"] / B
-        print("cfg2 structure", s, f"{time.time() - t0:.1f} s", flush=True)
-    _write("full_size_cfg2.json", dict(
-        what="oracle (float64) on the whole cfg2 batch, seed %d: E per structure, loss, per-structure force norms, "
-             "probes.summarise of dL/dtheta" % w.seed,
+        print(tag, "structure", s, f"{time.time() - t0:.1f} s", flush=True)
+    _write("full_size_%s.json" % tag, dict(
+        what="oracle (float64) on the whole cfg2 batch%s, seed %d: E per structure, loss, per-structure force norms, "
+             "probes.summarise of dL/dtheta" % ("" if l_max == 2 else " with features up to degree %d" % l_max, w.seed),
         E=E.tolist(), loss=loss, F_norm=[float(np.linalg.norm(F[inp.struct_ptr[s]:inp.struct_ptr[s + 1]])) for s in range(B)],
         grad=probes.summarise(w.seed, grad, synth.param_slices(w))))
 
@@ -156,4 +157,4 @@ def make_cfg4():
 
 if __name__ == "__main__":
     for name in sys.argv[1:]:
-        {"cfg2": make_cfg2, "cfg3": make_cfg3, "cfg4": make_cfg4}[name]()
+        {"cfg2": make_cfg2, "cfg2_lmax3": lambda: make_cfg2(3), "cfg3": make_cfg3, "cfg4": make_cfg4}[name]()

@@ -93,15 +93,17 @@ def test_cfg1_full_batch_128_experts():
     m.close()
 
 
-def test_cfg2_full_batch_sampled_structures():
-    w = synth.WORKLOADS[2]
+@pytest.mark.parametrize("l_max", [2, 3])
+def test_cfg2_full_batch_sampled_structures(l_max):
+    # l_max = 3: the same batch with features up to degree 3 (the workload `bench.py --workload cfg2_lmax3` times)
+    w = synth.WORKLOADS[2] if l_max == 2 else synth.shrink(synth.WORKLOADS[2], l_max=3)
     inp = synth.make_inputs(w)
     m = Mlip.for_workload(w)
     d = DevInputs(inp)
     out = m.mlip_train_step(d.pos, d.species, d.struct_ptr, d.cell, w.cutoff, d.params, d.E_ref, d.F_ref)
     torch.cuda.synchronize()
     E, F = out["E"].cpu().numpy(), out["F"].cpu().numpy()
-    for s in (3, 12):  # structures do not interact: E_s and the forces of s are exact per structure
+    for s in ((3, 12) if l_max == 2 else (12,)):  # structures do not interact: E_s and the forces of s are exact per structure
         a, b, r = _oracle_struct(w, inp, s)
         assert abs(E[s] - r["E"][0]) < TOL_BF16 * max(1.0, abs(r["E"][0]))
         assert rel(F[a:b], r["F"]) < TOL_BF16
@@ -111,13 +113,13 @@ def test_cfg2_full_batch_sampled_structures():
     # the whole batch against the stored oracle run of all 16 structures: every energy (relative), every
     # structure's force norm, the loss, and the full gradient (it passes through the split reductions over all
     # 296 k edges, which the two-structure cases do not reach)
-    gold = _golden("full_size_cfg2.json")
+    gold = _golden("full_size_cfg2.json" if l_max == 2 else "full_size_cfg2_lmax3.json")
     assert rel(E, gold["E"]) < TOL_BF16
     assert np.max(np.abs(E - np.array(gold["E"])) / np.abs(gold["E"])) < 3 * TOL_BF16
     fn = [np.linalg.norm(F[inp.struct_ptr[s]:inp.struct_ptr[s + 1]]) for s in range(w.n_structs)]
     assert rel(fn, gold["F_norm"]) < TOL_BF16
     assert abs(float(out["loss"].cpu()) - gold["loss"]) < TOL_BF16 * abs(gold["loss"])
-    _check_probes(w, out["grad"].cpu().numpy(), gold["grad"], TOL_BF16, "cfg2 grad")
+    _check_probes(w, out["grad"].cpu().numpy(), gold["grad"], TOL_BF16, "cfg2 grad, l_max %d" % l_max)
     m.close()
 
 
