@@ -23,10 +23,10 @@
  * Parameter vector (float32, each tensor row-major [out, in], concatenated in this order):
  *    whole model : emb[S,C]; per layer {W1[H,K], W2[C,H], V1[C,C], V2[C,C]} (edge MLP depth 2)
  *                  or {W1[H,K], W2[H,H], W3[C,H], V1, V2} (depth 3); U[C,C]; w_o[C]
- *    equivariant : emb[S,C]; per layer {W1[H,K], W2[11*C,H] (row = path*C + channel),
- *                  Wl0[C,C], Wl1[C,C], Wl2[C,C]}; U[C,C]; w_o[C]
+ *    equivariant : emb[S,C]; per layer {W1[H,K], W2[n_paths*C,H] (row = path*C + channel; n_paths = 11 for
+ *                  l_max = 2, 23 for l_max = 3), Wl0[C,C] .. Wl{l_max}[C,C]}; U[C,C]; w_o[C]
  *    stage       : the per-layer blocks only.
- *    With n_experts > 0 the node-level matrices (V1, V2; Wl0, Wl1, Wl2) are banks
+ *    With n_experts > 0 the node-level matrices (V1, V2; Wl0 .. Wl{l_max}) are banks
  *    [n_experts, C, C] in place of [C, C] (see mlip_set_expert_weights).
  *
  * Model (no biases anywhere; sigma = SiLU):
@@ -34,9 +34,10 @@
  *    f_c(r) = (1 + cos(pi r / r_c)) / 2;
  *    invariant layer: w_e = W2 sigma(W1 phi(r_e))  (depth 3: W3 sigma(W2 sigma(W1 phi))),
  *        a_i = sum_{e=(i<-j)} f_c(r_e) w_e (.) h_j,   h_i <- h_i + V2 sigma(V1 a_i);
- *    equivariant layer (features h_i[c; l m], l <= 2): radial weights R_e = W2 sigma(W1 phi(r_e)) as
- *        [11 paths, C]; m_e[c; l3 m3] = f_c(r_e) sum_p R_e[p, c] sum_{m1 m2} T^p[m1 m2 m3]
- *        h_j[c; l1 m1] Y_{l2 m2}(r_e / r_e) over the 11 even-parity paths p = (l1, l2, l3) with real Gaunt
+ *    equivariant layer (features h_i[c; l m], l <= l_max = 2 or 3): radial weights R_e = W2 sigma(W1 phi(r_e)) as
+ *        [n_paths, C]; m_e[c; l3 m3] = f_c(r_e) sum_p R_e[p, c] sum_{m1 m2} T^p[m1 m2 m3]
+ *        h_j[c; l1 m1] Y_{l2 m2}(r_e / r_e) over the even-parity paths p = (l1, l2, l3) with every degree <= l_max
+ *        (triangle rule, l1 + l2 + l3 even, ordered by (l1, l2, l3): 11 paths for l_max = 2, 23 for 3) with real Gaunt
  *        tensors T^p scaled to sum T^2 = 2 l3 + 1 and component-normalised real harmonics Y;
  *        a_i = sum_e m_e;  u_i[l] = Wl^(l) a_i[l];  h_i <- h_i + u_i, or with mlip_config.gate the gated
  *        update h_i[c; 0] += sigma(u_i[c; 0]), h_i[c; l m] += sigmoid(u_i[c; 0]) u_i[c; l m];
