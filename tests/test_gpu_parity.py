@@ -551,8 +551,12 @@ def test_equivariant_bf16_molecules_gradient_shares():
     m.close()
 
 
-def test_isolated_atoms_zero_edges():
+@pytest.mark.parametrize("which", ["invariant", "equivariant", "equivariant_lmax3"])
+def test_isolated_atoms_zero_edges(which):
     w = synth.shrink(synth.WORKLOADS[0], atoms_per_struct=3, box=20.0, min_dist=6.0)
+    if which != "invariant":  # no edges: every message kernel runs over empty rows, every edge product is skipped
+        w = synth.shrink(synth.WORKLOADS[2], n_structs=2, atoms_per_struct=3, box=20.0, min_dist=6.5, channels=8, edge_hidden=8, n_rbf=8,
+                         n_layers=2, gemm_bf16=False, l_max=3 if which.endswith("lmax3") else 2)
     inp = synth.make_inputs(w)
     ref = oracle_train_step(w, inp)
     m = Mlip.for_workload(w)
