@@ -241,6 +241,10 @@ __device__ __forceinline__ void tab_publish(const TabRegs<G>& r, float* slot, in
 // The coupling entries n = (p; m1, m2, m3) are ordered by slot (p, m3), so a slot's entries are consecutive: sums over a
 // slot's entries are kept in one register and handed on at the slot's last entry (ENT_SFIRST / ENT_SLAST), and a value that
 // belongs to the slot is formed at its first entry.  No array over the slots is ever held.
+// L0 (the model's first layer): the features entering it have their l = 0 component only (the embedding) and no tangent
+// (the embedding does not depend on the positions), so of the coupling entries n = (p; m1, m2, m3) only those with m1 = 0
+// contribute -- the paths (0, l, l), one entry per slot -- and one sender value per edge is gathered instead of a row of
+// NM; FF needs no adjoint of the embedding, BE only the l = 0 component of it (the embedding's gradient).
 template <int N>
 __device__ __forceinline__ void zero(float (&x)[N]) {
 #pragma unroll
@@ -258,7 +262,7 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <typename G, typename TF, bool UNI>
+template <typename G, typename TF, bool UNI, bool L0>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
@@ -276,7 +280,7 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
   for (int e = e0; e < e1; ++e) {
     const int j = jn;
     jn = sender[e + 1 < e1 ? e + 1 : e];  // next edge's sender: its gathers need not wait for an index
-    float x[NM], rho[NPATH];
+    float x[L0 ? 1 : NM], rho[NPATH];
     const float* cy = cyt + (int64_t)e * CY_LD;
     TabRegs<G> tr;
     if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
@@ -287,15 +291,19 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
     static_for<0, G::NNZ>([&](auto n_) {
       constexpr int n = decltype(n_)::value;
       constexpr int sl = G::ENT_SLOT[n];
-      S = G::ENT_SFIRST[n] ? cy[n] * x[G::ENT_M1[n]] : fmaf(cy[n], x[G::ENT_M1[n]], S);
-      if (G::ENT_SLAST[n]) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], S, acc[G::SLOT_M3[sl]]);
+      if constexpr (L0) {
+        if constexpr (G::ENT_M1[n] == 0) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], cy[n] * x[0], acc[G::SLOT_M3[sl]]);
+      } else {
+        S = G::ENT_SFIRST[n] ? cy[n] * x[G::ENT_M1[n]] : fmaf(cy[n], x[G::ENT_M1[n]], S);
+        if (G::ENT_SLAST[n]) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], S, acc[G::SLOT_M3[sl]]);
+      }
     });
   }
 #pragma unroll
   for (int m = 0; m < NM; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
 }
 
-template <typename G, typename TF, bool UNI>
+template <typename G, typename TF, bool UNI, bool L0>
 __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
@@ -309,8 +317,9 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
   if (t.active) {
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
-    float acc[NM], xi[NM], mi[NM];
-    loadm(mu_h_next, NC, io, acc);
+    constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features
+    float acc[NM], xi[NX], mi[NM];
+    if constexpr (!L0) loadm(mu_h_next, NC, io, acc);
     loadm(h, NC, io, xi);
     loadm(mu_a, NC, io, mi);
     float* slot = tabs[threadIdx.x >> 6];
@@ -324,7 +333,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       const float* cy = cyt + (int64_t)e * CY_LD;
       TabRegs<G> tr;
       if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
-      float xj[NM], mj[NM], rho[NPATH], rhop[NPATH];
+      float xj[NX], mj[NM], rho[NPATH], rhop[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
       loadm(h, NC, jo, xj);
       loadm(mu_a, NC, jo, mj);
@@ -332,7 +341,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       load_rho(rrow, t.c, rho);
       load_rho(rrow + NPP * C, t.c, rhop);
       if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
-      {  // the message this atom sends back along the reversed edge: couplings of -u
+      if constexpr (!L0) {  // the message this atom sends back along the reversed edge: couplings of -u
         float R = 0.f;
         static_for<0, G::NNZ>([&](auto n_) {
           constexpr int n = decltype(n_)::value;
@@ -348,7 +357,17 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       float s = 0.f;
       float nu[NM];
       zero(nu);
-      if constexpr (G::LMAX == 2) {
+      if constexpr (L0) {
+        static_for<0, G::NNZ>([&](auto n_) {
+          constexpr int n = decltype(n_)::value;
+          constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m2 = G::ENT_M2[n];
+          if constexpr (G::ENT_M1[n] == 0) {
+            const float W = fmaf(G::PATH_SIGN[p] * xi[0], mj[m3], xj[0] * mi[m3]);
+            s = fmaf(rhop[p] * cy[n], W, s);
+            nu[m2] = fmaf(rho[p] * G::ENT_COEF[n], W, nu[m2]);
+          }
+        });
+      } else if constexpr (G::LMAX == 2) {
         // few entries: the per-path and per-(path, m2) sums are kept side by side while the entries are walked in table order,
         // the order in which the loop above has left the table's values in registers
         float sp[NPATH], Gy[G::NYSLOT];
@@ -386,8 +405,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       f.y += s * g.y + (w.y - g.y * uw) * inv;
       f.z += s * g.z + (w.z - g.z * uw) * inv;
     }
+    if constexpr (!L0) {
 #pragma unroll
-    for (int m = 0; m < NM; ++m) mu_h[m * NC + io] = acc[m];
+      for (int m = 0; m < NM; ++m) mu_h[m * NC + io] = acc[m];
+    }
   }
   red[threadIdx.x] = f;
   __syncthreads();
@@ -403,7 +424,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
   }
 }
 
-template <typename G, typename TX, typename TF, bool UNI>
+template <typename G, typename TX, typename TF, bool UNI, bool L0>
 __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -433,10 +454,11 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
     if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
-    float xj[NM], xdj[NM], rho[NPATH], rr[NPATH];
+    constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features (their tangent vanishes in the first layer)
+    float xj[NX], xdj[NX], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
     loadm(h, NC, jo, xj);
-    loadm(hd, NC, jo, xdj);
+    if constexpr (!L0) loadm(hd, NC, jo, xdj);
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
@@ -451,12 +473,21 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     static_for<0, G::NNZ>([&](auto n_) {
       constexpr int n = decltype(n_)::value;
       constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n];
-      S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
-      S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
-      if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
-      if (G::ENT_SLAST[n]) {
-        acc[m3] = fmaf(rr[p], S1, fmaf(rho[p], S23, acc[m3]));
-        tp[p] = fmaf(mi[m3], S1, tp[p]);
+      if constexpr (L0) {
+        if constexpr (m1 == 0) {  // the slot's only live entry
+          const float s1 = cy[n] * xj[0];
+          acc[m3] = fmaf(rr[p], s1, acc[m3]);
+          if constexpr (G::ENT_M2[n] != 0) acc[m3] = fmaf(rho[p] * cyd[n], xj[0], acc[m3]);
+          tp[p] = fmaf(mi[m3], s1, tp[p]);
+        }
+      } else {
+        S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
+        S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
+        if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
+        if (G::ENT_SLAST[n]) {
+          acc[m3] = fmaf(rr[p], S1, fmaf(rho[p], S23, acc[m3]));
+          tp[p] = fmaf(mi[m3], S1, tp[p]);
+        }
       }
     });
     const float s = rd * env[e].x;
@@ -473,7 +504,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
 // written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.
 // Holding an edge's row of X back for one trip of the loop, so that its stores follow the next edge's loads, changed nothing:
 // two waves per SIMD already cover the store acknowledgements.)
-template <typename G, typename TX, typename TF, bool UNI>
+template <typename G, typename TX, typename TF, bool UNI, bool L0>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -486,7 +517,8 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
   const int64_t io = (int64_t)t.row * C + t.c;
-  float mi[NM], li[NM], acc[NM];
+  constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features, and needed ones of their adjoint
+  float mi[NM], li[NM], acc[NX];
   loadm(mu_a, NC, io, mi);
   loadm(lam_a, NC, io, li);
   loadm(lam_h_next, NC, io, acc);
@@ -503,10 +535,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
     if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
-    float xj[NM], xdj[NM], lj[NM], mj[NM], rho[NPATH], rr[NPATH];
+    float xj[NX], xdj[NX], lj[NM], mj[NM], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
     loadm(h, NC, jo, xj);
-    loadm(hd, NC, jo, xdj);
+    if constexpr (!L0) loadm(hd, NC, jo, xdj);
     loadm(lam_a, NC, jo, lj);
     loadm(mu_a, NC, jo, mj);
     const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
@@ -526,18 +558,33 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     static_for<0, G::NNZ>([&](auto n_) {
       constexpr int n = decltype(n_)::value;
       constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n];
-      if (G::ENT_SFIRST[n]) {
-        R2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
-        R1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
-      }
-      acc[m1] = fmaf(cy[n], R1, acc[m1]);
-      if constexpr (G::ENT_M2[n] != 0) acc[m1] = fmaf(cyd[n], R2, acc[m1]);
-      S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
-      S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
-      if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
-      if (G::ENT_SLAST[n]) {
-        ta[p] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[p]));
-        t4[p] = fmaf(mi[m3], S1, t4[p]);
+      if constexpr (L0) {
+        if constexpr (m1 == 0) {  // the slot's only live entry
+          const float r2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
+          const float r1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
+          acc[0] = fmaf(cy[n], r1, acc[0]);
+          const float s1 = cy[n] * xj[0];
+          ta[p] = fmaf(li[m3], s1, ta[p]);
+          if constexpr (G::ENT_M2[n] != 0) {
+            acc[0] = fmaf(cyd[n], r2, acc[0]);
+            ta[p] = fmaf(mi[m3] * cyd[n], xj[0], ta[p]);
+          }
+          t4[p] = fmaf(mi[m3], s1, t4[p]);
+        }
+      } else {
+        if (G::ENT_SFIRST[n]) {
+          R2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
+          R1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
+        }
+        acc[m1] = fmaf(cy[n], R1, acc[m1]);
+        if constexpr (G::ENT_M2[n] != 0) acc[m1] = fmaf(cyd[n], R2, acc[m1]);
+        S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
+        S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
+        if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
+        if (G::ENT_SLAST[n]) {
+          ta[p] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[p]));
+          t4[p] = fmaf(mi[m3], S1, t4[p]);
+        }
       }
     });
     const float2 cc = env[e];
@@ -547,7 +594,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     store_paths(X + (int64_t)e * NPP * C, t.c, ta);
   }
 #pragma unroll
-  for (int m = 0; m < NM; ++m) lam_h[m * NC + io] = acc[m];
+  for (int m = 0; m < NX; ++m) lam_h[m * NC + io] = acc[m];  // first layer: only the l = 0 component is needed (the embedding's gradient)
 }
 
 
@@ -897,7 +944,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      auto kern = uni ? k_tp_fe<G, TF, true> : k_tp_fe<G, TF, false>;
+      auto kern = l == 0 ? (uni ? k_tp_fe<G, TF, true, true> : k_tp_fe<G, TF, false, true>) : (uni ? k_tp_fe<G, TF, true, false> : k_tp_fe<G, TF, false, false>);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Rho[l]),
                          w->cy, w->h[l], (int)N, C, w->a[l]);
     }
@@ -946,7 +993,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
       mix_mm<P>(ctx, l, k, true, LdPlain{mu_z + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    auto kern = uni ? k_tp_ff<G, TF, true> : k_tp_ff<G, TF, false>;
+    auto kern = l == 0 ? (uni ? k_tp_ff<G, TF, true, true> : k_tp_ff<G, TF, false, true>) : (uni ? k_tp_ff<G, TF, true, false> : k_tp_ff<G, TF, false, false>);
     hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                        w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
@@ -978,7 +1025,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      auto kern = uni ? k_tp_bf<G, TX, TF, true> : k_tp_bf<G, TX, TF, false>;
+      auto kern = l == 0 ? (uni ? k_tp_bf<G, TX, TF, true, true> : k_tp_bf<G, TX, TF, false, true>) : (uni ? k_tp_bf<G, TX, TF, true, false> : k_tp_bf<G, TX, TF, false, false>);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
@@ -1060,7 +1107,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      auto kern = uni ? k_tp_be<G, TX, TF, true> : k_tp_be<G, TX, TF, false>;
+      auto kern = l == 0 ? (uni ? k_tp_be<G, TX, TF, true, true> : k_tp_be<G, TX, TF, false, true>) : (uni ? k_tp_be<G, TX, TF, true, false> : k_tp_be<G, TX, TF, false, false>);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
