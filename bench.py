@@ -47,13 +47,23 @@ def kernel_table(w, E, N):
     and node table touched once, indices and geometry included.  Equivariant tensor-product kernels: fp32
     vector flop = 2 (nnz(T) + components * paths) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
     FF, 3 in BF, 4 in BE; 83 + 9 * 11 for l <= 2, 353 + 16 * 23 for l <= 3), with two HBM byte counts beside it:
-    `hbm_streamed` = what this build moves (the materialised filter jets, 12 (24) values per channel and row, and their adjoints) and `hbm_floor` = node
+    `hbm_streamed` = what this build moves (the materialised filter jets, 12 (24) values per channel and row, and their adjoints)
+    In the first layer the features have their l = 0 component only, so the method itself needs just the l_max + 1 paths
+    (0, l, l) there ((l_max + 1)^2 coupling entries, 4 stored values per channel): all per-launch figures of the equivariant
+    model are averages over the layers' launches with that layer counted at its own size. and `hbm_floor` = node
     tables once plus 20 bytes per edge, what an implementation that recomputed the filters would move."""
     C, H, K = w.channels, w.edge_hidden, w.n_rbf
     eqv = w.l_max >= 2
     nnz, n_paths, n_comp, n_stored = COUPLINGS[w.l_max] if eqv else (0, 1, 1, 1)
-    Co = n_paths * C if eqv else C     # width of the radial filter per edge
-    Cs = n_stored * C if eqv else C    # stored width (one pad per channel in the equivariant layout)
+    L = w.n_layers
+    if eqv:  # layer averages (first layer: l_max + 1 paths, 4 stored values, (l_max + 1)^2 entries)
+        n_paths_avg = ((L - 1) * n_paths + (w.l_max + 1)) / L
+        n_stored_avg = ((L - 1) * n_stored + 4) / L
+        tp_flop_avg = ((L - 1) * (nnz + n_comp * n_paths) + ((w.l_max + 1) ** 2 + n_comp * (w.l_max + 1))) / L
+    else:
+        n_paths_avg = n_stored_avg = 1
+    Co = n_paths_avg * C               # width of the radial filter per edge
+    Cs = n_stored_avg * C              # stored width (one pad per channel in the equivariant layout)
     f4 = 4
     fj = 2 if (w.gemm_bf16 and not getattr(w, "filter_fp32", 0)) else 4   # filter jets
     fx = 2 if w.gemm_bf16 else 4                                           # their adjoints (matrix-product operands)
@@ -75,7 +85,7 @@ def kernel_table(w, E, N):
     names = {3: "msg_fe", 4: "msg_ff", 5: "msg_bf", 6: "msg_be"}
     for kid in (3, 4, 5, 6):
         if eqv:
-            flop = 2.0 * (nnz + n_comp * n_paths) * C * E * (kid - 2)
+            flop = 2.0 * tp_flop_avg * C * E * (kid - 2)
             t[kid] = (names[kid], "alu", flop, {"hbm_streamed_bytes": streamed[kid], "hbm_floor_bytes": tables[kid] * node + 20 * E})
         else:
             t[kid] = (names[kid], "hbm", streamed[kid], {})

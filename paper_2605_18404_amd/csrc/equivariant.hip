@@ -45,6 +45,8 @@ struct EqvWs {
   std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [NPP C][H]
   std::vector<float*> WpT;  // and their transpose [H][NPP C]
   float* gWp = nullptr;     // [NPP C][H] weight gradient in the regrouped row order
+  float* Wp0 = nullptr;     // first layer: the rows of its live paths only, [4 C][H], and the transpose [H][4 C]
+  float* WpT0 = nullptr;
   std::vector<float*> Wm[4], WmT[4];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
   float* cy = nullptr;      // [E][CY_LD] coupling coefficient x harmonic of the edge direction
   float* cyd = nullptr;     // [E][CY_LD] the same with the directional derivative of the harmonics (BF, BE)
@@ -244,7 +246,9 @@ __device__ __forceinline__ void tab_publish(const TabRegs<G>& r, float* slot, in
 // L0 (the model's first layer): the features entering it have their l = 0 component only (the embedding) and no tangent
 // (the embedding does not depend on the positions), so of the coupling entries n = (p; m1, m2, m3) only those with m1 = 0
 // contribute -- the paths (0, l, l), one entry per slot -- and one sender value per edge is gathered instead of a row of
-// NM; FF needs no adjoint of the embedding, BE only the l = 0 component of it (the embedding's gradient).
+// NM; FF needs no adjoint of the embedding, BE only the l = 0 component of it (the embedding's gradient).  Those paths
+// are the first l_max + 1 in the path order, so the first layer's filter jets and their adjoints are computed, stored and
+// multiplied for these paths alone: rows of 4 values per channel instead of NPP, a filter product of 4 C columns.
 template <int N>
 __device__ __forceinline__ void zero(float (&x)[N]) {
 #pragma unroll
@@ -266,7 +270,7 @@ template <typename G, typename TF, bool UNI, bool L0>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
-  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD;
+  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD;  // paths and row width of this layer
   RowChan t = row_chan(N, C);
   if (!t.active) return;  // no workgroup barrier below
   const int64_t NC = (int64_t)N * C;
@@ -309,7 +313,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
                                                   const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
                                                   int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
-  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   __shared__ float3 red[256];
   __shared__ float tabs[4][64 * G::TAB_LOADS];
   RowChan t = row_chan(N, C);
@@ -432,7 +436,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a, int N, int C,
                                                   float* __restrict__ ad,
                                                   TX* __restrict__ X) {
-  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -512,7 +516,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                   const float* __restrict__ lam_a, const float* __restrict__ lam_h_next, int N, int C,
                                                   float* __restrict__ lam_h, TX* __restrict__ X) {
-  constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
@@ -914,7 +918,11 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
   };
   for (int l = 0; l < L; ++l) {
-    hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, NPATH, NPP, w->Wp[l], w->WpT[l]);
+    // the first layer multiplies by its live paths only (the first LMAX + 1, rows of 4 per channel); the position gradient's
+    // products need all paths there too
+    if (l == 0) hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)4 * C * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, LMAX + 1, 4, w->Wp0, w->WpT0);
+    if (l > 0 || cf.position_grad)
+      hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, NPATH, NPP, w->Wp[l], w->WpT[l]);
     for (int k = 0; k <= LMAX; ++k) {
       if (cf.n_experts > 0)
         hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C, 64), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
@@ -940,7 +948,9 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
         gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PC, 2 * E});
+      const int PCl = l == 0 ? 4 * C : PC;  // filter width of this layer
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), l == 0 ? w->Wp0 : w->Wp[l], 2 * E, PCl, H,
+                 EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PCl, 2 * E});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
@@ -1023,6 +1033,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
+    const int PCl = l == 0 ? 4 * C : PC;  // width of this layer's filter jets and adjoints
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
       auto kern = l == 0 ? (uni ? k_tp_bf<G, TX, TF, true, true> : k_tp_bf<G, TX, TF, false, true>) : (uni ? k_tp_bf<G, TX, TF, true, false> : k_tp_bf<G, TX, TF, false, false>);
@@ -1041,13 +1052,13 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::odd(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, NPATH, NPP, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::odd(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, l == 0 ? LMAX + 1 : NPATH, l == 0 ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), l == 0 ? w->WpT0 : w->WpT[l], E, H, PCl, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -1093,6 +1104,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   if (want_gp) hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 0.f, 3 * N);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
+    const int PCl = l == 0 ? 4 * C : PC;  // width of this layer's filter jets and adjoints
     float* lh_next = w->lam_h[cur];
     float* lh = w->lam_h[cur ^ 1];
     const float* lam_z = lh_next;  // adjoint of the update's output; through the gate it becomes that of W a
@@ -1124,13 +1136,13 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PC * H);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PC), Act<P>::even(w->U[l], w->SJ[l], H), E, PC, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, w->gWp, C, H, NPATH, NPP, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::even(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, l == 0 ? LMAX + 1 : NPATH, l == 0 ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PC), w->WpT[l], E, H, PC, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), l == 0 ? w->WpT0 : w->WpT[l], E, H, PCl, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -1193,6 +1205,9 @@ int eqv_alloc(mlip_ctx* ctx) {
   auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
   w->X = AH(E * PC);
   w->gWp = A((int64_t)PC * H);
+  w->Wp0 = A((int64_t)4 * C * H);
+  w->WpT0 = A((int64_t)4 * C * H);
+  if (cf.gemm_dtype == MLIP_GEMM_BF16 && ok) ok &= add_shadow(ctx, w->Wp0, (int64_t)4 * C * H) && add_shadow(ctx, w->WpT0, (int64_t)4 * C * H);
   w->cy = A(E * CY_LD + TAB);  // + TAB: the cooperative fetch of the last edge's table reads TAB floats from its start
   w->cyd = A(E * CY_LD + TAB);
   w->X2 = AH(E * H);
