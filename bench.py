@@ -47,28 +47,34 @@ def kernel_table(w, E, N):
     and node table touched once, indices and geometry included.  Equivariant tensor-product kernels: fp32
     vector flop = 2 (nnz(T) + components * paths) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
     FF, 3 in BF, 4 in BE; 83 + 9 * 11 for l <= 2, 353 + 16 * 23 for l <= 3), with two HBM byte counts beside it:
-    `hbm_streamed` = what this build moves (the materialised filter jets, 12 (24) values per channel and row, and their adjoints)
-    In the first layer the features have their l = 0 component only, so the method itself needs just the l_max + 1 paths
-    (0, l, l) there ((l_max + 1)^2 coupling entries, 4 stored values per channel): all per-launch figures of the equivariant
-    model are averages over the layers' launches with that layer counted at its own size. and `hbm_floor` = node
-    tables once plus 20 bytes per edge, what an implementation that recomputed the filters would move."""
+    `hbm_streamed` = what this build moves (the materialised filter jets, 12 (24) values per channel and row, and their
+    adjoints, and every node table touched once) and `hbm_floor` = node tables once plus 20 bytes per edge, what an
+    implementation that recomputed the filters would move.
+    The first layer's input has its l = 0 component only and the readout takes only the l = 0 component of the last
+    layer's output, so the method itself needs just l_max + 1 paths in each of these two layers -- (0, l, l) and (l, l, 0),
+    (l_max + 1)^2 coupling entries, 4 stored values per channel, node tables of one component where only one is live: all
+    per-launch figures of the equivariant model are averages over the layers' launches, each layer counted at its own size."""
     C, H, K = w.channels, w.edge_hidden, w.n_rbf
     eqv = w.l_max >= 2
     nnz, n_paths, n_comp, n_stored = COUPLINGS[w.l_max] if eqv else (0, 1, 1, 1)
     L = w.n_layers
-    if eqv:  # layer averages (first layer: l_max + 1 paths, 4 stored values, (l_max + 1)^2 entries)
-        n_paths_avg = ((L - 1) * n_paths + (w.l_max + 1)) / L
-        n_stored_avg = ((L - 1) * n_stored + 4) / L
-        tp_flop_avg = ((L - 1) * (nnz + n_comp * n_paths) + ((w.l_max + 1) ** 2 + n_comp * (w.l_max + 1))) / L
-    else:
-        n_paths_avg = n_stored_avg = 1
-    Co = n_paths_avg * C               # width of the radial filter per edge
-    Cs = n_stored_avg * C              # stored width (one pad per channel in the equivariant layout)
     f4 = 4
     fj = 2 if (w.gemm_bf16 and not getattr(w, "filter_fp32", 0)) else 4   # filter jets
     fx = 2 if w.gemm_bf16 else 4                                           # their adjoints (matrix-product operands)
-    node = n_comp * N * C * f4
     geo = 16 + 4                       # unit vector + length, sender index
+    tab = N * C * f4                   # one component of a node table
+    M = n_comp
+    # per layer kind: paths, stored values per channel, coupling entries, node-table components touched by FE, FF, BF, BE
+    general = (n_paths, n_stored, nnz, (2 * M, 4 * M, 4 * M, 6 * M))
+    if eqv:
+        lp = w.l_max + 1
+        first = (lp, 4, lp * lp, (1 + M, 1 + M, 1 + 2 * M, 3 + 2 * M))
+        last = (lp, 4, lp * lp, (M + 1, 2 + 2 * M, 2 + 2 * M, 3 + 3 * M))
+        layers = [first] + [general] * (L - 2) + ([last] if L >= 2 else [])
+    else:
+        layers = [general] * L
+    avg = lambda f: sum(f(x) for x in layers) / len(layers)
+    Co = avg(lambda x: x[0]) * C       # width of the radial filter per edge
     t = {
         1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H, {}),
         2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co, {}),
@@ -77,18 +83,18 @@ def kernel_table(w, E, N):
         9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
         10: ("be_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
     }
-    streamed = {3: E * Cs * fj + 2 * node + E * geo,
-                4: 2 * E * Cs * fj + 4 * node + E * geo,
-                5: 2 * E * Cs * fj + E * Cs * fx + 4 * node + E * (geo + 8),
-                6: 2 * E * Cs * fj + E * Cs * fx + 6 * node + E * (geo + 8)}
-    tables = {3: 2, 4: 4, 5: 4, 6: 6}
+    jets = {3: 1, 4: 2, 5: 2, 6: 2}    # filter-jet rows read per edge
+    adj = {3: 0, 4: 0, 5: 1, 6: 1}     # adjoint rows written per edge
+    extra = {3: 0, 4: 0, 5: 8, 6: 8}   # envelope pair
     names = {3: "msg_fe", 4: "msg_ff", 5: "msg_bf", 6: "msg_be"}
     for kid in (3, 4, 5, 6):
+        streamed = avg(lambda x: E * x[1] * C * (jets[kid] * fj + adj[kid] * fx) + x[3][kid - 3] * tab) + E * (geo + extra[kid])
         if eqv:
-            flop = 2.0 * tp_flop_avg * C * E * (kid - 2)
-            t[kid] = (names[kid], "alu", flop, {"hbm_streamed_bytes": streamed[kid], "hbm_floor_bytes": tables[kid] * node + 20 * E})
+            flop = 2.0 * avg(lambda x: x[2] + M * x[0]) * C * E * (kid - 2)
+            floor = avg(lambda x: x[3][kid - 3] * tab) + 20 * E
+            t[kid] = (names[kid], "alu", flop, {"hbm_streamed_bytes": streamed, "hbm_floor_bytes": floor})
         else:
-            t[kid] = (names[kid], "hbm", streamed[kid], {})
+            t[kid] = (names[kid], "hbm", streamed, {})
     return dict(sorted(t.items()))
 
 

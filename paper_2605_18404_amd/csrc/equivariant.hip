@@ -47,6 +47,8 @@ struct EqvWs {
   float* gWp = nullptr;     // [NPP C][H] weight gradient in the regrouped row order
   float* Wp0 = nullptr;     // first layer: the rows of its live paths only, [4 C][H], and the transpose [H][4 C]
   float* WpT0 = nullptr;
+  float* WpZ = nullptr;     // last layer: the same for its live paths
+  float* WpTZ = nullptr;
   std::vector<float*> Wm[4], WmT[4];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
   float* cy = nullptr;      // [E][CY_LD] coupling coefficient x harmonic of the edge direction
   float* cyd = nullptr;     // [E][CY_LD] the same with the directional derivative of the harmonics (BF, BE)
@@ -249,6 +251,14 @@ __device__ __forceinline__ void tab_publish(const TabRegs<G>& r, float* slot, in
 // NM; FF needs no adjoint of the embedding, BE only the l = 0 component of it (the embedding's gradient).  Those paths
 // are the first l_max + 1 in the path order, so the first layer's filter jets and their adjoints are computed, stored and
 // multiplied for these paths alone: rows of 4 values per channel instead of NPP, a filter product of 4 C columns.
+// LZ (the model's last layer, if it is not also the first): the readout takes the l = 0 component of its output only, so
+// only the entries with m3 = 0 contribute -- the paths (l, l, 0), G::LAST_PATHS, whose filter rows are regrouped to the
+// same rows of 4 -- and the cotangents mu_a, lam_a of that layer have their l = 0 component only: FE and BF produce one
+// component, FF and BE gather one component of each adjoint instead of NM.
+enum { LS_ANY = 0, LS_FIRST = 1, LS_LAST = 2 };  // which layer a tensor-product kernel is specialised for
+// position of path p in a layer's stored filter rows
+template <typename G, int LS>
+__host__ __device__ constexpr int path_row(int p) { return LS == LS_LAST ? G::LAST_K[p] : p; }
 template <int N>
 __device__ __forceinline__ void zero(float (&x)[N]) {
 #pragma unroll
@@ -266,15 +276,17 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <typename G, typename TF, bool UNI, bool L0>
+template <typename G, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
-  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD;  // paths and row width of this layer
+  constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
+  constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD;  // paths and row width of this layer
+  constexpr int NA = LZ ? 1 : NM;  // components of the output that anything reads
   RowChan t = row_chan(N, C);
   if (!t.active) return;  // no workgroup barrier below
   const int64_t NC = (int64_t)N * C;
-  float acc[NM];
+  float acc[NA];
   zero(acc);
   __shared__ float tabs[4][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6];
@@ -297,23 +309,24 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
       constexpr int sl = G::ENT_SLOT[n];
       if constexpr (L0) {
         if constexpr (G::ENT_M1[n] == 0) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], cy[n] * x[0], acc[G::SLOT_M3[sl]]);
-      } else {
+      } else if constexpr (!LZ || G::SLOT_M3[sl] == 0) {
         S = G::ENT_SFIRST[n] ? cy[n] * x[G::ENT_M1[n]] : fmaf(cy[n], x[G::ENT_M1[n]], S);
-        if (G::ENT_SLAST[n]) acc[G::SLOT_M3[sl]] = fmaf(rho[G::SLOT_P[sl]], S, acc[G::SLOT_M3[sl]]);
+        if (G::ENT_SLAST[n]) acc[G::SLOT_M3[sl]] = fmaf(rho[path_row<G, LS>(G::SLOT_P[sl])], S, acc[G::SLOT_M3[sl]]);
       }
     });
   }
 #pragma unroll
-  for (int m = 0; m < NM; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
+  for (int m = 0; m < NA; ++m) a[m * NC + (int64_t)t.row * C + t.c] = acc[m];
 }
 
-template <typename G, typename TF, bool UNI, bool L0>
+template <typename G, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
                                                   const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
                                                   int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
-  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
+  constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   __shared__ float3 red[256];
   __shared__ float tabs[4][64 * G::TAB_LOADS];
   RowChan t = row_chan(N, C);
@@ -322,8 +335,14 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
     constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features
-    float acc[NM], xi[NX], mi[NM];
-    if constexpr (!L0) loadm(mu_h_next, NC, io, acc);
+    constexpr int NU = LZ ? 1 : NM;  // live components of the cotangent of the layer's messages
+    float acc[NM], xi[NX], mi[NU];
+    if constexpr (LZ) {  // the readout's cotangent has its l = 0 component only
+      zero(acc);
+      acc[0] = mu_h_next[io];
+    } else if constexpr (!L0) {
+      loadm(mu_h_next, NC, io, acc);
+    }
     loadm(h, NC, io, xi);
     loadm(mu_a, NC, io, mi);
     float* slot = tabs[threadIdx.x >> 6];
@@ -337,7 +356,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       const float* cy = cyt + (int64_t)e * CY_LD;
       TabRegs<G> tr;
       if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
-      float xj[NX], mj[NM], rho[NPATH], rhop[NPATH];
+      float xj[NX], mj[NU], rho[NPATH], rhop[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
       loadm(h, NC, jo, xj);
       loadm(mu_a, NC, jo, mj);
@@ -350,8 +369,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
         static_for<0, G::NNZ>([&](auto n_) {
           constexpr int n = decltype(n_)::value;
           constexpr int sl = G::ENT_SLOT[n];
-          if (G::ENT_SFIRST[n]) R = G::PATH_SIGN[G::SLOT_P[sl]] * rho[G::SLOT_P[sl]] * mj[G::SLOT_M3[sl]];
-          acc[G::ENT_M1[n]] = fmaf(cy[n], R, acc[G::ENT_M1[n]]);
+          if constexpr (!LZ || G::SLOT_M3[sl] == 0) {
+            if (G::ENT_SFIRST[n]) R = G::PATH_SIGN[G::SLOT_P[sl]] * rho[path_row<G, LS>(G::SLOT_P[sl])] * mj[G::SLOT_M3[sl]];
+            acc[G::ENT_M1[n]] = fmaf(cy[n], R, acc[G::ENT_M1[n]]);
+          }
         });
       }
       // Force terms.  With W_n = x_j[m1] mu_i[m3] + sign_p x_i[m1] mu_j[m3] per coupling entry n = (p; m1, m2, m3), formed
@@ -361,14 +382,15 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       float s = 0.f;
       float nu[NM];
       zero(nu);
-      if constexpr (L0) {
+      if constexpr (L0 || LZ) {  // few live entries (m1 = 0, or m3 = 0): each adds to both sums directly
         static_for<0, G::NNZ>([&](auto n_) {
           constexpr int n = decltype(n_)::value;
-          constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m2 = G::ENT_M2[n];
-          if constexpr (G::ENT_M1[n] == 0) {
-            const float W = fmaf(G::PATH_SIGN[p] * xi[0], mj[m3], xj[0] * mi[m3]);
-            s = fmaf(rhop[p] * cy[n], W, s);
-            nu[m2] = fmaf(rho[p] * G::ENT_COEF[n], W, nu[m2]);
+          constexpr int sl = G::ENT_SLOT[n], p = G::SLOT_P[sl], m3 = G::SLOT_M3[sl], m1 = G::ENT_M1[n], m2 = G::ENT_M2[n];
+          if constexpr (L0 ? m1 == 0 : m3 == 0) {
+            constexpr int pr = path_row<G, LS>(p);
+            const float W = fmaf(G::PATH_SIGN[p] * xi[m1], mj[m3], xj[m1] * mi[m3]);
+            s = fmaf(rhop[pr] * cy[n], W, s);
+            nu[m2] = fmaf(rho[pr] * G::ENT_COEF[n], W, nu[m2]);
           }
         });
       } else if constexpr (G::LMAX == 2) {
@@ -428,7 +450,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
   }
 }
 
-template <typename G, typename TX, typename TF, bool UNI, bool L0>
+template <typename G, typename TX, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -436,14 +458,16 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a, int N, int C,
                                                   float* __restrict__ ad,
                                                   TX* __restrict__ X) {
-  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
+  constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr int NU = LZ ? 1 : NM;  // live components of the messages' cotangent, and components of the output that anything reads
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
   const int64_t io = (int64_t)t.row * C + t.c;
-  float mi[NM];
+  float mi[NU];
   loadm(mu_a, NC, io, mi);
-  float acc[NM];
+  float acc[NU];
   zero(acc);
   __shared__ float tabs[4][2][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6][0];
@@ -484,13 +508,14 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
           if constexpr (G::ENT_M2[n] != 0) acc[m3] = fmaf(rho[p] * cyd[n], xj[0], acc[m3]);
           tp[p] = fmaf(mi[m3], s1, tp[p]);
         }
-      } else {
+      } else if constexpr (!LZ || m3 == 0) {
+        constexpr int pr = path_row<G, LS>(p);
         S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
         S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
         if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
         if (G::ENT_SLAST[n]) {
-          acc[m3] = fmaf(rr[p], S1, fmaf(rho[p], S23, acc[m3]));
-          tp[p] = fmaf(mi[m3], S1, tp[p]);
+          acc[m3] = fmaf(rr[pr], S1, fmaf(rho[pr], S23, acc[m3]));
+          tp[pr] = fmaf(mi[m3], S1, tp[pr]);
         }
       }
     });
@@ -500,7 +525,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     store_paths(X + (int64_t)e * NPP * C, t.c, tp);
   }
 #pragma unroll
-  for (int m = 0; m < NM; ++m) ad[m * NC + io] = acc[m];
+  for (int m = 0; m < NU; ++m) ad[m * NC + io] = acc[m];
 }
 
 // (Writing the adjoint of the OPPOSITE edge instead -- X[rev(e)] from this row's own features and the sender's adjoints,
@@ -508,7 +533,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
 // written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.
 // Holding an edge's row of X back for one trip of the loop, so that its stores follow the next edge's loads, changed nothing:
 // two waves per SIMD already cover the store acknowledgements.)
-template <typename G, typename TX, typename TF, bool UNI, bool L0>
+template <typename G, typename TX, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -516,16 +541,23 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a,
                                                   const float* __restrict__ lam_a, const float* __restrict__ lam_h_next, int N, int C,
                                                   float* __restrict__ lam_h, TX* __restrict__ X) {
-  constexpr int NM = G::NM, NPATH = L0 ? G::LMAX + 1 : G::NPATH, NPP = L0 ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
+  constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
+  constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
   if (!t.active) return;
   const int64_t NC = (int64_t)N * C;
   const int64_t io = (int64_t)t.row * C + t.c;
   constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features, and needed ones of their adjoint
-  float mi[NM], li[NM], acc[NX];
+  constexpr int NU = LZ ? 1 : NM;  // live components of the cotangents of the layer's messages
+  float mi[NU], li[NU], acc[NX];
   loadm(mu_a, NC, io, mi);
   loadm(lam_a, NC, io, li);
-  loadm(lam_h_next, NC, io, acc);
+  if constexpr (LZ) {  // the readout's adjoint has its l = 0 component only
+    zero(acc);
+    acc[0] = lam_h_next[io];
+  } else {
+    loadm(lam_h_next, NC, io, acc);
+  }
   __shared__ float tabs[4][2][64 * G::TAB_LOADS];
   float* slot = tabs[threadIdx.x >> 6][0];
   float* slotd = tabs[threadIdx.x >> 6][1];
@@ -539,7 +571,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
     if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
-    float xj[NX], xdj[NX], lj[NM], mj[NM], rho[NPATH], rr[NPATH];
+    float xj[NX], xdj[NX], lj[NU], mj[NU], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
     loadm(h, NC, jo, xj);
     if constexpr (!L0) loadm(hd, NC, jo, xdj);
@@ -575,10 +607,11 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
           }
           t4[p] = fmaf(mi[m3], s1, t4[p]);
         }
-      } else {
+      } else if constexpr (!LZ || m3 == 0) {
+        constexpr int pr = path_row<G, LS>(p);
         if (G::ENT_SFIRST[n]) {
-          R2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
-          R1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
+          R2 = G::PATH_SIGN[p] * rho[pr] * mj[m3];
+          R1 = G::PATH_SIGN[p] * fmaf(rho[pr], lj[m3], rr[pr] * mj[m3]);
         }
         acc[m1] = fmaf(cy[n], R1, acc[m1]);
         if constexpr (G::ENT_M2[n] != 0) acc[m1] = fmaf(cyd[n], R2, acc[m1]);
@@ -586,8 +619,8 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
         S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
         if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
         if (G::ENT_SLAST[n]) {
-          ta[p] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[p]));
-          t4[p] = fmaf(mi[m3], S1, t4[p]);
+          ta[pr] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[pr]));
+          t4[pr] = fmaf(mi[m3], S1, t4[pr]);
         }
       }
     });
@@ -785,23 +818,45 @@ __global__ void k_edge_cy(const float4* __restrict__ geo, const int32_t* __restr
 }
 
 
+// The paths a layer stores filter rows for: all NPATH in order (x < 0), or up to four listed ones (a specialised layer).
+struct PathList {
+  int n, x, y, z, w;  // n stored paths; which path each of the first four is, unless x < 0
+  __host__ __device__ int path(int k) const { return x < 0 ? k : (k == 0 ? x : k == 1 ? y : k == 2 ? z : w); }
+};
+template <typename G>
+PathList path_list(int ls) {
+  if (ls == LS_FIRST) return PathList{G::LMAX + 1, 0, 1, 2, 3};  // (0, l, l): the first LMAX + 1 paths
+  if (ls == LS_LAST) return PathList{G::LMAX + 1, G::LAST_PATHS[0], G::LAST_PATHS[1], G::LAST_PATHS[2], G::LAST_PATHS[G::LMAX]};
+  return PathList{G::NPATH, -1, 0, 0, 0};
+}
 // Filter weights W [NPATH C][H] (row p C + c) regrouped to the stored order of the filter jets:
-// Wp [(c NPP + p)][H], zero rows for the pad, and the transpose WpT [H][NPP C].
-__global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, int NPATH, int NPP, float* __restrict__ Wp, float* __restrict__ WpT) {
+// Wp [(c NPP + k)][H] for the k-th stored path, zero rows for the pad, and the transpose WpT [H][NPP C].
+__global__ void k_regroup_filter(const float* __restrict__ W, int C, int H, PathList pl, int NPP, float* __restrict__ Wp, float* __restrict__ WpT) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)NPP * C * H) return;
-  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
-  const float val = p < NPATH ? W[((int64_t)p * C + c) * H + hh] : 0.f;
+  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, k = r % NPP;
+  const float val = k < pl.n ? W[((int64_t)pl.path(k) * C + c) * H + hh] : 0.f;
   Wp[idx] = val;
   WpT[(int64_t)hh * NPP * C + r] = val;
 }
-// grad[(p C + c)][H] += g[(c NPP + p)][H]
-__global__ void k_regroup_add(const float* __restrict__ g, int C, int H, int NPATH, int NPP, float* __restrict__ grad) {
+// grad[(p C + c)][H] += g[(c NPP + k)][H] for the k-th stored path p
+__global__ void k_regroup_add(const float* __restrict__ g, int C, int H, PathList pl, int NPP, float* __restrict__ grad) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)NPP * C * H) return;
-  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, p = r % NPP;
-  if (p < NPATH) grad[((int64_t)p * C + c) * H + hh] += g[idx];
+  const int r = (int)(idx / H), hh = (int)(idx % H), c = r / NPP, k = r % NPP;
+  if (k < pl.n) grad[((int64_t)pl.path(k) * C + c) * H + hh] += g[idx];
 }
+// Which specialisation layer l of L runs as.  The position gradient's kernel reads every component of the last layer's
+// cotangents, so that layer stays general when the gradient is wanted.
+inline int layer_spec(int l, int L, bool position_grad) {
+  if (l == 0) return LS_FIRST;
+  return (l == L - 1 && !position_grad) ? LS_LAST : LS_ANY;
+}
+// the tensor-product kernel instance for a layer: KERN(k_tp_fe, ls, uni, G, TF) -> k_tp_fe<G, TF, uni, ls>
+#define TP_KERNEL(name, ls, uni, ...)                                                                                         \
+  ((ls) == LS_FIRST ? ((uni) ? name<__VA_ARGS__, true, LS_FIRST> : name<__VA_ARGS__, false, LS_FIRST>)                          \
+   : (ls) == LS_LAST ? ((uni) ? name<__VA_ARGS__, true, LS_LAST> : name<__VA_ARGS__, false, LS_LAST>)                           \
+                     : ((uni) ? name<__VA_ARGS__, true, LS_ANY> : name<__VA_ARGS__, false, LS_ANY>))
 
 // h0[m=0] = emb[species], other components zero
 __global__ void k_embed_l0(const float* __restrict__ emb, const int32_t* __restrict__ species, int64_t N, int C, int NM,
@@ -918,11 +973,14 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
     hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, st, th + off, w->paramsT + off, rows, cols);
   };
   for (int l = 0; l < L; ++l) {
-    // the first layer multiplies by its live paths only (the first LMAX + 1, rows of 4 per channel); the position gradient's
-    // products need all paths there too
-    if (l == 0) hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)4 * C * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, LMAX + 1, 4, w->Wp0, w->WpT0);
-    if (l > 0 || cf.position_grad)
-      hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, NPATH, NPP, w->Wp[l], w->WpT[l]);
+    // the first and the last layer multiply by their live paths only (rows of 4 per channel); the position gradient's
+    // products need all paths everywhere
+    const int ls = layer_spec(l, L, cf.position_grad);
+    if (ls != LS_ANY)
+      hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)4 * C * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, path_list<G>(ls), 4,
+                         ls == LS_FIRST ? w->Wp0 : w->WpZ, ls == LS_FIRST ? w->WpT0 : w->WpTZ);
+    if (ls == LS_ANY || cf.position_grad)
+      hipLaunchKernelGGL(k_regroup_filter, dim3(nblk((int64_t)PC * H)), dim3(256), 0, st, th + ctx->lay[l].W[1], C, H, path_list<G>(LS_ANY), NPP, w->Wp[l], w->WpT[l]);
     for (int k = 0; k <= LMAX; ++k) {
       if (cf.n_experts > 0)
         hipLaunchKernelGGL(k_merge_experts, dim3(nblk((int64_t)C * C, 64), (unsigned)((ctx->B + 15) / 16)), dim3(256), 0, st, ctx->d_alpha,
@@ -942,30 +1000,32 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
+    const int ls = layer_spec(l, L, cf.position_grad);
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
         gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-      const int PCl = l == 0 ? 4 * C : PC;  // filter width of this layer
-      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), l == 0 ? w->Wp0 : w->Wp[l], 2 * E, PCl, H,
+      const int PCl = ls != LS_ANY ? 4 * C : PC;  // filter width of this layer
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), ls == LS_FIRST ? w->Wp0 : ls == LS_LAST ? w->WpZ : w->Wp[l], 2 * E, PCl, H,
                  EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PCl, 2 * E});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      auto kern = l == 0 ? (uni ? k_tp_fe<G, TF, true, true> : k_tp_fe<G, TF, false, true>) : (uni ? k_tp_fe<G, TF, true, false> : k_tp_fe<G, TF, false, false>);
+      auto kern = TP_KERNEL(k_tp_fe, ls, uni, G, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Rho[l]),
                          w->cy, w->h[l], (int)N, C, w->a[l]);
     }
-    for (int k = 0; k <= LMAX; ++k) {
+    const int kmax = ls == LS_LAST ? 0 : LMAX;  // the readout takes the last layer's l = 0 output only
+    for (int k = 0; k <= kmax; ++k) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       if (gate)
         mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiStore{w->u[l] + o, C, rows});
       else
         mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
-    if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC, NM);
+    if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC, ls == LS_LAST ? 1 : NM);
   }
   gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
   hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
@@ -993,17 +1053,19 @@ int ff_impl(mlip_ctx* ctx, float* F) {
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
+    const int ls = layer_spec(l, L, cf.position_grad);
+    const int kmax = ls == LS_LAST ? 0 : LMAX;  // the last layer's cotangents have their l = 0 component only
     const float* mu_z = w->mu_h[l + 1];  // cotangent of the update's output; through the gate it becomes that of W a
     if (gate) {
-      hipLaunchKernelGGL(k_gate_ff, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->mu_h[l + 1], w->mu_u[l], NC, NM);
+      hipLaunchKernelGGL(k_gate_ff, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->mu_h[l + 1], w->mu_u[l], NC, ls == LS_LAST ? 1 : NM);
       mu_z = w->mu_u[l];
     }
-    for (int k = 0; k <= LMAX; ++k) {
+    for (int k = 0; k <= kmax; ++k) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       mix_mm<P>(ctx, l, k, true, LdPlain{mu_z + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
-    auto kern = l == 0 ? (uni ? k_tp_ff<G, TF, true, true> : k_tp_ff<G, TF, false, true>) : (uni ? k_tp_ff<G, TF, true, false> : k_tp_ff<G, TF, false, false>);
+    auto kern = TP_KERNEL(k_tp_ff, ls, uni, G, TF);
     hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                        w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
@@ -1033,14 +1095,16 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
-    const int PCl = l == 0 ? 4 * C : PC;  // width of this layer's filter jets and adjoints
+    const int ls = layer_spec(l, L, cf.position_grad);
+    const int PCl = ls != LS_ANY ? 4 * C : PC;  // width of this layer's filter jets and adjoints
+    const int kmax = ls == LS_LAST ? 0 : LMAX;  // the readout takes the last layer's l = 0 output only
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      auto kern = l == 0 ? (uni ? k_tp_bf<G, TX, TF, true, true> : k_tp_bf<G, TX, TF, false, true>) : (uni ? k_tp_bf<G, TX, TF, true, false> : k_tp_bf<G, TX, TF, false, false>);
+      auto kern = TP_KERNEL(k_tp_bf, ls, uni, G, TX, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
-    for (int k = 0; k <= LMAX; ++k) {
+    for (int k = 0; k <= kmax; ++k) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       if (gate)
         mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiStore{w->ud[l] + o, C, rows});
@@ -1048,17 +1112,17 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
         mix_mm<P>(ctx, l, k, false, LdPlain{w->ad[l] + o, C}, EpiAddStore{w->hd[l + 1] + o, w->hd[l] + o, C, rows});
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{(gate ? w->mu_u[l] : w->mu_h[l + 1]) + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
-    if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC, NM);
+    if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC, ls == LS_LAST ? 1 : NM);
     if (E > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::odd(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, l == 0 ? LMAX + 1 : NPATH, l == 0 ? 4 : NPP, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, path_list<G>(ls), ls != LS_ANY ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), l == 0 ? w->WpT0 : w->WpT[l], E, H, PCl, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], E, H, PCl, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -1104,22 +1168,24 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   if (want_gp) hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 0.f, 3 * N);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
-    const int PCl = l == 0 ? 4 * C : PC;  // width of this layer's filter jets and adjoints
+    const int ls = layer_spec(l, L, cf.position_grad);
+    const int PCl = ls != LS_ANY ? 4 * C : PC;  // width of this layer's filter jets and adjoints
+    const int kmax = ls == LS_LAST ? 0 : LMAX;  // the last layer's adjoints have their l = 0 component only
     float* lh_next = w->lam_h[cur];
     float* lh = w->lam_h[cur ^ 1];
     const float* lam_z = lh_next;  // adjoint of the update's output; through the gate it becomes that of W a
     if (gate) {
-      hipLaunchKernelGGL(k_gate_be, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->mu_h[l + 1], lh_next, w->lam_u, NC, NM);
+      hipLaunchKernelGGL(k_gate_be, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->mu_h[l + 1], lh_next, w->lam_u, NC, ls == LS_LAST ? 1 : NM);
       lam_z = w->lam_u;
     }
-    for (int k = 0; k <= LMAX; ++k) {
+    for (int k = 0; k <= kmax; ++k) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       mix_mm<P>(ctx, l, k, true, LdPlain{lam_z + o, C}, EpiStore{w->lam_a + o, C, rows});
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lam_z + o, C}, LdPlain{w->a[l] + o, C}, grad)));
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      auto kern = l == 0 ? (uni ? k_tp_be<G, TX, TF, true, true> : k_tp_be<G, TX, TF, false, true>) : (uni ? k_tp_be<G, TX, TF, true, false> : k_tp_be<G, TX, TF, false, false>);
+      auto kern = TP_KERNEL(k_tp_be, ls, uni, G, TX, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
@@ -1138,11 +1204,11 @@ int be_impl(mlip_ctx* ctx, float* grad) {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
         MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::even(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
-        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, l == 0 ? LMAX + 1 : NPATH, l == 0 ? 4 : NPP, grad + lo.W[1]);
+        hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, path_list<G>(ls), ls != LS_ANY ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), l == 0 ? w->WpT0 : w->WpT[l], E, H, PCl, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], E, H, PCl, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
       }
       MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
     }
@@ -1207,7 +1273,11 @@ int eqv_alloc(mlip_ctx* ctx) {
   w->gWp = A((int64_t)PC * H);
   w->Wp0 = A((int64_t)4 * C * H);
   w->WpT0 = A((int64_t)4 * C * H);
-  if (cf.gemm_dtype == MLIP_GEMM_BF16 && ok) ok &= add_shadow(ctx, w->Wp0, (int64_t)4 * C * H) && add_shadow(ctx, w->WpT0, (int64_t)4 * C * H);
+  w->WpZ = A((int64_t)4 * C * H);
+  w->WpTZ = A((int64_t)4 * C * H);
+  if (cf.gemm_dtype == MLIP_GEMM_BF16 && ok)
+    ok &= add_shadow(ctx, w->Wp0, (int64_t)4 * C * H) && add_shadow(ctx, w->WpT0, (int64_t)4 * C * H) && add_shadow(ctx, w->WpZ, (int64_t)4 * C * H) &&
+          add_shadow(ctx, w->WpTZ, (int64_t)4 * C * H);
   w->cy = A(E * CY_LD + TAB);  // + TAB: the cooperative fetch of the last edge's table reads TAB floats from its start
   w->cyd = A(E * CY_LD + TAB);
   w->X2 = AH(E * H);

@@ -157,6 +157,10 @@ def emit_tab(lmax, L):
     arr("YSLOT_M2", "int", [str(ys[1]) for ys in yslots])
     L.append("  // parity (-1)^l2 of each path: the couplings of the inverted direction are PATH_SIGN[p] times these")
     arr("PATH_SIGN", "float", ["-1.0f" if pp[1] % 2 else "1.0f" for pp in PATHS])
+    L.append("  // the paths (l, l, 0), the only ones that reach the l = 0 output: their indices, and each path's position among them (-1: none)")
+    last = [PATHS.index((l, l, 0)) for l in range(lmax + 1)]
+    arr("LAST_PATHS", "int", [str(x) for x in last])
+    arr("LAST_K", "int", [str(last.index(k)) if k in last else "-1" for k in range(len(PATHS))])
     L.append("  // parity (-1)^l of each component")
     arr("M_SIGN", "float", ["-1.0f" if l % 2 else "1.0f" for l in range(lmax + 1) for _ in range(2 * l + 1)])
     L.append("  // first component of each degree, and one past the last")
