@@ -256,3 +256,37 @@ def test_lmax3_force_and_gradient_by_central_differences():
     rs = O.train_step(cfg, inp.pos, inp.species, inp.struct_ptr, inp.cell, inp.params, inp.E_ref, inp.F_ref, split=True)
     assert np.allclose(rs["grad_bf"] + rs["grad_be"], r0["grad"], rtol=1e-10, atol=1e-13)
     assert np.abs(rs["grad_bf"]).max() > 0
+
+
+# ------------------------------------------------------------------ which couplings the first and the last layer use
+
+@pytest.mark.parametrize("l_max,gate", [(2, 0), (3, 0), (3, 1)])
+def test_first_and_last_layer_use_few_paths(l_max, gate):
+    """The embedding has its l = 0 component only, and the readout takes the l = 0 component of the last layer's output
+    only: the loss does not depend on the filter rows of the first layer outside the paths (0, l, l), nor on those of the
+    last layer outside (l, l, 0), nor on the last layer's mixing matrices of l >= 1, so their gradients vanish exactly;
+    every other block, the middle layer's included, has a gradient."""
+    w = _tiny(l_max=l_max, atoms_per_struct=8, box=6.0, cutoff=3.0, n_layers=3, channels=2, gate=gate)
+    inp = synth.make_inputs(w)
+    g = _step(w, inp)["grad"]
+    sl = synth.param_slices(w)
+    C = w.channels
+    paths = O.paths_of(l_max)
+
+    def rows(layer):
+        off, shape = sl[f"l{layer}.W2"]
+        return g[off:off + int(np.prod(shape))].reshape(len(paths), C, shape[1])
+
+    for layer, live in ((0, lambda p: p[0] == 0), (2, lambda p: p[2] == 0)):
+        r = rows(layer)
+        for k, p in enumerate(paths):
+            if live(p):
+                assert np.abs(r[k]).max() > 0, (layer, p)
+            else:
+                assert np.abs(r[k]).max() == 0, (layer, p)
+    assert all(np.abs(r).max() > 0 for r in rows(1))
+    for layer in range(3):
+        for lam in range(l_max + 1):
+            off, shape = sl[f"l{layer}.Wl{lam}"]
+            blk = np.abs(g[off:off + int(np.prod(shape))]).max()
+            assert (blk == 0) if (layer == 2 and lam > 0) else (blk > 0), (layer, lam)
