@@ -43,7 +43,8 @@ COUPLINGS = {2: (83, 11, 9, 12), 3: (353, 23, 16, 24)}
 
 def kernel_table(w, E, N):
     """Kernel ids of include/mlip.h -> (name, bound, algorithmic work per launch, extra figures).
-    Matrix products: flop = 2 x rows x inner x out.  Invariant gather kernels: HBM bytes, every edge tensor
+    Matrix products: flop = 2 x rows x inner x out, with one row (one jet of two rows) per edge PAIR: opposite edges have
+    the same length, so the edge MLP, its filter jets and their adjoints exist once per pair (E / 2).  Invariant gather kernels: HBM bytes, every edge tensor
     and node table touched once, indices and geometry included.  Equivariant tensor-product kernels: fp32
     vector flop = 2 (nnz(T) + components * paths) per edge, channel and evaluation of the trilinear form (1 in FE, 2 in
     FF, 3 in BF, 4 in BE; 83 + 9 * 11 for l <= 2, 353 + 16 * 23 for l <= 3), with two HBM byte counts beside it:
@@ -75,13 +76,14 @@ def kernel_table(w, E, N):
         layers = [general] * L
     avg = lambda f: sum(f(x) for x in layers) / len(layers)
     Co = avg(lambda x: x[0]) * C       # width of the radial filter per edge
+    Eu = E // 2                        # edge pairs: the rows (jets) of every product of the edge MLP
     t = {
-        1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * E) * K * H, {}),
-        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * E) * H * Co, {}),
-        7: ("bf_dgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
-        8: ("be_dgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
-        9: ("bf_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
-        10: ("be_wgrad_gemm", "mfma", 2.0 * E * Co * H, {}),
+        1: ("fe_hidden_gemm", "mfma", 2.0 * (2 * Eu) * K * H, {}),
+        2: ("fe_filter_gemm", "mfma", 2.0 * (2 * Eu) * H * Co, {}),
+        7: ("bf_dgrad_gemm", "mfma", 2.0 * Eu * Co * H, {}),
+        8: ("be_dgrad_gemm", "mfma", 2.0 * Eu * Co * H, {}),
+        9: ("bf_wgrad_gemm", "mfma", 2.0 * Eu * Co * H, {}),
+        10: ("be_wgrad_gemm", "mfma", 2.0 * Eu * Co * H, {}),
     }
     jets = {3: 1, 4: 2, 5: 2, 6: 2}    # filter-jet rows read per edge
     adj = {3: 0, 4: 0, 5: 1, 6: 1}     # adjoint rows written per edge

@@ -75,6 +75,7 @@ struct mlip_ctx {
   int phase = PH_NONE;
   // sizes of the current batch
   int64_t N = 0, E = 0;
+  int64_t Eu = 0;  // edge pairs: E / 2
   int32_t B = 0;
   int64_t n_params = 0;
   int64_t off_emb = -1, off_U = -1, off_wo = -1;
@@ -95,6 +96,12 @@ struct mlip_ctx {
   int32_t* d_code = nullptr;          // [max_edges] shift code 0..26
   int32_t* d_receiver = nullptr;      // [max_edges]
   int32_t* d_rev = nullptr;           // [max_edges]
+  // Edge pairs (model contexts only; null in a bare graph build).  An edge and its opposite have the same length, so all
+  // that depends on the length alone -- the radial basis, the edge MLP, the filter jets and their adjoints -- is kept once
+  // per pair: pair u = the rank of its lower-numbered edge among such edges, rows 2u and 2u + 1 of a per-pair jet matrix.
+  int2* d_se = nullptr;               // [max_edges] (sender, slot): slot = 2 u + (0 for the pair's lower-numbered edge, 1 for the other)
+  int32_t* d_und = nullptr;           // [max_edges / 2 + 1] the lower-numbered edge of each pair
+  int32_t* d_pair_pre = nullptr;      // [max_edges + 1] scan work array of the pair numbering
   int32_t* d_scan_tmp = nullptr;      // block sums for the scans
   int32_t* d_flag = nullptr;          // device flags [4]: word 0 = positions outside their cell (read by the graph build);
                                       // word 1 = deferred input diagnostics (INPUT_* bits, read by input_status)

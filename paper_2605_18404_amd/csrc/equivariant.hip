@@ -37,11 +37,14 @@ namespace {
 
 struct EqvWs {
   float* paramsT = nullptr;
-  float* jphi = nullptr;  // [E][2][K]
+  // Opposite edges have the same length: what depends on the length alone is kept once per edge PAIR (Eu = E / 2 rows or
+  // jets; pair u of an edge = slot >> 1, mlip_ctx::d_se), and the two edges' adjoint rows of X lie side by side (row = slot).
+  float* jphi = nullptr;  // [Eu][2][K]
   float2* env = nullptr;  // [E]
-  std::vector<float*> U;    // [E][2][H]
-  std::vector<__bf16*> SJ;  // bf16 GEMMs only: activated jets [E][2][H]
-  std::vector<float*> Rho;  // [E][2][C][NPP]: per channel the NPATH path filters + padding, operand precision (fp32 or bf16)
+  float2* env_u = nullptr;  // [Eu] the same per pair (rows of the filter product)
+  std::vector<float*> U;    // [Eu][2][H]
+  std::vector<__bf16*> SJ;  // bf16 GEMMs only: activated jets [Eu][2][H]
+  std::vector<float*> Rho;  // [Eu][2][C][NPP]: per channel the NPATH path filters + padding, operand precision (fp32 or bf16)
   std::vector<float*> Wp;   // per layer: filter weights with rows regrouped to that order, [NPP C][H]
   std::vector<float*> WpT;  // and their transpose [H][NPP C]
   float* gWp = nullptr;     // [NPP C][H] weight gradient in the regrouped row order
@@ -52,9 +55,9 @@ struct EqvWs {
   std::vector<float*> Wm[4], WmT[4];  // expert banks of the per-l mixing matrices merged per structure: [B][C][C], and transposed
   float* cy = nullptr;      // [E][CY_LD] coupling coefficient x harmonic of the edge direction
   float* cyd = nullptr;     // [E][CY_LD] the same with the directional derivative of the harmonics (BF, BE)
-  std::vector<float*> Y1;   // [E][H]  BF -> BE
-  float* X = nullptr;       // [E][C][NPP], operand precision
-  float* X2 = nullptr;      // [E][H]
+  std::vector<float*> Y1;   // [Eu][H]  BF -> BE
+  float* X = nullptr;       // [Eu][2][C][NPP] (the two edges of a pair), operand precision
+  float* X2 = nullptr;      // [Eu][H]
   std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [NM][N][C]
   std::vector<float*> u, mu_u, ud;  // gated update only, [NM][N][C]: pre-activations W a, their FF cotangents, their BF tangents
   float* lam_u = nullptr;           // gated update only: BE adjoint of the pre-activations
@@ -69,9 +72,9 @@ struct EqvWs {
   float* v = nullptr;
   float* Ebar = nullptr;
   // optional position gradient dL/dx (mlip_config.position_grad)
-  float* U2 = nullptr;      // [E][H] second-derivative row of the hidden level
-  float* Rj = nullptr;      // [E][2][C][12] radial weights R and dR/dr (before the envelope), fp32
-  float* Rpp = nullptr;     // [E][C][12] d2R/dr2
+  float* U2 = nullptr;      // [Eu][H] second-derivative row of the hidden level
+  float* Rj = nullptr;      // [Eu][2][C][12] radial weights R and dR/dr (before the envelope), fp32
+  float* Rpp = nullptr;     // [Eu][C][12] d2R/dr2
   float* gp_acc = nullptr;  // [N,3]
 };
 inline EqvWs* ws_of(mlip_ctx* ctx) { return (EqvWs*)ctx->model_ws; }
@@ -277,7 +280,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 template <typename G, typename TF, bool UNI, int LS>
-__global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                const float* __restrict__ h, int N, int C, float* __restrict__ a) {
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
@@ -292,16 +295,16 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
   float* slot = tabs[threadIdx.x >> 6];
   const int lane = threadIdx.x & 63;
   const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
-  int jn = e0 < e1 ? sender[e0] : 0;
+  int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
   for (int e = e0; e < e1; ++e) {
-    const int j = jn;
-    jn = sender[e + 1 < e1 ? e + 1 : e];  // next edge's sender: its gathers need not wait for an index
+    const int j = sn.x, es = sn.y;  // sender; pair row 2u + (0 | 1) of the edge
+    sn = se[e + 1 < e1 ? e + 1 : e];  // next edge's sender: its gathers need not wait for an index
     float x[L0 ? 1 : NM], rho[NPATH];
     const float* cy = cyt + (int64_t)e * CY_LD;
     TabRegs<G> tr;
     if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
     loadm(h, NC, (int64_t)j * C + t.c, x);
-    load_rho(Rho + (int64_t)(2 * e) * NPP * C, t.c, rho);
+    load_rho(Rho + (int64_t)(es & ~1) * NPP * C, t.c, rho);
     if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
     float S = 0.f;  // sum_n cy[n] x[m1_n] over the entries of one slot
     static_for<0, G::NNZ>([&](auto n_) {
@@ -320,7 +323,7 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
 }
 
 template <typename G, typename TF, bool UNI, int LS>
-__global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                   const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
                                                   const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
@@ -348,10 +351,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
     float* slot = tabs[threadIdx.x >> 6];
     const int lane = threadIdx.x & 63;
     const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
-    int jn = e0 < e1 ? sender[e0] : 0;
+    int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
     for (int e = e0; e < e1; ++e) {
-      const int j = jn;
-      jn = sender[e + 1 < e1 ? e + 1 : e];
+      const int j = sn.x, es = sn.y;
+      sn = se[e + 1 < e1 ? e + 1 : e];
       const float4 g = geo[e];
       const float* cy = cyt + (int64_t)e * CY_LD;
       TabRegs<G> tr;
@@ -360,7 +363,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       const int64_t jo = (int64_t)j * C + t.c;
       loadm(h, NC, jo, xj);
       loadm(mu_a, NC, jo, mj);
-      const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+      const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
       load_rho(rrow, t.c, rho);
       load_rho(rrow + NPP * C, t.c, rhop);
       if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
@@ -451,7 +454,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
 }
 
 template <typename G, typename TX, typename TF, bool UNI, int LS>
-__global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                   const float* __restrict__ cydt, const float* __restrict__ h,
@@ -474,10 +477,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
   float* slotd = tabs[threadIdx.x >> 6][1];
   const int lane = threadIdx.x & 63;
   const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
-  int jn = e0 < e1 ? sender[e0] : 0;
+  int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
   for (int e = e0; e < e1; ++e) {
-    const int j = jn;
-    jn = sender[e + 1 < e1 ? e + 1 : e];
+    const int j = sn.x, es = sn.y;
+    sn = se[e + 1 < e1 ? e + 1 : e];
     const float* cy = cyt + (int64_t)e * CY_LD;
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
@@ -487,7 +490,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     const int64_t jo = (int64_t)j * C + t.c;
     loadm(h, NC, jo, xj);
     if constexpr (!L0) loadm(hd, NC, jo, xdj);
-    const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+    const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
     if constexpr (UNI) { tab_publish<G>(tr, slot, lane); tab_publish<G>(trd, slotd, lane); cy = slot; cyd = slotd; }
@@ -522,7 +525,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     const float s = rd * env[e].x;
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) tp[p] *= s;
-    store_paths(X + (int64_t)e * NPP * C, t.c, tp);
+    store_paths(X + (int64_t)es * NPP * C, t.c, tp);
   }
 #pragma unroll
   for (int m = 0; m < NU; ++m) ad[m * NC + io] = acc[m];
@@ -534,7 +537,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
 // Holding an edge's row of X back for one trip of the loop, so that its stores follow the next edge's loads, changed nothing:
 // two waves per SIMD already cover the store acknowledgements.)
 template <typename G, typename TX, typename TF, bool UNI, int LS>
-__global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                   const float* __restrict__ cydt, const float* __restrict__ h,
@@ -563,10 +566,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
   float* slotd = tabs[threadIdx.x >> 6][1];
   const int lane = threadIdx.x & 63;
   const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
-  int jn = e0 < e1 ? sender[e0] : 0;
+  int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
   for (int e = e0; e < e1; ++e) {
-    const int j = jn;
-    jn = sender[e + 1 < e1 ? e + 1 : e];
+    const int j = sn.x, es = sn.y;
+    sn = se[e + 1 < e1 ? e + 1 : e];
     const float* cy = cyt + (int64_t)e * CY_LD;
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
@@ -577,7 +580,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     if constexpr (!L0) loadm(hd, NC, jo, xdj);
     loadm(lam_a, NC, jo, lj);
     loadm(mu_a, NC, jo, mj);
-    const TF* rrow = Rho + (int64_t)(2 * e) * NPP * C;
+    const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
     if constexpr (UNI) { tab_publish<G>(tr, slot, lane); tab_publish<G>(trd, slotd, lane); cy = slot; cyd = slotd; }
@@ -628,7 +631,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     const float s = cc.y * rd;
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) ta[p] = fmaf(cc.x, ta[p], s * t4[p]);
-    store_paths(X + (int64_t)e * NPP * C, t.c, ta);
+    store_paths(X + (int64_t)es * NPP * C, t.c, ta);
   }
 #pragma unroll
   for (int m = 0; m < NX; ++m) lam_h[m * NC + io] = acc[m];  // first layer: only the l = 0 component is needed (the embedding's gradient)
@@ -680,7 +683,7 @@ __device__ __forceinline__ float3 sph_hess_apply(float x, float y, float z, floa
 // u, dv negated; Y -> PY) is formed here too, from the row's own node values and the gathered sender's.
 // One thread per (receiver row, channel), couplings straight from the entry tables; off the timed path.
 template <typename G>
-__global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                const float4* __restrict__ geo, const float2* __restrict__ env,
                                                const float* __restrict__ Rj, const float* __restrict__ Rpp,
                                                const float* __restrict__ h, const float* __restrict__ hd,
@@ -700,7 +703,7 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
     loadm(mu_a, NC, io, mi);
     const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
     for (int e = row_ptr[t.row]; e < row_ptr[t.row + 1]; ++e) {
-      const int j = sender[e];
+      const int j = se[e].x, es = se[e].y;
       const float4 g = geo[e];
       const float2 cc = env[e];
       const float3 d = make_float3(v[3 * j] - vi0, v[3 * j + 1] - vi1, v[3 * j + 2] - vi2);
@@ -711,9 +714,9 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
       loadm(hd, NC, jo, xdj);
       loadm(lam_a, NC, jo, lj);
       loadm(mu_a, NC, jo, mj);
-      load_rho(Rj + (int64_t)(2 * e) * NPP * C, t.c, R);
-      load_rho(Rj + (int64_t)(2 * e + 1) * NPP * C, t.c, Rp);
-      load_rho(Rpp + (int64_t)e * NPP * C, t.c, Rq);
+      load_rho(Rj + (int64_t)(es & ~1) * NPP * C, t.c, R);
+      load_rho(Rj + (int64_t)(es | 1) * NPP * C, t.c, Rp);
+      load_rho(Rpp + (int64_t)(es >> 1) * NPP * C, t.c, Rq);
       const float c = cc.x, cp = cc.y, cq = -k2 * (c - 0.5f);
       float rho[NPATH], rr[NPATH], r1[NPATH], r2[NPATH];  // rho, rdot rho', rho', rho''
 #pragma unroll
@@ -964,7 +967,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   static_assert(sizeof(typename Act<P>::xop_t) == (P::IS_BF16 ? 2 : 4), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
-  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int64_t N = ctx->N, E = ctx->E, Eu = ctx->Eu, NC = N * cf.channels;  // atoms, edges, edge pairs (rows of the edge MLP's products)
   constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -992,7 +995,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   tr(ctx->off_U, C, C);
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights, their transposes and the regrouped filters
   if (E > 0)
-    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->jphi);
+    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->env_u, w->jphi);
   if (E > 0)
     hipLaunchKernelGGL((k_edge_cy<G, false>), dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
   hipLaunchKernelGGL(k_embed_l0, dim3(nblk(NM * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, NM, w->h[0]);
@@ -1001,20 +1004,20 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     const int ls = layer_spec(l, L, cf.position_grad);
-    if (E > 0) {
+    if (Eu > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * E));
+        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * Eu, H, K, Act<P>::store(w->U[l], w->SJ[l], H, 2 * Eu));
       }
       KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
       const int PCl = ls != LS_ANY ? 4 * C : PC;  // filter width of this layer
-      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), ls == LS_FIRST ? w->Wp0 : ls == LS_LAST ? w->WpZ : w->Wp[l], 2 * E, PCl, H,
-                 EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env, PCl, 2 * E});
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), ls == LS_FIRST ? w->Wp0 : ls == LS_LAST ? w->WpZ : w->Wp[l], 2 * Eu, PCl, H,
+                 EpiOmega<TF>{reinterpret_cast<TF*>(w->Rho[l]), w->env_u, PCl, 2 * Eu});
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
       auto kern = TP_KERNEL(k_tp_fe, ls, uni, G, TF);
-      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Rho[l]),
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, reinterpret_cast<const TF*>(w->Rho[l]),
                          w->cy, w->h[l], (int)N, C, w->a[l]);
     }
     const int kmax = ls == LS_LAST ? 0 : LMAX;  // the readout takes the last layer's l = 0 output only
@@ -1066,7 +1069,7 @@ int ff_impl(mlip_ctx* ctx, float* F) {
     }
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = TP_KERNEL(k_tp_ff, ls, uni, G, TF);
-    hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
+    hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
                        w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
@@ -1079,7 +1082,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int64_t N = ctx->N, E = ctx->E, Eu = ctx->Eu, NC = N * cf.channels;  // atoms, edges, edge pairs (rows of the edge MLP's products)
   constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -1101,7 +1104,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
       auto kern = TP_KERNEL(k_tp_bf, ls, uni, G, TX, TF);
-      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
     for (int k = 0; k <= kmax; ++k) {
@@ -1113,18 +1116,18 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{(gate ? w->mu_u[l] : w->mu_h[l + 1]) + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
     if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC, ls == LS_LAST ? 1 : NM);
-    if (E > 0) {
+    if (Eu > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::odd(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xpair(X, PCl), Act<P>::odd(w->U[l], w->SJ[l], H), Eu, PCl, H, w->gWp)));
         hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, path_list<G>(ls), ls != LS_ANY ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], E, H, PCl, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xpair(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], Eu, H, PCl, EpiYZ<TX>{w->Y1[l], X2, w->U[l], H, Eu});
       }
-      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi + K, 2 * K}, Eu, H, K, grad + lo.W[0])));
     }
   }
   gemm_nt<P>(ctx, LdPlain{w->hd[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->yd, C, N});
@@ -1143,7 +1146,7 @@ int be_impl(mlip_ctx* ctx, float* grad) {
   EqvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  const int64_t N = ctx->N, E = ctx->E, NC = N * cf.channels;
+  const int64_t N = ctx->N, E = ctx->E, Eu = ctx->Eu, NC = N * cf.channels;  // atoms, edges, edge pairs (rows of the edge MLP's products)
   constexpr int NM = G::NM, NPATH = G::NPATH, NPP = G::NPP, CY_LD = G::CY_LD, LMAX = G::LMAX;
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, PC = NPP * C;
   const float* th = ctx->d_params;
@@ -1186,31 +1189,31 @@ int be_impl(mlip_ctx* ctx, float* grad) {
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       auto kern = TP_KERNEL(k_tp_be, ls, uni, G, TX, TF);
-      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, w->env,
+      hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->env,
                          reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
-    if (want_gp && E > 0) {
+    if (want_gp && Eu > 0) {
       // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share
       const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
-      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2, H, E});
-      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * E, PC, H, EpiStore{w->Rj, PC, 2 * E});
-      gemm_nt<P>(ctx, LdJetSecond{w->U[l], w->U2, H}, w->Wp[l], E, PC, H, EpiStore{w->Rpp, PC, E});
+      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, ctx->d_und, dmu, gamma}, th + lo.W[0], Eu, H, K, EpiStore{w->U2, H, Eu});
+      gemm_nt<P>(ctx, Act<P>::jet(w->U[l], w->SJ[l], H), w->Wp[l], 2 * Eu, PC, H, EpiStore{w->Rj, PC, 2 * Eu});
+      gemm_nt<P>(ctx, LdJetSecond{w->U[l], w->U2, H}, w->Wp[l], Eu, PC, H, EpiStore{w->Rpp, PC, Eu});
       const float kk = 3.14159265358979323846f / cf.cutoff;
-      hipLaunchKernelGGL(k_tp_gp<G>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Rj, w->Rpp,
+      hipLaunchKernelGGL(k_tp_gp<G>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env, w->Rj, w->Rpp,
                          w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, kk * kk, (int)N, C, w->gp_acc);
     }
-    if (E > 0) {
+    if (Eu > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
         hipLaunchKernelGGL(k_fill, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, 0.f, (int64_t)PCl * H);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, PCl), Act<P>::even(w->U[l], w->SJ[l], H), E, PCl, H, w->gWp)));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xpair(X, PCl), Act<P>::even(w->U[l], w->SJ[l], H), Eu, PCl, H, w->gWp)));
         hipLaunchKernelGGL(k_regroup_add, dim3(nblk((int64_t)PCl * H)), dim3(256), 0, st, w->gWp, C, H, path_list<G>(ls), ls != LS_ANY ? 4 : NPP, grad + lo.W[1]);
       }
       {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-        gemm_nt<P>(ctx, Act<P>::xld(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], E, H, PCl, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, E});
+        gemm_nt<P>(ctx, Act<P>::xpair(X, PCl), ls == LS_FIRST ? w->WpT0 : ls == LS_LAST ? w->WpTZ : w->WpT[l], Eu, H, PCl, EpiLamU<TX>{X2, w->U[l], w->Y1[l], H, Eu});
       }
-      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+      MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), LdPlain{w->jphi, 2 * K}, Eu, H, K, grad + lo.W[0])));
     }
     cur ^= 1;
   }
@@ -1264,12 +1267,14 @@ int eqv_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
   w->paramsT = A(ctx->n_params);
   if (cf.gemm_dtype == MLIP_GEMM_BF16) ok &= add_shadow(ctx, ctx->d_params, ctx->n_params) && add_shadow(ctx, w->paramsT, ctx->n_params);
-  w->jphi = A(2 * E * K);
+  const int64_t Eu = E / 2 + 1;  // edge pairs
+  w->jphi = A(2 * Eu * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
+  ok &= (w->env_u = alloc_n<float2>(ctx, Eu)) != nullptr;
   const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
   // tensors held in the operand precision: half the floats when that is bf16
   auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
-  w->X = AH(E * PC);
+  w->X = AH(2 * Eu * PC);
   w->gWp = A((int64_t)PC * H);
   w->Wp0 = A((int64_t)4 * C * H);
   w->WpT0 = A((int64_t)4 * C * H);
@@ -1280,16 +1285,16 @@ int eqv_alloc(mlip_ctx* ctx) {
           add_shadow(ctx, w->WpTZ, (int64_t)4 * C * H);
   w->cy = A(E * CY_LD + TAB);  // + TAB: the cooperative fetch of the last edge's table reads TAB floats from its start
   w->cyd = A(E * CY_LD + TAB);
-  w->X2 = AH(E * H);
+  w->X2 = AH(Eu * H);
   const int64_t NC9 = (int64_t)NM * N * C;  // a node table: all components
   for (int l = 0; l < L; ++l) {
-    w->U.push_back(A(2 * E * H));
-    w->SJ.push_back(b16 ? (__bf16*)A(E * H) : nullptr);
-    w->Rho.push_back(cf.filter_fp32 ? A(2 * E * PC) : AH(2 * E * PC));
+    w->U.push_back(A(2 * Eu * H));
+    w->SJ.push_back(b16 ? (__bf16*)A(Eu * H) : nullptr);
+    w->Rho.push_back(cf.filter_fp32 ? A(2 * Eu * PC) : AH(2 * Eu * PC));
     w->Wp.push_back(A((int64_t)PC * H));
     w->WpT.push_back(A((int64_t)PC * H));
     if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
-    w->Y1.push_back(A(E * H));
+    w->Y1.push_back(A(Eu * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
     if (cf.gate) { w->u.push_back(A(NC9)); w->mu_u.push_back(A(NC9)); w->ud.push_back(A(NC9)); }
     if (cf.n_experts > 0)
@@ -1301,9 +1306,9 @@ int eqv_alloc(mlip_ctx* ctx) {
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
   if (cf.position_grad) {
-    w->U2 = A(E * H);
-    w->Rj = A(2 * E * PC);
-    w->Rpp = A(E * PC);
+    w->U2 = A(Eu * H);
+    w->Rj = A(2 * Eu * PC);
+    w->Rpp = A(Eu * PC);
     w->gp_acc = A(3 * N);
   }
   int64_t cap = 0;

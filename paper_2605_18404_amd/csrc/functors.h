@@ -39,6 +39,7 @@ __device__ __forceinline__ void st4(__bf16* p, float4 v) {
   bf16x4_t b = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
   *reinterpret_cast<bf16x4_t*>(p) = b;
 }
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 __device__ __forceinline__ float4 mul4(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
 __device__ __forceinline__ float4 silu4(float4 a) { return make_float4(silu(a.x), silu(a.y), silu(a.z), silu(a.w)); }
 __device__ __forceinline__ float4 dsilu4(float4 a) { return make_float4(dsilu(a.x), dsilu(a.y), dsilu(a.z), dsilu(a.w)); }
@@ -139,14 +140,15 @@ struct LdMuY {  // w_o[col] * silu'(y[row, col])
 };
 
 // ---- second-derivative rows, used only for the optional position gradient dL/dx
-struct LdPhi2 {  // row e, columns k..k+3 -> d^2 phi_k / dr^2 at r_e = (-2 gamma + 4 gamma^2 t^2) exp(-gamma t^2), t = r_e - k dmu
+struct LdPhi2 {  // row u (edge pair), columns k..k+3 -> d^2 phi_k / dr^2 at r_e = (-2 gamma + 4 gamma^2 t^2) exp(-gamma t^2), t = r_e - k dmu
   static constexpr bool PAIRED = false;
   __device__ __forceinline__ void shift(int64_t) {}
   static constexpr int WIDTH = 4;
   struct Raw { float r; int k; };
-  const float4* geo;  // [E] (unit vector, length)
+  const float4* geo;   // [E] (unit vector, length)
+  const int32_t* und;  // [Eu] an edge of each pair: rows are edge pairs
   float dmu, gamma;
-  __device__ __forceinline__ Raw fetch(int64_t e, int64_t c) const { return Raw{geo[e].w, (int)c}; }
+  __device__ __forceinline__ Raw fetch(int64_t u, int64_t c) const { return Raw{geo[und[u]].w, (int)c}; }
   __device__ __forceinline__ float4 finish(const Raw& x) const {
     float o[4];
 #pragma unroll
@@ -208,11 +210,59 @@ struct LdBf16x8 {  // the same matrix fetched eight values (16 bytes) at a time 
   __device__ __forceinline__ Raw finish(const Raw& x) const { return x; }
 };
 
+// ---- adjoints of per-pair quantities.  The two edges of a pair write their adjoint rows side by side (rows 2u and 2u + 1);
+// what reaches the per-pair edge MLP is their sum, formed while the operand is staged.
+struct LdPairSum {  // p[2 row][col] + p[2 row + 1][col]
+  static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
+  static constexpr int WIDTH = 4;
+  typedef Raw2 Raw;
+  const float* p;
+  int64_t ld;
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const {
+    const float* pe = p + 2 * r * ld + c;
+    return Raw{ld4(pe), ld4(pe + ld)};
+  }
+  __device__ __forceinline__ float4 finish(const Raw& x) const { return add4(x.a, x.b); }
+};
+struct LdBf16Pair {  // the same for a bf16 matrix
+  static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
+  static constexpr int WIDTH = 4;
+  struct Raw { bf16x4_t a, b; };
+  const __bf16* p;
+  int64_t ld;
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const {
+    const __bf16* pe = p + 2 * r * ld + c;
+    return Raw{*reinterpret_cast<const bf16x4_t*>(pe), *reinterpret_cast<const bf16x4_t*>(pe + ld)};
+  }
+  __device__ __forceinline__ float4 finish(const Raw& x) const {
+    return make_float4((float)x.a[0] + (float)x.b[0], (float)x.a[1] + (float)x.b[1], (float)x.a[2] + (float)x.b[2], (float)x.a[3] + (float)x.b[3]);
+  }
+};
+struct LdBf16x8Pair {  // ... fetched 16 bytes at a time (same conditions as LdBf16x8), summed in fp32 and rounded once
+  static constexpr bool PAIRED = false;
+  __device__ __forceinline__ void shift(int64_t) {}
+  static constexpr int WIDTH = 8;
+  struct Raw { bf16x8_t a, b; };
+  const __bf16* p;
+  int64_t ld;
+  __device__ __forceinline__ Raw fetch(int64_t r, int64_t c) const {
+    const __bf16* pe = p + 2 * r * ld + c;
+    return Raw{*reinterpret_cast<const bf16x8_t*>(pe), *reinterpret_cast<const bf16x8_t*>(pe + ld)};
+  }
+  __device__ __forceinline__ bf16x8_t finish(const Raw& x) const {
+    bf16x8_t o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (__bf16)((float)x.a[i] + (float)x.b[i]);
+    return o;
+  }
+};
+
 // ---------------------------------------------------------------------------- epilogues
 // operator()(r, col, a, b, z): a holds columns col..col+3 of output row r (even, in range) and b
 // the same columns of row r + 1, which the functor must skip when r + 1 == M unless the rows
 // come in pairs (jets: M = 2E).  z is the k-split index.
-__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 __device__ __forceinline__ float4 scale4(float s, float4 a) { return make_float4(s * a.x, s * a.y, s * a.z, s * a.w); }
 
 struct EpiStoreJetAct {  // u = v (fp32 jets) and the activated jets silu(u), silu'(u) u' rounded to bf16

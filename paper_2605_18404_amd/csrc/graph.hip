@@ -286,6 +286,30 @@ __global__ void k_reverse_map(const int32_t* __restrict__ row_ptr, const int32_t
   rev[e] = found;
 }
 
+// Edge pairs.  flag[e] = 1 for the lower-numbered edge of a pair; after the exclusive scan of the flags (pre),
+// that edge's pair index is pre[e].  An edge without an opposite (reported through the status word) is given slot 0:
+// every index stays in range, the results of such a call are not meaningful anyway.
+__global__ void k_pair_flags(const int32_t* __restrict__ rev, int64_t E, int32_t* __restrict__ flag) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < E) flag[e] = rev[e] > e ? 1 : 0;
+}
+__global__ void k_pair_assign(const int32_t* __restrict__ rev, const int32_t* __restrict__ sender, const int32_t* __restrict__ pre,
+                              int64_t E, int64_t Eu, int2* __restrict__ se, int32_t* __restrict__ und) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const int r = rev[e];
+  if (r > e) {
+    const int u = pre[e];
+    if (u < Eu) {  // always, for an involution without fixed points: at most E / 2 edges have a higher-numbered opposite
+      und[u] = (int32_t)e;
+      se[e] = make_int2(sender[e], 2 * u);
+      se[r] = make_int2(sender[r], 2 * u + 1);
+    }
+  } else if (r < 0) {
+    se[e] = make_int2(sender[e], 0);
+  }
+}
+
 __global__ void k_export_shift(const int32_t* __restrict__ code, int64_t E, int32_t* __restrict__ shift) {
   int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= E) return;
@@ -327,7 +351,10 @@ int graph_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_code = alloc_n<int32_t>(ctx, E)) != nullptr;
   ok &= (ctx->d_receiver = alloc_n<int32_t>(ctx, E)) != nullptr;
   ok &= (ctx->d_rev = alloc_n<int32_t>(ctx, E)) != nullptr;
-  int64_t scan_blocks = (std::max(N, ctx->max_bins) + SCAN_TILE) / SCAN_TILE + 1;
+  ok &= (ctx->d_se = alloc_n<int2>(ctx, E)) != nullptr;
+  ok &= (ctx->d_und = alloc_n<int32_t>(ctx, E / 2 + 1)) != nullptr;
+  ok &= (ctx->d_pair_pre = alloc_n<int32_t>(ctx, E + 1)) != nullptr;
+  int64_t scan_blocks = (std::max(std::max(N, ctx->max_bins), E) + SCAN_TILE) / SCAN_TILE + 1;
   ok &= (ctx->d_scan_tmp = alloc_n<int32_t>(ctx, scan_blocks)) != nullptr;
   ok &= (ctx->d_flag = alloc_n<int32_t>(ctx, 4)) != nullptr;
   ok &= (ctx->d_bounds = alloc_n<float>(ctx, 6 * B)) != nullptr;
@@ -514,11 +541,19 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
                        ctx->d_code, ctx->d_receiver);
     hipLaunchKernelGGL(k_reverse_map, dim3((unsigned)((E + TB - 1) / TB)), dim3(TB), 0, st, ctx->d_row_ptr,
                        ctx->d_sender, ctx->d_code, ctx->d_receiver, E, ctx->d_rev, ctx->d_flag);
+    if (ctx->d_se) {  // edge pairs (the sorting keys are no longer needed: their array holds the flags)
+      const unsigned eb = (unsigned)((E + TB - 1) / TB);
+      hipLaunchKernelGGL(k_pair_flags, dim3(eb), dim3(TB), 0, st, ctx->d_rev, E, ctx->d_key_tmp);
+      MLIP_TRY(scan_exclusive(ctx, ctx->d_key_tmp, ctx->d_pair_pre, E));
+      MLIP_HIP_CHECK(ctx, hipMemsetAsync(ctx->d_und, 0, sizeof(int32_t) * (E / 2 + 1), st));
+      hipLaunchKernelGGL(k_pair_assign, dim3(eb), dim3(TB), 0, st, ctx->d_rev, ctx->d_sender, ctx->d_pair_pre, E, E / 2, ctx->d_se, ctx->d_und);
+    }
   }
   MLIP_HIP_CHECK(ctx, hipGetLastError());
   ctx->N = N;
   ctx->B = B;
   ctx->E = E;
+  ctx->Eu = E / 2;
   ctx->phase = PH_GRAPH;
   return MLIP_OK;
 }

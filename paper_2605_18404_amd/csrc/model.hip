@@ -14,6 +14,11 @@
 // gradient is dL/dtheta.  Weight gradients: products that involve a derivative row of a jet
 // (or a tangent) are the second-order term of Eq. 2 and are added by BF; products with value
 // rows are the merged first-order term and are added by BE.
+//
+// Opposite edges have the same length, so the radial basis, the edge MLP and the filter jets are evaluated once per
+// edge PAIR (half the rows of every edge matrix product): pair u owns rows 2u, 2u + 1 of the jet matrices, and an
+// edge's slot = 2u + (0 | 1) says which pair it belongs to and which of the pair's two adjoint rows (X) it writes.
+// The adjoint of a pair's filter jet is the sum of its two edges' rows, formed when X is staged for a product.
 #include <algorithm>
 #include <cmath>
 
@@ -26,14 +31,15 @@ using namespace fx;
 struct InvWs {
   int L = 0, depth = 2;
   float* paramsT = nullptr;
-  float* jphi = nullptr;   // [E][2][K]
+  float* jphi = nullptr;   // [Eu][2][K]; every edge tensor below marked Eu has one row (or jet) per edge pair
   float2* env = nullptr;   // [E] (f_c, f_c')
-  std::vector<float*> U[2];   // hidden pre-activations, jets [E][2][H]; U[0] level 1, U[1] level 2 (depth 3)
-  std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [E][2][H]
-  std::vector<float*> Om;     // [E][2][C], in the operand precision (fp32 or bf16)
-  std::vector<float*> Y[2];   // [E][H]  BF -> BE
+  float2* env_u = nullptr; // [Eu] the same per edge pair (rows of the filter product)
+  std::vector<float*> U[2];   // hidden pre-activations, jets [Eu][2][H]; U[0] level 1, U[1] level 2 (depth 3)
+  std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [Eu][2][H]
+  std::vector<float*> Om;     // [Eu][2][C], in the operand precision (fp32 or bf16)
+  std::vector<float*> Y[2];   // [Eu][H]  BF -> BE
   std::vector<float*> Vm[2], VmT[2];  // expert banks merged per structure: [B][C][C] of V1 / V2 per layer, and transposed
-  float* X = nullptr;         // [E][max(C,H)] scratch, operand precision
+  float* X = nullptr;         // [Eu][2][C] adjoint rows of the two edges of each pair, then [Eu][max(C,H)] scratch; operand precision
   float* X2 = nullptr;
   std::vector<float*> h, a, q, mu_h, mu_a, mu_q, mu_t, hd, ad, qd;
   float* lam_h[2] = {nullptr, nullptr};
@@ -48,9 +54,9 @@ struct InvWs {
   float* Ebar = nullptr;    // [B]
   // optional position gradient dL/dx (mlip_config.position_grad): second-derivative rows of the hidden levels,
   // the last edge matrix's output with its first and second r-derivative, and the per-atom accumulator
-  float* U2[2] = {nullptr, nullptr};  // [E][H]
-  float* Wj = nullptr;                // [E][2][C] (w, w')
-  float* Wpp = nullptr;               // [E][C]   w''
+  float* U2[2] = {nullptr, nullptr};  // [Eu][H]
+  float* Wj = nullptr;                // [Eu][2][C] (w, w')
+  float* Wpp = nullptr;               // [Eu][C]   w''
   float* gp_acc = nullptr;            // [N,3]
 };
 
@@ -87,22 +93,25 @@ __device__ __forceinline__ void fma4s(float4& acc, float s, float4 a, float4 b) 
 // end are clamped to its last edge (a valid, redundant load), so no branch surrounds a load; only
 // the arithmetic and the stores of the tail are guarded.
 template <int D, typename In, typename Fetch, typename Use>
-__device__ __forceinline__ void walk_row(const int32_t* __restrict__ sender, int e0, int e1, Fetch fetch, Use use) {
+__device__ __forceinline__ void walk_row(const int2* __restrict__ se, int e0, int e1, Fetch fetch, Use use) {
   if (e0 >= e1) return;
   const int last = e1 - 1;
   auto clamp = [&](int e) { return e < last ? e : last; };
   In cur[D];
-  int jn[D];
+  int2 jn[D];  // (sender, slot) of an edge
 #pragma unroll
-  for (int k = 0; k < D; ++k) cur[k] = fetch(clamp(e0 + k), sender[clamp(e0 + k)]);
+  for (int k = 0; k < D; ++k) {
+    const int2 x = se[clamp(e0 + k)];
+    cur[k] = fetch(clamp(e0 + k), x.x, x.y);
+  }
 #pragma unroll
-  for (int k = 0; k < D; ++k) jn[k] = sender[clamp(e0 + D + k)];
+  for (int k = 0; k < D; ++k) jn[k] = se[clamp(e0 + D + k)];
   for (int e = e0; e < e1; e += D) {
     In nxt[D];
 #pragma unroll
-    for (int k = 0; k < D; ++k) nxt[k] = fetch(clamp(e + D + k), jn[k]);
+    for (int k = 0; k < D; ++k) nxt[k] = fetch(clamp(e + D + k), jn[k].x, jn[k].y);
 #pragma unroll
-    for (int k = 0; k < D; ++k) jn[k] = sender[clamp(e + 2 * D + k)];
+    for (int k = 0; k < D; ++k) jn[k] = se[clamp(e + 2 * D + k)];
 #pragma unroll
     for (int k = 0; k < D; ++k)
       if (e + k < e1) use(e + k, cur[k]);
@@ -113,7 +122,7 @@ __device__ __forceinline__ void walk_row(const int32_t* __restrict__ sender, int
 
 struct InFe { float4 w, hj; };
 template <typename TF>
-__global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const TF* __restrict__ Om, const float* __restrict__ h, int N, int C,
                                                 float* __restrict__ a) {
   RowThread t = row_thread(N, C / 4);
@@ -121,15 +130,15 @@ __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_
   const int c0 = 4 * t.cq;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   walk_row<4, InFe>(
-      sender, row_ptr[t.row], row_ptr[t.row + 1],
-      [&](int e, int j) { return InFe{ld4(Om + (int64_t)(2 * e) * C + c0), ld4(h + (int64_t)j * C + c0)}; },
+      se, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int, int j, int slot) { return InFe{ld4(Om + (int64_t)(slot & ~1) * C + c0), ld4(h + (int64_t)j * C + c0)}; },
       [&](int, const InFe& c) { fma4(acc, c.w, c.hj); });
   *reinterpret_cast<float4*>(a + (int64_t)t.row * C + c0) = acc;
 }
 
 struct InFf { float4 w, wp, hj, maj, ge; };
 template <typename TF>
-__global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const float4* __restrict__ geo, const TF* __restrict__ Om,
                                                 const float* __restrict__ h, const float* __restrict__ mu_a,
                                                 const float* __restrict__ mu_h_next, int N, int C,
@@ -144,11 +153,11 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
     float4 acc = ld4(mu_h_next + ro);
     const float4 hi = ld4(h + ro), mai = ld4(mu_a + ro);
     walk_row<2, InFf>(
-        sender, row_ptr[t.row], row_ptr[t.row + 1],
-        [&](int e, int j) {
+        se, row_ptr[t.row], row_ptr[t.row + 1],
+        [&](int e, int j, int slot) {
           InFf x;
-          x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
-          x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+          x.w = ld4(Om + (int64_t)(slot & ~1) * C + c0);
+          x.wp = ld4(Om + (int64_t)(slot | 1) * C + c0);
           x.hj = ld4(h + (int64_t)j * C + c0);
           x.maj = ld4(mu_a + (int64_t)j * C + c0);
           x.ge = geo[e];
@@ -176,9 +185,9 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
   }
 }
 
-struct InBf { float4 w, wp, hj, hdj, ge; float c, v0, v1, v2; };
+struct InBf { float4 w, wp, hj, hdj, ge; float c, v0, v1, v2; int slot; };
 template <typename TX, typename TF>
-__global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
@@ -192,11 +201,12 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
   walk_row<2, InBf>(
-      sender, row_ptr[t.row], row_ptr[t.row + 1],
-      [&](int e, int j) {
+      se, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int e, int j, int slot) {
         InBf x;
-        x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
-        x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+        x.slot = slot;
+        x.w = ld4(Om + (int64_t)(slot & ~1) * C + c0);
+        x.wp = ld4(Om + (int64_t)(slot | 1) * C + c0);
         x.hj = ld4(h + (int64_t)j * C + c0);
         x.hdj = ld4(hd + (int64_t)j * C + c0);
         x.ge = geo[e];
@@ -204,24 +214,23 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
         x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
         return x;
       },
-      [&](int e, const InBf& c) {
+      [&](int, const InBf& c) {
         const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
         fma4s(acc, rd, c.wp, c.hj);
         fma4(acc, c.w, c.hdj);
         const float s = rd * c.c;
-        st4(X + (int64_t)e * C + c0, make_float4(s * c.hj.x * mai.x, s * c.hj.y * mai.y, s * c.hj.z * mai.z, s * c.hj.w * mai.w));
+        st4(X + (int64_t)c.slot * C + c0, make_float4(s * c.hj.x * mai.x, s * c.hj.y * mai.y, s * c.hj.z * mai.z, s * c.hj.w * mai.w));
       });
   *reinterpret_cast<float4*>(ad + ro) = acc;
 }
 
 // BE gathers only the sender's adjoints lam_a[j], mu_a[j] (its own lam_h needs them).  The edge-MLP adjoint it writes is
-// that of the OPPOSITE edge (j <- i): X[rev(e)] = c (h_i lam_a,j + hdot_i mu_a,j) + c' rdot h_i mu_a,j needs this row's
-// own features and the same two gathered tables; r, rdot and the envelope are equal on opposite edges.  Every edge is
-// some edge's opposite, so each X row is written exactly once, and half the gathers are gone.
-struct InBe { float4 w, wp, laj, maj, ge; float2 cc; float v0, v1, v2; int er; };
+// that of the OPPOSITE edge (j <- i), the pair's other row (slot ^ 1): c (h_i lam_a,j + hdot_i mu_a,j) + c' rdot h_i mu_a,j
+// needs this row's own features and the same two gathered tables; r, rdot and the envelope are equal on opposite edges.
+// Every edge is some edge's opposite, so each X row is written exactly once, and half the gathers are gone.
+struct InBe { float4 w, wp, laj, maj, ge; float2 cc; float v0, v1, v2; int slot; };
 template <typename TX, typename TF>
-__global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
-                                                const int32_t* __restrict__ rev,
+__global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
@@ -236,17 +245,17 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
   float4 acc = ld4(lam_h_next + ro);
   const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
   walk_row<2, InBe>(
-      sender, row_ptr[t.row], row_ptr[t.row + 1],
-      [&](int e, int j) {
+      se, row_ptr[t.row], row_ptr[t.row + 1],
+      [&](int e, int j, int slot) {
         InBe x;
-        x.w = ld4(Om + (int64_t)(2 * e) * C + c0);
-        x.wp = ld4(Om + (int64_t)(2 * e + 1) * C + c0);
+        x.slot = slot;
+        x.w = ld4(Om + (int64_t)(slot & ~1) * C + c0);
+        x.wp = ld4(Om + (int64_t)(slot | 1) * C + c0);
         const int64_t jo = (int64_t)j * C + c0;
         x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
         x.ge = geo[e];
         x.cc = env[e];
         x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
-        x.er = rev[e];
         return x;
       },
       [&](int, const InBe& c) {
@@ -259,7 +268,7 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
         x.y = c.cc.x * (hi.y * c.laj.y + hdi.y * c.maj.y) + s * hi.y * c.maj.y;
         x.z = c.cc.x * (hi.z * c.laj.z + hdi.z * c.maj.z) + s * hi.z * c.maj.z;
         x.w = c.cc.x * (hi.w * c.laj.w + hdi.w * c.maj.w) + s * hi.w * c.maj.w;
-        if (c.er >= 0) st4(X + (int64_t)c.er * C + c0, x);
+        st4(X + (int64_t)(c.slot ^ 1) * C + c0, x);
       });
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
 }
@@ -272,7 +281,7 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
 // edge has the same r, omega, rdot and the opposite rhat, dv, so both are formed here from the row's own and the
 // gathered sender's node values.  omega' = c' w + c w', omega'' = c'' w + 2 c' w' + c w'', c'' = -(pi/r_c)^2 (c - 1/2).
 struct InGp { float4 w, wp, wpp, hj, hdj, laj, maj, ge; float2 cc; float v0, v1, v2; };
-__global__ void __launch_bounds__(256) k_msg_gp(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ sender,
+__global__ void __launch_bounds__(256) k_msg_gp(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const float4* __restrict__ geo, const float2* __restrict__ env,
                                                 const float* __restrict__ Wj, const float* __restrict__ Wpp,
                                                 const float* __restrict__ h, const float* __restrict__ hd,
@@ -288,12 +297,12 @@ __global__ void __launch_bounds__(256) k_msg_gp(const int32_t* __restrict__ row_
     const float4 hi = ld4(h + ro), hdi = ld4(hd + ro), mai = ld4(mu_a + ro), lai = ld4(lam_a + ro);
     const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
     walk_row<2, InGp>(
-        sender, row_ptr[t.row], row_ptr[t.row + 1],
-        [&](int e, int j) {
+        se, row_ptr[t.row], row_ptr[t.row + 1],
+        [&](int e, int j, int slot) {
           InGp x;
-          x.w = ld4(Wj + (int64_t)(2 * e) * C + c0);
-          x.wp = ld4(Wj + (int64_t)(2 * e + 1) * C + c0);
-          x.wpp = ld4(Wpp + (int64_t)e * C + c0);
+          x.w = ld4(Wj + (int64_t)(slot & ~1) * C + c0);
+          x.wp = ld4(Wj + (int64_t)(slot | 1) * C + c0);
+          x.wpp = ld4(Wpp + (int64_t)(slot >> 1) * C + c0);
           const int64_t jo = (int64_t)j * C + c0;
           x.hj = ld4(h + jo); x.hdj = ld4(hd + jo); x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
           x.ge = geo[e];
@@ -368,7 +377,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
   static_assert(sizeof(typename Act<P>::xop_t) == (P::IS_BF16 ? 2 : 4), "the workspace is sized for 2-byte operand-precision tensors in bf16 mode and 4-byte ones otherwise");
-  const int64_t N = ctx->N, E = ctx->E;
+  const int64_t N = ctx->N, E = ctx->E, Eu = ctx->Eu;  // atoms, edges, edge pairs (rows of the edge MLP)
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
   const bool stage = cf.model_kind == MLIP_MODEL_STAGE;
@@ -393,7 +402,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   if (P::IS_BF16) refresh_shadows(ctx);  // bf16 mirrors of the weights and of their transposes
 
   if (E > 0)
-    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->jphi);
+    launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->env_u, w->jphi);
   if (stage)
     MLIP_HIP_CHECK(ctx, hipMemcpyAsync(w->h[0], h_in, sizeof(float) * N * C, hipMemcpyDeviceToDevice, st));
   else
@@ -402,26 +411,26 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
   const int rpb = 256 / (C / 4);
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
-    if (E > 0) {
+    if (Eu > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_FE_HIDDEN_GEMM);
-        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * E, H, K, Act<P>::store(w->U[0][l], w->SJ[0][l], H, 2 * E));
+        gemm_nt<P>(ctx, LdPlain{w->jphi, K}, th + lo.W[0], 2 * Eu, H, K, Act<P>::store(w->U[0][l], w->SJ[0][l], H, 2 * Eu));
       }
       const float* ulast = w->U[0][l];
       const __bf16* sjlast = w->SJ[0][l];
       if (d == 3) {
-        gemm_nt<P>(ctx, Act<P>::jet(w->U[0][l], w->SJ[0][l], H), th + lo.W[1], 2 * E, H, H, Act<P>::store(w->U[1][l], w->SJ[1][l], H, 2 * E));
+        gemm_nt<P>(ctx, Act<P>::jet(w->U[0][l], w->SJ[0][l], H), th + lo.W[1], 2 * Eu, H, H, Act<P>::store(w->U[1][l], w->SJ[1][l], H, 2 * Eu));
         ulast = w->U[1][l];
         sjlast = w->SJ[1][l];
       }
       {
         KernelTimer kt(ctx, MLIP_K_FE_FILTER_GEMM);
-        gemm_nt<P>(ctx, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * E, C, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Om[l]), w->env, C, 2 * E});
+        gemm_nt<P>(ctx, Act<P>::jet(ulast, sjlast, H), th + lo.W[d - 1], 2 * Eu, C, H, EpiOmega<TF>{reinterpret_cast<TF*>(w->Om[l]), w->env_u, C, 2 * Eu});
       }
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
+      hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
                          (int)N, C, w->a[l]);
     }
     node_mm<P>(ctx, l, 0, false, LdPlain{w->a[l], C}, EpiStore{w->q[l], C, N});
@@ -460,7 +469,7 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
     node_mm<P>(ctx, l, 0, true, LdPlain{w->mu_q[l], C}, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
-      hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
+      hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
                          w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
     }
   }
@@ -476,7 +485,7 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  const int64_t N = ctx->N, E = ctx->E;
+  const int64_t N = ctx->N, Eu = ctx->Eu;  // atoms, edge pairs (rows of the edge MLP's products)
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
@@ -493,7 +502,7 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env,
+      hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
     }
     node_mm<P>(ctx, l, 0, false, LdPlain{w->ad[l], C}, EpiStore{w->qd[l], C, N});
@@ -501,35 +510,35 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
     // second-order weight gradients of the update MLP: mu_{h'}^T tdot, mu_q^T adot
     MLIP_TRY((node_wgrad<P>(ctx, l, 1, LdPlain{w->mu_h[l + 1], C}, LdDsiluMul{w->q[l], w->qd[l], C}, grad)));
     MLIP_TRY((node_wgrad<P>(ctx, l, 0, LdPlain{w->mu_q[l], C}, LdPlain{w->ad[l], C}, grad)));
-    if (E > 0) {
+    if (Eu > 0) {
       // X = rdot * mu_w (adjoint of the derivative row w').  Chain back through the jets' derivative rows.
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::odd(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xpair(X, C), Act<P>::odd(ulast, w->SJ[d - 2][l], H), Eu, C, H, grad + lo.W[d - 1])));
       }
       // The last data-gradient product of the chain feeds only the gradient of the first edge
       // matrix, Z^T phi' (K columns): fp32 folds that product into the epilogue (Z never reaches HBM).
-      const bool fold = !P::IS_BF16 && fold_ok(ctx, E, H, K);
+      const bool fold = !P::IS_BF16 && fold_ok(ctx, Eu, H, K);
       const FoldB fb{w->jphi + K, 2 * K, K, nullptr};
       if (d == 2) {
         KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
         if constexpr (!P::IS_BF16) {
-          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiYZFold<TX>{w->Y[0][l], ulast, H, E, fb}, grad + lo.W[0]);
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[1], Eu, H, C, EpiYZFold<TX>{w->Y[0][l], ulast, H, Eu, fb}, grad + lo.W[0]);
         }
-        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiYZ<TX>{w->Y[0][l], X2, ulast, H, E});
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[1], Eu, H, C, EpiYZ<TX>{w->Y[0][l], X2, ulast, H, Eu});
       } else {
         {
           KernelTimer kt(ctx, MLIP_K_BF_DGRAD);
-          gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[2], E, H, C, EpiYZ<TX>{w->Y[1][l], X2, ulast, H, E});
+          gemm_nt<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[2], Eu, H, C, EpiYZ<TX>{w->Y[1][l], X2, ulast, H, Eu});
         }
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::odd(w->U[0][l], w->SJ[0][l], H), Eu, H, H, grad + lo.W[1])));
         if constexpr (!P::IS_BF16) {
-          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZFold<TX>{w->Y[0][l], w->U[0][l], H, E, fb}, grad + lo.W[0]);
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], Eu, H, H, EpiYZFold<TX>{w->Y[0][l], w->U[0][l], H, Eu, fb}, grad + lo.W[0]);
         }
-        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, E});
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], Eu, H, H, EpiYZ<TX>{w->Y[0][l], X, w->U[0][l], H, Eu});
       }
-      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi + K, 2 * K}, E, H, K, grad + lo.W[0])));
+      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi + K, 2 * K}, Eu, H, K, grad + lo.W[0])));
     }
   }
   if (stage) {
@@ -552,7 +561,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
   InvWs* w = ws_of(ctx);
   const mlip_config& cf = ctx->cfg;
   hipStream_t st = ctx->stream;
-  const int64_t N = ctx->N, E = ctx->E;
+  const int64_t N = ctx->N, Eu = ctx->Eu;  // atoms, edge pairs (rows of the edge MLP's products)
   const int C = cf.channels, H = cf.edge_hidden, K = cf.n_rbf, L = cf.n_layers, d = cf.edge_mlp_depth;
   const float* th = ctx->d_params;
   const float* tT = w->paramsT;
@@ -586,53 +595,53 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     node_mm<P>(ctx, l, 0, true, LdPlain{w->lam_q, C}, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_rev, ctx->d_geo, w->env,
+      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env,
                          reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
     }
-    if (want_gp && E > 0) {
+    if (want_gp && Eu > 0) {
       // dL/dx (optional, off the timed path): the edge MLP's output with its first and second r-derivative
       // (second-derivative rows chained through the hidden levels), then this layer's share per atom
       const float dmu = cf.cutoff / (float)(K - 1), gamma = 0.5f / (dmu * dmu);
-      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, dmu, gamma}, th + lo.W[0], E, H, K, EpiStore{w->U2[0], H, E});
+      gemm_nt<P>(ctx, LdPhi2{ctx->d_geo, ctx->d_und, dmu, gamma}, th + lo.W[0], Eu, H, K, EpiStore{w->U2[0], H, Eu});
       const float* u2last = w->U2[0];
       if (d == 3) {
-        gemm_nt<P>(ctx, LdJetSecond{w->U[0][l], w->U2[0], H}, th + lo.W[1], E, H, H, EpiStore{w->U2[1], H, E});
+        gemm_nt<P>(ctx, LdJetSecond{w->U[0][l], w->U2[0], H}, th + lo.W[1], Eu, H, H, EpiStore{w->U2[1], H, Eu});
         u2last = w->U2[1];
       }
       const float* ul = w->U[d - 2][l];
-      gemm_nt<P>(ctx, Act<P>::jet(ul, w->SJ[d - 2][l], H), th + lo.W[d - 1], 2 * E, C, H, EpiStore{w->Wj, C, 2 * E});
-      gemm_nt<P>(ctx, LdJetSecond{ul, u2last, H}, th + lo.W[d - 1], E, C, H, EpiStore{w->Wpp, C, E});
+      gemm_nt<P>(ctx, Act<P>::jet(ul, w->SJ[d - 2][l], H), th + lo.W[d - 1], 2 * Eu, C, H, EpiStore{w->Wj, C, 2 * Eu});
+      gemm_nt<P>(ctx, LdJetSecond{ul, u2last, H}, th + lo.W[d - 1], Eu, C, H, EpiStore{w->Wpp, C, Eu});
       const float kk = 3.14159265358979323846f / cf.cutoff;
-      hipLaunchKernelGGL(k_msg_gp, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_sender, ctx->d_geo, w->env, w->Wj, w->Wpp,
+      hipLaunchKernelGGL(k_msg_gp, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env, w->Wj, w->Wpp,
                          w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, kk * kk, (int)N, C, w->gp_acc);
     }
-    if (E > 0) {
+    if (Eu > 0) {
       const float* ulast = w->U[d - 2][l];
       {
         KernelTimer kt(ctx, MLIP_K_BE_WGRAD);
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X, C), Act<P>::even(ulast, w->SJ[d - 2][l], H), E, C, H, grad + lo.W[d - 1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xpair(X, C), Act<P>::even(ulast, w->SJ[d - 2][l], H), Eu, C, H, grad + lo.W[d - 1])));
       }
       // as in BF: the last product of the chain is folded with phi (value rows) in fp32
-      const bool fold = !P::IS_BF16 && fold_ok(ctx, E, H, K);
+      const bool fold = !P::IS_BF16 && fold_ok(ctx, Eu, H, K);
       const FoldB fb{w->jphi, 2 * K, K, nullptr};
       if (d == 2) {
         KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
         if constexpr (!P::IS_BF16) {
-          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiLamUFold<TX>{ulast, w->Y[0][l], H, E, fb}, grad + lo.W[0]);
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[1], Eu, H, C, EpiLamUFold<TX>{ulast, w->Y[0][l], H, Eu, fb}, grad + lo.W[0]);
         }
-        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[1], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[0][l], H, E});
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[1], Eu, H, C, EpiLamU<TX>{X2, ulast, w->Y[0][l], H, Eu});
       } else {
         {
           KernelTimer kt(ctx, MLIP_K_BE_DGRAD);
-          gemm_nt<P>(ctx, Act<P>::xld(X, C), tT + lo.W[2], E, H, C, EpiLamU<TX>{X2, ulast, w->Y[1][l], H, E});
+          gemm_nt<P>(ctx, Act<P>::xpair(X, C), tT + lo.W[2], Eu, H, C, EpiLamU<TX>{X2, ulast, w->Y[1][l], H, Eu});
         }
-        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), E, H, H, grad + lo.W[1])));
+        MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(X2, H), Act<P>::even(w->U[0][l], w->SJ[0][l], H), Eu, H, H, grad + lo.W[1])));
         if constexpr (!P::IS_BF16) {
-          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamUFold<TX>{w->U[0][l], w->Y[0][l], H, E, fb}, grad + lo.W[0]);
+          if (fold) gemm_nt_fold<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], Eu, H, H, EpiLamUFold<TX>{w->U[0][l], w->Y[0][l], H, Eu, fb}, grad + lo.W[0]);
         }
-        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], E, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, E});
+        if (!fold) gemm_nt<P>(ctx, Act<P>::xld(X2, H), tT + lo.W[1], Eu, H, H, EpiLamU<TX>{X, w->U[0][l], w->Y[0][l], H, Eu});
       }
-      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi, 2 * K}, E, H, K, grad + lo.W[0])));
+      if (!fold) MLIP_TRY((gemm_wgrad<P>(ctx, Act<P>::xld(d == 3 ? X : X2, H), LdPlain{w->jphi, 2 * K}, Eu, H, K, grad + lo.W[0])));
     }
     cur ^= 1;
   }
@@ -667,22 +676,24 @@ int inv_alloc(mlip_ctx* ctx) {
   ok &= (ctx->d_geo = alloc_n<float4>(ctx, E)) != nullptr;
   w->paramsT = A(ctx->n_params);
   if (cf.gemm_dtype == MLIP_GEMM_BF16) ok &= add_shadow(ctx, ctx->d_params, ctx->n_params) && add_shadow(ctx, w->paramsT, ctx->n_params);
-  w->jphi = A(2 * E * K);
+  const int64_t Eu = E / 2 + 1;  // edge pairs
+  w->jphi = A(2 * Eu * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
+  ok &= (w->env_u = alloc_n<float2>(ctx, Eu)) != nullptr;
   const int64_t Wmax = std::max(C, H);
   const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
   // tensors held in the operand precision: half the floats when that is bf16
   auto AH = [&](int64_t n) { return A(b16 ? (n + 1) / 2 : n); };
-  w->X = AH(E * Wmax);
-  w->X2 = AH(E * Wmax);
+  w->X = AH(std::max(2 * Eu * C, Eu * Wmax));
+  w->X2 = AH(Eu * Wmax);
   for (int l = 0; l < L; ++l) {
-    w->U[0].push_back(A(2 * E * H));
-    w->U[1].push_back(d == 3 ? A(2 * E * H) : nullptr);
-    w->SJ[0].push_back(b16 ? (__bf16*)A(E * H) : nullptr);  // 2 E H bf16 = E H floats
-    w->SJ[1].push_back(b16 && d == 3 ? (__bf16*)A(E * H) : nullptr);
-    w->Om.push_back(cf.filter_fp32 ? A(2 * E * C) : AH(2 * E * C));
-    w->Y[0].push_back(A(E * H));
-    w->Y[1].push_back(d == 3 ? A(E * H) : nullptr);
+    w->U[0].push_back(A(2 * Eu * H));
+    w->U[1].push_back(d == 3 ? A(2 * Eu * H) : nullptr);
+    w->SJ[0].push_back(b16 ? (__bf16*)A(Eu * H) : nullptr);  // 2 Eu H bf16 = Eu H floats
+    w->SJ[1].push_back(b16 && d == 3 ? (__bf16*)A(Eu * H) : nullptr);
+    w->Om.push_back(cf.filter_fp32 ? A(2 * Eu * C) : AH(2 * Eu * C));
+    w->Y[0].push_back(A(Eu * H));
+    w->Y[1].push_back(d == 3 ? A(Eu * H) : nullptr);
     if (cf.n_experts > 0)
       for (int k = 0; k < 2; ++k) { w->Vm[k].push_back(A(B * C * C)); w->VmT[k].push_back(A(B * C * C)); }
     w->a.push_back(A(N * C)); w->q.push_back(A(N * C));
@@ -696,10 +707,10 @@ int inv_alloc(mlip_ctx* ctx) {
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
   if (cf.position_grad) {
-    w->U2[0] = A(E * H);
-    if (d == 3) w->U2[1] = A(E * H);
-    w->Wj = A(2 * E * C);
-    w->Wpp = A(E * C);
+    w->U2[0] = A(Eu * H);
+    if (d == 3) w->U2[1] = A(Eu * H);
+    w->Wj = A(2 * Eu * C);
+    w->Wpp = A(Eu * C);
     w->gp_acc = A(3 * N);
   }
   // split-k partial sums: the largest weight matrix times its split count

@@ -206,6 +206,7 @@ struct Act<gemm::Fp32> {
   typedef float xop_t;  // element type of the edge tensors that only feed matrix products
   typedef LdPlain XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
+  static LdPairSum xpair(const xop_t* x, int64_t ld) { return LdPairSum{x, ld}; }  // rows 2u, 2u + 1 summed
   static Jet jet(const float* u, const __bf16*, int H) { return Jet{u, H}; }
   static Even even(const float* u, const __bf16*, int H) { return Even{u, H}; }
   static Odd odd(const float* u, const __bf16*, int H) { return Odd{u, H}; }
@@ -220,6 +221,7 @@ struct Act<gemm::Bf16> {
   typedef __bf16 xop_t;  // rounded once by the producer: half the bytes, no conversion in the operand path
   typedef LdBf16 XLd;
   static XLd xld(const xop_t* x, int64_t ld) { return XLd{x, ld}; }
+  static LdBf16Pair xpair(const xop_t* x, int64_t ld) { return LdBf16Pair{x, ld}; }  // rows 2u, 2u + 1 summed
   static Jet jet(const float*, const __bf16* sj, int H) { return Jet{sj, H}; }
   static Even even(const float*, const __bf16* sj, int H) { return Even{sj, 2 * (int64_t)H}; }
   static Odd odd(const float*, const __bf16* sj, int H) { return Odd{sj + H, 2 * (int64_t)H}; }
@@ -271,7 +273,8 @@ void gemm_nt_as(hipStream_t st, const LdA& a, const LdB& b, int64_t M, int N, in
   const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
   // long reductions over raw bf16 operands: 256 x 128 tiles (128 x 64 per wave) stage a third fewer bytes through LDS per
   // matrix instruction (LDS takes 64 bytes per clock in, 256 out, and is what bounds these kernels)
-  if constexpr (P::IS_BF16 && LdA::WIDTH == 8 && LdB::WIDTH == 8) {
+  // (not with a pair-summing A loader: its two raw rows per item do not fit the register budget of that tile)
+  if constexpr (P::IS_BF16 && LdA::WIDTH == 8 && LdB::WIDTH == 8 && !std::is_same<LdA, LdBf16x8Pair>::value) {
     if (N % 128 == 0 && K >= 256 && tiles128 >= 2048) return (void)gemm::launch<P, 4, 2, 2, 2, true>(st, a, b, epi, M, N, K, 1);
   }
   if (N > 64 && tiles128 >= 512)
@@ -281,9 +284,14 @@ void gemm_nt_as(hipStream_t st, const LdA& a, const LdB& b, int64_t M, int N, in
 }
 // A bf16 operand is fetched 16 bytes at a time when its leading dimension, its extent along the
 // contiguous index and its base address allow it.
-inline bool wide_ok(const LdBf16& l, int64_t extent) {
+template <typename L>
+inline bool wide_ok(const L& l, int64_t extent) {
   return l.ld % 8 == 0 && extent % 8 == 0 && (reinterpret_cast<uintptr_t>(l.p) & 15) == 0;
 }
+// the 16-byte form of a bf16 loader
+template <typename L> struct WideOf { static constexpr bool has = false; typedef L type; };
+template <> struct WideOf<LdBf16> { static constexpr bool has = true; typedef LdBf16x8 type; };
+template <> struct WideOf<LdBf16Pair> { static constexpr bool has = true; typedef LdBf16x8Pair type; };
 // D[M][N] = A[M][K] W[N][K]^T through the epilogue.  In bf16 mode the weights come from their
 // bf16 mirror when one is registered.
 template <typename P, typename LdA, typename Epi>
@@ -292,15 +300,18 @@ void gemm_nt(mlip_ctx* ctx, const LdA& a, const float* W, int64_t M, int N, int 
   if constexpr (P::IS_BF16) {
     const __bf16* W16 = shadow_of(ctx, W);
     const bool wb = W16 && wide_ok(LdBf16{W16, K}, K);
-    if constexpr (std::is_same<LdA, LdBf16>::value) {
+    if constexpr (WideOf<LdA>::has) {
+      typedef typename WideOf<LdA>::type LdA8;
       if (wide_ok(a, K)) {
         // short reduction, many column tiles: the row-stripe kernel (A staged once per 128 rows)
-        if (wb && (K == 64 || K == 128) && N % 128 == 0 && N >= 256 && M >= 128 * 256 && M % 2 == 0) {
-          if (K == 64) return gemm::launch_stripe<64>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
-          return gemm::launch_stripe<128>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
+        if constexpr (std::is_same<LdA, LdBf16>::value) {
+          if (wb && (K == 64 || K == 128) && N % 128 == 0 && N >= 256 && M >= 128 * 256 && M % 2 == 0) {
+            if (K == 64) return gemm::launch_stripe<64>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
+            return gemm::launch_stripe<128>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, epi, M, N);
+          }
         }
-        if (wb) return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdBf16x8{W16, K}, M, N, K, epi);
-        return gemm_nt_as<P>(st, LdBf16x8{a.p, a.ld}, LdPlain{W, K}, M, N, K, epi);
+        if (wb) return gemm_nt_as<P>(st, LdA8{a.p, a.ld}, LdBf16x8{W16, K}, M, N, K, epi);
+        return gemm_nt_as<P>(st, LdA8{a.p, a.ld}, LdPlain{W, K}, M, N, K, epi);
       }
     }
     if (wb) return gemm_nt_as<P>(st, a, LdBf16x8{W16, K}, M, N, K, epi);
@@ -397,18 +408,20 @@ int gemm_wgrad_as(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout
 
 template <typename P, typename LdA, typename LdB>
 int gemm_wgrad(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int Nout, int Kout, float* grad) {
-  constexpr bool A16 = std::is_same<LdA, LdBf16>::value, B16 = std::is_same<LdB, LdBf16>::value;
+  constexpr bool A16 = WideOf<LdA>::has, B16 = WideOf<LdB>::has;
+  typedef typename WideOf<LdA>::type LdA8;
+  typedef typename WideOf<LdB>::type LdB8;
   bool wa = false, wb = false;
   if constexpr (A16) wa = wide_ok(a, Nout);
   if constexpr (B16) wb = wide_ok(b, Kout);
   if constexpr (A16 && B16) {
-    if (wa && wb) return gemm_wgrad_as<P>(ctx, LdBf16x8{a.p, a.ld}, LdBf16x8{b.p, b.ld}, R, Nout, Kout, grad);
+    if (wa && wb) return gemm_wgrad_as<P>(ctx, LdA8{a.p, a.ld}, LdB8{b.p, b.ld}, R, Nout, Kout, grad);
   }
   if constexpr (A16) {
-    if (wa) return gemm_wgrad_as<P>(ctx, LdBf16x8{a.p, a.ld}, b, R, Nout, Kout, grad);
+    if (wa) return gemm_wgrad_as<P>(ctx, LdA8{a.p, a.ld}, b, R, Nout, Kout, grad);
   }
   if constexpr (B16) {
-    if (wb) return gemm_wgrad_as<P>(ctx, a, LdBf16x8{b.p, b.ld}, R, Nout, Kout, grad);
+    if (wb) return gemm_wgrad_as<P>(ctx, a, LdB8{b.p, b.ld}, R, Nout, Kout, grad);
   }
   return gemm_wgrad_as<P>(ctx, a, b, R, Nout, Kout, grad);
 }
@@ -578,8 +591,9 @@ int gemm_wgrad_experts(mlip_ctx* ctx, const LdA& a, const LdB& b, int64_t R, int
 __global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__ pos, const int32_t* __restrict__ sender,
                                                        const int32_t* __restrict__ receiver, const int32_t* __restrict__ code,
                                                        const int32_t* __restrict__ atom_struct, const StructMeta* __restrict__ meta,
+                                                       const int2* __restrict__ se,
                                                        int64_t E, int K, int qshift, float rc, float4* __restrict__ geo,
-                                                       float2* __restrict__ env, float* __restrict__ jphi,
+                                                       float2* __restrict__ env, float2* __restrict__ env_u, float* __restrict__ jphi,
                                                        int32_t* __restrict__ flag) {
   const int q = threadIdx.x & ((1 << qshift) - 1);
   const int64_t e = (int64_t)blockIdx.x * (256 >> qshift) + (threadIdx.x >> qshift);
@@ -604,8 +618,13 @@ __global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__
     p[u] = expf(-gamma * t * t);
     d[u] = -2.f * gamma * t * p[u];
   }
-  *reinterpret_cast<float4*>(jphi + (2 * e) * K + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
-  *reinterpret_cast<float4*>(jphi + (2 * e + 1) * K + 4 * q) = make_float4(d[0], d[1], d[2], d[3]);
+  // the radial basis is kept once per edge pair (both edges have the same length, bit for bit: the opposite edge's
+  // difference vector is the exact negative): the pair's lower-numbered edge writes rows 2u, 2u + 1
+  const int slot = se[e].y;
+  if (!(slot & 1)) {
+    *reinterpret_cast<float4*>(jphi + (int64_t)slot * K + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
+    *reinterpret_cast<float4*>(jphi + (int64_t)(slot + 1) * K + 4 * q) = make_float4(d[0], d[1], d[2], d[3]);
+  }
   if (q == 0) {
     // two atoms at one place have no direction: report it (deferred input diagnostics) and keep the numbers finite
     if (!(r > 0.f)) atomicOr(flag + 1, INPUT_COINCIDENT);
@@ -615,15 +634,17 @@ __global__ void __launch_bounds__(256) k_edge_features(const float* __restrict__
     float sn, cs;
     sincosf(w * r, &sn, &cs);
     env[e] = make_float2(0.5f * (1.f + cs), -0.5f * w * sn);
+    if (!(slot & 1)) env_u[slot >> 1] = make_float2(0.5f * (1.f + cs), -0.5f * w * sn);
   }
 }
 
-inline void launch_edge_features(mlip_ctx* ctx, int64_t E, int K, float rc, float2* env, float* jphi) {
+// geo[E], env[E] per edge; env_u[Eu], jphi[Eu][2][K] per edge pair
+inline void launch_edge_features(mlip_ctx* ctx, int64_t E, int K, float rc, float2* env, float2* env_u, float* jphi) {
   int qshift = 0;
   while ((4 << qshift) < K) ++qshift;  // 2^qshift threads per edge, K <= 1024
   const int64_t per_block = 256 >> qshift;
   hipLaunchKernelGGL(k_edge_features, dim3((unsigned)((E + per_block - 1) / per_block)), dim3(256), 0, ctx->stream, ctx->d_pos,
-                     ctx->d_sender, ctx->d_receiver, ctx->d_code, ctx->d_atom_struct, ctx->d_meta, E, K, qshift, rc, ctx->d_geo, env, jphi, ctx->d_flag);
+                     ctx->d_sender, ctx->d_receiver, ctx->d_code, ctx->d_atom_struct, ctx->d_meta, ctx->d_se, E, K, qshift, rc, ctx->d_geo, env, env_u, jphi, ctx->d_flag);
 }
 
 
