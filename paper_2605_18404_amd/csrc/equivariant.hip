@@ -59,6 +59,10 @@ struct EqvWs {
   float* X = nullptr;       // [Eu][2][C][NPP] (the two edges of a pair), operand precision
   float* X2 = nullptr;      // [Eu][H]
   std::vector<float*> h, a, mu_h, mu_a, hd, ad;  // [NM][N][C]
+  // bf16 filter jets only: packed bf16 copies [N][C][NMP] of the tables gathered per edge from the sender (per layer: features,
+  // their tangents, the cotangent mu_a; one for the adjoint lam_a)
+  std::vector<__bf16*> gh, ghd, gmu;
+  __bf16* glam = nullptr;
   std::vector<float*> u, mu_u, ud;  // gated update only, [NM][N][C]: pre-activations W a, their FF cotangents, their BF tangents
   float* lam_u = nullptr;           // gated update only: BE adjoint of the pre-activations
   float* lam_h[2] = {nullptr, nullptr};
@@ -202,6 +206,56 @@ __device__ __forceinline__ void store_paths(__bf16* __restrict__ row, int c, con
   }
 }
 
+// Packed sender rows.  When the filter jets are stored in bf16, the node tables a kernel gathers per edge from the
+// SENDER (features, their tangents, the two cotangents) are read from bf16 copies laid out [N][C][NMP]: the NM components
+// of one (atom, channel) are contiguous (NMP = 10 for 9 components, 16 for 16), so a lane fetches its sender row with two
+// wide loads instead of NM four-byte ones, and the gathers -- most of these kernels' memory traffic -- move 20 (32) bytes
+// per table, lane and edge instead of 36 (64).  Both operands of the tensor product are then in the matrix products'
+// operand precision; the receiver's own rows, all sums and every table itself stay fp32.
+// (Used for l_max = 2 only: at l_max = 3 the kernels are bound by instruction issue, not by the gathers, and the
+// conversions made them 3 % slower.)
+template <int NM> struct PackedRow { static constexpr int NMP = NM == 9 ? 10 : 16; };
+template <typename TF, typename G>
+__host__ __device__ constexpr bool packed_rows() { return std::is_same<TF, __bf16>::value && G::LMAX == 2; }
+struct __attribute__((aligned(4))) Words4 { uint32_t x, y, z, w; };
+template <int NM>
+__device__ __forceinline__ void load_packed(const __bf16* __restrict__ g, int64_t row, float (&x)[NM]) {
+  static_assert(NM == 9 || NM == 16, "packed rows exist for l_max = 2 and 3");
+  const uint32_t* p = reinterpret_cast<const uint32_t*>(g + row * PackedRow<NM>::NMP);
+  const Words4 a = *reinterpret_cast<const Words4*>(p);
+  const uint32_t lo[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { x[2 * k] = bf_lo(lo[k]); x[2 * k + 1] = bf_hi(lo[k]); }
+  if constexpr (NM == 9) {
+    x[8] = bf_lo(p[4]);
+  } else {
+    const Words4 b = *reinterpret_cast<const Words4*>(p + 4);
+    const uint32_t hi[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { x[8 + 2 * k] = bf_lo(hi[k]); x[9 + 2 * k] = bf_hi(hi[k]); }
+  }
+}
+// a single live component comes from the fp32 table; a full row from the packed copy when there is one
+template <bool PACK, int NX>
+__device__ __forceinline__ void gather_row(const float* __restrict__ tab, const __bf16* __restrict__ packed, int64_t NC, int64_t row,
+                                           float (&x)[NX]) {
+  if constexpr (PACK && NX > 1) load_packed(packed, row, x);
+  else loadm(tab, NC, row, x);
+}
+// tab [NM][N][C] fp32 -> packed [N][C][NMP] bf16 (pad = 0)
+template <int NM>
+__global__ void k_pack_rows(const float* __restrict__ tab, int64_t NC, __bf16* __restrict__ packed) {
+  constexpr int NMP = PackedRow<NM>::NMP;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= NC) return;
+  float x[NMP];
+#pragma unroll
+  for (int m = 0; m < NMP; ++m) x[m] = m < NM ? tab[m * NC + idx] : 0.f;
+  uint32_t* q = reinterpret_cast<uint32_t*>(packed + idx * NMP);
+#pragma unroll
+  for (int k = 0; k < NMP / 2; ++k) q[k] = bf_pack(x[2 * k], x[2 * k + 1]);
+}
+
 struct RowChan {
   int row, c;
   bool active;
@@ -282,7 +336,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 template <typename G, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
-                                               const float* __restrict__ h, int N, int C, float* __restrict__ a) {
+                                               const float* __restrict__ h, const __bf16* __restrict__ gh, int N, int C,
+                                               float* __restrict__ a) {
+  constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
   constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD;  // paths and row width of this layer
   constexpr int NA = LZ ? 1 : NM;  // components of the output that anything reads
@@ -303,7 +359,7 @@ __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_p
     const float* cy = cyt + (int64_t)e * CY_LD;
     TabRegs<G> tr;
     if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
-    loadm(h, NC, (int64_t)j * C + t.c, x);
+    gather_row<PACK>(h, gh, NC, (int64_t)j * C + t.c, x);
     load_rho(Rho + (int64_t)(es & ~1) * NPP * C, t.c, rho);
     if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
     float S = 0.f;  // sum_n cy[n] x[m1_n] over the entries of one slot
@@ -326,8 +382,10 @@ template <typename G, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                   const float4* __restrict__ geo, const TF* __restrict__ Rho,
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
-                                                  const float* __restrict__ mu_a, const float* __restrict__ mu_h_next, int N,
+                                                  const float* __restrict__ mu_a, const __bf16* __restrict__ gh,
+                                                  const __bf16* __restrict__ gmu, const float* __restrict__ mu_h_next, int N,
                                                   int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
+  constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
   constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   __shared__ float3 red[256];
@@ -361,8 +419,8 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
       if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
       float xj[NX], mj[NU], rho[NPATH], rhop[NPATH];
       const int64_t jo = (int64_t)j * C + t.c;
-      loadm(h, NC, jo, xj);
-      loadm(mu_a, NC, jo, mj);
+      gather_row<PACK>(h, gh, NC, jo, xj);
+      gather_row<PACK>(mu_a, gmu, NC, jo, mj);
       const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
       load_rho(rrow, t.c, rho);
       load_rho(rrow + NPP * C, t.c, rhop);
@@ -458,9 +516,11 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                   const float* __restrict__ cydt, const float* __restrict__ h,
-                                                  const float* __restrict__ hd, const float* __restrict__ mu_a, int N, int C,
+                                                  const float* __restrict__ hd, const float* __restrict__ mu_a,
+                                                  const __bf16* __restrict__ gh, const __bf16* __restrict__ ghd, int N, int C,
                                                   float* __restrict__ ad,
                                                   TX* __restrict__ X) {
+  constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
   constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   constexpr int NU = LZ ? 1 : NM;  // live components of the messages' cotangent, and components of the output that anything reads
@@ -488,8 +548,8 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
     constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features (their tangent vanishes in the first layer)
     float xj[NX], xdj[NX], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
-    loadm(h, NC, jo, xj);
-    if constexpr (!L0) loadm(hd, NC, jo, xdj);
+    gather_row<PACK>(h, gh, NC, jo, xj);
+    if constexpr (!L0) gather_row<PACK>(hd, ghd, NC, jo, xdj);
     const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
@@ -542,8 +602,11 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                   const float* __restrict__ cydt, const float* __restrict__ h,
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                                  const float* __restrict__ lam_a, const float* __restrict__ lam_h_next, int N, int C,
+                                                  const float* __restrict__ lam_a, const __bf16* __restrict__ gh,
+                                                  const __bf16* __restrict__ ghd, const __bf16* __restrict__ gmu,
+                                                  const __bf16* __restrict__ glam, const float* __restrict__ lam_h_next, int N, int C,
                                                   float* __restrict__ lam_h, TX* __restrict__ X) {
+  constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
   constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
   RowChan t = row_chan(N, C);
@@ -576,10 +639,10 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
     float xj[NX], xdj[NX], lj[NU], mj[NU], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
-    loadm(h, NC, jo, xj);
-    if constexpr (!L0) loadm(hd, NC, jo, xdj);
-    loadm(lam_a, NC, jo, lj);
-    loadm(mu_a, NC, jo, mj);
+    gather_row<PACK>(h, gh, NC, jo, xj);
+    if constexpr (!L0) gather_row<PACK>(hd, ghd, NC, jo, xdj);
+    gather_row<PACK>(lam_a, glam, NC, jo, lj);
+    gather_row<PACK>(mu_a, gmu, NC, jo, mj);
     const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
     load_rho(rrow, t.c, rho);
     load_rho(rrow + NPP * C, t.c, rr);
@@ -960,6 +1023,15 @@ __global__ void k_gate_be(const float* __restrict__ u, const float* __restrict__
   lam_u[idx] = g.f1 * lam[idx] + g.ds * u_lam + ud0 * (g.f2 * mu[idx] + g.dds * u_mu) + g.ds * ud_mu;
 }
 
+// packed bf16 copy of a node table for the sender gathers (only when the filter jets are bf16)
+template <typename TF, typename G>
+void pack_rows(mlip_ctx* ctx, const float* tab, __bf16* packed) {
+  if constexpr (packed_rows<TF, G>()) {
+    const int64_t NC = ctx->N * ctx->cfg.channels;
+    hipLaunchKernelGGL(k_pack_rows<G::NM>, dim3(nblk(NC)), dim3(256), 0, ctx->stream, tab, NC, packed);
+  }
+}
+
 // ------------------------------------------------------------------------------ phases
 template <typename P, typename TF, typename G>
 int fe_impl(mlip_ctx* ctx, float* E_out) {
@@ -1018,7 +1090,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
       auto kern = TP_KERNEL(k_tp_fe, ls, uni, G, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, reinterpret_cast<const TF*>(w->Rho[l]),
-                         w->cy, w->h[l], (int)N, C, w->a[l]);
+                         w->cy, w->h[l], w->gh[l], (int)N, C, w->a[l]);
     }
     const int kmax = ls == LS_LAST ? 0 : LMAX;  // the readout takes the last layer's l = 0 output only
     for (int k = 0; k <= kmax; ++k) {
@@ -1029,6 +1101,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
         mix_mm<P>(ctx, l, k, false, LdPlain{w->a[l] + o, C}, EpiAddStore{w->h[l + 1] + o, w->h[l] + o, C, rows});
     }
     if (gate) hipLaunchKernelGGL(k_gate_fe, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->h[l], w->h[l + 1], NC, ls == LS_LAST ? 1 : NM);
+    if (l + 1 < L) pack_rows<TF, G>(ctx, w->h[l + 1], w->gh[l + 1]);  // the next layer gathers these rows in all four phases
   }
   gemm_nt<P>(ctx, LdPlain{w->h[L], C}, th + ctx->off_U, N, C, C, EpiStore{w->y, C, N});
   hipLaunchKernelGGL(k_atom_energy, dim3(nblk(N, 4)), dim3(256), 0, st, w->y, th + ctx->off_wo, (int)N, C, w->eps);
@@ -1067,10 +1140,11 @@ int ff_impl(mlip_ctx* ctx, float* F) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
       mix_mm<P>(ctx, l, k, true, LdPlain{mu_z + o, C}, EpiStore{w->mu_a[l] + o, C, rows});
     }
+    if (ls != LS_LAST) pack_rows<TF, G>(ctx, w->mu_a[l], w->gmu[l]);  // gathered by this phase and by BE (one component in the last layer)
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = TP_KERNEL(k_tp_ff, ls, uni, G, TF);
     hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
-                       w->cy, w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+                       w->cy, w->h[l], w->mu_a[l], w->gh[l], w->gmu[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
   }
   hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
   MLIP_HIP_CHECK(ctx, hipGetLastError());
@@ -1105,7 +1179,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
       auto kern = TP_KERNEL(k_tp_bf, ls, uni, G, TX, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->env,
-                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->gh[l], w->ghd[l], (int)N, C, w->ad[l], X);
     }
     for (int k = 0; k <= kmax; ++k) {
       const int64_t o = G::L_OFF[k] * NC, rows = (2 * k + 1) * N;
@@ -1116,6 +1190,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{(gate ? w->mu_u[l] : w->mu_h[l + 1]) + o, C}, LdPlain{w->ad[l] + o, C}, grad)));
     }
     if (gate) hipLaunchKernelGGL(k_gate_bf, dim3(nblk(NC)), dim3(256), 0, st, w->u[l], w->ud[l], w->hd[l], w->hd[l + 1], NC, ls == LS_LAST ? 1 : NM);
+    if (l + 1 < L) pack_rows<TF, G>(ctx, w->hd[l + 1], w->ghd[l + 1]);  // gathered by the next layer here and in BE
     if (Eu > 0) {
       {
         KernelTimer kt(ctx, MLIP_K_BF_WGRAD);
@@ -1186,11 +1261,13 @@ int be_impl(mlip_ctx* ctx, float* grad) {
       mix_mm<P>(ctx, l, k, true, LdPlain{lam_z + o, C}, EpiStore{w->lam_a + o, C, rows});
       MLIP_TRY((mix_wgrad<P>(ctx, l, k, LdPlain{lam_z + o, C}, LdPlain{w->a[l] + o, C}, grad)));
     }
+    if (ls != LS_LAST) pack_rows<TF, G>(ctx, w->lam_a, w->glam);
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       auto kern = TP_KERNEL(k_tp_be, ls, uni, G, TX, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->env,
-                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->gh[l], w->ghd[l], w->gmu[l],
+                         w->glam, lh_next, (int)N, C, lh, X);
     }
     if (want_gp && Eu > 0) {
       // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share
@@ -1287,6 +1364,8 @@ int eqv_alloc(mlip_ctx* ctx) {
   w->cyd = A(E * CY_LD + TAB);
   w->X2 = AH(Eu * H);
   const int64_t NC9 = (int64_t)NM * N * C;  // a node table: all components
+  const bool packed = b16 && !cf.filter_fp32 && lmax == 2;  // packed bf16 sender rows [N][C][10]: 5 floats per (atom, channel)
+  const int64_t NCP = N * C * 5;
   for (int l = 0; l < L; ++l) {
     w->U.push_back(A(2 * Eu * H));
     w->SJ.push_back(b16 ? (__bf16*)A(Eu * H) : nullptr);
@@ -1296,6 +1375,8 @@ int eqv_alloc(mlip_ctx* ctx) {
     if (b16 && ok) ok &= add_shadow(ctx, w->Wp[l], (int64_t)PC * H) && add_shadow(ctx, w->WpT[l], (int64_t)PC * H);
     w->Y1.push_back(A(Eu * H));
     w->a.push_back(A(NC9)); w->mu_a.push_back(A(NC9)); w->ad.push_back(A(NC9));
+    if (packed) { w->gh.push_back((__bf16*)A(NCP)); w->ghd.push_back((__bf16*)A(NCP)); w->gmu.push_back((__bf16*)A(NCP)); }
+    else { w->gh.push_back(nullptr); w->ghd.push_back(nullptr); w->gmu.push_back(nullptr); }
     if (cf.gate) { w->u.push_back(A(NC9)); w->mu_u.push_back(A(NC9)); w->ud.push_back(A(NC9)); }
     if (cf.n_experts > 0)
       for (int k = 0; k <= lmax; ++k) { w->Wm[k].push_back(A(B * C * C)); w->WmT[k].push_back(A(B * C * C)); }
@@ -1303,6 +1384,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   for (int l = 0; l <= L; ++l) { w->h.push_back(A(NC9)); w->mu_h.push_back(A(NC9)); w->hd.push_back(A(NC9)); }
   w->lam_h[0] = A(NC9); w->lam_h[1] = A(NC9); w->lam_a = A(NC9);
   if (cf.gate) w->lam_u = A(NC9);
+  if (packed) w->glam = (__bf16*)A(NCP);
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
   if (cf.position_grad) {
