@@ -81,8 +81,9 @@ typedef struct {
   int32_t gemm_dtype;       /* MLIP_GEMM_FP32, or MLIP_GEMM_BF16: both operands of every matrix
                                product rounded to bf16 (nearest even), fp32 accumulation; the
                                radial-filter jets (outputs of such a product) are also kept in
-                               bf16 unless filter_fp32 is set; node features, pre-activations and
-                               all sums stay fp32 */
+                               bf16 unless filter_fp32 is set, and with them (equivariant model, l_max = 2)
+                               the sender rows that the tensor product gathers per edge are read from bf16
+                               copies of the node tables; node features, pre-activations and all sums stay fp32 */
   int32_t n_experts;        /* 0: dense.  > 0 (whole models only): the node-level matrices of every layer
                                (invariant: the update MLP's two; equivariant: the three per-l mixing
                                matrices) are banks [n_experts][C][C] in the parameter vector, merged
@@ -93,7 +94,8 @@ typedef struct {
   int32_t filter_fp32;      /* bf16 mode only (ignored otherwise).  0: the radial-filter jets f_c w(r) -- outputs of a
                                bf16 product, consumed element-wise by the message kernels -- are stored in bf16, as a
                                mixed-precision linear layer returns them (half the bytes of the largest edge tensor).
-                               1: they are stored in fp32, so that bf16 rounding touches matrix-product operands only */
+                               1: they are stored in fp32 and the tensor product gathers fp32 sender rows, so that bf16
+                               rounding touches matrix-product operands only */
   int32_t position_grad;    /* 1: also allocate the workspace for the position gradient dL/dx (mlip_set_position_grad);
                                0: none, and that call is refused */
   float cutoff;             /* r_c, Angstrom */
