@@ -243,15 +243,16 @@ int mlip_train_step(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const flo
  * number of launches and the sum of their durations in milliseconds. */
 enum {
   MLIP_K_NONE = 0,
-  MLIP_K_FE_HIDDEN_GEMM = 1,  /* jets of the first hidden layer: [2E,K] x [K,H] */
-  MLIP_K_FE_FILTER_GEMM = 2,  /* last edge-MLP product with the envelope epilogue: [2E,H] x [H,C] */
+  MLIP_K_FE_HIDDEN_GEMM = 1,  /* jets of the first hidden layer: [2P,K] x [K,H]; P = E/2 pairs of opposite edges (equal
+                                 lengths: the edge MLP and its adjoints are evaluated once per pair) */
+  MLIP_K_FE_FILTER_GEMM = 2,  /* last edge-MLP product with the envelope epilogue: [2P,H] x [H,C] */
   MLIP_K_MSG_FE = 3,          /* gather * filter, segmented sum into receivers */
   MLIP_K_MSG_FF = 4,
   MLIP_K_MSG_BF = 5,
   MLIP_K_MSG_BE = 6,
-  MLIP_K_BF_DGRAD = 7,        /* [E,C] x [C,H] data gradient with the activation-derivative epilogue */
+  MLIP_K_BF_DGRAD = 7,        /* [P,C] x [C,H] data gradient with the activation-derivative epilogue */
   MLIP_K_BE_DGRAD = 8,
-  MLIP_K_BF_WGRAD = 9,        /* [C,E] x [E,H] weight gradient of the last edge-MLP matrix (split-k) */
+  MLIP_K_BF_WGRAD = 9,        /* [C,P] x [P,H] weight gradient of the last edge-MLP matrix (split-k) */
   MLIP_K_BE_WGRAD = 10,
   MLIP_K_GRAPH_NEIGHBOURS = 11,
   MLIP_K_EDGE_FEATURES = 12

@@ -591,19 +591,21 @@ __global__ void __launch_bounds__(256, 2) k_tp_bf(const int32_t* __restrict__ ro
   for (int m = 0; m < NU; ++m) ad[m * NC + io] = acc[m];
 }
 
-// (Writing the adjoint of the OPPOSITE edge instead -- X[rev(e)] from this row's own features and the sender's adjoints,
-// which halves the gathers and pays off in the invariant model's kernel -- was measured slower here: the rows of X are then
-// written in scattered 1.5 KB pieces of three strided 8-byte stores per lane, 5.9 -> 8.3 ms per launch at 20,000 atoms.
-// Holding an edge's row of X back for one trip of the loop, so that its stores follow the next edge's loads, changed nothing:
-// two waves per SIMD already cover the store acknowledgements.)
+// BE gathers only the sender's cotangents lam_a[j], mu_a[j] (its own lam_h needs them).  The adjoint of the filter jet
+// that it writes is that of the OPPOSITE edge (i -> j), the pair's other row of X: its path-wise forms need the features
+// of that edge's sender -- this row's own x_i, xdot_i, loaded once per row -- and the cotangents of its receiver j, which
+// are the two gathered tables; r, rdot, the envelope and the filter jet are equal on opposite edges, and the couplings of
+// -u are those of u times the path's parity sign.  Every edge is some edge's opposite, so each row of X is still written
+// exactly once, and half the gathers are gone.  (Before the filter jets were kept per edge pair this form was slower: the
+// rows of X were then written in sequence by the direct form and scattered by this one.  Holding an edge's row of X back
+// for one trip of the loop, so that its stores follow the next edge's loads, changed nothing.)
 template <typename G, typename TX, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                   const float2* __restrict__ env,
                                                   const TF* __restrict__ Rho, const float* __restrict__ cyt,
                                                   const float* __restrict__ cydt, const float* __restrict__ h,
                                                   const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                                  const float* __restrict__ lam_a, const __bf16* __restrict__ gh,
-                                                  const __bf16* __restrict__ ghd, const __bf16* __restrict__ gmu,
+                                                  const float* __restrict__ lam_a, const __bf16* __restrict__ gmu,
                                                   const __bf16* __restrict__ glam, const float* __restrict__ lam_h_next, int N, int C,
                                                   float* __restrict__ lam_h, TX* __restrict__ X) {
   constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
@@ -615,9 +617,9 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
   const int64_t io = (int64_t)t.row * C + t.c;
   constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features, and needed ones of their adjoint
   constexpr int NU = LZ ? 1 : NM;  // live components of the cotangents of the layer's messages
-  float mi[NU], li[NU], acc[NX];
-  loadm(mu_a, NC, io, mi);
-  loadm(lam_a, NC, io, li);
+  float xi[NX], xdi[NX], acc[NX];
+  loadm(h, NC, io, xi);
+  if constexpr (!L0) loadm(hd, NC, io, xdi);  // the first layer's input has no tangent
   if constexpr (LZ) {  // the readout's adjoint has its l = 0 component only
     zero(acc);
     acc[0] = lam_h_next[io];
@@ -637,10 +639,8 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
     const float* cyd = cydt + (int64_t)e * CY_LD;
     TabRegs<G> tr, trd;
     if constexpr (UNI) { tr = tab_fetch<G>(cy, lane); trd = tab_fetch<G>(cyd, lane); }
-    float xj[NX], xdj[NX], lj[NU], mj[NU], rho[NPATH], rr[NPATH];
+    float lj[NU], mj[NU], rho[NPATH], rr[NPATH];
     const int64_t jo = (int64_t)j * C + t.c;
-    gather_row<PACK>(h, gh, NC, jo, xj);
-    if constexpr (!L0) gather_row<PACK>(hd, ghd, NC, jo, xdj);
     gather_row<PACK>(lam_a, glam, NC, jo, lj);
     gather_row<PACK>(mu_a, gmu, NC, jo, mj);
     const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
@@ -651,7 +651,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
 #pragma unroll
     for (int p = 0; p < NPATH; ++p) rr[p] *= rd;
     // Per slot: R1, R2 = what the reversed edge (couplings of -u) hands back to this atom's features through cy and cyd;
-    // S1 = sum cy x, S23 = sum cy xdot + cyd x feed the adjoint of the filter jets:
+    // S1 = sum cy x_i, S23 = sum cy xdot_i + cyd x_i feed the adjoint of the opposite edge's filter jet (up to the path's sign):
     // value row  c (t(x,Y,lam) + t(xdot,Y,mu) + t(x,Ydot,mu)) + c' rdot t(x,Y,mu)
     float ta[NPATH], t4[NPATH];
     zero(ta);
@@ -665,13 +665,13 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
           const float r2 = G::PATH_SIGN[p] * rho[p] * mj[m3];
           const float r1 = G::PATH_SIGN[p] * fmaf(rho[p], lj[m3], rr[p] * mj[m3]);
           acc[0] = fmaf(cy[n], r1, acc[0]);
-          const float s1 = cy[n] * xj[0];
-          ta[p] = fmaf(li[m3], s1, ta[p]);
+          const float s1 = cy[n] * xi[0];
+          ta[p] = fmaf(lj[m3], s1, ta[p]);
           if constexpr (G::ENT_M2[n] != 0) {
             acc[0] = fmaf(cyd[n], r2, acc[0]);
-            ta[p] = fmaf(mi[m3] * cyd[n], xj[0], ta[p]);
+            ta[p] = fmaf(mj[m3] * cyd[n], xi[0], ta[p]);
           }
-          t4[p] = fmaf(mi[m3], s1, t4[p]);
+          t4[p] = fmaf(mj[m3], s1, t4[p]);
         }
       } else if constexpr (!LZ || m3 == 0) {
         constexpr int pr = path_row<G, LS>(p);
@@ -681,20 +681,23 @@ __global__ void __launch_bounds__(256, 2) k_tp_be(const int32_t* __restrict__ ro
         }
         acc[m1] = fmaf(cy[n], R1, acc[m1]);
         if constexpr (G::ENT_M2[n] != 0) acc[m1] = fmaf(cyd[n], R2, acc[m1]);
-        S1 = G::ENT_SFIRST[n] ? cy[n] * xj[m1] : fmaf(cy[n], xj[m1], S1);
-        S23 = G::ENT_SFIRST[n] ? cy[n] * xdj[m1] : fmaf(cy[n], xdj[m1], S23);
-        if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xj[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
+        S1 = G::ENT_SFIRST[n] ? cy[n] * xi[m1] : fmaf(cy[n], xi[m1], S1);
+        S23 = G::ENT_SFIRST[n] ? cy[n] * xdi[m1] : fmaf(cy[n], xdi[m1], S23);
+        if constexpr (G::ENT_M2[n] != 0) S23 = fmaf(cyd[n], xi[m1], S23);  // the constant harmonic has no rate of change: cyd[n] = 0
         if (G::ENT_SLAST[n]) {
-          ta[pr] = fmaf(li[m3], S1, fmaf(mi[m3], S23, ta[pr]));
-          t4[pr] = fmaf(mi[m3], S1, t4[pr]);
+          ta[pr] = fmaf(lj[m3], S1, fmaf(mj[m3], S23, ta[pr]));
+          t4[pr] = fmaf(mj[m3], S1, t4[pr]);
         }
       }
     });
     const float2 cc = env[e];
     const float s = cc.y * rd;
-#pragma unroll
-    for (int p = 0; p < NPATH; ++p) ta[p] = fmaf(cc.x, ta[p], s * t4[p]);
-    store_paths(X + (int64_t)es * NPP * C, t.c, ta);
+    static_for<0, NPATH>([&](auto k_) {  // the opposite edge sees the harmonics of -u: the path's parity sign
+      constexpr int k = decltype(k_)::value;
+      constexpr float sg = G::PATH_SIGN[LZ ? G::LAST_PATHS[k] : k];
+      ta[k] = sg * fmaf(cc.x, ta[k], s * t4[k]);
+    });
+    store_paths(X + (int64_t)(es ^ 1) * NPP * C, t.c, ta);
   }
 #pragma unroll
   for (int m = 0; m < NX; ++m) lam_h[m * NC + io] = acc[m];  // first layer: only the l = 0 component is needed (the embedding's gradient)
@@ -1266,8 +1269,8 @@ int be_impl(mlip_ctx* ctx, float* grad) {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
       auto kern = TP_KERNEL(k_tp_be, ls, uni, G, TX, TF);
       hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->env,
-                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->gh[l], w->ghd[l], w->gmu[l],
-                         w->glam, lh_next, (int)N, C, lh, X);
+                         reinterpret_cast<const TF*>(w->Rho[l]), w->cy, w->cyd, w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->gmu[l], w->glam, lh_next,
+                         (int)N, C, lh, X);
     }
     if (want_gp && Eu > 0) {
       // dL/dx (optional, off the timed path): radial weights with their first and second r-derivative, then this layer's share

@@ -1,7 +1,8 @@
 // Operand loaders and epilogues plugged into the GEMM template, and SiLU derivatives.
 // Every loader maps (matrix row, first of four consecutive columns) -> float4.
 // "Jets" are pairs (value, derivative with respect to the edge length r) stored as two
-// consecutive rows per edge: row 2e holds the value, row 2e+1 the derivative.
+// consecutive rows: row 2e holds the value, row 2e+1 the derivative.  The index e below counts
+// pairs of opposite edges (equal lengths, one jet per pair), E their number.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
