@@ -73,6 +73,7 @@ struct EqvWs {
   float* lam0 = nullptr;  // [N][C] scratch for the readout's adjoint
   float* eps = nullptr;
   float* Facc = nullptr;
+  float* Fp = nullptr;      // [L][Eu][C / 64][3] force terms per layer, edge pair and block of 64 channels (C a multiple of 64)
   float* v = nullptr;
   float* Ebar = nullptr;
   // optional position gradient dL/dx (mlip_config.position_grad)
@@ -333,6 +334,23 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Sum of v over the 64 lanes of a wave, delivered in lane 63 (other lanes hold partial sums): an inclusive scan inside each
+// row of 16 lanes by shifts of 1, 2, 4, 8 (lanes shifted in from outside the row read zero), then lane 15 of a row added
+// to the next row (rows 1 and 3), then lane 31 to rows 2 and 3.  Register-to-register: no LDS round trips.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_shifted(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, true));
+}
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  v += dpp_shifted<0x111, 0xf>(v);  // row_shr:1
+  v += dpp_shifted<0x112, 0xf>(v);  // row_shr:2
+  v += dpp_shifted<0x114, 0xf>(v);  // row_shr:4
+  v += dpp_shifted<0x118, 0xf>(v);  // row_shr:8
+  v += dpp_shifted<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+  v += dpp_shifted<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 template <typename G, typename TF, bool UNI, int LS>
 __global__ void __launch_bounds__(256) k_tp_fe(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                const TF* __restrict__ Rho, const float* __restrict__ cyt,
@@ -384,62 +402,53 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
                                                   const float* __restrict__ cyt, const float* __restrict__ h,
                                                   const float* __restrict__ mu_a, const __bf16* __restrict__ gh,
                                                   const __bf16* __restrict__ gmu, const float* __restrict__ mu_h_next, int N,
-                                                  int C, float* __restrict__ mu_h, float* __restrict__ Facc) {
+                                                  int C, float* __restrict__ mu_h, float* __restrict__ Facc,
+                                                  float* __restrict__ Fp) {
+  // Two jobs per edge: the message this atom sends back along the reversed edge (cotangent of the layer's input features),
+  // and the force terms.  The force that an edge pair exerts on its two atoms is equal and opposite (shown below), so with
+  // UNI (a wave holds channels of one receiver row: its branches are uniform) only the pair's lower-numbered edge evaluates
+  // it, in a second walk over the row's edges: the wave sums the term over its channels and stores it per (pair, channel
+  // block of 64) in Fp [Eu][C / 64][3]; the rows' forces are collected from Fp afterwards (k_force_rows).  Without UNI
+  // every edge evaluates its term, in one walk, into the row's Facc.
   constexpr bool PACK = packed_rows<TF, G>();  // sender rows from the packed bf16 copies
   constexpr bool L0 = LS == LS_FIRST, LZ = LS == LS_LAST;
   constexpr int NM = G::NM, NPATH = LS ? G::LMAX + 1 : G::NPATH, NPP = LS ? 4 : G::NPP, CY_LD = G::CY_LD, NNZ = G::NNZ;
-  __shared__ float3 red[256];
+  constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features
+  constexpr int NU = LZ ? 1 : NM;  // live components of the cotangent of the layer's messages
+  __shared__ float3 red[UNI ? 1 : 256];
   __shared__ float tabs[4][64 * G::TAB_LOADS];
   RowChan t = row_chan(N, C);
   float3 f = make_float3(0.f, 0.f, 0.f);
   if (t.active) {
     const int64_t NC = (int64_t)N * C;
     const int64_t io = (int64_t)t.row * C + t.c;
-    constexpr int NX = L0 ? 1 : NM;  // live components of the layer's input features
-    constexpr int NU = LZ ? 1 : NM;  // live components of the cotangent of the layer's messages
-    float acc[NM], xi[NX], mi[NU];
-    if constexpr (LZ) {  // the readout's cotangent has its l = 0 component only
-      zero(acc);
-      acc[0] = mu_h_next[io];
-    } else if constexpr (!L0) {
-      loadm(mu_h_next, NC, io, acc);
-    }
+    float xi[NX], mi[NU];
     loadm(h, NC, io, xi);
     loadm(mu_a, NC, io, mi);
     float* slot = tabs[threadIdx.x >> 6];
     const int lane = threadIdx.x & 63;
     const int e0 = uni<UNI>(row_ptr[t.row]), e1 = uni<UNI>(row_ptr[t.row + 1]);
-    int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
-    for (int e = e0; e < e1; ++e) {
-      const int j = sn.x, es = sn.y;
-      sn = se[e + 1 < e1 ? e + 1 : e];
-      const float4 g = geo[e];
-      const float* cy = cyt + (int64_t)e * CY_LD;
-      TabRegs<G> tr;
-      if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
-      float xj[NX], mj[NU], rho[NPATH], rhop[NPATH];
-      const int64_t jo = (int64_t)j * C + t.c;
-      gather_row<PACK>(h, gh, NC, jo, xj);
-      gather_row<PACK>(mu_a, gmu, NC, jo, mj);
-      const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
-      load_rho(rrow, t.c, rho);
-      load_rho(rrow + NPP * C, t.c, rhop);
-      if constexpr (UNI) { tab_publish<G>(tr, slot, lane); cy = slot; }
-      if constexpr (!L0) {  // the message this atom sends back along the reversed edge: couplings of -u
-        float R = 0.f;
-        static_for<0, G::NNZ>([&](auto n_) {
-          constexpr int n = decltype(n_)::value;
-          constexpr int sl = G::ENT_SLOT[n];
-          if constexpr (!LZ || G::SLOT_M3[sl] == 0) {
-            if (G::ENT_SFIRST[n]) R = G::PATH_SIGN[G::SLOT_P[sl]] * rho[path_row<G, LS>(G::SLOT_P[sl])] * mj[G::SLOT_M3[sl]];
-            acc[G::ENT_M1[n]] = fmaf(cy[n], R, acc[G::ENT_M1[n]]);
-          }
-        });
-      }
-      // Force terms.  With W_n = x_j[m1] mu_i[m3] + sign_p x_i[m1] mu_j[m3] per coupling entry n = (p; m1, m2, m3), formed
-      // once, both directions of the edge pair give
-      //   radial:  s = sum_p rho'_p sum_{n in p} (T_n Y[m2]) W_n,      angular:  nu[m2] = sum_p rho_p sum_{n in (p, m2)} T_n W_n
-      // (the opposite edge sees the harmonics of -u, i.e. the path's parity sign).
+
+    // acc += the reversed edge's message: couplings of -u, i.e. the path's parity sign
+    auto back_message = [&](const float* cy, const float (&rho)[NPATH], const float (&mj)[NU], float (&acc)[NM]) {
+      float R = 0.f;
+      static_for<0, G::NNZ>([&](auto n_) {
+        constexpr int n = decltype(n_)::value;
+        constexpr int sl = G::ENT_SLOT[n];
+        if constexpr (!LZ || G::SLOT_M3[sl] == 0) {
+          if (G::ENT_SFIRST[n]) R = G::PATH_SIGN[G::SLOT_P[sl]] * rho[path_row<G, LS>(G::SLOT_P[sl])] * mj[G::SLOT_M3[sl]];
+          acc[G::ENT_M1[n]] = fmaf(cy[n], R, acc[G::ENT_M1[n]]);
+        }
+      });
+    };
+    // Force terms.  With W_n = x_j[m1] mu_i[m3] + sign_p x_i[m1] mu_j[m3] per coupling entry n = (p; m1, m2, m3), formed
+    // once, both directions of the edge pair give
+    //   radial:  s = sum_p rho'_p sum_{n in p} (T_n Y[m2]) W_n,      angular:  nu[m2] = sum_p rho_p sum_{n in (p, m2)} T_n W_n
+    // (the opposite edge sees the harmonics of -u, i.e. the path's parity sign).  Seen from the opposite edge, W_n and
+    // the coupling each change by the path's sign, so s is the same and nu[m2] changes by the parity of m2's degree, which
+    // the gradient of the harmonics at -u turns into an overall minus: the term on the sender is minus this one.
+    auto force_term = [&](const float* cy, const float (&xj)[NX], const float (&mj)[NU], const float (&rho)[NPATH],
+                          const float (&rhop)[NPATH], const float4 g) -> float3 {
       float s = 0.f;
       float nu[NM];
       zero(nu);
@@ -455,8 +464,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
           }
         });
       } else if constexpr (G::LMAX == 2) {
-        // few entries: the per-path and per-(path, m2) sums are kept side by side while the entries are walked in table order,
-        // the order in which the loop above has left the table's values in registers
+        // few entries: the per-path and per-(path, m2) sums are kept side by side while the entries are walked in table order
         float sp[NPATH], Gy[G::NYSLOT];
         static_for<0, G::NNZ>([&](auto n_) {
           constexpr int n = decltype(n_)::value;
@@ -471,8 +479,7 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
         for (int ys = 0; ys < G::NYSLOT; ++ys) nu[G::YSLOT_M2[ys]] = fmaf(rho[G::YSLOT_P[ys]], Gy[ys], nu[G::YSLOT_M2[ys]]);
       } else {
         // many entries: they are walked in the order (path, m2), in which the runs of one (path, m2) pair and of one path are
-        // consecutive, so both sums stay in one register each; the table is read again rather than kept from the loop above
-        asm volatile("" ::: "memory");
+        // consecutive, so both sums stay in one register each
         float sp = 0.f, gy = 0.f;
         static_for<0, G::NNZ>([&](auto k_) {
           constexpr int k = decltype(k_)::value;
@@ -485,30 +492,121 @@ __global__ void __launch_bounds__(256, 2) k_tp_ff(const int32_t* __restrict__ ro
           if (G::YORD_PLAST[k]) s = fmaf(rhop[p], sp, s);
         });
       }
-      float3 w = sph_grad_T(g.x, g.y, g.z, nu);
-      float uw = g.x * w.x + g.y * w.y + g.z * w.z;
-      float inv = 1.f / g.w;
-      f.x += s * g.x + (w.x - g.x * uw) * inv;
-      f.y += s * g.y + (w.y - g.y * uw) * inv;
-      f.z += s * g.z + (w.z - g.z * uw) * inv;
+      const float3 w = sph_grad_T(g.x, g.y, g.z, nu);
+      const float uw = g.x * w.x + g.y * w.y + g.z * w.z;
+      const float inv = 1.f / g.w;
+      return make_float3(s * g.x + (w.x - g.x * uw) * inv, s * g.y + (w.y - g.y * uw) * inv, s * g.z + (w.z - g.z * uw) * inv);
+    };
+
+    float acc[NM];
+    if constexpr (LZ) {  // the readout's cotangent has its l = 0 component only
+      zero(acc);
+      acc[0] = mu_h_next[io];
+    } else if constexpr (!L0) {
+      loadm(mu_h_next, NC, io, acc);
+    }
+    if constexpr (!UNI || !L0) {  // (the first layer's input is the embedding: no cotangent to send back)
+      int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
+      for (int e = e0; e < e1; ++e) {
+        const int j = sn.x, es = sn.y;
+        sn = se[e + 1 < e1 ? e + 1 : e];
+        const float* cy = cyt + (int64_t)e * CY_LD;
+        TabRegs<G> tr;
+        if constexpr (UNI) tr = tab_fetch<G>(cy, lane);
+        float mj[NU], rho[NPATH];
+        const int64_t jo = (int64_t)j * C + t.c;
+        gather_row<PACK>(mu_a, gmu, NC, jo, mj);
+        const TF* rrow = Rho + (int64_t)(es & ~1) * NPP * C;
+        load_rho(rrow, t.c, rho);
+        if constexpr (!UNI) {  // one walk: the force term of every edge too
+          const float4 g = geo[e];
+          float xj[NX], rhop[NPATH];
+          gather_row<PACK>(h, gh, NC, jo, xj);
+          load_rho(rrow + NPP * C, t.c, rhop);
+          if constexpr (!L0) back_message(cy, rho, mj, acc);
+          if constexpr (G::LMAX == 3 && LS == LS_ANY) asm volatile("" ::: "memory");  // the table is read again rather than kept
+          const float3 fe = force_term(cy, xj, mj, rho, rhop, g);
+          f.x += fe.x; f.y += fe.y; f.z += fe.z;
+        } else {
+          tab_publish<G>(tr, slot, lane);
+          back_message(slot, rho, mj, acc);
+        }
+      }
     }
     if constexpr (!L0) {
 #pragma unroll
       for (int m = 0; m < NM; ++m) mu_h[m * NC + io] = acc[m];
     }
-  }
-  red[threadIdx.x] = f;
-  __syncthreads();
-  if (t.active && t.c == 0) {
-    float3 s = make_float3(0.f, 0.f, 0.f);
-    for (int k = 0; k < C; ++k) {
-      float3 x = red[threadIdx.x + k];
-      s.x += x.x; s.y += x.y; s.z += x.z;
+    if constexpr (UNI) {  // second walk: the force terms of the pairs whose lower-numbered edge this row receives
+      int2 sn = e0 < e1 ? se[e0] : make_int2(0, 0);
+      for (int e = e0; e < e1; ++e) {
+        const int j = sn.x, es = sn.y;
+        sn = se[e + 1 < e1 ? e + 1 : e];
+        if (es & 1) continue;
+        const float4 g = geo[e];
+        const TabRegs<G> tr = tab_fetch<G>(cyt + (int64_t)e * CY_LD, lane);
+        float xj[NX], mj[NU], rho[NPATH], rhop[NPATH];
+        const int64_t jo = (int64_t)j * C + t.c;
+        gather_row<PACK>(h, gh, NC, jo, xj);
+        gather_row<PACK>(mu_a, gmu, NC, jo, mj);
+        const TF* rrow = Rho + (int64_t)es * NPP * C;
+        load_rho(rrow, t.c, rho);
+        load_rho(rrow + NPP * C, t.c, rhop);
+        tab_publish<G>(tr, slot, lane);
+        float3 fe = force_term(slot, xj, mj, rho, rhop, g);
+        fe.x = wave_sum_to_lane63(fe.x);  // over the wave's 64 channels
+        fe.y = wave_sum_to_lane63(fe.y);
+        fe.z = wave_sum_to_lane63(fe.z);
+        if (lane == 63) {
+          float* q = Fp + ((int64_t)(es >> 1) * (C >> 6) + (t.c >> 6)) * 3;
+          q[0] = fe.x; q[1] = fe.y; q[2] = fe.z;
+        }
+      }
     }
-    Facc[3 * t.row] += s.x;
-    Facc[3 * t.row + 1] += s.y;
-    Facc[3 * t.row + 2] += s.z;
   }
+  if constexpr (!UNI) {
+    red[threadIdx.x] = f;
+    __syncthreads();
+    if (t.active && t.c == 0) {
+      float3 s = make_float3(0.f, 0.f, 0.f);
+      for (int k = 0; k < C; ++k) {
+        float3 x = red[threadIdx.x + k];
+        s.x += x.x; s.y += x.y; s.z += x.z;
+      }
+      Facc[3 * t.row] += s.x;
+      Facc[3 * t.row + 1] += s.y;
+      Facc[3 * t.row + 2] += s.z;
+    }
+  }
+}
+
+// Forces of the rows from the per-pair terms of all layers: Fp [L][Eu][NW][3] (layer, pair, channel block).  An atom takes
+// the term of every edge it receives with + if that edge is its pair's lower-numbered one (the one that evaluated it) and
+// with - otherwise.  One wave per atom, lanes over its edges; sums in a fixed order.
+__global__ void __launch_bounds__(256) k_force_rows(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
+                                                    const float* __restrict__ Fp, int L, int64_t Eu, int NW, int N,
+                                                    float* __restrict__ F) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= N) return;  // whole waves leave; no workgroup barrier below
+  float3 f = make_float3(0.f, 0.f, 0.f);
+  for (int e = row_ptr[row] + lane; e < row_ptr[row + 1]; e += 64) {
+    const int es = se[e].y;
+    float3 g = make_float3(0.f, 0.f, 0.f);
+    for (int l = 0; l < L; ++l)
+      for (int w = 0; w < NW; ++w) {
+        const float* q = Fp + (((int64_t)l * Eu + (es >> 1)) * NW + w) * 3;
+        g.x += q[0]; g.y += q[1]; g.z += q[2];
+      }
+    const float sg = (es & 1) ? -1.f : 1.f;
+    f.x += sg * g.x; f.y += sg * g.y; f.z += sg * g.z;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    f.x += __shfl_xor(f.x, o, 64);
+    f.y += __shfl_xor(f.y, o, 64);
+    f.z += __shfl_xor(f.z, o, 64);
+  }
+  if (lane == 0) { F[3 * row] = f.x; F[3 * row + 1] = f.y; F[3 * row + 2] = f.z; }
 }
 
 template <typename G, typename TX, typename TF, bool UNI, int LS>
@@ -1147,9 +1245,13 @@ int ff_impl(mlip_ctx* ctx, float* F) {
     KernelTimer kt(ctx, MLIP_K_MSG_FF);
     auto kern = TP_KERNEL(k_tp_ff, ls, uni, G, TF);
     hipLaunchKernelGGL(kern, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Rho[l]),
-                       w->cy, w->h[l], w->mu_a[l], w->gh[l], w->gmu[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
+                       w->cy, w->h[l], w->mu_a[l], w->gh[l], w->gmu[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc,
+                       uni ? w->Fp + (int64_t)l * ctx->Eu * (C / 64) * 3 : nullptr);
   }
-  hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
+  if (uni)  // the per-pair force terms of all layers, with their signs, summed per atom
+    hipLaunchKernelGGL(k_force_rows, dim3(nblk(N, 4)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->Fp, L, ctx->Eu, C / 64, (int)N, F);
+  else
+    hipLaunchKernelGGL(k_scale3, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 1.f, 3 * N, F);
   MLIP_HIP_CHECK(ctx, hipGetLastError());
   return MLIP_OK;
 }
@@ -1390,6 +1492,7 @@ int eqv_alloc(mlip_ctx* ctx) {
   if (packed) w->glam = (__bf16*)A(NCP);
   w->y = A(N * C); w->yd = A(N * C); w->lam_y = A(N * C);
   w->eps = A(N); w->Facc = A(3 * N); w->v = A(3 * N); w->Ebar = A(B);
+  if (C % 64 == 0) w->Fp = A((int64_t)L * Eu * (C / 64) * 3);
   if (cf.position_grad) {
     w->U2 = A(Eu * H);
     w->Rj = A(2 * Eu * PC);
