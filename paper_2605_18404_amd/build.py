@@ -9,8 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmlip.so")
-# (source, object name, extra flags); the equivariant model is compiled once per l_max (two objects, side by side)
-SOURCES = [("equivariant.hip", "equivariant_l3", ["-DMLIP_EQV_LMAX=3"]), ("equivariant.hip", "equivariant_l2", ["-DMLIP_EQV_LMAX=2"]),
+# (source, object name, extra flags); the equivariant model is compiled once per (l_max, phase) plus once for its interface
+# functions: nine objects, side by side (the heaviest first)
+SOURCES = [("equivariant.hip", f"equivariant_l{l}_p{ph}", [f"-DMLIP_EQV_LMAX={l}", f"-DMLIP_EQV_PHASE={ph}"])
+           for l in (3, 2) for ph in (3, 2, 1, 0)] + \
+          [("equivariant.hip", "equivariant_api", ["-DMLIP_EQV_PHASE=-1"]),
            ("model.hip", "model", []), ("api.hip", "api", []), ("graph.hip", "graph", []), ("graph_static.hip", "graph_static", []),
            ("optimizer.hip", "optimizer", []), ("gars.cpp", "gars", [])]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -33,7 +36,7 @@ def _compile(item) -> str:
 
 
 def build(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=max(1, min(8, os.cpu_count() or 1))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

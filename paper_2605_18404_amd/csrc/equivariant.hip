@@ -25,13 +25,19 @@
 #include "gaunt_table.h"
 #include "shared_kernels.h"
 
-// This file is compiled twice, with MLIP_EQV_LMAX = 2 and = 3: each object instantiates the kernels for one set of
-// coupling tables (the two compile side by side).  The l_max = 2 object also holds the model's interface functions,
-// which hand a context with l_max = 3 to eqv_phase_lmax3 in the other object.
+// This file is compiled nine times (side by side).  With MLIP_EQV_LMAX = 2 or 3 and MLIP_EQV_PHASE = 0..3 (FE, FF, BF, BE)
+// an object instantiates the kernels of one phase for one set of coupling tables and defines eqv_phase_l<l_max>_<phase>;
+// with MLIP_EQV_PHASE = -1 it holds the model's interface functions (workspace, the four calls), which pick one of those
+// eight by the context's l_max.
 #ifndef MLIP_EQV_LMAX
 #define MLIP_EQV_LMAX 2
 #endif
-int eqv_phase_lmax3(mlip_ctx* ctx, int phase, float* out);
+#ifndef MLIP_EQV_PHASE
+#define MLIP_EQV_PHASE -1
+#endif
+#define MLIP_EQV_DECLARE(l, ph) int eqv_phase_l##l##_##ph(mlip_ctx* ctx, float* out);
+MLIP_EQV_DECLARE(2, 0) MLIP_EQV_DECLARE(2, 1) MLIP_EQV_DECLARE(2, 2) MLIP_EQV_DECLARE(2, 3)
+MLIP_EQV_DECLARE(3, 0) MLIP_EQV_DECLARE(3, 1) MLIP_EQV_DECLARE(3, 2) MLIP_EQV_DECLARE(3, 3)
 
 namespace {
 
@@ -1411,21 +1417,27 @@ int be_impl(mlip_ctx* ctx, float* grad) {
 
 }  // namespace
 
-#if MLIP_EQV_LMAX == 3
-// The four phases for a context with l_max = 3 (called from the interface functions in the l_max = 2 object).
-int eqv_phase_lmax3(mlip_ctx* ctx, int phase, float* out) {
-  typedef gaunt::Tab<3> G;
-#define EQV3(fn)                                                                                            \
+#if MLIP_EQV_PHASE >= 0
+// One phase for a context whose l_max is this object's.  TF = storage type of the radial-filter jets: float, or bf16 in
+// bf16 mode unless the context asks for fp32 filters; G = the coupling tables.
+#define MLIP_EQV_CAT2(l, ph) eqv_phase_l##l##_##ph
+#define MLIP_EQV_CAT(l, ph) MLIP_EQV_CAT2(l, ph)
+int MLIP_EQV_CAT(MLIP_EQV_LMAX, MLIP_EQV_PHASE)(mlip_ctx* ctx, float* out) {
+  typedef gaunt::Tab<MLIP_EQV_LMAX> G;
+#define EQV_RUN(fn)                                                                                         \
   (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                    \
        ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float, G>(ctx, out) : fn<gemm::Bf16, __bf16, G>(ctx, out))  \
        : fn<gemm::Fp32, float, G>(ctx, out))
-  switch (phase) {
-    case 0: return EQV3(fe_impl);
-    case 1: return EQV3(ff_impl);
-    case 2: return EQV3(bf_impl);
-    default: return EQV3(be_impl);
-  }
-#undef EQV3
+#if MLIP_EQV_PHASE == 0
+  return EQV_RUN(fe_impl);
+#elif MLIP_EQV_PHASE == 1
+  return EQV_RUN(ff_impl);
+#elif MLIP_EQV_PHASE == 2
+  return EQV_RUN(bf_impl);
+#else
+  return EQV_RUN(be_impl);
+#endif
+#undef EQV_RUN
 }
 #else
 // =================================================================================== interface
@@ -1519,15 +1531,8 @@ void eqv_free(mlip_ctx* ctx) {
   ctx->model_ws = nullptr;
 }
 
-// TF = storage type of the radial-filter jets: float, or bf16 in bf16 mode unless the context asks for fp32 filters;
-// G = the coupling tables of this object's l_max
-#define DISPATCH_G(fn, G, ...)                                                                                      \
-  (ctx->cfg.gemm_dtype == MLIP_GEMM_BF16                                                                            \
-       ? (ctx->cfg.filter_fp32 ? fn<gemm::Bf16, float, G>(__VA_ARGS__) : fn<gemm::Bf16, __bf16, G>(__VA_ARGS__))    \
-       : fn<gemm::Fp32, float, G>(__VA_ARGS__))
-enum { EQV_FE, EQV_FF, EQV_BF, EQV_BE };
-#define DISPATCH(fn, which, ...) \
-  (ctx->cfg.l_max == 3 ? eqv_phase_lmax3(ctx, which, __VA_ARGS__) : DISPATCH_G(fn, gaunt::Tab<2>, ctx, __VA_ARGS__))
+// the phase's object for the context's l_max
+#define DISPATCH(ph, out) (ctx->cfg.l_max == 3 ? eqv_phase_l3_##ph(ctx, out) : eqv_phase_l2_##ph(ctx, out))
 
 int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float*,
                        float* E, float*) {
@@ -1539,7 +1544,7 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_pos, pos, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, st));
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->d_params, params, sizeof(float) * ctx->n_params, hipMemcpyDeviceToDevice, st));
   hipLaunchKernelGGL(k_copy_species, dim3(nblk(ctx->N)), dim3(256), 0, st, species, ctx->N, ctx->cfg.n_species, ctx->d_species, ctx->d_flag);
-  MLIP_TRY(DISPATCH(fe_impl, EQV_FE, E));
+  MLIP_TRY(DISPATCH(0, E));
   ctx->phase = PH_FE;
   return MLIP_OK;
 }
@@ -1547,7 +1552,7 @@ int eqv_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, 
 int eqv_forward_force(mlip_ctx* ctx, const float*, float* F, float*) {
   if (ctx->phase < PH_FE) MLIP_FAIL(ctx, MLIP_E_STATE, "forward_force: run forward_energy first");
   if (!F) MLIP_FAIL(ctx, MLIP_E_INVALID, "forward_force: null pointer");
-  MLIP_TRY(DISPATCH(ff_impl, EQV_FF, F));
+  MLIP_TRY(DISPATCH(1, F));
   ctx->phase = PH_FF;
   return MLIP_OK;
 }
@@ -1556,7 +1561,7 @@ int eqv_backward_force(mlip_ctx* ctx, const float* v, const float*, float* grad,
   if (ctx->phase < PH_FF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_force: run forward_force first");
   if (!v || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_force: null pointer");
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->v, v, sizeof(float) * 3 * ctx->N, hipMemcpyDeviceToDevice, ctx->stream));
-  MLIP_TRY(DISPATCH(bf_impl, EQV_BF, grad));
+  MLIP_TRY(DISPATCH(2, grad));
   ctx->phase = PH_BF;
   return MLIP_OK;
 }
@@ -1565,8 +1570,8 @@ int eqv_backward_energy(mlip_ctx* ctx, const float* Ebar, const float*, float* g
   if (ctx->phase < PH_BF) MLIP_FAIL(ctx, MLIP_E_STATE, "backward_energy: run backward_force first");
   if (!Ebar || !grad) MLIP_FAIL(ctx, MLIP_E_INVALID, "backward_energy: null pointer");
   MLIP_HIP_CHECK(ctx, hipMemcpyAsync(ws_of(ctx)->Ebar, Ebar, sizeof(float) * ctx->B, hipMemcpyDeviceToDevice, ctx->stream));
-  MLIP_TRY(DISPATCH(be_impl, EQV_BE, grad));
+  MLIP_TRY(DISPATCH(3, grad));
   ctx->phase = PH_BE;
   return MLIP_OK;
 }
-#endif  // MLIP_EQV_LMAX
+#endif  // MLIP_EQV_PHASE
