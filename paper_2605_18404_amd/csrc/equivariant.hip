@@ -960,34 +960,41 @@ __global__ void __launch_bounds__(256) k_tp_gp(const int32_t* __restrict__ row_p
 // Per-edge tables of coupling coefficient x harmonic: cy[e][n] = T_n Y_{m2_n}(u_e), and, with
 // WITH_DOT, cyd[e][n] = T_n Ydot_{m2_n} for the displacement rate v_sender - v_receiver,
 // followed (entry NNZ) by the rate of change of the edge length, u . (v_sender - v_receiver).
+// A workgroup takes 64 edges: 64 of its threads evaluate the harmonics (or their rates of change) of one edge each into
+// LDS, then all threads write the edges' tables in order (coalesced), one multiplication per entry.
 template <typename G, bool WITH_DOT>
-__global__ void k_edge_cy(const float4* __restrict__ geo, const int32_t* __restrict__ sender,
-                          const int32_t* __restrict__ receiver, const float* __restrict__ v, int64_t E,
-                          float* __restrict__ out) {
-  constexpr int NM = G::NM, NNZ = G::NNZ, CY_LD = G::CY_LD;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= E * CY_LD) return;
-  const int64_t e = idx / CY_LD;
-  const int n = (int)(idx % CY_LD);
-  const float4 g = geo[e];
-  float Y[NM];
-  float val = 0.f;
-  if (WITH_DOT) {
-    const int j = sender[e], i = receiver[e];
-    const float3 dv = make_float3(v[3 * j] - v[3 * i], v[3 * j + 1] - v[3 * i + 1], v[3 * j + 2] - v[3 * i + 2]);
-    sph_dot(g.x, g.y, g.z, g.w, dv, Y);
-    if (n == NNZ) val = g.x * dv.x + g.y * dv.y + g.z * dv.z;  // rate of change of the edge length
-  } else {
-    sph_harm(g.x, g.y, g.z, Y);
-  }
-  if (n < NNZ) {
-    const int m2 = gaunt::ent_m2_dev<G::LMAX>(n);
-    float y = Y[0];
+__global__ void __launch_bounds__(256) k_edge_cy(const float4* __restrict__ geo, const int32_t* __restrict__ sender,
+                                                 const int32_t* __restrict__ receiver, const float* __restrict__ v, int64_t E,
+                                                 float* __restrict__ out) {
+  constexpr int NM = G::NM, NNZ = G::NNZ, CY_LD = G::CY_LD, EB = 64;
+  __shared__ float ys[EB][NM + 2];  // harmonics of an edge, then the rate of change of its length; odd pitch
+  const int64_t eb = (int64_t)blockIdx.x * EB;
+  if (threadIdx.x < EB && eb + threadIdx.x < E) {
+    const int64_t e = eb + threadIdx.x;
+    const float4 g = geo[e];
+    float Y[NM];
+    float rd = 0.f;
+    if (WITH_DOT) {
+      const int j = sender[e], i = receiver[e];
+      const float3 dv = make_float3(v[3 * j] - v[3 * i], v[3 * j + 1] - v[3 * i + 1], v[3 * j + 2] - v[3 * i + 2]);
+      sph_dot(g.x, g.y, g.z, g.w, dv, Y);
+      rd = g.x * dv.x + g.y * dv.y + g.z * dv.z;
+    } else {
+      sph_harm(g.x, g.y, g.z, Y);
+    }
 #pragma unroll
-    for (int m = 1; m < NM; ++m) y = (m2 == m) ? Y[m] : y;
-    val = gaunt::ent_coef_dev<G::LMAX>(n) * y;
+    for (int m = 0; m < NM; ++m) ys[threadIdx.x][m] = Y[m];
+    ys[threadIdx.x][NM] = rd;
   }
-  out[idx] = val;
+  __syncthreads();
+  const int64_t n_out = (E - eb < EB ? E - eb : EB) * CY_LD;
+  for (int k = threadIdx.x; k < n_out; k += 256) {
+    const int el = k / CY_LD, n = k % CY_LD;
+    float val = 0.f;
+    if (n < NNZ) val = gaunt::ent_coef_dev<G::LMAX>(n) * ys[el][gaunt::ent_m2_dev<G::LMAX>(n)];
+    else if (n == NNZ) val = ys[el][NM];
+    out[eb * CY_LD + k] = val;
+  }
 }
 
 
@@ -1176,7 +1183,7 @@ int fe_impl(mlip_ctx* ctx, float* E_out) {
   if (E > 0)
     launch_edge_features(ctx, E, K, cf.cutoff, w->env, w->env_u, w->jphi);
   if (E > 0)
-    hipLaunchKernelGGL((k_edge_cy<G, false>), dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
+    hipLaunchKernelGGL((k_edge_cy<G, false>), dim3(nblk(E, 64)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, nullptr, E, w->cy);
   hipLaunchKernelGGL(k_embed_l0, dim3(nblk(NM * NC)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, NM, w->h[0]);
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
@@ -1278,7 +1285,7 @@ int bf_impl(mlip_ctx* ctx, float* grad) {
   TX* X2 = reinterpret_cast<TX*>(w->X2);
   hipLaunchKernelGGL(k_fill, dim3(nblk(NM * NC)), dim3(256), 0, st, w->hd[0], 0.f, NM * NC);
   if (E > 0)  // harmonics' rate of change under the displacement rate v: used by this phase and by BE
-    hipLaunchKernelGGL((k_edge_cy<G, true>), dim3(nblk(E * CY_LD)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, w->v, E, w->cyd);
+    hipLaunchKernelGGL((k_edge_cy<G, true>), dim3(nblk(E, 64)), dim3(256), 0, st, ctx->d_geo, ctx->d_sender, ctx->d_receiver, w->v, E, w->cyd);
   const int rpb = 256 / C;
   const bool uni = C % 64 == 0;  // a wave then holds channels of one receiver row only
   for (int l = 0; l < L; ++l) {
