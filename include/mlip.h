@@ -147,6 +147,12 @@ int mlip_graph_sizes(const mlip_ctx* ctx, int64_t* n_atoms_host, int64_t* n_stru
  * shift[E,3] (int32 components in {-1,0,1}), rev[E] (index of the opposite edge j <- i, -S).
  * Asking for rev makes the call synchronous (it checks mlip_input_status first). */
 int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
+/* The pairing of opposite edges that the model phases work with (an edge and its opposite have the same length, so
+ * the radial network of the model is evaluated once per pair): slot[E] (device, int32) = 2 u + d, where u in
+ * [0, E/2) is the edge's pair -- pairs are numbered in the order of their lower-numbered edges -- and d = 0 for the
+ * pair's lower-numbered edge, 1 for the other; pair_edge[E/2] (device, int32, may be NULL) = the lower-numbered edge
+ * of each pair.  Synchronous (checks mlip_input_status first: an edge without an opposite has no pair). */
+int mlip_graph_export_pairs(mlip_ctx* ctx, int32_t* slot, int32_t* pair_edge);
 
 /* For callers that cannot allocate device memory at this point -- code under HIP graph capture set-up,
  * tight serving loops that rebuild the neighbour list every step, harnesses that forbid hipMalloc: the

@@ -64,6 +64,7 @@ def load():
     lib.mlip_last_error.restype = C.c_char_p
     lib.mlip_graph_build.argtypes = [P, I64, I32, P, P, P, F, C.POINTER(I64)]
     lib.mlip_graph_export.argtypes = [P, P, P, P, P]
+    lib.mlip_graph_export_pairs.argtypes = [P, P, P]
     lib.mlip_graph_sizes.argtypes = [P, C.POINTER(I64), C.POINTER(I64), C.POINTER(I64)]
     lib.mlip_kernel_timer_select.argtypes = [P, I32]
     lib.mlip_kernel_timer_read.argtypes = [P, C.POINTER(I64), C.POINTER(C.c_float)]
@@ -234,6 +235,13 @@ class Mlip:
         shift, rev = torch.empty(E, 3, **o), torch.empty(E, **o)
         self._check(self.lib.mlip_graph_export(self.ctx, _ptr(row_ptr), _ptr(sender), _ptr(shift), _ptr(rev)))
         return row_ptr, sender, shift, rev
+
+    def mlip_graph_export_pairs(self):
+        E = self.n_edges
+        o = dict(device=self.device, dtype=torch.int32)
+        slot, pair_edge = torch.empty(E, **o), torch.empty(E // 2, **o)
+        self._check(self.lib.mlip_graph_export_pairs(self.ctx, _ptr(slot), _ptr(pair_edge)))
+        return slot, pair_edge
 
     def mlip_set_expert_weights(self, alpha):
         """alpha: device tensor [n_structs, n_experts] float32."""

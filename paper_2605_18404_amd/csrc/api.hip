@@ -229,6 +229,11 @@ int mlip_graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t*
   return graph_export(ctx, row_ptr, sender, shift, rev);
 }
 
+int mlip_graph_export_pairs(mlip_ctx* ctx, int32_t* slot, int32_t* pair_edge) {
+  if (!ctx) return MLIP_E_INVALID;
+  return graph_export_pairs(ctx, slot, pair_edge);
+}
+
 int mlip_forward_energy(mlip_ctx* ctx, const float* pos, const int32_t* species, const float* params, const float* h_in,
                         float* E, float* h_out) {
   if (!ctx) return MLIP_E_INVALID;

@@ -175,6 +175,7 @@ int graph_build(mlip_ctx* ctx, int64_t n_atoms, int32_t n_structs, const float* 
 int graph_export(mlip_ctx* ctx, int32_t* row_ptr, int32_t* sender, int32_t* shift, int32_t* rev);
 int input_status(mlip_ctx* ctx);
 int graph_export_shift(mlip_ctx* ctx, int32_t* shift);
+int graph_export_pairs(mlip_ctx* ctx, int32_t* slot, int32_t* pair_edge);
 constexpr int GRAPH_SCAN_TILE = 2048;  // elements per workgroup of the graph build's scans: d_scan_tmp holds one int per tile (+ 2)
 
 // model.hip (invariant model and pipeline stage) / equivariant.hip (l <= 2 model)

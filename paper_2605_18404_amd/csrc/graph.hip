@@ -572,6 +572,26 @@ int input_status(mlip_ctx* ctx) {
   return MLIP_OK;
 }
 
+__global__ void k_export_slots(const int2* __restrict__ se, int64_t E, int32_t* __restrict__ slot) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < E) slot[e] = se[e].y;
+}
+
+// slot[E] and the lower-numbered edge of each pair, from the pairing of the current graph
+int graph_export_pairs(mlip_ctx* ctx, int32_t* slot, int32_t* pair_edge) {
+  if (ctx->phase < PH_GRAPH) MLIP_FAIL(ctx, MLIP_E_STATE, "graph_export_pairs: no graph has been built");
+  if (!slot) MLIP_FAIL(ctx, MLIP_E_INVALID, "graph_export_pairs: null pointer");
+  if (!ctx->d_se) MLIP_FAIL(ctx, MLIP_E_STATE, "graph_export_pairs: this context keeps no edge pairs");
+  MLIP_TRY(input_status(ctx));
+  if (ctx->E <= 0) return MLIP_OK;
+  hipLaunchKernelGGL(k_export_slots, dim3((unsigned)((ctx->E + 255) / 256)), dim3(256), 0, ctx->stream, ctx->d_se, ctx->E, slot);
+  MLIP_HIP_CHECK(ctx, hipGetLastError());
+  if (pair_edge)
+    MLIP_HIP_CHECK(ctx, hipMemcpyAsync(pair_edge, ctx->d_und, sizeof(int32_t) * ctx->Eu, hipMemcpyDeviceToDevice, ctx->stream));
+  MLIP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+  return MLIP_OK;
+}
+
 // shift[E,3] from the stored shift codes of the current graph
 int graph_export_shift(mlip_ctx* ctx, int32_t* shift) {
   if (ctx->E <= 0) return MLIP_OK;

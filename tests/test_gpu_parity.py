@@ -50,6 +50,17 @@ def test_graph_bit_exact(name):
     assert np.array_equal(sender, ref["sender"])
     assert np.array_equal(shift, ref["shift"])
     assert np.array_equal(rev, ref["rev"])
+    # the pairing of opposite edges, from the oracle's reverse map: pairs numbered in the order of their lower-numbered edges
+    e = np.arange(n_edges)
+    lower = ref["rev"] > e
+    pair_edge_ref = e[lower]
+    slot_ref = np.empty(n_edges, np.int64)
+    slot_ref[pair_edge_ref] = 2 * np.arange(len(pair_edge_ref))
+    slot_ref[ref["rev"][pair_edge_ref]] = 2 * np.arange(len(pair_edge_ref)) + 1
+    slot, pair_edge = [t.cpu().numpy() for t in m.mlip_graph_export_pairs()]
+    assert len(pair_edge_ref) * 2 == n_edges
+    assert np.array_equal(slot, slot_ref)
+    assert np.array_equal(pair_edge, pair_edge_ref)
     m.close()
 
 
