@@ -34,6 +34,7 @@ struct InvWs {
   float* jphi = nullptr;   // [Eu][2][K]; every edge tensor below marked Eu has one row (or jet) per edge pair
   float2* env = nullptr;   // [E] (f_c, f_c')
   float2* env_u = nullptr; // [Eu] the same per edge pair (rows of the filter product)
+  float4* erd = nullptr;   // [E] (rdot, f_c, f_c', 0), written by BF for itself and BE
   std::vector<float*> U[2];   // hidden pre-activations, jets [Eu][2][H]; U[0] level 1, U[1] level 2 (depth 3)
   std::vector<__bf16*> SJ[2];  // bf16 GEMMs only: activated jets of each hidden level, [Eu][2][H]
   std::vector<float*> Om;     // [Eu][2][C], in the operand precision (fp32 or bf16)
@@ -120,8 +121,14 @@ __device__ __forceinline__ void walk_row(const int2* __restrict__ se, int e0, in
   }
 }
 
+// UNI: a row's C/4 threads fill whole waves (C a multiple of 256), so the row's edge range is the same in every lane of a
+// wave: taken from the first lane, it lets the edge indices, the (sender, slot) pairs and the per-edge values be fetched
+// by scalar loads, which leaves the vector memory pipeline -- what bounds these loops -- to the rows of Om and the gathers.
+template <bool UNI>
+__device__ __forceinline__ int uni_row(int x) { return UNI ? __builtin_amdgcn_readfirstlane(x) : x; }
+
 struct InFe { float4 w, hj; };
-template <typename TF>
+template <typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const TF* __restrict__ Om, const float* __restrict__ h, int N, int C,
                                                 float* __restrict__ a) {
@@ -130,14 +137,14 @@ __global__ void __launch_bounds__(256) k_msg_fe(const int32_t* __restrict__ row_
   const int c0 = 4 * t.cq;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   walk_row<4, InFe>(
-      se, row_ptr[t.row], row_ptr[t.row + 1],
+      se, uni_row<UNI>(row_ptr[t.row]), uni_row<UNI>(row_ptr[t.row + 1]),
       [&](int, int j, int slot) { return InFe{ld4(Om + (int64_t)(slot & ~1) * C + c0), ld4(h + (int64_t)j * C + c0)}; },
       [&](int, const InFe& c) { fma4(acc, c.w, c.hj); });
   *reinterpret_cast<float4*>(a + (int64_t)t.row * C + c0) = acc;
 }
 
 struct InFf { float4 w, wp, hj, maj, ge; };
-template <typename TF>
+template <typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
                                                 const float4* __restrict__ geo, const TF* __restrict__ Om,
                                                 const float* __restrict__ h, const float* __restrict__ mu_a,
@@ -153,7 +160,7 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
     float4 acc = ld4(mu_h_next + ro);
     const float4 hi = ld4(h + ro), mai = ld4(mu_a + ro);
     walk_row<2, InFf>(
-        se, row_ptr[t.row], row_ptr[t.row + 1],
+        se, uni_row<UNI>(row_ptr[t.row]), uni_row<UNI>(row_ptr[t.row + 1]),
         [&](int e, int j, int slot) {
           InFf x;
           x.w = ld4(Om + (int64_t)(slot & ~1) * C + c0);
@@ -185,13 +192,28 @@ __global__ void __launch_bounds__(256) k_msg_ff(const int32_t* __restrict__ row_
   }
 }
 
-struct InBf { float4 w, wp, hj, hdj, ge; float c, v0, v1, v2; int slot; };
-template <typename TX, typename TF>
+// Per edge (rdot, f_c, f_c', 0) with rdot = rhat . (v_sender - v_receiver): what BF and BE need of the geometry, the
+// envelope and the displacement rate, in one 16-byte value per edge (their loops are bound by the number of loads they
+// issue per edge, and every lane of a row would otherwise fetch the unit vector, the envelope and three rate components).
+__global__ void k_edge_rdot(const float4* __restrict__ geo, const float2* __restrict__ env, const int32_t* __restrict__ sender,
+                            const int32_t* __restrict__ receiver, const float* __restrict__ v, int64_t E,
+                            float4* __restrict__ out) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const int j = sender[e], i = receiver[e];
+  const float4 g = geo[e];
+  const float2 c = env[e];
+  const float rd = g.x * (v[3 * j] - v[3 * i]) + g.y * (v[3 * j + 1] - v[3 * i + 1]) + g.z * (v[3 * j + 2] - v[3 * i + 2]);
+  out[e] = make_float4(rd, c.x, c.y, 0.f);
+}
+
+struct InBf { float4 w, wp, hj, hdj, q; int slot; };
+template <typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
-                                                const float4* __restrict__ geo, const float2* __restrict__ env,
+                                                const float4* __restrict__ erd,
                                                 const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                                const float* __restrict__ v, int N, int C, float* __restrict__ ad,
+                                                int N, int C, float* __restrict__ ad,
                                                 TX* __restrict__ X) {
   RowThread t = row_thread(N, C / 4);
   if (!t.active) return;
@@ -199,9 +221,8 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
   const int64_t ro = (int64_t)t.row * C + c0;
   const float4 mai = ld4(mu_a + ro);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
   walk_row<2, InBf>(
-      se, row_ptr[t.row], row_ptr[t.row + 1],
+      se, uni_row<UNI>(row_ptr[t.row]), uni_row<UNI>(row_ptr[t.row + 1]),
       [&](int e, int j, int slot) {
         InBf x;
         x.slot = slot;
@@ -209,16 +230,14 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
         x.wp = ld4(Om + (int64_t)(slot | 1) * C + c0);
         x.hj = ld4(h + (int64_t)j * C + c0);
         x.hdj = ld4(hd + (int64_t)j * C + c0);
-        x.ge = geo[e];
-        x.c = env[e].x;
-        x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+        x.q = erd[e];
         return x;
       },
       [&](int, const InBf& c) {
-        const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
+        const float rd = c.q.x;
         fma4s(acc, rd, c.wp, c.hj);
         fma4(acc, c.w, c.hdj);
-        const float s = rd * c.c;
+        const float s = rd * c.q.y;
         st4(X + (int64_t)c.slot * C + c0, make_float4(s * c.hj.x * mai.x, s * c.hj.y * mai.y, s * c.hj.z * mai.z, s * c.hj.w * mai.w));
       });
   *reinterpret_cast<float4*>(ad + ro) = acc;
@@ -228,13 +247,13 @@ __global__ void __launch_bounds__(256) k_msg_bf(const int32_t* __restrict__ row_
 // that of the OPPOSITE edge (j <- i), the pair's other row (slot ^ 1): c (h_i lam_a,j + hdot_i mu_a,j) + c' rdot h_i mu_a,j
 // needs this row's own features and the same two gathered tables; r, rdot and the envelope are equal on opposite edges.
 // Every edge is some edge's opposite, so each X row is written exactly once, and half the gathers are gone.
-struct InBe { float4 w, wp, laj, maj, ge; float2 cc; float v0, v1, v2; int slot; };
-template <typename TX, typename TF>
+struct InBe { float4 w, wp, laj, maj, q; int slot; };
+template <typename TX, typename TF, bool UNI>
 __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_ptr, const int2* __restrict__ se,
-                                                const float4* __restrict__ geo, const float2* __restrict__ env,
+                                                const float4* __restrict__ erd,
                                                 const TF* __restrict__ Om, const float* __restrict__ h,
                                                 const float* __restrict__ hd, const float* __restrict__ mu_a,
-                                                const float* __restrict__ lam_a, const float* __restrict__ v,
+                                                const float* __restrict__ lam_a,
                                                 const float* __restrict__ lam_h_next, int N, int C,
                                                 float* __restrict__ lam_h, TX* __restrict__ X) {
   RowThread t = row_thread(N, C / 4);
@@ -243,9 +262,8 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
   const int64_t ro = (int64_t)t.row * C + c0;
   const float4 hi = ld4(h + ro), hdi = ld4(hd + ro);
   float4 acc = ld4(lam_h_next + ro);
-  const float vi0 = v[3 * t.row], vi1 = v[3 * t.row + 1], vi2 = v[3 * t.row + 2];
   walk_row<2, InBe>(
-      se, row_ptr[t.row], row_ptr[t.row + 1],
+      se, uni_row<UNI>(row_ptr[t.row]), uni_row<UNI>(row_ptr[t.row + 1]),
       [&](int e, int j, int slot) {
         InBe x;
         x.slot = slot;
@@ -253,21 +271,19 @@ __global__ void __launch_bounds__(256) k_msg_be(const int32_t* __restrict__ row_
         x.wp = ld4(Om + (int64_t)(slot | 1) * C + c0);
         const int64_t jo = (int64_t)j * C + c0;
         x.laj = ld4(lam_a + jo); x.maj = ld4(mu_a + jo);
-        x.ge = geo[e];
-        x.cc = env[e];
-        x.v0 = v[3 * j]; x.v1 = v[3 * j + 1]; x.v2 = v[3 * j + 2];
+        x.q = erd[e];
         return x;
       },
       [&](int, const InBe& c) {
-        const float rd = c.ge.x * (c.v0 - vi0) + c.ge.y * (c.v1 - vi1) + c.ge.z * (c.v2 - vi2);
+        const float rd = c.q.x, fc = c.q.y;
         fma4(acc, c.w, c.laj);
         fma4s(acc, rd, c.wp, c.maj);
-        const float s = c.cc.y * rd;
+        const float s = c.q.z * rd;
         float4 x;
-        x.x = c.cc.x * (hi.x * c.laj.x + hdi.x * c.maj.x) + s * hi.x * c.maj.x;
-        x.y = c.cc.x * (hi.y * c.laj.y + hdi.y * c.maj.y) + s * hi.y * c.maj.y;
-        x.z = c.cc.x * (hi.z * c.laj.z + hdi.z * c.maj.z) + s * hi.z * c.maj.z;
-        x.w = c.cc.x * (hi.w * c.laj.w + hdi.w * c.maj.w) + s * hi.w * c.maj.w;
+        x.x = fc * (hi.x * c.laj.x + hdi.x * c.maj.x) + s * hi.x * c.maj.x;
+        x.y = fc * (hi.y * c.laj.y + hdi.y * c.maj.y) + s * hi.y * c.maj.y;
+        x.z = fc * (hi.z * c.laj.z + hdi.z * c.maj.z) + s * hi.z * c.maj.z;
+        x.w = fc * (hi.w * c.laj.w + hdi.w * c.maj.w) + s * hi.w * c.maj.w;
         st4(X + (int64_t)(c.slot ^ 1) * C + c0, x);
       });
   *reinterpret_cast<float4*>(lam_h + ro) = acc;
@@ -409,6 +425,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     hipLaunchKernelGGL(k_embed, dim3(nblk(N * C)), dim3(256), 0, st, th + ctx->off_emb, ctx->d_species, N, C, w->h[0]);
 
   const int rpb = 256 / (C / 4);
+  const bool uni = C % 256 == 0;  // a row's threads then fill whole waves
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     if (Eu > 0) {
@@ -430,7 +447,7 @@ int fe_impl(mlip_ctx* ctx, const float* h_in, float* E_out, float* h_out) {
     }
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FE);
-      hipLaunchKernelGGL(k_msg_fe<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
+      hipLaunchKernelGGL((uni ? k_msg_fe<TF, true> : k_msg_fe<TF, false>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, reinterpret_cast<const TF*>(w->Om[l]), w->h[l],
                          (int)N, C, w->a[l]);
     }
     node_mm<P>(ctx, l, 0, false, LdPlain{w->a[l], C}, EpiStore{w->q[l], C, N});
@@ -463,13 +480,14 @@ int ff_impl(mlip_ctx* ctx, const float* g_out, float* F, float* g_in) {
     gemm_nt<P>(ctx, LdMuY{w->y, th + ctx->off_wo, C}, tT + ctx->off_U, N, C, C, EpiStore{w->mu_h[L], C, N});
   hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->Facc, 0.f, 3 * N);
   const int rpb = 256 / (C / 4);
+  const bool uni = C % 256 == 0;  // a row's threads then fill whole waves
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& lo = ctx->lay[l];
     node_mm<P>(ctx, l, 1, true, LdPlain{w->mu_h[l + 1], C}, EpiMuT{w->mu_t[l], w->mu_q[l], w->q[l], C, N});
     node_mm<P>(ctx, l, 0, true, LdPlain{w->mu_q[l], C}, EpiStore{w->mu_a[l], C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_FF);
-      hipLaunchKernelGGL(k_msg_ff<TF>, dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
+      hipLaunchKernelGGL((uni ? k_msg_ff<TF, true> : k_msg_ff<TF, false>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, reinterpret_cast<const TF*>(w->Om[l]),
                          w->h[l], w->mu_a[l], w->mu_h[l + 1], (int)N, C, w->mu_h[l], w->Facc);
     }
   }
@@ -498,12 +516,15 @@ int bf_impl(mlip_ctx* ctx, const float* hdot_in, float* grad, float* hdot_out) {
   else
     hipLaunchKernelGGL(k_fill, dim3(nblk(N * C)), dim3(256), 0, st, w->hd[0], 0.f, N * C);
   const int rpb = 256 / (C / 4);
+  const bool uni = C % 256 == 0;  // a row's threads then fill whole waves
+  if (ctx->E > 0)
+    hipLaunchKernelGGL(k_edge_rdot, dim3(nblk(ctx->E)), dim3(256), 0, st, ctx->d_geo, w->env, ctx->d_sender, ctx->d_receiver, w->v, ctx->E, w->erd);
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& lo = ctx->lay[l];
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BF);
-      hipLaunchKernelGGL((k_msg_bf<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env,
-                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->v, (int)N, C, w->ad[l], X);
+      hipLaunchKernelGGL((uni ? k_msg_bf<TX, TF, true> : k_msg_bf<TX, TF, false>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->erd,
+                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], (int)N, C, w->ad[l], X);
     }
     node_mm<P>(ctx, l, 0, false, LdPlain{w->ad[l], C}, EpiStore{w->qd[l], C, N});
     node_mm<P>(ctx, l, 1, false, LdDsiluMul{w->q[l], w->qd[l], C}, EpiAddStore{w->hd[l + 1], w->hd[l], C, N});
@@ -583,6 +604,7 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     gemm_nt<P>(ctx, LdPlain{w->lam_y, C}, tT + ctx->off_U, N, C, C, EpiStore{w->lam_h[cur], C, N});
   }
   const int rpb = 256 / (C / 4);
+  const bool uni = C % 256 == 0;  // a row's threads then fill whole waves
   const bool want_gp = ctx->d_grad_pos != nullptr;
   if (want_gp) hipLaunchKernelGGL(k_fill, dim3(nblk(3 * N)), dim3(256), 0, st, w->gp_acc, 0.f, 3 * N);
   for (int l = L - 1; l >= 0; --l) {
@@ -595,8 +617,8 @@ int be_impl(mlip_ctx* ctx, const float* lam_out, float* grad, float* lam_in) {
     node_mm<P>(ctx, l, 0, true, LdPlain{w->lam_q, C}, EpiStore{w->lam_a, C, N});
     {
       KernelTimer kt(ctx, MLIP_K_MSG_BE);
-      hipLaunchKernelGGL((k_msg_be<TX, TF>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, ctx->d_geo, w->env,
-                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, w->v, lh_next, (int)N, C, lh, X);
+      hipLaunchKernelGGL((uni ? k_msg_be<TX, TF, true> : k_msg_be<TX, TF, false>), dim3(nblk8(N, rpb)), dim3(256), 0, st, ctx->d_row_ptr, ctx->d_se, w->erd,
+                         reinterpret_cast<const TF*>(w->Om[l]), w->h[l], w->hd[l], w->mu_a[l], w->lam_a, lh_next, (int)N, C, lh, X);
     }
     if (want_gp && Eu > 0) {
       // dL/dx (optional, off the timed path): the edge MLP's output with its first and second r-derivative
@@ -680,6 +702,7 @@ int inv_alloc(mlip_ctx* ctx) {
   w->jphi = A(2 * Eu * K);
   ok &= (w->env = alloc_n<float2>(ctx, E)) != nullptr;
   ok &= (w->env_u = alloc_n<float2>(ctx, Eu)) != nullptr;
+  ok &= (w->erd = alloc_n<float4>(ctx, E)) != nullptr;
   const int64_t Wmax = std::max(C, H);
   const bool b16 = cf.gemm_dtype == MLIP_GEMM_BF16;
   // tensors held in the operand precision: half the floats when that is bf16
